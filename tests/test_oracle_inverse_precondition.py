@@ -1,0 +1,140 @@
+"""Pins for the oracle's damped inverse and two-sided preconditioning."""
+import numpy as np
+import pytest
+
+from oracle import kfac_oracle as orc
+from workloads import rng, shapes
+
+
+def _spd(seed, n, R=None):
+    R = R or 2 * n
+    X = rng.draw_normal(seed, 0, (R, n)).astype(np.float64)
+    return X.T @ X / R, X
+
+
+def test_inverse_small_closed_forms():
+    assert np.allclose(orc.inverse(np.array([[4.0]]), 1.0), [[0.2]])
+    a, b, d, lam = 3.0, 1.0, 2.0, 0.5
+    det = (a + lam) * (d + lam) - b * b
+    ref = np.array([[d + lam, -b], [-b, a + lam]]) / det
+    for m in ("gj", "chol"):
+        assert np.allclose(orc.inverse(np.array([[a, b], [b, d]]), lam, m), ref, rtol=1e-14)
+    diag = np.diag([1.0, 2.0, 4.0, 8.0])
+    assert np.allclose(orc.inverse(diag, 1.0), np.diag(1.0 / (np.array([1.0, 2.0, 4.0, 8.0]) + 1.0)), rtol=1e-15)
+
+
+@pytest.mark.parametrize("n", [1, 2, 7, 33, 130])
+def test_inverse_times_matrix_is_identity_and_routes_agree(n):
+    M, _ = _spd(10 + n, n)
+    lam = 0.03
+    gj = orc.inverse(M, lam, "gj")
+    ch = orc.inverse(M, lam, "chol")
+    Md = M + lam * np.eye(n)
+    assert np.linalg.norm(Md @ gj - np.eye(n)) / np.sqrt(n) < 1e-11
+    assert np.linalg.norm(gj @ Md - np.eye(n)) / np.sqrt(n) < 1e-11
+    assert np.linalg.norm(gj - ch) / np.linalg.norm(gj) < 1e-11
+    assert np.linalg.norm(gj - np.linalg.inv(Md)) / np.linalg.norm(gj) < 1e-11
+
+
+def test_inverse_needs_pivoting_case_and_asymmetry_probe():
+    # Gauss-Jordan route on a general (non-symmetric, zero leading pivot) matrix
+    M = np.array([[0.0, 2.0, 1.0], [1.0, 0.0, 3.0], [4.0, 1.0, 0.0]])
+    assert np.allclose(orc.inverse(M, 0.0, "gj"), np.linalg.inv(M), rtol=1e-13)
+
+
+def test_inverse_woodbury_for_rank_deficient_factor():
+    # (lam I + s X^T X)^{-1} = (1/lam) [I - X^T ((lam/s) I_R + X X^T)^{-1} X], R < d
+    R, d, s, lam = 4, 11, 0.25, 0.03
+    X = rng.draw_normal(21, 0, (R, d)).astype(np.float64)
+    F = orc.factor(X, s)
+    small = np.linalg.inv((lam / s) * np.eye(R) + X @ X.T)
+    ref = (np.eye(d) - X.T @ small @ X) / lam
+    for m in ("gj", "chol"):
+        got = orc.inverse(F, lam, m)
+        assert np.linalg.norm(got - ref) / np.linalg.norm(ref) < 1e-11
+
+
+def test_inverse_large_damping_limit_and_spd_failure_flag():
+    M, _ = _spd(30, 6)
+    lam = 1e9
+    assert np.allclose(orc.inverse(M, lam) * lam, np.eye(6), atol=1e-8)
+    bad = np.diag([1.0, 2.0, -3.0, 4.0])
+    assert orc.inverse_info(bad, 0.0) == 3           # first non-positive pivot, 1-based
+    assert orc.inverse_info(bad, 3.5) == 0
+
+
+def test_precondition_plain_product_with_nonsymmetric_operands():
+    # catches transposed operands / swapped sides, which symmetric inverses would hide
+    gen = np.random.default_rng(5)
+    Gi, Ai, g = gen.standard_normal((4, 4)), gen.standard_normal((7, 7)), gen.standard_normal((4, 7))
+    assert np.allclose(orc.precondition(Gi, g, Ai), Gi @ g @ Ai, rtol=1e-13, atol=1e-13)
+
+
+def test_precondition_identity_factors():
+    g = rng.draw_normal(8, 2, (5, 9)).astype(np.float64)
+    lamA, lamG = 0.03, 0.2
+    Ai = orc.inverse(np.eye(9), lamA)
+    Gi = orc.inverse(np.eye(5), lamG)
+    assert np.allclose(orc.precondition(Gi, g, Ai), g / ((1 + lamA) * (1 + lamG)), rtol=1e-13)
+
+
+def _kron_solve(A, G, grad):
+    """[(A (x) G)]^{-1} vec(grad) with column-major vec of the d_G x d_A matrix."""
+    dG, dA = grad.shape
+    K = np.kron(A, G)
+    v = np.linalg.solve(K, grad.reshape(-1, order="F"))
+    return v.reshape((dG, dA), order="F")
+
+
+def test_precondition_equals_explicit_kronecker_inverse_small():
+    dA, dG = 7, 4
+    A, _ = _spd(40, dA)
+    G, _ = _spd(41, dG)
+    grad = rng.draw_normal(42, 2, (dG, dA)).astype(np.float64)
+    # undamped, full rank: Eq. 5
+    P0 = orc.precondition(orc.inverse(G, 0.0), grad, orc.inverse(A, 0.0))
+    assert np.allclose(P0, _kron_solve(A, G, grad), rtol=1e-9, atol=1e-11)
+    # damping applied per factor: right-hand side of Eq. 12
+    lamA, lamG = 0.05, 0.2
+    P = orc.precondition(orc.inverse(G, lamG), grad, orc.inverse(A, lamA))
+    ref = _kron_solve(A + lamA * np.eye(dA), G + lamG * np.eye(dG), grad)
+    assert np.allclose(P, ref, rtol=1e-10, atol=1e-12)
+
+
+def test_whole_fc_config_against_explicit_kronecker_system():
+    # config 1 end to end: 65x65 (x) 32x32 = 2080 x 2080 dense system
+    layer = shapes.config_layers("fc_tiny")[0]
+    hp = shapes.config_hparams("fc_tiny")
+    act, gout, grad = rng.layer_inputs(layer, hp["batch"], 1000, hp["act"], hp["gout_var"] ** 0.5)
+    sA, sG = shapes.layer_scales(layer, hp["batch"])
+    A, G = orc.update_factors_layer(layer, act, gout, sA, sG, hp["decay"], np.eye(65), np.eye(32))
+    lam = hp["damping"]
+    Ai, Gi = orc.invert_layer(A, G, lam, lam)
+    P = orc.precondition_layer(Ai, Gi, grad)
+    ref = _kron_solve(A + lam * np.eye(65), G + lam * np.eye(32), grad.astype(np.float64))
+    assert np.linalg.norm(P - ref) / np.linalg.norm(ref) < 1e-10
+    # independent reconstruction of the running factors (numpy route)
+    abar = np.concatenate([act, np.ones((32, 1), np.float32)], axis=1).astype(np.float64)
+    assert np.allclose(A, 0.95 * np.eye(65) + 0.05 * abar.T @ abar / 32, rtol=1e-12, atol=1e-14)
+    assert np.allclose(G, 0.95 * np.eye(32) + 0.05 * gout.astype(np.float64).T @ gout.astype(np.float64) / 32,
+                       rtol=1e-12, atol=1e-14)
+
+
+def test_eigen_form_is_exact_inverse_of_damped_kronecker_product():
+    # Eq. 13 reproduces (A (x) G + gamma I)^{-1} vec(grad) exactly; Eq. 12's
+    # factored damping is only an approximation of it (the gap is reported, not asserted small).
+    dA, dG, gamma = 6, 4, 0.01
+    A, _ = _spd(50, dA)
+    G, _ = _spd(51, dG)
+    grad = rng.draw_normal(52, 2, (dG, dA)).astype(np.float64)
+    vA, QA = np.linalg.eigh(A)
+    vG, QG = np.linalg.eigh(G)
+    P = orc.precondition_eigen(QG, vG, QA, vA, grad, gamma)
+    K = np.kron(A, G) + gamma * np.eye(dA * dG)
+    ref = np.linalg.solve(K, grad.reshape(-1, order="F")).reshape((dG, dA), order="F")
+    assert np.allclose(P, ref, rtol=1e-10, atol=1e-12)
+    # pi-scaled per-factor damping of Eq. 12 stays within a loose factor of the exact form
+    pi = np.sqrt(np.trace(A) / dA) / np.sqrt(np.trace(G) / dG)
+    P12 = orc.precondition(orc.inverse(G, np.sqrt(gamma) / pi), grad, orc.inverse(A, pi * np.sqrt(gamma)))
+    gap = np.linalg.norm(P12 - ref) / np.linalg.norm(ref)
+    assert gap < 1.0
