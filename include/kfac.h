@@ -1,0 +1,137 @@
+/*
+ * kfac.h - C ABI of the MI355X (gfx950) K-FAC second-order update library.
+ *
+ * The library computes, for one layer or a set of layers, the work DP-KFAC
+ * (arXiv 2206.15143) assigns to the worker that owns those layers
+ * (Algorithm 1, the per-layer body of the loop over assigned layers):
+ *
+ *   1. Kronecker factors        A = s_A * abar^T abar,  G = s_G * g^T g     (Eq. 4)
+ *      with abar the layer input (im2col patches for a convolution, the
+ *      footnote of section 3; homogeneous 1 appended last for the bias),
+ *   2. running average          F <- decay * F + (1 - decay) * F_new        (Eqs. 10-11)
+ *   3. damped inverses          (A + lambda_A I)^{-1}, (G + lambda_G I)^{-1} (section 5.2)
+ *   4. preconditioned gradient  P = G_inv * grad * A_inv                     (Eq. 5, Eq. 12 rhs)
+ *
+ * Conventions
+ *   - Every pointer whose name starts with d_ is a DEVICE pointer owned by the
+ *     caller.  The library allocates no device memory and keeps no state.
+ *     Arrays of descriptors / pointers / scalars passed to the *_batched calls
+ *     are HOST arrays of length n.
+ *   - All matrices are row-major.  Factors and inverses are d x d fp32 with
+ *     leading dimension d.  Running factors: the LOWER triangle is read; both
+ *     triangles are written (mirrored) on exit.  Inverses are written as full,
+ *     bitwise symmetric matrices.
+ *   - Activations: LINEAR [rows, d_in]; CONV2D NCHW [batch, d_in, h, w].
+ *     Output gradients: LINEAR [rows, d_out]; CONV2D NCHW [batch, d_out, h_out, w_out].
+ *     Element type given by in_dtype (fp32 or bfloat16 bit patterns).
+ *   - Patch column order is (c, i, j), c slowest, i.e. the flattening of a
+ *     [C_out, C_in, kh, kw] weight to [C_out, C_in*kh*kw]; the bias column is
+ *     LAST.  Gradients and preconditioned gradients are [d_G, d_A] fp32 with the
+ *     bias gradient in the last column.
+ *   - `decay` is the weight on the OLD running factor.
+ *   - Calls are asynchronous on `hip_stream` (a hipStream_t, may be NULL for
+ *     the default stream); the caller synchronises.  Calls that share a
+ *     workspace must be ordered on one stream.
+ *   - Errors detectable on the host return a non-zero kfac_status before any
+ *     kernel is launched and leave all buffers untouched.  A factor that is not
+ *     positive definite after damping is reported through d_info (0 = ok,
+ *     k > 0 = the k-th pivot was not positive, 1-based); the contents of that
+ *     inverse are then unspecified (finite or not), other matrices are unaffected.
+ *   - Results are run-to-run bitwise reproducible (fixed reduction order, no
+ *     floating-point atomics).
+ */
+#ifndef KFAC_H
+#define KFAC_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KFAC_OK = 0,
+    KFAC_ERR_NULL = 1,       /* a required pointer is NULL */
+    KFAC_ERR_SHAPE = 2,      /* non-positive or inconsistent dimensions */
+    KFAC_ERR_DTYPE = 3,      /* unknown in_dtype / kind */
+    KFAC_ERR_WORKSPACE = 4,  /* workspace smaller than kfac_workspace_bytes says */
+    KFAC_ERR_PARAM = 5,      /* decay outside [0,1], negative damping, scale <= 0 */
+    KFAC_ERR_HIP = 6,        /* a HIP launch failed */
+    KFAC_ERR_ALIGN = 7       /* a device pointer is not aligned to its element type */
+} kfac_status;
+
+typedef enum { KFAC_F32 = 0, KFAC_BF16 = 1 } kfac_dtype;
+typedef enum { KFAC_LINEAR = 0, KFAC_CONV2D = 1 } kfac_kind;
+
+/* Plain data, copied by value. */
+typedef struct {
+    int kind;        /* kfac_kind */
+    int d_in;        /* LINEAR: input features.  CONV2D: input channels C_in */
+    int d_out;       /* LINEAR: output features. CONV2D: output channels C_out */
+    int kh, kw;      /* CONV2D: kernel size (groups 1, dilation 1); LINEAR: ignored */
+    int stride, pad; /* CONV2D only */
+    int has_bias;    /* 1: homogeneous column appended last, d_A = d_in*kh*kw + 1 */
+    int in_dtype;    /* kfac_dtype of activations and output gradients */
+} kfac_layer_desc;
+
+/* Order of the factors (section 3: A is d_{i-1} x d_{i-1}, G is d_i x d_i). */
+int kfac_dim_A(const kfac_layer_desc *desc);
+int kfac_dim_G(const kfac_layer_desc *desc);
+
+/* Leading dimension (in elements) of the patch matrix kfac_im2col writes:
+ * d_in*kh*kw rounded up to 16 bytes.  The bias column is not materialised. */
+int kfac_patch_ld(const kfac_layer_desc *desc);
+
+/* Bytes of workspace sufficient for any of the three per-layer calls. */
+size_t kfac_workspace_bytes(const kfac_layer_desc *desc, int batch, int h, int w);
+/* Same for the batched calls over n layers (host arrays). */
+size_t kfac_workspace_bytes_batched(int n, const kfac_layer_desc *descs, const int *batch, const int *h,
+                                    const int *w);
+
+/* Patch extraction alone (the first step of kfac_update_factors for CONV2D
+ * layers with kh*kw > 1 or stride > 1): d_patches is row-major
+ * [batch*h_out*w_out, kfac_patch_ld], row (n, oh, ow), column (c, i, j), zero
+ * padding, pad columns zero; same element type as the input. */
+kfac_status kfac_im2col(const kfac_layer_desc *desc, const void *d_act, int batch, int h, int w,
+                        void *d_patches, void *hip_stream);
+
+/* Factor construction + running average (Eq. 4, Eqs. 10-11).  LINEAR: rows =
+ * batch, h = w = 1.  d_A_run [d_A, d_A], d_G_run [d_G, d_G] are updated in place. */
+kfac_status kfac_update_factors(const kfac_layer_desc *desc, const void *d_act, const void *d_gout, int batch,
+                                int h, int w, float scale_A, float scale_G, float decay, float *d_A_run,
+                                float *d_G_run, void *d_work, size_t work_bytes, void *hip_stream);
+
+/* Damped inverses (section 5.2, matrix-inversion variant with the damping of
+ * each factor given explicitly).  d_info: 2 ints (A, G). */
+kfac_status kfac_invert(const kfac_layer_desc *desc, const float *d_A_run, const float *d_G_run,
+                        float damping_A, float damping_G, float *d_A_inv, float *d_G_inv, int *d_info,
+                        void *d_work, size_t work_bytes, void *hip_stream);
+
+/* P = G_inv * grad * A_inv (Eq. 5 / right-hand side of Eq. 12).  d_out may alias d_grad. */
+kfac_status kfac_precondition(const kfac_layer_desc *desc, const float *d_A_inv, const float *d_G_inv,
+                              const float *d_grad, float *d_out, void *d_work, size_t work_bytes,
+                              void *hip_stream);
+
+/* Grouped forms: the same three operations for n layers in one launch
+ * sequence (layers of one size class share kernel launches).  Host arrays of
+ * length n; d_info holds 2*n ints, (A, G) per layer. */
+kfac_status kfac_update_factors_batched(int n, const kfac_layer_desc *descs, const void *const *d_act,
+                                        const void *const *d_gout, const int *batch, const int *h,
+                                        const int *w, const float *scale_A, const float *scale_G, float decay,
+                                        float *const *d_A_run, float *const *d_G_run, void *d_work,
+                                        size_t work_bytes, void *hip_stream);
+kfac_status kfac_invert_batched(int n, const kfac_layer_desc *descs, const float *const *d_A_run,
+                                const float *const *d_G_run, float damping_A, float damping_G,
+                                float *const *d_A_inv, float *const *d_G_inv, int *d_info, void *d_work,
+                                size_t work_bytes, void *hip_stream);
+kfac_status kfac_precondition_batched(int n, const kfac_layer_desc *descs, const float *const *d_A_inv,
+                                      const float *const *d_G_inv, const float *const *d_grad,
+                                      float *const *d_out, void *d_work, size_t work_bytes, void *hip_stream);
+
+const char *kfac_status_string(kfac_status s);
+int kfac_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KFAC_H */

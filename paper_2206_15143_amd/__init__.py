@@ -1,0 +1,13 @@
+"""MI355X (gfx950) K-FAC second-order update: thin Python binding over the C-ABI HIP library.
+
+Every arithmetic step runs in the HIP kernels of libkfac_hip.so; this package
+only marshals arguments.  PyTorch is used for device memory and streams.
+"""
+from .binding import (  # noqa: F401
+    LayerDesc, KfacError, lib_path, load_library,
+    kfac_dim_A, kfac_dim_G, kfac_patch_ld, kfac_workspace_bytes, kfac_workspace_bytes_batched,
+    kfac_im2col, kfac_update_factors, kfac_invert, kfac_precondition,
+    kfac_update_factors_batched, kfac_invert_batched, kfac_precondition_batched,
+    kfac_status_string, kfac_version, kfac_tune,
+    KFAC_F32, KFAC_BF16, KFAC_LINEAR, KFAC_CONV2D,
+)

@@ -1,0 +1,214 @@
+"""ctypes binding with the same names as include/kfac.h (argument marshalling only).
+
+Tensors are torch CUDA tensors (or anything with ``data_ptr()``); raw integer
+device addresses are accepted too.  The HIP library must have been built
+(``python -m paper_2206_15143_amd.build``); there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+KFAC_F32, KFAC_BF16 = 0, 1
+KFAC_LINEAR, KFAC_CONV2D = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_NAME = "libkfac_hip.so"
+_lib = None
+
+
+class KfacError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = int(status)
+        super().__init__(f"{where}: {kfac_status_string(status)} (status {int(status)})")
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [("kind", C.c_int), ("d_in", C.c_int), ("d_out", C.c_int), ("kh", C.c_int), ("kw", C.c_int),
+                ("stride", C.c_int), ("pad", C.c_int), ("has_bias", C.c_int), ("in_dtype", C.c_int)]
+
+    @staticmethod
+    def linear(d_in: int, d_out: int, has_bias: bool = True, dtype: int = KFAC_F32) -> "LayerDesc":
+        return LayerDesc(KFAC_LINEAR, d_in, d_out, 1, 1, 1, 0, int(has_bias), dtype)
+
+    @staticmethod
+    def conv2d(c_in: int, c_out: int, k: int, stride: int = 1, pad: int = 0, has_bias: bool = True,
+               dtype: int = KFAC_F32, kw: Optional[int] = None) -> "LayerDesc":
+        return LayerDesc(KFAC_CONV2D, c_in, c_out, k, k if kw is None else kw, stride, pad, int(has_bias), dtype)
+
+    @staticmethod
+    def from_spec(spec, dtype: int = KFAC_F32) -> "LayerDesc":
+        """From a workloads.LayerSpec-like object (kind, c_in, c_out, k, stride, pad, has_bias)."""
+        if spec.kind == "conv":
+            return LayerDesc.conv2d(spec.c_in, spec.c_out, spec.k, spec.stride, spec.pad, spec.has_bias, dtype)
+        return LayerDesc.linear(spec.c_in, spec.c_out, spec.has_bias, dtype)
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, _LIB_NAME)
+
+
+def load_library():
+    """Load libkfac_hip.so; raises ImportError when it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it with `python -m paper_2206_15143_amd.build` "
+                          "(there is no CPU or PyTorch fallback)")
+    lib = C.CDLL(path)
+    vp, ip, fp, sz = C.c_void_p, C.POINTER(C.c_int), C.POINTER(C.c_float), C.c_size_t
+    dp = C.POINTER(LayerDesc)
+    vpp = C.POINTER(C.c_void_p)
+    lib.kfac_dim_A.argtypes = [dp]; lib.kfac_dim_A.restype = C.c_int
+    lib.kfac_dim_G.argtypes = [dp]; lib.kfac_dim_G.restype = C.c_int
+    lib.kfac_patch_ld.argtypes = [dp]; lib.kfac_patch_ld.restype = C.c_int
+    lib.kfac_workspace_bytes.argtypes = [dp, C.c_int, C.c_int, C.c_int]; lib.kfac_workspace_bytes.restype = sz
+    lib.kfac_workspace_bytes_batched.argtypes = [C.c_int, dp, ip, ip, ip]
+    lib.kfac_workspace_bytes_batched.restype = sz
+    lib.kfac_im2col.argtypes = [dp, vp, C.c_int, C.c_int, C.c_int, vp, vp]; lib.kfac_im2col.restype = C.c_int
+    lib.kfac_update_factors.argtypes = [dp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_float, C.c_float, C.c_float,
+                                        vp, vp, vp, sz, vp]
+    lib.kfac_update_factors.restype = C.c_int
+    lib.kfac_invert.argtypes = [dp, vp, vp, C.c_float, C.c_float, vp, vp, vp, vp, sz, vp]
+    lib.kfac_invert.restype = C.c_int
+    lib.kfac_precondition.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]; lib.kfac_precondition.restype = C.c_int
+    lib.kfac_update_factors_batched.argtypes = [C.c_int, dp, vpp, vpp, ip, ip, ip, fp, fp, C.c_float, vpp, vpp,
+                                                vp, sz, vp]
+    lib.kfac_update_factors_batched.restype = C.c_int
+    lib.kfac_invert_batched.argtypes = [C.c_int, dp, vpp, vpp, C.c_float, C.c_float, vpp, vpp, vp, vp, sz, vp]
+    lib.kfac_invert_batched.restype = C.c_int
+    lib.kfac_precondition_batched.argtypes = [C.c_int, dp, vpp, vpp, vpp, vpp, vp, sz, vp]
+    lib.kfac_precondition_batched.restype = C.c_int
+    lib.kfac_status_string.argtypes = [C.c_int]; lib.kfac_status_string.restype = C.c_char_p
+    lib.kfac_version.argtypes = []; lib.kfac_version.restype = C.c_int
+    lib.kfac_tune.argtypes = [C.c_char_p, C.c_long]; lib.kfac_tune.restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return int(t.data_ptr())
+
+
+def _nbytes(t) -> int:
+    if t is None:
+        return 0
+    return int(t.numel() * t.element_size())
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream) or None
+    if isinstance(stream, int):
+        return stream or None
+    return int(stream.cuda_stream) or None
+
+
+def _check(st: int, where: str):
+    if st != 0:
+        raise KfacError(st, where)
+
+
+def _descs(descs: Sequence[LayerDesc]):
+    return (LayerDesc * len(descs))(*descs)
+
+
+def _ints(v: Sequence[int]):
+    return (C.c_int * len(v))(*[int(x) for x in v])
+
+
+def _floats(v: Sequence[float]):
+    return (C.c_float * len(v))(*[float(x) for x in v])
+
+
+def _ptrs(ts):
+    return (C.c_void_p * len(ts))(*[_ptr(t) for t in ts])
+
+
+def kfac_status_string(status: int) -> str:
+    return load_library().kfac_status_string(int(status)).decode()
+
+
+def kfac_version() -> int:
+    return int(load_library().kfac_version())
+
+
+def kfac_tune(key: str, value: int) -> None:
+    if load_library().kfac_tune(key.encode(), int(value)) != 0:
+        raise KeyError(key)
+
+
+def kfac_dim_A(desc: LayerDesc) -> int:
+    return int(load_library().kfac_dim_A(C.byref(desc)))
+
+
+def kfac_dim_G(desc: LayerDesc) -> int:
+    return int(load_library().kfac_dim_G(C.byref(desc)))
+
+
+def kfac_patch_ld(desc: LayerDesc) -> int:
+    return int(load_library().kfac_patch_ld(C.byref(desc)))
+
+
+def kfac_workspace_bytes(desc: LayerDesc, batch: int, h: int = 1, w: int = 1) -> int:
+    return int(load_library().kfac_workspace_bytes(C.byref(desc), batch, h, w))
+
+
+def kfac_workspace_bytes_batched(descs, batch, h, w) -> int:
+    return int(load_library().kfac_workspace_bytes_batched(len(descs), _descs(descs), _ints(batch), _ints(h),
+                                                           _ints(w)))
+
+
+def kfac_im2col(desc, act, batch, h, w, patches, stream=None) -> None:
+    _check(load_library().kfac_im2col(C.byref(desc), _ptr(act), batch, h, w, _ptr(patches), _stream(stream)),
+           "kfac_im2col")
+
+
+def kfac_update_factors(desc, act, gout, batch, h, w, scale_A, scale_G, decay, A_run, G_run, work,
+                        stream=None) -> None:
+    _check(load_library().kfac_update_factors(C.byref(desc), _ptr(act), _ptr(gout), batch, h, w, scale_A, scale_G,
+                                              decay, _ptr(A_run), _ptr(G_run), _ptr(work), _nbytes(work),
+                                              _stream(stream)), "kfac_update_factors")
+
+
+def kfac_invert(desc, A_run, G_run, damping_A, damping_G, A_inv, G_inv, info, work, stream=None) -> None:
+    _check(load_library().kfac_invert(C.byref(desc), _ptr(A_run), _ptr(G_run), damping_A, damping_G, _ptr(A_inv),
+                                      _ptr(G_inv), _ptr(info), _ptr(work), _nbytes(work), _stream(stream)),
+           "kfac_invert")
+
+
+def kfac_precondition(desc, A_inv, G_inv, grad, out, work, stream=None) -> None:
+    _check(load_library().kfac_precondition(C.byref(desc), _ptr(A_inv), _ptr(G_inv), _ptr(grad), _ptr(out),
+                                            _ptr(work), _nbytes(work), _stream(stream)), "kfac_precondition")
+
+
+def kfac_update_factors_batched(descs, acts, gouts, batch, h, w, scale_A, scale_G, decay, A_runs, G_runs, work,
+                                stream=None) -> None:
+    n = len(descs)
+    _check(load_library().kfac_update_factors_batched(n, _descs(descs), _ptrs(acts), _ptrs(gouts), _ints(batch),
+                                                      _ints(h), _ints(w), _floats(scale_A), _floats(scale_G), decay,
+                                                      _ptrs(A_runs), _ptrs(G_runs), _ptr(work), _nbytes(work),
+                                                      _stream(stream)), "kfac_update_factors_batched")
+
+
+def kfac_invert_batched(descs, A_runs, G_runs, damping_A, damping_G, A_invs, G_invs, info, work,
+                        stream=None) -> None:
+    n = len(descs)
+    _check(load_library().kfac_invert_batched(n, _descs(descs), _ptrs(A_runs), _ptrs(G_runs), damping_A, damping_G,
+                                              _ptrs(A_invs), _ptrs(G_invs), _ptr(info), _ptr(work), _nbytes(work),
+                                              _stream(stream)), "kfac_invert_batched")
+
+
+def kfac_precondition_batched(descs, A_invs, G_invs, grads, outs, work, stream=None) -> None:
+    n = len(descs)
+    _check(load_library().kfac_precondition_batched(n, _descs(descs), _ptrs(A_invs), _ptrs(G_invs), _ptrs(grads),
+                                                    _ptrs(outs), _ptr(work), _nbytes(work), _stream(stream)),
+           "kfac_precondition_batched")

@@ -1,0 +1,436 @@
+// C ABI of the library (see include/kfac.h): argument validation, workspace
+// planning and the launch sequences.  No arithmetic happens on the host.
+#include "../../include/kfac.h"
+
+#include "common.hpp"
+
+#include <cstring>
+#include <string>
+#include <vector>
+
+namespace kfac {
+
+Tuning &tuning()
+{
+    static Tuning t;
+    return t;
+}
+
+namespace {
+
+struct Geo {
+    int dA, dG, d_core;
+    int Ho, Wo;
+    long R;             // rows of the patch matrix / samples
+    bool conv, patches; // patches: the extractor has to run
+    int ld;             // patch leading dimension (elements)
+    int esz;
+};
+
+bool desc_ok(const kfac_layer_desc *d)
+{
+    if (!d) return false;
+    if (d->kind != KFAC_LINEAR && d->kind != KFAC_CONV2D) return false;
+    if (d->in_dtype != KFAC_F32 && d->in_dtype != KFAC_BF16) return false;
+    return true;
+}
+
+kfac_status desc_check(const kfac_layer_desc *d)
+{
+    if (!d) return KFAC_ERR_NULL;
+    if (!desc_ok(d)) return KFAC_ERR_DTYPE;
+    if (d->d_in <= 0 || d->d_out <= 0) return KFAC_ERR_SHAPE;
+    if (d->has_bias != 0 && d->has_bias != 1) return KFAC_ERR_SHAPE;
+    if (d->kind == KFAC_CONV2D) {
+        if (d->kh <= 0 || d->kw <= 0 || d->stride <= 0 || d->pad < 0) return KFAC_ERR_SHAPE;
+        if ((long)d->d_in * d->kh * d->kw > (1l << 24)) return KFAC_ERR_SHAPE;
+    }
+    return KFAC_OK;
+}
+
+int core_dim(const kfac_layer_desc *d)
+{
+    return d->kind == KFAC_CONV2D ? d->d_in * d->kh * d->kw : d->d_in;
+}
+
+kfac_status geometry(const kfac_layer_desc *d, int batch, int h, int w, Geo &g)
+{
+    kfac_status st = desc_check(d);
+    if (st != KFAC_OK) return st;
+    if (batch <= 0) return KFAC_ERR_SHAPE;
+    g.esz = d->in_dtype == KFAC_F32 ? 4 : 2;
+    g.d_core = core_dim(d);
+    g.dA = g.d_core + d->has_bias;
+    g.dG = d->d_out;
+    g.conv = d->kind == KFAC_CONV2D;
+    const int vec = 16 / g.esz;
+    g.ld = (g.d_core + vec - 1) / vec * vec;
+    if (g.conv) {
+        if (h <= 0 || w <= 0) return KFAC_ERR_SHAPE;
+        if (h + 2 * d->pad < d->kh || w + 2 * d->pad < d->kw) return KFAC_ERR_SHAPE;
+        g.Ho = (h + 2 * d->pad - d->kh) / d->stride + 1;
+        g.Wo = (w + 2 * d->pad - d->kw) / d->stride + 1;
+        g.R = (long)batch * g.Ho * g.Wo;
+        g.patches = !(d->kh == 1 && d->kw == 1 && d->stride == 1 && d->pad == 0);
+    } else {
+        g.Ho = g.Wo = 1;
+        g.R = batch;
+        g.patches = false;
+    }
+    return KFAC_OK;
+}
+
+size_t patch_bytes(const Geo &g) { return g.patches ? align_up((size_t)g.R * g.ld * g.esz, 256) : 0; }
+
+bool aligned(const void *p, size_t a) { return ((uintptr_t)p) % a == 0; }
+
+// jobs of one layer; `patches` is where its patch matrix lives (if needed)
+void layer_jobs(const kfac_layer_desc *d, const Geo &g, const void *act, const void *gout, int batch, int h,
+                int w, float sA, float sG, float decay, float *A_run, float *G_run, void *patches,
+                std::vector<Im2colJob> &ij, std::vector<FactorJob> &fj)
+{
+    FactorJob a{};
+    a.dtype = d->in_dtype;
+    a.has_bias = d->has_bias;
+    a.scale = sA;
+    a.decay = decay;
+    a.F = A_run;
+    a.d_core = g.d_core;
+    a.K = g.R;
+    if (!g.conv) {
+        a.x = act; a.layout = kRows; a.ld = d->d_in; a.hw = 1; a.ctot = d->d_in;
+    } else if (!g.patches) {
+        a.x = act; a.layout = kNCHW; a.ld = 0; a.hw = h * w; a.ctot = d->d_in;
+    } else {
+        Im2colJob j{};
+        j.x = act; j.out = patches; j.dtype = d->in_dtype;
+        j.B = batch; j.C = d->d_in; j.H = h; j.W = w; j.kh = d->kh; j.kw = d->kw;
+        j.stride = d->stride; j.pad = d->pad; j.Ho = g.Ho; j.Wo = g.Wo; j.ld = g.ld;
+        ij.push_back(j);
+        a.x = patches; a.layout = kRows; a.ld = g.ld; a.hw = 1; a.ctot = g.d_core;
+    }
+    fj.push_back(a);
+
+    FactorJob q{};
+    q.dtype = d->in_dtype;
+    q.has_bias = 0;
+    q.scale = sG;
+    q.decay = decay;
+    q.F = G_run;
+    q.d_core = g.dG;
+    q.K = g.R;
+    q.x = gout;
+    if (!g.conv) {
+        q.layout = kRows; q.ld = d->d_out; q.hw = 1; q.ctot = d->d_out;
+    } else {
+        q.layout = kNCHW; q.ld = 0; q.hw = g.Ho * g.Wo; q.ctot = d->d_out;
+    }
+    fj.push_back(q);
+}
+
+// Layers are processed in chunks whose patch matrices fit a byte budget, so
+// that a chunk's patches are still cache resident when its factor kernel
+// reads them.
+struct Chunk { int first, last; };   // [first, last)
+
+std::vector<Chunk> make_chunks(const std::vector<Geo> &geo)
+{
+    std::vector<Chunk> out;
+    const size_t budget = (size_t)tuning().patch_chunk_bytes;
+    size_t acc = 0;
+    int first = 0;
+    const int n = (int)geo.size();
+    for (int i = 0; i < n; ++i) {
+        const size_t pb = patch_bytes(geo[i]);
+        if (i > first && (acc + pb > budget || i - first >= kMaxProblems / 2)) {
+            out.push_back({first, i});
+            first = i;
+            acc = 0;
+        }
+        acc += pb;
+    }
+    if (first < n) out.push_back({first, n});
+    return out;
+}
+
+struct UpdatePlan {
+    std::vector<Geo> geo;
+    std::vector<Chunk> chunks;
+    size_t patch_region = 0, syrk_region = 0;
+};
+
+kfac_status plan_update(int n, const kfac_layer_desc *descs, const int *batch, const int *h, const int *w,
+                        UpdatePlan &pl)
+{
+    pl.geo.resize(n);
+    for (int i = 0; i < n; ++i) {
+        kfac_status st = geometry(&descs[i], batch[i], h ? h[i] : 1, w ? w[i] : 1, pl.geo[i]);
+        if (st != KFAC_OK) return st;
+    }
+    pl.chunks = make_chunks(pl.geo);
+    for (const Chunk &c : pl.chunks) {
+        size_t pb = 0;
+        std::vector<Im2colJob> ij;
+        std::vector<FactorJob> fj;
+        for (int i = c.first; i < c.last; ++i) {
+            // placeholder pointers: only shapes matter for the workspace plan (but alignment
+            // decides nothing about sizes)
+            layer_jobs(&descs[i], pl.geo[i], nullptr, nullptr, batch[i], h ? h[i] : 1, w ? w[i] : 1, 1.f, 1.f,
+                       0.f, nullptr, nullptr, nullptr, ij, fj);
+            pb += patch_bytes(pl.geo[i]);
+        }
+        pl.patch_region = std::max(pl.patch_region, pb);
+        pl.syrk_region = std::max(pl.syrk_region, syrk_workspace_bytes(fj.data(), (int)fj.size()));
+    }
+    return KFAC_OK;
+}
+
+size_t invert_ws(int n, const kfac_layer_desc *descs)
+{
+    std::vector<InvertJob> jobs;
+    for (int i = 0; i < n; ++i) {
+        InvertJob a{}; a.n = core_dim(&descs[i]) + descs[i].has_bias; jobs.push_back(a);
+        InvertJob g{}; g.n = descs[i].d_out; jobs.push_back(g);
+    }
+    return invert_workspace_bytes(jobs.data(), (int)jobs.size());
+}
+
+size_t precond_ws(int n, const kfac_layer_desc *descs)
+{
+    size_t total = 0;
+    for (int i = 0; i < n; ++i) {
+        const size_t dA = core_dim(&descs[i]) + descs[i].has_bias, dG = descs[i].d_out;
+        total += align_up(dA * dG * sizeof(float), 256);
+    }
+    return total;
+}
+
+}  // namespace
+}  // namespace kfac
+
+using namespace kfac;
+
+extern "C" {
+
+int kfac_dim_A(const kfac_layer_desc *d)
+{
+    if (desc_check(d) != KFAC_OK) return -1;
+    return core_dim(d) + d->has_bias;
+}
+
+int kfac_dim_G(const kfac_layer_desc *d)
+{
+    if (desc_check(d) != KFAC_OK) return -1;
+    return d->d_out;
+}
+
+int kfac_patch_ld(const kfac_layer_desc *d)
+{
+    if (desc_check(d) != KFAC_OK) return -1;
+    const int vec = d->in_dtype == KFAC_F32 ? 4 : 8;
+    return (core_dim(d) + vec - 1) / vec * vec;
+}
+
+size_t kfac_workspace_bytes_batched(int n, const kfac_layer_desc *descs, const int *batch, const int *h,
+                                    const int *w)
+{
+    if (n <= 0 || !descs || !batch) return 0;
+    UpdatePlan pl;
+    if (plan_update(n, descs, batch, h, w, pl) != KFAC_OK) return 0;
+    size_t need = pl.patch_region + pl.syrk_region;
+    need = std::max(need, invert_ws(n, descs));
+    need = std::max(need, precond_ws(n, descs));
+    return need + 256;
+}
+
+size_t kfac_workspace_bytes(const kfac_layer_desc *d, int batch, int h, int w)
+{
+    return kfac_workspace_bytes_batched(1, d, &batch, &h, &w);
+}
+
+kfac_status kfac_im2col(const kfac_layer_desc *d, const void *d_act, int batch, int h, int w, void *d_patches,
+                        void *hip_stream)
+{
+    Geo g;
+    kfac_status st = geometry(d, batch, h, w, g);
+    if (st != KFAC_OK) return st;
+    if (!g.conv) return KFAC_ERR_SHAPE;
+    if (!d_act || !d_patches) return KFAC_ERR_NULL;
+    if (!aligned(d_act, g.esz) || !aligned(d_patches, 16)) return KFAC_ERR_ALIGN;
+    Im2colJob j{};
+    j.x = d_act; j.out = d_patches; j.dtype = d->in_dtype;
+    j.B = batch; j.C = d->d_in; j.H = h; j.W = w; j.kh = d->kh; j.kw = d->kw;
+    j.stride = d->stride; j.pad = d->pad; j.Ho = g.Ho; j.Wo = g.Wo; j.ld = g.ld;
+    return im2col_launch(&j, 1, (hipStream_t)hip_stream) == hipSuccess ? KFAC_OK : KFAC_ERR_HIP;
+}
+
+kfac_status kfac_update_factors_batched(int n, const kfac_layer_desc *descs, const void *const *d_act,
+                                        const void *const *d_gout, const int *batch, const int *h,
+                                        const int *w, const float *scale_A, const float *scale_G, float decay,
+                                        float *const *d_A_run, float *const *d_G_run, void *d_work,
+                                        size_t work_bytes, void *hip_stream)
+{
+    if (n <= 0) return KFAC_ERR_SHAPE;
+    if (!descs || !d_act || !d_gout || !batch || !scale_A || !scale_G || !d_A_run || !d_G_run)
+        return KFAC_ERR_NULL;
+    if (!(decay >= 0.f && decay <= 1.f)) return KFAC_ERR_PARAM;
+    UpdatePlan pl;
+    kfac_status st = plan_update(n, descs, batch, h, w, pl);
+    if (st != KFAC_OK) return st;
+    for (int i = 0; i < n; ++i) {
+        if (!d_act[i] || !d_gout[i] || !d_A_run[i] || !d_G_run[i]) return KFAC_ERR_NULL;
+        if (!(scale_A[i] > 0.f) || !(scale_G[i] > 0.f)) return KFAC_ERR_PARAM;
+        if (descs[i].kind == KFAC_CONV2D && (!h || !w)) return KFAC_ERR_NULL;
+        if (!aligned(d_act[i], pl.geo[i].esz) || !aligned(d_gout[i], pl.geo[i].esz) ||
+            !aligned(d_A_run[i], 4) || !aligned(d_G_run[i], 4))
+            return KFAC_ERR_ALIGN;
+    }
+    const size_t need = pl.patch_region + pl.syrk_region;
+    if (need > 0 && !d_work) return KFAC_ERR_NULL;
+    if (work_bytes < need || !aligned(d_work, 256)) return d_work && !aligned(d_work, 256) ? KFAC_ERR_ALIGN
+                                                                                           : KFAC_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    char *patch_base = static_cast<char *>(d_work);
+    char *syrk_base = patch_base + pl.patch_region;
+    for (const Chunk &c : pl.chunks) {
+        std::vector<Im2colJob> ij;
+        std::vector<FactorJob> fj;
+        size_t poff = 0;
+        for (int i = c.first; i < c.last; ++i) {
+            layer_jobs(&descs[i], pl.geo[i], d_act[i], d_gout[i], batch[i], h ? h[i] : 1, w ? w[i] : 1,
+                       scale_A[i], scale_G[i], decay, d_A_run[i], d_G_run[i], patch_base + poff, ij, fj);
+            poff += patch_bytes(pl.geo[i]);
+        }
+        if (!ij.empty() && im2col_launch(ij.data(), (int)ij.size(), s) != hipSuccess) return KFAC_ERR_HIP;
+        if (syrk_launch(fj.data(), (int)fj.size(), syrk_base, pl.syrk_region, s) != hipSuccess)
+            return KFAC_ERR_HIP;
+    }
+    return KFAC_OK;
+}
+
+kfac_status kfac_update_factors(const kfac_layer_desc *d, const void *d_act, const void *d_gout, int batch, int h,
+                                int w, float scale_A, float scale_G, float decay, float *d_A_run,
+                                float *d_G_run, void *d_work, size_t work_bytes, void *hip_stream)
+{
+    if (!d) return KFAC_ERR_NULL;
+    return kfac_update_factors_batched(1, d, &d_act, &d_gout, &batch, &h, &w, &scale_A, &scale_G, decay,
+                                       &d_A_run, &d_G_run, d_work, work_bytes, hip_stream);
+}
+
+kfac_status kfac_invert_batched(int n, const kfac_layer_desc *descs, const float *const *d_A_run,
+                                const float *const *d_G_run, float damping_A, float damping_G,
+                                float *const *d_A_inv, float *const *d_G_inv, int *d_info, void *d_work,
+                                size_t work_bytes, void *hip_stream)
+{
+    if (n <= 0) return KFAC_ERR_SHAPE;
+    if (!descs || !d_A_run || !d_G_run || !d_A_inv || !d_G_inv || !d_info || !d_work) return KFAC_ERR_NULL;
+    if (!(damping_A >= 0.f) || !(damping_G >= 0.f)) return KFAC_ERR_PARAM;
+    std::vector<InvertJob> jobs;
+    for (int i = 0; i < n; ++i) {
+        kfac_status st = desc_check(&descs[i]);
+        if (st != KFAC_OK) return st;
+        if (!d_A_run[i] || !d_G_run[i] || !d_A_inv[i] || !d_G_inv[i]) return KFAC_ERR_NULL;
+        if (!aligned(d_A_run[i], 4) || !aligned(d_G_run[i], 4) || !aligned(d_A_inv[i], 4) ||
+            !aligned(d_G_inv[i], 4))
+            return KFAC_ERR_ALIGN;
+        if (d_A_run[i] == d_A_inv[i] || d_G_run[i] == d_G_inv[i]) return KFAC_ERR_PARAM;
+        InvertJob a{};
+        a.M = d_A_run[i]; a.Minv = d_A_inv[i]; a.n = core_dim(&descs[i]) + descs[i].has_bias;
+        a.damping = damping_A; a.info = d_info + 2 * i;
+        jobs.push_back(a);
+        InvertJob g{};
+        g.M = d_G_run[i]; g.Minv = d_G_inv[i]; g.n = descs[i].d_out;
+        g.damping = damping_G; g.info = d_info + 2 * i + 1;
+        jobs.push_back(g);
+    }
+    if (!aligned(d_work, 256)) return KFAC_ERR_ALIGN;
+    if (invert_workspace_bytes(jobs.data(), (int)jobs.size()) > work_bytes) return KFAC_ERR_WORKSPACE;
+    return invert_launch(jobs.data(), (int)jobs.size(), d_work, work_bytes, (hipStream_t)hip_stream) == hipSuccess
+               ? KFAC_OK
+               : KFAC_ERR_HIP;
+}
+
+kfac_status kfac_invert(const kfac_layer_desc *d, const float *d_A_run, const float *d_G_run, float damping_A,
+                        float damping_G, float *d_A_inv, float *d_G_inv, int *d_info, void *d_work,
+                        size_t work_bytes, void *hip_stream)
+{
+    if (!d) return KFAC_ERR_NULL;
+    return kfac_invert_batched(1, d, &d_A_run, &d_G_run, damping_A, damping_G, &d_A_inv, &d_G_inv, d_info,
+                               d_work, work_bytes, hip_stream);
+}
+
+kfac_status kfac_precondition_batched(int n, const kfac_layer_desc *descs, const float *const *d_A_inv,
+                                      const float *const *d_G_inv, const float *const *d_grad,
+                                      float *const *d_out, void *d_work, size_t work_bytes, void *hip_stream)
+{
+    if (n <= 0) return KFAC_ERR_SHAPE;
+    if (!descs || !d_A_inv || !d_G_inv || !d_grad || !d_out || !d_work) return KFAC_ERR_NULL;
+    for (int i = 0; i < n; ++i) {
+        kfac_status st = desc_check(&descs[i]);
+        if (st != KFAC_OK) return st;
+        if (!d_A_inv[i] || !d_G_inv[i] || !d_grad[i] || !d_out[i]) return KFAC_ERR_NULL;
+        if (!aligned(d_A_inv[i], 4) || !aligned(d_G_inv[i], 4) || !aligned(d_grad[i], 4) || !aligned(d_out[i], 4))
+            return KFAC_ERR_ALIGN;
+    }
+    if (!aligned(d_work, 256)) return KFAC_ERR_ALIGN;
+    if (precond_ws(n, descs) > work_bytes) return KFAC_ERR_WORKSPACE;
+    std::vector<GemmJob> g1(n), g2(n);
+    size_t off = 0;
+    for (int i = 0; i < n; ++i) {
+        const int dA = core_dim(&descs[i]) + descs[i].has_bias, dG = descs[i].d_out;
+        float *Ut = reinterpret_cast<float *>(static_cast<char *>(d_work) + off);
+        off += align_up((size_t)dA * dG * sizeof(float), 256);
+        // U^T[dA, dG] = (G_inv grad)^T : A = G_inv (symmetric, read as its transpose), B = grad
+        GemmJob &a = g1[i];
+        a.A = d_G_inv[i]; a.B = d_grad[i]; a.C = Ut;
+        a.M = dG; a.N = dA; a.K = dG; a.lda = dG; a.ldb = dA; a.ldc = dG; a.mode = kStoreT; a.p0 = a.p1 = 0;
+        // P[dG, dA] = (U^T)^T A_inv
+        GemmJob &b = g2[i];
+        b.A = Ut; b.B = d_A_inv[i]; b.C = d_out[i];
+        b.M = dG; b.N = dA; b.K = dA; b.lda = dG; b.ldb = dA; b.ldc = dA; b.mode = kStore; b.p0 = b.p1 = 0;
+    }
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (gemm_launch(g1.data(), n, s) != hipSuccess) return KFAC_ERR_HIP;
+    if (gemm_launch(g2.data(), n, s) != hipSuccess) return KFAC_ERR_HIP;
+    return KFAC_OK;
+}
+
+kfac_status kfac_precondition(const kfac_layer_desc *d, const float *d_A_inv, const float *d_G_inv,
+                              const float *d_grad, float *d_out, void *d_work, size_t work_bytes,
+                              void *hip_stream)
+{
+    if (!d) return KFAC_ERR_NULL;
+    return kfac_precondition_batched(1, d, &d_A_inv, &d_G_inv, &d_grad, &d_out, d_work, work_bytes, hip_stream);
+}
+
+const char *kfac_status_string(kfac_status s)
+{
+    switch (s) {
+        case KFAC_OK: return "ok";
+        case KFAC_ERR_NULL: return "null pointer";
+        case KFAC_ERR_SHAPE: return "bad shape";
+        case KFAC_ERR_DTYPE: return "bad dtype or layer kind";
+        case KFAC_ERR_WORKSPACE: return "workspace too small";
+        case KFAC_ERR_PARAM: return "bad parameter";
+        case KFAC_ERR_HIP: return "HIP launch failed";
+        case KFAC_ERR_ALIGN: return "misaligned pointer";
+    }
+    return "unknown status";
+}
+
+int kfac_version(void) { return 100; }
+
+/* Development knob (not part of the documented ABI): returns 0 when the key is known. */
+int kfac_tune(const char *key, long value)
+{
+    Tuning &t = tuning();
+    const std::string k(key ? key : "");
+    if (k == "target_blocks") t.target_blocks = value;
+    else if (k == "min_tiles_per_split") t.min_tiles_per_split = value;
+    else if (k == "patch_chunk_bytes") t.patch_chunk_bytes = value;
+    else if (k == "syrk_force_bm") t.syrk_force_bm = value;
+    else return 1;
+    return 0;
+}
+
+}  // extern "C"

@@ -1,0 +1,93 @@
+// Shared host/device declarations of the K-FAC HIP library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include <vector>
+
+namespace kfac {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kMaxProblems = 40;   // problems per grouped launch (table travels as a kernel argument)
+
+enum Layout : int {
+    kRows = 0,   // X is [K, ld] row-major: element (k, c) at k*ld + c
+    kNCHW = 1    // X is [n][ctot][hw]: element (k = n*hw + p, c) at (n*ctot + c)*hw + p
+};
+
+// One factor to build: F <- decay*F + (1-decay)*scale*X^T X  (+ bias border).
+struct FactorJob {
+    const void *x;
+    int dtype;       // 0 fp32, 1 bf16
+    int layout;      // Layout
+    long K;          // number of rows (samples x positions)
+    long ld;         // kRows: row pitch in elements
+    int d_core;      // real columns of X
+    int hw, ctot;    // kNCHW addressing
+    int has_bias;    // factor has one more row/column: column sums and the count K
+    float scale, decay;
+    float *F;        // [d, d], d = d_core + has_bias
+};
+
+// One SPD matrix to invert: Minv = (M + damping I)^{-1}
+struct InvertJob {
+    const float *M;  // [n, n], lower triangle read
+    float *Minv;     // [n, n], full symmetric on exit
+    int n;
+    float damping;
+    int *info;       // device int
+};
+
+// C[M, N] = A^T B with A stored [K, lda] (element (k, m)), B stored [K, ldb].
+struct GemmJob {
+    const float *A;
+    const float *B;
+    float *C;
+    int M, N, K;
+    long lda, ldb, ldc;
+    int mode;        // GemmMode
+    int p0, p1;      // kSubLowerSkip: rows/cols in [p0, p1) are left untouched
+};
+
+enum GemmMode : int {
+    kStore = 0,          // C[m][n] = acc
+    kStoreT = 1,         // C[n][m] = acc   (ldc is the pitch of the transposed matrix)
+    kSubLowerSkip = 2    // C[m][n] -= acc for n <= m, m and n outside [p0, p1)
+};
+
+struct Im2colJob {
+    const void *x;   // NCHW
+    void *out;       // [B*Ho*Wo, ld]
+    int dtype;
+    int B, C, H, W, kh, kw, stride, pad, Ho, Wo;
+    int ld;
+};
+
+// ---- planners / launchers (each returns hipSuccess or the launch error) ----
+size_t syrk_workspace_bytes(const FactorJob *jobs, int n);
+hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_bytes, hipStream_t s);
+
+size_t invert_workspace_bytes(const InvertJob *jobs, int n);
+hipError_t invert_launch(const InvertJob *jobs, int n, void *work, size_t work_bytes, hipStream_t s);
+
+hipError_t gemm_launch(const GemmJob *jobs, int n, hipStream_t s);
+
+hipError_t im2col_launch(const Im2colJob *jobs, int n, hipStream_t s);
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// development knobs (set through kfac_tune)
+struct Tuning {
+    long target_blocks = 1024;       // blocks a grouped SYRK launch aims for
+    long min_tiles_per_split = 16;   // K tiles (of 16 rows) per split at least
+    long patch_chunk_bytes = 160l << 20;   // patch bytes materialised per chunk in the batched path
+    long invert_nb = 64;
+    long syrk_force_bm = 0;          // 0 = choose
+};
+Tuning &tuning();
+
+}  // namespace kfac

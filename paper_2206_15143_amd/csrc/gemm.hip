@@ -1,0 +1,187 @@
+// fp32 MFMA GEMM of the form  C = A^T B  (both operands stored K-major), used
+// for the two-sided preconditioning  P = G_inv * grad * A_inv  (Eq. 5 / rhs of
+// Eq. 12 of the DP-KFAC paper) and for the rank-nb update of the blocked
+// inversion.  Symmetric left factors (G_inv) are read as their own transpose,
+// and the first product is written transposed so that the second product is
+// again of the A^T B form: no operand is ever read with a strided K.
+#include "tn_engine.hpp"
+
+#include <algorithm>
+
+namespace kfac {
+
+struct GemmProb {
+    const float *A;
+    const float *B;
+    float *C;
+    long lda, ldb, ldc;
+    int M, N, K;
+    int tm, tn;       // tiles per side
+    int blk_start;
+    int mode;
+    int p0, p1;
+    int vecA, vecB;
+};
+
+struct GemmTable {
+    int count;
+    GemmProb p[kMaxProblems];
+};
+
+template <class T>
+__global__ __launch_bounds__(T::NT) void gemm_tn_kernel(const GemmTable tab)
+{
+    __shared__ float lds[2][2][T::PANEL];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave / T::NW, wn = wave % T::NW;
+
+    int pi = 0;
+    while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].blk_start) ++pi;
+    const GemmProb &pr = tab.p[pi];
+    const int local = blockIdx.x - pr.blk_start;
+    int bi, bj;
+    if (pr.mode == kSubLowerSkip) {
+        tri_decode(local, bi, bj);
+    } else {
+        bi = local / pr.tn;
+        bj = local - bi * pr.tn;
+    }
+    const int m0 = bi * T::BM, n0 = bj * T::BM;
+
+    Operand opA, opB;
+    opA.x = pr.A; opA.K = pr.K; opA.ld = pr.lda; opA.d = pr.M; opA.hw = 1; opA.ctot = 0; opA.vec = pr.vecA;
+    opB.x = pr.B; opB.K = pr.K; opB.ld = pr.ldb; opB.d = pr.N; opB.hw = 1; opB.ctot = 0; opB.vec = pr.vecB;
+
+    floatx4 acc[T::WT][T::WT];
+#pragma unroll
+    for (int i = 0; i < T::WT; ++i)
+#pragma unroll
+        for (int j = 0; j < T::WT; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    const long ktiles = (pr.K + T::KT - 1) / T::KT;
+    floatx4 sa[T::PASSES], sb[T::PASSES];
+    fetch_panel<T, kRows, 0>(sa, opA, 0, m0, tid);
+    fetch_panel<T, kRows, 0>(sb, opB, 0, n0, tid);
+    commit_panel<T, kRows>(sa, lds[0][0], tid);
+    commit_panel<T, kRows>(sb, lds[0][1], tid);
+    __syncthreads();
+    for (long t = 0; t < ktiles; ++t) {
+        const int cur = (int)(t & 1);
+        const bool more = (t + 1 < ktiles);
+        if (more) {
+            fetch_panel<T, kRows, 0>(sa, opA, (t + 1) * T::KT, m0, tid);
+            fetch_panel<T, kRows, 0>(sb, opB, (t + 1) * T::KT, n0, tid);
+        }
+        mma_stage<T, kRows, kRows, false>(lds[cur][0], lds[cur][1], wm, wn, lane, acc);
+        if (more) {
+            commit_panel<T, kRows>(sa, lds[cur ^ 1][0], tid);
+            commit_panel<T, kRows>(sb, lds[cur ^ 1][1], tid);
+        }
+        __syncthreads();
+    }
+
+    const int lr = lane & 15, lk = lane >> 4;
+#pragma unroll
+    for (int ti = 0; ti < T::WT; ++ti)
+#pragma unroll
+        for (int tj = 0; tj < T::WT; ++tj) {
+            const int n = n0 + (wn * T::WT + tj) * 16 + lr;
+            if (n >= pr.N) continue;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int m = m0 + (wm * T::WT + ti) * 16 + 4 * lk + v;
+                if (m >= pr.M) continue;
+                const float val = acc[ti][tj][v];
+                if (pr.mode == kStore) {
+                    pr.C[(long)m * pr.ldc + n] = val;
+                } else if (pr.mode == kStoreT) {
+                    pr.C[(long)n * pr.ldc + m] = val;
+                } else {
+                    const bool skip = (n > m) || (m >= pr.p0 && m < pr.p1) || (n >= pr.p0 && n < pr.p1);
+                    if (!skip) pr.C[(long)m * pr.ldc + n] -= val;
+                }
+            }
+        }
+}
+
+namespace {
+
+const int kBms[] = {128, 144, 64, 32};
+
+int choose_bm(int M, int N, bool square_lower)
+{
+    int best = 0;
+    double best_cost = 1e300;
+    for (int i = 0; i < 4; ++i) {
+        const long bm = kBms[i];
+        const long tm = (M + bm - 1) / bm, tn = (N + bm - 1) / bm;
+        const double tiles = square_lower ? (double)tm * (tm + 1) / 2 : (double)tm * tn;
+        const double penalty = bm >= 128 ? 1.0 : (bm >= 64 ? 1.15 : 1.4);
+        const double cost = tiles * bm * bm * penalty;
+        if (cost < best_cost - 1e-9) { best_cost = cost; best = i; }
+    }
+    return best;
+}
+
+template <class T>
+hipError_t launch_one(const GemmTable &tab, int blocks, hipStream_t s)
+{
+    hipLaunchKernelGGL((gemm_tn_kernel<T>), dim3(blocks), dim3(T::NT), 0, s, tab);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t gemm_launch(const GemmJob *jobs, int n, hipStream_t s)
+{
+    std::vector<int> cfg(n);
+    for (int i = 0; i < n; ++i) cfg[i] = choose_bm(jobs[i].M, jobs[i].N, jobs[i].mode == kSubLowerSkip);
+    for (int c = 0; c < 4; ++c) {
+        GemmTable tab;
+        tab.count = 0;
+        int blocks = 0;
+        auto flush = [&]() -> hipError_t {
+            if (tab.count == 0) return hipSuccess;
+            hipError_t e;
+            switch (c) {
+                case 0: e = launch_one<Tile<4, 2>>(tab, blocks, s); break;
+                case 1: e = launch_one<Tile<3, 3>>(tab, blocks, s); break;
+                case 2: e = launch_one<Tile<2, 2>>(tab, blocks, s); break;
+                default: e = launch_one<Tile<1, 2>>(tab, blocks, s); break;
+            }
+            tab.count = 0;
+            blocks = 0;
+            return e;
+        };
+        for (int i = 0; i < n; ++i) {
+            if (cfg[i] != c) continue;
+            const GemmJob &j = jobs[i];
+            if (j.M <= 0 || j.N <= 0 || j.K <= 0) continue;
+            GemmProb &p = tab.p[tab.count++];
+            const int bm = kBms[c];
+            p.A = j.A; p.B = j.B; p.C = j.C;
+            p.lda = j.lda; p.ldb = j.ldb; p.ldc = j.ldc;
+            p.M = j.M; p.N = j.N; p.K = j.K;
+            p.tm = (j.M + bm - 1) / bm;
+            p.tn = (j.N + bm - 1) / bm;
+            p.blk_start = blocks;
+            p.mode = j.mode;
+            p.p0 = j.p0; p.p1 = j.p1;
+            p.vecA = (((uintptr_t)j.A) % 16 == 0 && j.lda % 4 == 0) ? 1 : 0;
+            p.vecB = (((uintptr_t)j.B) % 16 == 0 && j.ldb % 4 == 0) ? 1 : 0;
+            blocks += (j.mode == kSubLowerSkip) ? p.tm * (p.tm + 1) / 2 : p.tm * p.tn;
+            if (tab.count == kMaxProblems) {
+                hipError_t e = flush();
+                if (e != hipSuccess) return e;
+            }
+        }
+        hipError_t e = flush();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace kfac

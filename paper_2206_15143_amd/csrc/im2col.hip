@@ -1,0 +1,202 @@
+// Patch extraction for convolution layers (the "convolution as a linear
+// transformation" of the footnote in section 3 of the DP-KFAC paper):
+//
+//   out[(n, oh, ow)][(c, i, j)] = x[n, c, oh*stride - pad + i, ow*stride - pad + j]   (0 outside)
+//
+// NCHW in, row-major [B*Ho*Wo, ld] out, same element type.  The bias column is
+// not written (the factor kernel derives its border from column sums), so rows
+// stay 16-byte aligned and every store is a full 16-byte vector.
+//
+// One workgroup handles (image n, strip of SR output rows, chunk of CC input
+// channels): the input slab it needs (with the zero halo) is staged once in
+// LDS with coalesced reads, together with a small table of slab offsets per
+// output column; then consecutive threads write consecutive 16-byte column
+// groups of consecutive output rows.
+#include "common.hpp"
+
+#include <algorithm>
+
+namespace kfac {
+
+struct Im2colProb {
+    const void *x;
+    void *out;
+    int B, C, H, W, kh, kw, stride, pad, Ho, Wo;
+    int ld;
+    int SR, CC;         // output rows per strip, channels per chunk
+    int nstrips, nchunks;
+    int IR, WP;         // slab rows / row pitch
+    int blk_start;
+};
+
+struct Im2colTable {
+    int count;
+    Im2colProb p[kMaxProblems];
+};
+
+template <typename E> struct VecOf;
+template <> struct VecOf<float> { typedef floatx4 type; static constexpr int N = 4; };
+template <> struct VecOf<unsigned short> { typedef uint4 type; static constexpr int N = 8; };
+
+template <typename E>
+__global__ __launch_bounds__(256) void im2col_kernel(const Im2colTable tab)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int VEC = VecOf<E>::N;
+
+    int pi = 0;
+    while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].blk_start) ++pi;
+    const Im2colProb &pr = tab.p[pi];
+    int local = blockIdx.x - pr.blk_start;
+    const int chunk = local % pr.nchunks; local /= pr.nchunks;
+    const int strip = local % pr.nstrips;
+    const int n = local / pr.nstrips;
+
+    const int kk = pr.kh * pr.kw;
+    const int c0 = chunk * pr.CC;
+    const int cc = min(pr.CC, pr.C - c0);
+    const int oh0 = strip * pr.SR;
+    const int sr = min(pr.SR, pr.Ho - oh0);
+    const int plane = pr.IR * pr.WP;
+    const int slab_elems = pr.CC * plane;       // + 1 zero cell
+    const int col0 = c0 * kk;                    // first output column of this chunk
+    const bool last = (chunk == pr.nchunks - 1);
+    const int ncols_valid = cc * kk;
+    const int ncols_out = last ? (pr.ld - col0) : ncols_valid;   // the last chunk also writes the pad columns
+    const int ncg = ncols_out / VEC;
+
+    E *slab = reinterpret_cast<E *>(smem);
+    int *offs = reinterpret_cast<int *>(smem + ((size_t)(slab_elems + 1) * sizeof(E) + 15) / 16 * 16);
+
+    // ---- stage the input slab (zero halo) ----
+    const E *xin = reinterpret_cast<const E *>(pr.x) + ((long)n * pr.C + c0) * pr.H * pr.W;
+    const int ir_used = (sr - 1) * pr.stride + pr.kh;
+    for (int idx = threadIdx.x; idx < cc * ir_used * pr.WP; idx += 256) {
+        const int c = idx / (ir_used * pr.WP);
+        const int rem = idx - c * (ir_used * pr.WP);
+        const int r = rem / pr.WP;
+        const int xx = rem - r * pr.WP;
+        const int ih = oh0 * pr.stride - pr.pad + r;
+        const int iw = xx - pr.pad;
+        E v = 0;
+        if (ih >= 0 && ih < pr.H && iw >= 0 && iw < pr.W) v = xin[((long)c * pr.H + ih) * pr.W + iw];
+        slab[c * plane + r * pr.WP + xx] = v;
+    }
+    if (threadIdx.x == 0) slab[slab_elems] = 0;
+    for (int col = threadIdx.x; col < ncg * VEC; col += 256) {
+        int off = slab_elems;                    // pad column -> the zero cell
+        if (col < ncols_valid) {
+            const int c = col / kk;
+            const int rem = col - c * kk;
+            const int i = rem / pr.kw;
+            const int j = rem - i * pr.kw;
+            off = c * plane + i * pr.WP + j;
+        }
+        offs[col] = off;
+    }
+    __syncthreads();
+
+    // ---- write the rows ----
+    E *out = reinterpret_cast<E *>(pr.out);
+    const long row0 = ((long)n * pr.Ho + oh0) * pr.Wo;
+    const int total = sr * pr.Wo * ncg;
+    for (int idx = threadIdx.x; idx < total; idx += 256) {
+        const int rowl = idx / ncg;
+        const int cg = idx - rowl * ncg;
+        const int ohl = rowl / pr.Wo;
+        const int ow = rowl - ohl * pr.Wo;
+        const int base = ohl * pr.stride * pr.WP + ow * pr.stride;
+        E vals[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const int o = offs[cg * VEC + e];
+            vals[e] = slab[o == slab_elems ? o : o + base];
+        }
+        typename VecOf<E>::type v;
+        __builtin_memcpy(&v, vals, sizeof(v));
+        *reinterpret_cast<typename VecOf<E>::type *>(out + (row0 + rowl) * pr.ld + col0 + cg * VEC) = v;
+    }
+}
+
+namespace {
+
+int gcd(int a, int b) { return b ? gcd(b, a % b) : a; }
+
+size_t smem_bytes(const Im2colProb &p, int esz)
+{
+    const size_t slab = ((size_t)(p.CC * p.IR * p.WP + 1) * esz + 15) / 16 * 16;
+    return slab + (size_t)(p.CC * p.kh * p.kw + 16) * sizeof(int);
+}
+
+void plan(Im2colProb &p, int esz)
+{
+    const int vec = 16 / esz;
+    const int kk = p.kh * p.kw;
+    const int g = vec / gcd(kk, vec);             // CC must be a multiple of g (or the whole of C)
+    p.WP = (p.Wo - 1) * p.stride + p.kw;
+    int SR = std::max(1, std::min(p.Ho, (64 + p.Wo - 1) / p.Wo));
+    const size_t budget = 48 * 1024;
+    for (;;) {
+        p.SR = SR;
+        p.IR = (SR - 1) * p.stride + p.kh;
+        // largest channel chunk that fits
+        const size_t per_c = (size_t)p.IR * p.WP * esz + (size_t)kk * sizeof(int);
+        long cc = (long)((budget - 256) / per_c);
+        if (cc >= p.C) {
+            p.CC = p.C;
+        } else {
+            cc = cc / g * g;
+            p.CC = (int)cc;
+        }
+        if (p.CC >= 1 && (p.CC == p.C || p.CC % g == 0)) break;
+        if (SR == 1) { p.CC = std::min(p.C, g); break; }   // tiny chunk: still correct
+        SR = std::max(1, SR / 2);
+    }
+    p.nstrips = (p.Ho + p.SR - 1) / p.SR;
+    p.nchunks = (p.C + p.CC - 1) / p.CC;
+}
+
+}  // namespace
+
+hipError_t im2col_launch(const Im2colJob *jobs, int n, hipStream_t s)
+{
+    for (int dt = 0; dt < 2; ++dt) {
+        Im2colTable tab;
+        tab.count = 0;
+        int blocks = 0;
+        size_t smem = 0;
+        auto flush = [&]() -> hipError_t {
+            if (tab.count == 0) return hipSuccess;
+            if (smem > 64 * 1024) return hipErrorInvalidValue;   // slab of one output row does not fit LDS
+            if (dt == 0)
+                hipLaunchKernelGGL((im2col_kernel<float>), dim3(blocks), dim3(256), smem, s, tab);
+            else
+                hipLaunchKernelGGL((im2col_kernel<unsigned short>), dim3(blocks), dim3(256), smem, s, tab);
+            tab.count = 0;
+            blocks = 0;
+            smem = 0;
+            return hipGetLastError();
+        };
+        for (int i = 0; i < n; ++i) {
+            if (jobs[i].dtype != dt) continue;
+            const Im2colJob &j = jobs[i];
+            Im2colProb &p = tab.p[tab.count++];
+            p.x = j.x; p.out = j.out;
+            p.B = j.B; p.C = j.C; p.H = j.H; p.W = j.W; p.kh = j.kh; p.kw = j.kw;
+            p.stride = j.stride; p.pad = j.pad; p.Ho = j.Ho; p.Wo = j.Wo; p.ld = j.ld;
+            plan(p, dt == 0 ? 4 : 2);
+            p.blk_start = blocks;
+            blocks += p.B * p.nstrips * p.nchunks;
+            smem = std::max(smem, smem_bytes(p, dt == 0 ? 4 : 2));
+            if (tab.count == kMaxProblems) {
+                hipError_t e = flush();
+                if (e != hipSuccess) return e;
+            }
+        }
+        hipError_t e = flush();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace kfac

@@ -1,0 +1,307 @@
+// Damped inverse of the Kronecker factors, (M + damping I)^{-1} (section 5.2 of
+// the DP-KFAC paper, matrix-inversion variant).
+//
+// Method: blocked symmetric Gauss-Jordan ("sweep") on the lower triangle,
+// batched over matrices.  Sweeping the pivot block K of a symmetric matrix does
+//     P      = M_KK^{-1}
+//     M_iK  <- M_iK P                      (i != K)
+//     M_ij  <- M_ij - M_iK P M_Kj          (i, j != K)
+//     M_KK  <- -P
+// and after all blocks have been swept the matrix holds -M^{-1}.  The pivots met
+// on the way are the pivots of the Cholesky / LDL^T factorisation (the
+// technique section 5.2 names), so "pivot k not positive" is the same
+// positive-definiteness test; unlike potrf + trtri + lauum there is a single
+// pass of n/nb steps, every step is one rank-nb MFMA update of the whole
+// triangle (n^3 flops in total) and the result appears in place.
+//
+// Per step: sweep_pivot_kernel (one workgroup per matrix inverts the nb x nb
+// pivot block in LDS), sweep_panel_kernel (V = old panel, W = V P, both stored
+// K-major for the MFMA update; new panel written in place), then the rank-nb
+// update through the A^T B GEMM (gemm.hip, mode kSubLowerSkip).
+#include "common.hpp"
+
+#include <algorithm>
+
+namespace kfac {
+
+constexpr int NB = 64;   // pivot block order
+
+__device__ __forceinline__ long lmin(long a, long b) { return a < b ? a : b; }
+
+struct InvProb {
+    const float *M;
+    float *W;        // working matrix = output buffer [n, n]
+    float *P;        // [NB, NB] pivot-block inverse
+    float *Vt;       // [NB, ldv]
+    float *Wt;       // [NB, ldv]
+    int *info;
+    int n;
+    int ldv;         // n rounded up to 4 (16-byte aligned rows)
+    float damping;
+    int blk_start;
+};
+
+struct InvTable {
+    int count;
+    int step;
+    InvProb p[kMaxProblems];
+};
+
+// W(lower) = M(lower) + damping I
+__global__ __launch_bounds__(256) void sweep_init_kernel(const InvTable tab)
+{
+    int pi = 0;
+    while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].blk_start) ++pi;
+    const InvProb &pr = tab.p[pi];
+    const int local = blockIdx.x - pr.blk_start;
+    const long total = (long)pr.n * pr.n;
+    if (local == 0 && threadIdx.x == 0) *pr.info = 0;
+    for (long e = (long)local * 4096 + threadIdx.x; e < lmin(total, (long)(local + 1) * 4096); e += 256) {
+        const int i = (int)(e / pr.n), j = (int)(e - (long)i * pr.n);
+        if (j <= i) pr.W[e] = pr.M[e] + (i == j ? pr.damping : 0.f);
+    }
+}
+
+// Inverts the pivot block of step `tab.step` by an unblocked sweep in LDS.
+__global__ __launch_bounds__(256) void sweep_pivot_kernel(const InvTable tab)
+{
+    __shared__ float S[NB][NB + 1];
+    const InvProb &pr = tab.p[blockIdx.x];
+    const int p0 = tab.step * NB;
+    if (p0 >= pr.n) return;
+    const int bs = min(NB, pr.n - p0);
+    const int tid = threadIdx.x;
+
+    for (int e = tid; e < NB * NB; e += 256) {
+        const int i = e / NB, j = e % NB;
+        float v = (i == j) ? 1.f : 0.f;      // identity padding keeps the tail block well defined
+        if (i < bs && j < bs) {
+            v = (j <= i) ? pr.W[(long)(p0 + i) * pr.n + p0 + j] : pr.W[(long)(p0 + j) * pr.n + p0 + i];
+        }
+        S[i][j] = v;
+    }
+    const int i = tid >> 2, jq = tid & 3;
+    int fail = 0;
+    for (int k = 0; k < bs; ++k) {
+        __syncthreads();
+        const float p = S[k][k];
+        if (!(p > 0.f) && fail == 0) fail = p0 + k + 1;
+        const float ip = 1.0f / p;
+        const float ci = S[i][k];
+        float rk[NB / 4];
+#pragma unroll
+        for (int m = 0; m < NB / 4; ++m) rk[m] = S[k][jq + 4 * m];
+        __syncthreads();
+#pragma unroll
+        for (int m = 0; m < NB / 4; ++m) {
+            const int j = jq + 4 * m;
+            float v;
+            if (i == k)
+                v = (j == k) ? -ip : rk[m] * ip;
+            else if (j == k)
+                v = ci * ip;
+            else
+                v = S[i][j] - (ci * rk[m]) * ip;
+            S[i][j] = v;
+        }
+    }
+    __syncthreads();
+    for (int e = tid; e < NB * NB; e += 256) {
+        const int r = e / NB, c = e % NB;
+        const bool in = (r < bs && c < bs);
+        pr.P[e] = in ? -S[r][c] : 0.f;
+        if (in && c <= r) pr.W[(long)(p0 + r) * pr.n + p0 + c] = S[r][c];
+    }
+    if (fail != 0 && tid == 0 && *pr.info == 0) *pr.info = fail;
+}
+
+// One workgroup per 64 rows of the panel of step `tab.step`.
+__global__ __launch_bounds__(256) void sweep_panel_kernel(const InvTable tab)
+{
+    __shared__ float Ps[NB][NB + 1];
+    __shared__ float Vs[NB][NB + 1];   // [kk][i]
+    int pi = 0;
+    while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].blk_start) ++pi;
+    const InvProb &pr = tab.p[pi];
+    const int chunk = blockIdx.x - pr.blk_start;
+    const int p0 = tab.step * NB;
+    if (p0 >= pr.n) return;
+    const int bs = min(NB, pr.n - p0);
+    const int i0 = chunk * NB;
+    const int tid = threadIdx.x;
+    const int n = pr.n;
+
+    if (i0 == p0) {   // the pivot rows themselves: zero columns in V and W
+        for (int e = tid; e < NB * NB; e += 256) {
+            const int kk = e / NB, i = e % NB;
+            if (i0 + i < n) {
+                pr.Vt[(long)kk * pr.ldv + i0 + i] = 0.f;
+                pr.Wt[(long)kk * pr.ldv + i0 + i] = 0.f;
+            }
+        }
+        return;
+    }
+    for (int e = tid; e < NB * NB; e += 256) Ps[e / NB][e % NB] = pr.P[e];
+    if (i0 > p0) {    // column panel: M[gi][p0 + kk], contiguous in kk
+        for (int e = tid; e < NB * NB; e += 256) {
+            const int i = e / NB, kk = e % NB;
+            const int gi = i0 + i;
+            Vs[kk][i] = (gi < n && kk < bs) ? pr.W[(long)gi * n + p0 + kk] : 0.f;
+        }
+    } else {          // row panel: M[p0 + kk][gi], contiguous in gi
+        for (int e = tid; e < NB * NB; e += 256) {
+            const int kk = e / NB, i = e % NB;
+            const int gi = i0 + i;
+            Vs[kk][i] = (gi < n && kk < bs) ? pr.W[(long)(p0 + kk) * n + gi] : 0.f;
+        }
+    }
+    __syncthreads();
+    const int i = tid & 63, kq = tid >> 6;
+    const int gi = i0 + i;
+    float acc[16];
+#pragma unroll
+    for (int t = 0; t < 16; ++t) acc[t] = 0.f;
+    for (int m = 0; m < NB; ++m) {
+        const float vm = Vs[m][i];
+#pragma unroll
+        for (int t = 0; t < 16; ++t) acc[t] += Ps[kq * 16 + t][m] * vm;
+    }
+    if (gi < n) {
+#pragma unroll
+        for (int t = 0; t < 16; ++t) {
+            const int kk = kq * 16 + t;
+            pr.Vt[(long)kk * pr.ldv + gi] = Vs[kk][i];
+            pr.Wt[(long)kk * pr.ldv + gi] = acc[t];
+            if (kk < bs) {
+                if (i0 > p0)
+                    pr.W[(long)gi * n + p0 + kk] = acc[t];
+                else
+                    pr.W[(long)(p0 + kk) * n + gi] = acc[t];
+            }
+        }
+    }
+}
+
+// out = -W mirrored to both triangles (in place)
+__global__ __launch_bounds__(256) void sweep_finish_kernel(const InvTable tab)
+{
+    int pi = 0;
+    while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].blk_start) ++pi;
+    const InvProb &pr = tab.p[pi];
+    const int local = blockIdx.x - pr.blk_start;
+    const long total = (long)pr.n * pr.n;
+    for (long e = (long)local * 4096 + threadIdx.x; e < lmin(total, (long)(local + 1) * 4096); e += 256) {
+        const int i = (int)(e / pr.n), j = (int)(e - (long)i * pr.n);
+        if (j <= i) {
+            const float v = -pr.W[e];
+            pr.W[e] = v;
+            pr.W[(long)j * pr.n + i] = v;
+        }
+    }
+}
+
+namespace {
+size_t job_ws_floats(int n) { return (size_t)NB * NB + 2 * (size_t)NB * ((n + 3) / 4 * 4); }
+}  // namespace
+
+size_t invert_workspace_bytes(const InvertJob *jobs, int n)
+{
+    size_t total = 0;
+    for (int i = 0; i < n; ++i) total += align_up(job_ws_floats(jobs[i].n) * sizeof(float), 256);
+    return total;
+}
+
+hipError_t invert_launch(const InvertJob *jobs, int n, void *work, size_t work_bytes, hipStream_t s)
+{
+    if (invert_workspace_bytes(jobs, n) > work_bytes) return hipErrorInvalidValue;
+    // largest matrices first so that one launch group holds similar step counts
+    std::vector<int> order(n);
+    for (int i = 0; i < n; ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return jobs[a].n > jobs[b].n; });
+    std::vector<size_t> offs(n);
+    size_t off = 0;
+    for (int i = 0; i < n; ++i) {
+        offs[i] = off;
+        off += align_up(job_ws_floats(jobs[i].n) * sizeof(float), 256);
+    }
+
+    for (int g0 = 0; g0 < n; g0 += kMaxProblems) {
+        const int cnt = std::min(kMaxProblems, n - g0);
+        InvTable tab;
+        tab.count = cnt;
+        tab.step = 0;
+        int nmax = 0;
+        for (int k = 0; k < cnt; ++k) {
+            const InvertJob &j = jobs[order[g0 + k]];
+            InvProb &p = tab.p[k];
+            float *ws = reinterpret_cast<float *>(static_cast<char *>(work) + offs[order[g0 + k]]);
+            p.M = j.M; p.W = j.Minv; p.info = j.info; p.n = j.n; p.damping = j.damping;
+            p.ldv = (j.n + 3) / 4 * 4;
+            p.P = ws;
+            p.Vt = ws + NB * NB;
+            p.Wt = p.Vt + (size_t)NB * p.ldv;
+            nmax = std::max(nmax, j.n);
+        }
+        // element-wise kernels: 4096 elements per block
+        int blocks = 0;
+        for (int k = 0; k < cnt; ++k) {
+            tab.p[k].blk_start = blocks;
+            blocks += (int)(((long)tab.p[k].n * tab.p[k].n + 4095) / 4096);
+        }
+        const int ew_blocks = blocks;
+        hipLaunchKernelGGL(sweep_init_kernel, dim3(ew_blocks), dim3(256), 0, s, tab);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+
+        const int steps = (nmax + NB - 1) / NB;
+        for (int st = 0; st < steps; ++st) {
+            tab.step = st;
+            const int p0 = st * NB;
+            // matrices are sorted by size: those still active form a prefix
+            int active = 0;
+            while (active < cnt && tab.p[active].n > p0) ++active;
+            InvTable t2 = tab;
+            t2.count = active;
+            hipLaunchKernelGGL(sweep_pivot_kernel, dim3(active), dim3(256), 0, s, t2);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            // panel + update only where something lies outside the pivot block
+            int act2 = 0;
+            while (act2 < active && tab.p[act2].n > NB) ++act2;
+            if (act2 == 0) continue;
+            t2.count = act2;
+            blocks = 0;
+            for (int k = 0; k < act2; ++k) {
+                t2.p[k].blk_start = blocks;
+                blocks += (t2.p[k].n + NB - 1) / NB;
+            }
+            hipLaunchKernelGGL(sweep_panel_kernel, dim3(blocks), dim3(256), 0, s, t2);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            std::vector<GemmJob> gj(act2);
+            for (int k = 0; k < act2; ++k) {
+                const InvProb &p = t2.p[k];
+                GemmJob &g = gj[k];
+                g.A = p.Wt; g.B = p.Vt; g.C = p.W;
+                g.M = p.n; g.N = p.n; g.K = NB;
+                g.lda = p.ldv; g.ldb = p.ldv; g.ldc = p.n;
+                g.mode = kSubLowerSkip;
+                g.p0 = p0;
+                g.p1 = std::min(p.n, p0 + NB);
+            }
+            e = gemm_launch(gj.data(), act2, s);
+            if (e != hipSuccess) return e;
+        }
+        blocks = 0;
+        for (int k = 0; k < cnt; ++k) {
+            tab.p[k].blk_start = blocks;
+            blocks += (int)(((long)tab.p[k].n * tab.p[k].n + 4095) / 4096);
+        }
+        hipLaunchKernelGGL(sweep_finish_kernel, dim3(blocks), dim3(256), 0, s, tab);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace kfac

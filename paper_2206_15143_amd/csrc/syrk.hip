@@ -1,0 +1,409 @@
+// Kronecker-factor construction (Eq. 4 of the DP-KFAC paper) with the running
+// average of Eqs. 10-11 fused into the reduction epilogue:
+//
+//     F <- decay * F + (1 - decay) * scale * X^T X          (lower triangle, mirrored)
+//
+// and, for layers with a bias, the border of the homogeneous column
+// (F[d][c] = column sums of X, F[d][d] = number of rows) computed on the side
+// from the values the loader already holds, so the ones column is never
+// materialised and the MFMA tiles stay multiples of 16.
+//
+// Two kernels:
+//   syrk_partial_kernel : lower-triangular BM x BM block tiles x split-K slices,
+//                         fp32 MFMA, partial tiles to the workspace.
+//   syrk_reduce_kernel  : sums the slices in a fixed order (deterministic),
+//                         applies scale and the running average, writes both
+//                         triangles.
+#include "tn_engine.hpp"
+
+#include <algorithm>
+#include <cmath>
+
+namespace kfac {
+
+struct SyrkProb {
+    const void *x;
+    float *partial;   // [splits][nblk][BM*BM] tiles, then [splits][nb][BM] column sums
+    float *F;
+    long K;
+    long ld;
+    int d;            // core columns
+    int hw, ctot;
+    int nb;           // block tiles per side
+    int splits;
+    int tiles_per_split;
+    int blk_start;    // first flattened block of this problem (partial kernel)
+    int red_start;    // first flattened block of this problem (reduce kernel)
+    int vec;
+    int has_bias;
+    float scale, decay;
+};
+
+struct SyrkTable {
+    int count;
+    SyrkProb p[kMaxProblems];
+};
+
+template <class T, int LAYOUT, int DT>
+__global__ __launch_bounds__(T::NT) void syrk_partial_kernel(const SyrkTable tab)
+{
+    __shared__ float lds[2][2][T::PANEL];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave / T::NW, wn = wave % T::NW;
+
+    int pi = 0;
+    while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].blk_start) ++pi;
+    const SyrkProb &pr = tab.p[pi];
+    const int local = blockIdx.x - pr.blk_start;
+    const int nblk = pr.nb * (pr.nb + 1) / 2;
+    const int split = local / nblk;
+    const int blk = local - split * nblk;
+    int bi, bj;
+    tri_decode(blk, bi, bj);
+    const bool diag = (bi == bj);
+    const bool do_colsum = pr.has_bias && bj == 0;
+
+    Operand op;
+    op.x = pr.x; op.K = pr.K; op.ld = pr.ld; op.d = pr.d; op.hw = pr.hw; op.ctot = pr.ctot; op.vec = pr.vec;
+
+    const long ktiles = (pr.K + T::KT - 1) / T::KT;
+    const long t0 = (long)split * pr.tiles_per_split;
+    const long t1 = (t0 + pr.tiles_per_split < ktiles) ? t0 + pr.tiles_per_split : ktiles;
+
+    floatx4 acc[T::WT][T::WT];
+#pragma unroll
+    for (int i = 0; i < T::WT; ++i)
+#pragma unroll
+        for (int j = 0; j < T::WT; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    floatx4 cs[T::PASSES];
+#pragma unroll
+    for (int p = 0; p < T::PASSES; ++p) cs[p] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    const int u0 = bi * T::BM, v0 = bj * T::BM;
+    const bool active = !diag || wn <= wm;
+    const bool tri = diag && wn == wm;
+
+    floatx4 su[T::PASSES], sv[T::PASSES];
+    if (t0 < t1) {
+        fetch_panel<T, LAYOUT, DT>(su, op, t0 * T::KT, u0, tid);
+        if (!diag) fetch_panel<T, LAYOUT, DT>(sv, op, t0 * T::KT, v0, tid);
+        if (do_colsum) {
+#pragma unroll
+            for (int p = 0; p < T::PASSES; ++p) cs[p] += su[p];
+        }
+        commit_panel<T, LAYOUT>(su, lds[0][0], tid);
+        if (!diag) commit_panel<T, LAYOUT>(sv, lds[0][1], tid);
+    }
+    __syncthreads();
+
+    for (long t = t0; t < t1; ++t) {
+        const int cur = (int)((t - t0) & 1);
+        const bool more = (t + 1 < t1);
+        if (more) {
+            fetch_panel<T, LAYOUT, DT>(su, op, (t + 1) * T::KT, u0, tid);
+            if (!diag) fetch_panel<T, LAYOUT, DT>(sv, op, (t + 1) * T::KT, v0, tid);
+        }
+        if (active) {
+            const float *Us = lds[cur][0];
+            const float *Vs = diag ? lds[cur][0] : lds[cur][1];
+            if (tri)
+                mma_stage<T, LAYOUT, LAYOUT, true>(Us, Vs, wm, wn, lane, acc);
+            else
+                mma_stage<T, LAYOUT, LAYOUT, false>(Us, Vs, wm, wn, lane, acc);
+        }
+        if (more) {
+            if (do_colsum) {
+#pragma unroll
+                for (int p = 0; p < T::PASSES; ++p) cs[p] += su[p];
+            }
+            commit_panel<T, LAYOUT>(su, lds[cur ^ 1][0], tid);
+            if (!diag) commit_panel<T, LAYOUT>(sv, lds[cur ^ 1][1], tid);
+        }
+        __syncthreads();
+    }
+
+    // ---- partial tile out ----
+    if (active) {
+        float *dst = pr.partial + ((long)split * nblk + blk) * (T::BM * T::BM);
+        const int lr = lane & 15, lk = lane >> 4;
+#pragma unroll
+        for (int ti = 0; ti < T::WT; ++ti)
+#pragma unroll
+            for (int tj = 0; tj < T::WT; ++tj) {
+                if (tri && tj > ti) continue;
+                const int row = (wm * T::WT + ti) * 16 + 4 * lk;
+                const int col = (wn * T::WT + tj) * 16 + lr;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) dst[(row + v) * T::BM + col] = acc[ti][tj][v];
+            }
+    }
+
+    // ---- column sums of the U panel (bias border) ----
+    if (do_colsum) {
+        float *red = &lds[0][0][0];   // all waves are past the last barrier of the K loop
+        constexpr int SLOTS = (LAYOUT == kRows) ? T::NT / (T::BM / 4) : T::KT / 4;
+#pragma unroll
+        for (int p = 0; p < T::PASSES; ++p) {
+            const int idx = tid + p * T::NT;
+            if (LAYOUT == kRows) {
+                // every pass of a thread hits the same column group
+                if (p > 0) cs[0] += cs[p];
+            } else if (idx < T::V4) {
+                const int c = idx / (T::KT / 4), kq = idx % (T::KT / 4);
+                red[kq * T::BM + c] = cs[p].x + cs[p].y + cs[p].z + cs[p].w;
+            }
+        }
+        if (LAYOUT == kRows) {
+            const int slot = tid / (T::BM / 4);
+            const int c = (tid % (T::BM / 4)) * 4;
+            red[slot * T::BM + c + 0] = cs[0].x;
+            red[slot * T::BM + c + 1] = cs[0].y;
+            red[slot * T::BM + c + 2] = cs[0].z;
+            red[slot * T::BM + c + 3] = cs[0].w;
+        }
+        __syncthreads();
+        if (tid < T::BM) {
+            float s = 0.f;
+#pragma unroll
+            for (int k = 0; k < SLOTS; ++k) s += red[k * T::BM + tid];
+            float *csum = pr.partial + (long)pr.splits * nblk * (T::BM * T::BM);
+            csum[((long)split * pr.nb + bi) * T::BM + tid] = s;
+        }
+    }
+}
+
+// One block per BM x BM tile of the lower triangle (plus, with a bias, one
+// block per block row for the border).  Fixed summation order over the splits.
+template <class T>
+__global__ __launch_bounds__(256) void syrk_reduce_kernel(const SyrkTable tab)
+{
+    int pi = 0;
+    while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].red_start) ++pi;
+    const SyrkProb &pr = tab.p[pi];
+    const int local = blockIdx.x - pr.red_start;
+    const int nblk = pr.nb * (pr.nb + 1) / 2;
+    const int dF = pr.d + pr.has_bias;
+    const float wnew = (1.0f - pr.decay) * pr.scale;
+    constexpr int TILE = T::BM * T::BM;
+
+    if (local < nblk) {
+        int bi, bj;
+        tri_decode(local, bi, bj);
+        const float *src = pr.partial + (long)local * TILE;
+        const long sstride = (long)nblk * TILE;
+        for (int e = threadIdx.x; e < TILE; e += 256) {
+            const int r = e / T::BM, c = e - r * T::BM;
+            const int u = bi * T::BM + r, v = bj * T::BM + c;
+            if (u >= pr.d || v > u) continue;
+            float s = 0.f;
+            for (int k = 0; k < pr.splits; ++k) s += src[k * sstride + e];
+            const float out = pr.decay * pr.F[(long)u * dF + v] + wnew * s;
+            pr.F[(long)u * dF + v] = out;
+            pr.F[(long)v * dF + u] = out;
+        }
+    } else {
+        const int bi = local - nblk;
+        const float *csum = pr.partial + (long)pr.splits * nblk * TILE;
+        for (int r = threadIdx.x; r < T::BM; r += 256) {
+            const int u = bi * T::BM + r;
+            if (u >= pr.d) continue;
+            float s = 0.f;
+            for (int k = 0; k < pr.splits; ++k) s += csum[((long)k * pr.nb + bi) * T::BM + r];
+            const float out = pr.decay * pr.F[(long)pr.d * dF + u] + wnew * s;
+            pr.F[(long)pr.d * dF + u] = out;
+            pr.F[(long)u * dF + pr.d] = out;
+        }
+        if (bi == 0 && threadIdx.x == 0) {
+            const long dd = (long)pr.d * dF + pr.d;
+            pr.F[dd] = pr.decay * pr.F[dd] + wnew * (float)pr.K;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+namespace {
+
+struct Cfg { int wt, nw, bm; };
+const Cfg kCfgs[] = {{4, 2, 128}, {3, 3, 144}, {2, 2, 64}, {1, 2, 32}};
+
+// padded MFMA work (in 16x16 tiles) of the lower triangle for a config
+long tri_tiles(int d, const Cfg &c)
+{
+    const long nb = (d + c.bm - 1) / c.bm;
+    const long nw = nb * c.nw;
+    return nw * (nw - 1) / 2 * c.wt * c.wt + nw * (c.wt * (c.wt + 1) / 2);
+}
+
+int choose_cfg(int d)
+{
+    const long force = tuning().syrk_force_bm;
+    int best = 0;
+    double best_cost = 1e300;
+    for (int i = 0; i < 4; ++i) {
+        if (force && kCfgs[i].bm != force) continue;
+        // small tiles re-read the panels more often: mild penalty
+        const double penalty = kCfgs[i].bm >= 128 ? 1.0 : (kCfgs[i].bm >= 64 ? 1.1 : 1.25);
+        const double cost = (double)tri_tiles(d, kCfgs[i]) * penalty;
+        if (cost < best_cost - 1e-9) { best_cost = cost; best = i; }
+    }
+    return best;
+}
+
+struct Planned {
+    int cfg;
+    int nb, nblk, splits, tps;
+    size_t partial_floats;
+};
+
+// jobs of one launch group share (cfg, layout, dtype)
+void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<Planned> &pl)
+{
+    const Tuning &tu = tuning();
+    double work = 0;
+    for (int j : idx) {
+        Planned &p = pl[j];
+        const Cfg &c = kCfgs[p.cfg];
+        p.nb = (jobs[j].d_core + c.bm - 1) / c.bm;
+        p.nblk = p.nb * (p.nb + 1) / 2;
+        const long ktiles = (jobs[j].K + 15) / 16;
+        work += (double)p.nblk * (double)ktiles;
+    }
+    long tpb = (long)std::ceil(work / (double)tu.target_blocks);
+    tpb = std::max<long>(tpb, tu.min_tiles_per_split);
+    for (int j : idx) {
+        Planned &p = pl[j];
+        const Cfg &c = kCfgs[p.cfg];
+        const long ktiles = std::max<long>(1, (jobs[j].K + 15) / 16);
+        p.splits = (int)((ktiles + tpb - 1) / tpb);
+        p.tps = (int)((ktiles + p.splits - 1) / p.splits);
+        p.splits = (int)((ktiles + p.tps - 1) / p.tps);
+        p.partial_floats = (size_t)p.splits * ((size_t)p.nblk * c.bm * c.bm + (size_t)p.nb * c.bm);
+    }
+}
+
+int group_key(const FactorJob &j, int cfg) { return cfg * 4 + j.layout * 2 + j.dtype; }
+
+void plan_all(const FactorJob *jobs, int n, std::vector<Planned> &pl, std::vector<std::vector<int>> &groups)
+{
+    pl.assign(n, Planned());
+    std::vector<int> keys(n);
+    for (int i = 0; i < n; ++i) {
+        pl[i].cfg = choose_cfg(jobs[i].d_core);
+        keys[i] = group_key(jobs[i], pl[i].cfg);
+    }
+    groups.clear();
+    for (int key = 0; key < 16; ++key) {
+        std::vector<int> cur;
+        for (int i = 0; i < n; ++i) {
+            if (keys[i] != key) continue;
+            cur.push_back(i);
+            if ((int)cur.size() == kMaxProblems) { groups.push_back(cur); cur.clear(); }
+        }
+        if (!cur.empty()) groups.push_back(cur);
+    }
+    for (auto &g : groups) plan_group(jobs, g, pl);
+}
+
+bool vec_ok(const FactorJob &j)
+{
+    const size_t eb = j.dtype == 0 ? 4 : 2;
+    if (((uintptr_t)j.x) % (4 * eb) != 0) return false;
+    if (j.layout == kRows) return j.ld % 4 == 0;
+    return j.hw % 4 == 0;
+}
+
+template <class T, int LAYOUT, int DT>
+hipError_t launch_cfg(const SyrkTable &tab, int blocks, int red_blocks, hipStream_t s)
+{
+    hipLaunchKernelGGL((syrk_partial_kernel<T, LAYOUT, DT>), dim3(blocks), dim3(T::NT), 0, s, tab);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((syrk_reduce_kernel<T>), dim3(red_blocks), dim3(256), 0, s, tab);
+    return hipGetLastError();
+}
+
+template <class T>
+hipError_t launch_ld(const SyrkTable &tab, int layout, int dt, int blocks, int red_blocks, hipStream_t s)
+{
+    if (layout == kRows) {
+        if (dt == 0) return launch_cfg<T, kRows, 0>(tab, blocks, red_blocks, s);
+        return launch_cfg<T, kRows, 1>(tab, blocks, red_blocks, s);
+    }
+    if (dt == 0) return launch_cfg<T, kNCHW, 0>(tab, blocks, red_blocks, s);
+    return launch_cfg<T, kNCHW, 1>(tab, blocks, red_blocks, s);
+}
+
+}  // namespace
+
+size_t syrk_workspace_bytes(const FactorJob *jobs, int n)
+{
+    std::vector<Planned> pl;
+    std::vector<std::vector<int>> groups;
+    plan_all(jobs, n, pl, groups);
+    size_t total = 0;
+    for (int i = 0; i < n; ++i) total += align_up(pl[i].partial_floats * sizeof(float), 256);
+    return total;
+}
+
+hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_bytes, hipStream_t s)
+{
+    std::vector<Planned> pl;
+    std::vector<std::vector<int>> groups;
+    plan_all(jobs, n, pl, groups);
+    size_t off = 0;
+    std::vector<size_t> offs(n);
+    for (int i = 0; i < n; ++i) {
+        offs[i] = off;
+        off += align_up(pl[i].partial_floats * sizeof(float), 256);
+    }
+    if (off > work_bytes) return hipErrorInvalidValue;
+
+    for (auto &g : groups) {
+        SyrkTable tab;
+        tab.count = (int)g.size();
+        int blocks = 0, red = 0;
+        for (int k = 0; k < tab.count; ++k) {
+            const int j = g[k];
+            const FactorJob &job = jobs[j];
+            SyrkProb &p = tab.p[k];
+            p.x = job.x;
+            p.partial = reinterpret_cast<float *>(static_cast<char *>(work) + offs[j]);
+            p.F = job.F;
+            p.K = job.K;
+            p.ld = job.ld;
+            p.d = job.d_core;
+            p.hw = job.hw > 0 ? job.hw : 1;
+            p.ctot = job.ctot;
+            p.nb = pl[j].nb;
+            p.splits = pl[j].splits;
+            p.tiles_per_split = pl[j].tps;
+            p.blk_start = blocks;
+            p.red_start = red;
+            p.vec = vec_ok(job) ? 1 : 0;
+            p.has_bias = job.has_bias;
+            p.scale = job.scale;
+            p.decay = job.decay;
+            blocks += pl[j].nblk * pl[j].splits;
+            red += pl[j].nblk + (job.has_bias ? pl[j].nb : 0);
+        }
+        const int cfg = pl[g[0]].cfg;
+        const int layout = jobs[g[0]].layout, dt = jobs[g[0]].dtype;
+        hipError_t e;
+        switch (cfg) {
+            case 0: e = launch_ld<Tile<4, 2>>(tab, layout, dt, blocks, red, s); break;
+            case 1: e = launch_ld<Tile<3, 3>>(tab, layout, dt, blocks, red, s); break;
+            case 2: e = launch_ld<Tile<2, 2>>(tab, layout, dt, blocks, red, s); break;
+            default: e = launch_ld<Tile<1, 2>>(tab, layout, dt, blocks, red, s); break;
+        }
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace kfac

@@ -1,0 +1,171 @@
+"""GPU parity: the HIP library (through the C-ABI binding) against the CPU oracle,
+element by element on the same seeded inputs.
+
+Tolerances (relative Frobenius error, from the benchmark spec): 1e-4 for the
+fp32 factors, 1e-4 for the inverses, 1e-3 for the preconditioned gradient.
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import paper_2206_15143_amd as kf
+from oracle import kfac_oracle as orc
+from workloads import rng, shapes
+from workloads.shapes import LayerSpec
+
+import gpu_util as gu
+
+
+def _run_and_check(layers, batch, seed, act_kind="relu_normal", gout_std=0.0316, decay=0.95, damping=0.03,
+                   dtype="f32", batched=True, tols=(1e-4, 1e-4, 1e-3)):
+    inputs = gu.draw_inputs(layers, batch, seed, act_kind, gout_std, dtype)
+    scales = gu.scales_for(layers, batch)
+    gpu = gu.run_layers_gpu(layers, batch, inputs, scales, decay, damping, dtype, batched)
+    out = []
+    for i, l in enumerate(layers):
+        print(f"layer {i}: {l}", flush=True)
+        ref = gu.run_layer_oracle(l, inputs[i], scales[i], decay, damping)
+        out.append(gu.check_layer(gpu[i], ref, *tols, tag=f"layer {i} {l.kind} dA={l.d_A} dG={l.d_G}"))
+    return out
+
+
+def test_config1_fc_tiny_end_to_end():
+    layers = shapes.config_layers("fc_tiny")
+    hp = shapes.config_hparams("fc_tiny")
+    errs = _run_and_check(layers, hp["batch"], 1000, hp["act"], hp["gout_var"] ** 0.5, hp["decay"], hp["damping"],
+                          batched=False)
+    print(errs)
+
+
+@pytest.mark.parametrize("d_in,d_out,rows,bias", [
+    (20, 7, 50, True),        # one 32-tile, ragged everything
+    (64, 32, 33, True),       # 64 + bias
+    (144, 16, 300, True),     # the 144 tile config
+    (150, 40, 257, False),    # just over 144, no bias, rows not a multiple of 16
+    (300, 130, 100, True),    # several tiles per side, R < d (rank deficient before the average)
+])
+def test_linear_layers(d_in, d_out, rows, bias):
+    layer = LayerSpec("linear", d_in, d_out, rows=rows, has_bias=bias)
+    _run_and_check([layer], rows, 2000 + d_in, act_kind="normal", gout_std=0.1, batched=False)
+
+
+@pytest.mark.parametrize("cin,cout,k,stride,pad,h,batch", [
+    (4, 6, 3, 1, 1, 8, 3),
+    (16, 16, 3, 1, 1, 12, 2),
+    (3, 8, 7, 2, 3, 20, 2),     # stem-like: odd C*k*k (147 -> padded ld)
+    (8, 12, 1, 1, 0, 6, 3),     # 1x1 stride 1: NCHW read directly, HW % 4 == 0
+    (8, 12, 1, 1, 0, 7, 3),     # 1x1 with HW = 49 (unaligned scalar path)
+    (8, 16, 1, 2, 0, 8, 2),     # strided 1x1 projection
+    (5, 4, 3, 2, 1, 9, 2),      # odd channels, stride 2
+])
+def test_conv_layers(cin, cout, k, stride, pad, h, batch):
+    layer = LayerSpec("conv", cin, cout, k, stride, pad, h)
+    _run_and_check([layer], batch, 3000 + cin * 10 + k, batched=False)
+
+
+def test_im2col_alone_is_bit_exact():
+    for (cin, k, stride, pad, h, batch) in [(16, 3, 1, 1, 32, 2), (3, 7, 2, 3, 30, 2), (64, 3, 1, 1, 8, 3),
+                                            (12, 1, 2, 0, 10, 2), (200, 3, 1, 1, 7, 1)]:
+        print("im2col", cin, k, stride, pad, h, batch, flush=True)
+        x = rng.draw_relu_normal(77, 0, (batch, cin, h, h))
+        desc = kf.LayerDesc.conv2d(cin, 4, k, stride, pad)
+        ld = kf.kfac_patch_ld(desc)
+        ho = (h + 2 * pad - k) // stride + 1
+        out = torch.full((batch * ho * ho, ld), float("nan"), device=gu.DEV)
+        kf.kfac_im2col(desc, gu.to_dev(x), batch, h, h, out)
+        torch.cuda.synchronize()
+        ref = orc.patches(x, k, k, stride, pad, has_bias=False)
+        got = out.cpu().numpy()
+        assert np.array_equal(got[:, :ref.shape[1]].astype(np.float64), ref)
+        assert np.all(got[:, ref.shape[1]:] == 0)
+
+
+@pytest.mark.parametrize("n", [1, 5, 64, 65, 130, 257, 400])
+def test_inverse_sizes(n):
+    gen = np.random.default_rng(n)
+    X = gen.standard_normal((2 * n + 3, n))
+    M = (X.T @ X / (2 * n + 3)).astype(np.float32)
+    lam = 0.03
+    desc = kf.LayerDesc.linear(n, 3, has_bias=False)
+    G = np.eye(3, dtype=np.float32)
+    A_inv = torch.full((n, n), float("nan"), device=gu.DEV)
+    G_inv = torch.full((3, 3), float("nan"), device=gu.DEV)
+    info = torch.full((2,), -1, dtype=torch.int32, device=gu.DEV)
+    ws = gu.workspace(kf.kfac_workspace_bytes(desc, 8))
+    kf.kfac_invert(desc, gu.to_dev(M), gu.to_dev(G), lam, lam, A_inv, G_inv, info, ws)
+    torch.cuda.synchronize()
+    ref = orc.inverse(M.astype(np.float64), lam)
+    got = A_inv.cpu().numpy()
+    assert list(info.cpu().numpy()) == [0, 0]
+    assert gu.rel_fro(got, ref) < 1e-4
+    assert np.array_equal(got, got.T)
+    assert np.allclose(G_inv.cpu().numpy(), np.eye(3) / (1 + lam), rtol=1e-6)
+
+
+def test_not_positive_definite_is_flagged():
+    n = 70
+    M = np.eye(n, dtype=np.float32)
+    M[66, 66] = -2.0
+    desc = kf.LayerDesc.linear(n, 2, has_bias=False)
+    A_inv = torch.zeros((n, n), device=gu.DEV)
+    G_inv = torch.zeros((2, 2), device=gu.DEV)
+    info = torch.full((2,), -1, dtype=torch.int32, device=gu.DEV)
+    ws = gu.workspace(kf.kfac_workspace_bytes(desc, 8))
+    kf.kfac_invert(desc, gu.to_dev(M), gu.to_dev(np.eye(2, dtype=np.float32)), 0.5, 0.5, A_inv, G_inv, info, ws)
+    torch.cuda.synchronize()
+    assert list(info.cpu().numpy()) == [67, 0]
+    assert orc.inverse_info(M.astype(np.float64), 0.5) == 67
+
+
+def test_batched_mixed_layers_match_oracle_and_single_calls():
+    layers = [LayerSpec("conv", 4, 6, 3, 1, 1, 8), LayerSpec("linear", 70, 20, rows=40),
+              LayerSpec("conv", 8, 8, 1, 1, 0, 4), LayerSpec("conv", 16, 16, 3, 1, 1, 8),
+              LayerSpec("linear", 10, 3, rows=40, has_bias=False)]
+    batch = 5
+    inputs = gu.draw_inputs(layers, batch, 4000, "relu_normal", 0.05)
+    scales = gu.scales_for(layers, batch)
+    g1 = gu.run_layers_gpu(layers, batch, inputs, scales, 0.9, 0.01, batched=True)
+    g2 = gu.run_layers_gpu(layers, batch, inputs, scales, 0.9, 0.01, batched=False)
+    for i, l in enumerate(layers):
+        ref = gu.run_layer_oracle(l, inputs[i], scales[i], 0.9, 0.01)
+        gu.check_layer(g1[i], ref, tag=f"batched {i}")
+        gu.check_layer(g2[i], ref, tag=f"single {i}")
+
+
+def test_running_average_ends_and_repeat_is_bitwise_reproducible():
+    layer = LayerSpec("conv", 6, 5, 3, 1, 1, 10)
+    batch = 4
+    inp = gu.draw_inputs([layer], batch, 5000, "relu_normal", 0.1)
+    sc = gu.scales_for([layer], batch)
+    gen = np.random.default_rng(0)
+    A0 = (lambda m: m @ m.T)(gen.standard_normal((layer.d_A, layer.d_A)))
+    G0 = (lambda m: m @ m.T)(gen.standard_normal((layer.d_G, layer.d_G)))
+    A0f, G0f = A0.astype(np.float32).astype(np.float64), G0.astype(np.float32).astype(np.float64)
+    r1 = gu.run_layers_gpu([layer], batch, inp, sc, 1.0, 0.5, A0=[A0f], G0=[G0f])[0]
+    assert np.array_equal(r1["A"], A0f.astype(np.float32)) and np.array_equal(r1["G"], G0f.astype(np.float32))
+    r0 = gu.run_layers_gpu([layer], batch, inp, sc, 0.0, 0.5, A0=[A0f], G0=[G0f])[0]
+    ref = gu.run_layer_oracle(layer, inp[0], sc[0], 0.0, 0.5, A0f, G0f)
+    gu.check_layer(r0, ref, tag="decay 0")
+    ra = gu.run_layers_gpu([layer], batch, inp, sc, 0.95, 0.03)[0]
+    rb = gu.run_layers_gpu([layer], batch, inp, sc, 0.95, 0.03)[0]
+    for k in ("A", "G", "A_inv", "G_inv", "P"):
+        assert np.array_equal(ra[k], rb[k]), k
+
+
+def test_bf16_inputs_match_oracle_on_the_same_bits():
+    layers = [LayerSpec("linear", 96, 48, rows=200), LayerSpec("conv", 8, 8, 3, 1, 1, 8),
+              LayerSpec("conv", 16, 8, 1, 1, 0, 4)]
+    batch = 4
+    inputs = gu.draw_inputs(layers, batch, 6000, "relu_normal", 0.05, dtype="bf16")
+    scales = gu.scales_for(layers, batch)
+    gpu = gu.run_layers_gpu(layers, batch, inputs, scales, 0.95, 0.03, dtype="bf16")
+    for i, l in enumerate(layers):
+        ref = gu.run_layer_oracle(l, inputs[i], scales[i], 0.95, 0.03)
+        gu.check_layer(gpu[i], ref, tag=f"bf16 {i}")
+    # against the unrounded fp32 draws the allowance is 2e-2 on the preconditioned gradient
+    raw = gu.draw_inputs(layers, batch, 6000, "relu_normal", 0.05, dtype="f32")
+    for i, l in enumerate(layers):
+        ref = gu.run_layer_oracle(l, raw[i], scales[i], 0.95, 0.03)
+        assert gu.rel_fro(gpu[i]["P"], ref["P"]) < 2e-2
