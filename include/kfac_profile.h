@@ -1,0 +1,44 @@
+/*
+ * kfac_profile.h - measurement hooks of the K-FAC HIP library (not needed by
+ * callers of kfac.h).  Used by bench.py to time single kernel classes with HIP
+ * events on the launch stream, and by tuning sweeps.
+ */
+#ifndef KFAC_PROFILE_H
+#define KFAC_PROFILE_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Kernel classes the library launches. */
+enum {
+    KFAC_K_IM2COL = 0,       /* patch extraction */
+    KFAC_K_SYRK = 1,         /* MFMA X^T X partial tiles (the KF-GEMM) */
+    KFAC_K_SYRK_REDUCE = 2,  /* split reduction + running average epilogue */
+    KFAC_K_INV_INIT = 3,
+    KFAC_K_INV_PIVOT = 4,
+    KFAC_K_INV_PANEL = 5,
+    KFAC_K_INV_FINISH = 6,
+    KFAC_K_GEMM = 7,         /* A^T B MFMA GEMM (preconditioning and inverse updates) */
+    KFAC_K_COUNT = 8
+};
+
+/* When enabled, every kernel launch is bracketed by a pair of HIP events
+ * recorded on the launch stream (this allocates events; leave it off in
+ * production).  Host arrays; returns 0. */
+int kfac_timing_enable(int on);
+/* Waits for the recorded events, ADDS per-class elapsed milliseconds and launch
+ * counts into the two host arrays of KFAC_K_COUNT entries and forgets the
+ * recorded launches.  Returns 0, or non-zero on a HIP error. */
+int kfac_timing_collect(double *ms_per_class, long *launches_per_class);
+const char *kfac_timing_class_name(int cls);
+
+/* Development knob: "target_blocks", "min_tiles_per_split", "patch_chunk_bytes",
+ * "syrk_force_bm".  Returns 0 when the key is known.  Changing a knob changes
+ * the workspace requirement: query kfac_workspace_bytes* again afterwards. */
+int kfac_tune(const char *key, long value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

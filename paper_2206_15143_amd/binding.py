@@ -85,6 +85,10 @@ def load_library():
     lib.kfac_status_string.argtypes = [C.c_int]; lib.kfac_status_string.restype = C.c_char_p
     lib.kfac_version.argtypes = []; lib.kfac_version.restype = C.c_int
     lib.kfac_tune.argtypes = [C.c_char_p, C.c_long]; lib.kfac_tune.restype = C.c_int
+    lib.kfac_timing_enable.argtypes = [C.c_int]; lib.kfac_timing_enable.restype = C.c_int
+    lib.kfac_timing_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_long)]
+    lib.kfac_timing_collect.restype = C.c_int
+    lib.kfac_timing_class_name.argtypes = [C.c_int]; lib.kfac_timing_class_name.restype = C.c_char_p
     _lib = lib
     return lib
 
@@ -144,6 +148,23 @@ def kfac_version() -> int:
 def kfac_tune(key: str, value: int) -> None:
     if load_library().kfac_tune(key.encode(), int(value)) != 0:
         raise KeyError(key)
+
+
+KFAC_K_COUNT = 8
+
+
+def kfac_timing_enable(on: bool) -> None:
+    load_library().kfac_timing_enable(int(bool(on)))
+
+
+def kfac_timing_collect() -> dict:
+    """{class name: (milliseconds, launches)} accumulated since the last collect."""
+    lib = load_library()
+    ms = (C.c_double * KFAC_K_COUNT)()
+    cnt = (C.c_long * KFAC_K_COUNT)()
+    if lib.kfac_timing_collect(ms, cnt) != 0:
+        raise RuntimeError("kfac_timing_collect: HIP event error")
+    return {lib.kfac_timing_class_name(i).decode(): (float(ms[i]), int(cnt[i])) for i in range(KFAC_K_COUNT)}
 
 
 def kfac_dim_A(desc: LayerDesc) -> int:

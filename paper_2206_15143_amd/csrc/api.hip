@@ -17,6 +17,43 @@ Tuning &tuning()
 }
 
 namespace {
+struct TimingState {
+    bool on = false;
+    struct Rec { int cls; hipEvent_t a, b; };
+    std::vector<Rec> recs;
+    std::vector<hipEvent_t> pool;
+    hipEvent_t get()
+    {
+        if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+        hipEvent_t e = nullptr;
+        (void)hipEventCreate(&e);
+        return e;
+    }
+};
+TimingState &timing()
+{
+    static TimingState t;
+    return t;
+}
+}  // namespace
+
+void timing_begin(int cls, hipStream_t s)
+{
+    TimingState &t = timing();
+    if (!t.on) return;
+    TimingState::Rec r{cls, t.get(), t.get()};
+    (void)hipEventRecord(r.a, s);
+    t.recs.push_back(r);
+}
+
+void timing_end(hipStream_t s)
+{
+    TimingState &t = timing();
+    if (!t.on || t.recs.empty()) return;
+    (void)hipEventRecord(t.recs.back().b, s);
+}
+
+namespace {
 
 struct Geo {
     int dA, dG, d_core;
@@ -420,7 +457,36 @@ const char *kfac_status_string(kfac_status s)
 
 int kfac_version(void) { return 100; }
 
-/* Development knob (not part of the documented ABI): returns 0 when the key is known. */
+int kfac_timing_enable(int on)
+{
+    timing().on = on != 0;
+    return 0;
+}
+
+int kfac_timing_collect(double *ms, long *launches)
+{
+    auto &t = timing();
+    int rc = 0;
+    for (auto &r : t.recs) {
+        float e = 0.f;
+        if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&e, r.a, r.b) != hipSuccess) rc = 1;
+        if (ms) ms[r.cls] += e;
+        if (launches) launches[r.cls] += 1;
+        t.pool.push_back(r.a);
+        t.pool.push_back(r.b);
+    }
+    t.recs.clear();
+    return rc;
+}
+
+const char *kfac_timing_class_name(int cls)
+{
+    static const char *names[KFAC_K_COUNT] = {"im2col", "syrk_partial", "syrk_reduce", "inv_init",
+                                              "inv_pivot", "inv_panel", "inv_finish", "gemm_tn"};
+    return (cls >= 0 && cls < KFAC_K_COUNT) ? names[cls] : "?";
+}
+
+/* Development knob: returns 0 when the key is known. */
 int kfac_tune(const char *key, long value)
 {
     Tuning &t = tuning();

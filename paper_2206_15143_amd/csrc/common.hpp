@@ -7,6 +7,8 @@
 
 #include <vector>
 
+#include "../../include/kfac_profile.h"
+
 namespace kfac {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -82,12 +84,24 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // development knobs (set through kfac_tune)
 struct Tuning {
-    long target_blocks = 1024;       // blocks a grouped SYRK launch aims for
+    long target_blocks = 512;        // blocks a grouped SYRK launch aims for
     long min_tiles_per_split = 16;   // K tiles (of 16 rows) per split at least
     long patch_chunk_bytes = 160l << 20;   // patch bytes materialised per chunk in the batched path
     long invert_nb = 64;
     long syrk_force_bm = 0;          // 0 = choose
 };
 Tuning &tuning();
+
+// Optional per-launch HIP-event timing (see include/kfac_profile.h).
+void timing_begin(int cls, hipStream_t s);
+void timing_end(hipStream_t s);
+
+// Launch wrapper: records the event pair when timing is enabled.
+#define KFAC_LAUNCH(cls, stream, kernel, grid, block, smem, ...)               \
+    do {                                                                       \
+        ::kfac::timing_begin((cls), (stream));                                 \
+        hipLaunchKernelGGL(kernel, grid, block, smem, stream, __VA_ARGS__);    \
+        ::kfac::timing_end((stream));                                          \
+    } while (0)
 
 }  // namespace kfac

@@ -129,7 +129,7 @@ int choose_bm(int M, int N, bool square_lower)
 template <class T>
 hipError_t launch_one(const GemmTable &tab, int blocks, hipStream_t s)
 {
-    hipLaunchKernelGGL((gemm_tn_kernel<T>), dim3(blocks), dim3(T::NT), 0, s, tab);
+    KFAC_LAUNCH(KFAC_K_GEMM, s, (gemm_tn_kernel<T>), dim3(blocks), dim3(T::NT), 0, tab);
     return hipGetLastError();
 }
 

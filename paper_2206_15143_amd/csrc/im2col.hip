@@ -169,9 +169,9 @@ hipError_t im2col_launch(const Im2colJob *jobs, int n, hipStream_t s)
             if (tab.count == 0) return hipSuccess;
             if (smem > 64 * 1024) return hipErrorInvalidValue;   // slab of one output row does not fit LDS
             if (dt == 0)
-                hipLaunchKernelGGL((im2col_kernel<float>), dim3(blocks), dim3(256), smem, s, tab);
+                KFAC_LAUNCH(KFAC_K_IM2COL, s, (im2col_kernel<float>), dim3(blocks), dim3(256), smem, tab);
             else
-                hipLaunchKernelGGL((im2col_kernel<unsigned short>), dim3(blocks), dim3(256), smem, s, tab);
+                KFAC_LAUNCH(KFAC_K_IM2COL, s, (im2col_kernel<unsigned short>), dim3(blocks), dim3(256), smem, tab);
             tab.count = 0;
             blocks = 0;
             smem = 0;

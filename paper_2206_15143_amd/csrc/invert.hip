@@ -249,7 +249,7 @@ hipError_t invert_launch(const InvertJob *jobs, int n, void *work, size_t work_b
             blocks += (int)(((long)tab.p[k].n * tab.p[k].n + 4095) / 4096);
         }
         const int ew_blocks = blocks;
-        hipLaunchKernelGGL(sweep_init_kernel, dim3(ew_blocks), dim3(256), 0, s, tab);
+        KFAC_LAUNCH(KFAC_K_INV_INIT, s, sweep_init_kernel, dim3(ew_blocks), dim3(256), 0, tab);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
 
@@ -262,7 +262,7 @@ hipError_t invert_launch(const InvertJob *jobs, int n, void *work, size_t work_b
             while (active < cnt && tab.p[active].n > p0) ++active;
             InvTable t2 = tab;
             t2.count = active;
-            hipLaunchKernelGGL(sweep_pivot_kernel, dim3(active), dim3(256), 0, s, t2);
+            KFAC_LAUNCH(KFAC_K_INV_PIVOT, s, sweep_pivot_kernel, dim3(active), dim3(256), 0, t2);
             e = hipGetLastError();
             if (e != hipSuccess) return e;
             // panel + update only where something lies outside the pivot block
@@ -275,7 +275,7 @@ hipError_t invert_launch(const InvertJob *jobs, int n, void *work, size_t work_b
                 t2.p[k].blk_start = blocks;
                 blocks += (t2.p[k].n + NB - 1) / NB;
             }
-            hipLaunchKernelGGL(sweep_panel_kernel, dim3(blocks), dim3(256), 0, s, t2);
+            KFAC_LAUNCH(KFAC_K_INV_PANEL, s, sweep_panel_kernel, dim3(blocks), dim3(256), 0, t2);
             e = hipGetLastError();
             if (e != hipSuccess) return e;
             std::vector<GemmJob> gj(act2);
@@ -297,7 +297,7 @@ hipError_t invert_launch(const InvertJob *jobs, int n, void *work, size_t work_b
             tab.p[k].blk_start = blocks;
             blocks += (int)(((long)tab.p[k].n * tab.p[k].n + 4095) / 4096);
         }
-        hipLaunchKernelGGL(sweep_finish_kernel, dim3(blocks), dim3(256), 0, s, tab);
+        KFAC_LAUNCH(KFAC_K_INV_FINISH, s, sweep_finish_kernel, dim3(blocks), dim3(256), 0, tab);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -176,8 +176,11 @@ __global__ __launch_bounds__(T::NT) void syrk_partial_kernel(const SyrkTable tab
     }
 }
 
-// One block per BM x BM tile of the lower triangle (plus, with a bias, one
-// block per block row for the border).  Fixed summation order over the splits.
+// Split reduction + running average.  Each block owns 1024 consecutive elements
+// of one BM x BM tile of the lower triangle (plus, with a bias, one block per
+// block row for the border).  Fixed summation order over the splits.
+constexpr int kRedChunk = 256;
+
 template <class T>
 __global__ __launch_bounds__(256) void syrk_reduce_kernel(const SyrkTable tab)
 {
@@ -189,24 +192,39 @@ __global__ __launch_bounds__(256) void syrk_reduce_kernel(const SyrkTable tab)
     const int dF = pr.d + pr.has_bias;
     const float wnew = (1.0f - pr.decay) * pr.scale;
     constexpr int TILE = T::BM * T::BM;
+    constexpr int CPT = (TILE + kRedChunk - 1) / kRedChunk;   // chunks per tile
 
-    if (local < nblk) {
+    if (local < nblk * CPT) {
+        const int tile = local / CPT;
+        const int chunk = local - tile * CPT;
         int bi, bj;
-        tri_decode(local, bi, bj);
-        const float *src = pr.partial + (long)local * TILE;
+        tri_decode(tile, bi, bj);
+        const float *src = pr.partial + (long)tile * TILE;
         const long sstride = (long)nblk * TILE;
-        for (int e = threadIdx.x; e < TILE; e += 256) {
+#pragma unroll
+        for (int q = 0; q < kRedChunk / 256; ++q) {
+            const int e = chunk * kRedChunk + q * 256 + threadIdx.x;
+            if (e >= TILE) continue;
             const int r = e / T::BM, c = e - r * T::BM;
             const int u = bi * T::BM + r, v = bj * T::BM + c;
             if (u >= pr.d || v > u) continue;
-            float s = 0.f;
-            for (int k = 0; k < pr.splits; ++k) s += src[k * sstride + e];
+            // four interleaved running sums (fixed order, so still deterministic) keep loads in flight
+            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+            int k = 0;
+            for (; k + 4 <= pr.splits; k += 4) {
+                s0 += src[(k + 0) * sstride + e];
+                s1 += src[(k + 1) * sstride + e];
+                s2 += src[(k + 2) * sstride + e];
+                s3 += src[(k + 3) * sstride + e];
+            }
+            for (; k < pr.splits; ++k) s0 += src[k * sstride + e];
+            const float s = (s0 + s1) + (s2 + s3);
             const float out = pr.decay * pr.F[(long)u * dF + v] + wnew * s;
             pr.F[(long)u * dF + v] = out;
             pr.F[(long)v * dF + u] = out;
         }
     } else {
-        const int bi = local - nblk;
+        const int bi = local - nblk * CPT;
         const float *csum = pr.partial + (long)pr.splits * nblk * TILE;
         for (int r = threadIdx.x; r < T::BM; r += 256) {
             const int u = bi * T::BM + r;
@@ -321,10 +339,10 @@ bool vec_ok(const FactorJob &j)
 template <class T, int LAYOUT, int DT>
 hipError_t launch_cfg(const SyrkTable &tab, int blocks, int red_blocks, hipStream_t s)
 {
-    hipLaunchKernelGGL((syrk_partial_kernel<T, LAYOUT, DT>), dim3(blocks), dim3(T::NT), 0, s, tab);
+    KFAC_LAUNCH(KFAC_K_SYRK, s, (syrk_partial_kernel<T, LAYOUT, DT>), dim3(blocks), dim3(T::NT), 0, tab);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((syrk_reduce_kernel<T>), dim3(red_blocks), dim3(256), 0, s, tab);
+    KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<T>), dim3(red_blocks), dim3(256), 0, tab);
     return hipGetLastError();
 }
 
@@ -390,7 +408,11 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
             p.scale = job.scale;
             p.decay = job.decay;
             blocks += pl[j].nblk * pl[j].splits;
-            red += pl[j].nblk + (job.has_bias ? pl[j].nb : 0);
+            {
+                const int bm = kCfgs[pl[j].cfg].bm;
+                const int cpt = (bm * bm + kRedChunk - 1) / kRedChunk;
+                red += pl[j].nblk * cpt + (job.has_bias ? pl[j].nb : 0);
+            }
         }
         const int cfg = pl[g[0]].cfg;
         const int layout = jobs[g[0]].layout, dt = jobs[g[0]].dtype;

@@ -9,12 +9,15 @@ bfloat16 on the host, round-to-nearest-even.
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 
 _GAMMA = np.uint64(0x9E3779B97F4A7C15)
 _M1 = np.uint64(0xBF58476D1CE4E5B9)
 _M2 = np.uint64(0x94D049BB133111EB)
-_CHUNK = 1 << 22
+_CHUNK = 1 << 20
 
 
 def _mix64(z: np.ndarray) -> np.ndarray:
@@ -35,15 +38,24 @@ def draw_normal(seed: int, stream: int, shape, std: float = 1.0) -> np.ndarray:
     n = int(np.prod(shape))
     out = np.empty(n, dtype=np.float32)
     key = _key(seed, stream)
-    with np.errstate(over="ignore"):
-        for lo in range(0, n, _CHUNK):
-            hi = min(n, lo + _CHUNK)
+
+    def fill(lo):
+        hi = min(n, lo + _CHUNK)
+        with np.errstate(over="ignore"):
             ctr = np.arange(lo + 1, hi + 1, dtype=np.uint64)
             z = _mix64(key + ctr * _GAMMA)
-            u1 = ((z >> np.uint64(32)).astype(np.float64) + 1.0) * (1.0 / 4294967296.0)   # (0, 1]
-            u2 = (z & np.uint64(0xFFFFFFFF)).astype(np.float64) * (1.0 / 4294967296.0)    # [0, 1)
-            g = np.sqrt(-2.0 * np.log(u1)) * np.cos((2.0 * np.pi) * u2)
-            out[lo:hi] = (g * std).astype(np.float32)
+        u1 = ((z >> np.uint64(32)).astype(np.float64) + 1.0) * (1.0 / 4294967296.0)   # (0, 1]
+        u2 = (z & np.uint64(0xFFFFFFFF)).astype(np.float64) * (1.0 / 4294967296.0)    # [0, 1)
+        g = np.sqrt(-2.0 * np.log(u1)) * np.cos((2.0 * np.pi) * u2)
+        out[lo:hi] = (g * std).astype(np.float32)
+
+    starts = range(0, n, _CHUNK)
+    if len(starts) > 1:     # chunks are independent (counter based): fill them on a few threads
+        with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
+            list(ex.map(fill, starts))
+    else:
+        for lo in starts:
+            fill(lo)
     return out.reshape(shape)
 
 
