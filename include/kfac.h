@@ -23,7 +23,8 @@
  *     bitwise symmetric matrices.
  *   - Activations: LINEAR [rows, d_in]; CONV2D NCHW [batch, d_in, h, w].
  *     Output gradients: LINEAR [rows, d_out]; CONV2D NCHW [batch, d_out, h_out, w_out].
- *     Element type given by in_dtype (fp32 or bfloat16 bit patterns).
+ *     Element type given by in_dtype (fp32 or bfloat16 bit patterns).  Activation, output-gradient
+ *     and patch buffers must be 16-byte aligned; fp32 matrices 4-byte aligned; workspaces 256-byte aligned.
  *   - Patch column order is (c, i, j), c slowest, i.e. the flattening of a
  *     [C_out, C_in, kh, kw] weight to [C_out, C_in*kh*kw]; the bias column is
  *     LAST.  Gradients and preconditioned gradients are [d_G, d_A] fp32 with the
@@ -57,7 +58,7 @@ typedef enum {
     KFAC_ERR_WORKSPACE = 4,  /* workspace smaller than kfac_workspace_bytes says */
     KFAC_ERR_PARAM = 5,      /* decay outside [0,1], negative damping, scale <= 0 */
     KFAC_ERR_HIP = 6,        /* a HIP launch failed */
-    KFAC_ERR_ALIGN = 7       /* a device pointer is not aligned to its element type */
+    KFAC_ERR_ALIGN = 7       /* a device pointer is not aligned as required */
 } kfac_status;
 
 typedef enum { KFAC_F32 = 0, KFAC_BF16 = 1 } kfac_dtype;

@@ -293,7 +293,7 @@ kfac_status kfac_im2col(const kfac_layer_desc *d, const void *d_act, int batch, 
     if (st != KFAC_OK) return st;
     if (!g.conv) return KFAC_ERR_SHAPE;
     if (!d_act || !d_patches) return KFAC_ERR_NULL;
-    if (!aligned(d_act, g.esz) || !aligned(d_patches, 16)) return KFAC_ERR_ALIGN;
+    if (!aligned(d_act, 16) || !aligned(d_patches, 16)) return KFAC_ERR_ALIGN;
     Im2colJob j{};
     j.x = d_act; j.out = d_patches; j.dtype = d->in_dtype;
     j.B = batch; j.C = d->d_in; j.H = h; j.W = w; j.kh = d->kh; j.kw = d->kw;
@@ -318,7 +318,7 @@ kfac_status kfac_update_factors_batched(int n, const kfac_layer_desc *descs, con
         if (!d_act[i] || !d_gout[i] || !d_A_run[i] || !d_G_run[i]) return KFAC_ERR_NULL;
         if (!(scale_A[i] > 0.f) || !(scale_G[i] > 0.f)) return KFAC_ERR_PARAM;
         if (descs[i].kind == KFAC_CONV2D && (!h || !w)) return KFAC_ERR_NULL;
-        if (!aligned(d_act[i], pl.geo[i].esz) || !aligned(d_gout[i], pl.geo[i].esz) ||
+        if (!aligned(d_act[i], 16) || !aligned(d_gout[i], 16) ||
             !aligned(d_A_run[i], 4) || !aligned(d_G_run[i], 4))
             return KFAC_ERR_ALIGN;
     }
@@ -495,6 +495,8 @@ int kfac_tune(const char *key, long value)
     else if (k == "min_tiles_per_split") t.min_tiles_per_split = value;
     else if (k == "patch_chunk_bytes") t.patch_chunk_bytes = value;
     else if (k == "syrk_force_bm") t.syrk_force_bm = value;
+    else if (k == "use_wave_kernel") t.use_wave_kernel = value;
+    else if (k == "wave_debug") t.wave_debug = value;
     else return 1;
     return 0;
 }

@@ -89,6 +89,8 @@ struct Tuning {
     long patch_chunk_bytes = 160l << 20;   // patch bytes materialised per chunk in the batched path
     long invert_nb = 64;
     long syrk_force_bm = 0;          // 0 = choose
+    long use_wave_kernel = 1;        // wave-unit SYRK for aligned row-major fp32 operands
+    long wave_debug = 0;             // measurement only: 1 = skip MFMAs, 2 = skip data loads (results are wrong)
 };
 Tuning &tuning();
 

@@ -41,8 +41,15 @@ struct SyrkProb {
 
 struct SyrkTable {
     int count;
+    int debug;   // measurement switches of the wave kernel (0 in normal use): 1 = no MFMAs, 2 = no data loads
     SyrkProb p[kMaxProblems];
 };
+
+}  // namespace kfac
+
+#include "syrk_wave.hpp"
+
+namespace kfac {
 
 template <class T, int LAYOUT, int DT>
 __global__ __launch_bounds__(T::NT) void syrk_partial_kernel(const SyrkTable tab)
@@ -248,7 +255,21 @@ __global__ __launch_bounds__(256) void syrk_reduce_kernel(const SyrkTable tab)
 namespace {
 
 struct Cfg { int wt, nw, bm; };
-const Cfg kCfgs[] = {{4, 2, 128}, {3, 3, 144}, {2, 2, 64}, {1, 2, 32}};
+// the last entry is the wave-unit kernel (syrk_wave.hpp): 144-wide macro tiles, same partial layout as Tile<3,3>
+const Cfg kCfgs[] = {{4, 2, 128}, {3, 3, 144}, {2, 2, 64}, {1, 2, 32}, {0, 0, 144}};
+constexpr int kWaveCfg = 4;
+
+bool wave_eligible(const FactorJob &j)
+{
+    // shape-only test (the C ABI requires 16-byte aligned inputs), so that the workspace plan made
+    // without pointers matches the launch
+    if (!(tuning().use_wave_kernel && j.dtype == 0 && j.layout == kRows && j.ld % 4 == 0 && j.ld < (1l << 22)))
+        return false;
+    // the wave kernel always multiplies whole 45-tile units: use it only where that wastes little
+    const long T = (j.d_core + 15) / 16, m = (j.d_core + W_MT - 1) / W_MT;
+    const long exact = T * (T + 1) / 2, padded = 45 * m + 81 * m * (m - 1) / 2;
+    return padded * 100 <= exact * 115;
+}
 
 // padded MFMA work (in 16x16 tiles) of the lower triangle for a config
 long tri_tiles(int d, const Cfg &c)
@@ -276,6 +297,7 @@ int choose_cfg(int d)
 struct Planned {
     int cfg;
     int nb, nblk, splits, tps;
+    int bps;   // blocks per split
     size_t partial_floats;
 };
 
@@ -290,7 +312,8 @@ void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<
         p.nb = (jobs[j].d_core + c.bm - 1) / c.bm;
         p.nblk = p.nb * (p.nb + 1) / 2;
         const long ktiles = (jobs[j].K + 15) / 16;
-        work += (double)p.nblk * (double)ktiles;
+        p.bps = (p.cfg == kWaveCfg) ? wave_blocks_per_split(p.nb) : p.nblk;
+        work += (double)p.bps * (double)ktiles;
     }
     long tpb = (long)std::ceil(work / (double)tu.target_blocks);
     tpb = std::max<long>(tpb, tu.min_tiles_per_split);
@@ -298,7 +321,10 @@ void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<
         Planned &p = pl[j];
         const Cfg &c = kCfgs[p.cfg];
         const long ktiles = std::max<long>(1, (jobs[j].K + 15) / 16);
-        p.splits = (int)((ktiles + tpb - 1) / tpb);
+        long tpb_j = tpb;
+        if (p.cfg == kWaveCfg)   // a split's byte range must stay below 2^31 (32-bit buffer offsets)
+            tpb_j = std::max<long>(1, std::min<long>(tpb_j, 0x7fffffffl / (64 * jobs[j].ld) - 1));
+        p.splits = (int)((ktiles + tpb_j - 1) / tpb_j);
         p.tps = (int)((ktiles + p.splits - 1) / p.splits);
         p.splits = (int)((ktiles + p.tps - 1) / p.tps);
         p.partial_floats = (size_t)p.splits * ((size_t)p.nblk * c.bm * c.bm + (size_t)p.nb * c.bm);
@@ -312,11 +338,11 @@ void plan_all(const FactorJob *jobs, int n, std::vector<Planned> &pl, std::vecto
     pl.assign(n, Planned());
     std::vector<int> keys(n);
     for (int i = 0; i < n; ++i) {
-        pl[i].cfg = choose_cfg(jobs[i].d_core);
+        pl[i].cfg = wave_eligible(jobs[i]) ? kWaveCfg : choose_cfg(jobs[i].d_core);
         keys[i] = group_key(jobs[i], pl[i].cfg);
     }
     groups.clear();
-    for (int key = 0; key < 16; ++key) {
+    for (int key = 0; key < 20; ++key) {
         std::vector<int> cur;
         for (int i = 0; i < n; ++i) {
             if (keys[i] != key) continue;
@@ -385,6 +411,7 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
     for (auto &g : groups) {
         SyrkTable tab;
         tab.count = (int)g.size();
+        tab.debug = (int)tuning().wave_debug;
         int blocks = 0, red = 0;
         for (int k = 0; k < tab.count; ++k) {
             const int j = g[k];
@@ -407,7 +434,7 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
             p.has_bias = job.has_bias;
             p.scale = job.scale;
             p.decay = job.decay;
-            blocks += pl[j].nblk * pl[j].splits;
+            blocks += pl[j].bps * pl[j].splits;
             {
                 const int bm = kCfgs[pl[j].cfg].bm;
                 const int cpt = (bm * bm + kRedChunk - 1) / kRedChunk;
@@ -418,6 +445,14 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
         const int layout = jobs[g[0]].layout, dt = jobs[g[0]].dtype;
         hipError_t e;
         switch (cfg) {
+            case kWaveCfg: {
+                KFAC_LAUNCH(KFAC_K_SYRK, s, syrk_wave_kernel, dim3(blocks), dim3(256), 0, tab);
+                e = hipGetLastError();
+                if (e != hipSuccess) break;
+                KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<3, 3>>), dim3(red), dim3(256), 0, tab);
+                e = hipGetLastError();
+                break;
+            }
             case 0: e = launch_ld<Tile<4, 2>>(tab, layout, dt, blocks, red, s); break;
             case 1: e = launch_ld<Tile<3, 3>>(tab, layout, dt, blocks, red, s); break;
             case 2: e = launch_ld<Tile<2, 2>>(tab, layout, dt, blocks, red, s); break;

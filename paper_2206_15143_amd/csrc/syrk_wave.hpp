@@ -1,0 +1,367 @@
+// Second-generation partial-product kernel for X^T X on row-major fp32 X
+// (patch matrices, linear-layer inputs): "one wavefront = one 45-tile unit".
+//
+// The lower triangle is cut into 144 x 144 macro tiles (9 x 9 MFMA tiles of
+// v_mfma_f32_16x16x4_f32).  A wavefront owns one unit of at most 45 MFMA tiles
+// and keeps all 45 accumulators (180 registers) for the whole K range:
+//   DIAG(i)     : the 45 lower tiles of macro tile (i, i); one operand set (a == b),
+//   HALF(i,j,h) : rows of macro i x column tiles [0,5) (h=0) or [5,9) (h=1) of macro j < i.
+// A workgroup is four wavefronts that share the staged column panels:
+//   D block, full  : DIAG(a), DIAG(a+1), HALF(a+1,a,0), HALF(a+1,a,1)      panels a, a+1
+//   D block, single: DIAG(a) only (last macro of an odd count): the four waves
+//                    split K (each takes one k-step of four) over three staged
+//                    K tiles and add their accumulators through LDS at the end
+//   R block        : HALF(i,j,0), HALF(i,j,1), HALF(i,j+1,0), HALF(i,j+1,1)  panels i, j, j+1
+// Every unit does 36-45 MFMAs per 9-14 LDS operand reads, and the waves of a
+// block carry equal work (within 10 %), unlike square block tiles whose
+// diagonal blocks leave a third of the waves idle.
+//
+// Panels ([16 rows][144 columns], pitch 144 = 16 mod 32: conflict-free operand
+// reads) are filled by buffer_load_dwordx4 ... lds: each wave instruction
+// copies 1 KB straight from global memory into LDS, nine per panel, with no
+// staging registers; rows past K and columns past the row length read as zero
+// through the buffer range check.  A ring of four stage buffers keeps three
+// stages of loads in flight behind the MFMAs of the current one (a single CU
+// must have ~60 KB outstanding to pull its share of HBM bandwidth).
+#pragma once
+
+#include "tn_engine.hpp"
+
+namespace kfac {
+
+constexpr int W_MT = 144;           // macro tile order
+constexpr int W_NT = 9;             // MFMA tiles per macro side
+constexpr int W_KT = 16;            // rows per staged K tile
+constexpr int W_PANEL = W_KT * W_MT;   // floats per panel stage
+constexpr int W_SLOTS = 3;
+constexpr unsigned W_OOB = 0x80000000u;
+
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+
+__host__ __device__ inline int wave_blocks_per_split(int m)
+{
+    int n = (m + 1) / 2;
+    for (int i = 2; i < m; ++i) n += i / 2;
+    return n;
+}
+
+struct WaveRole {
+    int rslot, cslot;   // panel slots of the row / column operand
+    int ctile0;         // first column tile inside the column panel
+    int nc;             // column tiles (5 or 4); 0 = DIAG
+    int I, J;           // macro tile written
+    int nrt;            // valid row tiles of macro I
+};
+
+// One k-step (4 rows) of a DIAG unit.  Straight-line code: all 45 tiles are always multiplied (tiles
+// past the matrix edge see zero-filled operands), so every MFMA accumulates in place.
+__device__ __forceinline__ void unit_diag(const float *P, int kk, int lane, floatx4 (&acc)[45])
+{
+    const int lr = lane & 15, lk = lane >> 4;
+    const float *src = P + (kk + lk) * W_MT + lr;
+    float a[W_NT];
+#pragma unroll
+    for (int t = 0; t < W_NT; ++t) a[t] = src[t * 16];
+#pragma unroll
+    for (int ti = 0; ti < W_NT; ++ti)
+#pragma unroll
+        for (int tj = 0; tj <= ti; ++tj)
+            acc[ti * (ti + 1) / 2 + tj] =
+                __builtin_amdgcn_mfma_f32_16x16x4f32(a[ti], a[tj], acc[ti * (ti + 1) / 2 + tj], 0, 0, 0);
+}
+
+// One k-step of a HALF unit: 9 row tiles x NC (5 or 4) column tiles.
+template <int NC>
+__device__ __forceinline__ void unit_half(const float *Pr, const float *Pc, int kk, int lane, floatx4 (&acc)[45])
+{
+    const int lr = lane & 15, lk = lane >> 4;
+    const float *sr = Pr + (kk + lk) * W_MT + lr;
+    const float *sc = Pc + (kk + lk) * W_MT + lr;     // Pc already points at the first column tile
+    float a[W_NT], b[NC];
+#pragma unroll
+    for (int t = 0; t < W_NT; ++t) a[t] = sr[t * 16];
+#pragma unroll
+    for (int t = 0; t < NC; ++t) b[t] = sc[t * 16];
+#pragma unroll
+    for (int ti = 0; ti < W_NT; ++ti)
+#pragma unroll
+        for (int tj = 0; tj < NC; ++tj)
+            acc[ti * 5 + tj] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[ti], b[tj], acc[ti * 5 + tj], 0, 0, 0);
+}
+
+enum WaveKind : int { kSingle = 0, kDiag = 1, kHalf5 = 2, kHalf4 = 3 };
+
+constexpr int W_NSTAGE = 4;                              // ring of stage buffers (three stages in flight)
+constexpr int W_STAGE = W_SLOTS * W_PANEL;               // floats per stage buffer
+constexpr int W_LDS_FLOATS = W_NSTAGE * W_STAGE + 256;   // + 1 KB landing zone for the padding loads
+constexpr int W_LOADS_PER_STAGE = 9;                     // buffer->LDS instructions per wave and stage (fixed)
+
+typedef int int4v __attribute__((ext_vector_type(4)));
+
+// One 1 KB global->LDS copy: lane l moves 16 bytes from (resource base + voff + soff) to LDS byte
+// address lds_byte + 16*l.  Out-of-range offsets store zeros.  Issued through inline assembly so
+// that the wait for its completion can be placed by hand (s_waitcnt vmcnt(N) in wave_sync): the
+// loop keeps three stages of loads in flight behind the MFMAs.
+__device__ __forceinline__ void dma16(unsigned lds_byte, unsigned voff, int4v rsrc, unsigned soff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_byte), "v"(voff), "s"(rsrc), "s"(soff)
+                 : "memory");
+}
+
+// Wait until at most two stages of this wave's loads are outstanding, then meet the other waves.
+__device__ __forceinline__ void wave_sync()
+{
+    asm volatile("s_waitcnt vmcnt(18)\n\ts_barrier" ::: "memory");
+}
+
+struct WaveCtx {
+    int4v rsrc;
+    unsigned vo[W_SLOTS][3];   // per-lane byte offsets of the 1 KB pieces q = w, w+4, w+8 of each panel slot
+    unsigned tile_bytes;
+    unsigned lds_base;         // LDS byte address of the stage ring
+    int nslots, ntl, nstages;
+    int w, lane, tid;
+    int rslot, cslot, ctile0;
+    bool single, owns_colsum;
+    bool no_mfma, no_load;   // measurement switches
+};
+
+// Issue the loads of stage g into ring buffer g % 4: exactly nine instructions per wave, whatever
+// the block kind (missing panels, pieces past the ninth and stages past the end become all-out-of-range
+// loads, which move no data), so the vmcnt arithmetic of wave_sync is the same everywhere.
+__device__ __forceinline__ void wave_issue(const WaveCtx &c, int g)
+{
+    const unsigned buf = c.lds_base + (unsigned)((g & (W_NSTAGE - 1)) * W_STAGE * 4);
+    const unsigned dummy = c.lds_base + (unsigned)(W_NSTAGE * W_STAGE * 4);
+#pragma unroll
+    for (int s = 0; s < W_SLOTS; ++s) {
+        const int tl = c.single ? 3 * g + s : g;       // K tile (relative to the split) this slot holds
+        const bool live = (s < c.nslots) && (g < c.nstages) && (tl < c.ntl) && !c.no_load;
+        const unsigned so = live ? (unsigned)tl * c.tile_bytes : 0u;
+#pragma unroll
+        for (int qi = 0; qi < 3; ++qi) {
+            const int q = c.w + 4 * qi;
+            const bool piece = q < W_NT;
+            const unsigned v = (live && piece) ? c.vo[s][qi] : W_OOB;
+            const unsigned dst = piece ? buf + (unsigned)((s * W_PANEL + q * 256) * 4) : dummy;
+            dma16(dst, v, c.rsrc, so);
+        }
+    }
+}
+
+// The whole K loop of one wave, specialised on the kind of unit it owns so that the loop body is
+// straight-line MFMA code accumulating in place.  All four specialisations execute the same number
+// of barriers (nstages is uniform over the workgroup).
+template <int KIND>
+__device__ __forceinline__ void wave_loop(const WaveCtx &c, const float *lds, floatx4 (&acc)[45], float &cs0,
+                                          float &cs1)
+{
+    wave_issue(c, 0);
+    wave_issue(c, 1);
+    wave_issue(c, 2);
+    wave_sync();
+    for (int g = 0; g < c.nstages; ++g) {
+        wave_issue(c, g + 3);
+        const float *buf = lds + (g & (W_NSTAGE - 1)) * W_STAGE;
+        if (c.no_mfma) {
+            // measurement only
+        } else if (KIND == kSingle) {
+            // wave w multiplies rows 4w..4w+3 of each of the three staged K tiles
+#pragma unroll
+            for (int st = 0; st < 3; ++st) unit_diag(buf + st * W_PANEL, 4 * c.w, c.lane, acc);
+        } else if (KIND == kDiag) {
+            const float *P = buf + c.rslot * W_PANEL;
+#pragma unroll
+            for (int st = 0; st < 4; ++st) unit_diag(P, 4 * st, c.lane, acc);
+        } else {
+            const float *Pr = buf + c.rslot * W_PANEL;
+            const float *Pc = buf + c.cslot * W_PANEL + c.ctile0 * 16;
+#pragma unroll
+            for (int st = 0; st < 4; ++st) unit_half<KIND == kHalf5 ? 5 : 4>(Pr, Pc, 4 * st, c.lane, acc);
+        }
+        if (c.owns_colsum && c.tid < W_MT) {
+            // column sums of the staged rows (rows past K are zero)
+            const float *c0 = buf + c.tid;
+            float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+            for (int k = 0; k < W_KT; ++k) s0 += c0[k * W_MT];
+#pragma unroll
+            for (int k = 0; k < W_KT; ++k) s1 += c0[W_PANEL + k * W_MT];
+            if (KIND == kSingle) {
+                float s2 = 0.f;
+#pragma unroll
+                for (int k = 0; k < W_KT; ++k) s2 += c0[2 * W_PANEL + k * W_MT];
+                cs0 += (s0 + s1) + s2;
+            } else {
+                cs0 += s0;
+                cs1 += s1;
+            }
+        }
+        wave_sync();
+    }
+    // the padding loads of the stages past the end may still be landing in the ring
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+__global__ __launch_bounds__(256) void syrk_wave_kernel(const SyrkTable tab)
+{
+    __shared__ float lds[W_LDS_FLOATS];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    int pi = 0;
+    while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].blk_start) ++pi;
+    const SyrkProb &pr = tab.p[pi];
+    const int m = pr.nb;
+    const int nbps = wave_blocks_per_split(m);
+    const int local = blockIdx.x - pr.blk_start;
+    const int split = local / nbps;
+    const int b = local - split * nbps;
+    const int nds = (m + 1) / 2;
+    const int nblk = m * (m + 1) / 2;
+    const int ntiles_last = (pr.d - (m - 1) * W_MT + 15) / 16;   // valid MFMA tiles of the last macro
+
+    // ---- block kind, panel slots, wave role ----
+    int mac0 = 0, mac1 = 0, mac2 = 0;   // macro index per panel slot
+    WaveCtx c;
+    c.single = false;
+    c.owns_colsum = false;
+    int kind, I, J;
+    if (b < nds) {
+        const int a = 2 * b;
+        c.owns_colsum = pr.has_bias != 0;
+        if (a + 1 < m) {
+            c.nslots = 2; mac0 = a; mac1 = a + 1;
+            if (w == 0)      { kind = kDiag;  c.rslot = 0; c.cslot = 0; c.ctile0 = 0; I = a;     J = a; }
+            else if (w == 1) { kind = kDiag;  c.rslot = 1; c.cslot = 1; c.ctile0 = 0; I = a + 1; J = a + 1; }
+            else if (w == 2) { kind = kHalf5; c.rslot = 1; c.cslot = 0; c.ctile0 = 0; I = a + 1; J = a; }
+            else             { kind = kHalf4; c.rslot = 1; c.cslot = 0; c.ctile0 = 5; I = a + 1; J = a; }
+        } else {
+            c.single = true;
+            c.nslots = 3; mac0 = mac1 = mac2 = a;
+            kind = kSingle; c.rslot = 0; c.cslot = 0; c.ctile0 = 0; I = a; J = a;
+        }
+    } else {
+        int r = b - nds, i = 2;
+        while (r >= i / 2) { r -= i / 2; ++i; }
+        const int j = 2 * r;
+        c.nslots = 3; mac0 = i; mac1 = j; mac2 = j + 1;
+        c.rslot = 0; I = i;
+        if (w == 0)      { kind = kHalf5; c.cslot = 1; c.ctile0 = 0; J = j; }
+        else if (w == 1) { kind = kHalf4; c.cslot = 1; c.ctile0 = 5; J = j; }
+        else if (w == 2) { kind = kHalf5; c.cslot = 2; c.ctile0 = 0; J = j + 1; }
+        else             { kind = kHalf4; c.cslot = 2; c.ctile0 = 5; J = j + 1; }
+    }
+    const int nrt = (I == m - 1) ? ntiles_last : W_NT;   // valid row tiles of macro I (only the stores look at it)
+
+    // ---- K range of this split, buffer resource over it ----
+    const long ktiles = (pr.K + W_KT - 1) / W_KT;
+    const long t0 = (long)split * pr.tiles_per_split;
+    const long t1 = (t0 + pr.tiles_per_split < ktiles) ? t0 + pr.tiles_per_split : ktiles;
+    c.ntl = (int)(t1 - t0);
+    const long row0 = t0 * W_KT;
+    const float *base = reinterpret_cast<const float *>(pr.x) + row0 * pr.ld;
+    const long bytes_left = (pr.K - row0) * pr.ld * 4;
+    const int nrec = bytes_left > 0x7fffffffl ? 0x7fffffff : (int)bytes_left;
+    {   // raw buffer resource over the rows of this split: base, stride 0, byte count, dword format
+        const unsigned long ba = (unsigned long)base;
+        c.rsrc.x = (int)(unsigned)ba;
+        c.rsrc.y = (int)(unsigned)(ba >> 32);
+        c.rsrc.z = nrec;
+        c.rsrc.w = 0x00020000;
+    }
+    c.lds_base = (unsigned)(unsigned long)(__attribute__((address_space(3))) float *)lds;
+    c.w = w; c.lane = lane; c.tid = tid;
+    c.no_mfma = (tab.debug & 1) != 0;
+    c.no_load = (tab.debug & 2) != 0;
+    const int ld = (int)pr.ld;
+#pragma unroll
+    for (int qi = 0; qi < 3; ++qi) {
+        const int q = w + 4 * qi;
+        const int f = 256 * q + 4 * lane;
+        const int k = f / W_MT;
+        const int col = f - k * W_MT;
+        const bool qok = q < W_NT;
+        const int g0 = mac0 * W_MT + col, g1 = mac1 * W_MT + col, g2 = mac2 * W_MT + col;
+        c.vo[0][qi] = (qok && g0 < ld) ? (unsigned)((k * ld + g0) * 4) : W_OOB;
+        c.vo[1][qi] = (qok && g1 < ld) ? (unsigned)((k * ld + g1) * 4) : W_OOB;
+        c.vo[2][qi] = (qok && g2 < ld) ? (unsigned)((k * ld + g2) * 4) : W_OOB;
+    }
+    c.tile_bytes = (unsigned)(W_KT * ld * 4);
+    c.nstages = (c.ntl + (c.single ? 3 : 1) - 1) / (c.single ? 3 : 1);
+
+    floatx4 acc[45];
+#pragma unroll
+    for (int i = 0; i < 45; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+    float cs0 = 0.f, cs1 = 0.f;
+
+    if (kind == kSingle)     wave_loop<kSingle>(c, lds, acc, cs0, cs1);
+    else if (kind == kDiag)  wave_loop<kDiag>(c, lds, acc, cs0, cs1);
+    else if (kind == kHalf5) wave_loop<kHalf5>(c, lds, acc, cs0, cs1);
+    else                     wave_loop<kHalf4>(c, lds, acc, cs0, cs1);
+
+    // ---- single blocks: add the four waves' accumulators through LDS (fixed order w1, w2, w3) ----
+    if (c.single) {
+        float *xch = lds;   // 45 * 4 * 64 floats = 46080 bytes of the (now idle) stage ring
+        for (int r = 1; r < 4; ++r) {
+            __syncthreads();
+            if (w == r) {
+#pragma unroll
+                for (int i = 0; i < 45; ++i)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) xch[(i * 4 + v) * 64 + lane] = acc[i][v];
+            }
+            __syncthreads();
+            if (w == 0) {
+#pragma unroll
+                for (int i = 0; i < 45; ++i)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[i][v] += xch[(i * 4 + v) * 64 + lane];
+            }
+        }
+    }
+
+    // ---- partial tiles out ----
+    if (!c.single || w == 0) {
+        float *dst = pr.partial + ((long)split * nblk + (I * (I + 1) / 2 + J)) * (W_MT * W_MT);
+        const int lr = lane & 15, lk = lane >> 4;
+        if (kind == kSingle || kind == kDiag) {
+#pragma unroll
+            for (int ti = 0; ti < W_NT; ++ti) {
+                if (ti < nrt) {
+#pragma unroll
+                    for (int tj = 0; tj <= ti; ++tj)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            dst[(ti * 16 + 4 * lk + v) * W_MT + tj * 16 + lr] = acc[ti * (ti + 1) / 2 + tj][v];
+                }
+            }
+        } else {
+            const int nc = (kind == kHalf5) ? 5 : 4;
+#pragma unroll
+            for (int ti = 0; ti < W_NT; ++ti) {
+                if (ti < nrt) {
+#pragma unroll
+                    for (int tj = 0; tj < 5; ++tj) {
+                        if (tj < nc) {
+#pragma unroll
+                            for (int v = 0; v < 4; ++v)
+                                dst[(ti * 16 + 4 * lk + v) * W_MT + (c.ctile0 + tj) * 16 + lr] = acc[ti * 5 + tj][v];
+                        }
+                    }
+                }
+            }
+        }
+    }
+    if (c.owns_colsum && tid < W_MT) {
+        float *csum = pr.partial + (long)pr.splits * nblk * (W_MT * W_MT);
+        csum[((long)split * m + mac0) * W_MT + tid] = cs0;
+        if (!c.single) csum[((long)split * m + mac1) * W_MT + tid] = cs1;
+    }
+}
+
+}  // namespace kfac
