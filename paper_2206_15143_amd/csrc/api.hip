@@ -60,6 +60,7 @@ struct Geo {
     int Ho, Wo;
     long R;             // rows of the patch matrix / samples
     bool conv, patches; // patches: the extractor has to run
+    bool fused3;        // 3x3/s1/p1 fp32 conv whose A factor is built straight from the NCHW input
     int ld;             // patch leading dimension (elements)
     int esz;
 };
@@ -109,10 +110,15 @@ kfac_status geometry(const kfac_layer_desc *d, int batch, int h, int w, Geo &g)
         g.Wo = (w + 2 * d->pad - d->kw) / d->stride + 1;
         g.R = (long)batch * g.Ho * g.Wo;
         g.patches = !(d->kh == 1 && d->kw == 1 && d->stride == 1 && d->pad == 0);
+        g.fused3 = tuning().fuse_conv3 && d->in_dtype == KFAC_F32 && d->kh == 3 && d->kw == 3 && d->stride == 1 &&
+                   d->pad == 1 && d->d_in % 16 == 0 && conv3_rows(h, w) > 0 &&
+                   (long)batch * d->d_in * h * w * 4 < 0x7fff0000l;
+        if (g.fused3) g.patches = false;
     } else {
         g.Ho = g.Wo = 1;
         g.R = batch;
         g.patches = false;
+        g.fused3 = false;
     }
     return KFAC_OK;
 }
@@ -136,6 +142,8 @@ void layer_jobs(const kfac_layer_desc *d, const Geo &g, const void *act, const v
     a.K = g.R;
     if (!g.conv) {
         a.x = act; a.layout = kRows; a.ld = d->d_in; a.hw = 1; a.ctot = d->d_in;
+    } else if (g.fused3) {
+        a.x = act; a.layout = kConv3; a.ld = 0; a.hw = h * w; a.ctot = d->d_in; a.h = h; a.w = w;
     } else if (!g.patches) {
         a.x = act; a.layout = kNCHW; a.ld = 0; a.hw = h * w; a.ctot = d->d_in;
     } else {
@@ -497,6 +505,7 @@ int kfac_tune(const char *key, long value)
     else if (k == "syrk_force_bm") t.syrk_force_bm = value;
     else if (k == "use_wave_kernel") t.use_wave_kernel = value;
     else if (k == "wave_debug") t.wave_debug = value;
+    else if (k == "fuse_conv3") t.fuse_conv3 = value;
     else return 1;
     return 0;
 }

@@ -18,7 +18,8 @@ constexpr int kMaxProblems = 40;   // problems per grouped launch (table travels
 
 enum Layout : int {
     kRows = 0,   // X is [K, ld] row-major: element (k, c) at k*ld + c
-    kNCHW = 1    // X is [n][ctot][hw]: element (k = n*hw + p, c) at (n*ctot + c)*hw + p
+    kNCHW = 1,   // X is [n][ctot][hw]: element (k = n*hw + p, c) at (n*ctot + c)*hw + p
+    kConv3 = 2   // X is the NCHW input of a 3x3/stride 1/pad 1 convolution; the patch rows are implicit
 };
 
 // One factor to build: F <- decay*F + (1-decay)*scale*X^T X  (+ bias border).
@@ -29,7 +30,8 @@ struct FactorJob {
     long K;          // number of rows (samples x positions)
     long ld;         // kRows: row pitch in elements
     int d_core;      // real columns of X
-    int hw, ctot;    // kNCHW addressing
+    int hw, ctot;    // kNCHW / kConv3 addressing (ctot = channels)
+    int h, w;        // kConv3: image size
     int has_bias;    // factor has one more row/column: column sums and the count K
     float scale, decay;
     float *F;        // [d, d], d = d_core + has_bias
@@ -80,6 +82,9 @@ hipError_t gemm_launch(const GemmJob *jobs, int n, hipStream_t s);
 
 hipError_t im2col_launch(const Im2colJob *jobs, int n, hipStream_t s);
 
+// output rows per stage of the fused 3x3 convolution factor kernel; 0 = image shape not supported
+int conv3_rows(int h, int w);
+
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // development knobs (set through kfac_tune)
@@ -90,6 +95,7 @@ struct Tuning {
     long invert_nb = 64;
     long syrk_force_bm = 0;          // 0 = choose
     long use_wave_kernel = 1;        // wave-unit SYRK for aligned row-major fp32 operands
+    long fuse_conv3 = 1;             // 3x3/s1/p1 fp32 convs: build A straight from the NCHW input
     long wave_debug = 0;             // measurement only: 1 = skip MFMAs, 2 = skip data loads (results are wrong)
 };
 Tuning &tuning();

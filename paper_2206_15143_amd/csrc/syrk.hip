@@ -48,6 +48,7 @@ struct SyrkTable {
 }  // namespace kfac
 
 #include "syrk_wave.hpp"
+#include "syrk_conv3.hpp"
 
 namespace kfac {
 
@@ -188,7 +189,10 @@ __global__ __launch_bounds__(T::NT) void syrk_partial_kernel(const SyrkTable tab
 // block row for the border).  Fixed summation order over the splits.
 constexpr int kRedChunk = 256;
 
-template <class T>
+// NATIVE: the partial tiles are stored as the MFMA accumulators lie in registers (per 16x16 tile
+// [lane][4], tiles row-major inside the 144-wide macro tile), which lets the wave kernels store
+// 16 bytes per lane; element e of a macro tile then maps to row / column as decoded below.
+template <class T, bool NATIVE = false>
 __global__ __launch_bounds__(256) void syrk_reduce_kernel(const SyrkTable tab)
 {
     int pi = 0;
@@ -212,7 +216,17 @@ __global__ __launch_bounds__(256) void syrk_reduce_kernel(const SyrkTable tab)
         for (int q = 0; q < kRedChunk / 256; ++q) {
             const int e = chunk * kRedChunk + q * 256 + threadIdx.x;
             if (e >= TILE) continue;
-            const int r = e / T::BM, c = e - r * T::BM;
+            int r, c;
+            if (NATIVE) {
+                const int tile16 = e >> 8, within = e & 255;
+                const int ti = tile16 / (T::BM / 16), tj = tile16 - ti * (T::BM / 16);
+                const int ln = within >> 2, vv = within & 3;
+                r = ti * 16 + 4 * (ln >> 4) + vv;
+                c = tj * 16 + (ln & 15);
+            } else {
+                r = e / T::BM;
+                c = e - r * T::BM;
+            }
             const int u = bi * T::BM + r, v = bj * T::BM + c;
             if (u >= pr.d || v > u) continue;
             // four interleaved running sums (fixed order, so still deterministic) keep loads in flight
@@ -256,8 +270,9 @@ namespace {
 
 struct Cfg { int wt, nw, bm; };
 // the last entry is the wave-unit kernel (syrk_wave.hpp): 144-wide macro tiles, same partial layout as Tile<3,3>
-const Cfg kCfgs[] = {{4, 2, 128}, {3, 3, 144}, {2, 2, 64}, {1, 2, 32}, {0, 0, 144}};
+const Cfg kCfgs[] = {{4, 2, 128}, {3, 3, 144}, {2, 2, 64}, {1, 2, 32}, {0, 0, 144}, {0, 0, 144}};
 constexpr int kWaveCfg = 4;
+constexpr int kConv3Cfg = 5;   // fused 3x3 convolution kernel (syrk_conv3.hpp), same partial layout
 
 bool wave_eligible(const FactorJob &j)
 {
@@ -298,6 +313,7 @@ struct Planned {
     int cfg;
     int nb, nblk, splits, tps;
     int bps;   // blocks per split
+    int unit_rows = 16, rows_per_stage = 0;   // K rows per tile / conv stage; output rows per conv stage
     size_t partial_floats;
 };
 
@@ -311,23 +327,41 @@ void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<
         const Cfg &c = kCfgs[p.cfg];
         p.nb = (jobs[j].d_core + c.bm - 1) / c.bm;
         p.nblk = p.nb * (p.nb + 1) / 2;
+        p.bps = (p.cfg == kWaveCfg || p.cfg == kConv3Cfg) ? wave_blocks_per_split(p.nb) : p.nblk;
+        if (p.cfg == kConv3Cfg) {
+            // K is walked in conv stages of R output rows; count them in units of 16 patch rows
+            p.rows_per_stage = conv3_choose_rows(jobs[j].h, jobs[j].w);
+            p.unit_rows = p.rows_per_stage * jobs[j].w;
+        } else {
+            p.unit_rows = 16;
+        }
         const long ktiles = (jobs[j].K + 15) / 16;
-        p.bps = (p.cfg == kWaveCfg) ? wave_blocks_per_split(p.nb) : p.nblk;
         work += (double)p.bps * (double)ktiles;
     }
     long tpb = (long)std::ceil(work / (double)tu.target_blocks);
     tpb = std::max<long>(tpb, tu.min_tiles_per_split);
-    for (int j : idx) {
-        Planned &p = pl[j];
-        const Cfg &c = kCfgs[p.cfg];
-        const long ktiles = std::max<long>(1, (jobs[j].K + 15) / 16);
-        long tpb_j = tpb;
-        if (p.cfg == kWaveCfg)   // a split's byte range must stay below 2^31 (32-bit buffer offsets)
-            tpb_j = std::max<long>(1, std::min<long>(tpb_j, 0x7fffffffl / (64 * jobs[j].ld) - 1));
-        p.splits = (int)((ktiles + tpb_j - 1) / tpb_j);
-        p.tps = (int)((ktiles + p.splits - 1) / p.splits);
-        p.splits = (int)((ktiles + p.tps - 1) / p.tps);
-        p.partial_floats = (size_t)p.splits * ((size_t)p.nblk * c.bm * c.bm + (size_t)p.nb * c.bm);
+    // Blocks of a launch carry equal work and run about one per CU, so a launch a few blocks over the
+    // target costs a whole extra round: grow the slice until the total fits.
+    for (int iter = 0; iter < 64; ++iter) {
+        long total = 0;
+        for (int j : idx) {
+            Planned &p = pl[j];
+            const Cfg &c = kCfgs[p.cfg];
+            const long ktiles = std::max<long>(1, (jobs[j].K + p.unit_rows - 1) / p.unit_rows);
+            long tpb_j = std::max<long>(1, tpb * 16 / p.unit_rows);
+            if (p.cfg == kWaveCfg)   // a split's byte range must stay below 2^31 (32-bit buffer offsets)
+                tpb_j = std::max<long>(1, std::min<long>(tpb_j, 0x7fffffffl / (64 * jobs[j].ld) - 1));
+            p.splits = (int)((ktiles + tpb_j - 1) / tpb_j);
+            p.tps = (int)((ktiles + p.splits - 1) / p.splits);
+            p.splits = (int)((ktiles + p.tps - 1) / p.tps);
+            p.partial_floats = (size_t)p.splits * ((size_t)p.nblk * c.bm * c.bm + (size_t)p.nb * c.bm);
+            total += (long)p.bps * p.splits;
+        }
+        if (total <= tu.target_blocks || tpb > (1l << 40)) break;
+        bool can_shrink = false;
+        for (int j : idx) can_shrink |= pl[j].splits > 1;
+        if (!can_shrink) break;
+        tpb += std::max<long>(1, tpb / 32);
     }
 }
 
@@ -338,11 +372,12 @@ void plan_all(const FactorJob *jobs, int n, std::vector<Planned> &pl, std::vecto
     pl.assign(n, Planned());
     std::vector<int> keys(n);
     for (int i = 0; i < n; ++i) {
-        pl[i].cfg = wave_eligible(jobs[i]) ? kWaveCfg : choose_cfg(jobs[i].d_core);
+        if (jobs[i].layout == kConv3) pl[i].cfg = kConv3Cfg;
+        else pl[i].cfg = wave_eligible(jobs[i]) ? kWaveCfg : choose_cfg(jobs[i].d_core);
         keys[i] = group_key(jobs[i], pl[i].cfg);
     }
     groups.clear();
-    for (int key = 0; key < 20; ++key) {
+    for (int key = 0; key < 32; ++key) {
         std::vector<int> cur;
         for (int i = 0; i < n; ++i) {
             if (keys[i] != key) continue;
@@ -385,6 +420,8 @@ hipError_t launch_ld(const SyrkTable &tab, int layout, int dt, int blocks, int r
 
 }  // namespace
 
+int conv3_rows(int h, int w) { return conv3_choose_rows(h, w); }
+
 size_t syrk_workspace_bytes(const FactorJob *jobs, int n)
 {
     std::vector<Planned> pl;
@@ -421,7 +458,7 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
             p.partial = reinterpret_cast<float *>(static_cast<char *>(work) + offs[j]);
             p.F = job.F;
             p.K = job.K;
-            p.ld = job.ld;
+            p.ld = (pl[j].cfg == kConv3Cfg) ? conv3_pack(job.h, job.w, pl[j].rows_per_stage) : job.ld;
             p.d = job.d_core;
             p.hw = job.hw > 0 ? job.hw : 1;
             p.ctot = job.ctot;
@@ -443,13 +480,34 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
         }
         const int cfg = pl[g[0]].cfg;
         const int layout = jobs[g[0]].layout, dt = jobs[g[0]].dtype;
-        hipError_t e;
+        hipError_t e = hipSuccess;
         switch (cfg) {
+            case kConv3Cfg: {
+                size_t lds_bytes = 0;
+                for (int k = 0; k < tab.count; ++k) {
+                    const FactorJob &job = jobs[g[k]];
+                    const Conv3Geo geo = conv3_geo(job.h, job.w, pl[g[k]].rows_per_stage);
+                    lds_bytes = std::max(lds_bytes, (size_t)(C3_PRE + C3_NSTAGE * W_SLOTS * geo.slab + 256) * 4);
+                }
+                static bool attr_set = false;
+                if (!attr_set) {
+                    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&syrk_conv3_kernel<4>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+                    if (e != hipSuccess) break;
+                    attr_set = true;
+                }
+                KFAC_LAUNCH(KFAC_K_SYRK, s, (syrk_conv3_kernel<4>), dim3(blocks), dim3(256), lds_bytes, tab);
+                e = hipGetLastError();
+                if (e != hipSuccess) break;
+                KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<3, 3>, true>), dim3(red), dim3(256), 0, tab);
+                e = hipGetLastError();
+                break;
+            }
             case kWaveCfg: {
                 KFAC_LAUNCH(KFAC_K_SYRK, s, syrk_wave_kernel, dim3(blocks), dim3(256), 0, tab);
                 e = hipGetLastError();
                 if (e != hipSuccess) break;
-                KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<3, 3>>), dim3(red), dim3(256), 0, tab);
+                KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<3, 3>, true>), dim3(red), dim3(256), 0, tab);
                 e = hipGetLastError();
                 break;
             }

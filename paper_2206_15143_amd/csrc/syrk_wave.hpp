@@ -205,6 +205,109 @@ __device__ __forceinline__ void wave_loop(const WaveCtx &c, const float *lds, fl
     asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// Which macro tiles the panels of a block hold and which unit each of its four waves owns.
+struct BlockRole {
+    int mac0, mac1, mac2;     // macro index per panel slot
+    int nslots;
+    bool single, owns_colsum;
+    int kind;                 // WaveKind of this wave
+    int rslot, cslot, ctile0; // panel slots of the row / column operand, first column tile
+    int I, J;                 // macro tile this wave writes
+};
+
+__device__ __forceinline__ BlockRole decode_role(int m, int b, int w, bool has_bias)
+{
+    BlockRole r;
+    r.mac0 = r.mac1 = r.mac2 = 0;
+    r.single = false;
+    r.owns_colsum = false;
+    const int nds = (m + 1) / 2;
+    if (b < nds) {
+        const int a = 2 * b;
+        r.owns_colsum = has_bias;
+        if (a + 1 < m) {
+            r.nslots = 2; r.mac0 = a; r.mac1 = a + 1;
+            if (w == 0)      { r.kind = kDiag;  r.rslot = 0; r.cslot = 0; r.ctile0 = 0; r.I = a;     r.J = a; }
+            else if (w == 1) { r.kind = kDiag;  r.rslot = 1; r.cslot = 1; r.ctile0 = 0; r.I = a + 1; r.J = a + 1; }
+            else if (w == 2) { r.kind = kHalf5; r.rslot = 1; r.cslot = 0; r.ctile0 = 0; r.I = a + 1; r.J = a; }
+            else             { r.kind = kHalf4; r.rslot = 1; r.cslot = 0; r.ctile0 = 5; r.I = a + 1; r.J = a; }
+        } else {
+            r.single = true;
+            r.nslots = 3; r.mac0 = r.mac1 = r.mac2 = a;
+            r.kind = kSingle; r.rslot = 0; r.cslot = 0; r.ctile0 = 0; r.I = a; r.J = a;
+        }
+    } else {
+        int q = b - nds, i = 2;
+        while (q >= i / 2) { q -= i / 2; ++i; }
+        const int j = 2 * q;
+        r.nslots = 3; r.mac0 = i; r.mac1 = j; r.mac2 = j + 1;
+        r.rslot = 0; r.I = i;
+        if (w == 0)      { r.kind = kHalf5; r.cslot = 1; r.ctile0 = 0; r.J = j; }
+        else if (w == 1) { r.kind = kHalf4; r.cslot = 1; r.ctile0 = 5; r.J = j; }
+        else if (w == 2) { r.kind = kHalf5; r.cslot = 2; r.ctile0 = 0; r.J = j + 1; }
+        else             { r.kind = kHalf4; r.cslot = 2; r.ctile0 = 5; r.J = j + 1; }
+    }
+    return r;
+}
+
+// After the K loop: single blocks add the four waves' accumulators through LDS (fixed order
+// w1, w2, w3), then every unit stores its partial tiles and the block its column sums.
+// xch: at least 45*4*64 floats of LDS no load is in flight to.
+__device__ __forceinline__ void wave_epilogue(const SyrkProb &pr, const BlockRole &r, int split, int w, int lane,
+                                              int tid, int nrt, float *xch, floatx4 (&acc)[45], float cs0, float cs1)
+{
+    const int m = pr.nb;
+    const int nblk = m * (m + 1) / 2;
+    if (r.single) {
+        for (int q = 1; q < 4; ++q) {
+            __syncthreads();
+            if (w == q) {
+#pragma unroll
+                for (int i = 0; i < 45; ++i)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) xch[(i * 4 + v) * 64 + lane] = acc[i][v];
+            }
+            __syncthreads();
+            if (w == 0) {
+#pragma unroll
+                for (int i = 0; i < 45; ++i)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[i][v] += xch[(i * 4 + v) * 64 + lane];
+            }
+        }
+    }
+    if (!r.single || w == 0) {
+        // tiles go out as they lie in the accumulators: 16 bytes per lane, 1 KB per tile, fully coalesced
+        float *dst = pr.partial + ((long)split * nblk + (r.I * (r.I + 1) / 2 + r.J)) * (W_MT * W_MT);
+        floatx4 *dst4 = reinterpret_cast<floatx4 *>(dst) + lane;
+        if (r.kind == kSingle || r.kind == kDiag) {
+#pragma unroll
+            for (int ti = 0; ti < W_NT; ++ti) {
+                if (ti < nrt) {
+#pragma unroll
+                    for (int tj = 0; tj <= ti; ++tj) dst4[(ti * W_NT + tj) * 64] = acc[ti * (ti + 1) / 2 + tj];
+                }
+            }
+        } else {
+            const int nc = (r.kind == kHalf5) ? 5 : 4;
+#pragma unroll
+            for (int ti = 0; ti < W_NT; ++ti) {
+                if (ti < nrt) {
+#pragma unroll
+                    for (int tj = 0; tj < 5; ++tj) {
+                        if (tj < nc) dst4[(ti * W_NT + r.ctile0 + tj) * 64] = acc[ti * 5 + tj];
+                    }
+                }
+            }
+        }
+    }
+    if (r.owns_colsum && tid < W_MT) {
+        float *csum = pr.partial + (long)pr.splits * nblk * (W_MT * W_MT);
+        csum[((long)split * m + r.mac0) * W_MT + tid] = cs0;
+        if (!r.single) csum[((long)split * m + r.mac1) * W_MT + tid] = cs1;
+    }
+}
+
 __global__ __launch_bounds__(256) void syrk_wave_kernel(const SyrkTable tab)
 {
     __shared__ float lds[W_LDS_FLOATS];
@@ -221,42 +324,13 @@ __global__ __launch_bounds__(256) void syrk_wave_kernel(const SyrkTable tab)
     const int local = blockIdx.x - pr.blk_start;
     const int split = local / nbps;
     const int b = local - split * nbps;
-    const int nds = (m + 1) / 2;
-    const int nblk = m * (m + 1) / 2;
     const int ntiles_last = (pr.d - (m - 1) * W_MT + 15) / 16;   // valid MFMA tiles of the last macro
 
-    // ---- block kind, panel slots, wave role ----
-    int mac0 = 0, mac1 = 0, mac2 = 0;   // macro index per panel slot
+    const BlockRole r = decode_role(m, b, w, pr.has_bias != 0);
     WaveCtx c;
-    c.single = false;
-    c.owns_colsum = false;
-    int kind, I, J;
-    if (b < nds) {
-        const int a = 2 * b;
-        c.owns_colsum = pr.has_bias != 0;
-        if (a + 1 < m) {
-            c.nslots = 2; mac0 = a; mac1 = a + 1;
-            if (w == 0)      { kind = kDiag;  c.rslot = 0; c.cslot = 0; c.ctile0 = 0; I = a;     J = a; }
-            else if (w == 1) { kind = kDiag;  c.rslot = 1; c.cslot = 1; c.ctile0 = 0; I = a + 1; J = a + 1; }
-            else if (w == 2) { kind = kHalf5; c.rslot = 1; c.cslot = 0; c.ctile0 = 0; I = a + 1; J = a; }
-            else             { kind = kHalf4; c.rslot = 1; c.cslot = 0; c.ctile0 = 5; I = a + 1; J = a; }
-        } else {
-            c.single = true;
-            c.nslots = 3; mac0 = mac1 = mac2 = a;
-            kind = kSingle; c.rslot = 0; c.cslot = 0; c.ctile0 = 0; I = a; J = a;
-        }
-    } else {
-        int r = b - nds, i = 2;
-        while (r >= i / 2) { r -= i / 2; ++i; }
-        const int j = 2 * r;
-        c.nslots = 3; mac0 = i; mac1 = j; mac2 = j + 1;
-        c.rslot = 0; I = i;
-        if (w == 0)      { kind = kHalf5; c.cslot = 1; c.ctile0 = 0; J = j; }
-        else if (w == 1) { kind = kHalf4; c.cslot = 1; c.ctile0 = 5; J = j; }
-        else if (w == 2) { kind = kHalf5; c.cslot = 2; c.ctile0 = 0; J = j + 1; }
-        else             { kind = kHalf4; c.cslot = 2; c.ctile0 = 5; J = j + 1; }
-    }
-    const int nrt = (I == m - 1) ? ntiles_last : W_NT;   // valid row tiles of macro I (only the stores look at it)
+    c.single = r.single; c.owns_colsum = r.owns_colsum; c.nslots = r.nslots;
+    c.rslot = r.rslot; c.cslot = r.cslot; c.ctile0 = r.ctile0;
+    const int nrt = (r.I == m - 1) ? ntiles_last : W_NT;   // valid row tiles of macro I (only the stores look at it)
 
     // ---- K range of this split, buffer resource over it ----
     const long ktiles = (pr.K + W_KT - 1) / W_KT;
@@ -286,7 +360,7 @@ __global__ __launch_bounds__(256) void syrk_wave_kernel(const SyrkTable tab)
         const int k = f / W_MT;
         const int col = f - k * W_MT;
         const bool qok = q < W_NT;
-        const int g0 = mac0 * W_MT + col, g1 = mac1 * W_MT + col, g2 = mac2 * W_MT + col;
+        const int g0 = r.mac0 * W_MT + col, g1 = r.mac1 * W_MT + col, g2 = r.mac2 * W_MT + col;
         c.vo[0][qi] = (qok && g0 < ld) ? (unsigned)((k * ld + g0) * 4) : W_OOB;
         c.vo[1][qi] = (qok && g1 < ld) ? (unsigned)((k * ld + g1) * 4) : W_OOB;
         c.vo[2][qi] = (qok && g2 < ld) ? (unsigned)((k * ld + g2) * 4) : W_OOB;
@@ -299,69 +373,12 @@ __global__ __launch_bounds__(256) void syrk_wave_kernel(const SyrkTable tab)
     for (int i = 0; i < 45; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
     float cs0 = 0.f, cs1 = 0.f;
 
-    if (kind == kSingle)     wave_loop<kSingle>(c, lds, acc, cs0, cs1);
-    else if (kind == kDiag)  wave_loop<kDiag>(c, lds, acc, cs0, cs1);
-    else if (kind == kHalf5) wave_loop<kHalf5>(c, lds, acc, cs0, cs1);
-    else                     wave_loop<kHalf4>(c, lds, acc, cs0, cs1);
+    if (r.kind == kSingle)     wave_loop<kSingle>(c, lds, acc, cs0, cs1);
+    else if (r.kind == kDiag)  wave_loop<kDiag>(c, lds, acc, cs0, cs1);
+    else if (r.kind == kHalf5) wave_loop<kHalf5>(c, lds, acc, cs0, cs1);
+    else                       wave_loop<kHalf4>(c, lds, acc, cs0, cs1);
 
-    // ---- single blocks: add the four waves' accumulators through LDS (fixed order w1, w2, w3) ----
-    if (c.single) {
-        float *xch = lds;   // 45 * 4 * 64 floats = 46080 bytes of the (now idle) stage ring
-        for (int r = 1; r < 4; ++r) {
-            __syncthreads();
-            if (w == r) {
-#pragma unroll
-                for (int i = 0; i < 45; ++i)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) xch[(i * 4 + v) * 64 + lane] = acc[i][v];
-            }
-            __syncthreads();
-            if (w == 0) {
-#pragma unroll
-                for (int i = 0; i < 45; ++i)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) acc[i][v] += xch[(i * 4 + v) * 64 + lane];
-            }
-        }
-    }
-
-    // ---- partial tiles out ----
-    if (!c.single || w == 0) {
-        float *dst = pr.partial + ((long)split * nblk + (I * (I + 1) / 2 + J)) * (W_MT * W_MT);
-        const int lr = lane & 15, lk = lane >> 4;
-        if (kind == kSingle || kind == kDiag) {
-#pragma unroll
-            for (int ti = 0; ti < W_NT; ++ti) {
-                if (ti < nrt) {
-#pragma unroll
-                    for (int tj = 0; tj <= ti; ++tj)
-#pragma unroll
-                        for (int v = 0; v < 4; ++v)
-                            dst[(ti * 16 + 4 * lk + v) * W_MT + tj * 16 + lr] = acc[ti * (ti + 1) / 2 + tj][v];
-                }
-            }
-        } else {
-            const int nc = (kind == kHalf5) ? 5 : 4;
-#pragma unroll
-            for (int ti = 0; ti < W_NT; ++ti) {
-                if (ti < nrt) {
-#pragma unroll
-                    for (int tj = 0; tj < 5; ++tj) {
-                        if (tj < nc) {
-#pragma unroll
-                            for (int v = 0; v < 4; ++v)
-                                dst[(ti * 16 + 4 * lk + v) * W_MT + (c.ctile0 + tj) * 16 + lr] = acc[ti * 5 + tj][v];
-                        }
-                    }
-                }
-            }
-        }
-    }
-    if (c.owns_colsum && tid < W_MT) {
-        float *csum = pr.partial + (long)pr.splits * nblk * (W_MT * W_MT);
-        csum[((long)split * m + mac0) * W_MT + tid] = cs0;
-        if (!c.single) csum[((long)split * m + mac1) * W_MT + tid] = cs1;
-    }
+    wave_epilogue(pr, r, split, w, lane, tid, nrt, lds, acc, cs0, cs1);
 }
 
 }  // namespace kfac

@@ -65,6 +65,30 @@ def test_conv_layers(cin, cout, k, stride, pad, h, batch):
     _run_and_check([layer], batch, 3000 + cin * 10 + k, batched=False)
 
 
+@pytest.mark.parametrize("cin,h,batch,bias", [
+    (16, 32, 3, True),     # one macro tile, 4 output rows per stage (the 16-channel CIFAR shape)
+    (16, 16, 5, False),    # no bias
+    (32, 16, 3, True),     # two macro tiles: diagonal block with four different units
+    (48, 8, 5, True),      # three macro tiles: full + single diagonal blocks and a row block
+    (64, 8, 7, True),      # four macro tiles, whole image per stage
+    (16, 28, 2, True),     # W = 28 (ImageNet stage 3 width)
+])
+def test_fused_3x3_conv_factor(cin, h, batch, bias):
+    # 3x3 / stride 1 / pad 1 with C_in a multiple of 16: A is built straight from the NCHW input
+    layer = LayerSpec("conv", cin, 8, 3, 1, 1, h, has_bias=bias)
+    _run_and_check([layer], batch, 7000 + cin + h, batched=True)
+    # same answer as the path through the materialised patch matrix
+    inputs = gu.draw_inputs([layer], batch, 7100, "relu_normal", 0.05)
+    scales = gu.scales_for([layer], batch)
+    fused = gu.run_layers_gpu([layer], batch, inputs, scales, 0.95, 0.03)[0]
+    kf.kfac_tune("fuse_conv3", 0)
+    try:
+        plain = gu.run_layers_gpu([layer], batch, inputs, scales, 0.95, 0.03)[0]
+    finally:
+        kf.kfac_tune("fuse_conv3", 1)
+    assert gu.rel_fro(fused["A"], plain["A"]) < 1e-5
+
+
 def test_im2col_alone_is_bit_exact():
     for (cin, k, stride, pad, h, batch) in [(16, 3, 1, 1, 32, 2), (3, 7, 2, 3, 30, 2), (64, 3, 1, 1, 8, 3),
                                             (12, 1, 2, 0, 10, 2), (200, 3, 1, 1, 7, 1)]:
