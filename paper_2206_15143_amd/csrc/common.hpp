@@ -96,6 +96,8 @@ struct Tuning {
     long syrk_force_bm = 0;          // 0 = choose
     long use_wave_kernel = 1;        // wave-unit SYRK for aligned row-major fp32 operands
     long fuse_conv3 = 1;             // 3x3/s1/p1 fp32 convs: build A straight from the NCHW input
+    long update_bm = 64;             // block tile of the inverse's rank-64 update GEMM (0 = choose; 64 measured best)
+    long gemm_bm = 0;                // block tile of the preconditioning GEMMs (0 = choose)
     long wave_debug = 0;             // measurement only: 1 = skip MFMAs, 2 = skip data loads (results are wrong)
 };
 Tuning &tuning();

@@ -113,6 +113,10 @@ const int kBms[] = {128, 144, 64, 32};
 
 int choose_bm(int M, int N, bool square_lower)
 {
+    const long force = square_lower ? tuning().update_bm : tuning().gemm_bm;
+    if (force)
+        for (int i = 0; i < 4; ++i)
+            if (kBms[i] == force) return i;
     int best = 0;
     double best_cost = 1e300;
     for (int i = 0; i < 4; ++i) {

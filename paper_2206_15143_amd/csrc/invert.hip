@@ -18,7 +18,7 @@
 // pivot block in LDS), sweep_panel_kernel (V = old panel, W = V P, both stored
 // K-major for the MFMA update; new panel written in place), then the rank-nb
 // update through the A^T B GEMM (gemm.hip, mode kSubLowerSkip).
-#include "common.hpp"
+#include "tn_engine.hpp"
 
 #include <algorithm>
 
@@ -62,64 +62,88 @@ __global__ __launch_bounds__(256) void sweep_init_kernel(const InvTable tab)
     }
 }
 
-// Inverts the pivot block of step `tab.step` by an unblocked sweep in LDS.
+// Inverts the pivot block of step `tab.step` by an unblocked sweep.  The 64 x 64 block lives in
+// registers (thread (i, jq) holds S[i][jq + 4m], m = 0..15); per elimination step only the pivot
+// row and column travel through LDS (double buffered), so a step costs one barrier, 17 LDS reads
+// and 16 FMAs per thread.
 __global__ __launch_bounds__(256) void sweep_pivot_kernel(const InvTable tab)
 {
-    __shared__ float S[NB][NB + 1];
+    __shared__ float colb[2][NB];
+    __shared__ float rowb[2][NB];
     const InvProb &pr = tab.p[blockIdx.x];
     const int p0 = tab.step * NB;
     if (p0 >= pr.n) return;
     const int bs = min(NB, pr.n - p0);
     const int tid = threadIdx.x;
-
-    for (int e = tid; e < NB * NB; e += 256) {
-        const int i = e / NB, j = e % NB;
-        float v = (i == j) ? 1.f : 0.f;      // identity padding keeps the tail block well defined
-        if (i < bs && j < bs) {
-            v = (j <= i) ? pr.W[(long)(p0 + i) * pr.n + p0 + j] : pr.W[(long)(p0 + j) * pr.n + p0 + i];
-        }
-        S[i][j] = v;
-    }
     const int i = tid >> 2, jq = tid & 3;
+    const long n = pr.n;
+
+    float s[NB / 4];
+#pragma unroll
+    for (int m = 0; m < NB / 4; ++m) {
+        const int j = jq + 4 * m;
+        float v = (i == j) ? 1.f : 0.f;      // identity padding keeps the tail block well defined
+        if (i < bs && j < bs) v = (j <= i) ? pr.W[(p0 + i) * n + p0 + j] : pr.W[(p0 + j) * n + p0 + i];
+        s[m] = v;
+    }
+    if (jq == 0) colb[0][i] = s[0];
+    if (i == 0) {
+#pragma unroll
+        for (int m = 0; m < NB / 4; ++m) rowb[0][jq + 4 * m] = s[m];
+    }
+    __syncthreads();
+
     int fail = 0;
     for (int k = 0; k < bs; ++k) {
-        __syncthreads();
-        const float p = S[k][k];
+        const int b = k & 1;
+        const float p = rowb[b][k];
         if (!(p > 0.f) && fail == 0) fail = p0 + k + 1;
-        const float ip = 1.0f / p;
-        const float ci = S[i][k];
-        float rk[NB / 4];
-#pragma unroll
-        for (int m = 0; m < NB / 4; ++m) rk[m] = S[k][jq + 4 * m];
-        __syncthreads();
+        const float ip = __builtin_amdgcn_rcpf(p);   // 1 ulp reciprocal: far below the fp32 error of the sweep
+        const float ci = colb[b][i];
+        const bool prow = (i == k);
+        const float cip = ci * ip;
+        // selects instead of branches: the four cases (pivot, pivot row, pivot column, rest) differ per element
 #pragma unroll
         for (int m = 0; m < NB / 4; ++m) {
             const int j = jq + 4 * m;
-            float v;
-            if (i == k)
-                v = (j == k) ? -ip : rk[m] * ip;
-            else if (j == k)
-                v = ci * ip;
-            else
-                v = S[i][j] - (ci * rk[m]) * ip;
-            S[i][j] = v;
+            const float rk = rowb[b][j];
+            const bool pcol = (j == k);
+            const float rest = s[m] - (ci * rk) * ip;
+            const float on_row = pcol ? -ip : rk * ip;
+            const float off_row = pcol ? cip : rest;
+            s[m] = prow ? on_row : off_row;
         }
+        // publish the next pivot column and row
+        const int kn = k + 1;
+        float cv = s[0];
+#pragma unroll
+        for (int m = 1; m < NB / 4; ++m) cv = (m == (kn >> 2)) ? s[m] : cv;
+        if (jq == (kn & 3)) colb[b ^ 1][i] = cv;
+        if (i == kn) {
+#pragma unroll
+            for (int m = 0; m < NB / 4; ++m) rowb[b ^ 1][jq + 4 * m] = s[m];
+        }
+        __syncthreads();
     }
-    __syncthreads();
-    for (int e = tid; e < NB * NB; e += 256) {
-        const int r = e / NB, c = e % NB;
-        const bool in = (r < bs && c < bs);
-        pr.P[e] = in ? -S[r][c] : 0.f;
-        if (in && c <= r) pr.W[(long)(p0 + r) * pr.n + p0 + c] = S[r][c];
+#pragma unroll
+    for (int m = 0; m < NB / 4; ++m) {
+        const int j = jq + 4 * m;
+        const bool in = (i < bs && j < bs);
+        pr.P[i * NB + j] = in ? -s[m] : 0.f;
+        if (in && j <= i) pr.W[(p0 + i) * n + p0 + j] = s[m];
     }
     if (fail != 0 && tid == 0 && *pr.info == 0) *pr.info = fail;
 }
 
-// One workgroup per 64 rows of the panel of step `tab.step`.
+// One workgroup per 64 rows of the panel of step `tab.step`: V = old panel rows (transposed to
+// K-major), W^T = P V^T on the MFMA units (P is symmetric, so it is its own K-major operand), then
+// V^T and W^T go to the workspace for the rank-64 update and W replaces the panel in place.
 __global__ __launch_bounds__(256) void sweep_panel_kernel(const InvTable tab)
 {
-    __shared__ float Ps[NB][NB + 1];
-    __shared__ float Vs[NB][NB + 1];   // [kk][i]
+    typedef Tile<2, 2> T;                          // 64 x 64 output, four waves of 32 x 32
+    constexpr int PITCH = T::PITCH;                // 80: conflict-free K-major operand reads
+    __shared__ float Ps[NB * PITCH];               // [k][m]
+    __shared__ float Vs[NB * PITCH];               // [k][i]
     int pi = 0;
     while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].blk_start) ++pi;
     const InvProb &pr = tab.p[pi];
@@ -141,45 +165,56 @@ __global__ __launch_bounds__(256) void sweep_panel_kernel(const InvTable tab)
         }
         return;
     }
-    for (int e = tid; e < NB * NB; e += 256) Ps[e / NB][e % NB] = pr.P[e];
+    for (int e = tid; e < NB * NB; e += 256) Ps[(e / NB) * PITCH + (e % NB)] = pr.P[e];
     if (i0 > p0) {    // column panel: M[gi][p0 + kk], contiguous in kk
         for (int e = tid; e < NB * NB; e += 256) {
             const int i = e / NB, kk = e % NB;
             const int gi = i0 + i;
-            Vs[kk][i] = (gi < n && kk < bs) ? pr.W[(long)gi * n + p0 + kk] : 0.f;
+            Vs[kk * PITCH + i] = (gi < n && kk < bs) ? pr.W[(long)gi * n + p0 + kk] : 0.f;
         }
     } else {          // row panel: M[p0 + kk][gi], contiguous in gi
         for (int e = tid; e < NB * NB; e += 256) {
             const int kk = e / NB, i = e % NB;
             const int gi = i0 + i;
-            Vs[kk][i] = (gi < n && kk < bs) ? pr.W[(long)(p0 + kk) * n + gi] : 0.f;
+            Vs[kk * PITCH + i] = (gi < n && kk < bs) ? pr.W[(long)(p0 + kk) * n + gi] : 0.f;
         }
     }
     __syncthreads();
-    const int i = tid & 63, kq = tid >> 6;
-    const int gi = i0 + i;
-    float acc[16];
+
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    floatx4 acc[T::WT][T::WT];
 #pragma unroll
-    for (int t = 0; t < 16; ++t) acc[t] = 0.f;
-    for (int m = 0; m < NB; ++m) {
-        const float vm = Vs[m][i];
+    for (int a = 0; a < T::WT; ++a)
 #pragma unroll
-        for (int t = 0; t < 16; ++t) acc[t] += Ps[kq * 16 + t][m] * vm;
-    }
-    if (gi < n) {
+        for (int b = 0; b < T::WT; ++b) acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int t = 0; t < 16; ++t) {
-            const int kk = kq * 16 + t;
-            pr.Vt[(long)kk * pr.ldv + gi] = Vs[kk][i];
-            pr.Wt[(long)kk * pr.ldv + gi] = acc[t];
-            if (kk < bs) {
-                if (i0 > p0)
-                    pr.W[(long)gi * n + p0 + kk] = acc[t];
-                else
-                    pr.W[(long)(p0 + kk) * n + gi] = acc[t];
+    for (int q = 0; q < NB / T::KT; ++q)
+        mma_stage<T, kRows, kRows, false>(Ps + q * T::KT * PITCH, Vs + q * T::KT * PITCH, wm, wn, lane, acc);
+
+    // acc[ti][tj][v] = W^T[m][i], m = (wm*2+ti)*16 + 4*lk + v, i = (wn*2+tj)*16 + lr
+    const int lr = lane & 15, lk = lane >> 4;
+#pragma unroll
+    for (int ti = 0; ti < T::WT; ++ti)
+#pragma unroll
+        for (int tj = 0; tj < T::WT; ++tj) {
+            const int i = (wn * T::WT + tj) * 16 + lr;
+            const int gi = i0 + i;
+            if (gi >= n) continue;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int m = (wm * T::WT + ti) * 16 + 4 * lk + v;
+                const float w = acc[ti][tj][v];
+                pr.Vt[(long)m * pr.ldv + gi] = Vs[m * PITCH + i];
+                pr.Wt[(long)m * pr.ldv + gi] = w;
+                if (m < bs) {
+                    if (i0 > p0)
+                        pr.W[(long)gi * n + p0 + m] = w;
+                    else
+                        pr.W[(long)(p0 + m) * n + gi] = w;
+                }
             }
         }
-    }
 }
 
 // out = -W mirrored to both triangles (in place)

@@ -314,6 +314,7 @@ struct Planned {
     int nb, nblk, splits, tps;
     int bps;   // blocks per split
     int unit_rows = 16, rows_per_stage = 0;   // K rows per tile / conv stage; output rows per conv stage
+    int stretch = 1;                          // relative speed of this problem's blocks per K row
     size_t partial_floats;
 };
 
@@ -335,8 +336,11 @@ void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<
         } else {
             p.unit_rows = 16;
         }
+        // A block that holds a single unit (one macro tile in all) spreads it over its four waves and
+        // needs a quarter of the time per K row: give it four times the rows.
+        p.stretch = ((p.cfg == kWaveCfg || p.cfg == kConv3Cfg) && p.nb == 1) ? 4 : 1;
         const long ktiles = (jobs[j].K + 15) / 16;
-        work += (double)p.bps * (double)ktiles;
+        work += (double)p.bps * (double)ktiles / p.stretch;
     }
     long tpb = (long)std::ceil(work / (double)tu.target_blocks);
     tpb = std::max<long>(tpb, tu.min_tiles_per_split);
@@ -348,7 +352,7 @@ void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<
             Planned &p = pl[j];
             const Cfg &c = kCfgs[p.cfg];
             const long ktiles = std::max<long>(1, (jobs[j].K + p.unit_rows - 1) / p.unit_rows);
-            long tpb_j = std::max<long>(1, tpb * 16 / p.unit_rows);
+            long tpb_j = std::max<long>(1, tpb * p.stretch * 16 / p.unit_rows);
             if (p.cfg == kWaveCfg)   // a split's byte range must stay below 2^31 (32-bit buffer offsets)
                 tpb_j = std::max<long>(1, std::min<long>(tpb_j, 0x7fffffffl / (64 * jobs[j].ld) - 1));
             p.splits = (int)((ktiles + tpb_j - 1) / tpb_j);

@@ -215,25 +215,34 @@ __device__ __forceinline__ void conv3_loop(const Conv3Ctx &c, const Conv3Lanes<N
                 if (KIND == kSingle && 3 * g + s >= c.nst) break;   // past the end of the split: stale rows
                 const float *slabR = buf + ((KIND == kSingle) ? s : c.rslot) * G.slab;
                 const float *slabC = buf + c.cslot * G.slab;
-                int ow = (KIND == kSingle) ? 4 * c.w : 0, ro = 0;
-                while (ow >= G.W) { ow -= G.W; ro += G.Wp; }
+                // position of the k-step inside the stage: column ow, row offset ro (floats); advanced
+                // without branches so that fetches and MFMAs stay in one basic block
+                const int inc_rows = (inc / G.W) * G.Wp, inc_cols = inc % G.W;
+                int ow = ((KIND == kSingle) ? 4 * c.w : 0) % G.W;
+                int ro = (((KIND == kSingle) ? 4 * c.w : 0) / G.W) * G.Wp;
                 auto advance = [&]() {
-                    ow += inc;
-                    while (ow >= G.W) { ow -= G.W; ro += G.Wp; }
+                    ow += inc_cols;
+                    ro += inc_rows;
+                    const bool wrap = ow >= G.W;
+                    ow -= wrap ? G.W : 0;
+                    ro += wrap ? G.Wp : 0;
                 };
-                Conv3Ops A, B;
-                conv3_load<KIND>(A, slabR, slabC, cb, cc, ro + ow);
-                int i = 0;
+                // One copy of the MFMA chain per unit kind (several copies make the compiler shuffle the
+                // 180 accumulator registers between them).  The fetch of the next step is unconditional:
+                // after the last step it reads a little past the stage's rows, still inside the LDS
+                // allocation (next slab or the landing zone), and the values are dropped.  Scheduling
+                // fences keep "13-14 fetches, then 45 MFMAs" as written.
+                Conv3Ops cur, nxt;
+                conv3_load<KIND>(cur, slabR, slabC, cb, cc, ro + ow);
 #pragma unroll 1
-                for (; i + 2 <= steps; i += 2) {
+                for (int i = 0; i < steps; ++i) {
                     advance();
-                    conv3_load<KIND>(B, slabR, slabC, cb, cc, ro + ow);
-                    conv3_mma<KIND>(A, acc);
-                    advance();
-                    if (i + 2 < steps) conv3_load<KIND>(A, slabR, slabC, cb, cc, ro + ow);
-                    conv3_mma<KIND>(B, acc);
+                    conv3_load<KIND>(nxt, slabR, slabC, cb, cc, ro + ow);
+                    __builtin_amdgcn_sched_barrier(0);
+                    conv3_mma<KIND>(cur, acc);
+                    __builtin_amdgcn_sched_barrier(0);
+                    cur = nxt;
                 }
-                if (i < steps) conv3_mma<KIND>(A, acc);
             }
         }
         if (c.owns_colsum && c.tid < G.rows) {
