@@ -507,6 +507,7 @@ int kfac_tune(const char *key, long value)
     else if (k == "wave_debug") t.wave_debug = value;
     else if (k == "fuse_conv3") t.fuse_conv3 = value;
     else if (k == "update_bm") t.update_bm = value;
+    else if (k == "use_small_kernel") t.use_small_kernel = value;
     else if (k == "gemm_bm") t.gemm_bm = value;
     else return 1;
     return 0;

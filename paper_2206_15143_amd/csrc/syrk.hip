@@ -49,6 +49,7 @@ struct SyrkTable {
 
 #include "syrk_wave.hpp"
 #include "syrk_conv3.hpp"
+#include "syrk_small.hpp"
 
 namespace kfac {
 
@@ -270,9 +271,17 @@ namespace {
 
 struct Cfg { int wt, nw, bm; };
 // the last entry is the wave-unit kernel (syrk_wave.hpp): 144-wide macro tiles, same partial layout as Tile<3,3>
-const Cfg kCfgs[] = {{4, 2, 128}, {3, 3, 144}, {2, 2, 64}, {1, 2, 32}, {0, 0, 144}, {0, 0, 144}};
+const Cfg kCfgs[] = {{4, 2, 128}, {3, 3, 144}, {2, 2, 64}, {1, 2, 32}, {0, 0, 144}, {0, 0, 144}, {0, 0, 32}, {0, 0, 64}};
 constexpr int kWaveCfg = 4;
 constexpr int kConv3Cfg = 5;   // fused 3x3 convolution kernel (syrk_conv3.hpp), same partial layout
+constexpr int kSmall32Cfg = 6; // narrow NCHW operands (syrk_small.hpp), partial tile 32 x 32 (d <= 32)
+constexpr int kSmall64Cfg = 7; // same, 64 x 64 (d <= 64)
+
+bool small_eligible(const FactorJob &j)
+{
+    return tuning().use_small_kernel && j.dtype == 0 && j.layout == kNCHW && j.d_core <= 64 && !j.has_bias &&
+           j.hw % 4 == 0;
+}
 
 bool wave_eligible(const FactorJob &j)
 {
@@ -351,7 +360,9 @@ void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<
         for (int j : idx) {
             Planned &p = pl[j];
             const Cfg &c = kCfgs[p.cfg];
-            const long ktiles = std::max<long>(1, (jobs[j].K + p.unit_rows - 1) / p.unit_rows);
+            long ktiles = std::max<long>(1, (jobs[j].K + p.unit_rows - 1) / p.unit_rows);
+            if (p.cfg == kSmall32Cfg || p.cfg == kSmall64Cfg)   // walked in 16-position groups per image
+                ktiles = (jobs[j].K / jobs[j].hw) * ((jobs[j].hw + 15) / 16);
             long tpb_j = std::max<long>(1, tpb * p.stretch * 16 / p.unit_rows);
             if (p.cfg == kWaveCfg)   // a split's byte range must stay below 2^31 (32-bit buffer offsets)
                 tpb_j = std::max<long>(1, std::min<long>(tpb_j, 0x7fffffffl / (64 * jobs[j].ld) - 1));
@@ -377,11 +388,12 @@ void plan_all(const FactorJob *jobs, int n, std::vector<Planned> &pl, std::vecto
     std::vector<int> keys(n);
     for (int i = 0; i < n; ++i) {
         if (jobs[i].layout == kConv3) pl[i].cfg = kConv3Cfg;
+        else if (small_eligible(jobs[i])) pl[i].cfg = jobs[i].d_core <= 32 ? kSmall32Cfg : kSmall64Cfg;
         else pl[i].cfg = wave_eligible(jobs[i]) ? kWaveCfg : choose_cfg(jobs[i].d_core);
         keys[i] = group_key(jobs[i], pl[i].cfg);
     }
     groups.clear();
-    for (int key = 0; key < 32; ++key) {
+    for (int key = 0; key < 40; ++key) {
         std::vector<int> cur;
         for (int i = 0; i < n; ++i) {
             if (keys[i] != key) continue;
@@ -504,6 +516,23 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
                 e = hipGetLastError();
                 if (e != hipSuccess) break;
                 KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<3, 3>, true>), dim3(red), dim3(256), 0, tab);
+                e = hipGetLastError();
+                break;
+            }
+            case kSmall32Cfg:
+            case kSmall64Cfg: {
+                int ntl = 1;
+                for (int k = 0; k < tab.count; ++k) ntl = std::max(ntl, (jobs[g[k]].d_core + 15) / 16);
+                if (ntl == 1) KFAC_LAUNCH(KFAC_K_SYRK, s, (syrk_small_nchw_kernel<1>), dim3(blocks), dim3(256), 0, tab);
+                else if (ntl == 2) KFAC_LAUNCH(KFAC_K_SYRK, s, (syrk_small_nchw_kernel<2>), dim3(blocks), dim3(256), 0, tab);
+                else if (ntl == 3) KFAC_LAUNCH(KFAC_K_SYRK, s, (syrk_small_nchw_kernel<3>), dim3(blocks), dim3(256), 0, tab);
+                else KFAC_LAUNCH(KFAC_K_SYRK, s, (syrk_small_nchw_kernel<4>), dim3(blocks), dim3(256), 0, tab);
+                e = hipGetLastError();
+                if (e != hipSuccess) break;
+                if (cfg == kSmall32Cfg)
+                    KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<1, 2>>), dim3(red), dim3(256), 0, tab);
+                else
+                    KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<2, 2>>), dim3(red), dim3(256), 0, tab);
                 e = hipGetLastError();
                 break;
             }
