@@ -68,19 +68,41 @@ __global__ __launch_bounds__(256) void im2col_kernel(const Im2colTable tab)
     E *slab = reinterpret_cast<E *>(smem);
     int *offs = reinterpret_cast<int *>(smem + ((size_t)(slab_elems + 1) * sizeof(E) + 15) / 16 * 16);
 
-    // ---- stage the input slab (zero halo) ----
+    // ---- stage the input slab (zero halo): one wave per slab row, lanes along x, so the only
+    // integer division is a scalar one per row ----
     const E *xin = reinterpret_cast<const E *>(pr.x) + ((long)n * pr.C + c0) * pr.H * pr.W;
     const int ir_used = (sr - 1) * pr.stride + pr.kh;
-    for (int idx = threadIdx.x; idx < cc * ir_used * pr.WP; idx += 256) {
-        const int c = idx / (ir_used * pr.WP);
-        const int rem = idx - c * (ir_used * pr.WP);
-        const int r = rem / pr.WP;
-        const int xx = rem - r * pr.WP;
-        const int ih = oh0 * pr.stride - pr.pad + r;
-        const int iw = xx - pr.pad;
-        E v = 0;
-        if (ih >= 0 && ih < pr.H && iw >= 0 && iw < pr.W) v = xin[((long)c * pr.H + ih) * pr.W + iw];
-        slab[c * plane + r * pr.WP + xx] = v;
+    // lanes of a wave cover rpp slab rows at a time (rpp = 64 / WP, at least 1), so narrow images
+    // keep all lanes busy; (channel, row) advance incrementally
+    {
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        const int rpp = pr.WP >= 64 ? 1 : 64 / pr.WP;
+        const int lrow = (rpp == 1) ? 0 : lane / pr.WP;
+        const int lx = (rpp == 1) ? lane : lane - lrow * pr.WP;
+        const int nrows = cc * ir_used;
+        const int stride_rows = 4 * rpp;
+        int rowid = wave * rpp + lrow;
+        int c = rowid / ir_used;
+        int r = rowid - c * ir_used;
+        const int dc = stride_rows / ir_used, dr = stride_rows - dc * ir_used;
+        const bool lane_ok = lrow < rpp;
+        for (; rowid < nrows; rowid += stride_rows) {
+            if (lane_ok) {
+                const int ih = oh0 * pr.stride - pr.pad + r;
+                const bool rok = ih >= 0 && ih < pr.H;
+                const E *src = xin + ((long)c * pr.H + ih) * pr.W - pr.pad;
+                E *dst = slab + c * plane + r * pr.WP;
+                for (int xx = lx; xx < pr.WP; xx += 64) {
+                    const int iw = xx - pr.pad;
+                    E v = 0;
+                    if (rok && iw >= 0 && iw < pr.W) v = src[xx];
+                    dst[xx] = v;
+                }
+            }
+            c += dc;
+            r += dr;
+            if (r >= ir_used) { r -= ir_used; ++c; }
+        }
     }
     if (threadIdx.x == 0) slab[slab_elems] = 0;
     for (int col = threadIdx.x; col < ncg * VEC; col += 256) {
@@ -96,15 +118,17 @@ __global__ __launch_bounds__(256) void im2col_kernel(const Im2colTable tab)
     }
     __syncthreads();
 
-    // ---- write the rows ----
+    // ---- write the rows: item idx = (row, 16-byte column group), consecutive threads take
+    // consecutive items; (row, group) and (oh, ow) advance incrementally (no division per item) ----
     E *out = reinterpret_cast<E *>(pr.out);
     const long row0 = ((long)n * pr.Ho + oh0) * pr.Wo;
     const int total = sr * pr.Wo * ncg;
+    const int step_rows = 256 / ncg, step_cg = 256 - step_rows * ncg;
+    int rowl = threadIdx.x / ncg;
+    int cg = threadIdx.x - rowl * ncg;
+    int ohl = rowl / pr.Wo;
+    int ow = rowl - ohl * pr.Wo;
     for (int idx = threadIdx.x; idx < total; idx += 256) {
-        const int rowl = idx / ncg;
-        const int cg = idx - rowl * ncg;
-        const int ohl = rowl / pr.Wo;
-        const int ow = rowl - ohl * pr.Wo;
         const int base = ohl * pr.stride * pr.WP + ow * pr.stride;
         E vals[VEC];
 #pragma unroll
@@ -115,6 +139,13 @@ __global__ __launch_bounds__(256) void im2col_kernel(const Im2colTable tab)
         typename VecOf<E>::type v;
         __builtin_memcpy(&v, vals, sizeof(v));
         *reinterpret_cast<typename VecOf<E>::type *>(out + (row0 + rowl) * pr.ld + col0 + cg * VEC) = v;
+        // next item of this thread: 256 items further
+        cg += step_cg;
+        int dr = step_rows;
+        if (cg >= ncg) { cg -= ncg; ++dr; }
+        rowl += dr;
+        ow += dr;
+        while (ow >= pr.Wo) { ow -= pr.Wo; ++ohl; }
     }
 }
 
@@ -128,14 +159,15 @@ size_t smem_bytes(const Im2colProb &p, int esz)
     return slab + (size_t)(p.CC * p.kh * p.kw + 16) * sizeof(int);
 }
 
-void plan(Im2colProb &p, int esz)
+void plan(Im2colProb &p, int esz, int sr_cap)
 {
     const int vec = 16 / esz;
     const int kk = p.kh * p.kw;
     const int g = vec / gcd(kk, vec);             // CC must be a multiple of g (or the whole of C)
     p.WP = (p.Wo - 1) * p.stride + p.kw;
-    int SR = std::max(1, std::min(p.Ho, (64 + p.Wo - 1) / p.Wo));
-    const size_t budget = 48 * 1024;
+    int SR = std::max(1, std::min(p.Ho, (128 + p.Wo - 1) / p.Wo));
+    if (sr_cap > 0) SR = std::min(SR, sr_cap);
+    const size_t budget = 20 * 1024;   // small slabs: several workgroups per CU overlap their load and store phases
     for (;;) {
         p.SR = SR;
         p.IR = (SR - 1) * p.stride + p.kh;
@@ -154,6 +186,17 @@ void plan(Im2colProb &p, int esz)
     }
     p.nstrips = (p.Ho + p.SR - 1) / p.SR;
     p.nchunks = (p.C + p.CC - 1) / p.CC;
+}
+
+// Shorter strips until the layer alone gives the device a few workgroups per CU.
+void plan_enough_blocks(Im2colProb &p, int esz)
+{
+    plan(p, esz, 0);
+    int cap = p.SR;
+    while ((long)p.B * p.nstrips * p.nchunks < 1024 && cap > 1) {
+        cap = (cap + 1) / 2;
+        plan(p, esz, cap);
+    }
 }
 
 }  // namespace
@@ -184,7 +227,7 @@ hipError_t im2col_launch(const Im2colJob *jobs, int n, hipStream_t s)
             p.x = j.x; p.out = j.out;
             p.B = j.B; p.C = j.C; p.H = j.H; p.W = j.W; p.kh = j.kh; p.kw = j.kw;
             p.stride = j.stride; p.pad = j.pad; p.Ho = j.Ho; p.Wo = j.Wo; p.ld = j.ld;
-            plan(p, dt == 0 ? 4 : 2);
+            plan_enough_blocks(p, dt == 0 ? 4 : 2);
             p.blk_start = blocks;
             blocks += p.B * p.nstrips * p.nchunks;
             smem = std::max(smem, smem_bytes(p, dt == 0 ? 4 : 2));
