@@ -33,6 +33,10 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tune", action="append", default=[], help="development knob key=value")
     ap.add_argument("--seed", type=int, default=2000)
+    ap.add_argument("--traffic", type=float, default=None,
+                    help="HBM bytes per launch of the dominant kernel, from the rocprofv3 --pmc runs "
+                         "(FETCH_SIZE + WRITE_SIZE, scaled by the calibration copy); default: the figure "
+                         "stored in profiles/hbm_traffic_<workload>.txt if that file exists")
     return ap.parse_args()
 
 
@@ -61,6 +65,36 @@ def make_inputs(layers, batch, hp, seed, torch, dev):
         gouts.append(go.contiguous())
         grads.append(torch.randn((l.d_G, l.d_A), generator=g, device=dev))
     return acts, gouts, grads
+
+
+def im2col_leg(kf, torch, step_update, ws_bytes_fn, work, steps):
+    """The patch extractor in its batched launch configuration.  The full update above builds
+    3x3/stride-1 fp32 factors straight from the NCHW input, so on such layers the extractor never
+    runs; here the factor update is repeated with that fusion switched off and the extractor's
+    launches are timed with HIP events (inputs differ per layer, so nothing is reused across launches)."""
+    total = work["im2col_read"] + work["im2col_write"]
+    if not total:
+        return None
+    kf.kfac_tune("fuse_conv3", 0)
+    try:
+        ws = torch.empty(ws_bytes_fn(), dtype=torch.uint8, device="cuda:0")
+        step_update(ws)
+        torch.cuda.synchronize()
+        kf.kfac_timing_enable(True)
+        reps = max(1, steps // 4)
+        for _ in range(reps):
+            step_update(ws)
+        torch.cuda.synchronize()
+        ms, n, _ = kf.kfac_timing_collect()["im2col"]
+        kf.kfac_timing_enable(False)
+    finally:
+        kf.kfac_tune("fuse_conv3", 1)
+    gbs = total * reps / (ms * 1e-3) / 1e9
+    return dict(bound="hbm", kernel="im2col_kernel", achieved=round(gbs, 1), peak=8000.0, unit="GB/s",
+                frac=round(gbs / 8000.0, 4), ms_per_step=round(ms / reps, 4), launches_per_step=n // reps,
+                avg_launch_ms=round(ms / n, 5), algorithmic_bytes_per_step=total,
+                note="factor update repeated with the fused 3x3 path off so that every k>1 conv layer "
+                     "goes through the extractor (grouped launches of up to 20 layers)")
 
 
 def cpu_baseline(config, layers, hp):
@@ -153,23 +187,44 @@ def main():
     kf.kfac_timing_enable(False)
     stages = {k: round(v[0] / args.steps, 4) for k, v in cls.items()}
     launches = {k: v[1] // args.steps for k, v in cls.items()}
-
     in_bytes = 2 if bf else 4
     work = shapes.algorithmic_work(layers, batch, in_bytes)
+    peak = PEAK_FP32_MFMA_TFLOPS   # every factor kernel runs on fp32 MFMA (bf16 inputs are widened on load)
+    # KF-GEMM kernels: per kernel, algorithmic triangle flops (counted by the library per launch) over
+    # the HIP-event time of its launches; the roofline object is the one with the largest share of time
+    names = {"syrk_partial": "syrk_partial_kernel", "syrk_wave": "syrk_wave_kernel",
+             "syrk_conv3": "syrk_conv3_kernel", "syrk_small": "syrk_small_nchw_kernel"}
+    per_kernel = {}
+    for k, kname in names.items():
+        ms, n, flops = cls[k]
+        if n == 0:
+            continue
+        tf = flops / (ms * 1e-3) / 1e12
+        per_kernel[kname] = dict(achieved=round(tf, 2), frac=round(tf / peak, 4), ms_per_step=round(ms / args.steps, 4),
+                                 launches_per_step=n // args.steps,
+                                 avg_launch_ms=round(ms / n, 5), algorithmic_flops_per_step=flops / args.steps)
+    dom = max(per_kernel, key=lambda k: per_kernel[k]["ms_per_step"])
+    d = per_kernel[dom]
+    traffic = args.traffic
+    tfile = os.path.join(ROOT, "profiles", f"hbm_traffic_{args.config}.txt")
+    if traffic is None and os.path.exists(tfile):   # comment lines, then one JSON object {kernel: {...}}
+        with open(tfile) as fh:
+            body = "".join(line for line in fh if not line.startswith("#"))
+        traffic = json.loads(body).get(dom, {}).get("hbm_bytes_per_launch")
+    roofline = dict(bound="mfma", kernel=dom, achieved=d["achieved"], peak=peak, unit="TFLOP/s", frac=d["frac"],
+                    traffic=traffic, launches_per_step=d["launches_per_step"], avg_launch_ms=d["avg_launch_ms"],
+                    algorithmic_flops_per_launch=d["algorithmic_flops_per_step"] / d["launches_per_step"])
     syrk_flops = work["syrk_A"] + work["syrk_G"]
-    syrk_ms, syrk_launches = cls["syrk_partial"][0] / args.steps, launches["syrk_partial"]
+    assert abs(sum(v["algorithmic_flops_per_step"] for v in per_kernel.values()) - syrk_flops) <= 1e-6 * syrk_flops
+    syrk_ms = sum(v["ms_per_step"] for v in per_kernel.values())
     achieved = syrk_flops / (syrk_ms * 1e-3) / 1e12
-    peak = PEAK_FP32_MFMA_TFLOPS   # the factor kernel runs on fp32 MFMA (bf16 inputs are widened on load)
-    roofline = dict(bound="mfma", kernel="syrk_partial_kernel", achieved=round(achieved, 2), peak=peak,
-                    unit="TFLOP/s", frac=round(achieved / peak, 4), traffic=None,
-                    launches_per_step=syrk_launches, avg_launch_ms=round(syrk_ms / max(syrk_launches, 1), 5),
-                    algorithmic_flops_per_step=syrk_flops)
-    im2col_bytes = work["im2col_read"] + work["im2col_write"]
-    extra = {}
-    if im2col_bytes and stages["im2col"] > 0:
-        gbs = im2col_bytes / (stages["im2col"] * 1e-3) / 1e9
-        extra["im2col"] = dict(bound="hbm", achieved=round(gbs, 1), peak=8000.0, unit="GB/s",
-                               frac=round(gbs / 8000.0, 4), algorithmic_bytes_per_step=im2col_bytes)
+    extra = dict(kf_gemm_kernels=per_kernel)
+    im2 = im2col_leg(kf, torch,
+                     lambda w_: kf.kfac_update_factors_batched(descs, acts, gouts, b, h, h, sA, sG, hp["decay"],
+                                                               A_run, G_run, w_),
+                     lambda: kf.kfac_workspace_bytes_batched(descs, b, h, h), work, args.steps)
+    if im2:
+        extra["im2col"] = im2
 
     out = dict(metric=METRIC, value=round(ms_per_step, 4), unit="ms", n_gpus=1, steps=args.steps,
                warmup=args.warmup, ms_per_step=round(ms_per_step, 4), higher_is_better=False, scaling="weak",
@@ -178,6 +233,11 @@ def main():
                            in_dtype=hp["dtype"]),
                kf_gemm_mfma_util_pct=round(100 * achieved / peak, 2),
                stage_ms=stages, launches_per_step=launches, roofline=roofline, **extra)
+    # one plain copy of known size: the launch the byte counters of a rocprofv3 --pmc run are scaled by
+    csrc = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+    cdst = torch.empty_like(csrc)
+    kf.kfac_profile_copy(cdst, csrc, csrc.numel())
+    torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config, layers, hp)
     print(json.dumps(out))

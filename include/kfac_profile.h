@@ -6,6 +6,8 @@
 #ifndef KFAC_PROFILE_H
 #define KFAC_PROFILE_H
 
+#include <stddef.h>
+
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -13,25 +15,36 @@ extern "C" {
 /* Kernel classes the library launches. */
 enum {
     KFAC_K_IM2COL = 0,       /* patch extraction */
-    KFAC_K_SYRK = 1,         /* MFMA X^T X partial tiles (the KF-GEMM) */
+    KFAC_K_SYRK = 1,         /* MFMA X^T X partial tiles (the KF-GEMM), block-tile kernel */
     KFAC_K_SYRK_REDUCE = 2,  /* split reduction + running average epilogue */
     KFAC_K_INV_INIT = 3,
     KFAC_K_INV_PIVOT = 4,
     KFAC_K_INV_PANEL = 5,
     KFAC_K_INV_FINISH = 6,
     KFAC_K_GEMM = 7,         /* A^T B MFMA GEMM (preconditioning and inverse updates) */
-    KFAC_K_COUNT = 8
+    KFAC_K_SYRK_WAVE = 8,    /* KF-GEMM, wave-unit kernel for row-major fp32 operands */
+    KFAC_K_SYRK_CONV3 = 9,   /* KF-GEMM fused with 3x3 patch extraction (reads the NCHW input) */
+    KFAC_K_SYRK_SMALL = 10,  /* KF-GEMM, direct kernel for narrow NCHW operands */
+    KFAC_K_COUNT = 11
 };
 
 /* When enabled, every kernel launch is bracketed by a pair of HIP events
  * recorded on the launch stream (this allocates events; leave it off in
  * production).  Host arrays; returns 0. */
 int kfac_timing_enable(int on);
-/* Waits for the recorded events, ADDS per-class elapsed milliseconds and launch
- * counts into the two host arrays of KFAC_K_COUNT entries and forgets the
- * recorded launches.  Returns 0, or non-zero on a HIP error. */
-int kfac_timing_collect(double *ms_per_class, long *launches_per_class);
+/* Waits for the recorded events, ADDS per-class elapsed milliseconds, launch
+ * counts and algorithmic work into the host arrays of KFAC_K_COUNT entries (any
+ * may be NULL) and forgets the recorded launches.  Work is counted for the
+ * KF-GEMM classes only: sum over the launch's problems of rows * d * (d + 1)
+ * flops (one triangle, d including the bias column).  Returns 0, or non-zero
+ * on a HIP error. */
+int kfac_timing_collect(double *ms_per_class, long *launches_per_class, double *work_per_class);
 const char *kfac_timing_class_name(int cls);
+
+/* Plain device-to-device copy kernel (calib_copy_kernel) of `bytes` bytes (a
+ * multiple of 16; both pointers 16-byte aligned): a launch of known HBM traffic
+ * against which hardware byte counters are scaled.  Returns 0 on success. */
+int kfac_profile_copy(void *d_dst, const void *d_src, size_t bytes, void *hip_stream);
 
 /* Development knob: "target_blocks", "min_tiles_per_split", "patch_chunk_bytes",
  * "syrk_force_bm".  Returns 0 when the key is known.  Changing a knob changes

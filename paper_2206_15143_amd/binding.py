@@ -86,8 +86,10 @@ def load_library():
     lib.kfac_version.argtypes = []; lib.kfac_version.restype = C.c_int
     lib.kfac_tune.argtypes = [C.c_char_p, C.c_long]; lib.kfac_tune.restype = C.c_int
     lib.kfac_timing_enable.argtypes = [C.c_int]; lib.kfac_timing_enable.restype = C.c_int
-    lib.kfac_timing_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_long)]
+    lib.kfac_timing_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_long), C.POINTER(C.c_double)]
     lib.kfac_timing_collect.restype = C.c_int
+    lib.kfac_profile_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.kfac_profile_copy.restype = C.c_int
     lib.kfac_timing_class_name.argtypes = [C.c_int]; lib.kfac_timing_class_name.restype = C.c_char_p
     _lib = lib
     return lib
@@ -150,7 +152,12 @@ def kfac_tune(key: str, value: int) -> None:
         raise KeyError(key)
 
 
-KFAC_K_COUNT = 8
+KFAC_K_COUNT = 11
+
+
+def kfac_profile_copy(dst, src, nbytes: int, stream=None) -> None:
+    if load_library().kfac_profile_copy(_ptr(dst), _ptr(src), C.c_size_t(nbytes), _stream(stream)) != 0:
+        raise RuntimeError("kfac_profile_copy failed")
 
 
 def kfac_timing_enable(on: bool) -> None:
@@ -158,13 +165,16 @@ def kfac_timing_enable(on: bool) -> None:
 
 
 def kfac_timing_collect() -> dict:
-    """{class name: (milliseconds, launches)} accumulated since the last collect."""
+    """{class name: (milliseconds, launches, work)} accumulated since the last collect; work is the
+    algorithmic flop count of the KF-GEMM classes (0 for the others)."""
     lib = load_library()
     ms = (C.c_double * KFAC_K_COUNT)()
     cnt = (C.c_long * KFAC_K_COUNT)()
-    if lib.kfac_timing_collect(ms, cnt) != 0:
+    work = (C.c_double * KFAC_K_COUNT)()
+    if lib.kfac_timing_collect(ms, cnt, work) != 0:
         raise RuntimeError("kfac_timing_collect: HIP event error")
-    return {lib.kfac_timing_class_name(i).decode(): (float(ms[i]), int(cnt[i])) for i in range(KFAC_K_COUNT)}
+    return {lib.kfac_timing_class_name(i).decode(): (float(ms[i]), int(cnt[i]), float(work[i]))
+            for i in range(KFAC_K_COUNT)}
 
 
 def kfac_dim_A(desc: LayerDesc) -> int:

@@ -19,7 +19,7 @@ Tuning &tuning()
 namespace {
 struct TimingState {
     bool on = false;
-    struct Rec { int cls; hipEvent_t a, b; };
+    struct Rec { int cls; hipEvent_t a, b; double work; };
     std::vector<Rec> recs;
     std::vector<hipEvent_t> pool;
     hipEvent_t get()
@@ -41,7 +41,7 @@ void timing_begin(int cls, hipStream_t s)
 {
     TimingState &t = timing();
     if (!t.on) return;
-    TimingState::Rec r{cls, t.get(), t.get()};
+    TimingState::Rec r{cls, t.get(), t.get(), 0.0};
     (void)hipEventRecord(r.a, s);
     t.recs.push_back(r);
 }
@@ -51,6 +51,13 @@ void timing_end(hipStream_t s)
     TimingState &t = timing();
     if (!t.on || t.recs.empty()) return;
     (void)hipEventRecord(t.recs.back().b, s);
+}
+
+void timing_work(double work)
+{
+    TimingState &t = timing();
+    if (!t.on || t.recs.empty()) return;
+    t.recs.back().work = work;
 }
 
 namespace {
@@ -471,7 +478,7 @@ int kfac_timing_enable(int on)
     return 0;
 }
 
-int kfac_timing_collect(double *ms, long *launches)
+int kfac_timing_collect(double *ms, long *launches, double *work)
 {
     auto &t = timing();
     int rc = 0;
@@ -480,6 +487,7 @@ int kfac_timing_collect(double *ms, long *launches)
         if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&e, r.a, r.b) != hipSuccess) rc = 1;
         if (ms) ms[r.cls] += e;
         if (launches) launches[r.cls] += 1;
+        if (work) work[r.cls] += r.work;
         t.pool.push_back(r.a);
         t.pool.push_back(r.b);
     }
@@ -490,8 +498,28 @@ int kfac_timing_collect(double *ms, long *launches)
 const char *kfac_timing_class_name(int cls)
 {
     static const char *names[KFAC_K_COUNT] = {"im2col", "syrk_partial", "syrk_reduce", "inv_init",
-                                              "inv_pivot", "inv_panel", "inv_finish", "gemm_tn"};
+                                              "inv_pivot", "inv_panel", "inv_finish", "gemm_tn",
+                                              "syrk_wave", "syrk_conv3", "syrk_small"};
     return (cls >= 0 && cls < KFAC_K_COUNT) ? names[cls] : "?";
+}
+
+namespace {
+__global__ __launch_bounds__(256) void calib_copy_kernel(float4 *__restrict__ dst, const float4 *__restrict__ src, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+}  // namespace
+
+int kfac_profile_copy(void *d_dst, const void *d_src, size_t bytes, void *hip_stream)
+{
+    if (!d_dst || !d_src || bytes == 0 || bytes % 16 || (reinterpret_cast<uintptr_t>(d_dst) & 15) ||
+        (reinterpret_cast<uintptr_t>(d_src) & 15))
+        return 1;
+    const size_t n = bytes / 16;
+    const int blocks = (int)std::min<size_t>((n + 255) / 256, 256 * 16);
+    hipLaunchKernelGGL(calib_copy_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                       static_cast<float4 *>(d_dst), static_cast<const float4 *>(d_src), n);
+    return hipGetLastError() == hipSuccess ? 0 : 2;
 }
 
 /* Development knob: returns 0 when the key is known. */

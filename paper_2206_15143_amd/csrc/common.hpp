@@ -106,6 +106,7 @@ Tuning &tuning();
 // Optional per-launch HIP-event timing (see include/kfac_profile.h).
 void timing_begin(int cls, hipStream_t s);
 void timing_end(hipStream_t s);
+void timing_work(double work);   // algorithmic work of the launch recorded last
 
 // Launch wrapper: records the event pair when timing is enabled.
 #define KFAC_LAUNCH(cls, stream, kernel, grid, block, smem, ...)               \

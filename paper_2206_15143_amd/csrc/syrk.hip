@@ -414,9 +414,10 @@ bool vec_ok(const FactorJob &j)
 }
 
 template <class T, int LAYOUT, int DT>
-hipError_t launch_cfg(const SyrkTable &tab, int blocks, int red_blocks, hipStream_t s)
+hipError_t launch_cfg(const SyrkTable &tab, int blocks, int red_blocks, double flops, hipStream_t s)
 {
     KFAC_LAUNCH(KFAC_K_SYRK, s, (syrk_partial_kernel<T, LAYOUT, DT>), dim3(blocks), dim3(T::NT), 0, tab);
+    timing_work(flops);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<T>), dim3(red_blocks), dim3(256), 0, tab);
@@ -424,14 +425,14 @@ hipError_t launch_cfg(const SyrkTable &tab, int blocks, int red_blocks, hipStrea
 }
 
 template <class T>
-hipError_t launch_ld(const SyrkTable &tab, int layout, int dt, int blocks, int red_blocks, hipStream_t s)
+hipError_t launch_ld(const SyrkTable &tab, int layout, int dt, int blocks, int red_blocks, double flops, hipStream_t s)
 {
     if (layout == kRows) {
-        if (dt == 0) return launch_cfg<T, kRows, 0>(tab, blocks, red_blocks, s);
-        return launch_cfg<T, kRows, 1>(tab, blocks, red_blocks, s);
+        if (dt == 0) return launch_cfg<T, kRows, 0>(tab, blocks, red_blocks, flops, s);
+        return launch_cfg<T, kRows, 1>(tab, blocks, red_blocks, flops, s);
     }
-    if (dt == 0) return launch_cfg<T, kNCHW, 0>(tab, blocks, red_blocks, s);
-    return launch_cfg<T, kNCHW, 1>(tab, blocks, red_blocks, s);
+    if (dt == 0) return launch_cfg<T, kNCHW, 0>(tab, blocks, red_blocks, flops, s);
+    return launch_cfg<T, kNCHW, 1>(tab, blocks, red_blocks, flops, s);
 }
 
 }  // namespace
@@ -466,9 +467,11 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
         tab.count = (int)g.size();
         tab.debug = (int)tuning().wave_debug;
         int blocks = 0, red = 0;
+        double flops = 0.0;
         for (int k = 0; k < tab.count; ++k) {
             const int j = g[k];
             const FactorJob &job = jobs[j];
+            flops += (double)job.K * (job.d_core + job.has_bias) * (job.d_core + job.has_bias + 1);
             SyrkProb &p = tab.p[k];
             p.x = job.x;
             p.partial = reinterpret_cast<float *>(static_cast<char *>(work) + offs[j]);
@@ -512,7 +515,8 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
                     if (e != hipSuccess) break;
                     attr_set = true;
                 }
-                KFAC_LAUNCH(KFAC_K_SYRK, s, (syrk_conv3_kernel<4>), dim3(blocks), dim3(256), lds_bytes, tab);
+                KFAC_LAUNCH(KFAC_K_SYRK_CONV3, s, (syrk_conv3_kernel<4>), dim3(blocks), dim3(256), lds_bytes, tab);
+                timing_work(flops);
                 e = hipGetLastError();
                 if (e != hipSuccess) break;
                 KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<3, 3>, true>), dim3(red), dim3(256), 0, tab);
@@ -523,10 +527,11 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
             case kSmall64Cfg: {
                 int ntl = 1;
                 for (int k = 0; k < tab.count; ++k) ntl = std::max(ntl, (jobs[g[k]].d_core + 15) / 16);
-                if (ntl == 1) KFAC_LAUNCH(KFAC_K_SYRK, s, (syrk_small_nchw_kernel<1>), dim3(blocks), dim3(256), 0, tab);
-                else if (ntl == 2) KFAC_LAUNCH(KFAC_K_SYRK, s, (syrk_small_nchw_kernel<2>), dim3(blocks), dim3(256), 0, tab);
-                else if (ntl == 3) KFAC_LAUNCH(KFAC_K_SYRK, s, (syrk_small_nchw_kernel<3>), dim3(blocks), dim3(256), 0, tab);
-                else KFAC_LAUNCH(KFAC_K_SYRK, s, (syrk_small_nchw_kernel<4>), dim3(blocks), dim3(256), 0, tab);
+                if (ntl == 1) KFAC_LAUNCH(KFAC_K_SYRK_SMALL, s, (syrk_small_nchw_kernel<1>), dim3(blocks), dim3(256), 0, tab);
+                else if (ntl == 2) KFAC_LAUNCH(KFAC_K_SYRK_SMALL, s, (syrk_small_nchw_kernel<2>), dim3(blocks), dim3(256), 0, tab);
+                else if (ntl == 3) KFAC_LAUNCH(KFAC_K_SYRK_SMALL, s, (syrk_small_nchw_kernel<3>), dim3(blocks), dim3(256), 0, tab);
+                else KFAC_LAUNCH(KFAC_K_SYRK_SMALL, s, (syrk_small_nchw_kernel<4>), dim3(blocks), dim3(256), 0, tab);
+                timing_work(flops);
                 e = hipGetLastError();
                 if (e != hipSuccess) break;
                 if (cfg == kSmall32Cfg)
@@ -537,17 +542,18 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
                 break;
             }
             case kWaveCfg: {
-                KFAC_LAUNCH(KFAC_K_SYRK, s, syrk_wave_kernel, dim3(blocks), dim3(256), 0, tab);
+                KFAC_LAUNCH(KFAC_K_SYRK_WAVE, s, syrk_wave_kernel, dim3(blocks), dim3(256), 0, tab);
+                timing_work(flops);
                 e = hipGetLastError();
                 if (e != hipSuccess) break;
                 KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<3, 3>, true>), dim3(red), dim3(256), 0, tab);
                 e = hipGetLastError();
                 break;
             }
-            case 0: e = launch_ld<Tile<4, 2>>(tab, layout, dt, blocks, red, s); break;
-            case 1: e = launch_ld<Tile<3, 3>>(tab, layout, dt, blocks, red, s); break;
-            case 2: e = launch_ld<Tile<2, 2>>(tab, layout, dt, blocks, red, s); break;
-            default: e = launch_ld<Tile<1, 2>>(tab, layout, dt, blocks, red, s); break;
+            case 0: e = launch_ld<Tile<4, 2>>(tab, layout, dt, blocks, red, flops, s); break;
+            case 1: e = launch_ld<Tile<3, 3>>(tab, layout, dt, blocks, red, flops, s); break;
+            case 2: e = launch_ld<Tile<2, 2>>(tab, layout, dt, blocks, red, flops, s); break;
+            default: e = launch_ld<Tile<1, 2>>(tab, layout, dt, blocks, red, flops, s); break;
         }
         if (e != hipSuccess) return e;
     }
