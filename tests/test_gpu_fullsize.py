@@ -62,51 +62,67 @@ def test_resnet110_config_batched_full_size():
         assert abs(g["A"][-1, -1] - corner) <= 1e-6 * corner
 
 
-def test_resnet50_config_distinct_shapes_full_size():
-    name = "resnet50_imagenet"
+FULL_SIZE_CONFIGS = [("resnet50_imagenet", 24), ("resnet50_imagenet_bf16", 24), ("transformer_encoder_bf16", 3)]
+
+
+def _distinct(name):
+    return list(Counter(shapes.config_layers(name)).keys())
+
+
+def _shape_cases():
+    cases = []
+    for name, n in FULL_SIZE_CONFIGS:
+        d = _distinct(name)
+        assert len(d) == n, (name, len(d))
+        cases += [pytest.param(name, i, id=f"{name}-{i}") for i in range(n)]
+    return cases
+
+
+@pytest.mark.parametrize("name,i", _shape_cases())
+def test_distinct_shapes_full_size(name, i):
+    """Every distinct layer shape of the ResNet-50-shaped (fp32 B=32, bf16 B=64) and transformer-shaped
+    (bf16, 4096 token rows) workloads at full size, through the batched entry points."""
     hp = shapes.config_hparams(name)
     batch = hp["batch"]
     lam = hp["damping"]
     std = hp["gout_var"] ** 0.5
-    distinct = list(Counter(shapes.config_layers(name)).keys())
-    assert len(distinct) == 24
-    gen = np.random.default_rng(3)
-    for i, l in enumerate(distinct):
-        print(f"shape {i}: {l}", flush=True)
-        inp = rng.layer_inputs(l, batch, 3000 + i, hp["act"], std)
-        sc = shapes.layer_scales(l, batch)
-        g = gu.run_layers_gpu([l], batch, [inp], [sc], hp["decay"], lam, batched=True)[0]
-        assert list(g["info"]) == [0, 0]
-        abar, grow = orc.layer_rows(l, inp[0], inp[1])
-        small = l.d_A <= 600
-        if small:
-            ref = gu.run_layer_oracle(l, inp, sc, hp["decay"], lam)
-            errs = gu.check_layer(g, ref, tag=str(l))
-            print({k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
-            continue
-        # sampled entries of both factors, straight from the definition
-        for F, X, s, d in ((g["A"], abar, sc[0], l.d_A), (g["G"], grow, sc[1], l.d_G)):
-            us = np.concatenate([gen.integers(0, d, 40), [d - 1, d - 1, 0]])
-            vs = np.concatenate([gen.integers(0, d, 40), [d - 1, 0, 0]])
-            ref = np.array([orc.running_average(np.array([[1.0 if u == v else 0.0]]),
-                                                np.array([[orc.factor_entry(X, s, int(u), int(v))]]),
-                                                hp["decay"])[0, 0] for u, v in zip(us, vs)])
-            got = F[us, vs].astype(np.float64)
-            assert np.linalg.norm(got - ref) / np.linalg.norm(ref) < 1e-4
-            assert np.array_equal(F, F.T)
-        # trace of the new A factor = scale * ||abar||_F^2 (cheap at any size)
-        tr_new = (np.trace(g["A"].astype(np.float64)) - hp["decay"] * l.d_A) / (1 - hp["decay"])
-        assert abs(tr_new - sc[0] * (abar ** 2).sum()) <= 1e-4 * tr_new
-        del abar, grow
-        for F, X in ((g["A"], g["A_inv"]), (g["G"], g["G_inv"])):
-            assert np.array_equal(X, X.T)
-            if F.shape[0] <= 2400:
-                assert gu.rel_fro(X, orc.inverse(F.astype(np.float64), lam)) < 1e-4
-            else:
-                # X - M^-1 = M^-1 (M X - I) and M >= (decay + lam) I for a running average started at
-                # the identity, so ||X - M^-1||_F <= ||M X - I||_F / (decay + lam)
-                bound = _residual(F, X, lam) / (hp["decay"] + lam)
-                assert bound / np.linalg.norm(X.astype(np.float64)) < 1e-4
-        Pref = orc.precondition(g["G_inv"].astype(np.float64), inp[2].astype(np.float64),
-                                g["A_inv"].astype(np.float64))
-        assert gu.rel_fro(g["P"], Pref) < 1e-3
+    dtype = hp["dtype"]
+    l = _distinct(name)[i]
+    gen = np.random.default_rng(3 + i)
+    print(f"{name} shape {i}: {l}", flush=True)
+    inp = rng.layer_inputs(l, batch, 1000 * hp["index"] + 500 + i, hp["act"], std, dtype)
+    sc = shapes.layer_scales(l, batch)
+    g = gu.run_layers_gpu([l], batch, [inp], [sc], hp["decay"], lam, dtype=dtype, batched=True)[0]
+    assert list(g["info"]) == [0, 0]
+    abar, grow = orc.layer_rows(l, inp[0], inp[1])
+    if l.d_A <= 300 or (l.d_A <= 600 and l.n_rows(batch) <= 110000):
+        ref = gu.run_layer_oracle(l, inp, sc, hp["decay"], lam)
+        errs = gu.check_layer(g, ref, tag=str(l))
+        print({k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+        return
+    # sampled entries of both factors, straight from the definition
+    for F, X, s, d in ((g["A"], abar, sc[0], l.d_A), (g["G"], grow, sc[1], l.d_G)):
+        us = np.concatenate([gen.integers(0, d, 40), [d - 1, d - 1, 0]])
+        vs = np.concatenate([gen.integers(0, d, 40), [d - 1, 0, 0]])
+        ref = np.array([orc.running_average(np.array([[1.0 if u == v else 0.0]]),
+                                            np.array([[orc.factor_entry(X, s, int(u), int(v))]]),
+                                            hp["decay"])[0, 0] for u, v in zip(us, vs)])
+        got = F[us, vs].astype(np.float64)
+        assert np.linalg.norm(got - ref) / np.linalg.norm(ref) < 1e-4
+        assert np.array_equal(F, F.T)
+    # trace of the new A factor = scale * ||abar||_F^2 (cheap at any size)
+    tr_new = (np.trace(g["A"].astype(np.float64)) - hp["decay"] * l.d_A) / (1 - hp["decay"])
+    assert abs(tr_new - sc[0] * (abar ** 2).sum()) <= 1e-4 * tr_new
+    del abar, grow
+    for F, X in ((g["A"], g["A_inv"]), (g["G"], g["G_inv"])):
+        assert np.array_equal(X, X.T)
+        if F.shape[0] <= 1300:
+            assert gu.rel_fro(X, orc.inverse(F.astype(np.float64), lam)) < 1e-4
+        else:
+            # X - M^-1 = M^-1 (M X - I) and M >= (decay + lam) I for a running average started at
+            # the identity, so ||X - M^-1||_F <= ||M X - I||_F / (decay + lam)
+            bound = _residual(F, X, lam) / (hp["decay"] + lam)
+            assert bound / np.linalg.norm(X.astype(np.float64)) < 1e-4
+    Pref = orc.precondition(g["G_inv"].astype(np.float64), inp[2].astype(np.float64),
+                            g["A_inv"].astype(np.float64))
+    assert gu.rel_fro(g["P"], Pref) < 1e-3

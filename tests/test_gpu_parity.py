@@ -89,9 +89,33 @@ def test_fused_3x3_conv_factor(cin, h, batch, bias):
     assert gu.rel_fro(fused["A"], plain["A"]) < 1e-5
 
 
+@pytest.mark.parametrize("cout,h,batch", [
+    (16, 8, 5),      # one 16-tile, HW = 64
+    (32, 6, 7),      # HW = 36: a multiple of 4 but not of 16 (ragged last k-group of every image)
+    (48, 10, 3),     # three tiles (d between the 32 and 64 instances), HW = 100
+    (64, 8, 9),      # four tiles
+    (40, 4, 6),      # d not a multiple of 16, HW = 16
+    (24, 7, 4),      # HW = 49 is not a multiple of 4: the block-tile kernel takes it
+])
+def test_narrow_nchw_output_gradient_factor(cout, h, batch):
+    # G of a conv layer with few output channels: read from NCHW by the direct (no-LDS) kernel
+    layer = LayerSpec("conv", 4, cout, 3, 1, 1, h)
+    _run_and_check([layer], batch, 7500 + cout + h, batched=True)
+    inputs = gu.draw_inputs([layer], batch, 7600, "relu_normal", 0.05)
+    scales = gu.scales_for([layer], batch)
+    direct = gu.run_layers_gpu([layer], batch, inputs, scales, 0.95, 0.03)[0]
+    kf.kfac_tune("use_small_kernel", 0)
+    try:
+        tiled = gu.run_layers_gpu([layer], batch, inputs, scales, 0.95, 0.03)[0]
+    finally:
+        kf.kfac_tune("use_small_kernel", 1)
+    assert gu.rel_fro(direct["G"], tiled["G"]) < 1e-5
+
+
 def test_im2col_alone_is_bit_exact():
     for (cin, k, stride, pad, h, batch) in [(16, 3, 1, 1, 32, 2), (3, 7, 2, 3, 30, 2), (64, 3, 1, 1, 8, 3),
-                                            (12, 1, 2, 0, 10, 2), (200, 3, 1, 1, 7, 1)]:
+                                            (12, 1, 2, 0, 10, 2), (200, 3, 1, 1, 7, 1), (5, 3, 1, 1, 70, 1),
+                                            (6, 5, 2, 2, 33, 2), (2, 3, 1, 0, 9, 3)]:
         print("im2col", cin, k, stride, pad, h, batch, flush=True)
         x = rng.draw_relu_normal(77, 0, (batch, cin, h, h))
         desc = kf.LayerDesc.conv2d(cin, 4, k, stride, pad)
