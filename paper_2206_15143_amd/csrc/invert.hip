@@ -18,9 +18,10 @@
 // pivot block in LDS), sweep_panel_kernel (V = old panel, W = V P, both stored
 // K-major for the MFMA update; new panel written in place), then the rank-nb
 // update through the A^T B GEMM (gemm.hip, mode kSubLowerSkip).
-#include "tn_engine.hpp"
+#include "invert_fused.hpp"
 
 #include <algorithm>
+#include <vector>
 
 namespace kfac {
 
@@ -236,29 +237,107 @@ __global__ __launch_bounds__(256) void sweep_finish_kernel(const InvTable tab)
 }
 
 namespace {
-size_t job_ws_floats(int n) { return (size_t)NB * NB + 2 * (size_t)NB * ((n + 3) / 4 * 4); }
+size_t job_ws_floats(int n) { return 2 * (size_t)NB * NB + 2 * (size_t)NB * ((n + 3) / 4 * 4); }
+size_t table_bytes(int n) { return align_up((size_t)n * sizeof(InvProbF), 256); }
+
+// One-launch-per-step sweep for the matrices listed in `idx` (sorted by order, largest first).
+hipError_t fused_launch(const InvertJob *jobs, const std::vector<int> &idx, const std::vector<size_t> &offs,
+                        void *work, InvProbF *dtab, hipStream_t s)
+{
+    const int total = (int)idx.size();
+    // descriptors -> device table, 64 per upload launch
+    for (int g0 = 0; g0 < total; g0 += 64) {
+        InvUpload u;
+        u.dst = dtab + g0;
+        u.count = std::min(64, total - g0);
+        for (int k = 0; k < u.count; ++k) {
+            const InvertJob &j = jobs[idx[g0 + k]];
+            InvProbF &p = u.p[k];
+            float *ws = reinterpret_cast<float *>(static_cast<char *>(work) + offs[idx[g0 + k]]);
+            p.M = j.M; p.W = j.Minv; p.info = j.info; p.n = j.n; p.damping = j.damping;
+            p.ldv = (j.n + 3) / 4 * 4;
+            p.nblk = (j.n + FNB - 1) / FNB;
+            p.P = ws;
+            p.Vt = ws + 2 * FNB * FNB;
+        }
+        KFAC_LAUNCH(KFAC_K_INV_INIT, s, inv_upload_kernel, dim3(1), dim3(64), 0, u);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    // classes of equal order, in sequences of at most kMaxInvClasses
+    int c0 = 0;
+    while (c0 < total) {
+        InvSeq q;
+        q.tab = dtab;
+        q.nclass = 0;
+        q.step = 0;
+        int c = c0;
+        while (c < total && q.nclass < kMaxInvClasses) {
+            int e = c;
+            while (e < total && jobs[idx[e]].n == jobs[idx[c]].n) ++e;
+            InvClass &k = q.c[q.nclass++];
+            k.first = c; k.count = e - c; k.n = jobs[idx[c]].n; k.nblk = (k.n + FNB - 1) / FNB;
+            k.per = 0; k.blk_start = 0;
+            c = e;
+        }
+        c0 = c;
+        auto lay_out = [&](InvSeq &t, int nclass, auto per_fn) {
+            long blocks = 0;
+            t.nclass = nclass;
+            for (int k = 0; k < nclass; ++k) {
+                t.c[k].per = per_fn(t.c[k]);
+                t.c[k].blk_start = (int)blocks;
+                blocks += (long)t.c[k].per * t.c[k].count;
+            }
+            return blocks;
+        };
+        const int nclass = q.nclass;
+        long blocks = 0;
+        hipError_t e = hipSuccess;
+        blocks = lay_out(q, nclass, [](const InvClass &) { return 1; });
+        KFAC_LAUNCH(KFAC_K_INV_PIVOT, s, fsweep_pivot0_kernel, dim3((unsigned)blocks), dim3(256), 0, q);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        const int steps = q.c[0].nblk;   // classes are sorted: the first is the largest
+        for (int st = 0; st < steps && steps > 1; ++st) {
+            int active = 0;
+            while (active < nclass && q.c[active].nblk > st && q.c[active].nblk > 1) ++active;
+            if (active == 0) break;
+            q.step = st;
+            blocks = lay_out(q, active, [](const InvClass &k) { return k.nblk * (k.nblk + 1) / 2; });
+            if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
+            KFAC_LAUNCH(KFAC_K_INV_STEP, s, fsweep_step_kernel, dim3((unsigned)blocks), dim3(256), 0, q);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+    }
+    return hipSuccess;
+}
 }  // namespace
 
 size_t invert_workspace_bytes(const InvertJob *jobs, int n)
 {
-    size_t total = 0;
+    size_t total = table_bytes(n);
     for (int i = 0; i < n; ++i) total += align_up(job_ws_floats(jobs[i].n) * sizeof(float), 256);
     return total;
 }
 
-hipError_t invert_launch(const InvertJob *jobs, int n, void *work, size_t work_bytes, hipStream_t s)
+hipError_t invert_launch(const InvertJob *jobs, int n_all, void *work, size_t work_bytes, hipStream_t s)
 {
-    if (invert_workspace_bytes(jobs, n) > work_bytes) return hipErrorInvalidValue;
-    // largest matrices first so that one launch group holds similar step counts
-    std::vector<int> order(n);
-    for (int i = 0; i < n; ++i) order[i] = i;
-    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return jobs[a].n > jobs[b].n; });
-    std::vector<size_t> offs(n);
-    size_t off = 0;
-    for (int i = 0; i < n; ++i) {
+    if (invert_workspace_bytes(jobs, n_all) > work_bytes) return hipErrorInvalidValue;
+    std::vector<size_t> offs(n_all);
+    size_t off = table_bytes(n_all);
+    for (int i = 0; i < n_all; ++i) {
         offs[i] = off;
         off += align_up(job_ws_floats(jobs[i].n) * sizeof(float), 256);
     }
+    // largest matrices first so that one launch group holds similar step counts
+    std::vector<int> order, fused;
+    for (int i = 0; i < n_all; ++i) (jobs[i].n <= tuning().invert_fused_max_n ? fused : order).push_back(i);
+    auto by_size = [&](int a, int b) { return jobs[a].n > jobs[b].n; };
+    std::stable_sort(order.begin(), order.end(), by_size);
+    std::stable_sort(fused.begin(), fused.end(), by_size);
+    const int n = (int)order.size();
 
     for (int g0 = 0; g0 < n; g0 += kMaxProblems) {
         const int cnt = std::min(kMaxProblems, n - g0);
@@ -336,6 +415,8 @@ hipError_t invert_launch(const InvertJob *jobs, int n, void *work, size_t work_b
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
+    if (!fused.empty())
+        return fused_launch(jobs, fused, offs, work, static_cast<InvProbF *>(work), s);
     return hipSuccess;
 }
 

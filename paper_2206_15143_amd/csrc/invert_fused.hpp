@@ -1,0 +1,406 @@
+// One-launch-per-step form of the blocked symmetric sweep (see invert.hip for
+// the method), for the small and medium factors where the three-kernel step
+// (pivot, panel, update) is bound by launch latency and by the serial pivot
+// block inversion rather than by flops.
+//
+// Step K of the sweep is ONE launch over all lower-triangular 64 x 64 tiles of
+// all matrices that are still active:
+//   - a tile in the pivot row/column (panel tile) computes W = V P and stores
+//     it in place;
+//   - any other tile (i, j) loads V_i and V_j, forms W_i = V_i P on the MFMA
+//     units again (cheaper than a launch that would share it) and applies
+//     M_ij -= W_i V_j^T;
+//   - tiles in row/column K+1 also store their new values K-major into the
+//     side buffer V' that step K+1 reads (so the panel is never read from the
+//     matrix while panel tiles overwrite it);
+//   - the workgroup of tile (K+1, K+1) goes on to invert that block, which is
+//     final for step K+1 once updated: P' and the in-place block are ready
+//     when the launch ends.  That tile gets block index 0 of its matrix so
+//     that it starts first.
+// Step 0 reads the input factor (plus damping) instead of the working matrix and
+// the last step of a matrix stores the negated result to both triangles, so
+// there is no initialisation or finishing pass.
+// P and V are double buffered by step parity.  Problem descriptors live in
+// device memory (uploaded by a small kernel from kernel arguments), so one
+// launch covers any number of matrices; the launch argument only carries the
+// table of distinct sizes.
+#pragma once
+
+#include "tn_engine.hpp"
+
+namespace kfac {
+
+constexpr int FNB = 64;            // pivot block order
+constexpr int kMaxInvClasses = 24; // distinct matrix orders per launch sequence
+
+struct InvProbF {
+    const float *M;   // input factor [n, n], lower triangle read
+    float *W;         // working matrix = output [n, n]
+    float *P;         // 2 x [64, 64] pivot-block inverses (step parity)
+    float *Vt;        // 2 x [64, ldv] K-major panels (step parity)
+    int *info;
+    int n;
+    int ldv;          // n rounded up to 4
+    float damping;
+    int nblk;
+};
+
+struct InvUpload {
+    InvProbF *dst;
+    int count;
+    InvProbF p[64];
+};
+
+struct InvClass {
+    int first;       // index of the first problem of this class in the device table
+    int count;       // problems in the class
+    int n, nblk;
+    int per;         // blocks per problem in this launch
+    int blk_start;   // first block of the class in this launch
+};
+
+struct InvSeq {
+    const InvProbF *tab;
+    int nclass;
+    int step;
+    InvClass c[kMaxInvClasses];
+};
+
+__global__ __launch_bounds__(64) void inv_upload_kernel(const InvUpload u)
+{
+    // plain vector stores of the descriptors into the device table
+    const int words = (int)(sizeof(InvProbF) / 4);
+    const unsigned *src = reinterpret_cast<const unsigned *>(u.p);
+    unsigned *dst = reinterpret_cast<unsigned *>(u.dst);
+    for (int e = threadIdx.x + blockIdx.x * 64; e < u.count * words; e += 64 * gridDim.x) dst[e] = src[e];
+}
+
+__device__ __forceinline__ bool seq_locate(const InvSeq &q, int blk, int &prob, int &local, int &ci)
+{
+    ci = 0;
+    while (ci + 1 < q.nclass && blk >= q.c[ci + 1].blk_start) ++ci;
+    const InvClass &c = q.c[ci];
+    const int off = blk - c.blk_start;
+    const int pl = off / c.per;
+    if (pl >= c.count) return false;
+    prob = c.first + pl;
+    local = off - pl * c.per;
+    return true;
+}
+
+// Unblocked sweep of a 64 x 64 block held in registers: thread (i = tid >> 2, jq = tid & 3) owns
+// S[i][jq + 4m], m = 0..15.  Per elimination step only the pivot row and column travel through LDS
+// (double buffered): one barrier, five LDS reads and ~50 VALU operations per thread.  The step
+// index is a compile-time constant after unrolling, so the pivot-column fix-up and the publication
+// of the next row/column need no dynamic register indexing.  Blocks smaller than 64 are padded
+// with the identity by the caller; the padded pivots are 1 and change nothing.
+// colb: [2][64]; rowb: [2][4][16] (row k stored as rowb[jq][m] = S[k][jq + 4m]).
+// Returns 0 or the 1-based index (within the block) of the first non-positive pivot.
+__device__ __forceinline__ int sweep64(float (&s)[16], float *colb, float *rowb, int tid)
+{
+    const int i = tid >> 2, jq = tid & 3;
+    if (jq == 0) colb[i] = s[0];
+    if (i == 0) {
+#pragma unroll
+        for (int m = 0; m < 16; ++m) rowb[jq * 16 + m] = s[m];
+    }
+    __syncthreads();
+    int fail = 0;
+#pragma unroll
+    for (int k = 0; k < FNB; ++k) {
+        const int b = k & 1;
+        const float *rb = rowb + b * 64;
+        const float p = rb[(k & 3) * 16 + (k >> 2)];
+        if (!(p > 0.f) && fail == 0) fail = k + 1;
+        const float ip = __builtin_amdgcn_rcpf(p);   // 1 ulp reciprocal: far below the fp32 error of the sweep
+        const float ci = colb[b * 64 + i];
+        const float cip = ci * ip;
+        const bool prow = (i == k);
+        float rk[16];
+#pragma unroll
+        for (int m4 = 0; m4 < 4; ++m4) {
+            const floatx4 v = *reinterpret_cast<const floatx4 *>(rb + jq * 16 + 4 * m4);
+            rk[4 * m4 + 0] = v.x; rk[4 * m4 + 1] = v.y; rk[4 * m4 + 2] = v.z; rk[4 * m4 + 3] = v.w;
+        }
+#pragma unroll
+        for (int m = 0; m < 16; ++m) {
+            const float upd = __builtin_fmaf(-cip, rk[m], s[m]);
+            const float onr = rk[m] * ip;
+            s[m] = prow ? onr : upd;
+        }
+        // pivot column (j == k): -1/p on the pivot itself, c/p elsewhere
+        if (jq == (k & 3)) s[k >> 2] = prow ? -ip : cip;
+        if (k + 1 < FNB) {
+            const int kn = k + 1;
+            if (jq == (kn & 3)) colb[(b ^ 1) * 64 + i] = s[kn >> 2];
+            if (i == kn) {
+                float *wb = rowb + (b ^ 1) * 64 + jq * 16;
+#pragma unroll
+                for (int m4 = 0; m4 < 4; ++m4)
+                    *reinterpret_cast<floatx4 *>(wb + 4 * m4) =
+                        floatx4{s[4 * m4], s[4 * m4 + 1], s[4 * m4 + 2], s[4 * m4 + 3]};
+            }
+            __syncthreads();
+        }
+    }
+    return fail;
+}
+
+// Inverse of the first pivot block (one workgroup per matrix).
+__global__ __launch_bounds__(256) void fsweep_pivot0_kernel(const InvSeq q)
+{
+    __shared__ float colb[2 * 64];
+    __shared__ __attribute__((aligned(16))) float rowb[2 * 64];
+    int prob, local, ci;
+    if (!seq_locate(q, blockIdx.x, prob, local, ci)) return;
+    const InvProbF pr = q.tab[prob];
+    const int tid = threadIdx.x;
+    const int i = tid >> 2, jq = tid & 3;
+    const int bs = min(FNB, pr.n);
+    const long n = pr.n;
+    float s[16];
+#pragma unroll
+    for (int m = 0; m < 16; ++m) {
+        const int j = jq + 4 * m;
+        float v = (i == j) ? 1.f : 0.f;
+        if (i < bs && j < bs) {
+            const int a = max(i, j), b = min(i, j);
+            v = pr.M[a * n + b] + (a == b ? pr.damping : 0.f);
+        }
+        s[m] = v;
+    }
+    const int fail = sweep64(s, colb, rowb, tid);
+    const bool whole = pr.nblk == 1;   // the block is the matrix: store the result itself, both triangles
+#pragma unroll
+    for (int m = 0; m < 16; ++m) {
+        const int j = jq + 4 * m;
+        const bool in = (i < bs && j < bs);
+        pr.P[i * FNB + j] = in ? -s[m] : 0.f;
+        if (in && j <= i) {
+            pr.W[i * n + j] = whole ? -s[m] : s[m];
+            if (whole) pr.W[j * n + i] = -s[m];
+        }
+    }
+    if (tid == 0) *pr.info = (fail <= bs) ? fail : 0;
+}
+
+// One step of the sweep for every tile of every active matrix (see the header of this file).
+__global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
+{
+    typedef Tile<2, 2> T;
+    constexpr int PITCH = T::PITCH;   // 80
+    __shared__ __attribute__((aligned(16))) float Ps[FNB * PITCH];   // P, then W^T
+    __shared__ __attribute__((aligned(16))) float Va[FNB * PITCH];   // V of the tile's row block (or the panel block)
+    __shared__ __attribute__((aligned(16))) float Vb[FNB * PITCH];   // V of the tile's column block
+    __shared__ float colb[2 * 64];
+    __shared__ __attribute__((aligned(16))) float rowb[2 * 64];
+
+    int prob, t, ci;
+    if (!seq_locate(q, blockIdx.x, prob, t, ci)) return;
+    const InvProbF pr = q.tab[prob];
+    const int K = q.step, K1 = K + 1;
+    const int nblk = pr.nblk;
+    if (K >= nblk) return;
+    int bi, bj;
+    tri_decode(t, bi, bj);
+    if (K1 < nblk) {   // the next pivot tile takes block 0 and gives tile (0, 0) its own slot
+        const int tp = K1 * (K1 + 1) / 2 + K1;
+        if (t == 0) { bi = K1; bj = K1; }
+        else if (t == tp) { bi = 0; bj = 0; }
+    }
+    const int tid = threadIdx.x;
+    const int n = pr.n, ldv = pr.ldv;
+    const bool first = (K == 0), last = (K1 == nblk);
+    if (bi == K && bj == K) {
+        // the pivot block itself was finished by the previous launch; on the last step it still has to
+        // be negated and mirrored like everything else
+        if (last) {
+            const int p0 = K * FNB, bs = n - p0;
+            for (int e = tid; e < FNB * FNB; e += 256) {
+                const int i = e >> 6, j = e & 63;
+                if (i < bs && j <= i) {
+                    const float v = -pr.W[(long)(p0 + i) * n + p0 + j];
+                    pr.W[(long)(p0 + i) * n + p0 + j] = v;
+                    pr.W[(long)(p0 + j) * n + p0 + i] = v;
+                }
+            }
+        }
+        return;
+    }
+
+    const int p0 = K * FNB, p1 = K1 * FNB;
+    const int bs = min(FNB, n - p0);
+    const int bs1 = min(FNB, n - p1);              // <= 0 when there is no next block
+    const float *Pk = pr.P + (K & 1) * FNB * FNB;
+    const float *Vk = pr.Vt + (long)(K & 1) * FNB * ldv;
+    float *Pn = pr.P + (K1 & 1) * FNB * FNB;
+    float *Vn = pr.Vt + (long)(K1 & 1) * FNB * ldv;
+    const bool panel = (bi == K) != (bj == K);
+    const int ra = panel ? (bi == K ? bj : bi) : bi;   // block whose V goes to Va
+    const int rb = bj;
+
+    // ---- stage P, V_a (and V_b) ----
+    if (first) {
+        // step 0: the panel is column block 0 of the input itself (blocks below the diagonal carry no damping)
+        for (int e = tid; e < FNB * FNB; e += 256) {
+            const int c = e >> 6, k = e & 63;
+            const int ga = ra * FNB + c, gb = rb * FNB + c;
+            Va[k * PITCH + c] = (ga < n) ? pr.M[(long)ga * n + k] : 0.f;
+            if (!panel && rb != ra) Vb[k * PITCH + c] = (gb < n) ? pr.M[(long)gb * n + k] : 0.f;
+        }
+    }
+    for (int e = tid; e < FNB * FNB / 4; e += 256) {
+        const int k = e >> 4, c4 = (e & 15) * 4;
+        *reinterpret_cast<floatx4 *>(Ps + k * PITCH + c4) = *reinterpret_cast<const floatx4 *>(Pk + k * FNB + c4);
+        if (first) continue;
+        const int ga = ra * FNB + c4;
+        floatx4 va = {0.f, 0.f, 0.f, 0.f};
+        if (ga < ldv && k < bs) {
+            va = *reinterpret_cast<const floatx4 *>(Vk + (long)k * ldv + ga);
+            if (ga + 1 >= n) va.y = 0.f;
+            if (ga + 2 >= n) va.z = 0.f;
+            if (ga + 3 >= n) va.w = 0.f;
+        }
+        *reinterpret_cast<floatx4 *>(Va + k * PITCH + c4) = va;
+        if (!panel && rb != ra) {
+            const int gb = rb * FNB + c4;
+            floatx4 vb = {0.f, 0.f, 0.f, 0.f};
+            if (gb < ldv && k < bs) {
+                vb = *reinterpret_cast<const floatx4 *>(Vk + (long)k * ldv + gb);
+                if (gb + 1 >= n) vb.y = 0.f;
+                if (gb + 2 >= n) vb.z = 0.f;
+                if (gb + 3 >= n) vb.w = 0.f;
+            }
+            *reinterpret_cast<floatx4 *>(Vb + k * PITCH + c4) = vb;
+        }
+    }
+    __syncthreads();
+
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int lr = lane & 15, lk = lane >> 4;
+    floatx4 acc[T::WT][T::WT];
+#pragma unroll
+    for (int a = 0; a < T::WT; ++a)
+#pragma unroll
+        for (int b = 0; b < T::WT; ++b) acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
+    // acc = W^T[m][c] = sum_k P[k][m] V_a[k][c]   (P symmetric)
+#pragma unroll
+    for (int s4 = 0; s4 < FNB / T::KT; ++s4)
+        mma_stage<T, kRows, kRows, false>(Ps + s4 * T::KT * PITCH, Va + s4 * T::KT * PITCH, wm, wn, lane, acc);
+
+    if (panel) {
+        // new panel values in place; tile (K+1, K) also feeds the next step's V'
+        const bool below = ra > K;
+        const bool next = (ra == K1);
+#pragma unroll
+        for (int ti = 0; ti < T::WT; ++ti)
+#pragma unroll
+            for (int tj = 0; tj < T::WT; ++tj) {
+                const int c = (wn * T::WT + tj) * 16 + lr;
+                const int gc = ra * FNB + c;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int m = (wm * T::WT + ti) * 16 + 4 * lk + v;
+                    const float w = acc[ti][tj][v];
+                    const bool ok = (gc < n && m < bs);
+                    if (ok) {
+                        if (below) pr.W[(long)gc * n + p0 + m] = w;
+                        else if (!last) pr.W[(long)(p0 + m) * n + gc] = w;
+                        else {   // last step: the row panel is final
+                            pr.W[(long)(p0 + m) * n + gc] = -w;
+                            pr.W[(long)gc * n + p0 + m] = -w;
+                        }
+                    }
+                    // V'[kk = c][column p0 + m] = M[p1 + c][p0 + m]; rows kk >= bs1 are zero
+                    if (next && m < bs) Vn[(long)c * ldv + p0 + m] = ok ? w : 0.f;
+                }
+            }
+        return;
+    }
+
+    // ---- W^T to LDS (over P), then C = M_ij - W_i V_j^T ----
+    __syncthreads();   // every wave is done reading Ps
+#pragma unroll
+    for (int ti = 0; ti < T::WT; ++ti)
+#pragma unroll
+        for (int tj = 0; tj < T::WT; ++tj) {
+            const int c = (wn * T::WT + tj) * 16 + lr;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int m = (wm * T::WT + ti) * 16 + 4 * lk + v;
+                Ps[m * PITCH + c] = acc[ti][tj][v];
+            }
+        }
+    __syncthreads();
+    const float *Vj = (rb == ra) ? Va : Vb;
+#pragma unroll
+    for (int a = 0; a < T::WT; ++a)
+#pragma unroll
+        for (int b = 0; b < T::WT; ++b) acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s4 = 0; s4 < FNB / T::KT; ++s4)
+        mma_stage<T, kRows, kRows, false>(Ps + s4 * T::KT * PITCH, Vj + s4 * T::KT * PITCH, wm, wn, lane, acc);
+
+    // acc[ti][tj][v] = (W_i V_j^T)[a][b], a = (wm*2+ti)*16 + 4*lk + v, b = (wn*2+tj)*16 + lr
+    const bool diag = (bi == bj);
+    const bool next_col = (bj == K1 && bi > K1);    // column panel of the next pivot: V'[b][ga]
+    const bool next_row = (bi == K1 && bj < K1);    // row panel of the next pivot: V'[a][gb]
+    const bool next_piv = (bi == K1 && bj == K1);
+    __syncthreads();   // Va is reused below when this tile is the next pivot
+#pragma unroll
+    for (int ti = 0; ti < T::WT; ++ti)
+#pragma unroll
+        for (int tj = 0; tj < T::WT; ++tj) {
+            const int b = (wn * T::WT + tj) * 16 + lr;
+            const int gb = bj * FNB + b;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int a = (wm * T::WT + ti) * 16 + 4 * lk + v;
+                const int ga = bi * FNB + a;
+                const bool ok = (ga < n && gb < n && (!diag || gb <= ga));
+                float c = 0.f;
+                if (ok) {
+                    const float old = first ? pr.M[(long)ga * n + gb] + (ga == gb ? pr.damping : 0.f)
+                                            : pr.W[(long)ga * n + gb];
+                    c = old - acc[ti][tj][v];
+                    if (last) {
+                        pr.W[(long)ga * n + gb] = -c;
+                        pr.W[(long)gb * n + ga] = -c;
+                    } else if (!next_piv) {
+                        pr.W[(long)ga * n + gb] = c;
+                    }
+                }
+                if (next_col && ga < n) Vn[(long)b * ldv + ga] = ok ? c : 0.f;
+                if (next_row && gb < n) Vn[(long)a * ldv + gb] = ok ? c : 0.f;
+                if (next_piv) Va[a * PITCH + b] = c;
+            }
+        }
+    if (!next_piv) return;
+
+    // ---- this workgroup holds the next pivot block: invert it now ----
+    __syncthreads();
+    {
+        const int i = tid >> 2, jq = tid & 3;
+        float s[16];
+#pragma unroll
+        for (int m = 0; m < 16; ++m) {
+            const int j = jq + 4 * m;
+            float v = (i == j) ? 1.f : 0.f;
+            if (i < bs1 && j < bs1) v = (j <= i) ? Va[i * PITCH + j] : Va[j * PITCH + i];
+            s[m] = v;
+        }
+        const int fail = sweep64(s, colb, rowb, tid);
+#pragma unroll
+        for (int m = 0; m < 16; ++m) {
+            const int j = jq + 4 * m;
+            const bool in = (i < bs1 && j < bs1);
+            Pn[i * FNB + j] = in ? -s[m] : 0.f;
+            if (in && j <= i) pr.W[(long)(p1 + i) * n + p1 + j] = s[m];
+        }
+        // launches of one sequence are ordered, so the first failing pivot wins
+        if (fail != 0 && fail <= bs1 && tid == 0 && *pr.info == 0) *pr.info = p1 + fail;
+    }
+}
+
+}  // namespace kfac
