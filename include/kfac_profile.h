@@ -26,7 +26,8 @@ enum {
     KFAC_K_SYRK_CONV3 = 9,   /* KF-GEMM fused with 3x3 patch extraction (reads the NCHW input) */
     KFAC_K_SYRK_SMALL = 10,  /* KF-GEMM, direct kernel for narrow NCHW operands */
     KFAC_K_INV_STEP = 11,    /* fused sweep step: panel + update + next pivot in one launch */
-    KFAC_K_COUNT = 12
+    KFAC_K_SYRK_BF16 = 12,   /* KF-GEMM on the bf16 MFMA units (row-major bf16 operands) */
+    KFAC_K_COUNT = 13
 };
 
 /* When enabled, every kernel launch is bracketed by a pair of HIP events

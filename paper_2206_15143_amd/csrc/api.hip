@@ -499,7 +499,8 @@ const char *kfac_timing_class_name(int cls)
 {
     static const char *names[KFAC_K_COUNT] = {"im2col", "syrk_partial", "syrk_reduce", "inv_init",
                                               "inv_pivot", "inv_panel", "inv_finish", "gemm_tn",
-                                              "syrk_wave", "syrk_conv3", "syrk_small", "inv_step"};
+                                              "syrk_wave", "syrk_conv3", "syrk_small", "inv_step",
+                                              "syrk_bf16"};
     return (cls >= 0 && cls < KFAC_K_COUNT) ? names[cls] : "?";
 }
 
@@ -537,6 +538,7 @@ int kfac_tune(const char *key, long value)
     else if (k == "update_bm") t.update_bm = value;
     else if (k == "use_small_kernel") t.use_small_kernel = value;
     else if (k == "invert_fused_max_n") t.invert_fused_max_n = value;
+    else if (k == "use_bf16_mfma") t.use_bf16_mfma = value;
     else if (k == "gemm_bm") t.gemm_bm = value;
     else return 1;
     return 0;

@@ -50,6 +50,7 @@ struct SyrkTable {
 #include "syrk_wave.hpp"
 #include "syrk_conv3.hpp"
 #include "syrk_small.hpp"
+#include "syrk_bf16.hpp"
 
 namespace kfac {
 
@@ -271,16 +272,26 @@ namespace {
 
 struct Cfg { int wt, nw, bm; };
 // the last entry is the wave-unit kernel (syrk_wave.hpp): 144-wide macro tiles, same partial layout as Tile<3,3>
-const Cfg kCfgs[] = {{4, 2, 128}, {3, 3, 144}, {2, 2, 64}, {1, 2, 32}, {0, 0, 144}, {0, 0, 144}, {0, 0, 32}, {0, 0, 64}};
+const Cfg kCfgs[] = {{4, 2, 128}, {3, 3, 144}, {2, 2, 64}, {1, 2, 32}, {0, 0, 144}, {0, 0, 144}, {0, 0, 32}, {0, 0, 64},
+                     {0, 0, 256}};
 constexpr int kWaveCfg = 4;
 constexpr int kConv3Cfg = 5;   // fused 3x3 convolution kernel (syrk_conv3.hpp), same partial layout
 constexpr int kSmall32Cfg = 6; // narrow NCHW operands (syrk_small.hpp), partial tile 32 x 32 (d <= 32)
 constexpr int kSmall64Cfg = 7; // same, 64 x 64 (d <= 64)
+constexpr int kBf16Cfg = 8;    // row-major bf16 operands on the bf16 MFMA units (syrk_bf16.hpp), 256 x 256 tiles
 
 bool small_eligible(const FactorJob &j)
 {
     return tuning().use_small_kernel && j.dtype == 0 && j.layout == kNCHW && j.d_core <= 64 && !j.has_bias &&
            j.hw % 4 == 0;
+}
+
+bool bf16_eligible(const FactorJob &j)
+{
+    // rows of whole 16-byte pieces; columns between d_core and the next multiple of 8 must exist and be
+    // zero (true for patch matrices, whose pitch is d_core rounded up to 16 bytes with zero padding)
+    return tuning().use_bf16_mfma && j.dtype == 1 && j.layout == kRows && j.ld % 8 == 0 &&
+           (j.d_core + 7) / 8 * 8 <= j.ld && j.ld < (1l << 22) && j.d_core >= 96;
 }
 
 bool wave_eligible(const FactorJob &j)
@@ -343,7 +354,7 @@ void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<
             p.rows_per_stage = conv3_choose_rows(jobs[j].h, jobs[j].w);
             p.unit_rows = p.rows_per_stage * jobs[j].w;
         } else {
-            p.unit_rows = 16;
+            p.unit_rows = (p.cfg == kBf16Cfg) ? H_KT : 16;
         }
         // A block that holds a single unit (one macro tile in all) spreads it over its four waves and
         // needs a quarter of the time per K row: give it four times the rows.
@@ -366,6 +377,8 @@ void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<
             long tpb_j = std::max<long>(1, tpb * p.stretch * 16 / p.unit_rows);
             if (p.cfg == kWaveCfg)   // a split's byte range must stay below 2^31 (32-bit buffer offsets)
                 tpb_j = std::max<long>(1, std::min<long>(tpb_j, 0x7fffffffl / (64 * jobs[j].ld) - 1));
+            if (p.cfg == kBf16Cfg)
+                tpb_j = std::max<long>(1, std::min<long>(tpb_j, 0x7fffffffl / (2 * H_KT * jobs[j].ld) - 1));
             p.splits = (int)((ktiles + tpb_j - 1) / tpb_j);
             p.tps = (int)((ktiles + p.splits - 1) / p.splits);
             p.splits = (int)((ktiles + p.tps - 1) / p.tps);
@@ -389,6 +402,7 @@ void plan_all(const FactorJob *jobs, int n, std::vector<Planned> &pl, std::vecto
     for (int i = 0; i < n; ++i) {
         if (jobs[i].layout == kConv3) pl[i].cfg = kConv3Cfg;
         else if (small_eligible(jobs[i])) pl[i].cfg = jobs[i].d_core <= 32 ? kSmall32Cfg : kSmall64Cfg;
+        else if (bf16_eligible(jobs[i])) pl[i].cfg = kBf16Cfg;
         else pl[i].cfg = wave_eligible(jobs[i]) ? kWaveCfg : choose_cfg(jobs[i].d_core);
         keys[i] = group_key(jobs[i], pl[i].cfg);
     }
@@ -538,6 +552,15 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
                     KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<1, 2>>), dim3(red), dim3(256), 0, tab);
                 else
                     KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<2, 2>>), dim3(red), dim3(256), 0, tab);
+                e = hipGetLastError();
+                break;
+            }
+            case kBf16Cfg: {
+                KFAC_LAUNCH(KFAC_K_SYRK_BF16, s, syrk_bf16_kernel, dim3(blocks), dim3(512), 0, tab);
+                timing_work(flops);
+                e = hipGetLastError();
+                if (e != hipSuccess) break;
+                KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<8, 2>>), dim3(red), dim3(256), 0, tab);
                 e = hipGetLastError();
                 break;
             }

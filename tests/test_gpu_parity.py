@@ -217,3 +217,28 @@ def test_bf16_inputs_match_oracle_on_the_same_bits():
     for i, l in enumerate(layers):
         ref = gu.run_layer_oracle(l, raw[i], scales[i], 0.95, 0.03)
         assert gu.rel_fro(gpu[i]["P"], ref["P"]) < 2e-2
+
+
+@pytest.mark.parametrize("layer,batch", [
+    (LayerSpec("linear", 256, 24, rows=300), 300),                 # one block tile, ragged last K stage, bias border
+    (LayerSpec("linear", 520, 16, rows=77), 77),                   # three block rows, last one 8 columns wide
+    (LayerSpec("linear", 104, 8, rows=40, has_bias=False), 40),    # narrower than one tile, no bias
+    (LayerSpec("linear", 768, 320, rows=1500), 1500),              # A and G both on the bf16 units, several K splits
+    (LayerSpec("conv", 32, 8, 3, 1, 1, 10), 3),                    # bf16 patch matrix (d = 288)
+    (LayerSpec("conv", 12, 8, 3, 2, 1, 9), 5),                     # d = 108: pitch padded to 112 with zero columns
+])
+def test_bf16_mfma_factor_kernel(layer, batch):
+    # row-major bf16 operands take the bf16 MFMA kernel; same bits into the oracle
+    inputs = gu.draw_inputs([layer], batch, 6500 + layer.d_A, "relu_normal", 0.05, dtype="bf16")
+    scales = gu.scales_for([layer], batch)
+    fast = gu.run_layers_gpu([layer], batch, inputs, scales, 0.95, 0.03, dtype="bf16")[0]
+    ref = gu.run_layer_oracle(layer, inputs[0], scales[0], 0.95, 0.03)
+    gu.check_layer(fast, ref, tag=str(layer))
+    # and the same factors as the kernel that widens bf16 to fp32 on load
+    kf.kfac_tune("use_bf16_mfma", 0)
+    try:
+        wide = gu.run_layers_gpu([layer], batch, inputs, scales, 0.95, 0.03, dtype="bf16")[0]
+    finally:
+        kf.kfac_tune("use_bf16_mfma", 1)
+    assert gu.rel_fro(fast["A"], wide["A"]) < 1e-5
+    assert gu.rel_fro(fast["G"], wide["G"]) < 1e-5
