@@ -290,8 +290,11 @@ bool bf16_eligible(const FactorJob &j)
 {
     // rows of whole 16-byte pieces; columns between d_core and the next multiple of 8 must exist and be
     // zero (true for patch matrices, whose pitch is d_core rounded up to 16 bytes with zero padding)
-    return tuning().use_bf16_mfma && j.dtype == 1 && j.layout == kRows && j.ld % 8 == 0 &&
-           (j.d_core + 7) / 8 * 8 <= j.ld && j.ld < (1l << 22) && j.d_core >= 96;
+    if (!(tuning().use_bf16_mfma && j.dtype == 1 && j.d_core >= 96)) return false;
+    if (j.layout == kRows)
+        return j.ld % 8 == 0 && (j.d_core + 7) / 8 * 8 <= j.ld && j.ld < (1l << 22);
+    // NCHW: channel rows must start on 4-byte boundaries and the tensor must fit 32-bit buffer offsets
+    return j.layout == kNCHW && j.hw % 2 == 0 && (j.K / j.hw) * (long)j.ctot * j.hw * 2 < 0x7fffffffl;
 }
 
 bool wave_eligible(const FactorJob &j)
@@ -374,10 +377,12 @@ void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<
             long ktiles = std::max<long>(1, (jobs[j].K + p.unit_rows - 1) / p.unit_rows);
             if (p.cfg == kSmall32Cfg || p.cfg == kSmall64Cfg)   // walked in 16-position groups per image
                 ktiles = (jobs[j].K / jobs[j].hw) * ((jobs[j].hw + 15) / 16);
+            if (p.cfg == kBf16Cfg && jobs[j].layout == kNCHW)   // 32-position stages that never cross an image
+                ktiles = (jobs[j].K / jobs[j].hw) * ((jobs[j].hw + H_KT - 1) / H_KT);
             long tpb_j = std::max<long>(1, tpb * p.stretch * 16 / p.unit_rows);
             if (p.cfg == kWaveCfg)   // a split's byte range must stay below 2^31 (32-bit buffer offsets)
                 tpb_j = std::max<long>(1, std::min<long>(tpb_j, 0x7fffffffl / (64 * jobs[j].ld) - 1));
-            if (p.cfg == kBf16Cfg)
+            if (p.cfg == kBf16Cfg && jobs[j].layout == kRows)
                 tpb_j = std::max<long>(1, std::min<long>(tpb_j, 0x7fffffffl / (2 * H_KT * jobs[j].ld) - 1));
             p.splits = (int)((ktiles + tpb_j - 1) / tpb_j);
             p.tps = (int)((ktiles + p.splits - 1) / p.splits);
@@ -556,7 +561,10 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
                 break;
             }
             case kBf16Cfg: {
-                KFAC_LAUNCH(KFAC_K_SYRK_BF16, s, syrk_bf16_kernel, dim3(blocks), dim3(512), 0, tab);
+                if (layout == kRows)
+                    KFAC_LAUNCH(KFAC_K_SYRK_BF16, s, syrk_bf16_kernel<kRows>, dim3(blocks), dim3(512), 0, tab);
+                else
+                    KFAC_LAUNCH(KFAC_K_SYRK_BF16, s, syrk_bf16_kernel<kNCHW>, dim3(blocks), dim3(512), 0, tab);
                 timing_work(flops);
                 e = hipGetLastError();
                 if (e != hipSuccess) break;

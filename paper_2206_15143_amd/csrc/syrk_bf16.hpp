@@ -18,6 +18,13 @@
 // column i.  The row pitch is 288 elements (= 16 banks mod 64), so the four rows
 // and two column halves a half-wave touches fall on disjoint banks.
 //
+// NCHW operands (1x1 convolution inputs, output gradients of every
+// convolution) are k-contiguous already: their panels are staged [column][32 k]
+// (pitch 80 bytes, conflict-free for 16-byte reads) and a lane's operand is one
+// ds_read_b128.  A K stage never crosses an image; the k positions past the
+// end of an image in its last stage are cleared in the A operand registers (the
+// matching B values are finite neighbours and are multiplied by zero).
+//
 // On diagonal blocks the two waves whose tile lies wholly above the diagonal
 // compute the column sums of the block (the bias border of A) as a product
 // with a vector of ones instead of idling.
@@ -37,6 +44,11 @@ constexpr int H_NSTAGE = 3;
 constexpr int H_PIECES = 2 * H_KT * H_SEGS;  // 2304 16-byte pieces per stage = 36 wave instructions
 constexpr int H_LOADS = 5;                   // DMA instructions per wave and stage (8 waves x 5 = 40 >= 36)
 constexpr int H_LDS_BYTES = H_NSTAGE * H_STAGE_B + 1024;
+// NCHW staging: [256 columns][32 k] with an 80-byte column pitch, five 16-byte pieces per column
+constexpr int HN_PITCH_B = 80;
+constexpr int HN_PANEL_B = H_BM * HN_PITCH_B;   // 20480
+constexpr int HN_STAGE_B = 2 * HN_PANEL_B;      // 40960 = 40 wave instructions
+constexpr int HN_LDS_BYTES = H_NSTAGE * HN_STAGE_B + 1024;
 
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef short short8v __attribute__((ext_vector_type(8)));
@@ -54,21 +66,47 @@ __device__ __forceinline__ bf16x8 tr_frag(const unsigned char *lds, int byte)
     return __builtin_bit_cast(bf16x8, v);
 }
 
+__device__ __forceinline__ bf16x8 nchw_frag(const unsigned char *lds, int byte)
+{
+    const short8v v = *reinterpret_cast<const short8v *>(lds + byte);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+// clears elements e >= nv of an operand fragment (nv may be <= 0 or >= 8)
+__device__ __forceinline__ bf16x8 keep_first(bf16x8 x, int nv)
+{
+    typedef unsigned uint4v __attribute__((ext_vector_type(4)));
+    uint4v u = __builtin_bit_cast(uint4v, x);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const unsigned m = (nv >= 2 * q + 2) ? 0xffffffffu : (nv == 2 * q + 1 ? 0x0000ffffu : 0u);
+        u[q] &= m;
+    }
+    return __builtin_bit_cast(bf16x8, u);
+}
+
 struct HalfCtx {
     int4v rsrc;
     unsigned vo[H_LOADS];       // per-lane global byte offsets of this wave's pieces (W_OOB = none)
     unsigned dst[H_LOADS];      // LDS byte offset of each instruction inside a stage (or the landing zone)
     unsigned lds_base;
-    unsigned tile_bytes;        // global bytes per K stage
+    unsigned tile_bytes;        // kRows: global bytes per K stage
     int nstages;
+    // kNCHW: stage -> (image, k tile inside the image)
+    int tpi, hw;                // K tiles per image, positions per image
+    unsigned img_bytes;         // bytes from one image to the next
+    int img0, kt0;              // image / tile of the split's first stage
 };
 
-__device__ __forceinline__ void half_issue(const HalfCtx &c, int g)
+// so: global byte offset of the stage (uniform)
+template <int LAYOUT>
+__device__ __forceinline__ void half_issue(const HalfCtx &c, int g, unsigned so_live)
 {
+    constexpr int STAGE_B = (LAYOUT == kRows) ? H_STAGE_B : HN_STAGE_B;
     const bool live = g < c.nstages;
-    const unsigned buf = c.lds_base + (unsigned)((g % H_NSTAGE) * H_STAGE_B);
-    const unsigned dummy = c.lds_base + (unsigned)(H_NSTAGE * H_STAGE_B);
-    const unsigned so = live ? (unsigned)g * c.tile_bytes : 0u;
+    const unsigned buf = c.lds_base + (unsigned)((g % H_NSTAGE) * STAGE_B);
+    const unsigned dummy = c.lds_base + (unsigned)(H_NSTAGE * STAGE_B);
+    const unsigned so = live ? so_live : 0u;
 #pragma unroll
     for (int i = 0; i < H_LOADS; ++i) {
         const bool piece = c.dst[i] != 0xffffffffu;
@@ -84,28 +122,70 @@ __device__ __forceinline__ void half_sync()
 
 enum HalfKind : int { kHFull = 0, kHOnes = 1, kHIdle = 2 };
 
+// Walks the stages of a split: global byte offset of each stage and, for NCHW, the number of valid
+// k positions in it.
+template <int LAYOUT>
+struct StageWalk {
+    unsigned so;
+    int img, kt, rem;
+    __device__ __forceinline__ void start(const HalfCtx &c)
+    {
+        if (LAYOUT == kRows) { so = 0; rem = H_KT; }
+        else { img = c.img0; kt = c.kt0; so = (unsigned)img * c.img_bytes + (unsigned)(kt * H_KT * 2); rem = c.hw - kt * H_KT; }
+    }
+    __device__ __forceinline__ void next(const HalfCtx &c)
+    {
+        if (LAYOUT == kRows) { so += c.tile_bytes; }
+        else {
+            ++kt;
+            if (kt == c.tpi) { kt = 0; ++img; }
+            so = (unsigned)img * c.img_bytes + (unsigned)(kt * H_KT * 2);
+            rem = c.hw - kt * H_KT;
+        }
+    }
+};
+
 // The K loop of one wave.  KIND is uniform over a wavefront, so the MFMA chain is straight-line code.
-template <int KIND>
+template <int LAYOUT, int KIND>
 __device__ __forceinline__ void half_loop(const HalfCtx &c, const unsigned char *lds, int a_byte, int b_byte,
-                                          floatx16 (&acc)[8])
+                                          int lg, floatx16 (&acc)[8])
 {
-    half_issue(c, 0);
-    half_issue(c, 1);
+    constexpr int STAGE_B = (LAYOUT == kRows) ? H_STAGE_B : HN_STAGE_B;
+    constexpr int JSTEP = (LAYOUT == kRows) ? 16 * H_PITCH_B : 32;      // bytes from one k16 step to the next
+    constexpr int TSTEP = (LAYOUT == kRows) ? 64 : 32 * HN_PITCH_B;     // bytes from one 32-column tile to the next
+    StageWalk<LAYOUT> wi, wc;     // stage being issued / stage being multiplied
+    wi.start(c);
+    wc.start(c);
+    half_issue<LAYOUT>(c, 0, wi.so);
+    wi.next(c);
+    half_issue<LAYOUT>(c, 1, wi.so);
+    wi.next(c);
     asm volatile("s_waitcnt vmcnt(5)\n\ts_barrier" ::: "memory");
     bf16x8 ones;
 #pragma unroll
     for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
     for (int g = 0; g < c.nstages; ++g) {
-        half_issue(c, g + 2);
-        const unsigned char *buf = lds + (g % H_NSTAGE) * H_STAGE_B;
+        half_issue<LAYOUT>(c, g + 2, wi.so);
+        wi.next(c);
+        const unsigned char *buf = lds + (g % H_NSTAGE) * STAGE_B;
+        const bool tail = (LAYOUT == kNCHW) && wc.rem < H_KT;
         if (KIND == kHFull) {
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 bf16x8 a[4], b[2];
 #pragma unroll
-                for (int t = 0; t < 4; ++t) a[t] = tr_frag(buf, a_byte + j * 16 * H_PITCH_B + t * 64);
+                for (int t = 0; t < 4; ++t)
+                    a[t] = (LAYOUT == kRows) ? tr_frag(buf, a_byte + j * JSTEP + t * TSTEP)
+                                             : nchw_frag(buf, a_byte + j * JSTEP + t * TSTEP);
 #pragma unroll
-                for (int t = 0; t < 2; ++t) b[t] = tr_frag(buf, b_byte + j * 16 * H_PITCH_B + t * 64);
+                for (int t = 0; t < 2; ++t)
+                    b[t] = (LAYOUT == kRows) ? tr_frag(buf, b_byte + j * JSTEP + t * TSTEP)
+                                             : nchw_frag(buf, b_byte + j * JSTEP + t * TSTEP);
+                if (tail) {
+                    const int nv = wc.rem - 16 * j - 8 * lg;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) a[t] = keep_first(a[t], nv);
+                }
 #pragma unroll
                 for (int ti = 0; ti < 4; ++ti)
 #pragma unroll
@@ -117,21 +197,26 @@ __device__ __forceinline__ void half_loop(const HalfCtx &c, const unsigned char 
             for (int j = 0; j < 2; ++j) {
                 bf16x8 b[4];
 #pragma unroll
-                for (int t = 0; t < 4; ++t) b[t] = tr_frag(buf, b_byte + j * 16 * H_PITCH_B + t * 64);
+                for (int t = 0; t < 4; ++t)
+                    b[t] = (LAYOUT == kRows) ? tr_frag(buf, b_byte + j * JSTEP + t * TSTEP)
+                                             : nchw_frag(buf, b_byte + j * JSTEP + t * TSTEP);
+                const bf16x8 o = tail ? keep_first(ones, wc.rem - 16 * j - 8 * lg) : ones;
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
-                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, b[t], acc[t], 0, 0, 0);
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o, b[t], acc[t], 0, 0, 0);
             }
         }
+        wc.next(c);
         half_sync();
     }
     // the padding loads of the stages past the end may still be landing
     asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+template <int LAYOUT>
 __global__ __launch_bounds__(512) void syrk_bf16_kernel(const SyrkTable tab)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char lds[H_LDS_BYTES];
+    __shared__ __attribute__((aligned(16))) unsigned char lds[LAYOUT == kRows ? H_LDS_BYTES : HN_LDS_BYTES];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -149,37 +234,69 @@ __global__ __launch_bounds__(512) void syrk_bf16_kernel(const SyrkTable tab)
     tri_decode(blk, bi, bj);
     const bool diag = (bi == bj);
 
-    // ---- K range of this split, buffer resource over it ----
-    const long ktiles = (pr.K + H_KT - 1) / H_KT;
-    const long t0 = (long)split * pr.tiles_per_split;
-    const long t1 = (t0 + pr.tiles_per_split < ktiles) ? t0 + pr.tiles_per_split : ktiles;
-    const long row0 = t0 * H_KT;
-    const unsigned short *base = reinterpret_cast<const unsigned short *>(pr.x) + row0 * pr.ld;
-    const long bytes_left = (pr.K - row0) * pr.ld * 2;
+    // ---- K range of this split, buffer resource, per-lane piece offsets ----
     HalfCtx c;
-    {
+    c.lds_base = (unsigned)(unsigned long)(__attribute__((address_space(3))) unsigned char *)lds;
+    const long t0 = (long)split * pr.tiles_per_split;
+    const int ld = (int)pr.ld;
+    if (LAYOUT == kRows) {
+        const long ktiles = (pr.K + H_KT - 1) / H_KT;
+        const long t1 = (t0 + pr.tiles_per_split < ktiles) ? t0 + pr.tiles_per_split : ktiles;
+        const long row0 = t0 * H_KT;
+        const unsigned short *base = reinterpret_cast<const unsigned short *>(pr.x) + row0 * pr.ld;
+        const long bytes_left = (pr.K - row0) * pr.ld * 2;
         const unsigned long ba = (unsigned long)base;
         c.rsrc.x = (int)(unsigned)ba;
         c.rsrc.y = (int)(unsigned)(ba >> 32);
         c.rsrc.z = bytes_left > 0x7fffffffl ? 0x7fffffff : (int)bytes_left;
         c.rsrc.w = 0x00020000;
-    }
-    c.lds_base = (unsigned)(unsigned long)(__attribute__((address_space(3))) unsigned char *)lds;
-    c.nstages = (int)(t1 - t0);
-    const int ld = (int)pr.ld;
-    c.tile_bytes = (unsigned)(H_KT * ld * 2);
+        c.nstages = (int)(t1 - t0);
+        c.tile_bytes = (unsigned)(H_KT * ld * 2);
+        c.tpi = 1; c.hw = 0; c.img_bytes = 0; c.img0 = 0; c.kt0 = 0;
 #pragma unroll
-    for (int i = 0; i < H_LOADS; ++i) {
-        const int inst = i * 8 + w;                 // wave instruction index inside the stage
-        const int p = inst * 64 + lane;             // 16-byte piece
-        const int panel = p / (H_KT * H_SEGS);
-        const int r = p - panel * (H_KT * H_SEGS);
-        const int row = r / H_SEGS, seg = r - row * H_SEGS;
-        const int col = (panel == 0 ? bi : bj) * H_BM + seg * 8;
-        const bool inst_ok = inst * 64 < H_PIECES && !(diag && inst * 64 >= H_KT * H_SEGS);
-        const bool ok = inst_ok && p < H_PIECES && seg < 32 && col < ld;
-        c.vo[i] = ok ? (unsigned)((row * ld + col) * 2) : W_OOB;
-        c.dst[i] = inst_ok ? (unsigned)(inst * 1024) : 0xffffffffu;
+        for (int i = 0; i < H_LOADS; ++i) {
+            const int inst = i * 8 + w;                 // wave instruction index inside the stage
+            const int p = inst * 64 + lane;             // 16-byte piece
+            const int panel = p / (H_KT * H_SEGS);
+            const int r = p - panel * (H_KT * H_SEGS);
+            const int row = r / H_SEGS, seg = r - row * H_SEGS;
+            const int col = (panel == 0 ? bi : bj) * H_BM + seg * 8;
+            const bool inst_ok = inst * 64 < H_PIECES && !(diag && inst * 64 >= H_KT * H_SEGS);
+            const bool ok = inst_ok && p < H_PIECES && seg < 32 && col < ld;
+            c.vo[i] = ok ? (unsigned)((row * ld + col) * 2) : W_OOB;
+            c.dst[i] = inst_ok ? (unsigned)(inst * 1024) : 0xffffffffu;
+        }
+    } else {
+        // x is [images][ctot][hw]; the buffer covers the whole tensor (the host checked it is below 2 GiB)
+        const int hw = pr.hw;
+        const int nimg = (int)(pr.K / hw);
+        c.tpi = (hw + H_KT - 1) / H_KT;
+        c.hw = hw;
+        c.img_bytes = (unsigned)pr.ctot * (unsigned)hw * 2u;
+        const long ktiles = (long)nimg * c.tpi;
+        const long t1 = (t0 + pr.tiles_per_split < ktiles) ? t0 + pr.tiles_per_split : ktiles;
+        c.nstages = (int)(t1 - t0);
+        c.img0 = (int)(t0 / c.tpi);
+        c.kt0 = (int)(t0 - (long)c.img0 * c.tpi);
+        c.tile_bytes = 0;
+        const unsigned long ba = (unsigned long)pr.x;
+        c.rsrc.x = (int)(unsigned)ba;
+        c.rsrc.y = (int)(unsigned)(ba >> 32);
+        c.rsrc.z = (int)((long)nimg * c.img_bytes);
+        c.rsrc.w = 0x00020000;
+#pragma unroll
+        for (int i = 0; i < H_LOADS; ++i) {
+            const int inst = i * 8 + w;                 // 40 instructions: 20 per panel
+            const int p = inst * 64 + lane;
+            const int panel = p / (H_BM * 5);
+            const int r = p - panel * (H_BM * 5);
+            const int cl = r / 5, seg = r - cl * 5;
+            const int col = (panel == 0 ? bi : bj) * H_BM + cl;
+            const bool inst_ok = !(diag && panel == 1);
+            const bool ok = inst_ok && seg < 4 && col < pr.d;
+            c.vo[i] = ok ? (unsigned)((col * hw + seg * 8) * 2) : W_OOB;
+            c.dst[i] = inst_ok ? (unsigned)(inst * 1024) : 0xffffffffu;
+        }
     }
 
     floatx16 acc[8];
@@ -188,23 +305,33 @@ __global__ __launch_bounds__(512) void syrk_bf16_kernel(const SyrkTable tab)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
 
-    // per-lane part of the transposing read address: row 8*kgroup + e, column 16*colhalf + 4*q
-    const int s16 = lane & 15, gi = lane >> 4;
-    const int lane_byte = (8 * (gi >> 1) + (s16 >> 2)) * H_PITCH_B + (16 * (gi & 1) + 4 * (s16 & 3)) * 2;
-    const int bpanel = diag ? 0 : H_PANEL_B;
+    const int lr = lane & 31, lg = lane >> 5;
+    int lane_byte, a_byte, b_byte, o_byte;
+    if (LAYOUT == kRows) {
+        // per-lane part of the transposing read address: row 8*kgroup + e, column 16*colhalf + 4*q
+        const int s16 = lane & 15, gi = lane >> 4;
+        lane_byte = (8 * (gi >> 1) + (s16 >> 2)) * H_PITCH_B + (16 * (gi & 1) + 4 * (s16 & 3)) * 2;
+        a_byte = lane_byte + wm * 128 * 2;
+        b_byte = (diag ? 0 : H_PANEL_B) + lane_byte + wn * 64 * 2;
+        o_byte = lane_byte + (wn - 2) * 128 * 2;
+    } else {
+        lane_byte = lr * HN_PITCH_B + 16 * lg;
+        a_byte = lane_byte + wm * 128 * HN_PITCH_B;
+        b_byte = (diag ? 0 : HN_PANEL_B) + lane_byte + wn * 64 * HN_PITCH_B;
+        o_byte = lane_byte + (wn - 2) * 128 * HN_PITCH_B;
+    }
 
     // wave roles: on diagonal blocks the tiles of waves (0, 2) and (0, 3) lie above the diagonal
     const bool upper = diag && wm == 0 && wn >= 2;
     const bool ones_duty = upper && pr.has_bias;
     if (!upper) {
-        half_loop<kHFull>(c, lds, lane_byte + wm * 128 * 2, bpanel + lane_byte + wn * 64 * 2, acc);
+        half_loop<LAYOUT, kHFull>(c, lds, a_byte, b_byte, lg, acc);
     } else if (ones_duty) {
-        half_loop<kHOnes>(c, lds, 0, lane_byte + (wn - 2) * 128 * 2, acc);
+        half_loop<LAYOUT, kHOnes>(c, lds, 0, o_byte, lg, acc);
     } else {
-        half_loop<kHIdle>(c, lds, 0, 0, acc);
+        half_loop<LAYOUT, kHIdle>(c, lds, 0, 0, lg, acc);
     }
 
-    const int lr = lane & 31, lg = lane >> 5;
     if (!upper) {
         float *dst = pr.partial + ((long)split * nblk + blk) * (H_BM * H_BM);
 #pragma unroll

@@ -226,6 +226,10 @@ def test_bf16_inputs_match_oracle_on_the_same_bits():
     (LayerSpec("linear", 768, 320, rows=1500), 1500),              # A and G both on the bf16 units, several K splits
     (LayerSpec("conv", 32, 8, 3, 1, 1, 10), 3),                    # bf16 patch matrix (d = 288)
     (LayerSpec("conv", 12, 8, 3, 2, 1, 9), 5),                     # d = 108: pitch padded to 112 with zero columns
+    (LayerSpec("conv", 128, 96, 1, 1, 0, 6), 3),                   # 1x1: A and G read from NCHW, HW = 36 (4-position tail)
+    (LayerSpec("conv", 264, 100, 1, 1, 0, 8), 5),                  # two block columns, HW = 64 (no tail), d_G not a multiple of 8
+    (LayerSpec("conv", 8, 300, 3, 1, 1, 14), 2),                   # G of a 3x3 conv, HW = 196, two block rows
+    (LayerSpec("conv", 96, 96, 1, 1, 0, 5), 4),                    # HW = 25 is odd: the widening kernel takes it
 ])
 def test_bf16_mfma_factor_kernel(layer, batch):
     # row-major bf16 operands take the bf16 MFMA kernel; same bits into the oracle
