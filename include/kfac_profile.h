@@ -27,7 +27,8 @@ enum {
     KFAC_K_SYRK_SMALL = 10,  /* KF-GEMM, direct kernel for narrow NCHW operands */
     KFAC_K_INV_STEP = 11,    /* fused sweep step: panel + update + next pivot in one launch */
     KFAC_K_SYRK_BF16 = 12,   /* KF-GEMM on the bf16 MFMA units (row-major bf16 operands) */
-    KFAC_K_COUNT = 13
+    KFAC_K_GEMM_WAVE = 13,   /* A^T B on the wave-unit GEMM (large preconditioning and inverse products) */
+    KFAC_K_COUNT = 14
 };
 
 /* When enabled, every kernel launch is bracketed by a pair of HIP events

@@ -152,7 +152,7 @@ def kfac_tune(key: str, value: int) -> None:
         raise KeyError(key)
 
 
-KFAC_K_COUNT = 13
+KFAC_K_COUNT = 14
 
 
 def kfac_profile_copy(dst, src, nbytes: int, stream=None) -> None:

@@ -432,10 +432,10 @@ kfac_status kfac_precondition_batched(int n, const kfac_layer_desc *descs, const
         const int dA = core_dim(&descs[i]) + descs[i].has_bias, dG = descs[i].d_out;
         float *Ut = reinterpret_cast<float *>(static_cast<char *>(d_work) + off);
         off += align_up((size_t)dA * dG * sizeof(float), 256);
-        // U^T[dA, dG] = (G_inv grad)^T : A = G_inv (symmetric, read as its transpose), B = grad
+        // U^T[dA, dG] = grad^T G_inv  (G_inv symmetric): A = grad, B = G_inv, both K-major over d_G
         GemmJob &a = g1[i];
-        a.A = d_G_inv[i]; a.B = d_grad[i]; a.C = Ut;
-        a.M = dG; a.N = dA; a.K = dG; a.lda = dG; a.ldb = dA; a.ldc = dG; a.mode = kStoreT; a.p0 = a.p1 = 0;
+        a.A = d_grad[i]; a.B = d_G_inv[i]; a.C = Ut;
+        a.M = dA; a.N = dG; a.K = dG; a.lda = dA; a.ldb = dG; a.ldc = dG; a.mode = kStore; a.p0 = a.p1 = 0;
         // P[dG, dA] = (U^T)^T A_inv
         GemmJob &b = g2[i];
         b.A = Ut; b.B = d_A_inv[i]; b.C = d_out[i];
@@ -500,7 +500,7 @@ const char *kfac_timing_class_name(int cls)
     static const char *names[KFAC_K_COUNT] = {"im2col", "syrk_partial", "syrk_reduce", "inv_init",
                                               "inv_pivot", "inv_panel", "inv_finish", "gemm_tn",
                                               "syrk_wave", "syrk_conv3", "syrk_small", "inv_step",
-                                              "syrk_bf16"};
+                                              "syrk_bf16", "gemm_wave"};
     return (cls >= 0 && cls < KFAC_K_COUNT) ? names[cls] : "?";
 }
 
@@ -539,6 +539,7 @@ int kfac_tune(const char *key, long value)
     else if (k == "use_small_kernel") t.use_small_kernel = value;
     else if (k == "invert_fused_max_n") t.invert_fused_max_n = value;
     else if (k == "use_bf16_mfma") t.use_bf16_mfma = value;
+    else if (k == "use_wave_gemm") t.use_wave_gemm = value;
     else if (k == "gemm_bm") t.gemm_bm = value;
     else return 1;
     return 0;

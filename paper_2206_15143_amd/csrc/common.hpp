@@ -44,6 +44,8 @@ struct InvertJob {
     int n;
     float damping;
     int *info;       // device int
+    int ldm = 0;     // row pitch of M (0 = n)
+    int ldo = 0;     // row pitch of Minv (0 = n)
 };
 
 // C[M, N] = A^T B with A stored [K, lda] (element (k, m)), B stored [K, ldb].
@@ -97,6 +99,7 @@ struct Tuning {
     long syrk_force_bm = 0;          // 0 = choose
     long use_wave_kernel = 1;        // wave-unit SYRK for aligned row-major fp32 operands
     long use_bf16_mfma = 1;          // row-major bf16 operands: bf16 MFMA kernel instead of widening to fp32
+    long use_wave_gemm = 1;          // wide A^T B products on the wave-unit GEMM
     long use_small_kernel = 1;       // direct MFMA kernel for narrow NCHW operands (d <= 64)
     long fuse_conv3 = 1;             // 3x3/s1/p1 fp32 convs: build A straight from the NCHW input
     long update_bm = 64;             // block tile of the inverse's rank-64 update GEMM (0 = choose; 64 measured best)

@@ -4,9 +4,10 @@
 // inversion.  Symmetric left factors (G_inv) are read as their own transpose,
 // and the first product is written transposed so that the second product is
 // again of the A^T B form: no operand is ever read with a strided K.
-#include "tn_engine.hpp"
+#include "gemm_wave.hpp"
 
 #include <algorithm>
+#include <vector>
 
 namespace kfac {
 
@@ -139,10 +140,73 @@ hipError_t launch_one(const GemmTable &tab, int blocks, hipStream_t s)
 
 }  // namespace
 
+namespace {
+// Products wide enough to fill 144-wide macro tiles go to the wave-unit kernel.  A lower-triangular
+// update qualifies only when its untouched band starts and ends on macro-tile boundaries.
+bool wave_gemm_eligible(const GemmJob &j)
+{
+    if (!tuning().use_wave_gemm || j.mode == kStoreT) return false;
+    if (j.M < 100 || j.N < 100 || j.K < 16) return false;
+    if ((long)j.K * j.lda * 4 > 0x7fffffffl || (long)j.K * j.ldb * 4 > 0x7fffffffl) return false;
+    if (((uintptr_t)j.A) % 4 || ((uintptr_t)j.B) % 4) return false;
+    if (j.mode == kSubLowerSkip)
+        return j.M == j.N && j.p0 % W_MT == 0 && (j.p1 % W_MT == 0 || j.p1 >= j.M);
+    return true;
+}
+
+hipError_t wave_gemm_launch(const GemmJob *jobs, const std::vector<int> &idx, hipStream_t s)
+{
+    GemmWTable tab;
+    tab.count = 0;
+    long blocks = 0;
+    auto flush = [&]() -> hipError_t {
+        if (tab.count == 0) return hipSuccess;
+        KFAC_LAUNCH(KFAC_K_GEMM_WAVE, s, gemm_wave_kernel, dim3((unsigned)blocks), dim3(256), 0, tab);
+        tab.count = 0;
+        blocks = 0;
+        return hipGetLastError();
+    };
+    for (int i : idx) {
+        const GemmJob &j = jobs[i];
+        GemmWProb &p = tab.p[tab.count++];
+        p.A = j.A; p.B = j.B; p.C = j.C;
+        p.lda = (int)j.lda; p.ldb = (int)j.ldb; p.ldc = (int)j.ldc;
+        p.M = j.M; p.N = j.N; p.K = j.K;
+        p.mI = (j.M + W_MT - 1) / W_MT;
+        const int nJ = (j.N + W_MT - 1) / W_MT;
+        p.nJ2 = (nJ + 1) / 2;
+        p.mode = j.mode; p.p0 = j.p0; p.p1 = j.p1;
+        p.blk_start = (int)blocks;
+        if (j.mode == kSubLowerSkip) {
+            for (int I = 0; I < p.mI; ++I) blocks += I / 2 + 1;
+        } else {
+            blocks += (long)p.mI * p.nJ2;
+        }
+        if (tab.count == kMaxProblems) {
+            hipError_t e = flush();
+            if (e != hipSuccess) return e;
+        }
+    }
+    return flush();
+}
+}  // namespace
+
 hipError_t gemm_launch(const GemmJob *jobs, int n, hipStream_t s)
 {
     std::vector<int> cfg(n);
-    for (int i = 0; i < n; ++i) cfg[i] = choose_bm(jobs[i].M, jobs[i].N, jobs[i].mode == kSubLowerSkip);
+    std::vector<int> wave;
+    for (int i = 0; i < n; ++i) {
+        if (jobs[i].M > 0 && jobs[i].N > 0 && jobs[i].K > 0 && wave_gemm_eligible(jobs[i])) {
+            cfg[i] = -1;
+            wave.push_back(i);
+        } else {
+            cfg[i] = choose_bm(jobs[i].M, jobs[i].N, jobs[i].mode == kSubLowerSkip);
+        }
+    }
+    if (!wave.empty()) {
+        hipError_t e = wave_gemm_launch(jobs, wave, s);
+        if (e != hipSuccess) return e;
+    }
     for (int c = 0; c < 4; ++c) {
         GemmTable tab;
         tab.count = 0;

@@ -63,159 +63,117 @@ __global__ __launch_bounds__(256) void sweep_init_kernel(const InvTable tab)
     }
 }
 
-// Inverts the pivot block of step `tab.step` by an unblocked sweep.  The 64 x 64 block lives in
-// registers (thread (i, jq) holds S[i][jq + 4m], m = 0..15); per elimination step only the pivot
-// row and column travel through LDS (double buffered), so a step costs one barrier, 17 LDS reads
-// and 16 FMAs per thread.
-__global__ __launch_bounds__(256) void sweep_pivot_kernel(const InvTable tab)
+// ---- two-level blocked sweep for the large factors -------------------------------------------
+// Outer pivot blocks of PB = 288 rows (two 144-wide macro tiles of the wave GEMM).  Per outer step:
+// the pivot block is inverted by the one-launch-per-step sweep above (a 288 x 288 problem), the old
+// panel is gathered K-major into V, W = V P and the rank-288 update of the rest of the triangle run
+// on the wave-unit GEMM (gemm_wave.hpp), and the new panel and -P are scattered back in place.
+constexpr int PB = 288;
+
+struct BlkProb {
+    float *W;          // working matrix [n, n]
+    float *Vt;         // [PB, ldv]
+    float *Wt;         // [PB, ldv]
+    const float *P;    // [PB, PB] inverse of the pivot block
+    int *info;
+    const int *ninfo;  // status of the pivot block inversion (0 or 1-based pivot index inside the block)
+    int n, ldv, p0, bs;
+    int blk_start;
+};
+
+struct BlkTable {
+    int count;
+    BlkProb p[32];
+};
+
+// V[kk][gi] = old panel, K-major: row panel (gi < p0) copied, column panel (gi >= p0 + bs) transposed
+// through LDS, pivot columns zero.  One workgroup per 32 x 32 tile.
+__global__ __launch_bounds__(256) void blk_gather_kernel(const BlkTable tab)
 {
-    __shared__ float colb[2][NB];
-    __shared__ float rowb[2][NB];
-    const InvProb &pr = tab.p[blockIdx.x];
-    const int p0 = tab.step * NB;
-    if (p0 >= pr.n) return;
-    const int bs = min(NB, pr.n - p0);
-    const int tid = threadIdx.x;
-    const int i = tid >> 2, jq = tid & 3;
-    const long n = pr.n;
-
-    float s[NB / 4];
-#pragma unroll
-    for (int m = 0; m < NB / 4; ++m) {
-        const int j = jq + 4 * m;
-        float v = (i == j) ? 1.f : 0.f;      // identity padding keeps the tail block well defined
-        if (i < bs && j < bs) v = (j <= i) ? pr.W[(p0 + i) * n + p0 + j] : pr.W[(p0 + j) * n + p0 + i];
-        s[m] = v;
-    }
-    if (jq == 0) colb[0][i] = s[0];
-    if (i == 0) {
-#pragma unroll
-        for (int m = 0; m < NB / 4; ++m) rowb[0][jq + 4 * m] = s[m];
-    }
-    __syncthreads();
-
-    int fail = 0;
-    for (int k = 0; k < bs; ++k) {
-        const int b = k & 1;
-        const float p = rowb[b][k];
-        if (!(p > 0.f) && fail == 0) fail = p0 + k + 1;
-        const float ip = __builtin_amdgcn_rcpf(p);   // 1 ulp reciprocal: far below the fp32 error of the sweep
-        const float ci = colb[b][i];
-        const bool prow = (i == k);
-        const float cip = ci * ip;
-        // selects instead of branches: the four cases (pivot, pivot row, pivot column, rest) differ per element
-#pragma unroll
-        for (int m = 0; m < NB / 4; ++m) {
-            const int j = jq + 4 * m;
-            const float rk = rowb[b][j];
-            const bool pcol = (j == k);
-            const float rest = s[m] - (ci * rk) * ip;
-            const float on_row = pcol ? -ip : rk * ip;
-            const float off_row = pcol ? cip : rest;
-            s[m] = prow ? on_row : off_row;
-        }
-        // publish the next pivot column and row
-        const int kn = k + 1;
-        float cv = s[0];
-#pragma unroll
-        for (int m = 1; m < NB / 4; ++m) cv = (m == (kn >> 2)) ? s[m] : cv;
-        if (jq == (kn & 3)) colb[b ^ 1][i] = cv;
-        if (i == kn) {
-#pragma unroll
-            for (int m = 0; m < NB / 4; ++m) rowb[b ^ 1][jq + 4 * m] = s[m];
-        }
-        __syncthreads();
-    }
-#pragma unroll
-    for (int m = 0; m < NB / 4; ++m) {
-        const int j = jq + 4 * m;
-        const bool in = (i < bs && j < bs);
-        pr.P[i * NB + j] = in ? -s[m] : 0.f;
-        if (in && j <= i) pr.W[(p0 + i) * n + p0 + j] = s[m];
-    }
-    if (fail != 0 && tid == 0 && *pr.info == 0) *pr.info = fail;
-}
-
-// One workgroup per 64 rows of the panel of step `tab.step`: V = old panel rows (transposed to
-// K-major), W^T = P V^T on the MFMA units (P is symmetric, so it is its own K-major operand), then
-// V^T and W^T go to the workspace for the rank-64 update and W replaces the panel in place.
-__global__ __launch_bounds__(256) void sweep_panel_kernel(const InvTable tab)
-{
-    typedef Tile<2, 2> T;                          // 64 x 64 output, four waves of 32 x 32
-    constexpr int PITCH = T::PITCH;                // 80: conflict-free K-major operand reads
-    __shared__ float Ps[NB * PITCH];               // [k][m]
-    __shared__ float Vs[NB * PITCH];               // [k][i]
+    __shared__ float t[32][33];
     int pi = 0;
     while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].blk_start) ++pi;
-    const InvProb &pr = tab.p[pi];
-    const int chunk = blockIdx.x - pr.blk_start;
-    const int p0 = tab.step * NB;
-    if (p0 >= pr.n) return;
-    const int bs = min(NB, pr.n - p0);
-    const int i0 = chunk * NB;
-    const int tid = threadIdx.x;
-    const int n = pr.n;
-
-    if (i0 == p0) {   // the pivot rows themselves: zero columns in V and W
-        for (int e = tid; e < NB * NB; e += 256) {
-            const int kk = e / NB, i = e % NB;
-            if (i0 + i < n) {
-                pr.Vt[(long)kk * pr.ldv + i0 + i] = 0.f;
-                pr.Wt[(long)kk * pr.ldv + i0 + i] = 0.f;
-            }
+    const BlkProb &pr = tab.p[pi];
+    const int local = blockIdx.x - pr.blk_start;
+    const int kt = (pr.bs + 31) / 32;
+    const int gt = local / kt, kq = local - gt * kt;
+    const int g0 = gt * 32, k0 = kq * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const long n = pr.n;
+    const int p0 = pr.p0, p1 = pr.p0 + pr.bs;
+    // p0 and p1 are multiples of 32 (or p1 = n): a tile lies wholly in one of the three regions
+    if (g0 < p0) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int kk = k0 + ty + 8 * r, gi = g0 + tx;
+            if (kk < pr.bs && gi < pr.n) pr.Vt[(long)kk * pr.ldv + gi] = pr.W[(p0 + kk) * n + gi];
         }
-        return;
+    } else if (g0 >= p1) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int gi = g0 + ty + 8 * r, kk = k0 + tx;
+            t[ty + 8 * r][tx] = (gi < pr.n && kk < pr.bs) ? pr.W[gi * n + p0 + kk] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int kk = k0 + ty + 8 * r, gi = g0 + tx;
+            if (kk < pr.bs && gi < pr.n) pr.Vt[(long)kk * pr.ldv + gi] = t[tx][ty + 8 * r];
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int kk = k0 + ty + 8 * r, gi = g0 + tx;
+            if (kk < pr.bs && gi < pr.n) pr.Vt[(long)kk * pr.ldv + gi] = 0.f;
+        }
     }
-    for (int e = tid; e < NB * NB; e += 256) Ps[(e / NB) * PITCH + (e % NB)] = pr.P[e];
-    if (i0 > p0) {    // column panel: M[gi][p0 + kk], contiguous in kk
-        for (int e = tid; e < NB * NB; e += 256) {
-            const int i = e / NB, kk = e % NB;
-            const int gi = i0 + i;
-            Vs[kk * PITCH + i] = (gi < n && kk < bs) ? pr.W[(long)gi * n + p0 + kk] : 0.f;
+}
+
+// New panel W = V P back in place (row panel copied, column panel transposed), pivot block <- -P,
+// and the pivot-block status folded into the matrix's info.
+__global__ __launch_bounds__(256) void blk_scatter_kernel(const BlkTable tab)
+{
+    __shared__ float t[32][33];
+    int pi = 0;
+    while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].blk_start) ++pi;
+    const BlkProb &pr = tab.p[pi];
+    const int local = blockIdx.x - pr.blk_start;
+    const int kt = (pr.bs + 31) / 32;
+    const int gt = local / kt, kq = local - gt * kt;
+    const int g0 = gt * 32, k0 = kq * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const long n = pr.n;
+    const int p0 = pr.p0, p1 = pr.p0 + pr.bs;
+    if (local == 0 && threadIdx.x == 0) {
+        const int f = *pr.ninfo;
+        if (f != 0 && *pr.info == 0) *pr.info = p0 + f;
+    }
+    if (g0 < p0) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int kk = k0 + ty + 8 * r, gi = g0 + tx;
+            if (kk < pr.bs && gi < pr.n) pr.W[(p0 + kk) * n + gi] = pr.Wt[(long)kk * pr.ldv + gi];
         }
-    } else {          // row panel: M[p0 + kk][gi], contiguous in gi
-        for (int e = tid; e < NB * NB; e += 256) {
-            const int kk = e / NB, i = e % NB;
-            const int gi = i0 + i;
-            Vs[kk * PITCH + i] = (gi < n && kk < bs) ? pr.W[(long)(p0 + kk) * n + gi] : 0.f;
+    } else if (g0 >= p1) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int kk = k0 + ty + 8 * r, gi = g0 + tx;
+            t[ty + 8 * r][tx] = (kk < pr.bs && gi < pr.n) ? pr.Wt[(long)kk * pr.ldv + gi] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int gi = g0 + ty + 8 * r, kk = k0 + tx;
+            if (gi < pr.n && kk < pr.bs) pr.W[gi * n + p0 + kk] = t[tx][ty + 8 * r];
+        }
+    } else {
+        // pivot block: rows g0.., columns k0..; lower part <- -P
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int a = g0 - p0 + ty + 8 * r, b = k0 + tx;
+            if (a < pr.bs && b <= a) pr.W[(p0 + a) * n + p0 + b] = -pr.P[a * PB + b];
         }
     }
-    __syncthreads();
-
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    floatx4 acc[T::WT][T::WT];
-#pragma unroll
-    for (int a = 0; a < T::WT; ++a)
-#pragma unroll
-        for (int b = 0; b < T::WT; ++b) acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int q = 0; q < NB / T::KT; ++q)
-        mma_stage<T, kRows, kRows, false>(Ps + q * T::KT * PITCH, Vs + q * T::KT * PITCH, wm, wn, lane, acc);
-
-    // acc[ti][tj][v] = W^T[m][i], m = (wm*2+ti)*16 + 4*lk + v, i = (wn*2+tj)*16 + lr
-    const int lr = lane & 15, lk = lane >> 4;
-#pragma unroll
-    for (int ti = 0; ti < T::WT; ++ti)
-#pragma unroll
-        for (int tj = 0; tj < T::WT; ++tj) {
-            const int i = (wn * T::WT + tj) * 16 + lr;
-            const int gi = i0 + i;
-            if (gi >= n) continue;
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int m = (wm * T::WT + ti) * 16 + 4 * lk + v;
-                const float w = acc[ti][tj][v];
-                pr.Vt[(long)m * pr.ldv + gi] = Vs[m * PITCH + i];
-                pr.Wt[(long)m * pr.ldv + gi] = w;
-                if (m < bs) {
-                    if (i0 > p0)
-                        pr.W[(long)gi * n + p0 + m] = w;
-                    else
-                        pr.W[(long)(p0 + m) * n + gi] = w;
-                }
-            }
-        }
 }
 
 // out = -W mirrored to both triangles (in place)
@@ -237,8 +195,15 @@ __global__ __launch_bounds__(256) void sweep_finish_kernel(const InvTable tab)
 }
 
 namespace {
-size_t job_ws_floats(int n) { return 2 * (size_t)NB * NB + 2 * (size_t)NB * ((n + 3) / 4 * 4); }
-size_t table_bytes(int n) { return align_up((size_t)n * sizeof(InvProbF), 256); }
+bool takes_fused(int n) { return n <= tuning().invert_fused_max_n; }
+size_t fused_ws_floats(int n) { return 2 * (size_t)NB * NB + 2 * (size_t)NB * ((n + 3) / 4 * 4); }
+// large matrices: V, W panels, P, the workspace of the nested pivot-block inversion, its status word
+size_t job_ws_floats(int n)
+{
+    if (takes_fused(n)) return fused_ws_floats(n);
+    return 2 * (size_t)PB * ((n + 3) / 4 * 4) + (size_t)PB * PB + fused_ws_floats(PB) + 64;
+}
+size_t table_bytes(int n) { return align_up((size_t)2 * n * sizeof(InvProbF), 256); }
 
 // One-launch-per-step sweep for the matrices listed in `idx` (sorted by order, largest first).
 hipError_t fused_launch(const InvertJob *jobs, const std::vector<int> &idx, const std::vector<size_t> &offs,
@@ -257,6 +222,8 @@ hipError_t fused_launch(const InvertJob *jobs, const std::vector<int> &idx, cons
             p.M = j.M; p.W = j.Minv; p.info = j.info; p.n = j.n; p.damping = j.damping;
             p.ldv = (j.n + 3) / 4 * 4;
             p.nblk = (j.n + FNB - 1) / FNB;
+            p.ldm = j.ldm > 0 ? j.ldm : j.n;
+            p.ldw = j.ldo > 0 ? j.ldo : j.n;
             p.P = ws;
             p.Vt = ws + 2 * FNB * FNB;
         }
@@ -313,6 +280,149 @@ hipError_t fused_launch(const InvertJob *jobs, const std::vector<int> &idx, cons
     }
     return hipSuccess;
 }
+// Two-level blocked sweep of the matrices listed in `idx` (sorted by order, largest first).
+hipError_t blocked_launch(const InvertJob *jobs, const std::vector<int> &idx, const std::vector<size_t> &offs,
+                          void *work, InvProbF *dtab, hipStream_t s)
+{
+    const int total = (int)idx.size();
+    struct Big { float *Vt, *Wt, *P, *nws; int *ninfo; int ldv; };
+    std::vector<Big> big(total);
+    for (int k = 0; k < total; ++k) {
+        const InvertJob &j = jobs[idx[k]];
+        float *ws = reinterpret_cast<float *>(static_cast<char *>(work) + offs[idx[k]]);
+        Big &b = big[k];
+        b.ldv = (j.n + 3) / 4 * 4;
+        b.Vt = ws;
+        b.Wt = b.Vt + (size_t)PB * b.ldv;
+        b.P = b.Wt + (size_t)PB * b.ldv;
+        b.nws = b.P + (size_t)PB * PB;
+        b.ninfo = reinterpret_cast<int *>(b.nws + fused_ws_floats(PB));
+    }
+    // W = M + damping I (lower), info = 0
+    for (int g0 = 0; g0 < total; g0 += kMaxProblems) {
+        InvTable tab;
+        tab.count = std::min(kMaxProblems, total - g0);
+        tab.step = 0;
+        int blocks = 0;
+        for (int k = 0; k < tab.count; ++k) {
+            const InvertJob &j = jobs[idx[g0 + k]];
+            InvProb &p = tab.p[k];
+            p.M = j.M; p.W = j.Minv; p.info = j.info; p.n = j.n; p.damping = j.damping;
+            p.ldv = big[g0 + k].ldv; p.P = nullptr; p.Vt = nullptr; p.Wt = nullptr;
+            p.blk_start = blocks;
+            blocks += (int)(((long)j.n * j.n + 4095) / 4096);
+        }
+        KFAC_LAUNCH(KFAC_K_INV_INIT, s, sweep_init_kernel, dim3(blocks), dim3(256), 0, tab);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    const int steps = (jobs[idx[0]].n + PB - 1) / PB;
+    std::vector<InvertJob> nested;
+    std::vector<int> nidx;
+    std::vector<size_t> noffs;
+    std::vector<GemmJob> gp, gu;
+    for (int st = 0; st < steps; ++st) {
+        const int p0 = st * PB;
+        int active = 0;
+        while (active < total && jobs[idx[active]].n > p0) ++active;
+        // 1. inverse of the pivot blocks (in their current, updated state) -> P
+        nested.assign(active, InvertJob());
+        nidx.resize(active);
+        noffs.resize(active);
+        for (int k = 0; k < active; ++k) {
+            const InvertJob &j = jobs[idx[k]];
+            InvertJob &q = nested[k];
+            q.M = j.Minv + (size_t)p0 * j.n + p0;
+            q.Minv = big[k].P;
+            q.n = std::min(PB, j.n - p0);
+            q.damping = 0.f;
+            q.info = big[k].ninfo;
+            q.ldm = j.n;
+            q.ldo = PB;
+            nidx[k] = k;
+            noffs[k] = (size_t)(reinterpret_cast<char *>(big[k].nws) - static_cast<char *>(work));
+        }
+        // nested problems are grouped by order (all PB except possibly the last block of a matrix)
+        std::stable_sort(nidx.begin(), nidx.end(), [&](int a, int b) { return nested[a].n > nested[b].n; });
+        hipError_t e = fused_launch(nested.data(), nidx, noffs, work, dtab, s);
+        if (e != hipSuccess) return e;
+        // 2. gather V, 3. W^T = P V^T, 4. update, 5. scatter
+        for (int g0 = 0; g0 < active; g0 += 32) {
+            BlkTable tab;
+            tab.count = std::min(32, active - g0);
+            int blocks = 0;
+            for (int k = 0; k < tab.count; ++k) {
+                const InvertJob &j = jobs[idx[g0 + k]];
+                BlkProb &p = tab.p[k];
+                p.W = j.Minv; p.Vt = big[g0 + k].Vt; p.Wt = big[g0 + k].Wt; p.P = big[g0 + k].P;
+                p.info = j.info; p.ninfo = big[g0 + k].ninfo;
+                p.n = j.n; p.ldv = big[g0 + k].ldv; p.p0 = p0; p.bs = std::min(PB, j.n - p0);
+                p.blk_start = blocks;
+                blocks += ((j.n + 31) / 32) * ((p.bs + 31) / 32);
+            }
+            KFAC_LAUNCH(KFAC_K_INV_PANEL, s, blk_gather_kernel, dim3(blocks), dim3(256), 0, tab);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+        gp.assign(active, GemmJob());
+        gu.assign(active, GemmJob());
+        int nupd = 0;
+        for (int k = 0; k < active; ++k) {
+            const InvertJob &j = jobs[idx[k]];
+            const int bs = std::min(PB, j.n - p0);
+            GemmJob &a = gp[k];
+            a.A = big[k].P; a.B = big[k].Vt; a.C = big[k].Wt;
+            a.M = bs; a.N = j.n; a.K = bs; a.lda = PB; a.ldb = big[k].ldv; a.ldc = big[k].ldv;
+            a.mode = kStore; a.p0 = a.p1 = 0;
+            if (j.n > PB) {
+                GemmJob &u = gu[nupd++];
+                u.A = big[k].Wt; u.B = big[k].Vt; u.C = j.Minv;
+                u.M = j.n; u.N = j.n; u.K = bs; u.lda = big[k].ldv; u.ldb = big[k].ldv; u.ldc = j.n;
+                u.mode = kSubLowerSkip; u.p0 = p0; u.p1 = p0 + bs;
+            }
+        }
+        e = gemm_launch(gp.data(), active, s);
+        if (e != hipSuccess) return e;
+        e = gemm_launch(gu.data(), nupd, s);
+        if (e != hipSuccess) return e;
+        for (int g0 = 0; g0 < active; g0 += 32) {
+            BlkTable tab;
+            tab.count = std::min(32, active - g0);
+            int blocks = 0;
+            for (int k = 0; k < tab.count; ++k) {
+                const InvertJob &j = jobs[idx[g0 + k]];
+                BlkProb &p = tab.p[k];
+                p.W = j.Minv; p.Vt = big[g0 + k].Vt; p.Wt = big[g0 + k].Wt; p.P = big[g0 + k].P;
+                p.info = j.info; p.ninfo = big[g0 + k].ninfo;
+                p.n = j.n; p.ldv = big[g0 + k].ldv; p.p0 = p0; p.bs = std::min(PB, j.n - p0);
+                p.blk_start = blocks;
+                blocks += ((j.n + 31) / 32) * ((p.bs + 31) / 32);
+            }
+            KFAC_LAUNCH(KFAC_K_INV_PANEL, s, blk_scatter_kernel, dim3(blocks), dim3(256), 0, tab);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+    }
+    // negate and mirror
+    for (int g0 = 0; g0 < total; g0 += kMaxProblems) {
+        InvTable tab;
+        tab.count = std::min(kMaxProblems, total - g0);
+        tab.step = 0;
+        int blocks = 0;
+        for (int k = 0; k < tab.count; ++k) {
+            const InvertJob &j = jobs[idx[g0 + k]];
+            InvProb &p = tab.p[k];
+            p.M = j.M; p.W = j.Minv; p.info = j.info; p.n = j.n; p.damping = j.damping;
+            p.ldv = big[g0 + k].ldv; p.P = nullptr; p.Vt = nullptr; p.Wt = nullptr;
+            p.blk_start = blocks;
+            blocks += (int)(((long)j.n * j.n + 4095) / 4096);
+        }
+        KFAC_LAUNCH(KFAC_K_INV_FINISH, s, sweep_finish_kernel, dim3(blocks), dim3(256), 0, tab);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
 }  // namespace
 
 size_t invert_workspace_bytes(const InvertJob *jobs, int n)
@@ -331,92 +441,22 @@ hipError_t invert_launch(const InvertJob *jobs, int n_all, void *work, size_t wo
         offs[i] = off;
         off += align_up(job_ws_floats(jobs[i].n) * sizeof(float), 256);
     }
-    // largest matrices first so that one launch group holds similar step counts
-    std::vector<int> order, fused;
-    for (int i = 0; i < n_all; ++i) (jobs[i].n <= tuning().invert_fused_max_n ? fused : order).push_back(i);
+    // largest matrices first so that the matrices still active at a step form a prefix
+    std::vector<int> large, fused;
+    for (int i = 0; i < n_all; ++i) (takes_fused(jobs[i].n) ? fused : large).push_back(i);
     auto by_size = [&](int a, int b) { return jobs[a].n > jobs[b].n; };
-    std::stable_sort(order.begin(), order.end(), by_size);
+    std::stable_sort(large.begin(), large.end(), by_size);
     std::stable_sort(fused.begin(), fused.end(), by_size);
-    const int n = (int)order.size();
-
-    for (int g0 = 0; g0 < n; g0 += kMaxProblems) {
-        const int cnt = std::min(kMaxProblems, n - g0);
-        InvTable tab;
-        tab.count = cnt;
-        tab.step = 0;
-        int nmax = 0;
-        for (int k = 0; k < cnt; ++k) {
-            const InvertJob &j = jobs[order[g0 + k]];
-            InvProb &p = tab.p[k];
-            float *ws = reinterpret_cast<float *>(static_cast<char *>(work) + offs[order[g0 + k]]);
-            p.M = j.M; p.W = j.Minv; p.info = j.info; p.n = j.n; p.damping = j.damping;
-            p.ldv = (j.n + 3) / 4 * 4;
-            p.P = ws;
-            p.Vt = ws + NB * NB;
-            p.Wt = p.Vt + (size_t)NB * p.ldv;
-            nmax = std::max(nmax, j.n);
-        }
-        // element-wise kernels: 4096 elements per block
-        int blocks = 0;
-        for (int k = 0; k < cnt; ++k) {
-            tab.p[k].blk_start = blocks;
-            blocks += (int)(((long)tab.p[k].n * tab.p[k].n + 4095) / 4096);
-        }
-        const int ew_blocks = blocks;
-        KFAC_LAUNCH(KFAC_K_INV_INIT, s, sweep_init_kernel, dim3(ew_blocks), dim3(256), 0, tab);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-
-        const int steps = (nmax + NB - 1) / NB;
-        for (int st = 0; st < steps; ++st) {
-            tab.step = st;
-            const int p0 = st * NB;
-            // matrices are sorted by size: those still active form a prefix
-            int active = 0;
-            while (active < cnt && tab.p[active].n > p0) ++active;
-            InvTable t2 = tab;
-            t2.count = active;
-            KFAC_LAUNCH(KFAC_K_INV_PIVOT, s, sweep_pivot_kernel, dim3(active), dim3(256), 0, t2);
-            e = hipGetLastError();
-            if (e != hipSuccess) return e;
-            // panel + update only where something lies outside the pivot block
-            int act2 = 0;
-            while (act2 < active && tab.p[act2].n > NB) ++act2;
-            if (act2 == 0) continue;
-            t2.count = act2;
-            blocks = 0;
-            for (int k = 0; k < act2; ++k) {
-                t2.p[k].blk_start = blocks;
-                blocks += (t2.p[k].n + NB - 1) / NB;
-            }
-            KFAC_LAUNCH(KFAC_K_INV_PANEL, s, sweep_panel_kernel, dim3(blocks), dim3(256), 0, t2);
-            e = hipGetLastError();
-            if (e != hipSuccess) return e;
-            std::vector<GemmJob> gj(act2);
-            for (int k = 0; k < act2; ++k) {
-                const InvProb &p = t2.p[k];
-                GemmJob &g = gj[k];
-                g.A = p.Wt; g.B = p.Vt; g.C = p.W;
-                g.M = p.n; g.N = p.n; g.K = NB;
-                g.lda = p.ldv; g.ldb = p.ldv; g.ldc = p.n;
-                g.mode = kSubLowerSkip;
-                g.p0 = p0;
-                g.p1 = std::min(p.n, p0 + NB);
-            }
-            e = gemm_launch(gj.data(), act2, s);
-            if (e != hipSuccess) return e;
-        }
-        blocks = 0;
-        for (int k = 0; k < cnt; ++k) {
-            tab.p[k].blk_start = blocks;
-            blocks += (int)(((long)tab.p[k].n * tab.p[k].n + 4095) / 4096);
-        }
-        KFAC_LAUNCH(KFAC_K_INV_FINISH, s, sweep_finish_kernel, dim3(blocks), dim3(256), 0, tab);
-        e = hipGetLastError();
+    InvProbF *dtab = static_cast<InvProbF *>(work);
+    if (!fused.empty()) {
+        hipError_t e = fused_launch(jobs, fused, offs, work, dtab, s);
         if (e != hipSuccess) return e;
     }
-    if (!fused.empty())
-        return fused_launch(jobs, fused, offs, work, static_cast<InvProbF *>(work), s);
+    if (!large.empty()) {
+        // the nested pivot-block inversions use the second half of the descriptor table
+        hipError_t e = blocked_launch(jobs, large, offs, work, dtab + n_all, s);
+        if (e != hipSuccess) return e;
+    }
     return hipSuccess;
 }
 

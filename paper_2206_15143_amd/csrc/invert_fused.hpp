@@ -43,6 +43,7 @@ struct InvProbF {
     int ldv;          // n rounded up to 4
     float damping;
     int nblk;
+    int ldm, ldw;     // row pitches of M and W
 };
 
 struct InvUpload {
@@ -157,7 +158,7 @@ __global__ __launch_bounds__(256) void fsweep_pivot0_kernel(const InvSeq q)
     const int tid = threadIdx.x;
     const int i = tid >> 2, jq = tid & 3;
     const int bs = min(FNB, pr.n);
-    const long n = pr.n;
+    const long ldm = pr.ldm, ldw = pr.ldw;
     float s[16];
 #pragma unroll
     for (int m = 0; m < 16; ++m) {
@@ -165,7 +166,7 @@ __global__ __launch_bounds__(256) void fsweep_pivot0_kernel(const InvSeq q)
         float v = (i == j) ? 1.f : 0.f;
         if (i < bs && j < bs) {
             const int a = max(i, j), b = min(i, j);
-            v = pr.M[a * n + b] + (a == b ? pr.damping : 0.f);
+            v = pr.M[a * ldm + b] + (a == b ? pr.damping : 0.f);
         }
         s[m] = v;
     }
@@ -177,8 +178,8 @@ __global__ __launch_bounds__(256) void fsweep_pivot0_kernel(const InvSeq q)
         const bool in = (i < bs && j < bs);
         pr.P[i * FNB + j] = in ? -s[m] : 0.f;
         if (in && j <= i) {
-            pr.W[i * n + j] = whole ? -s[m] : s[m];
-            if (whole) pr.W[j * n + i] = -s[m];
+            pr.W[i * ldw + j] = whole ? -s[m] : s[m];
+            if (whole) pr.W[j * ldw + i] = -s[m];
         }
     }
     if (tid == 0) *pr.info = (fail <= bs) ? fail : 0;
@@ -210,6 +211,7 @@ __global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
     }
     const int tid = threadIdx.x;
     const int n = pr.n, ldv = pr.ldv;
+    const long ldm = pr.ldm, ldw = pr.ldw;
     const bool first = (K == 0), last = (K1 == nblk);
     if (bi == K && bj == K) {
         // the pivot block itself was finished by the previous launch; on the last step it still has to
@@ -219,9 +221,9 @@ __global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
             for (int e = tid; e < FNB * FNB; e += 256) {
                 const int i = e >> 6, j = e & 63;
                 if (i < bs && j <= i) {
-                    const float v = -pr.W[(long)(p0 + i) * n + p0 + j];
-                    pr.W[(long)(p0 + i) * n + p0 + j] = v;
-                    pr.W[(long)(p0 + j) * n + p0 + i] = v;
+                    const float v = -pr.W[(long)(p0 + i) * ldw + p0 + j];
+                    pr.W[(long)(p0 + i) * ldw + p0 + j] = v;
+                    pr.W[(long)(p0 + j) * ldw + p0 + i] = v;
                 }
             }
         }
@@ -239,14 +241,39 @@ __global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
     const int ra = panel ? (bi == K ? bj : bi) : bi;   // block whose V goes to Va
     const int rb = bj;
 
+    // the tile's current values: fetched now, needed after the two products
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int lr = lane & 15, lk = lane >> 4;
+    const bool diag = (bi == bj);
+    float oldc[T::WT][T::WT][4];
+    if (!panel) {
+#pragma unroll
+        for (int ti = 0; ti < T::WT; ++ti)
+#pragma unroll
+            for (int tj = 0; tj < T::WT; ++tj) {
+                const int gb = bj * FNB + (wn * T::WT + tj) * 16 + lr;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int ga = bi * FNB + (wm * T::WT + ti) * 16 + 4 * lk + v;
+                    const bool ok = (ga < n && gb < n && (!diag || gb <= ga));
+                    float o = 0.f;
+                    if (ok)
+                        o = first ? pr.M[(long)ga * ldm + gb] + (ga == gb ? pr.damping : 0.f)
+                                  : pr.W[(long)ga * ldw + gb];
+                    oldc[ti][tj][v] = o;
+                }
+            }
+    }
+
     // ---- stage P, V_a (and V_b) ----
     if (first) {
         // step 0: the panel is column block 0 of the input itself (blocks below the diagonal carry no damping)
         for (int e = tid; e < FNB * FNB; e += 256) {
             const int c = e >> 6, k = e & 63;
             const int ga = ra * FNB + c, gb = rb * FNB + c;
-            Va[k * PITCH + c] = (ga < n) ? pr.M[(long)ga * n + k] : 0.f;
-            if (!panel && rb != ra) Vb[k * PITCH + c] = (gb < n) ? pr.M[(long)gb * n + k] : 0.f;
+            Va[k * PITCH + c] = (ga < n) ? pr.M[(long)ga * ldm + k] : 0.f;
+            if (!panel && rb != ra) Vb[k * PITCH + c] = (gb < n) ? pr.M[(long)gb * ldm + k] : 0.f;
         }
     }
     for (int e = tid; e < FNB * FNB / 4; e += 256) {
@@ -276,9 +303,6 @@ __global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
     }
     __syncthreads();
 
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int lr = lane & 15, lk = lane >> 4;
     floatx4 acc[T::WT][T::WT];
 #pragma unroll
     for (int a = 0; a < T::WT; ++a)
@@ -305,11 +329,11 @@ __global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
                     const float w = acc[ti][tj][v];
                     const bool ok = (gc < n && m < bs);
                     if (ok) {
-                        if (below) pr.W[(long)gc * n + p0 + m] = w;
-                        else if (!last) pr.W[(long)(p0 + m) * n + gc] = w;
+                        if (below) pr.W[(long)gc * ldw + p0 + m] = w;
+                        else if (!last) pr.W[(long)(p0 + m) * ldw + gc] = w;
                         else {   // last step: the row panel is final
-                            pr.W[(long)(p0 + m) * n + gc] = -w;
-                            pr.W[(long)gc * n + p0 + m] = -w;
+                            pr.W[(long)(p0 + m) * ldw + gc] = -w;
+                            pr.W[(long)gc * ldw + p0 + m] = -w;
                         }
                     }
                     // V'[kk = c][column p0 + m] = M[p1 + c][p0 + m]; rows kk >= bs1 are zero
@@ -343,7 +367,6 @@ __global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
         mma_stage<T, kRows, kRows, false>(Ps + s4 * T::KT * PITCH, Vj + s4 * T::KT * PITCH, wm, wn, lane, acc);
 
     // acc[ti][tj][v] = (W_i V_j^T)[a][b], a = (wm*2+ti)*16 + 4*lk + v, b = (wn*2+tj)*16 + lr
-    const bool diag = (bi == bj);
     const bool next_col = (bj == K1 && bi > K1);    // column panel of the next pivot: V'[b][ga]
     const bool next_row = (bi == K1 && bj < K1);    // row panel of the next pivot: V'[a][gb]
     const bool next_piv = (bi == K1 && bj == K1);
@@ -361,14 +384,12 @@ __global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
                 const bool ok = (ga < n && gb < n && (!diag || gb <= ga));
                 float c = 0.f;
                 if (ok) {
-                    const float old = first ? pr.M[(long)ga * n + gb] + (ga == gb ? pr.damping : 0.f)
-                                            : pr.W[(long)ga * n + gb];
-                    c = old - acc[ti][tj][v];
+                    c = oldc[ti][tj][v] - acc[ti][tj][v];
                     if (last) {
-                        pr.W[(long)ga * n + gb] = -c;
-                        pr.W[(long)gb * n + ga] = -c;
+                        pr.W[(long)ga * ldw + gb] = -c;
+                        pr.W[(long)gb * ldw + ga] = -c;
                     } else if (!next_piv) {
-                        pr.W[(long)ga * n + gb] = c;
+                        pr.W[(long)ga * ldw + gb] = c;
                     }
                 }
                 if (next_col && ga < n) Vn[(long)b * ldv + ga] = ok ? c : 0.f;
@@ -396,7 +417,7 @@ __global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
             const int j = jq + 4 * m;
             const bool in = (i < bs1 && j < bs1);
             Pn[i * FNB + j] = in ? -s[m] : 0.f;
-            if (in && j <= i) pr.W[(long)(p1 + i) * n + p1 + j] = s[m];
+            if (in && j <= i) pr.W[(long)(p1 + i) * ldw + p1 + j] = s[m];
         }
         // launches of one sequence are ordered, so the first failing pivot wins
         if (fail != 0 && fail <= bs1 && tid == 0 && *pr.info == 0) *pr.info = p1 + fail;

@@ -19,34 +19,6 @@
 #include <algorithm>
 #include <cmath>
 
-namespace kfac {
-
-struct SyrkProb {
-    const void *x;
-    float *partial;   // [splits][nblk][BM*BM] tiles, then [splits][nb][BM] column sums
-    float *F;
-    long K;
-    long ld;
-    int d;            // core columns
-    int hw, ctot;
-    int nb;           // block tiles per side
-    int splits;
-    int tiles_per_split;
-    int blk_start;    // first flattened block of this problem (partial kernel)
-    int red_start;    // first flattened block of this problem (reduce kernel)
-    int vec;
-    int has_bias;
-    float scale, decay;
-};
-
-struct SyrkTable {
-    int count;
-    int debug;   // measurement switches of the wave kernel (0 in normal use): 1 = no MFMAs, 2 = no data loads
-    SyrkProb p[kMaxProblems];
-};
-
-}  // namespace kfac
-
 #include "syrk_wave.hpp"
 #include "syrk_conv3.hpp"
 #include "syrk_small.hpp"

@@ -152,6 +152,57 @@ def test_inverse_sizes(n):
     assert np.allclose(G_inv.cpu().numpy(), np.eye(3) / (1 + lam), rtol=1e-6)
 
 
+@pytest.mark.parametrize("n", [130, 288, 289, 400, 577, 700, 1000])
+def test_inverse_two_level_blocked_path(n):
+    # orders above the knob take the two-level blocked sweep (288-row outer blocks, wave-unit GEMM
+    # updates); lowering the knob exercises it at sizes the oracle inverts in a moment
+    gen = np.random.default_rng(100 + n)
+    X = gen.standard_normal((n + 7, n))
+    M = (X.T @ X / (n + 7)).astype(np.float32)
+    lam = 0.05
+    desc = kf.LayerDesc.linear(n, 70, has_bias=False)
+    H = gen.standard_normal((90, 70))
+    G = (H.T @ H / 90).astype(np.float32)
+    A_inv = torch.full((n, n), float("nan"), device=gu.DEV)
+    G_inv = torch.full((70, 70), float("nan"), device=gu.DEV)
+    info = torch.full((2,), -1, dtype=torch.int32, device=gu.DEV)
+    kf.kfac_tune("invert_fused_max_n", 100)
+    try:
+        ws = gu.workspace(kf.kfac_workspace_bytes(desc, 8))
+        kf.kfac_invert(desc, gu.to_dev(M), gu.to_dev(G), lam, lam, A_inv, G_inv, info, ws)
+        torch.cuda.synchronize()
+    finally:
+        kf.kfac_tune("invert_fused_max_n", 1280)
+    assert list(info.cpu().numpy()) == [0, 0]
+    got = A_inv.cpu().numpy()
+    assert gu.rel_fro(got, orc.inverse(M.astype(np.float64), lam)) < 1e-4
+    assert np.array_equal(got, got.T)
+    assert gu.rel_fro(G_inv.cpu().numpy(), orc.inverse(G.astype(np.float64), lam)) < 1e-4
+
+
+def test_not_positive_definite_in_a_late_block_is_flagged_by_the_blocked_path():
+    n = 700
+    gen = np.random.default_rng(5)
+    X = gen.standard_normal((n + 9, n))
+    M = (X.T @ X / (n + 9)).astype(np.float32)
+    M[650, 650] = -5.0          # makes a pivot in the third outer block negative
+    desc = kf.LayerDesc.linear(n, 3, has_bias=False)
+    A_inv = torch.empty((n, n), device=gu.DEV)
+    G_inv = torch.empty((3, 3), device=gu.DEV)
+    info = torch.full((2,), -1, dtype=torch.int32, device=gu.DEV)
+    kf.kfac_tune("invert_fused_max_n", 100)
+    try:
+        ws = gu.workspace(kf.kfac_workspace_bytes(desc, 8))
+        kf.kfac_invert(desc, gu.to_dev(M), gu.to_dev(np.eye(3, dtype=np.float32)), 0.01, 0.01, A_inv, G_inv, info, ws)
+        torch.cuda.synchronize()
+    finally:
+        kf.kfac_tune("invert_fused_max_n", 1280)
+    flags = info.cpu().numpy()
+    assert flags[1] == 0
+    # the pivots of the sweep are those of the LDL^T factorisation: the oracle names the first bad one
+    assert flags[0] == orc.inverse_info(M.astype(np.float64), 0.01)
+
+
 def test_not_positive_definite_is_flagged():
     n = 70
     M = np.eye(n, dtype=np.float32)
