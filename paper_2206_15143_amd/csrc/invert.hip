@@ -176,21 +176,35 @@ __global__ __launch_bounds__(256) void blk_scatter_kernel(const BlkTable tab)
     }
 }
 
-// out = -W mirrored to both triangles (in place)
+// out = -W mirrored to both triangles (in place).  One workgroup per 32 x 32 tile of the lower
+// triangle; the mirror image goes through LDS so that both stores are along rows.
 __global__ __launch_bounds__(256) void sweep_finish_kernel(const InvTable tab)
 {
+    __shared__ float t[32][33];
     int pi = 0;
     while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].blk_start) ++pi;
     const InvProb &pr = tab.p[pi];
-    const int local = blockIdx.x - pr.blk_start;
-    const long total = (long)pr.n * pr.n;
-    for (long e = (long)local * 4096 + threadIdx.x; e < lmin(total, (long)(local + 1) * 4096); e += 256) {
-        const int i = (int)(e / pr.n), j = (int)(e - (long)i * pr.n);
-        if (j <= i) {
-            const float v = -pr.W[e];
-            pr.W[e] = v;
-            pr.W[(long)j * pr.n + i] = v;
+    int bi, bj;
+    tri_decode(blockIdx.x - pr.blk_start, bi, bj);
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const long n = pr.n;
+    const int i0 = bi * 32, j0 = bj * 32;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int i = i0 + ty + 8 * r, j = j0 + tx;
+        float v = 0.f;
+        if (i < pr.n && j <= i) {
+            v = -pr.W[i * n + j];
+            pr.W[i * n + j] = v;
         }
+        t[ty + 8 * r][tx] = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        // element (j, i) of the upper triangle, j from this tile's columns, i from its rows
+        const int j = j0 + ty + 8 * r, i = i0 + tx;
+        if (i < pr.n && j < i) pr.W[j * n + i] = t[tx][ty + 8 * r];
     }
 }
 
@@ -415,7 +429,8 @@ hipError_t blocked_launch(const InvertJob *jobs, const std::vector<int> &idx, co
             p.M = j.M; p.W = j.Minv; p.info = j.info; p.n = j.n; p.damping = j.damping;
             p.ldv = big[g0 + k].ldv; p.P = nullptr; p.Vt = nullptr; p.Wt = nullptr;
             p.blk_start = blocks;
-            blocks += (int)(((long)j.n * j.n + 4095) / 4096);
+            const int nb32 = (j.n + 31) / 32;
+            blocks += nb32 * (nb32 + 1) / 2;
         }
         KFAC_LAUNCH(KFAC_K_INV_FINISH, s, sweep_finish_kernel, dim3(blocks), dim3(256), 0, tab);
         hipError_t e = hipGetLastError();

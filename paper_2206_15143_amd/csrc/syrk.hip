@@ -180,29 +180,32 @@ __global__ __launch_bounds__(256) void syrk_reduce_kernel(const SyrkTable tab)
     constexpr int CPT = (TILE + kRedChunk - 1) / kRedChunk;   // chunks per tile
 
     if (local < nblk * CPT) {
+        // one 16 x 16 sub-tile per block: thread t holds one element; the mirror image goes through LDS so
+        // that both stores run along rows of F
+        __shared__ float mir[16][17];
         const int tile = local / CPT;
         const int chunk = local - tile * CPT;
         int bi, bj;
         tri_decode(tile, bi, bj);
         const float *src = pr.partial + (long)tile * TILE;
         const long sstride = (long)nblk * TILE;
-#pragma unroll
-        for (int q = 0; q < kRedChunk / 256; ++q) {
-            const int e = chunk * kRedChunk + q * 256 + threadIdx.x;
-            if (e >= TILE) continue;
-            int r, c;
-            if (NATIVE) {
-                const int tile16 = e >> 8, within = e & 255;
-                const int ti = tile16 / (T::BM / 16), tj = tile16 - ti * (T::BM / 16);
-                const int ln = within >> 2, vv = within & 3;
-                r = ti * 16 + 4 * (ln >> 4) + vv;
-                c = tj * 16 + (ln & 15);
-            } else {
-                r = e / T::BM;
-                c = e - r * T::BM;
-            }
-            const int u = bi * T::BM + r, v = bj * T::BM + c;
-            if (u >= pr.d || v > u) continue;
+        constexpr int S = T::BM / 16;            // sub-tiles per tile side
+        const int sr = chunk / S, sc = chunk - sr * S;
+        const int t = threadIdx.x;
+        int r, c, e;
+        if (NATIVE) {
+            const int ln = t >> 2, vv = t & 3;
+            r = 4 * (ln >> 4) + vv;
+            c = ln & 15;
+            e = chunk * 256 + t;
+        } else {
+            r = t >> 4;
+            c = t & 15;
+            e = (sr * 16 + r) * T::BM + sc * 16 + c;
+        }
+        const int u = bi * T::BM + sr * 16 + r, v = bj * T::BM + sc * 16 + c;
+        float out = 0.f;
+        if (u < pr.d && v <= u) {
             // four interleaved running sums (fixed order, so still deterministic) keep loads in flight
             float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
             int k = 0;
@@ -213,10 +216,16 @@ __global__ __launch_bounds__(256) void syrk_reduce_kernel(const SyrkTable tab)
                 s3 += src[(k + 3) * sstride + e];
             }
             for (; k < pr.splits; ++k) s0 += src[k * sstride + e];
-            const float s = (s0 + s1) + (s2 + s3);
-            const float out = pr.decay * pr.F[(long)u * dF + v] + wnew * s;
+            const float sum = (s0 + s1) + (s2 + s3);
+            out = pr.decay * pr.F[(long)u * dF + v] + wnew * sum;
             pr.F[(long)u * dF + v] = out;
-            pr.F[(long)v * dF + u] = out;
+        }
+        mir[r][c] = out;
+        __syncthreads();
+        {
+            const int c2 = t >> 4, r2 = t & 15;
+            const int u2 = bi * T::BM + sr * 16 + r2, v2 = bj * T::BM + sc * 16 + c2;
+            if (u2 < pr.d && v2 < u2) pr.F[(long)v2 * dF + u2] = mir[r2][c2];
         }
     } else {
         const int bi = local - nblk * CPT;
