@@ -20,6 +20,9 @@
  *                               weight on the old running factor.
  *   oracle_inverse_gj         - (M + damping I)^{-1} of section 5.2 by
  *                               Gauss-Jordan elimination with partial pivoting.
+ *   oracle_pi_damping         - the two damping terms of the factored Tikhonov split (Eq. 12):
+ *                               pi = sqrt((tr A / dim A) / (tr G / dim G)),
+ *                               lambda_A = pi sqrt(gamma), lambda_G = sqrt(gamma) / pi
  *   oracle_inverse_chol       - same result through Cholesky (the technique
  *                               section 5.2 names); used to cross-check the
  *                               Gauss-Jordan route.
@@ -204,6 +207,20 @@ int oracle_inverse_chol(const double *M, int n, double damping, double *Minv)
 }
 
 /* P = Ginv [dG x dG] * grad [dG x dA] * Ainv [dA x dA] */
+/* Eq. 12: (A (x) G + gamma I)^-1 is approximated by (A + pi sqrt(gamma) I)^-1 (x) (G + sqrt(gamma)/pi I)^-1
+ * with pi^2 = (tr A / dim A) / (tr G / dim G).  out[0] = lambda_A, out[1] = lambda_G.  A trace that is
+ * not positive leaves pi = 1 (the split is then the symmetric one). */
+void oracle_pi_damping(const double *A, int dA, const double *G, int dG, double gamma, double *out)
+{
+    double trA = 0.0, trG = 0.0;
+    for (int i = 0; i < dA; ++i) trA += A[(long)i * dA + i];
+    for (int i = 0; i < dG; ++i) trG += G[(long)i * dG + i];
+    double pi = 1.0;
+    if (trA > 0.0 && trG > 0.0) pi = sqrt((trA / dA) / (trG / dG));
+    out[0] = pi * sqrt(gamma);
+    out[1] = sqrt(gamma) / pi;
+}
+
 void oracle_precondition(const double *Ginv, const double *grad, const double *Ainv, int dG, int dA, double *P)
 {
     double *T = (double *)malloc(sizeof(double) * (size_t)dG * dA);

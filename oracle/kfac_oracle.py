@@ -153,6 +153,20 @@ def update_factors_layer(layer, act, gout, scale_A, scale_G, decay, A_run, G_run
     return running_average(A_run, A_new, decay), running_average(G_run, G_new, decay)
 
 
+def pi_damping(A_run: np.ndarray, G_run: np.ndarray, gamma: float):
+    """(lambda_A, lambda_G) of the factored Tikhonov split, Eq. 12."""
+    A = np.ascontiguousarray(A_run, dtype=np.float64)
+    G = np.ascontiguousarray(G_run, dtype=np.float64)
+    out = np.empty(2, dtype=np.float64)
+    _lib.oracle_pi_damping(_d(A), C.c_int(A.shape[0]), _d(G), C.c_int(G.shape[0]), C.c_double(gamma), _d(out))
+    return float(out[0]), float(out[1])
+
+
+def invert_layer_pi(A_run, G_run, gamma):
+    lam_A, lam_G = pi_damping(A_run, G_run, gamma)
+    return inverse(A_run, lam_A), inverse(G_run, lam_G), lam_A, lam_G
+
+
 def invert_layer(A_run, G_run, damping_A, damping_G):
     return inverse(A_run, damping_A), inverse(G_run, damping_G)
 

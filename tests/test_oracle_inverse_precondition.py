@@ -138,3 +138,57 @@ def test_eigen_form_is_exact_inverse_of_damped_kronecker_product():
     P12 = orc.precondition(orc.inverse(G, np.sqrt(gamma) / pi), grad, orc.inverse(A, pi * np.sqrt(gamma)))
     gap = np.linalg.norm(P12 - ref) / np.linalg.norm(ref)
     assert gap < 1.0
+
+
+# ---- factored Tikhonov damping (Eq. 12) -------------------------------------------------------
+
+def test_pi_damping_closed_forms():
+    # A = a I, G = g I: pi = sqrt(a / g) whatever the orders
+    lam_A, lam_G = orc.pi_damping(4.0 * np.eye(7), 0.25 * np.eye(3), 0.01)
+    assert abs(lam_A - 4.0 * 0.1) < 1e-15 and abs(lam_G - 0.1 / 4.0) < 1e-15
+    # equal mean eigenvalues: the split is symmetric, both terms are sqrt(gamma)
+    A = np.diag([1.0, 2.0, 3.0])
+    G = np.diag([2.0, 2.0])
+    lam_A, lam_G = orc.pi_damping(A, G, 0.04)
+    assert abs(lam_A - 0.2) < 1e-15 and abs(lam_G - 0.2) < 1e-15
+
+
+def test_pi_damping_invariants():
+    gen = np.random.default_rng(11)
+    X = gen.standard_normal((40, 9)); A = X.T @ X / 40
+    Y = gen.standard_normal((40, 5)); G = Y.T @ Y / 40 * 1e-3
+    gamma = 0.003
+    lam_A, lam_G = orc.pi_damping(A, G, gamma)
+    assert abs(lam_A * lam_G - gamma) < 1e-15                      # the product of the two terms is gamma
+    assert abs(lam_A / lam_G - (np.trace(A) / 9) / (np.trace(G) / 5)) < 1e-9 * lam_A / lam_G
+    # scaling A by c scales pi by sqrt(c); off-diagonal entries do not matter
+    lam_A2, lam_G2 = orc.pi_damping(9.0 * A, G, gamma)
+    assert abs(lam_A2 - 3.0 * lam_A) < 1e-12 and abs(lam_G2 - lam_G / 3.0) < 1e-12
+    A_off = A.copy(); A_off[0, 3] += 5.0
+    assert orc.pi_damping(A_off, G, gamma) == (lam_A, lam_G)
+
+
+def test_pi_is_the_split_that_minimises_the_cross_terms():
+    # (A + lA I) (x) (G + lG I) = A (x) G + lA I (x) G + lG A (x) I + gamma I: with lA lG = gamma fixed, the
+    # trace of the two cross terms, lA dA tr G + lG dG tr A, is smallest at the pi of Eq. 12
+    gen = np.random.default_rng(12)
+    X = gen.standard_normal((30, 6)); A = X.T @ X / 30
+    Y = gen.standard_normal((30, 4)); G = Y.T @ Y / 30 * 0.05
+    gamma = 0.01
+    lam_A, lam_G = orc.pi_damping(A, G, gamma)
+    cross = lambda lA: lA * 6 * np.trace(G) + (gamma / lA) * 4 * np.trace(A)
+    grid = lam_A * np.exp(np.linspace(-2, 2, 4001))
+    best = grid[np.argmin([cross(x) for x in grid])]
+    assert abs(best - lam_A) < 2e-3 * lam_A
+    assert cross(lam_A) <= cross(lam_A * 1.01) and cross(lam_A) <= cross(lam_A / 1.01)
+
+
+def test_invert_layer_pi_is_the_plain_inverse_at_the_split_dampings():
+    gen = np.random.default_rng(13)
+    X = gen.standard_normal((50, 8)); A = X.T @ X / 50
+    Y = gen.standard_normal((50, 5)); G = Y.T @ Y / 50
+    Ai, Gi, lam_A, lam_G = orc.invert_layer_pi(A, G, 0.02)
+    assert np.allclose(Ai @ (A + lam_A * np.eye(8)), np.eye(8), atol=1e-10)
+    assert np.allclose(Gi @ (G + lam_G * np.eye(5)), np.eye(5), atol=1e-10)
+    # non-positive trace: symmetric split
+    assert orc.pi_damping(np.zeros((3, 3)), G, 0.04) == (0.2, 0.2)
