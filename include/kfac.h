@@ -108,6 +108,15 @@ kfac_status kfac_invert(const kfac_layer_desc *desc, const float *d_A_run, const
                         float damping_A, float damping_G, float *d_A_inv, float *d_G_inv, int *d_info,
                         void *d_work, size_t work_bytes, void *hip_stream);
 
+/* Damped inverses with the factored Tikhonov split of Eq. 12: from the running factors,
+ *   pi = sqrt((tr A / d_A) / (tr G / d_G)),  lambda_A = pi sqrt(gamma),  lambda_G = sqrt(gamma) / pi,
+ * computed on the device (no host synchronisation), then A_inv = (A + lambda_A I)^{-1},
+ * G_inv = (G + lambda_G I)^{-1}.  A trace that is not positive leaves pi = 1.  d_damping may be NULL;
+ * otherwise 2 floats receive (lambda_A, lambda_G).  gamma >= 0.  Everything else as kfac_invert. */
+kfac_status kfac_invert_pi(const kfac_layer_desc *desc, const float *d_A_run, const float *d_G_run, float gamma,
+                           float *d_A_inv, float *d_G_inv, int *d_info, float *d_damping, void *d_work,
+                           size_t work_bytes, void *hip_stream);
+
 /* P = G_inv * grad * A_inv (Eq. 5 / right-hand side of Eq. 12).  d_out may alias d_grad. */
 kfac_status kfac_precondition(const kfac_layer_desc *desc, const float *d_A_inv, const float *d_G_inv,
                               const float *d_grad, float *d_out, void *d_work, size_t work_bytes,
@@ -125,6 +134,11 @@ kfac_status kfac_invert_batched(int n, const kfac_layer_desc *descs, const float
                                 const float *const *d_G_run, float damping_A, float damping_G,
                                 float *const *d_A_inv, float *const *d_G_inv, int *d_info, void *d_work,
                                 size_t work_bytes, void *hip_stream);
+/* d_damping: NULL or 2*n floats, (lambda_A, lambda_G) per layer. */
+kfac_status kfac_invert_pi_batched(int n, const kfac_layer_desc *descs, const float *const *d_A_run,
+                                   const float *const *d_G_run, float gamma, float *const *d_A_inv,
+                                   float *const *d_G_inv, int *d_info, float *d_damping, void *d_work,
+                                   size_t work_bytes, void *hip_stream);
 kfac_status kfac_precondition_batched(int n, const kfac_layer_desc *descs, const float *const *d_A_inv,
                                       const float *const *d_G_inv, const float *const *d_grad,
                                       float *const *d_out, void *d_work, size_t work_bytes, void *hip_stream);

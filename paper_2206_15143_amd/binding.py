@@ -74,6 +74,10 @@ def load_library():
     lib.kfac_update_factors.restype = C.c_int
     lib.kfac_invert.argtypes = [dp, vp, vp, C.c_float, C.c_float, vp, vp, vp, vp, sz, vp]
     lib.kfac_invert.restype = C.c_int
+    lib.kfac_invert_pi.argtypes = [dp, vp, vp, C.c_float, vp, vp, vp, vp, vp, sz, vp]
+    lib.kfac_invert_pi.restype = C.c_int
+    lib.kfac_invert_pi_batched.argtypes = [C.c_int, dp, vpp, vpp, C.c_float, vpp, vpp, vp, vp, vp, sz, vp]
+    lib.kfac_invert_pi_batched.restype = C.c_int
     lib.kfac_precondition.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]; lib.kfac_precondition.restype = C.c_int
     lib.kfac_update_factors_batched.argtypes = [C.c_int, dp, vpp, vpp, ip, ip, ip, fp, fp, C.c_float, vpp, vpp,
                                                 vp, sz, vp]
@@ -216,6 +220,12 @@ def kfac_invert(desc, A_run, G_run, damping_A, damping_G, A_inv, G_inv, info, wo
            "kfac_invert")
 
 
+def kfac_invert_pi(desc, A_run, G_run, gamma, A_inv, G_inv, info, damping, work, stream=None) -> None:
+    _check(load_library().kfac_invert_pi(C.byref(desc), _ptr(A_run), _ptr(G_run), gamma, _ptr(A_inv), _ptr(G_inv),
+                                         _ptr(info), _ptr(damping), _ptr(work), _nbytes(work), _stream(stream)),
+           "kfac_invert_pi")
+
+
 def kfac_precondition(desc, A_inv, G_inv, grad, out, work, stream=None) -> None:
     _check(load_library().kfac_precondition(C.byref(desc), _ptr(A_inv), _ptr(G_inv), _ptr(grad), _ptr(out),
                                             _ptr(work), _nbytes(work), _stream(stream)), "kfac_precondition")
@@ -236,6 +246,14 @@ def kfac_invert_batched(descs, A_runs, G_runs, damping_A, damping_G, A_invs, G_i
     _check(load_library().kfac_invert_batched(n, _descs(descs), _ptrs(A_runs), _ptrs(G_runs), damping_A, damping_G,
                                               _ptrs(A_invs), _ptrs(G_invs), _ptr(info), _ptr(work), _nbytes(work),
                                               _stream(stream)), "kfac_invert_batched")
+
+
+def kfac_invert_pi_batched(descs, A_runs, G_runs, gamma, A_invs, G_invs, info, damping, work, stream=None) -> None:
+    n = len(descs)
+    _check(load_library().kfac_invert_pi_batched(n, _descs(descs), _ptrs(A_runs), _ptrs(G_runs), gamma,
+                                                 _ptrs(A_invs), _ptrs(G_invs), _ptr(info), _ptr(damping),
+                                                 _ptr(work), _nbytes(work), _stream(stream)),
+           "kfac_invert_pi_batched")
 
 
 def kfac_precondition_batched(descs, A_invs, G_invs, grads, outs, work, stream=None) -> None:

@@ -247,6 +247,12 @@ size_t invert_ws(int n, const kfac_layer_desc *descs)
     return invert_workspace_bytes(jobs.data(), (int)jobs.size());
 }
 
+// the inversion workspace is followed by the 2n device-side damping terms of kfac_invert_pi
+size_t invert_ws_total(int n, const kfac_layer_desc *descs)
+{
+    return align_up(invert_ws(n, descs), 256) + align_up((size_t)2 * n * sizeof(float), 256);
+}
+
 size_t precond_ws(int n, const kfac_layer_desc *descs)
 {
     size_t total = 0;
@@ -290,7 +296,7 @@ size_t kfac_workspace_bytes_batched(int n, const kfac_layer_desc *descs, const i
     UpdatePlan pl;
     if (plan_update(n, descs, batch, h, w, pl) != KFAC_OK) return 0;
     size_t need = pl.patch_region + pl.syrk_region;
-    need = std::max(need, invert_ws(n, descs));
+    need = std::max(need, invert_ws_total(n, descs));
     need = std::max(need, precond_ws(n, descs));
     return need + 256;
 }
@@ -400,6 +406,57 @@ kfac_status kfac_invert_batched(int n, const kfac_layer_desc *descs, const float
     return invert_launch(jobs.data(), (int)jobs.size(), d_work, work_bytes, (hipStream_t)hip_stream) == hipSuccess
                ? KFAC_OK
                : KFAC_ERR_HIP;
+}
+
+kfac_status kfac_invert_pi_batched(int n, const kfac_layer_desc *descs, const float *const *d_A_run,
+                                   const float *const *d_G_run, float gamma, float *const *d_A_inv,
+                                   float *const *d_G_inv, int *d_info, float *d_damping, void *d_work,
+                                   size_t work_bytes, void *hip_stream)
+{
+    if (n <= 0) return KFAC_ERR_SHAPE;
+    if (!descs || !d_A_run || !d_G_run || !d_A_inv || !d_G_inv || !d_info || !d_work) return KFAC_ERR_NULL;
+    if (!(gamma >= 0.f)) return KFAC_ERR_PARAM;
+    if (d_damping && !aligned(d_damping, 4)) return KFAC_ERR_ALIGN;
+    if (!aligned(d_work, 256)) return KFAC_ERR_ALIGN;
+    for (int i = 0; i < n; ++i) {
+        kfac_status st = desc_check(&descs[i]);
+        if (st != KFAC_OK) return st;
+        if (!d_A_run[i] || !d_G_run[i] || !d_A_inv[i] || !d_G_inv[i]) return KFAC_ERR_NULL;
+        if (!aligned(d_A_run[i], 4) || !aligned(d_G_run[i], 4) || !aligned(d_A_inv[i], 4) ||
+            !aligned(d_G_inv[i], 4))
+            return KFAC_ERR_ALIGN;
+        if (d_A_run[i] == d_A_inv[i] || d_G_run[i] == d_G_inv[i]) return KFAC_ERR_PARAM;
+    }
+    if (invert_ws_total(n, descs) > work_bytes) return KFAC_ERR_WORKSPACE;
+    const size_t inv_bytes = align_up(invert_ws(n, descs), 256);
+    float *lam = d_damping ? d_damping : reinterpret_cast<float *>(static_cast<char *>(d_work) + inv_bytes);
+    std::vector<InvertJob> jobs;
+    std::vector<int> dA(n), dG(n);
+    for (int i = 0; i < n; ++i) {
+        dA[i] = core_dim(&descs[i]) + descs[i].has_bias;
+        dG[i] = descs[i].d_out;
+        InvertJob a{};
+        a.M = d_A_run[i]; a.Minv = d_A_inv[i]; a.n = dA[i]; a.damping = 0.f; a.damping_dev = lam + 2 * i;
+        a.info = d_info + 2 * i;
+        jobs.push_back(a);
+        InvertJob g{};
+        g.M = d_G_run[i]; g.Minv = d_G_inv[i]; g.n = dG[i]; g.damping = 0.f; g.damping_dev = lam + 2 * i + 1;
+        g.info = d_info + 2 * i + 1;
+        jobs.push_back(g);
+    }
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (pi_damping_launch(d_A_run, d_G_run, dA.data(), dG.data(), n, gamma, lam, s) != hipSuccess)
+        return KFAC_ERR_HIP;
+    return invert_launch(jobs.data(), (int)jobs.size(), d_work, inv_bytes, s) == hipSuccess ? KFAC_OK : KFAC_ERR_HIP;
+}
+
+kfac_status kfac_invert_pi(const kfac_layer_desc *d, const float *d_A_run, const float *d_G_run, float gamma,
+                           float *d_A_inv, float *d_G_inv, int *d_info, float *d_damping, void *d_work,
+                           size_t work_bytes, void *hip_stream)
+{
+    if (!d) return KFAC_ERR_NULL;
+    return kfac_invert_pi_batched(1, d, &d_A_run, &d_G_run, gamma, &d_A_inv, &d_G_inv, d_info, d_damping, d_work,
+                                  work_bytes, hip_stream);
 }
 
 kfac_status kfac_invert(const kfac_layer_desc *d, const float *d_A_run, const float *d_G_run, float damping_A,

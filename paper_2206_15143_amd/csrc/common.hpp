@@ -44,6 +44,7 @@ struct InvertJob {
     int n;
     float damping;
     int *info;       // device int
+    const float *damping_dev = nullptr;   // when set, the damping is read from this device float instead
     int ldm = 0;     // row pitch of M (0 = n)
     int ldo = 0;     // row pitch of Minv (0 = n)
 };
@@ -79,6 +80,9 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
 
 size_t invert_workspace_bytes(const InvertJob *jobs, int n);
 hipError_t invert_launch(const InvertJob *jobs, int n, void *work, size_t work_bytes, hipStream_t s);
+// lam[2i] = pi sqrt(gamma), lam[2i+1] = sqrt(gamma) / pi for the factor pair (A_i, G_i), pi from the traces (Eq. 12)
+hipError_t pi_damping_launch(const float *const *A, const float *const *G, const int *dA, const int *dG, int n,
+                             float gamma, float *lam, hipStream_t s);
 
 hipError_t gemm_launch(const GemmJob *jobs, int n, hipStream_t s);
 

@@ -40,6 +40,7 @@ struct InvProb {
     int ldv;         // n rounded up to 4 (16-byte aligned rows)
     float damping;
     int blk_start;
+    const float *dptr;   // device-side damping (overrides `damping` when not null)
 };
 
 struct InvTable {
@@ -56,10 +57,11 @@ __global__ __launch_bounds__(256) void sweep_init_kernel(const InvTable tab)
     const InvProb &pr = tab.p[pi];
     const int local = blockIdx.x - pr.blk_start;
     const long total = (long)pr.n * pr.n;
+    const float damping = pr.dptr ? *pr.dptr : pr.damping;
     if (local == 0 && threadIdx.x == 0) *pr.info = 0;
     for (long e = (long)local * 4096 + threadIdx.x; e < lmin(total, (long)(local + 1) * 4096); e += 256) {
         const int i = (int)(e / pr.n), j = (int)(e - (long)i * pr.n);
-        if (j <= i) pr.W[e] = pr.M[e] + (i == j ? pr.damping : 0.f);
+        if (j <= i) pr.W[e] = pr.M[e] + (i == j ? damping : 0.f);
     }
 }
 
@@ -233,7 +235,7 @@ hipError_t fused_launch(const InvertJob *jobs, const std::vector<int> &idx, cons
             const InvertJob &j = jobs[idx[g0 + k]];
             InvProbF &p = u.p[k];
             float *ws = reinterpret_cast<float *>(static_cast<char *>(work) + offs[idx[g0 + k]]);
-            p.M = j.M; p.W = j.Minv; p.info = j.info; p.n = j.n; p.damping = j.damping;
+            p.M = j.M; p.W = j.Minv; p.info = j.info; p.n = j.n; p.damping = j.damping; p.dptr = j.damping_dev;
             p.ldv = (j.n + 3) / 4 * 4;
             p.nblk = (j.n + FNB - 1) / FNB;
             p.ldm = j.ldm > 0 ? j.ldm : j.n;
@@ -321,7 +323,7 @@ hipError_t blocked_launch(const InvertJob *jobs, const std::vector<int> &idx, co
         for (int k = 0; k < tab.count; ++k) {
             const InvertJob &j = jobs[idx[g0 + k]];
             InvProb &p = tab.p[k];
-            p.M = j.M; p.W = j.Minv; p.info = j.info; p.n = j.n; p.damping = j.damping;
+            p.M = j.M; p.W = j.Minv; p.info = j.info; p.n = j.n; p.damping = j.damping; p.dptr = j.damping_dev;
             p.ldv = big[g0 + k].ldv; p.P = nullptr; p.Vt = nullptr; p.Wt = nullptr;
             p.blk_start = blocks;
             blocks += (int)(((long)j.n * j.n + 4095) / 4096);
@@ -426,7 +428,7 @@ hipError_t blocked_launch(const InvertJob *jobs, const std::vector<int> &idx, co
         for (int k = 0; k < tab.count; ++k) {
             const InvertJob &j = jobs[idx[g0 + k]];
             InvProb &p = tab.p[k];
-            p.M = j.M; p.W = j.Minv; p.info = j.info; p.n = j.n; p.damping = j.damping;
+            p.M = j.M; p.W = j.Minv; p.info = j.info; p.n = j.n; p.damping = j.damping; p.dptr = j.damping_dev;
             p.ldv = big[g0 + k].ldv; p.P = nullptr; p.Vt = nullptr; p.Wt = nullptr;
             p.blk_start = blocks;
             const int nb32 = (j.n + 31) / 32;
@@ -470,6 +472,68 @@ hipError_t invert_launch(const InvertJob *jobs, int n_all, void *work, size_t wo
     if (!large.empty()) {
         // the nested pivot-block inversions use the second half of the descriptor table
         hipError_t e = blocked_launch(jobs, large, offs, work, dtab + n_all, s);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+// ---- factored Tikhonov damping (Eq. 12) ----------------------------------------------------
+struct PiTable {
+    int count;
+    float gamma;
+    float *lam;
+    const float *A[kMaxProblems];
+    const float *G[kMaxProblems];
+    int dA[kMaxProblems], dG[kMaxProblems];
+    int first;
+};
+
+// One workgroup per layer: traces of A and G (fixed-order tree sums), pi = sqrt((tr A / d_A) / (tr G / d_G)),
+// lam[2l] = pi sqrt(gamma), lam[2l+1] = sqrt(gamma) / pi.  A trace that is not positive leaves pi = 1.
+__global__ __launch_bounds__(256) void pi_damping_kernel(const PiTable tab)
+{
+    __shared__ float red[2][256];
+    const int l = blockIdx.x, t = threadIdx.x;
+    const float *A = tab.A[l], *G = tab.G[l];
+    const int dA = tab.dA[l], dG = tab.dG[l];
+    float sa = 0.f, sg = 0.f;
+    for (int i = t; i < dA; i += 256) sa += A[(long)i * dA + i];
+    for (int i = t; i < dG; i += 256) sg += G[(long)i * dG + i];
+    red[0][t] = sa;
+    red[1][t] = sg;
+    __syncthreads();
+    for (int h = 128; h > 0; h >>= 1) {
+        if (t < h) {
+            red[0][t] += red[0][t + h];
+            red[1][t] += red[1][t + h];
+        }
+        __syncthreads();
+    }
+    if (t == 0) {
+        const float trA = red[0][0], trG = red[1][0];
+        float pi = 1.f;
+        if (trA > 0.f && trG > 0.f) pi = sqrtf((trA / (float)dA) / (trG / (float)dG));
+        const float sq = sqrtf(tab.gamma);
+        tab.lam[2 * (tab.first + l)] = pi * sq;
+        tab.lam[2 * (tab.first + l) + 1] = sq / pi;
+    }
+}
+
+hipError_t pi_damping_launch(const float *const *A, const float *const *G, const int *dA, const int *dG, int n,
+                             float gamma, float *lam, hipStream_t s)
+{
+    for (int g0 = 0; g0 < n; g0 += kMaxProblems) {
+        PiTable tab;
+        tab.count = std::min(kMaxProblems, n - g0);
+        tab.gamma = gamma;
+        tab.lam = lam;
+        tab.first = g0;
+        for (int k = 0; k < tab.count; ++k) {
+            tab.A[k] = A[g0 + k]; tab.G[k] = G[g0 + k];
+            tab.dA[k] = dA[g0 + k]; tab.dG[k] = dG[g0 + k];
+        }
+        KFAC_LAUNCH(KFAC_K_INV_INIT, s, pi_damping_kernel, dim3(tab.count), dim3(256), 0, tab);
+        hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     return hipSuccess;

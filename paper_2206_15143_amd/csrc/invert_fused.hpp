@@ -44,6 +44,7 @@ struct InvProbF {
     float damping;
     int nblk;
     int ldm, ldw;     // row pitches of M and W
+    const float *dptr; // device-side damping (overrides `damping` when not null)
 };
 
 struct InvUpload {
@@ -159,6 +160,7 @@ __global__ __launch_bounds__(256) void fsweep_pivot0_kernel(const InvSeq q)
     const int i = tid >> 2, jq = tid & 3;
     const int bs = min(FNB, pr.n);
     const long ldm = pr.ldm, ldw = pr.ldw;
+    const float damping = pr.dptr ? *pr.dptr : pr.damping;
     float s[16];
 #pragma unroll
     for (int m = 0; m < 16; ++m) {
@@ -166,7 +168,7 @@ __global__ __launch_bounds__(256) void fsweep_pivot0_kernel(const InvSeq q)
         float v = (i == j) ? 1.f : 0.f;
         if (i < bs && j < bs) {
             const int a = max(i, j), b = min(i, j);
-            v = pr.M[a * ldm + b] + (a == b ? pr.damping : 0.f);
+            v = pr.M[a * ldm + b] + (a == b ? damping : 0.f);
         }
         s[m] = v;
     }
@@ -213,6 +215,7 @@ __global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
     const int n = pr.n, ldv = pr.ldv;
     const long ldm = pr.ldm, ldw = pr.ldw;
     const bool first = (K == 0), last = (K1 == nblk);
+    const float damping = (first && pr.dptr) ? *pr.dptr : pr.damping;
     if (bi == K && bj == K) {
         // the pivot block itself was finished by the previous launch; on the last step it still has to
         // be negated and mirrored like everything else
@@ -259,7 +262,7 @@ __global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
                     const bool ok = (ga < n && gb < n && (!diag || gb <= ga));
                     float o = 0.f;
                     if (ok)
-                        o = first ? pr.M[(long)ga * ldm + gb] + (ga == gb ? pr.damping : 0.f)
+                        o = first ? pr.M[(long)ga * ldm + gb] + (ga == gb ? damping : 0.f)
                                   : pr.W[(long)ga * ldw + gb];
                     oldc[ti][tj][v] = o;
                 }

@@ -297,3 +297,47 @@ def test_bf16_mfma_factor_kernel(layer, batch):
         kf.kfac_tune("use_bf16_mfma", 1)
     assert gu.rel_fro(fast["A"], wide["A"]) < 1e-5
     assert gu.rel_fro(fast["G"], wide["G"]) < 1e-5
+
+
+def test_pi_damped_inverse_matches_oracle():
+    # Eq. 12 split of the damping, computed on the device from the traces of the running factors
+    layers = [LayerSpec("linear", 64, 32, rows=32), LayerSpec("conv", 16, 24, 3, 1, 1, 8),
+              LayerSpec("linear", 300, 130, rows=100), LayerSpec("conv", 4, 6, 3, 1, 1, 8)]
+    batch = 4
+    gamma = 0.003
+    inputs = gu.draw_inputs(layers, batch, 8100, "relu_normal", 0.0316)
+    scales = gu.scales_for(layers, batch)
+    descs = [kf.LayerDesc.from_spec(l, kf.KFAC_F32) for l in layers]
+    b, h, w = gu.batch_args(layers, batch)
+    n = len(layers)
+    A_run = [torch.eye(l.d_A, device=gu.DEV) for l in layers]
+    G_run = [torch.eye(l.d_G, device=gu.DEV) for l in layers]
+    A_inv = [torch.full((l.d_A, l.d_A), float("nan"), device=gu.DEV) for l in layers]
+    G_inv = [torch.full((l.d_G, l.d_G), float("nan"), device=gu.DEV) for l in layers]
+    info = torch.full((2 * n,), -1, dtype=torch.int32, device=gu.DEV)
+    lam = torch.full((2 * n,), float("nan"), device=gu.DEV)
+    ws = gu.workspace(kf.kfac_workspace_bytes_batched(descs, b, h, w))
+    kf.kfac_update_factors_batched(descs, [gu.to_dev(i[0]) for i in inputs], [gu.to_dev(i[1]) for i in inputs],
+                                   b, h, w, [s[0] for s in scales], [s[1] for s in scales], 0.95, A_run, G_run, ws)
+    kf.kfac_invert_pi_batched(descs, A_run, G_run, gamma, A_inv, G_inv, info, lam, ws)
+    torch.cuda.synchronize()
+    assert not info.cpu().numpy().any()
+    lam_h = lam.cpu().numpy().astype(np.float64)
+    for i, l in enumerate(layers):
+        A = A_run[i].cpu().numpy().astype(np.float64)
+        G = G_run[i].cpu().numpy().astype(np.float64)
+        Ai, Gi, lA, lG = orc.invert_layer_pi(A, G, gamma)
+        assert abs(lam_h[2 * i] - lA) < 1e-5 * lA and abs(lam_h[2 * i + 1] - lG) < 1e-5 * lG
+        assert gu.rel_fro(A_inv[i].cpu().numpy(), Ai) < 1e-4
+        assert gu.rel_fro(G_inv[i].cpu().numpy(), Gi) < 1e-4
+    # single-layer call without the damping output, on the path for large orders
+    kf.kfac_tune("invert_fused_max_n", 100)
+    try:
+        ws1 = gu.workspace(kf.kfac_workspace_bytes(descs[2], b[2]))
+        A1 = torch.empty_like(A_inv[2]); G1 = torch.empty_like(G_inv[2])
+        kf.kfac_invert_pi(descs[2], A_run[2], G_run[2], gamma, A1, G1, info[:2], None, ws1)
+        torch.cuda.synchronize()
+    finally:
+        kf.kfac_tune("invert_fused_max_n", 1280)
+    assert gu.rel_fro(A1.cpu().numpy(), A_inv[2].cpu().numpy()) < 1e-5
+    assert gu.rel_fro(G1.cpu().numpy(), G_inv[2].cpu().numpy()) < 1e-5
