@@ -346,7 +346,11 @@ void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<
         const long ktiles = (jobs[j].K + 15) / 16;
         work += (double)p.bps * (double)ktiles / p.stretch;
     }
-    long tpb = (long)std::ceil(work / (double)tu.target_blocks);
+    // The narrow-NCHW kernel is bound by loads in flight, not by MFMAs: several of its light workgroups
+    // share a CU, so it gets four times the blocks.
+    const int cfg0 = pl[idx[0]].cfg;
+    const long target = (cfg0 == kSmall32Cfg || cfg0 == kSmall64Cfg) ? 4 * tu.target_blocks : tu.target_blocks;
+    long tpb = (long)std::ceil(work / (double)target);
     tpb = std::max<long>(tpb, tu.min_tiles_per_split);
     // Blocks of a launch carry equal work and run about one per CU, so a launch a few blocks over the
     // target costs a whole extra round: grow the slice until the total fits.
@@ -366,12 +370,15 @@ void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<
             if (p.cfg == kBf16Cfg && jobs[j].layout == kRows)
                 tpb_j = std::max<long>(1, std::min<long>(tpb_j, 0x7fffffffl / (2 * H_KT * jobs[j].ld) - 1));
             p.splits = (int)((ktiles + tpb_j - 1) / tpb_j);
+            // every element of the block-tile kernels' partials is summed serially over the splits by one
+            // thread of the reduction: keep that chain short
+            if (p.cfg < kWaveCfg) p.splits = std::min(p.splits, 128);
             p.tps = (int)((ktiles + p.splits - 1) / p.splits);
             p.splits = (int)((ktiles + p.tps - 1) / p.tps);
             p.partial_floats = (size_t)p.splits * ((size_t)p.nblk * c.bm * c.bm + (size_t)p.nb * c.bm);
             total += (long)p.bps * p.splits;
         }
-        if (total <= tu.target_blocks || tpb > (1l << 40)) break;
+        if (total <= target || tpb > (1l << 40)) break;
         bool can_shrink = false;
         for (int j : idx) can_shrink |= pl[j].splits > 1;
         if (!can_shrink) break;

@@ -17,7 +17,7 @@ __global__ __launch_bounds__(256) void syrk_small_nchw_kernel(const SyrkTable ta
 {
     constexpr int BM = NTL <= 2 ? 32 : 64;      // partial tile pitch expected by the reduction kernel
     constexpr int NACC = NTL * (NTL + 1) / 2;
-    constexpr int DEPTH = 4;                     // groups of loads in flight per wave
+    constexpr int DEPTH = NTL <= 2 ? 8 : 4;      // groups of loads in flight per wave
     __shared__ float red[3][NACC * 256];
 
     const int tid = threadIdx.x;
