@@ -277,7 +277,7 @@ hipError_t fused_launch(const InvertJob *jobs, const std::vector<int> &idx, cons
         const int nclass = q.nclass;
         long blocks = 0;
         hipError_t e = hipSuccess;
-        blocks = lay_out(q, nclass, [](const InvClass &) { return 1; });
+        blocks = lay_out(q, nclass, [](const InvClass &k) { return k.nblk; });
         KFAC_LAUNCH(KFAC_K_INV_PIVOT, s, fsweep_pivot0_kernel, dim3((unsigned)blocks), dim3(256), 0, q);
         e = hipGetLastError();
         if (e != hipSuccess) return e;

@@ -148,15 +148,31 @@ __device__ __forceinline__ int sweep64(float (&s)[16], float *colb, float *rowb,
     return fail;
 }
 
-// Inverse of the first pivot block (one workgroup per matrix).
+// Workgroup 0 of a matrix inverts the first pivot block; workgroup r >= 1 copies block r of the first
+// column panel K-major into V[0] (transposed through LDS), so that step 0 stages its panels like any
+// other step.
 __global__ __launch_bounds__(256) void fsweep_pivot0_kernel(const InvSeq q)
 {
     __shared__ float colb[2 * 64];
     __shared__ __attribute__((aligned(16))) float rowb[2 * 64];
+    __shared__ float tile[64][65];
     int prob, local, ci;
     if (!seq_locate(q, blockIdx.x, prob, local, ci)) return;
     const InvProbF pr = q.tab[prob];
     const int tid = threadIdx.x;
+    if (local > 0) {
+        const int g0 = local * FNB;
+        for (int e = tid; e < FNB * FNB; e += 256) {
+            const int c = e >> 6, k = e & 63;
+            tile[c][k] = (g0 + c < pr.n) ? pr.M[(long)(g0 + c) * pr.ldm + k] : 0.f;
+        }
+        __syncthreads();
+        for (int e = tid; e < FNB * FNB; e += 256) {
+            const int k = e >> 6, c = e & 63;
+            if (g0 + c < pr.n) pr.Vt[(long)k * pr.ldv + g0 + c] = tile[c][k];
+        }
+        return;
+    }
     const int i = tid >> 2, jq = tid & 3;
     const int bs = min(FNB, pr.n);
     const long ldm = pr.ldm, ldw = pr.ldw;
@@ -192,9 +208,10 @@ __global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
 {
     typedef Tile<2, 2> T;
     constexpr int PITCH = T::PITCH;   // 80
-    __shared__ __attribute__((aligned(16))) float Ps[FNB * PITCH];   // P, then W^T
+    // two operand buffers (41 KB with the sweep's row/column buffers: three workgroups per CU).  P is
+    // not staged: every lane keeps its 32 operand values of P in registers.
     __shared__ __attribute__((aligned(16))) float Va[FNB * PITCH];   // V of the tile's row block (or the panel block)
-    __shared__ __attribute__((aligned(16))) float Vb[FNB * PITCH];   // V of the tile's column block
+    __shared__ __attribute__((aligned(16))) float Vb[FNB * PITCH];   // V of the tile's column block, or W^T
     __shared__ float colb[2 * 64];
     __shared__ __attribute__((aligned(16))) float rowb[2 * 64];
 
@@ -269,20 +286,16 @@ __global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
             }
     }
 
-    // ---- stage P, V_a (and V_b) ----
-    if (first) {
-        // step 0: the panel is column block 0 of the input itself (blocks below the diagonal carry no damping)
-        for (int e = tid; e < FNB * FNB; e += 256) {
-            const int c = e >> 6, k = e & 63;
-            const int ga = ra * FNB + c, gb = rb * FNB + c;
-            Va[k * PITCH + c] = (ga < n) ? pr.M[(long)ga * ldm + k] : 0.f;
-            if (!panel && rb != ra) Vb[k * PITCH + c] = (gb < n) ? pr.M[(long)gb * ldm + k] : 0.f;
-        }
-    }
+    // ---- P operand values of this lane: P[k = 4s + lk][m = (wm*2 + t)*16 + lr] ----
+    float pa[FNB / 4][T::WT];
+#pragma unroll
+    for (int s4 = 0; s4 < FNB / 4; ++s4)
+#pragma unroll
+        for (int t2 = 0; t2 < T::WT; ++t2) pa[s4][t2] = Pk[(4 * s4 + lk) * FNB + (wm * T::WT + t2) * 16 + lr];
+
+    // ---- stage V_a (and V_b) ----
     for (int e = tid; e < FNB * FNB / 4; e += 256) {
         const int k = e >> 4, c4 = (e & 15) * 4;
-        *reinterpret_cast<floatx4 *>(Ps + k * PITCH + c4) = *reinterpret_cast<const floatx4 *>(Pk + k * FNB + c4);
-        if (first) continue;
         const int ga = ra * FNB + c4;
         floatx4 va = {0.f, 0.f, 0.f, 0.f};
         if (ga < ldv && k < bs) {
@@ -313,8 +326,16 @@ __global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
         for (int b = 0; b < T::WT; ++b) acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
     // acc = W^T[m][c] = sum_k P[k][m] V_a[k][c]   (P symmetric)
 #pragma unroll
-    for (int s4 = 0; s4 < FNB / T::KT; ++s4)
-        mma_stage<T, kRows, kRows, false>(Ps + s4 * T::KT * PITCH, Va + s4 * T::KT * PITCH, wm, wn, lane, acc);
+    for (int s4 = 0; s4 < FNB / 4; ++s4) {
+        float b[T::WT];
+#pragma unroll
+        for (int t2 = 0; t2 < T::WT; ++t2) b[t2] = Va[(4 * s4 + lk) * PITCH + (wn * T::WT + t2) * 16 + lr];
+#pragma unroll
+        for (int ti = 0; ti < T::WT; ++ti)
+#pragma unroll
+            for (int tj = 0; tj < T::WT; ++tj)
+                acc[ti][tj] = __builtin_amdgcn_mfma_f32_16x16x4f32(pa[s4][ti], b[tj], acc[ti][tj], 0, 0, 0);
+    }
 
     if (panel) {
         // new panel values in place; tile (K+1, K) also feeds the next step's V'
@@ -346,8 +367,12 @@ __global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
         return;
     }
 
-    // ---- W^T to LDS (over P), then C = M_ij - W_i V_j^T ----
-    __syncthreads();   // every wave is done reading Ps
+    // ---- W^T to LDS, then C = M_ij - W_i V_j^T ----
+    // off-diagonal tiles: V_a is dead after the first product and takes W^T; diagonal tiles still need
+    // V_a as V_j and put W^T into the unused second buffer
+    float *Ws = diag ? Vb : Va;
+    const float *Vj = diag ? Va : Vb;
+    __syncthreads();   // every wave is done reading V_a
 #pragma unroll
     for (int ti = 0; ti < T::WT; ++ti)
 #pragma unroll
@@ -356,18 +381,17 @@ __global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int m = (wm * T::WT + ti) * 16 + 4 * lk + v;
-                Ps[m * PITCH + c] = acc[ti][tj][v];
+                Ws[m * PITCH + c] = acc[ti][tj][v];
             }
         }
     __syncthreads();
-    const float *Vj = (rb == ra) ? Va : Vb;
 #pragma unroll
     for (int a = 0; a < T::WT; ++a)
 #pragma unroll
         for (int b = 0; b < T::WT; ++b) acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s4 = 0; s4 < FNB / T::KT; ++s4)
-        mma_stage<T, kRows, kRows, false>(Ps + s4 * T::KT * PITCH, Vj + s4 * T::KT * PITCH, wm, wn, lane, acc);
+        mma_stage<T, kRows, kRows, false>(Ws + s4 * T::KT * PITCH, Vj + s4 * T::KT * PITCH, wm, wn, lane, acc);
 
     // acc[ti][tj][v] = (W_i V_j^T)[a][b], a = (wm*2+ti)*16 + 4*lk + v, b = (wn*2+tj)*16 + lr
     const bool next_col = (bj == K1 && bi > K1);    // column panel of the next pivot: V'[b][ga]
