@@ -1,9 +1,11 @@
 // Factor of a narrow NCHW operand (conv output gradients with d <= 64 channels): G = X^T X where
 // X^T is stored [image][channel][position], i.e. K is contiguous.  The work is bound by reading X
-// once, so there is no LDS staging: lane (lr, lk) of a wave loads 16 bytes = four consecutive
+// once, so there is no LDS staging: lane (lr, lk) of a wave ends up with 16 bytes = four consecutive
 // positions of channel 16*t + lr, and the four components feed four MFMAs.  That is legal because
 // a symmetric product only needs both operands to agree on which K element sits where (here the
-// same register is both operands).  Each wave walks its own range of 16-position groups with the
+// same register is both operands).  The load itself is issued in a memory-friendly lane order (four
+// adjacent lanes read the 64 contiguous bytes of one channel) and a cross-lane permutation
+// (ds_bpermute, no memory traffic) brings the pieces to the lanes the MFMA layout wants.  Each wave walks its own range of 16-position groups with the
 // loads of the next groups in flight, the four waves of a block add up through LDS and the block
 // writes one partial tile for the split reduction.
 #pragma once
@@ -48,15 +50,26 @@ __global__ __launch_bounds__(256) void syrk_small_nchw_kernel(const SyrkTable ta
     // (image, group-in-image) of the next group to fetch
     long n = gb / gpi;
     int gi = (int)(gb - n * gpi);
+    // load order: lane l reads piece l & 3 (positions 4*(l&3)..+3) of channel l >> 2; the MFMA lane
+    // (lr, lk) = lane lk*16 + lr needs piece lk of channel lr, i.e. the data of load lane lr*4 + lk
+    const int lc = lane >> 2, lq = lane & 3;
+    const int src_byte = (lr * 4 + lk) * 4;
     auto fetch = [&](floatx4 (&v)[NTL]) {
-        const int p = gi * 16 + 4 * lk;
+        const int p = gi * 16 + 4 * lq;
 #pragma unroll
         for (int t = 0; t < NTL; ++t) {
-            const int c = t * 16 + lr;
+            const int c = t * 16 + lc;
             v[t] = floatx4{0.f, 0.f, 0.f, 0.f};
             if (c < d && p < hw) v[t] = *reinterpret_cast<const floatx4 *>(x + (n * pr.ctot + c) * (long)hw + p);
         }
         if (++gi == gpi) { gi = 0; ++n; }
+    };
+    auto to_mfma_lanes = [&](floatx4 (&v)[NTL]) {
+#pragma unroll
+        for (int t = 0; t < NTL; ++t)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                v[t][e] = __int_as_float(__builtin_amdgcn_ds_bpermute(src_byte, __float_as_int(v[t][e])));
     };
     auto mma = [&](const floatx4 (&v)[NTL]) {
 #pragma unroll
@@ -84,12 +97,16 @@ __global__ __launch_bounds__(256) void syrk_small_nchw_kernel(const SyrkTable ta
 #pragma unroll
             for (int t = 0; t < NTL; ++t) cur[t] = buf[s][t];
             if (done + DEPTH + s < cnt) fetch(buf[s]);
+            to_mfma_lanes(cur);
             mma(cur);
         }
     }
 #pragma unroll
     for (int s = 0; s < DEPTH; ++s) {
-        if (done + s < cnt) mma(buf[s]);
+        if (done + s < cnt) {
+            to_mfma_lanes(buf[s]);
+            mma(buf[s]);
+        }
     }
 
     // add the four waves (fixed order) and write the block's partial tile, row-major BM x BM
