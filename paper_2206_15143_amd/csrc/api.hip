@@ -6,6 +6,7 @@
 
 #include <cstring>
 #include <string>
+#include <tuple>
 #include <vector>
 
 namespace kfac {
@@ -181,27 +182,66 @@ void layer_jobs(const kfac_layer_desc *d, const Geo &g, const void *act, const v
 }
 
 // Layers are processed in chunks whose patch matrices fit a byte budget, so
-// that a chunk's patches are still cache resident when its factor kernel
-// reads them.
-struct Chunk { int first, last; };   // [first, last)
+// that a chunk's patches are still in the last-level cache when the SYRK reads
+// them.  Layers are independent, so the chunks need not follow the caller's
+// order: layers of one shape are kept together (a grouped launch over equal
+// problems has no imbalance between its workgroups) and a run of equal layers
+// longer than a chunk is cut into equal parts.
+struct Chunk { std::vector<int> idx; };
 
-std::vector<Chunk> make_chunks(const std::vector<Geo> &geo)
+std::vector<Chunk> make_chunks(const std::vector<Geo> &geo, const kfac_layer_desc *descs, const int *batch,
+                               const int *h, const int *w)
 {
-    std::vector<Chunk> out;
-    const size_t budget = (size_t)tuning().patch_chunk_bytes;
-    size_t acc = 0;
-    int first = 0;
     const int n = (int)geo.size();
-    for (int i = 0; i < n; ++i) {
+    const int cap = kMaxProblems / 2;
+    const size_t budget = (size_t)tuning().patch_chunk_bytes;
+    auto key = [&](int i) {
+        const kfac_layer_desc &d = descs[i];
+        return std::make_tuple(geo[i].fused3 ? 0 : 1, d.kind, d.in_dtype, d.d_in, d.d_out, d.kh, d.kw, d.stride,
+                               d.pad, d.has_bias, batch[i], h ? h[i] : 1, w ? w[i] : 1);
+    };
+    std::vector<int> order(n);
+    for (int i = 0; i < n; ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return key(a) < key(b); });
+
+    std::vector<Chunk> out;
+    Chunk cur;
+    size_t acc = 0;
+    auto flush = [&]() {
+        if (!cur.idx.empty()) out.push_back(cur);
+        cur.idx.clear();
+        acc = 0;
+    };
+    auto add = [&](int i) {
         const size_t pb = patch_bytes(geo[i]);
-        if (i > first && (acc + pb > budget || i - first >= kMaxProblems / 2)) {
-            out.push_back({first, i});
-            first = i;
-            acc = 0;
-        }
+        if (!cur.idx.empty() && (acc + pb > budget || (int)cur.idx.size() >= cap)) flush();
+        cur.idx.push_back(i);
         acc += pb;
+    };
+    int r0 = 0;
+    while (r0 < n) {
+        int r1 = r0;
+        while (r1 < n && key(order[r1]) == key(order[r0])) ++r1;
+        const int cnt = r1 - r0;
+        if (cnt >= 8) {
+            // a long run of equal layers gets chunks of its own, cut into equal parts
+            flush();
+            const size_t pb = patch_bytes(geo[order[r0]]);
+            int per = cap;
+            if (pb > 0) per = (int)std::max<size_t>(1, std::min<size_t>(cap, budget / pb));
+            const int parts = (cnt + per - 1) / per;
+            const int each = (cnt + parts - 1) / parts;
+            for (int k = 0; k < cnt; ++k) {
+                if (k > 0 && k % each == 0) flush();
+                cur.idx.push_back(order[r0 + k]);
+            }
+            flush();
+        } else {
+            for (int k = r0; k < r1; ++k) add(order[k]);
+        }
+        r0 = r1;
     }
-    if (first < n) out.push_back({first, n});
+    flush();
     return out;
 }
 
@@ -219,12 +259,12 @@ kfac_status plan_update(int n, const kfac_layer_desc *descs, const int *batch, c
         kfac_status st = geometry(&descs[i], batch[i], h ? h[i] : 1, w ? w[i] : 1, pl.geo[i]);
         if (st != KFAC_OK) return st;
     }
-    pl.chunks = make_chunks(pl.geo);
+    pl.chunks = make_chunks(pl.geo, descs, batch, h, w);
     for (const Chunk &c : pl.chunks) {
         size_t pb = 0;
         std::vector<Im2colJob> ij;
         std::vector<FactorJob> fj;
-        for (int i = c.first; i < c.last; ++i) {
+        for (int i : c.idx) {
             // placeholder pointers: only shapes matter for the workspace plan (but alignment
             // decides nothing about sizes)
             layer_jobs(&descs[i], pl.geo[i], nullptr, nullptr, batch[i], h ? h[i] : 1, w ? w[i] : 1, 1.f, 1.f,
@@ -354,7 +394,7 @@ kfac_status kfac_update_factors_batched(int n, const kfac_layer_desc *descs, con
         std::vector<Im2colJob> ij;
         std::vector<FactorJob> fj;
         size_t poff = 0;
-        for (int i = c.first; i < c.last; ++i) {
+        for (int i : c.idx) {
             layer_jobs(&descs[i], pl.geo[i], d_act[i], d_gout[i], batch[i], h ? h[i] : 1, w ? w[i] : 1,
                        scale_A[i], scale_G[i], decay, d_A_run[i], d_G_run[i], patch_base + poff, ij, fj);
             poff += patch_bytes(pl.geo[i]);
