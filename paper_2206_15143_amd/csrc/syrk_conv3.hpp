@@ -179,10 +179,21 @@ __device__ __forceinline__ int conv3_col_offset(const Conv3Geo &G, int col)
     return (cl * G.SR + i) * G.Wp + j - 1;
 }
 
-// rs0 / rs1: per-thread sums of "its" slab row (three shift variants) for the macro tiles of slots 0 / 1
+// Bias border.  Instead of summing every patch column, the workgroup sums the slab rows (channel, input
+// row): a patch column (c, i, j) sees a row shifted by j - 1, so its sum over ow is the full row sum
+// (j = 1), minus the last element (j = 0) or minus the first (j = 2).  The 16-byte pieces of a slab
+// are dealt to all 256 threads (piece p of thread t is item t + 256 p, always the same across stages,
+// so the sums stay in registers); threads below the row count also keep the first and last element
+// of "their" row.  Index 0 / 1: macro tiles of panel slots 0 / 1.
+constexpr int C3_NIT = 4;   // pieces per thread and slab (a slab has at most 1024 pieces)
+struct Conv3ColAcc {
+    float it[2][C3_NIT];
+    float first[2], last[2];
+};
+
 template <int KIND, int NIW>
 __device__ __forceinline__ void conv3_loop(const Conv3Ctx &c, const Conv3Lanes<NIW> &ln, const float *lds,
-                                           floatx4 (&acc)[45], float (&rs0)[3], float (&rs1)[3])
+                                           floatx4 (&acc)[45], Conv3ColAcc &ca)
 {
     const Conv3Geo &G = c.g;
     const int lr = c.lane & 15, lk = c.lane >> 4;
@@ -194,6 +205,19 @@ __device__ __forceinline__ void conv3_loop(const Conv3Ctx &c, const Conv3Lanes<N
         const int tile = c.ctile0 + t;
         cc[t] = (tile < W_NT) ? conv3_col_offset(G, tile * 16 + lr) + lk : 0;
     }
+
+    // slab offsets of this thread's pieces for the row sums (-1: none), the same at every stage
+    int ioff[C3_NIT];
+    {
+        const int w4 = G.W / 4, nitems = G.rows * w4;
+#pragma unroll
+        for (int q = 0; q < C3_NIT; ++q) {
+            const int item = c.tid + 256 * q;
+            const int row = item / w4, x4 = item - row * w4;
+            ioff[q] = (c.owns_colsum && item < nitems) ? row * G.Wp + 4 * x4 : -1;
+        }
+    }
+    const int eoff = (c.owns_colsum && c.tid < G.rows) ? c.tid * G.Wp : -1;
 
     conv3_issue<NIW>(c, ln, 0);
     conv3_issue<NIW>(c, ln, 1);
@@ -227,45 +251,47 @@ __device__ __forceinline__ void conv3_loop(const Conv3Ctx &c, const Conv3Lanes<N
                     ow -= wrap ? G.W : 0;
                     ro += wrap ? G.Wp : 0;
                 };
-                // One copy of the MFMA chain per unit kind (several copies make the compiler shuffle the
-                // 180 accumulator registers between them).  The fetch of the next step is unconditional:
-                // after the last step it reads a little past the stage's rows, still inside the LDS
-                // allocation (next slab or the landing zone), and the values are dropped.  Scheduling
-                // fences keep "13-14 fetches, then 45 MFMAs" as written.
-                Conv3Ops cur, nxt;
-                conv3_load<KIND>(cur, slabR, slabC, cb, cc, ro + ow);
+                // Two register sets of operands used alternately (no copies): while the 45 MFMAs of one
+                // step run, the 13-14 LDS fetches of the next step are already issued into the other
+                // set.  The fetch after the last step reads a little past the stage's rows, still inside
+                // the LDS allocation (next slab or the landing zone), and the values are dropped.
+                // Scheduling fences keep "fetches, then MFMAs" as written.
+                Conv3Ops p, q;
+                conv3_load<KIND>(p, slabR, slabC, cb, cc, ro + ow);
+                int i = 0;
 #pragma unroll 1
-                for (int i = 0; i < steps; ++i) {
+                for (; i + 2 <= steps; i += 2) {
                     advance();
-                    conv3_load<KIND>(nxt, slabR, slabC, cb, cc, ro + ow);
+                    conv3_load<KIND>(q, slabR, slabC, cb, cc, ro + ow);
                     __builtin_amdgcn_sched_barrier(0);
-                    conv3_mma<KIND>(cur, acc);
+                    conv3_mma<KIND>(p, acc);
                     __builtin_amdgcn_sched_barrier(0);
-                    cur = nxt;
+                    advance();
+                    conv3_load<KIND>(p, slabR, slabC, cb, cc, ro + ow);
+                    __builtin_amdgcn_sched_barrier(0);
+                    conv3_mma<KIND>(q, acc);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
+                if (i < steps) conv3_mma<KIND>(p, acc);   // odd number of steps
             }
         }
-        if (c.owns_colsum && c.tid < G.rows) {
-            // Bias border: instead of summing every patch column, each thread sums one slab row
-            // (channel, input row).  A patch column (c, i, j) sees that row shifted by j - 1, so its
-            // sum over ow is the full row sum (j = 1), minus the last element (j = 0) or minus the
-            // first (j = 2); the three variants are accumulated per slab row and turned into the 144
-            // column sums once, after the K loop.
+        if (c.owns_colsum) {
             const int nsl = (KIND == kSingle) ? 3 : 2;
             for (int s = 0; s < nsl; ++s) {
                 if (KIND == kSingle && 3 * g + s >= c.nst) break;
-                const floatx4 *p4 = reinterpret_cast<const floatx4 *>(buf + s * G.slab + c.tid * G.Wp);
-                float sum = 0.f, first = 0.f, last = 0.f;
-                for (int x = 0; x < G.W / 4; ++x) {
-                    const floatx4 v = p4[x];
-                    if (x == 0) first = v.x;
-                    last = v.w;
-                    sum += (v.x + v.y) + (v.z + v.w);
+                const int cls = (KIND == kSingle || s == 0) ? 0 : 1;
+                const float *sl = buf + s * G.slab;
+#pragma unroll
+                for (int q = 0; q < C3_NIT; ++q) {
+                    if (ioff[q] >= 0) {
+                        const floatx4 v = *reinterpret_cast<const floatx4 *>(sl + ioff[q]);
+                        ca.it[cls][q] += (v.x + v.y) + (v.z + v.w);
+                    }
                 }
-                float *t = (KIND == kSingle || s == 0) ? rs0 : rs1;
-                t[0] += sum - last;
-                t[1] += sum;
-                t[2] += sum - first;
+                if (eoff >= 0) {
+                    ca.first[cls] += sl[eoff];
+                    ca.last[cls] += sl[eoff + G.W - 1];
+                }
             }
         }
         conv3_sync<NIW>();
@@ -350,22 +376,44 @@ __global__ __launch_bounds__(256) void syrk_conv3_kernel(const SyrkTable tab)
     floatx4 acc[45];
 #pragma unroll
     for (int i = 0; i < 45; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
-    float rs0[3] = {0.f, 0.f, 0.f}, rs1[3] = {0.f, 0.f, 0.f};
+    Conv3ColAcc ca;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+#pragma unroll
+        for (int q = 0; q < C3_NIT; ++q) ca.it[k][q] = 0.f;
+        ca.first[k] = 0.f;
+        ca.last[k] = 0.f;
+    }
 
-    if (r.kind == kSingle)     conv3_loop<kSingle, NIW>(c, ln, lds, acc, rs0, rs1);
-    else if (r.kind == kDiag)  conv3_loop<kDiag, NIW>(c, ln, lds, acc, rs0, rs1);
-    else if (r.kind == kHalf5) conv3_loop<kHalf5, NIW>(c, ln, lds, acc, rs0, rs1);
-    else                       conv3_loop<kHalf4, NIW>(c, ln, lds, acc, rs0, rs1);
+    if (r.kind == kSingle)     conv3_loop<kSingle, NIW>(c, ln, lds, acc, ca);
+    else if (r.kind == kDiag)  conv3_loop<kDiag, NIW>(c, ln, lds, acc, ca);
+    else if (r.kind == kHalf5) conv3_loop<kHalf5, NIW>(c, ln, lds, acc, ca);
+    else                       conv3_loop<kHalf4, NIW>(c, ln, lds, acc, ca);
 
-    // slab-row sums -> sums of the 144 patch columns of each owned macro tile (the ring is idle now)
+    // piece sums -> slab-row sums (fixed order) -> sums of the 144 patch columns of each owned macro tile
+    // (the ring is idle now)
     float cs0 = 0.f, cs1 = 0.f;
     if (r.owns_colsum) {
-        float *t = lds;                      // [2][rows][3]
+        const int w4 = G.W / 4, nitems = G.rows * w4;
+        float *pieces = lds;                         // [2][nitems]
+        float *t = lds + 2 * nitems;                 // [2][rows][3]
+#pragma unroll
+        for (int q = 0; q < C3_NIT; ++q) {
+            const int item = tid + 256 * q;
+            if (item < nitems) {
+                pieces[item] = ca.it[0][q];
+                pieces[nitems + item] = ca.it[1][q];
+            }
+        }
+        __syncthreads();
         if (tid < G.rows) {
 #pragma unroll
-            for (int j = 0; j < 3; ++j) {
-                t[(0 * G.rows + tid) * 3 + j] = rs0[j];
-                t[(1 * G.rows + tid) * 3 + j] = rs1[j];
+            for (int k = 0; k < 2; ++k) {
+                float sum = 0.f;
+                for (int x = 0; x < w4; ++x) sum += pieces[k * nitems + tid * w4 + x];
+                t[(k * G.rows + tid) * 3 + 0] = sum - ca.last[k];
+                t[(k * G.rows + tid) * 3 + 1] = sum;
+                t[(k * G.rows + tid) * 3 + 2] = sum - ca.first[k];
             }
         }
         __syncthreads();
