@@ -239,6 +239,21 @@ __device__ __forceinline__ void conv3_loop(const Conv3Ctx &c, const Conv3Lanes<N
                 if (KIND == kSingle && 3 * g + s >= c.nst) break;   // past the end of the split: stale rows
                 const float *slabR = buf + ((KIND == kSingle) ? s : c.rslot) * G.slab;
                 const float *slabC = buf + c.cslot * G.slab;
+                // single blocks: the row-sum fetches of this slab go out ahead of the MFMA loop and are
+                // added up after it (their LDS latency hides behind the MFMAs)
+                floatx4 cv[C3_NIT];
+                float cf = 0.f, cl = 0.f;
+                if (KIND == kSingle && c.owns_colsum) {
+#pragma unroll
+                    for (int q = 0; q < C3_NIT; ++q) {
+                        cv[q] = floatx4{0.f, 0.f, 0.f, 0.f};
+                        if (ioff[q] >= 0) cv[q] = *reinterpret_cast<const floatx4 *>(slabR + ioff[q]);
+                    }
+                    if (eoff >= 0) {
+                        cf = slabR[eoff];
+                        cl = slabR[eoff + G.W - 1];
+                    }
+                }
                 // position of the k-step inside the stage: column ow, row offset ro (floats); advanced
                 // without branches so that fetches and MFMAs stay in one basic block
                 const int inc_rows = (inc / G.W) * G.Wp, inc_cols = inc % G.W;
@@ -273,9 +288,15 @@ __device__ __forceinline__ void conv3_loop(const Conv3Ctx &c, const Conv3Lanes<N
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 if (i < steps) conv3_mma<KIND>(p, acc);   // odd number of steps
+                if (KIND == kSingle && c.owns_colsum) {
+#pragma unroll
+                    for (int q = 0; q < C3_NIT; ++q) ca.it[0][q] += (cv[q].x + cv[q].y) + (cv[q].z + cv[q].w);
+                    ca.first[0] += cf;
+                    ca.last[0] += cl;
+                }
             }
         }
-        if (c.owns_colsum) {
+        if (KIND != kSingle && c.owns_colsum) {
             const int nsl = (KIND == kSingle) ? 3 : 2;
             for (int s = 0; s < nsl; ++s) {
                 if (KIND == kSingle && 3 * g + s >= c.nst) break;
