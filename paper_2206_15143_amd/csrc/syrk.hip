@@ -206,17 +206,25 @@ __global__ __launch_bounds__(256) void syrk_reduce_kernel(const SyrkTable tab)
         const int u = bi * T::BM + sr * 16 + r, v = bj * T::BM + sc * 16 + c;
         float out = 0.f;
         if (u < pr.d && v <= u) {
-            // four interleaved running sums (fixed order, so still deterministic) keep loads in flight
-            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+            // sixteen interleaved running sums (fixed order, so still deterministic) keep loads in flight
+            float a[16];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) a[j] = 0.f;
             int k = 0;
-            for (; k + 4 <= pr.splits; k += 4) {
-                s0 += src[(k + 0) * sstride + e];
-                s1 += src[(k + 1) * sstride + e];
-                s2 += src[(k + 2) * sstride + e];
-                s3 += src[(k + 3) * sstride + e];
+            for (; k + 16 <= pr.splits; k += 16) {
+#pragma unroll
+                for (int j = 0; j < 16; ++j) a[j] += src[(k + j) * sstride + e];
             }
-            for (; k < pr.splits; ++k) s0 += src[k * sstride + e];
-            const float sum = (s0 + s1) + (s2 + s3);
+            for (; k + 4 <= pr.splits; k += 4) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) a[j] += src[(k + j) * sstride + e];
+            }
+            for (; k < pr.splits; ++k) a[0] += src[k * sstride + e];
+#pragma unroll
+            for (int h = 8; h > 0; h >>= 1)
+#pragma unroll
+                for (int j = 0; j < h; ++j) a[j] += a[j + h];
+            const float sum = a[0];
             out = pr.decay * pr.F[(long)u * dF + v] + wnew * sum;
             pr.F[(long)u * dF + v] = out;
         }
