@@ -313,8 +313,9 @@ int choose_cfg(int d)
     double best_cost = 1e300;
     for (int i = 0; i < 4; ++i) {
         if (force && kCfgs[i].bm != force) continue;
-        // small tiles re-read the panels more often: mild penalty
-        const double penalty = kCfgs[i].bm >= 128 ? 1.0 : (kCfgs[i].bm >= 64 ? 1.1 : 1.25);
+        // small tiles re-read the panels more often and run at a fraction of the MFMA rate of the large
+        // ones (measured on long-K problems: 32-wide tiles are about 3x slower per padded tile)
+        const double penalty = kCfgs[i].bm >= 128 ? 1.0 : (kCfgs[i].bm >= 64 ? 1.3 : 2.2);
         const double cost = (double)tri_tiles(d, kCfgs[i]) * penalty;
         if (cost < best_cost - 1e-9) { best_cost = cost; best = i; }
     }
