@@ -262,11 +262,12 @@ namespace {
 struct Cfg { int wt, nw, bm; };
 // the last entry is the wave-unit kernel (syrk_wave.hpp): 144-wide macro tiles, same partial layout as Tile<3,3>
 const Cfg kCfgs[] = {{4, 2, 128}, {3, 3, 144}, {2, 2, 64}, {1, 2, 32}, {0, 0, 144}, {0, 0, 144}, {0, 0, 32}, {0, 0, 64},
-                     {0, 0, 256}};
+                     {0, 0, 256}, {0, 0, 144}};
 constexpr int kWaveCfg = 4;
 constexpr int kConv3Cfg = 5;   // fused 3x3 convolution kernel (syrk_conv3.hpp), same partial layout
 constexpr int kSmall32Cfg = 6; // narrow NCHW operands (syrk_small.hpp), partial tile 32 x 32 (d <= 32)
 constexpr int kSmall64Cfg = 7; // same, 64 x 64 (d <= 64)
+constexpr int kWaveNchwCfg = 9; // wave-unit kernel for NCHW fp32 operands (same partial layout as kWaveCfg)
 constexpr int kBf16Cfg = 8;    // row-major bf16 operands on the bf16 MFMA units (syrk_bf16.hpp), 256 x 256 tiles
 
 bool small_eligible(const FactorJob &j)
@@ -286,16 +287,31 @@ bool bf16_eligible(const FactorJob &j)
     return j.layout == kNCHW && j.hw % 2 == 0 && (j.K / j.hw) * (long)j.ctot * j.hw * 2 < 0x7fffffffl;
 }
 
+bool wave_waste_ok(int d)
+{
+    // the wave kernels always multiply whole 45-tile units: use them only where that wastes little
+    // (measured: with a quarter of padding, as 2^n channel counts have, they only tie with the block-tile kernel)
+    const long T = (d + 15) / 16, m = (d + W_MT - 1) / W_MT;
+    const long exact = T * (T + 1) / 2, padded = 45 * m + 81 * m * (m - 1) / 2;
+    return padded * 100 <= exact * 115;
+}
+
+bool wave_nchw_eligible(const FactorJob &j)
+{
+    if (!(tuning().use_wave_kernel && j.dtype == 0 && j.layout == kNCHW && j.hw > 0)) return false;
+    // K stages of 16 positions that never cross an image: small odd maps (7 x 7) would pad K by a quarter
+    const long slots = (j.hw + W_KT - 1) / W_KT * W_KT;
+    if (slots * 10 > (long)j.hw * 11) return false;
+    return (j.K / j.hw) * (long)j.ctot * j.hw * 4 < 0x7fffffffl && wave_waste_ok(j.d_core);
+}
+
 bool wave_eligible(const FactorJob &j)
 {
     // shape-only test (the C ABI requires 16-byte aligned inputs), so that the workspace plan made
     // without pointers matches the launch
     if (!(tuning().use_wave_kernel && j.dtype == 0 && j.layout == kRows && j.ld % 4 == 0 && j.ld < (1l << 22)))
         return false;
-    // the wave kernel always multiplies whole 45-tile units: use it only where that wastes little
-    const long T = (j.d_core + 15) / 16, m = (j.d_core + W_MT - 1) / W_MT;
-    const long exact = T * (T + 1) / 2, padded = 45 * m + 81 * m * (m - 1) / 2;
-    return padded * 100 <= exact * 115;
+    return wave_waste_ok(j.d_core);
 }
 
 // padded MFMA work (in 16x16 tiles) of the lower triangle for a config
@@ -341,7 +357,8 @@ void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<
         const Cfg &c = kCfgs[p.cfg];
         p.nb = (jobs[j].d_core + c.bm - 1) / c.bm;
         p.nblk = p.nb * (p.nb + 1) / 2;
-        p.bps = (p.cfg == kWaveCfg || p.cfg == kConv3Cfg) ? wave_blocks_per_split(p.nb) : p.nblk;
+        p.bps = (p.cfg == kWaveCfg || p.cfg == kConv3Cfg || p.cfg == kWaveNchwCfg) ? wave_blocks_per_split(p.nb)
+                                                                                    : p.nblk;
         if (p.cfg == kConv3Cfg) {
             // K is walked in conv stages of R output rows; count them in units of 16 patch rows
             p.rows_per_stage = conv3_choose_rows(jobs[j].h, jobs[j].w);
@@ -351,7 +368,7 @@ void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<
         }
         // A block that holds a single unit (one macro tile in all) spreads it over its four waves and
         // needs a quarter of the time per K row: give it four times the rows.
-        p.stretch = ((p.cfg == kWaveCfg || p.cfg == kConv3Cfg) && p.nb == 1) ? 4 : 1;
+        p.stretch = ((p.cfg == kWaveCfg || p.cfg == kConv3Cfg || p.cfg == kWaveNchwCfg) && p.nb == 1) ? 4 : 1;
         const long ktiles = (jobs[j].K + 15) / 16;
         work += (double)p.bps * (double)ktiles / p.stretch;
     }
@@ -371,6 +388,8 @@ void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<
             long ktiles = std::max<long>(1, (jobs[j].K + p.unit_rows - 1) / p.unit_rows);
             if (p.cfg == kSmall32Cfg || p.cfg == kSmall64Cfg)   // walked in 16-position groups per image
                 ktiles = (jobs[j].K / jobs[j].hw) * ((jobs[j].hw + 15) / 16);
+            if (p.cfg == kWaveNchwCfg)   // 16-position stages that never cross an image
+                ktiles = (jobs[j].K / jobs[j].hw) * ((jobs[j].hw + W_KT - 1) / W_KT);
             if (p.cfg == kBf16Cfg && jobs[j].layout == kNCHW)   // 32-position stages that never cross an image
                 ktiles = (jobs[j].K / jobs[j].hw) * ((jobs[j].hw + H_KT - 1) / H_KT);
             long tpb_j = std::max<long>(1, tpb * p.stretch * 16 / p.unit_rows);
@@ -405,6 +424,7 @@ void plan_all(const FactorJob *jobs, int n, std::vector<Planned> &pl, std::vecto
         if (jobs[i].layout == kConv3) pl[i].cfg = kConv3Cfg;
         else if (small_eligible(jobs[i])) pl[i].cfg = jobs[i].d_core <= 32 ? kSmall32Cfg : kSmall64Cfg;
         else if (bf16_eligible(jobs[i])) pl[i].cfg = kBf16Cfg;
+        else if (wave_nchw_eligible(jobs[i])) pl[i].cfg = kWaveNchwCfg;
         else pl[i].cfg = wave_eligible(jobs[i]) ? kWaveCfg : choose_cfg(jobs[i].d_core);
         keys[i] = group_key(jobs[i], pl[i].cfg);
     }
@@ -566,6 +586,15 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
                 e = hipGetLastError();
                 if (e != hipSuccess) break;
                 KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<8, 2>>), dim3(red), dim3(256), 0, tab);
+                e = hipGetLastError();
+                break;
+            }
+            case kWaveNchwCfg: {
+                KFAC_LAUNCH(KFAC_K_SYRK_WAVE, s, syrk_wave_nchw_kernel, dim3(blocks), dim3(256), 0, tab);
+                timing_work(flops);
+                e = hipGetLastError();
+                if (e != hipSuccess) break;
+                KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<3, 3>, true>), dim3(red), dim3(256), 0, tab);
                 e = hipGetLastError();
                 break;
             }

@@ -295,4 +295,230 @@ __global__ __launch_bounds__(256) void syrk_wave_kernel(const SyrkTable tab)
     wave_epilogue(pr, r, split, w, lane, tid, nrt, lds, acc, cs0, cs1);
 }
 
+// ---------------------------------------------------------------------------------------------
+// NCHW fp32 operands (inputs of 1x1 convolutions, output gradients of convolutions with more than 64
+// channels): X^T is stored [image][channel][position], so a channel's K values are contiguous.  The
+// panels are staged [144 channels][16 positions] with a pitch of 20 floats (16-byte pieces stay
+// aligned, and the operand read "channel lr, position lk" of 64 lanes spreads two lanes per bank);
+// a K stage never crosses an image, and the positions past the end of an image in its last stage
+// are cleared in the operand registers.  Units, roles, ring and epilogue are those of the row-major
+// kernel above.
+constexpr int WN_PITCH = 20;
+constexpr int WN_PANEL = 12 * 256;                       // floats per panel slot: 12 DMA instructions of 1 KB
+constexpr int WN_STAGE = W_SLOTS * WN_PANEL;
+constexpr int WN_LDS_FLOATS = W_NSTAGE * WN_STAGE + 256;
+
+// one k-step of a DIAG unit; nv = valid positions left in this stage's K tile
+__device__ __forceinline__ void unit_diag_nchw(const float *P, int kk, int lane, int nv, floatx4 (&acc)[45])
+{
+    const int lr = lane & 15, lk = lane >> 4;
+    const float *src = P + lr * WN_PITCH + kk + lk;
+    const bool ok = kk + lk < nv;
+    float a[W_NT];
+#pragma unroll
+    for (int t = 0; t < W_NT; ++t) {
+        const float v = src[t * 16 * WN_PITCH];
+        a[t] = ok ? v : 0.f;
+    }
+#pragma unroll
+    for (int ti = 0; ti < W_NT; ++ti)
+#pragma unroll
+        for (int tj = 0; tj <= ti; ++tj)
+            acc[ti * (ti + 1) / 2 + tj] =
+                __builtin_amdgcn_mfma_f32_16x16x4f32(a[ti], a[tj], acc[ti * (ti + 1) / 2 + tj], 0, 0, 0);
+}
+
+template <int NC>
+__device__ __forceinline__ void unit_half_nchw(const float *Pr, const float *Pc, int kk, int lane, int nv,
+                                               floatx4 (&acc)[45])
+{
+    const int lr = lane & 15, lk = lane >> 4;
+    const float *sr = Pr + lr * WN_PITCH + kk + lk;
+    const float *sc = Pc + lr * WN_PITCH + kk + lk;      // Pc already points at the first column tile
+    const bool ok = kk + lk < nv;
+    float a[W_NT], b[NC];
+#pragma unroll
+    for (int t = 0; t < W_NT; ++t) {
+        const float v = sr[t * 16 * WN_PITCH];
+        a[t] = ok ? v : 0.f;                             // clearing one operand is enough
+    }
+#pragma unroll
+    for (int t = 0; t < NC; ++t) b[t] = sc[t * 16 * WN_PITCH];
+#pragma unroll
+    for (int ti = 0; ti < W_NT; ++ti)
+#pragma unroll
+        for (int tj = 0; tj < NC; ++tj)
+            acc[ti * 5 + tj] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[ti], b[tj], acc[ti * 5 + tj], 0, 0, 0);
+}
+
+struct WaveNCtx {
+    int4v rsrc;
+    unsigned vo[W_SLOTS][3];
+    unsigned lds_base;
+    unsigned img_bytes;          // bytes from one image to the next
+    int tpi, hw;                 // K tiles per image, positions per image
+    int img, kt;                 // (image, tile) of the next K tile to be issued
+    int nslots, ntl, nstages;
+    int w, lane, tid;
+    int rslot, cslot, ctile0;
+    bool single, owns_colsum;
+};
+
+// Issue the loads of ring step g (always nine instructions per wave).  K tiles are issued in order,
+// so the (image, tile) walk advances by one per live slot of a single block, by one per step otherwise.
+__device__ __forceinline__ void waven_issue(WaveNCtx &c, int g)
+{
+    const unsigned buf = c.lds_base + (unsigned)((g & (W_NSTAGE - 1)) * WN_STAGE * 4);
+    const unsigned dummy = c.lds_base + (unsigned)(W_NSTAGE * WN_STAGE * 4);
+#pragma unroll
+    for (int s = 0; s < W_SLOTS; ++s) {
+        const int tl = c.single ? 3 * g + s : g;
+        const bool live = (s < c.nslots) && (g < c.nstages) && (tl < c.ntl);
+        const unsigned so = live ? (unsigned)c.img * c.img_bytes + (unsigned)(c.kt * W_KT * 4) : 0u;
+#pragma unroll
+        for (int qi = 0; qi < 3; ++qi) {
+            const int q = c.w + 4 * qi;                  // 12 instructions per panel: all of them carry pieces
+            const unsigned v = live ? c.vo[s][qi] : W_OOB;
+            dma16(buf + (unsigned)((s * WN_PANEL + q * 256) * 4), v, c.rsrc, so);
+        }
+        const bool adv = c.single ? live : (s == W_SLOTS - 1 && g < c.nstages);
+        if (adv) {
+            if (++c.kt == c.tpi) { c.kt = 0; ++c.img; }
+        }
+    }
+    (void)dummy;
+}
+
+template <int KIND>
+__device__ __forceinline__ void waven_loop(WaveNCtx &c, const float *lds, int img0, int kt0, floatx4 (&acc)[45],
+                                           float &cs0, float &cs1)
+{
+    waven_issue(c, 0);
+    waven_issue(c, 1);
+    waven_issue(c, 2);
+    wave_sync();
+    // (image, tile) of the K tile being multiplied: only the tile index matters (valid positions)
+    int kt = kt0;
+    auto rem_and_next = [&]() {
+        const int nv = c.hw - kt * W_KT;
+        if (++kt == c.tpi) kt = 0;
+        return nv;
+    };
+    (void)img0;
+    for (int g = 0; g < c.nstages; ++g) {
+        waven_issue(c, g + 3);
+        const float *buf = lds + (g & (W_NSTAGE - 1)) * WN_STAGE;
+        int nvs[3];
+        if (KIND == kSingle) {
+#pragma unroll
+            for (int st = 0; st < 3; ++st) nvs[st] = (3 * g + st < c.ntl) ? rem_and_next() : 0;
+#pragma unroll
+            for (int st = 0; st < 3; ++st) unit_diag_nchw(buf + st * WN_PANEL, 4 * c.w, c.lane, nvs[st], acc);
+        } else {
+            nvs[0] = rem_and_next();
+            nvs[1] = nvs[2] = nvs[0];
+            if (KIND == kDiag) {
+                const float *P = buf + c.rslot * WN_PANEL;
+#pragma unroll
+                for (int st = 0; st < 4; ++st) unit_diag_nchw(P, 4 * st, c.lane, nvs[0], acc);
+            } else {
+                const float *Pr = buf + c.rslot * WN_PANEL;
+                const float *Pc = buf + c.cslot * WN_PANEL + c.ctile0 * 16 * WN_PITCH;
+#pragma unroll
+                for (int st = 0; st < 4; ++st)
+                    unit_half_nchw<KIND == kHalf5 ? 5 : 4>(Pr, Pc, 4 * st, c.lane, nvs[0], acc);
+            }
+        }
+        if (c.owns_colsum && c.tid < W_MT) {
+            // column sums of the staged positions (positions past the image end are not counted)
+            const float *c0 = buf + c.tid * WN_PITCH;
+            auto sum16 = [&](const float *p, int nv) {
+                float s = 0.f;
+#pragma unroll
+                for (int k = 0; k < W_KT; ++k) s += (k < nv) ? p[k] : 0.f;
+                return s;
+            };
+            if (KIND == kSingle) {
+                cs0 += (sum16(c0, nvs[0]) + sum16(c0 + WN_PANEL, nvs[1])) + sum16(c0 + 2 * WN_PANEL, nvs[2]);
+            } else {
+                cs0 += sum16(c0, nvs[0]);
+                cs1 += sum16(c0 + WN_PANEL, nvs[0]);
+            }
+        }
+        wave_sync();
+    }
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+__global__ __launch_bounds__(256) void syrk_wave_nchw_kernel(const SyrkTable tab)
+{
+    __shared__ float lds[WN_LDS_FLOATS];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    int pi = 0;
+    while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].blk_start) ++pi;
+    const SyrkProb &pr = tab.p[pi];
+    const int m = pr.nb;
+    const int nbps = wave_blocks_per_split(m);
+    const int local = blockIdx.x - pr.blk_start;
+    const int split = local / nbps;
+    const int b = local - split * nbps;
+    const int ntiles_last = (pr.d - (m - 1) * W_MT + 15) / 16;
+
+    const BlockRole r = decode_role(m, b, w, pr.has_bias != 0);
+    WaveNCtx c;
+    c.single = r.single; c.owns_colsum = r.owns_colsum; c.nslots = r.nslots;
+    c.rslot = r.rslot; c.cslot = r.cslot; c.ctile0 = r.ctile0;
+    const int nrt = (r.I == m - 1) ? ntiles_last : W_NT;
+
+    const int hw = pr.hw;
+    const long nimg = pr.K / hw;
+    c.hw = hw;
+    c.tpi = (hw + W_KT - 1) / W_KT;
+    c.img_bytes = (unsigned)pr.ctot * (unsigned)hw * 4u;
+    const long ktiles = nimg * c.tpi;
+    const long t0 = (long)split * pr.tiles_per_split;
+    const long t1 = (t0 + pr.tiles_per_split < ktiles) ? t0 + pr.tiles_per_split : ktiles;
+    c.ntl = (int)(t1 - t0);
+    c.img = (int)(t0 / c.tpi);
+    c.kt = (int)(t0 - (long)c.img * c.tpi);
+    const int img0 = c.img, kt0 = c.kt;
+    {   // the buffer covers the whole tensor (below 2 GiB, checked on the host)
+        const unsigned long ba = (unsigned long)pr.x;
+        c.rsrc.x = (int)(unsigned)ba;
+        c.rsrc.y = (int)(unsigned)(ba >> 32);
+        c.rsrc.z = (int)(nimg * (long)c.img_bytes);
+        c.rsrc.w = 0x00020000;
+    }
+    c.lds_base = (unsigned)(unsigned long)(__attribute__((address_space(3))) float *)lds;
+    c.w = w; c.lane = lane; c.tid = tid;
+#pragma unroll
+    for (int qi = 0; qi < 3; ++qi) {
+        const int q = w + 4 * qi;
+        const int p = q * 64 + lane;                 // 16-byte piece: channel p / 5, positions 4*(p % 5)..+3
+        const int ch = p / 5, kq = p - ch * 5;
+        const bool pok = ch < W_MT && kq < 4;
+        const int g0 = r.mac0 * W_MT + ch, g1 = r.mac1 * W_MT + ch, g2 = r.mac2 * W_MT + ch;
+        c.vo[0][qi] = (pok && g0 < pr.d) ? (unsigned)((g0 * hw + kq * 4) * 4) : W_OOB;
+        c.vo[1][qi] = (pok && g1 < pr.d) ? (unsigned)((g1 * hw + kq * 4) * 4) : W_OOB;
+        c.vo[2][qi] = (pok && g2 < pr.d) ? (unsigned)((g2 * hw + kq * 4) * 4) : W_OOB;
+    }
+    c.nstages = (c.ntl + (c.single ? 3 : 1) - 1) / (c.single ? 3 : 1);
+
+    floatx4 acc[45];
+#pragma unroll
+    for (int i = 0; i < 45; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+    float cs0 = 0.f, cs1 = 0.f;
+
+    if (r.kind == kSingle)     waven_loop<kSingle>(c, lds, img0, kt0, acc, cs0, cs1);
+    else if (r.kind == kDiag)  waven_loop<kDiag>(c, lds, img0, kt0, acc, cs0, cs1);
+    else if (r.kind == kHalf5) waven_loop<kHalf5>(c, lds, img0, kt0, acc, cs0, cs1);
+    else                       waven_loop<kHalf4>(c, lds, img0, kt0, acc, cs0, cs1);
+
+    wave_epilogue(pr, r, split, w, lane, tid, nrt, lds, acc, cs0, cs1);
+}
+
 }  // namespace kfac

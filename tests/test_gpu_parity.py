@@ -112,6 +112,30 @@ def test_narrow_nchw_output_gradient_factor(cout, h, batch):
     assert gu.rel_fro(direct["G"], tiled["G"]) < 1e-5
 
 
+@pytest.mark.parametrize("cin,cout,h,batch,bias", [
+    (144, 8, 6, 3, True),      # A of a 1x1 conv from NCHW: one macro tile, HW = 36 (4-position tail), bias border
+    (136, 8, 13, 4, False),    # HW = 169 (odd: 4-byte aligned channel rows, 9-position tail), ragged last tile
+    (8, 300, 8, 2, True),      # G with 300 channels: three macro tiles, HW = 64 (no tail)
+    (288, 160, 12, 2, True),   # A two macro tiles, G two macro tiles (d = 160: 10 tiles), HW = 144
+    (144, 8, 7, 3, True),      # HW = 49 would pad K by a quarter: the block-tile kernel takes it
+    (2048 // 8, 130, 4, 2, True),   # d_A = 256 (2^n: padded by a quarter), HW = 16: one K tile per image
+])
+def test_wide_nchw_fp32_factors(cin, cout, h, batch, bias):
+    # fp32 NCHW operands wider than 128 channels take the wave-unit kernel that stages [channel][position]
+    layer = LayerSpec("conv", cin, cout, 1, 1, 0, h, has_bias=bias)
+    _run_and_check([layer], batch, 7700 + cin + h, batched=True)
+    inputs = gu.draw_inputs([layer], batch, 7800, "relu_normal", 0.05)
+    scales = gu.scales_for([layer], batch)
+    wave = gu.run_layers_gpu([layer], batch, inputs, scales, 0.95, 0.03)[0]
+    kf.kfac_tune("use_wave_kernel", 0)
+    try:
+        tiled = gu.run_layers_gpu([layer], batch, inputs, scales, 0.95, 0.03)[0]
+    finally:
+        kf.kfac_tune("use_wave_kernel", 1)
+    assert gu.rel_fro(wave["A"], tiled["A"]) < 1e-5
+    assert gu.rel_fro(wave["G"], tiled["G"]) < 1e-5
+
+
 def test_im2col_alone_is_bit_exact():
     for (cin, k, stride, pad, h, batch) in [(16, 3, 1, 1, 32, 2), (3, 7, 2, 3, 30, 2), (64, 3, 1, 1, 8, 3),
                                             (12, 1, 2, 0, 10, 2), (200, 3, 1, 1, 7, 1), (5, 3, 1, 1, 70, 1),
