@@ -212,8 +212,17 @@ def main():
         with open(tfile) as fh:
             body = "".join(line for line in fh if not line.startswith("#"))
         traffic = json.loads(body).get(dom, {}).get("hbm_bytes_per_launch")
+    # counter-based MFMA busy fraction of the same kernel (rocprofv3 --pmc run, see profiles/), if recorded
+    mfma_busy = None
+    mfile = os.path.join(ROOT, "profiles", f"mfma_util_bench_{args.config}.txt")
+    if os.path.exists(mfile):
+        with open(mfile) as fh:
+            for line in fh:
+                if line.startswith(dom):
+                    mfma_busy = float(line.split()[-3])
+                    break
     roofline = dict(bound="mfma", kernel=dom, achieved=d["achieved"], peak=peak, unit="TFLOP/s", frac=d["frac"],
-                    traffic=traffic, launches_per_step=d["launches_per_step"], avg_launch_ms=d["avg_launch_ms"],
+                    traffic=traffic, mfma_busy_counter=mfma_busy, launches_per_step=d["launches_per_step"], avg_launch_ms=d["avg_launch_ms"],
                     algorithmic_flops_per_launch=d["algorithmic_flops_per_step"] / d["launches_per_step"])
     syrk_flops = work["syrk_A"] + work["syrk_G"]
     assert abs(sum(v["algorithmic_flops_per_step"] for v in per_kernel.values()) - syrk_flops) <= 1e-6 * syrk_flops
