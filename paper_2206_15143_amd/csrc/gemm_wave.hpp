@@ -177,11 +177,9 @@ __global__ __launch_bounds__(256, 2) void gemm_wave_kernel(const GemmWTable tab)
             }
         return;
     }
-    // read-modify-write of the lower triangle: all loads of a tile row are issued before its stores, so a
-    // tile row costs one memory round trip instead of twenty
-#pragma unroll
-    for (int ti = 0; ti < W_NT; ++ti) {
-        float old[5][4];
+    // read-modify-write of the lower triangle: the 20 loads of a tile row are issued together, and the loads
+    // of the next tile row go out before the stores of the current one, so the nine round trips overlap
+    auto load_row = [&](int ti, float (&old)[5][4]) {
 #pragma unroll
         for (int tj = 0; tj < 5; ++tj) {
             const int n = Jw * W_MT + (ctile0 + tj) * 16 + lr;
@@ -192,6 +190,8 @@ __global__ __launch_bounds__(256, 2) void gemm_wave_kernel(const GemmWTable tab)
                 old[tj][v] = ok ? pr.C[(long)m * pr.ldc + n] : 0.f;
             }
         }
+    };
+    auto store_row = [&](int ti, const float (&old)[5][4]) {
 #pragma unroll
         for (int tj = 0; tj < 5; ++tj) {
             const int n = Jw * W_MT + (ctile0 + tj) * 16 + lr;
@@ -202,6 +202,15 @@ __global__ __launch_bounds__(256, 2) void gemm_wave_kernel(const GemmWTable tab)
                 if (ok) pr.C[(long)m * pr.ldc + n] = old[tj][v] - acc[ti * 5 + tj][v];
             }
         }
+    };
+    float oa[5][4], ob[5][4];
+    load_row(0, oa);
+#pragma unroll
+    for (int ti = 0; ti < W_NT; ti += 2) {
+        if (ti + 1 < W_NT) load_row(ti + 1, ob);
+        store_row(ti, oa);
+        if (ti + 2 < W_NT) load_row(ti + 2, oa);
+        if (ti + 1 < W_NT) store_row(ti + 1, ob);
     }
 }
 
