@@ -36,7 +36,8 @@ struct Im2colTable {
 
 template <typename E> struct VecOf;
 template <> struct VecOf<float> { typedef floatx4 type; static constexpr int N = 4; };
-template <> struct VecOf<unsigned short> { typedef uint4 type; static constexpr int N = 8; };
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+template <> struct VecOf<unsigned short> { typedef uintx4 type; static constexpr int N = 8; };
 
 template <typename E>
 __global__ __launch_bounds__(256) void im2col_kernel(const Im2colTable tab)
@@ -118,34 +119,53 @@ __global__ __launch_bounds__(256) void im2col_kernel(const Im2colTable tab)
     }
     __syncthreads();
 
-    // ---- write the rows: item idx = (row, 16-byte column group), consecutive threads take
-    // consecutive items; (row, group) and (oh, ow) advance incrementally (no division per item) ----
+    // ---- write the rows: item = (row, 16-byte column group).  Thread t keeps ONE column group
+    // (t mod ncg) for the whole strip and walks rows t / ncg, t / ncg + rows_per_pass, ...: its VEC slab
+    // offsets are read from the table once and stay in registers, and consecutive threads still write
+    // consecutive 16-byte groups of a row.  (The 256 mod ncg threads past the last whole row idle.) ----
     E *out = reinterpret_cast<E *>(pr.out);
     const long row0 = ((long)n * pr.Ho + oh0) * pr.Wo;
-    const int total = sr * pr.Wo * ncg;
-    const int step_rows = 256 / ncg, step_cg = 256 - step_rows * ncg;
-    int rowl = threadIdx.x / ncg;
-    int cg = threadIdx.x - rowl * ncg;
-    int ohl = rowl / pr.Wo;
-    int ow = rowl - ohl * pr.Wo;
-    for (int idx = threadIdx.x; idx < total; idx += 256) {
-        const int base = ohl * pr.stride * pr.WP + ow * pr.stride;
-        E vals[VEC];
+    const int nrows = sr * pr.Wo;
+    if (ncg <= 256) {
+        const int rows_per_pass = 256 / ncg;
+        int rowl = threadIdx.x / ncg;
+        const int cg = threadIdx.x - rowl * ncg;
+        if (rowl >= rows_per_pass) return;
+        int o[VEC];
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-            const int o = offs[cg * VEC + e];
-            vals[e] = slab[o == slab_elems ? o : o + base];
+        for (int e = 0; e < VEC; ++e) o[e] = offs[cg * VEC + e];
+        int ohl = rowl / pr.Wo;
+        int ow = rowl - ohl * pr.Wo;
+        const int d_oh = rows_per_pass / pr.Wo, d_ow = rows_per_pass - d_oh * pr.Wo;
+        for (; rowl < nrows; rowl += rows_per_pass) {
+            const int base = ohl * pr.stride * pr.WP + ow * pr.stride;
+            E vals[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) vals[e] = slab[o[e] == slab_elems ? o[e] : o[e] + base];
+            typename VecOf<E>::type v;
+            __builtin_memcpy(&v, vals, sizeof(v));
+            *reinterpret_cast<typename VecOf<E>::type *>(out + (row0 + rowl) * pr.ld + col0 + cg * VEC) = v;
+            ohl += d_oh;
+            ow += d_ow;
+            if (ow >= pr.Wo) { ow -= pr.Wo; ++ohl; }
         }
-        typename VecOf<E>::type v;
-        __builtin_memcpy(&v, vals, sizeof(v));
-        *reinterpret_cast<typename VecOf<E>::type *>(out + (row0 + rowl) * pr.ld + col0 + cg * VEC) = v;
-        // next item of this thread: 256 items further
-        cg += step_cg;
-        int dr = step_rows;
-        if (cg >= ncg) { cg -= ncg; ++dr; }
-        rowl += dr;
-        ow += dr;
-        while (ow >= pr.Wo) { ow -= pr.Wo; ++ohl; }
+        return;
+    }
+    // more column groups than threads: every thread walks several groups of each row
+    for (int rowl = 0; rowl < nrows; ++rowl) {
+        const int ohl = rowl / pr.Wo, ow = rowl - ohl * pr.Wo;
+        const int base = ohl * pr.stride * pr.WP + ow * pr.stride;
+        for (int cg = threadIdx.x; cg < ncg; cg += 256) {
+            E vals[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                const int o = offs[cg * VEC + e];
+                vals[e] = slab[o == slab_elems ? o : o + base];
+            }
+            typename VecOf<E>::type v;
+            __builtin_memcpy(&v, vals, sizeof(v));
+            *reinterpret_cast<typename VecOf<E>::type *>(out + (row0 + rowl) * pr.ld + col0 + cg * VEC) = v;
+        }
     }
 }
 
