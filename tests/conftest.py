@@ -8,6 +8,13 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+def pytest_sessionstart(session):
+    # tests load the library that is built; it is compiled here only when there is none at all
+    from paper_2206_15143_amd import binding, build as hip_build
+    if not os.path.exists(binding.lib_path()):
+        hip_build.build()
+
+
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
     config.addinivalue_line("markers", "slow: long-running CPU test")
