@@ -135,6 +135,9 @@ def main():
     import torch
     import paper_2206_15143_amd as kf
     from workloads import shapes
+    if not os.path.exists(kf.lib_path()):   # the library that is built is the one that runs; compile only if there is none
+        from paper_2206_15143_amd import build as hip_build
+        hip_build.build()
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
