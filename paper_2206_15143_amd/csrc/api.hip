@@ -637,6 +637,7 @@ int kfac_tune(const char *key, long value)
     else if (k == "invert_fused_max_n") t.invert_fused_max_n = value;
     else if (k == "use_bf16_mfma") t.use_bf16_mfma = value;
     else if (k == "use_wave_gemm") t.use_wave_gemm = value;
+    else if (k == "gemm_xcd_remap_min") t.gemm_xcd_remap_min = value;
     else if (k == "gemm_bm") t.gemm_bm = value;
     else return 1;
     return 0;

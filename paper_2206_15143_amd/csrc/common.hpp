@@ -103,6 +103,7 @@ struct Tuning {
     long syrk_force_bm = 0;          // 0 = choose
     long use_wave_kernel = 1;        // wave-unit SYRK for aligned row-major fp32 operands
     long use_bf16_mfma = 1;          // row-major bf16 operands: bf16 MFMA kernel instead of widening to fp32
+    long gemm_xcd_remap_min = 8;     // wave GEMM launches with at least this many problems renumber their tiles per XCD
     long use_wave_gemm = 1;          // wide A^T B products on the wave-unit GEMM
     long use_small_kernel = 1;       // direct MFMA kernel for narrow NCHW operands (d <= 64)
     long fuse_conv3 = 1;             // 3x3/s1/p1 fp32 convs: build A straight from the NCHW input
@@ -124,5 +125,17 @@ void timing_work(double work);   // algorithmic work of the launch recorded last
         hipLaunchKernelGGL(kernel, grid, block, smem, stream, __VA_ARGS__);    \
         ::kfac::timing_end((stream));                                          \
     } while (0)
+
+#if defined(__HIPCC__)
+// Workgroups are dealt to the eight XCDs round-robin by the hardware (workgroup i runs on XCD i mod 8).
+// This renumbering gives every XCD a contiguous range of logical block ids, so that neighbouring tiles,
+// which share operand panels, meet in the same XCD's L2.
+__device__ __forceinline__ int xcd_block_id()
+{
+    const int nb = gridDim.x, x = blockIdx.x & 7, idx = blockIdx.x >> 3;
+    const int base = nb >> 3, rem = nb & 7;          // XCD y holds base + (y < rem) workgroups
+    return x * base + (x < rem ? x : rem) + idx;
+}
+#endif
 
 }  // namespace kfac

@@ -161,6 +161,15 @@ hipError_t wave_gemm_launch(const GemmJob *jobs, const std::vector<int> &idx, hi
     long blocks = 0;
     auto flush = [&]() -> hipError_t {
         if (tab.count == 0) return hipSuccess;
+        // Contiguous tile ranges per XCD pay when a launch spans many problems of similar depth (each XCD
+        // then works on a few matrices).  With mixed depths the long workgroups would pile up on one
+        // XCD, and with a handful of problems the round-robin order measured as good or better.
+        int kmin = tab.p[0].K, kmax = tab.p[0].K;
+        for (int k = 1; k < tab.count; ++k) {
+            kmin = std::min(kmin, tab.p[k].K);
+            kmax = std::max(kmax, tab.p[k].K);
+        }
+        tab.xcd_remap = (tab.count >= tuning().gemm_xcd_remap_min && 2 * kmax <= 3 * kmin) ? 1 : 0;
         KFAC_LAUNCH(KFAC_K_GEMM_WAVE, s, gemm_wave_kernel, dim3((unsigned)blocks), dim3(256), 0, tab);
         tab.count = 0;
         blocks = 0;
@@ -204,6 +213,8 @@ hipError_t gemm_launch(const GemmJob *jobs, int n, hipStream_t s)
         }
     }
     if (!wave.empty()) {
+        // deepest products first: launches of similar depth, and the long workgroups start early
+        std::stable_sort(wave.begin(), wave.end(), [&](int a, int b) { return jobs[a].K > jobs[b].K; });
         hipError_t e = wave_gemm_launch(jobs, wave, s);
         if (e != hipSuccess) return e;
     }

@@ -1,8 +1,10 @@
 // C = A^T B (both operands K-major fp32) with the wave-unit tiling of the factor
 // kernel (syrk_wave.hpp): a workgroup owns one 144-wide macro row of A's columns
-// and two adjacent 144-wide macro columns of B's columns; each of its four
-// wavefronts keeps a 9 x 5 or 9 x 4 unit of v_mfma_f32_16x16x4_f32 accumulators
-// for the whole K range.  Panels [16 k][144 columns] are copied from global
+// and two adjacent 144-wide macro columns of B's columns; the 81 MFMA tiles
+// (v_mfma_f32_16x16x4_f32) of a macro tile are cut into units of 40 and 41 for
+// two wavefronts (column tiles 0-3 plus the top four tiles of column 4, and
+// the rest), so the four wavefronts of a workgroup carry equal work; each
+// keeps its accumulators for the whole K range.  Panels [16 k][144 columns] are copied from global
 // memory straight into LDS by buffer_load_dwordx4 ... lds, double buffered: the
 // two stage buffers take 55 KB, so two workgroups share a CU and the prologue
 // and the read-modify-write epilogue of one overlap the MFMA loop of the other.
@@ -34,6 +36,7 @@ struct GemmWProb {
 
 struct GemmWTable {
     int count;
+    int xcd_remap;   // 1: give every XCD a contiguous range of tiles (pays when the launch spans many problems)
     GemmWProb p[kMaxProblems];
 };
 
@@ -68,6 +71,34 @@ __device__ __forceinline__ void gemmw_issue(const GemmWCtx &c, int g)
     }
 }
 
+// Tile (ti, tj) of a unit's 9 x 5 grid (tj counts from the unit's first column tile: 0 for part 0,
+// 4 for part 1).  Part 0 owns columns 0-3 and rows 0-3 of column 4; part 1 owns rows 4-8 of column 4
+// (its local column 0) and columns 5-8.
+template <int PART>
+__device__ __forceinline__ constexpr bool gemmw_owns(int ti, int tj)
+{
+    return PART == 0 ? (tj < 4 || ti < 4) : (tj > 0 || ti >= 4);
+}
+
+template <int PART>
+__device__ __forceinline__ void gemmw_unit(const float *Pr, const float *Pc, int kk, int lane, floatx4 (&acc)[45])
+{
+    const int lr = lane & 15, lk = lane >> 4;
+    const float *sr = Pr + (kk + lk) * W_MT + lr;
+    const float *sc = Pc + (kk + lk) * W_MT + lr;     // Pc already points at the unit's first column tile
+    float a[W_NT], b[5];
+#pragma unroll
+    for (int t = 0; t < W_NT; ++t) a[t] = sr[t * 16];
+#pragma unroll
+    for (int t = 0; t < 5; ++t) b[t] = sc[t * 16];
+#pragma unroll
+    for (int ti = 0; ti < W_NT; ++ti)
+#pragma unroll
+        for (int tj = 0; tj < 5; ++tj)
+            if (gemmw_owns<PART>(ti, tj))
+                acc[ti * 5 + tj] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[ti], b[tj], acc[ti * 5 + tj], 0, 0, 0);
+}
+
 template <int NC>
 __device__ __forceinline__ void gemmw_loop(const GemmWCtx &c, const float *lds, int cslot, int ctile0, int lane,
                                            floatx4 (&acc)[45])
@@ -80,7 +111,7 @@ __device__ __forceinline__ void gemmw_loop(const GemmWCtx &c, const float *lds, 
         const float *Pr = buf;
         const float *Pc = buf + cslot * W_PANEL + ctile0 * 16;
 #pragma unroll
-        for (int st = 0; st < 4; ++st) unit_half<NC>(Pr, Pc, 4 * st, lane, acc);
+        for (int st = 0; st < 4; ++st) gemmw_unit<NC>(Pr, Pc, 4 * st, lane, acc);
         asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
     }
 }
@@ -93,10 +124,11 @@ __global__ __launch_bounds__(256, 2) void gemm_wave_kernel(const GemmWTable tab)
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
 
+    const int bid = tab.xcd_remap ? xcd_block_id() : (int)blockIdx.x;
     int pi = 0;
-    while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].blk_start) ++pi;
+    while (pi + 1 < tab.count && bid >= tab.p[pi + 1].blk_start) ++pi;
     const GemmWProb &pr = tab.p[pi];
-    int local = blockIdx.x - pr.blk_start;
+    int local = bid - pr.blk_start;
     int I, jp;
     if (pr.mode == kSubLowerSkip) {
         // macro row I holds the column pairs with first column 2*jp <= I
@@ -109,8 +141,8 @@ __global__ __launch_bounds__(256, 2) void gemm_wave_kernel(const GemmWTable tab)
     }
     const int J0 = 2 * jp;
     const int Jw = J0 + (w >> 1);          // macro column of this wave
-    const int nc = (w & 1) ? 4 : 5;
-    const int ctile0 = (w & 1) ? 5 : 0;
+    const int part = w & 1;
+    const int ctile0 = part ? 4 : 0;
 
     if (pr.mode == kSubLowerSkip) {
         // macro tiles inside the pivot rows / columns are left untouched (p0 and p1 are multiples of 144)
@@ -151,8 +183,8 @@ __global__ __launch_bounds__(256, 2) void gemm_wave_kernel(const GemmWTable tab)
 #pragma unroll
     for (int i = 0; i < 45; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    if (w & 1) gemmw_loop<4>(c, lds, 1 + (w >> 1), ctile0, lane, acc);
-    else gemmw_loop<5>(c, lds, 1 + (w >> 1), ctile0, lane, acc);
+    if (part) gemmw_loop<1>(c, lds, 1 + (w >> 1), ctile0, lane, acc);
+    else gemmw_loop<0>(c, lds, 1 + (w >> 1), ctile0, lane, acc);
 
     // ---- epilogue: acc[ti*5 + tj][v] = C[I*144 + ti*16 + 4*lk + v][Jw*144 + (ctile0 + tj)*16 + lr] ----
     const int lr = lane & 15, lk = lane >> 4;
@@ -166,7 +198,7 @@ __global__ __launch_bounds__(256, 2) void gemm_wave_kernel(const GemmWTable tab)
         for (int ti = 0; ti < W_NT; ++ti)
 #pragma unroll
             for (int tj = 0; tj < 5; ++tj) {
-                if (tj >= nc) continue;
+                if (!(part ? gemmw_owns<1>(ti, tj) : gemmw_owns<0>(ti, tj))) continue;
                 const int n = Jw * W_MT + (ctile0 + tj) * 16 + lr;
                 if (n >= pr.N) continue;
 #pragma unroll
@@ -186,7 +218,7 @@ __global__ __launch_bounds__(256, 2) void gemm_wave_kernel(const GemmWTable tab)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int m = I * W_MT + ti * 16 + 4 * lk + v;
-                const bool ok = tj < nc && n < pr.N && m < pr.M && n <= m;
+                const bool ok = (part ? gemmw_owns<1>(ti, tj) : gemmw_owns<0>(ti, tj)) && n < pr.N && m < pr.M && n <= m;
                 old[tj][v] = ok ? pr.C[(long)m * pr.ldc + n] : 0.f;
             }
         }
@@ -198,7 +230,7 @@ __global__ __launch_bounds__(256, 2) void gemm_wave_kernel(const GemmWTable tab)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int m = I * W_MT + ti * 16 + 4 * lk + v;
-                const bool ok = tj < nc && n < pr.N && m < pr.M && n <= m;
+                const bool ok = (part ? gemmw_owns<1>(ti, tj) : gemmw_owns<0>(ti, tj)) && n < pr.N && m < pr.M && n <= m;
                 if (ok) pr.C[(long)m * pr.ldc + n] = old[tj][v] - acc[ti * 5 + tj][v];
             }
         }

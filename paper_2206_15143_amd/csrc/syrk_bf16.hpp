@@ -223,10 +223,11 @@ __global__ __launch_bounds__(512) void syrk_bf16_kernel(const SyrkTable tab)
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = w >> 2, wn = w & 3;
 
+    const int bid = xcd_block_id();
     int pi = 0;
-    while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].blk_start) ++pi;
+    while (pi + 1 < tab.count && bid >= tab.p[pi + 1].blk_start) ++pi;
     const SyrkProb &pr = tab.p[pi];
-    const int local = blockIdx.x - pr.blk_start;
+    const int local = bid - pr.blk_start;
     const int nblk = pr.nb * (pr.nb + 1) / 2;
     const int split = local / nblk;
     const int blk = local - split * nblk;
