@@ -49,9 +49,10 @@ const char *kfac_timing_class_name(int cls);
  * against which hardware byte counters are scaled.  Returns 0 on success. */
 int kfac_profile_copy(void *d_dst, const void *d_src, size_t bytes, void *hip_stream);
 
-/* Development knob: "target_blocks", "min_tiles_per_split", "patch_chunk_bytes",
- * "syrk_force_bm".  Returns 0 when the key is known.  Changing a knob changes
- * the workspace requirement: query kfac_workspace_bytes* again afterwards. */
+/* Development knobs (planner targets, kernel selection switches; the keys are listed in
+ * kfac_tune() in csrc/api.hip, e.g. "target_blocks", "patch_chunk_bytes", "fuse_conv3",
+ * "use_bf16_mfma", "invert_fused_max_n").  Returns 0 when the key is known.  Changing a knob can
+ * change the workspace requirement: query kfac_workspace_bytes* again afterwards. */
 int kfac_tune(const char *key, long value);
 
 #ifdef __cplusplus

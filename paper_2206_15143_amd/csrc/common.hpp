@@ -98,7 +98,6 @@ struct Tuning {
     long target_blocks = 512;        // blocks a grouped SYRK launch aims for
     long min_tiles_per_split = 16;   // K tiles (of 16 rows) per split at least
     long patch_chunk_bytes = 160l << 20;   // patch bytes materialised per chunk in the batched path
-    long invert_nb = 64;
     long invert_fused_max_n = 1280;  // orders up to this take the one-launch-per-step sweep
     long syrk_force_bm = 0;          // 0 = choose
     long use_wave_kernel = 1;        // wave-unit SYRK for aligned row-major fp32 operands

@@ -14,22 +14,12 @@ constexpr int W_PANEL = W_KT * W_MT;   // floats per panel stage
 constexpr int W_SLOTS = 3;
 constexpr unsigned W_OOB = 0x80000000u;
 
-typedef __attribute__((address_space(3))) void *lds_ptr_t;
-
 __host__ __device__ inline int wave_blocks_per_split(int m)
 {
     int n = (m + 1) / 2;
     for (int i = 2; i < m; ++i) n += i / 2;
     return n;
 }
-
-struct WaveRole {
-    int rslot, cslot;   // panel slots of the row / column operand
-    int ctile0;         // first column tile inside the column panel
-    int nc;             // column tiles (5 or 4); 0 = DIAG
-    int I, J;           // macro tile written
-    int nrt;            // valid row tiles of macro I
-};
 
 // One k-step (4 rows) of a DIAG unit.  Straight-line code: all 45 tiles are always multiplied (tiles
 // past the matrix edge see zero-filled operands), so every MFMA accumulates in place.
@@ -72,7 +62,6 @@ enum WaveKind : int { kSingle = 0, kDiag = 1, kHalf5 = 2, kHalf4 = 3 };
 constexpr int W_NSTAGE = 4;                              // ring of stage buffers (three stages in flight)
 constexpr int W_STAGE = W_SLOTS * W_PANEL;               // floats per stage buffer
 constexpr int W_LDS_FLOATS = W_NSTAGE * W_STAGE + 256;   // + 1 KB landing zone for the padding loads
-constexpr int W_LOADS_PER_STAGE = 9;                     // buffer->LDS instructions per wave and stage (fixed)
 
 typedef int int4v __attribute__((ext_vector_type(4)));
 
