@@ -1,9 +1,10 @@
 // fp32 MFMA GEMM of the form  C = A^T B  (both operands stored K-major), used
 // for the two-sided preconditioning  P = G_inv * grad * A_inv  (Eq. 5 / rhs of
-// Eq. 12 of the DP-KFAC paper) and for the rank-nb update of the blocked
-// inversion.  Symmetric left factors (G_inv) are read as their own transpose,
-// and the first product is written transposed so that the second product is
-// again of the A^T B form: no operand is ever read with a strided K.
+// Eq. 12 of the DP-KFAC paper): U^T = grad^T G_inv, then P = (U^T)^T A_inv, both
+// with row-major outputs, no operand is ever read with a strided K; and for the
+// panel products and rank-k updates of the blocked inversion.  Wide products
+// go to the wave-unit kernel (gemm_wave.hpp), the rest to the block-tile kernel
+// below.
 #include "gemm_wave.hpp"
 
 #include <algorithm>

@@ -8,12 +8,18 @@
 // from the values the loader already holds, so the ones column is never
 // materialised and the MFMA tiles stay multiples of 16.
 //
-// Two kernels:
-//   syrk_partial_kernel : lower-triangular BM x BM block tiles x split-K slices,
-//                         fp32 MFMA, partial tiles to the workspace.
-//   syrk_reduce_kernel  : sums the slices in a fixed order (deterministic),
-//                         applies scale and the running average, writes both
-//                         triangles.
+// Every factor goes through a partial-product kernel (lower-triangular tiles x
+// split-K slices, partial tiles to the workspace) and the reduction kernel:
+//   syrk_partial_kernel    : block-tile fp32 MFMA kernel, any layout / dtype (this file)
+//   syrk_wave_kernel       : wave-unit kernel, row-major fp32 (syrk_wave.hpp)
+//   syrk_wave_nchw_kernel  : wave-unit kernel, wide NCHW fp32 (syrk_wave.hpp)
+//   syrk_conv3_kernel      : 3x3 convolution inputs, patch matrix never built (syrk_conv3.hpp)
+//   syrk_small_nchw_kernel : narrow NCHW fp32, no LDS staging (syrk_small.hpp)
+//   syrk_bf16_kernel       : bf16 inputs on the bf16 MFMA units (syrk_bf16.hpp)
+//   syrk_reduce_kernel     : sums the slices in a fixed order (deterministic), applies scale and
+//                            the running average, writes both triangles.
+// The planner below picks the kernel and the split of K per factor and groups
+// equal choices into launches of up to 40 factors.
 #include "tn_engine.hpp"
 
 #include <algorithm>
