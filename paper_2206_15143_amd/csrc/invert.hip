@@ -14,10 +14,17 @@
 // pass of n/nb steps, every step is one rank-nb MFMA update of the whole
 // triangle (n^3 flops in total) and the result appears in place.
 //
-// Per step: sweep_pivot_kernel (one workgroup per matrix inverts the nb x nb
-// pivot block in LDS), sweep_panel_kernel (V = old panel, W = V P, both stored
-// K-major for the MFMA update; new panel written in place), then the rank-nb
-// update through the A^T B GEMM (gemm.hip, mode kSubLowerSkip).
+// Two forms, chosen per matrix by its order:
+//   - up to invert_fused_max_n (1280): 64-row blocks, ONE launch per step for all
+//     matrices (invert_fused.hpp): panel product, update and the inversion of
+//     the next pivot block fused;
+//   - above: two-level blocking with 288-row outer blocks (blocked_launch
+//     below): the pivot block is inverted by the first form, the panel product
+//     W = P V and the rank-288 update run on the wave-unit GEMM (gemm.hip, mode
+//     kSubLowerSkip), small kernels gather the old panel K-major and scatter
+//     the new one.
+// kfac_invert_pi computes the two damping terms of Eq. 12 on the device first
+// (pi_damping_kernel) and the kernels above read them through a device pointer.
 #include "invert_fused.hpp"
 
 #include <algorithm>
