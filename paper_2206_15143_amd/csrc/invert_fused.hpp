@@ -148,14 +148,134 @@ __device__ __forceinline__ int sweep64(float (&s)[16], float *colb, float *rowb,
     return fail;
 }
 
+// One pivot of the in-register 16 x 16 sweep (see sweep64_blocked): lane (lr, lk) holds D[lr][4lk..4lk+3].
+template <int K>
+__device__ __forceinline__ void sweep16_pivot(float (&d)[4], int lr, int lk, int c0, int &fail)
+{
+    float rk[4];
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+        rk[m] = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(d[m]), 0x150 + K, 0xf, 0xf, false));
+    // the pivot D[K][K] sits in lane K + 16*(K>>2), register K & 3
+    const float p = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(d[K & 3]), K + 16 * (K >> 2)));
+    if (!(p > 0.f) && fail == 0) fail = c0 + K + 1;
+    const float ip = __builtin_amdgcn_rcpf(p);
+    // column element D[i][K] = D[K][i]: element i of the row, held by lane i + 16*(i>>2) in register i & 3
+    float mine = rk[0];
+    mine = (lr & 3) == 1 ? rk[1] : mine;
+    mine = (lr & 3) == 2 ? rk[2] : mine;
+    mine = (lr & 3) == 3 ? rk[3] : mine;
+    const float ci = __int_as_float(__builtin_amdgcn_ds_bpermute((lr + 16 * (lr >> 2)) * 4, __float_as_int(mine)));
+    const float cip = ci * ip;
+    const bool prow = (lr == K);
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        const float upd = __builtin_fmaf(-cip, rk[m], d[m]);
+        const float onr = rk[m] * ip;
+        float v = prow ? onr : upd;
+        if (m == (K & 3)) v = (lk == (K >> 2)) ? (prow ? -ip : cip) : v;
+        d[m] = v;
+    }
+}
+
+// Blocked form of the same sweep for a 64 x 64 block held in LDS (full symmetric storage, row pitch
+// SW_PITCH; blocks smaller than 64 are padded with the identity by the caller).  Four sub-steps of 16
+// pivots.  Per sub-step: wavefront 0 sweeps the 16 x 16 pivot block inside its registers (lane (i, q)
+// holds D[i][4q..4q+3]; the pivot row reaches the lanes by DPP row broadcast, the pivot column, equal to
+// the row by symmetry, by one ds_bpermute: no barrier inside the 16 pivots); then all four wavefronts
+// form W = V P and the rank-16 update of the other blocks on the MFMA units and write the new panel.
+// On exit S holds the swept block (-inverse).  Pb: [16][17], Wb: [64][17] scratch.
+// Returns 0 or the 1-based index (within the block) of the first non-positive pivot (valid in wave 0).
+constexpr int SW_PITCH = 68;
+
+__device__ __forceinline__ int sweep64_blocked(float *S, float *Pb, float *Wb, int tid)
+{
+    const int lane = tid & 63, w = tid >> 6;
+    const int lr = lane & 15, lk = lane >> 4;
+    int fail = 0;
+#pragma unroll 1
+    for (int kb = 0; kb < 4; ++kb) {
+        const int c0 = kb * 16;
+        if (w == 0) {
+            // ---- the 16 x 16 pivot block, in registers ----
+            float d[4];
+            {
+                const floatx4 v = *reinterpret_cast<const floatx4 *>(S + (c0 + lr) * SW_PITCH + c0 + 4 * lk);
+                d[0] = v.x; d[1] = v.y; d[2] = v.z; d[3] = v.w;
+            }
+            sweep16_pivot<0>(d, lr, lk, c0, fail);
+            sweep16_pivot<1>(d, lr, lk, c0, fail);
+            sweep16_pivot<2>(d, lr, lk, c0, fail);
+            sweep16_pivot<3>(d, lr, lk, c0, fail);
+            sweep16_pivot<4>(d, lr, lk, c0, fail);
+            sweep16_pivot<5>(d, lr, lk, c0, fail);
+            sweep16_pivot<6>(d, lr, lk, c0, fail);
+            sweep16_pivot<7>(d, lr, lk, c0, fail);
+            sweep16_pivot<8>(d, lr, lk, c0, fail);
+            sweep16_pivot<9>(d, lr, lk, c0, fail);
+            sweep16_pivot<10>(d, lr, lk, c0, fail);
+            sweep16_pivot<11>(d, lr, lk, c0, fail);
+            sweep16_pivot<12>(d, lr, lk, c0, fail);
+            sweep16_pivot<13>(d, lr, lk, c0, fail);
+            sweep16_pivot<14>(d, lr, lk, c0, fail);
+            sweep16_pivot<15>(d, lr, lk, c0, fail);
+            // P = -swept block
+#pragma unroll
+            for (int m = 0; m < 4; ++m) Pb[lr * 17 + 4 * lk + m] = -d[m];
+        }
+        __syncthreads();
+        // ---- W = V P for the row tile of this wavefront (rows 16w..16w+15) ----
+        if (w != kb) {
+            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4) {
+                const float a = S[(16 * w + lr) * SW_PITCH + c0 + 4 * s4 + lk];
+                const float b = Pb[(4 * s4 + lk) * 17 + lr];
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v) Wb[(16 * w + 4 * lk + v) * 17 + lr] = acc[v];
+        }
+        __syncthreads();
+        // ---- S_ij -= W_i V_j^T for the nine blocks outside the pivot row and column ----
+        for (int t = w; t < 9; t += 4) {
+            const int r3 = t / 3, c3 = t - 3 * r3;
+            const int bi = r3 + (r3 >= kb ? 1 : 0), bj = c3 + (c3 >= kb ? 1 : 0);
+            floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4) {
+                const float a = Wb[(16 * bi + lr) * 17 + 4 * s4 + lk];
+                const float b = S[(16 * bj + lr) * SW_PITCH + c0 + 4 * s4 + lk];
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v) S[(16 * bi + 4 * lk + v) * SW_PITCH + 16 * bj + lr] -= acc[v];
+        }
+        __syncthreads();
+        // ---- new panel (both triangles) and pivot block ----
+        for (int e = tid; e < 64 * 16; e += 256) {
+            const int i = e >> 4, c = e & 15;
+            if ((i >> 4) != kb) {
+                const float wv = Wb[i * 17 + c];
+                S[i * SW_PITCH + c0 + c] = wv;
+                S[(c0 + c) * SW_PITCH + i] = wv;
+            } else {
+                S[i * SW_PITCH + c0 + c] = -Pb[(i - c0) * 17 + c];
+            }
+        }
+        __syncthreads();
+    }
+    return fail;
+}
+
 // Workgroup 0 of a matrix inverts the first pivot block; workgroup r >= 1 copies block r of the first
 // column panel K-major into V[0] (transposed through LDS), so that step 0 stages its panels like any
 // other step.
 __global__ __launch_bounds__(256) void fsweep_pivot0_kernel(const InvSeq q)
 {
-    __shared__ float colb[2 * 64];
-    __shared__ __attribute__((aligned(16))) float rowb[2 * 64];
-    __shared__ float tile[64][65];
+    __shared__ __attribute__((aligned(16))) float sbuf[64 * SW_PITCH];
+    __shared__ __attribute__((aligned(16))) float pw[16 * 17 + 64 * 17];
+    float (*tile)[65] = reinterpret_cast<float (*)[65]>(sbuf);
     int prob, local, ci;
     if (!seq_locate(q, blockIdx.x, prob, local, ci)) return;
     const InvProbF pr = q.tab[prob];
@@ -173,31 +293,30 @@ __global__ __launch_bounds__(256) void fsweep_pivot0_kernel(const InvSeq q)
         }
         return;
     }
-    const int i = tid >> 2, jq = tid & 3;
     const int bs = min(FNB, pr.n);
     const long ldm = pr.ldm, ldw = pr.ldw;
     const float damping = pr.dptr ? *pr.dptr : pr.damping;
-    float s[16];
-#pragma unroll
-    for (int m = 0; m < 16; ++m) {
-        const int j = jq + 4 * m;
+    for (int e = tid; e < FNB * FNB; e += 256) {
+        const int i = e >> 6, j = e & 63;
         float v = (i == j) ? 1.f : 0.f;
         if (i < bs && j < bs) {
             const int a = max(i, j), b = min(i, j);
             v = pr.M[a * ldm + b] + (a == b ? damping : 0.f);
         }
-        s[m] = v;
+        sbuf[i * SW_PITCH + j] = v;
     }
-    const int fail = sweep64(s, colb, rowb, tid);
+    __syncthreads();
+    int fail = sweep64_blocked(sbuf, pw, pw + 16 * 17, tid);
+    fail = __builtin_amdgcn_readfirstlane(fail);
     const bool whole = pr.nblk == 1;   // the block is the matrix: store the result itself, both triangles
-#pragma unroll
-    for (int m = 0; m < 16; ++m) {
-        const int j = jq + 4 * m;
+    for (int e = tid; e < FNB * FNB; e += 256) {
+        const int i = e >> 6, j = e & 63;
         const bool in = (i < bs && j < bs);
-        pr.P[i * FNB + j] = in ? -s[m] : 0.f;
+        const float v = sbuf[i * SW_PITCH + j];
+        pr.P[i * FNB + j] = in ? -v : 0.f;
         if (in && j <= i) {
-            pr.W[i * ldw + j] = whole ? -s[m] : s[m];
-            if (whole) pr.W[j * ldw + i] = -s[m];
+            pr.W[i * ldw + j] = whole ? -v : v;
+            if (whole) pr.W[j * ldw + i] = -v;
         }
     }
     if (tid == 0) *pr.info = (fail <= bs) ? fail : 0;
@@ -212,8 +331,6 @@ __global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
     // not staged: every lane keeps its 32 operand values of P in registers.
     __shared__ __attribute__((aligned(16))) float Va[FNB * PITCH];   // V of the tile's row block (or the panel block)
     __shared__ __attribute__((aligned(16))) float Vb[FNB * PITCH];   // V of the tile's column block, or W^T
-    __shared__ float colb[2 * 64];
-    __shared__ __attribute__((aligned(16))) float rowb[2 * 64];
 
     int prob, t, ci;
     if (!seq_locate(q, blockIdx.x, prob, t, ci)) return;
@@ -429,22 +546,20 @@ __global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
     // ---- this workgroup holds the next pivot block: invert it now ----
     __syncthreads();
     {
-        const int i = tid >> 2, jq = tid & 3;
-        float s[16];
-#pragma unroll
-        for (int m = 0; m < 16; ++m) {
-            const int j = jq + 4 * m;
+        for (int e = tid; e < FNB * FNB; e += 256) {
+            const int i = e >> 6, j = e & 63;
             float v = (i == j) ? 1.f : 0.f;
             if (i < bs1 && j < bs1) v = (j <= i) ? Va[i * PITCH + j] : Va[j * PITCH + i];
-            s[m] = v;
+            Vb[i * SW_PITCH + j] = v;
         }
-        const int fail = sweep64(s, colb, rowb, tid);
-#pragma unroll
-        for (int m = 0; m < 16; ++m) {
-            const int j = jq + 4 * m;
+        __syncthreads();
+        const int fail = sweep64_blocked(Vb, Va, Va + 16 * 17, tid);
+        for (int e = tid; e < FNB * FNB; e += 256) {
+            const int i = e >> 6, j = e & 63;
             const bool in = (i < bs1 && j < bs1);
-            Pn[i * FNB + j] = in ? -s[m] : 0.f;
-            if (in && j <= i) pr.W[(long)(p1 + i) * ldw + p1 + j] = s[m];
+            const float v = Vb[i * SW_PITCH + j];
+            Pn[i * FNB + j] = in ? -v : 0.f;
+            if (in && j <= i) pr.W[(long)(p1 + i) * ldw + p1 + j] = v;
         }
         // launches of one sequence are ordered, so the first failing pivot wins
         if (fail != 0 && fail <= bs1 && tid == 0 && *pr.info == 0) *pr.info = p1 + fail;
