@@ -90,64 +90,6 @@ __device__ __forceinline__ bool seq_locate(const InvSeq &q, int blk, int &prob, 
     return true;
 }
 
-// Unblocked sweep of a 64 x 64 block held in registers: thread (i = tid >> 2, jq = tid & 3) owns
-// S[i][jq + 4m], m = 0..15.  Per elimination step only the pivot row and column travel through LDS
-// (double buffered): one barrier, five LDS reads and ~50 VALU operations per thread.  The step
-// index is a compile-time constant after unrolling, so the pivot-column fix-up and the publication
-// of the next row/column need no dynamic register indexing.  Blocks smaller than 64 are padded
-// with the identity by the caller; the padded pivots are 1 and change nothing.
-// colb: [2][64]; rowb: [2][4][16] (row k stored as rowb[jq][m] = S[k][jq + 4m]).
-// Returns 0 or the 1-based index (within the block) of the first non-positive pivot.
-__device__ __forceinline__ int sweep64(float (&s)[16], float *colb, float *rowb, int tid)
-{
-    const int i = tid >> 2, jq = tid & 3;
-    if (jq == 0) colb[i] = s[0];
-    if (i == 0) {
-#pragma unroll
-        for (int m = 0; m < 16; ++m) rowb[jq * 16 + m] = s[m];
-    }
-    __syncthreads();
-    int fail = 0;
-#pragma unroll
-    for (int k = 0; k < FNB; ++k) {
-        const int b = k & 1;
-        const float *rb = rowb + b * 64;
-        const float p = rb[(k & 3) * 16 + (k >> 2)];
-        if (!(p > 0.f) && fail == 0) fail = k + 1;
-        const float ip = __builtin_amdgcn_rcpf(p);   // 1 ulp reciprocal: far below the fp32 error of the sweep
-        const float ci = colb[b * 64 + i];
-        const float cip = ci * ip;
-        const bool prow = (i == k);
-        float rk[16];
-#pragma unroll
-        for (int m4 = 0; m4 < 4; ++m4) {
-            const floatx4 v = *reinterpret_cast<const floatx4 *>(rb + jq * 16 + 4 * m4);
-            rk[4 * m4 + 0] = v.x; rk[4 * m4 + 1] = v.y; rk[4 * m4 + 2] = v.z; rk[4 * m4 + 3] = v.w;
-        }
-#pragma unroll
-        for (int m = 0; m < 16; ++m) {
-            const float upd = __builtin_fmaf(-cip, rk[m], s[m]);
-            const float onr = rk[m] * ip;
-            s[m] = prow ? onr : upd;
-        }
-        // pivot column (j == k): -1/p on the pivot itself, c/p elsewhere
-        if (jq == (k & 3)) s[k >> 2] = prow ? -ip : cip;
-        if (k + 1 < FNB) {
-            const int kn = k + 1;
-            if (jq == (kn & 3)) colb[(b ^ 1) * 64 + i] = s[kn >> 2];
-            if (i == kn) {
-                float *wb = rowb + (b ^ 1) * 64 + jq * 16;
-#pragma unroll
-                for (int m4 = 0; m4 < 4; ++m4)
-                    *reinterpret_cast<floatx4 *>(wb + 4 * m4) =
-                        floatx4{s[4 * m4], s[4 * m4 + 1], s[4 * m4 + 2], s[4 * m4 + 3]};
-            }
-            __syncthreads();
-        }
-    }
-    return fail;
-}
-
 // One pivot of the in-register 16 x 16 sweep (see sweep64_blocked): lane (lr, lk) holds D[lr][4lk..4lk+3].
 template <int K>
 __device__ __forceinline__ void sweep16_pivot(float (&d)[4], int lr, int lk, int c0, int &fail)
@@ -159,7 +101,7 @@ __device__ __forceinline__ void sweep16_pivot(float (&d)[4], int lr, int lk, int
     // the pivot D[K][K] sits in lane K + 16*(K>>2), register K & 3
     const float p = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(d[K & 3]), K + 16 * (K >> 2)));
     if (!(p > 0.f) && fail == 0) fail = c0 + K + 1;
-    const float ip = __builtin_amdgcn_rcpf(p);
+    const float ip = __builtin_amdgcn_rcpf(p);   // 1 ulp reciprocal: far below the fp32 error of the sweep
     // column element D[i][K] = D[K][i]: element i of the row, held by lane i + 16*(i>>2) in register i & 3
     float mine = rk[0];
     mine = (lr & 3) == 1 ? rk[1] : mine;
@@ -178,7 +120,7 @@ __device__ __forceinline__ void sweep16_pivot(float (&d)[4], int lr, int lk, int
     }
 }
 
-// Blocked form of the same sweep for a 64 x 64 block held in LDS (full symmetric storage, row pitch
+// Sweep of a 64 x 64 pivot block held in LDS (full symmetric storage, row pitch
 // SW_PITCH; blocks smaller than 64 are padded with the identity by the caller).  Four sub-steps of 16
 // pivots.  Per sub-step: wavefront 0 sweeps the 16 x 16 pivot block inside its registers (lane (i, q)
 // holds D[i][4q..4q+3]; the pivot row reaches the lanes by DPP row broadcast, the pivot column, equal to
@@ -306,8 +248,7 @@ __global__ __launch_bounds__(256) void fsweep_pivot0_kernel(const InvSeq q)
         sbuf[i * SW_PITCH + j] = v;
     }
     __syncthreads();
-    int fail = sweep64_blocked(sbuf, pw, pw + 16 * 17, tid);
-    fail = __builtin_amdgcn_readfirstlane(fail);
+    const int fail = sweep64_blocked(sbuf, pw, pw + 16 * 17, tid);   // valid in wavefront 0
     const bool whole = pr.nblk == 1;   // the block is the matrix: store the result itself, both triangles
     for (int e = tid; e < FNB * FNB; e += 256) {
         const int i = e >> 6, j = e & 63;
@@ -327,7 +268,7 @@ __global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
 {
     typedef Tile<2, 2> T;
     constexpr int PITCH = T::PITCH;   // 80
-    // two operand buffers (41 KB with the sweep's row/column buffers: three workgroups per CU).  P is
+    // two operand buffers (40 KB: three workgroups per CU; the pivot-block sweep reuses them).  P is
     // not staged: every lane keeps its 32 operand values of P in registers.
     __shared__ __attribute__((aligned(16))) float Va[FNB * PITCH];   // V of the tile's row block (or the panel block)
     __shared__ __attribute__((aligned(16))) float Vb[FNB * PITCH];   // V of the tile's column block, or W^T
