@@ -635,6 +635,10 @@ int kfac_tune(const char *key, long value)
     else if (k == "update_bm") t.update_bm = value;
     else if (k == "use_small_kernel") t.use_small_kernel = value;
     else if (k == "invert_fused_max_n") t.invert_fused_max_n = value;
+    else if (k == "im2col_piece_elems") t.im2col_piece_elems = value;
+    else if (k == "im2col_block_bytes") t.im2col_block_bytes = value;
+    else if (k == "im2col_lds_bytes") t.im2col_lds_bytes = value;
+    else if (k == "im2col_min_blocks") t.im2col_min_blocks = value;
     else if (k == "use_bf16_mfma") t.use_bf16_mfma = value;
     else if (k == "use_wave_gemm") t.use_wave_gemm = value;
     else if (k == "gemm_xcd_remap_min") t.gemm_xcd_remap_min = value;

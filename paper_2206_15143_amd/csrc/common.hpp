@@ -98,6 +98,10 @@ struct Tuning {
     long target_blocks = 512;        // blocks a grouped SYRK launch aims for
     long min_tiles_per_split = 16;   // K tiles (of 16 rows) per split at least
     long patch_chunk_bytes = 160l << 20;   // patch bytes materialised per chunk in the batched path
+    long im2col_piece_elems = 128;   // patch extraction: elements of one output row a workgroup writes at least
+    long im2col_block_bytes = 80 * 1024;  // output bytes per workgroup aimed for
+    long im2col_lds_bytes = 20 * 1024;    // slab budget of a workgroup
+    long im2col_min_blocks = 1024;   // shorter strips until a layer has this many workgroups
     long invert_fused_max_n = 1280;  // orders up to this take the one-launch-per-step sweep
     long syrk_force_bm = 0;          // 0 = choose
     long use_wave_kernel = 1;        // wave-unit SYRK for aligned row-major fp32 operands

@@ -179,44 +179,38 @@ size_t smem_bytes(const Im2colProb &p, int esz)
     return slab + (size_t)(p.CC * p.kh * p.kw + 16) * sizeof(int);
 }
 
-void plan(Im2colProb &p, int esz, int sr_cap)
+// Strip height SR and channel chunk CC of a layer.  Measured over the 3x3 / 7x7, stride 1 / 2 shapes of
+// the workloads, alone and inside the grouped factor update: the slab of a workgroup should stay near
+// 20 KB (several workgroups per CU, so the load phase of one hides behind the stores of others) and the
+// channel chunk narrow (pieces of ~128 elements per output row), which leaves the slab to a taller
+// strip: the halo rows are re-read once per strip.
+void plan_enough_blocks(Im2colProb &p, int esz)
 {
+    const Tuning &t = tuning();
     const int vec = 16 / esz;
     const int kk = p.kh * p.kw;
     const int g = vec / gcd(kk, vec);             // CC must be a multiple of g (or the whole of C)
     p.WP = (p.Wo - 1) * p.stride + p.kw;
-    int SR = std::max(1, std::min(p.Ho, (128 + p.Wo - 1) / p.Wo));
-    if (sr_cap > 0) SR = std::min(SR, sr_cap);
-    const size_t budget = 20 * 1024;   // small slabs: several workgroups per CU overlap their load and store phases
-    for (;;) {
-        p.SR = SR;
-        p.IR = (SR - 1) * p.stride + p.kh;
-        // largest channel chunk that fits
-        const size_t per_c = (size_t)p.IR * p.WP * esz + (size_t)kk * sizeof(int);
-        long cc = (long)((budget - 256) / per_c);
-        if (cc >= p.C) {
-            p.CC = p.C;
-        } else {
-            cc = cc / g * g;
-            p.CC = (int)cc;
-        }
-        if (p.CC >= 1 && (p.CC == p.C || p.CC % g == 0)) break;
-        if (SR == 1) { p.CC = std::min(p.C, g); break; }   // tiny chunk: still correct
-        SR = std::max(1, SR / 2);
-    }
-    p.nstrips = (p.Ho + p.SR - 1) / p.SR;
-    p.nchunks = (p.C + p.CC - 1) / p.CC;
-}
-
-// Shorter strips until the layer alone gives the device a few workgroups per CU.
-void plan_enough_blocks(Im2colProb &p, int esz)
-{
-    plan(p, esz, 0);
-    int cap = p.SR;
-    while ((long)p.B * p.nstrips * p.nchunks < 1024 && cap > 1) {
-        cap = (cap + 1) / 2;
-        plan(p, esz, cap);
-    }
+    auto set = [&](int sr, int cc) {
+        p.SR = sr;
+        p.IR = (sr - 1) * p.stride + p.kh;
+        p.CC = cc;
+        p.nstrips = (p.Ho + sr - 1) / sr;
+        p.nchunks = (p.C + cc - 1) / cc;
+    };
+    auto slab = [&](int sr, int cc) { return (size_t)cc * ((sr - 1) * p.stride + p.kh) * p.WP * esz + (size_t)cc * kk * 4 + 512; };
+    const size_t lds = (size_t)std::min(60l * 1024, std::max(2048l, t.im2col_lds_bytes));
+    long cc = ((t.im2col_piece_elems + kk - 1) / kk + g - 1) / g * g;
+    if (cc >= p.C) cc = p.C;
+    while (cc > g && cc != p.C && slab(1, (int)cc) > lds) cc -= g;
+    if (cc == p.C && slab(1, (int)cc) > lds) cc = std::max<long>(g, (long)(p.C / g) * g);
+    while (cc > g && slab(1, (int)cc) > lds) cc -= g;
+    const long row_bytes = (long)p.Wo * cc * kk * esz;      // output of one strip row of the chunk
+    int sr = (int)std::max(1l, std::min<long>(p.Ho, t.im2col_block_bytes / std::max(1l, row_bytes)));
+    while (sr > 1 && slab(sr, (int)cc) > lds) --sr;
+    set(sr, (int)cc);
+    while (sr > 1 && (long)p.B * p.nstrips * p.nchunks < t.im2col_min_blocks) set(--sr, (int)cc);
+    set((p.Ho + p.nstrips - 1) / p.nstrips, (int)cc);   // same number of strips, equal heights
 }
 
 }  // namespace
@@ -230,7 +224,7 @@ hipError_t im2col_launch(const Im2colJob *jobs, int n, hipStream_t s)
         size_t smem = 0;
         auto flush = [&]() -> hipError_t {
             if (tab.count == 0) return hipSuccess;
-            if (smem > 64 * 1024) return hipErrorInvalidValue;   // slab of one output row does not fit LDS
+            if (smem > 64 * 1024) return hipErrorInvalidValue;   // slab of one output row of the smallest chunk does not fit LDS
             if (dt == 0)
                 KFAC_LAUNCH(KFAC_K_IM2COL, s, (im2col_kernel<float>), dim3(blocks), dim3(256), smem, tab);
             else
