@@ -193,7 +193,7 @@ std::vector<Chunk> make_chunks(const std::vector<Geo> &geo, const kfac_layer_des
                                const int *h, const int *w)
 {
     const int n = (int)geo.size();
-    const int cap = kMaxProblems / 2;
+    const int cap = kMaxProblems;   // the A and the G factors of conv layers go to different kernels: one table each
     const size_t budget = (size_t)tuning().patch_chunk_bytes;
     auto key = [&](int i) {
         const kfac_layer_desc &d = descs[i];
