@@ -164,10 +164,11 @@ __global__ __launch_bounds__(T::NT) void syrk_partial_kernel(const SyrkTable tab
     }
 }
 
-// Split reduction + running average.  Each block owns 1024 consecutive elements
+// Split reduction + running average.  Each block owns kRedGroup 16 x 16 sub-tiles
 // of one BM x BM tile of the lower triangle (plus, with a bias, one block per
 // block row for the border).  Fixed summation order over the splits.
 constexpr int kRedChunk = 256;
+constexpr int kRedGroup = 4;   // sub-tiles per block
 
 // NATIVE: the partial tiles are stored as the MFMA accumulators lie in registers (per 16x16 tile
 // [lane][4], tiles row-major inside the 144-wide macro tile), which lets the wave kernels store
@@ -185,64 +186,89 @@ __global__ __launch_bounds__(256) void syrk_reduce_kernel(const SyrkTable tab)
     constexpr int TILE = T::BM * T::BM;
     constexpr int CPT = (TILE + kRedChunk - 1) / kRedChunk;   // chunks per tile
 
-    if (local < nblk * CPT) {
-        // one 16 x 16 sub-tile per block: thread t holds one element; the mirror image goes through LDS so
-        // that both stores run along rows of F
-        __shared__ float mir[16][17];
-        const int tile = local / CPT;
-        const int chunk = local - tile * CPT;
+    constexpr int GPT = (CPT + kRedGroup - 1) / kRedGroup;    // blocks per tile
+    if (local < nblk * GPT) {
+        // kRedGroup 16 x 16 sub-tiles per block: thread t holds one element of each; all loads are issued
+        // before the first store.  The mirror image goes through LDS so that both stores run along rows of F.
+        __shared__ float mir[kRedGroup][16][17];
+        const int tile = local / GPT;
+        const int grp = local - tile * GPT;
         int bi, bj;
         tri_decode(tile, bi, bj);
         const float *src = pr.partial + (long)tile * TILE;
         const long sstride = (long)nblk * TILE;
         constexpr int S = T::BM / 16;            // sub-tiles per tile side
-        const int sr = chunk / S, sc = chunk - sr * S;
         const int t = threadIdx.x;
-        int r, c, e;
+        int r, c;
         if (NATIVE) {
             const int ln = t >> 2, vv = t & 3;
             r = 4 * (ln >> 4) + vv;
             c = ln & 15;
-            e = chunk * 256 + t;
         } else {
             r = t >> 4;
             c = t & 15;
-            e = (sr * 16 + r) * T::BM + sc * 16 + c;
         }
-        const int u = bi * T::BM + sr * 16 + r, v = bj * T::BM + sc * 16 + c;
-        float out = 0.f;
-        if (u < pr.d && v <= u) {
-            // sixteen interleaved running sums (fixed order, so still deterministic) keep loads in flight
-            float a[16];
+        float sum[kRedGroup], old[kRedGroup];
+        bool live[kRedGroup];
 #pragma unroll
-            for (int j = 0; j < 16; ++j) a[j] = 0.f;
-            int k = 0;
-            for (; k + 16 <= pr.splits; k += 16) {
+        for (int q = 0; q < kRedGroup; ++q) {
+            const int chunk = grp * kRedGroup + q;
+            const int sr = chunk / S, sc = chunk - sr * S;
+            const int e = NATIVE ? chunk * 256 + t : (sr * 16 + r) * T::BM + sc * 16 + c;
+            const int u = bi * T::BM + sr * 16 + r, v = bj * T::BM + sc * 16 + c;
+            live[q] = chunk < CPT && u < pr.d && v <= u;
+            sum[q] = 0.f;
+            old[q] = 0.f;
+            if (live[q]) {
+                old[q] = pr.F[(long)u * dF + v];
+                if (pr.splits == 1) {
+                    sum[q] = src[e];
+                } else {
+                    // sixteen interleaved running sums (fixed order, so still deterministic) keep loads in flight
+                    float a[16];
 #pragma unroll
-                for (int j = 0; j < 16; ++j) a[j] += src[(k + j) * sstride + e];
+                    for (int j = 0; j < 16; ++j) a[j] = 0.f;
+                    int k = 0;
+                    for (; k + 16 <= pr.splits; k += 16) {
+#pragma unroll
+                        for (int j = 0; j < 16; ++j) a[j] += src[(k + j) * sstride + e];
+                    }
+                    for (; k + 4 <= pr.splits; k += 4) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) a[j] += src[(k + j) * sstride + e];
+                    }
+                    for (; k < pr.splits; ++k) a[0] += src[k * sstride + e];
+#pragma unroll
+                    for (int h = 8; h > 0; h >>= 1)
+#pragma unroll
+                        for (int j = 0; j < h; ++j) a[j] += a[j + h];
+                    sum[q] = a[0];
+                }
             }
-            for (; k + 4 <= pr.splits; k += 4) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) a[j] += src[(k + j) * sstride + e];
-            }
-            for (; k < pr.splits; ++k) a[0] += src[k * sstride + e];
-#pragma unroll
-            for (int h = 8; h > 0; h >>= 1)
-#pragma unroll
-                for (int j = 0; j < h; ++j) a[j] += a[j + h];
-            const float sum = a[0];
-            out = pr.decay * pr.F[(long)u * dF + v] + wnew * sum;
-            pr.F[(long)u * dF + v] = out;
         }
-        mir[r][c] = out;
+#pragma unroll
+        for (int q = 0; q < kRedGroup; ++q) {
+            const int chunk = grp * kRedGroup + q;
+            const int sr = chunk / S, sc = chunk - sr * S;
+            const int u = bi * T::BM + sr * 16 + r, v = bj * T::BM + sc * 16 + c;
+            float out = 0.f;
+            if (live[q]) {
+                out = pr.decay * old[q] + wnew * sum[q];
+                pr.F[(long)u * dF + v] = out;
+            }
+            mir[q][r][c] = out;
+        }
         __syncthreads();
-        {
+#pragma unroll
+        for (int q = 0; q < kRedGroup; ++q) {
+            const int chunk = grp * kRedGroup + q;
+            const int sr = chunk / S, sc = chunk - sr * S;
             const int c2 = t >> 4, r2 = t & 15;
             const int u2 = bi * T::BM + sr * 16 + r2, v2 = bj * T::BM + sc * 16 + c2;
-            if (u2 < pr.d && v2 < u2) pr.F[(long)v2 * dF + u2] = mir[r2][c2];
+            if (chunk < CPT && u2 < pr.d && v2 < u2) pr.F[(long)v2 * dF + u2] = mir[q][r2][c2];
         }
     } else {
-        const int bi = local - nblk * CPT;
+        const int bi = local - nblk * GPT;
         const float *csum = pr.partial + (long)pr.splits * nblk * TILE;
         for (int r = threadIdx.x; r < T::BM; r += 256) {
             const int u = bi * T::BM + r;
@@ -536,7 +562,8 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
             {
                 const int bm = kCfgs[pl[j].cfg].bm;
                 const int cpt = (bm * bm + kRedChunk - 1) / kRedChunk;
-                red += pl[j].nblk * cpt + (job.has_bias ? pl[j].nb : 0);
+                const int gpt = (cpt + kRedGroup - 1) / kRedGroup;
+                red += pl[j].nblk * gpt + (job.has_bias ? pl[j].nb : 0);
             }
         }
         const int cfg = pl[g[0]].cfg;
