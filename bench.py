@@ -50,8 +50,8 @@ def make_inputs(layers, batch, hp, seed, torch, dev):
     acts, gouts, grads = [], [], []
     for l in layers:
         if l.kind == "conv":
-            ashape = (batch, l.c_in, l.h_in, l.h_in)
-            gshape = (batch, l.c_out, l.h_out, l.h_out)
+            ashape = (batch, l.c_in, l.h_in, l.w)
+            gshape = (batch, l.c_out, l.h_out, l.w_out)
         else:
             ashape = (l.rows, l.c_in)
             gshape = (l.rows, l.c_out)
@@ -153,6 +153,7 @@ def main():
     descs = [kf.LayerDesc.from_spec(l, kf.KFAC_BF16 if bf else kf.KFAC_F32) for l in layers]
     b = [batch if l.kind == "conv" else l.rows for l in layers]
     h = [l.h_in if l.kind == "conv" else 1 for l in layers]
+    w = [l.w if l.kind == "conv" else 1 for l in layers]
     sc = [shapes.layer_scales(l, batch) for l in layers]
     sA, sG = [s[0] for s in sc], [s[1] for s in sc]
 
@@ -163,11 +164,11 @@ def main():
     G_inv = [torch.empty((l.d_G, l.d_G), device=dev) for l in layers]
     outs = [torch.empty((l.d_G, l.d_A), device=dev) for l in layers]
     info = torch.zeros(2 * len(layers), dtype=torch.int32, device=dev)
-    ws = torch.empty(kf.kfac_workspace_bytes_batched(descs, b, h, h), dtype=torch.uint8, device=dev)
+    ws = torch.empty(kf.kfac_workspace_bytes_batched(descs, b, h, w), dtype=torch.uint8, device=dev)
     lam = hp["damping"]
 
     def step():
-        kf.kfac_update_factors_batched(descs, acts, gouts, b, h, h, sA, sG, hp["decay"], A_run, G_run, ws)
+        kf.kfac_update_factors_batched(descs, acts, gouts, b, h, w, sA, sG, hp["decay"], A_run, G_run, ws)
         kf.kfac_invert_batched(descs, A_run, G_run, lam, lam, A_inv, G_inv, info, ws)
         kf.kfac_precondition_batched(descs, A_inv, G_inv, grads, outs, ws)
 
@@ -233,9 +234,9 @@ def main():
     achieved = syrk_flops / (syrk_ms * 1e-3) / 1e12
     extra = dict(kf_gemm_kernels=per_kernel)
     im2 = im2col_leg(kf, torch,
-                     lambda w_: kf.kfac_update_factors_batched(descs, acts, gouts, b, h, h, sA, sG, hp["decay"],
+                     lambda w_: kf.kfac_update_factors_batched(descs, acts, gouts, b, h, w, sA, sG, hp["decay"],
                                                                A_run, G_run, w_),
-                     lambda: kf.kfac_workspace_bytes_batched(descs, b, h, h), work, args.steps)
+                     lambda: kf.kfac_workspace_bytes_batched(descs, b, h, w), work, args.steps)
     if im2:
         extra["im2col"] = im2
 

@@ -138,7 +138,7 @@ def precondition_eigen(QG, vG, QA, vA, grad, gamma: float) -> np.ndarray:
 def layer_rows(layer, act: np.ndarray, gout: np.ndarray):
     """(a_bar [R, d_A], g [R, d_G]) for a workloads.LayerSpec."""
     if layer.kind == "conv":
-        abar = patches(act, layer.k, layer.k, layer.stride, layer.pad, layer.has_bias)
+        abar = patches(act, layer.k, layer.kw, layer.stride, layer.pad, layer.has_bias)
         g = rows_from_nchw(gout)
     else:
         abar = linear_rows(act, layer.has_bias)

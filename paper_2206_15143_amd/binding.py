@@ -39,9 +39,10 @@ class LayerDesc(C.Structure):
 
     @staticmethod
     def from_spec(spec, dtype: int = KFAC_F32) -> "LayerDesc":
-        """From a workloads.LayerSpec-like object (kind, c_in, c_out, k, stride, pad, has_bias)."""
+        """From a workloads.LayerSpec-like object (kind, c_in, c_out, k, stride, pad, has_bias; kw if present)."""
         if spec.kind == "conv":
-            return LayerDesc.conv2d(spec.c_in, spec.c_out, spec.k, spec.stride, spec.pad, spec.has_bias, dtype)
+            return LayerDesc.conv2d(spec.c_in, spec.c_out, spec.k, spec.stride, spec.pad, spec.has_bias, dtype,
+                                    kw=getattr(spec, "kw", None))
         return LayerDesc.linear(spec.c_in, spec.c_out, spec.has_bias, dtype)
 
 

@@ -32,7 +32,8 @@ def workspace(nbytes: int) -> torch.Tensor:
 def batch_args(layers, batch):
     b = [batch if l.kind == "conv" else l.rows for l in layers]
     h = [l.h_in if l.kind == "conv" else 1 for l in layers]
-    return b, h, list(h)
+    w = [l.w if l.kind == "conv" else 1 for l in layers]
+    return b, h, w
 
 
 class GpuLayerResult:

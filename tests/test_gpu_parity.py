@@ -154,6 +154,36 @@ def test_im2col_alone_is_bit_exact():
         assert np.all(got[:, ref.shape[1]:] == 0)
 
 
+def test_im2col_nonsquare_kernels_and_maps_bit_exact():
+    for (cin, kh, kw, stride, pad, h, w, batch) in [(8, 1, 7, 1, 0, 17, 17, 2), (8, 7, 1, 1, 0, 17, 23, 2),
+                                                    (5, 1, 3, 1, 1, 8, 12, 3), (6, 3, 5, 2, 2, 21, 30, 2),
+                                                    (4, 5, 2, 1, 0, 9, 40, 1), (16, 3, 3, 1, 1, 6, 50, 2)]:
+        print("im2col", cin, kh, kw, stride, pad, h, w, batch, flush=True)
+        x = rng.draw_relu_normal(78, 0, (batch, cin, h, w))
+        desc = kf.LayerDesc.conv2d(cin, 4, kh, stride, pad, kw=kw)
+        ld = kf.kfac_patch_ld(desc)
+        ho = (h + 2 * pad - kh) // stride + 1
+        wo = (w + 2 * pad - kw) // stride + 1
+        out = torch.full((batch * ho * wo, ld), float("nan"), device=gu.DEV)
+        kf.kfac_im2col(desc, gu.to_dev(x), batch, h, w, out)
+        torch.cuda.synchronize()
+        ref = orc.patches(x, kh, kw, stride, pad, has_bias=False)
+        got = out.cpu().numpy()
+        assert np.array_equal(got[:, :ref.shape[1]].astype(np.float64), ref)
+        assert np.all(got[:, ref.shape[1]:] == 0)
+
+
+@pytest.mark.parametrize("cin,kh,kw,h,w,pad,bias", [(24, 1, 7, 17, 17, 0, True), (24, 7, 1, 9, 14, 0, True),
+                                                    (24, 3, 1, 8, 12, 1, False), (32, 3, 3, 10, 16, 1, True),
+                                                    (16, 3, 3, 12, 8, 1, True)])
+def test_nonsquare_layer_end_to_end(cin, kh, kw, h, w, pad, bias):
+    # kernel height != width and map height != width through all three calls (3 x 3 with a multiple of
+    # 16 channels takes the fused convolution kernel, here on non-square maps)
+    layer = LayerSpec("conv", cin, 20, kh, 1, pad, h, has_bias=bias, k_w=kw, w_in=w)
+    _run_and_check([layer], 6, 9100 + 10 * kh + kw, batched=True)
+    _run_and_check([layer], 6, 9200 + 10 * kh + kw, batched=False)
+
+
 @pytest.mark.parametrize("n", [1, 5, 64, 65, 130, 257, 400])
 def test_inverse_sizes(n):
     gen = np.random.default_rng(n)

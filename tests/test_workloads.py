@@ -45,6 +45,23 @@ def test_layer_counts_and_dims():
     assert (l1[0].d_A, l1[0].d_G, l1[0].rows) == (65, 32, 32)
 
 
+def test_further_layer_sets():
+    v = shapes.config_layers("vgg16_cifar")
+    assert len(v) == 16 and sum(1 for l in v if l.kind == "conv") == 13
+    assert max(l.d_A for l in v) == 4609 and {l.h_in for l in v if l.kind == "conv"} == {32, 16, 8, 4, 2}
+    inc = shapes.config_layers("inception_nonsquare")
+    assert all(l.k != l.kw for l in inc)
+    l = inc[2]                                             # 1x7 kernel on a 17 x 23 map, no padding
+    assert (l.h_out, l.w_out, l.d_A, l.n_rows(32)) == (17, 17, 224 * 7 + 1, 32 * 17 * 17)
+    a, g, _ = rng.layer_inputs(l, 2, 5, "relu_normal", 0.1)
+    assert a.shape == (2, 224, 17, 23) and g.shape == (2, 256, 17, 17)
+    b = shapes.config_layers("bert_base_small_batch")
+    assert len(b) == 72 and all(l.rows == 512 and l.rows < l.d_A for l in b)
+    # the square shorthand still means what it meant
+    s = shapes.LayerSpec("conv", 4, 8, 3, 1, 1, 10)
+    assert (s.kw, s.w, s.w_out, s.d_core) == (3, 10, 10, 36)
+
+
 def test_generator_is_counter_based_and_seeded():
     a = rng.draw_normal(7, 0, (1000,))
     b = rng.draw_normal(7, 0, (5000,))

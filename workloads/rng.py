@@ -88,8 +88,8 @@ def layer_inputs(layer, batch: int, seed: int, act_kind: str, gout_std: float, d
     are exactly representable in bfloat16 (already rounded).
     """
     if layer.kind == "conv":
-        ashape = (batch, layer.c_in, layer.h_in, layer.h_in)
-        gshape = (batch, layer.c_out, layer.h_out, layer.h_out)
+        ashape = (batch, layer.c_in, layer.h_in, layer.w)
+        gshape = (batch, layer.c_out, layer.h_out, layer.w_out)
     else:
         ashape = (layer.rows, layer.c_in)
         gshape = (layer.rows, layer.c_out)

@@ -1,4 +1,4 @@
-"""Layer-shape tables of the five synthetic workloads.
+"""Layer-shape tables of the synthetic workloads (five headline configurations and three further sets).
 
 The shapes stand in for the networks the paper trains (section 6.1: ResNet-110
 on Cifar-10, ResNet-50 on ImageNet, Transformer encoder blocks).  Only the
@@ -23,14 +23,28 @@ class LayerSpec:
     h_in: int = 1        # conv input spatial size (square)
     rows: int = 0        # linear: number of rows (samples / tokens)
     has_bias: bool = True
+    k_w: int = 0         # conv kernel width when it differs from k (0: square)
+    w_in: int = 0        # conv input width when it differs from h_in (0: square)
+
+    @property
+    def kw(self) -> int:
+        return self.k_w if self.k_w > 0 else self.k
+
+    @property
+    def w(self) -> int:
+        return self.w_in if self.w_in > 0 else self.h_in
 
     @property
     def h_out(self) -> int:
         return (self.h_in + 2 * self.pad - self.k) // self.stride + 1
 
     @property
+    def w_out(self) -> int:
+        return (self.w + 2 * self.pad - self.kw) // self.stride + 1
+
+    @property
     def d_core(self) -> int:
-        return self.c_in * self.k * self.k if self.kind == "conv" else self.c_in
+        return self.c_in * self.k * self.kw if self.kind == "conv" else self.c_in
 
     @property
     def d_A(self) -> int:
@@ -43,11 +57,11 @@ class LayerSpec:
     def n_rows(self, batch: int) -> int:
         """Rows R of the patch matrix (conv: batch * H_out * W_out)."""
         if self.kind == "conv":
-            return batch * self.h_out * self.h_out
+            return batch * self.h_out * self.w_out
         return self.rows
 
     def needs_im2col(self) -> bool:
-        return self.kind == "conv" and (self.k > 1 or self.stride > 1 or self.pad > 0)
+        return self.kind == "conv" and (self.k > 1 or self.kw > 1 or self.stride > 1 or self.pad > 0)
 
 
 def _conv(cin, cout, k, h, stride=1, pad=None):
@@ -95,6 +109,40 @@ def _cfg5() -> List[LayerSpec]:
     return block * 24
 
 
+def _vgg16_cifar(batch: int) -> List[LayerSpec]:
+    """VGG-16-shaped stack for 32x32 inputs (one of the CNNs of section 6.1): thirteen 3x3 convolutions
+    with 64..512 channels (A dims up to 4609), three fully connected layers."""
+    layers = []
+    cin, h = 3, 32
+    for cout, reps in ((64, 2), (128, 2), (256, 3), (512, 3), (512, 3)):
+        for _ in range(reps):
+            layers.append(_conv(cin, cout, 3, h))
+            cin = cout
+        h //= 2                                                        # 2x2 pooling between the groups
+    layers += [LayerSpec("linear", 512, 512, rows=batch), LayerSpec("linear", 512, 512, rows=batch),
+               LayerSpec("linear", 512, 10, rows=batch)]
+    return layers
+
+
+def _inception_nonsquare() -> List[LayerSpec]:
+    """Factorised 1x7 / 7x1 and 1x3 / 3x1 convolutions with the channel counts of Inception-v4's 17x17 and
+    8x8 stages (section 6.1 lists Inception-v4).  The layer descriptor has one padding value for both
+    directions, so the layers are taken unpadded (the asymmetric "same" padding of the network is not
+    expressible); one layer has a non-square input map."""
+    def ns(cin, cout, kh, kw, h, w=0):
+        return LayerSpec("conv", cin, cout, kh, 1, 0, h, k_w=kw, w_in=w)
+    return [ns(192, 192, 1, 7, 17), ns(192, 224, 7, 1, 17), ns(224, 256, 1, 7, 17, 23),
+            ns(384, 256, 1, 3, 8), ns(384, 256, 3, 1, 8), ns(448, 512, 3, 1, 8, 12)]
+
+
+def _bert_small_batch() -> List[LayerSpec]:
+    """BERT-base-shaped linear layers (hidden 768, FFN 3072, 12 blocks) with 4 sequences of 128 tokens per
+    update (the fine-tuning batch size of section 6.1): 512 rows, so every un-averaged factor is rank-deficient."""
+    block = [LayerSpec("linear", 768, 768, rows=512)] * 4
+    block += [LayerSpec("linear", 768, 3072, rows=512), LayerSpec("linear", 3072, 768, rows=512)]
+    return block * 12
+
+
 # name -> (layers, hyper-parameters)
 CONFIGS: Dict[str, dict] = {
     "fc_tiny": dict(index=1, batch=32, dtype="f32", act="normal", gout_var=1e-2,
@@ -107,6 +155,13 @@ CONFIGS: Dict[str, dict] = {
                                    damping=0.001, decay=0.95),
     "transformer_encoder_bf16": dict(index=5, batch=32, dtype="bf16", act="normal", gout_var=1e-4,
                                      damping=0.003, decay=0.95),
+    # further layer sets of the networks section 6.1 names (not headline configurations)
+    "vgg16_cifar": dict(index=6, batch=128, dtype="f32", act="relu_normal", gout_var=1e-3,
+                        damping=0.03, decay=0.95),
+    "inception_nonsquare": dict(index=7, batch=32, dtype="f32", act="relu_normal", gout_var=1e-3,
+                                damping=0.001, decay=0.95),
+    "bert_base_small_batch": dict(index=8, batch=4, dtype="f32", act="normal", gout_var=1e-4,
+                                  damping=0.003, decay=0.95),
 }
 
 
@@ -125,6 +180,12 @@ def config_layers(name: str) -> List[LayerSpec]:
         return _resnet50(hp["batch"])
     if idx == 5:
         return _cfg5()
+    if idx == 6:
+        return _vgg16_cifar(hp["batch"])
+    if idx == 7:
+        return _inception_nonsquare()
+    if idx == 8:
+        return _bert_small_batch()
     raise KeyError(name)
 
 
@@ -155,8 +216,8 @@ def algorithmic_work(layers: List[LayerSpec], batch: int, in_bytes: int) -> dict
         w["syrk_G"] += R * l.d_G * (l.d_G + 1)
         w["invert"] += l.d_A ** 3 + l.d_G ** 3
         w["precond"] += 2 * l.d_G * l.d_G * l.d_A + 2 * l.d_G * l.d_A * l.d_A
-        if l.kind == "conv" and l.k > 1:
-            w["im2col_read"] += batch * l.c_in * l.h_in * l.h_in * in_bytes
+        if l.kind == "conv" and (l.k > 1 or l.kw > 1):
+            w["im2col_read"] += batch * l.c_in * l.h_in * l.w * in_bytes
             w["im2col_write"] += R * l.d_A * in_bytes
         w["syrk_in_bytes"] += R * (l.d_A + l.d_G) * in_bytes
         w["ema_bytes"] += 4 * (l.d_A * (l.d_A + 1) + l.d_G * (l.d_G + 1))
