@@ -94,7 +94,7 @@ def im2col_leg(kf, torch, step_update, ws_bytes_fn, work, steps):
                 frac=round(gbs / 8000.0, 4), ms_per_step=round(ms / reps, 4), launches_per_step=n // reps,
                 avg_launch_ms=round(ms / n, 5), algorithmic_bytes_per_step=total,
                 note="factor update repeated with the fused 3x3 path off so that every k>1 conv layer "
-                     "goes through the extractor (grouped launches of up to 20 layers)")
+                     "goes through the extractor (grouped launches of up to 40 layers)")
 
 
 def cpu_baseline(config, layers, hp):
@@ -182,6 +182,24 @@ def main():
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
     assert int(info.abs().sum().item()) == 0, "a factor was flagged not positive definite"
 
+    # the three calls timed one by one, for the stale-factor schedule of the paper's last experiment
+    # (factors refreshed every F_freq iterations, inverses every K_freq, preconditioning every iteration)
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) * 1e3 / args.steps
+    t_upd = timed(lambda: kf.kfac_update_factors_batched(descs, acts, gouts, b, h, w, sA, sG, hp["decay"], A_run, G_run, ws))
+    t_inv = timed(lambda: kf.kfac_invert_batched(descs, A_run, G_run, lam, lam, A_inv, G_inv, info, ws))
+    t_pre = timed(lambda: kf.kfac_precondition_batched(descs, A_inv, G_inv, grads, outs, ws))
+    F_FREQ, K_FREQ = 50, 500
+    schedule = dict(update_factors_ms=round(t_upd, 4), invert_ms=round(t_inv, 4), precondition_ms=round(t_pre, 4),
+                    F_freq=F_FREQ, K_freq=K_FREQ,
+                    amortised_ms_per_iteration=round(t_pre + t_upd / F_FREQ + t_inv / K_FREQ, 4))
+
     # per-kernel-class durations: the same steps again with a HIP-event pair around every launch
     kf.kfac_timing_enable(True)
     for _ in range(args.steps):
@@ -232,7 +250,7 @@ def main():
     assert abs(sum(v["algorithmic_flops_per_step"] for v in per_kernel.values()) - syrk_flops) <= 1e-6 * syrk_flops
     syrk_ms = sum(v["ms_per_step"] for v in per_kernel.values())
     achieved = syrk_flops / (syrk_ms * 1e-3) / 1e12
-    extra = dict(kf_gemm_kernels=per_kernel)
+    extra = dict(kf_gemm_kernels=per_kernel, stale_schedule=schedule)
     im2 = im2col_leg(kf, torch,
                      lambda w_: kf.kfac_update_factors_batched(descs, acts, gouts, b, h, w, sA, sG, hp["decay"],
                                                                A_run, G_run, w_),

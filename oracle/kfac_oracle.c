@@ -28,8 +28,10 @@
  *                               Gauss-Jordan route.
  *   oracle_precondition       - right-hand side of Eq. 12 / Eq. 5:
  *                               P = G_inv * grad * A_inv.
- *   oracle_precondition_eigen - Eq. 13 given eigen-decompositions (used by the
- *                               tests to confirm the Kronecker algebra).
+ *   oracle_eigh_jacobi        - eigen-decomposition M = Q diag(v) Q^T of a symmetric factor
+ *                               (the Q_A, v_A, Q_G, v_G of Eq. 13) by the classical cyclic
+ *                               Jacobi rotation method; eigenvalues ascending.
+ *   oracle_precondition_eigen - Eq. 13 given eigen-decompositions.
  *
  * Parity pins live in tests/test_oracle_*.py (closed forms, brute-force
  * Kronecker product, Woodbury identity, direct convolution, rank, PSD).
@@ -239,6 +241,70 @@ void oracle_precondition(const double *Ginv, const double *grad, const double *A
             P[(long)i * dA + j] = s;
         }
     free(T);
+}
+
+/* Symmetric eigen-decomposition by cyclic Jacobi: sweep over all (p, q), p < q, and annihilate M[p][q] by the
+ * plane rotation whose tangent is the smaller root of t^2 + 2 tau t - 1 = 0, tau = (M[q][q] - M[p][p]) / (2 M[p][q]);
+ * the product of the rotations is Q.  Stops when the off-diagonal norm is below 1e-15 of the total norm
+ * (or after 60 sweeps).  On exit v is ascending and column k of Q (row-major n x n) belongs to v[k].
+ * Returns the number of sweeps. */
+int oracle_eigh_jacobi(const double *M, int n, double *Q, double *v)
+{
+    double *A = (double *)malloc(sizeof(double) * (size_t)n * n);
+    memcpy(A, M, sizeof(double) * (size_t)n * n);
+    for (int i = 0; i < n; ++i)
+        for (int j = 0; j < n; ++j) Q[(long)i * n + j] = (i == j) ? 1.0 : 0.0;
+    int sweep = 0;
+    for (; sweep < 60; ++sweep) {
+        double off = 0.0, tot = 0.0;
+        for (int i = 0; i < n; ++i)
+            for (int j = 0; j < n; ++j) {
+                const double a = A[(long)i * n + j];
+                tot += a * a;
+                if (i != j) off += a * a;
+            }
+        if (off <= 1e-30 * tot) break;
+        for (int p = 0; p < n - 1; ++p)
+            for (int q = p + 1; q < n; ++q) {
+                const double apq = A[(long)p * n + q];
+                if (apq == 0.0) continue;
+                const double tau = (A[(long)q * n + q] - A[(long)p * n + p]) / (2.0 * apq);
+                const double t = (tau >= 0.0 ? 1.0 : -1.0) / (fabs(tau) + sqrt(1.0 + tau * tau));
+                const double c = 1.0 / sqrt(1.0 + t * t), sn = t * c;
+                for (int k = 0; k < n; ++k) {          /* columns p, q:  A <- A J */
+                    const double akp = A[(long)k * n + p], akq = A[(long)k * n + q];
+                    A[(long)k * n + p] = c * akp - sn * akq;
+                    A[(long)k * n + q] = sn * akp + c * akq;
+                }
+                for (int k = 0; k < n; ++k) {          /* rows p, q:  A <- J^T A */
+                    const double apk = A[(long)p * n + k], aqk = A[(long)q * n + k];
+                    A[(long)p * n + k] = c * apk - sn * aqk;
+                    A[(long)q * n + k] = sn * apk + c * aqk;
+                }
+                for (int k = 0; k < n; ++k) {          /* Q <- Q J */
+                    const double qkp = Q[(long)k * n + p], qkq = Q[(long)k * n + q];
+                    Q[(long)k * n + p] = c * qkp - sn * qkq;
+                    Q[(long)k * n + q] = sn * qkp + c * qkq;
+                }
+            }
+    }
+    for (int i = 0; i < n; ++i) v[i] = A[(long)i * n + i];
+    /* ascending order (selection sort, columns of Q follow) */
+    for (int i = 0; i < n - 1; ++i) {
+        int m = i;
+        for (int j = i + 1; j < n; ++j)
+            if (v[j] < v[m]) m = j;
+        if (m != i) {
+            const double tv = v[i]; v[i] = v[m]; v[m] = tv;
+            for (int k = 0; k < n; ++k) {
+                const double tq = Q[(long)k * n + i];
+                Q[(long)k * n + i] = Q[(long)k * n + m];
+                Q[(long)k * n + m] = tq;
+            }
+        }
+    }
+    free(A);
+    return sweep;
 }
 
 /* Eq. 13: P = Q_G [ (Q_G^T grad Q_A) / (v_G v_A^T + gamma) ] Q_A^T, with the

@@ -118,6 +118,23 @@ def precondition(Ginv: np.ndarray, grad: np.ndarray, Ainv: np.ndarray) -> np.nda
     return out
 
 
+def eigh(M: np.ndarray):
+    """(v ascending, Q with the eigenvectors in its columns) of a symmetric matrix, cyclic Jacobi."""
+    M = np.ascontiguousarray(M, dtype=np.float64)
+    n = M.shape[0]
+    Q = np.empty((n, n), dtype=np.float64)
+    v = np.empty(n, dtype=np.float64)
+    _lib.oracle_eigh_jacobi(_d(M), C.c_int(n), _d(Q), _d(v))
+    return v, Q
+
+
+def precondition_eigen_layer(A_run, G_run, grad, gamma: float) -> np.ndarray:
+    """Eq. 13 from the running factors: decompose both, then precondition."""
+    vA, QA = eigh(A_run)
+    vG, QG = eigh(G_run)
+    return precondition_eigen(QG, vG, QA, vA, grad, gamma)
+
+
 def precondition_eigen(QG, vG, QA, vA, grad, gamma: float) -> np.ndarray:
     QG = np.ascontiguousarray(QG, dtype=np.float64)
     QA = np.ascontiguousarray(QA, dtype=np.float64)

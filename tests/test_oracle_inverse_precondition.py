@@ -140,6 +140,55 @@ def test_eigen_form_is_exact_inverse_of_damped_kronecker_product():
     assert gap < 1.0
 
 
+# ---- eigen-decomposition of the factors (Eq. 13) ----------------------------------------------
+
+def test_eigh_closed_forms():
+    # diagonal matrix: eigenvalues are the entries, ascending; eigenvectors are unit vectors
+    v, Q = orc.eigh(np.diag([3.0, -1.0, 2.0]))
+    assert np.array_equal(v, [-1.0, 2.0, 3.0])
+    assert np.array_equal(np.abs(Q), np.eye(3)[:, [1, 2, 0]])
+    # 2 x 2: [[a, b], [b, a]] has a -+ b with eigenvectors (1, -+1) / sqrt 2
+    v, Q = orc.eigh(np.array([[2.0, 0.5], [0.5, 2.0]]))
+    assert np.allclose(v, [1.5, 2.5], rtol=0, atol=1e-15)
+    assert np.allclose(np.abs(Q), np.full((2, 2), np.sqrt(0.5)), atol=1e-15) and Q[0, 0] * Q[1, 0] < 0 < Q[0, 1] * Q[1, 1]
+    # identity plus rank one: c I + u u^T has one eigenvalue c + |u|^2 (vector u / |u|), the rest c
+    u = rng.draw_normal(60, 0, (9,)).astype(np.float64)
+    v, Q = orc.eigh(0.7 * np.eye(9) + np.outer(u, u))
+    assert np.allclose(v[:-1], 0.7, atol=1e-13) and abs(v[-1] - (0.7 + u @ u)) < 1e-12
+    assert abs(abs(Q[:, -1] @ u) - np.linalg.norm(u)) < 1e-12
+
+
+@pytest.mark.parametrize("n", [1, 2, 5, 33, 80])
+def test_eigh_against_lapack_and_invariants(n):
+    M, _ = _spd(70 + n, n)
+    M[0, n - 1] = M[n - 1, 0] = M[0, n - 1] - 0.3          # not a Gram matrix any more; may be indefinite
+    v, Q = orc.eigh(M)
+    assert np.allclose(v, np.linalg.eigvalsh(M), rtol=1e-12, atol=1e-13 * np.abs(M).max())
+    assert np.all(np.diff(v) >= 0)
+    assert np.allclose(Q.T @ Q, np.eye(n), atol=1e-13)
+    assert np.allclose(M @ Q, Q * v, atol=1e-12 * np.abs(M).max())
+    assert abs(v.sum() - np.trace(M)) < 1e-12 * np.abs(M).max() * n
+    # a transposed (row) eigenvector layout would fail this for a non-symmetric Q
+    assert np.allclose((Q * v) @ Q.T, M, atol=1e-12 * np.abs(M).max())
+
+
+def test_eigen_layer_helper_matches_inverse_form_when_damping_factorises():
+    # with gamma = 0 both Eq. 13 and the inverse form reduce to G^-1 grad A^-1
+    dA, dG = 7, 5
+    A, _ = _spd(81, dA)
+    G, _ = _spd(82, dG)
+    grad = rng.draw_normal(83, 2, (dG, dA)).astype(np.float64)
+    P = orc.precondition_eigen_layer(A, G, grad, 0.0)
+    ref = np.linalg.solve(G, grad) @ np.linalg.inv(A)
+    assert np.allclose(P, ref, rtol=1e-9, atol=1e-11)
+    # and with damping it is the exact damped Kronecker solve
+    gamma = 0.02
+    P = orc.precondition_eigen_layer(A, G, grad, gamma)
+    K = np.kron(A, G) + gamma * np.eye(dA * dG)
+    ref = np.linalg.solve(K, grad.reshape(-1, order="F")).reshape((dG, dA), order="F")
+    assert np.allclose(P, ref, rtol=1e-10, atol=1e-12)
+
+
 # ---- factored Tikhonov damping (Eq. 12) -------------------------------------------------------
 
 def test_pi_damping_closed_forms():
