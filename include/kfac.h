@@ -83,7 +83,7 @@ int kfac_dim_G(const kfac_layer_desc *desc);
  * d_in*kh*kw rounded up to 16 bytes.  The bias column is not materialised. */
 int kfac_patch_ld(const kfac_layer_desc *desc);
 
-/* Bytes of workspace sufficient for any of the three per-layer calls. */
+/* Bytes of workspace sufficient for any of the per-layer calls. */
 size_t kfac_workspace_bytes(const kfac_layer_desc *desc, int batch, int h, int w);
 /* Same for the batched calls over n layers (host arrays). */
 size_t kfac_workspace_bytes_batched(int n, const kfac_layer_desc *descs, const int *batch, const int *h,
@@ -122,6 +122,23 @@ kfac_status kfac_precondition(const kfac_layer_desc *desc, const float *d_A_inv,
                               const float *d_grad, float *d_out, void *d_work, size_t work_bytes,
                               void *hip_stream);
 
+/* Eigen-decomposition variant of the preconditioner (section 5.2, Eq. 13).
+ *
+ * kfac_eigen: A_run = Q_A diag(v_A) Q_A^T and G_run = Q_G diag(v_G) Q_G^T.  d_Q_A [d_A, d_A], d_Q_G [d_G, d_G]
+ * fp32 row-major with the eigenvectors in their COLUMNS; d_v_A [d_A], d_v_G [d_G] the eigenvalues, entry k
+ * belonging to column k (no particular order).  The running factors are read (lower triangle) and not
+ * modified; outputs must not alias them.  d_info: 2 ints (A, G): 0 = converged, 1 = the sweep budget of the
+ * iteration ran out (the results are then the current iterate: still an orthogonal Q with W = Q^T M).
+ *
+ * kfac_precondition_eigen:  P = Q_G [ (Q_G^T grad Q_A) ./ (v_G v_A^T + gamma) ] Q_A^T, gamma >= 0.
+ * Shapes of grad / out as in kfac_precondition; d_out may alias d_grad. */
+kfac_status kfac_eigen(const kfac_layer_desc *desc, const float *d_A_run, const float *d_G_run, float *d_Q_A,
+                       float *d_v_A, float *d_Q_G, float *d_v_G, int *d_info, void *d_work, size_t work_bytes,
+                       void *hip_stream);
+kfac_status kfac_precondition_eigen(const kfac_layer_desc *desc, const float *d_Q_A, const float *d_v_A,
+                                    const float *d_Q_G, const float *d_v_G, float gamma, const float *d_grad,
+                                    float *d_out, void *d_work, size_t work_bytes, void *hip_stream);
+
 /* Grouped forms: the same three operations for n layers in one launch
  * sequence (layers of one size class share kernel launches).  Host arrays of
  * length n; d_info holds 2*n ints, (A, G) per layer. */
@@ -142,6 +159,16 @@ kfac_status kfac_invert_pi_batched(int n, const kfac_layer_desc *descs, const fl
 kfac_status kfac_precondition_batched(int n, const kfac_layer_desc *descs, const float *const *d_A_inv,
                                       const float *const *d_G_inv, const float *const *d_grad,
                                       float *const *d_out, void *d_work, size_t work_bytes, void *hip_stream);
+
+kfac_status kfac_eigen_batched(int n, const kfac_layer_desc *descs, const float *const *d_A_run,
+                               const float *const *d_G_run, float *const *d_Q_A, float *const *d_v_A,
+                               float *const *d_Q_G, float *const *d_v_G, int *d_info, void *d_work,
+                               size_t work_bytes, void *hip_stream);
+kfac_status kfac_precondition_eigen_batched(int n, const kfac_layer_desc *descs, const float *const *d_Q_A,
+                                            const float *const *d_v_A, const float *const *d_Q_G,
+                                            const float *const *d_v_G, float gamma, const float *const *d_grad,
+                                            float *const *d_out, void *d_work, size_t work_bytes,
+                                            void *hip_stream);
 
 const char *kfac_status_string(kfac_status s);
 int kfac_version(void);

@@ -28,7 +28,10 @@ enum {
     KFAC_K_INV_STEP = 11,    /* fused sweep step: panel + update + next pivot in one launch */
     KFAC_K_SYRK_BF16 = 12,   /* KF-GEMM on the bf16 MFMA units (row-major bf16 operands) */
     KFAC_K_GEMM_WAVE = 13,   /* A^T B on the wave-unit GEMM (large preconditioning and inverse products) */
-    KFAC_K_COUNT = 14
+    KFAC_K_EIG_INIT = 14,    /* eigen-decomposition: working copies W = M, V = I */
+    KFAC_K_EIG_ROUND = 15,   /* eigen-decomposition: one round of the block Jacobi sweep */
+    KFAC_K_EIG_FINAL = 16,   /* eigen-decomposition: eigenvalues and Q = V^T; transposes for Eq. 13 */
+    KFAC_K_COUNT = 17
 };
 
 /* When enabled, every kernel launch is bracketed by a pair of HIP events

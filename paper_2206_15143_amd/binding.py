@@ -87,6 +87,13 @@ def load_library():
     lib.kfac_invert_batched.restype = C.c_int
     lib.kfac_precondition_batched.argtypes = [C.c_int, dp, vpp, vpp, vpp, vpp, vp, sz, vp]
     lib.kfac_precondition_batched.restype = C.c_int
+    lib.kfac_eigen.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]; lib.kfac_eigen.restype = C.c_int
+    lib.kfac_eigen_batched.argtypes = [C.c_int, dp, vpp, vpp, vpp, vpp, vpp, vpp, vp, vp, sz, vp]
+    lib.kfac_eigen_batched.restype = C.c_int
+    lib.kfac_precondition_eigen.argtypes = [dp, vp, vp, vp, vp, C.c_float, vp, vp, vp, sz, vp]
+    lib.kfac_precondition_eigen.restype = C.c_int
+    lib.kfac_precondition_eigen_batched.argtypes = [C.c_int, dp, vpp, vpp, vpp, vpp, C.c_float, vpp, vpp, vp, sz, vp]
+    lib.kfac_precondition_eigen_batched.restype = C.c_int
     lib.kfac_status_string.argtypes = [C.c_int]; lib.kfac_status_string.restype = C.c_char_p
     lib.kfac_version.argtypes = []; lib.kfac_version.restype = C.c_int
     lib.kfac_tune.argtypes = [C.c_char_p, C.c_long]; lib.kfac_tune.restype = C.c_int
@@ -157,7 +164,7 @@ def kfac_tune(key: str, value: int) -> None:
         raise KeyError(key)
 
 
-KFAC_K_COUNT = 14
+KFAC_K_COUNT = 17
 
 
 def kfac_profile_copy(dst, src, nbytes: int, stream=None) -> None:
@@ -255,6 +262,33 @@ def kfac_invert_pi_batched(descs, A_runs, G_runs, gamma, A_invs, G_invs, info, d
                                                  _ptrs(A_invs), _ptrs(G_invs), _ptr(info), _ptr(damping),
                                                  _ptr(work), _nbytes(work), _stream(stream)),
            "kfac_invert_pi_batched")
+
+
+def kfac_eigen(desc, A_run, G_run, Q_A, v_A, Q_G, v_G, info, work, stream=None) -> None:
+    _check(load_library().kfac_eigen(C.byref(desc), _ptr(A_run), _ptr(G_run), _ptr(Q_A), _ptr(v_A), _ptr(Q_G),
+                                     _ptr(v_G), _ptr(info), _ptr(work), _nbytes(work), _stream(stream)),
+           "kfac_eigen")
+
+
+def kfac_eigen_batched(descs, A_runs, G_runs, Q_As, v_As, Q_Gs, v_Gs, info, work, stream=None) -> None:
+    n = len(descs)
+    _check(load_library().kfac_eigen_batched(n, _descs(descs), _ptrs(A_runs), _ptrs(G_runs), _ptrs(Q_As),
+                                             _ptrs(v_As), _ptrs(Q_Gs), _ptrs(v_Gs), _ptr(info), _ptr(work),
+                                             _nbytes(work), _stream(stream)), "kfac_eigen_batched")
+
+
+def kfac_precondition_eigen(desc, Q_A, v_A, Q_G, v_G, gamma, grad, out, work, stream=None) -> None:
+    _check(load_library().kfac_precondition_eigen(C.byref(desc), _ptr(Q_A), _ptr(v_A), _ptr(Q_G), _ptr(v_G), gamma,
+                                                  _ptr(grad), _ptr(out), _ptr(work), _nbytes(work),
+                                                  _stream(stream)), "kfac_precondition_eigen")
+
+
+def kfac_precondition_eigen_batched(descs, Q_As, v_As, Q_Gs, v_Gs, gamma, grads, outs, work, stream=None) -> None:
+    n = len(descs)
+    _check(load_library().kfac_precondition_eigen_batched(n, _descs(descs), _ptrs(Q_As), _ptrs(v_As), _ptrs(Q_Gs),
+                                                          _ptrs(v_Gs), gamma, _ptrs(grads), _ptrs(outs),
+                                                          _ptr(work), _nbytes(work), _stream(stream)),
+           "kfac_precondition_eigen_batched")
 
 
 def kfac_precondition_batched(descs, A_invs, G_invs, grads, outs, work, stream=None) -> None:

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libkfac_hip.so")
-SOURCES = ["api.hip", "syrk.hip", "gemm.hip", "im2col.hip", "invert.hip"]
+SOURCES = ["api.hip", "syrk.hip", "gemm.hip", "im2col.hip", "invert.hip", "eigen.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]

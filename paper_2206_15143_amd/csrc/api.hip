@@ -303,6 +303,43 @@ size_t precond_ws(int n, const kfac_layer_desc *descs)
     return total;
 }
 
+std::vector<EigenJob> eigen_jobs(int n, const kfac_layer_desc *descs, const float *const *A, const float *const *G,
+                                 float *const *QA, float *const *vA, float *const *QG, float *const *vG, int *info)
+{
+    std::vector<EigenJob> jobs;
+    for (int i = 0; i < n; ++i) {
+        EigenJob a{};
+        a.n = core_dim(&descs[i]) + descs[i].has_bias;
+        EigenJob g{};
+        g.n = descs[i].d_out;
+        if (A) {
+            a.M = A[i]; a.Q = QA[i]; a.v = vA[i]; a.info = info + 2 * i;
+            g.M = G[i]; g.Q = QG[i]; g.v = vG[i]; g.info = info + 2 * i + 1;
+        }
+        jobs.push_back(a);
+        jobs.push_back(g);
+    }
+    return jobs;
+}
+
+size_t eigen_ws(int n, const kfac_layer_desc *descs)
+{
+    std::vector<EigenJob> jobs = eigen_jobs(n, descs, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
+    return eigen_workspace_bytes(jobs.data(), (int)jobs.size());
+}
+
+// Eq. 13 workspace per layer: two d_A x d_G intermediates and the transposes of Q_A and Q_G
+size_t precond_eigen_ws(int n, const kfac_layer_desc *descs)
+{
+    size_t total = 0;
+    for (int i = 0; i < n; ++i) {
+        const size_t dA = core_dim(&descs[i]) + descs[i].has_bias, dG = descs[i].d_out;
+        total += 2 * align_up(dA * dG * sizeof(float), 256) + align_up(dA * dA * sizeof(float), 256) +
+                 align_up(dG * dG * sizeof(float), 256);
+    }
+    return total;
+}
+
 }  // namespace
 }  // namespace kfac
 
@@ -338,6 +375,8 @@ size_t kfac_workspace_bytes_batched(int n, const kfac_layer_desc *descs, const i
     size_t need = pl.patch_region + pl.syrk_region;
     need = std::max(need, invert_ws_total(n, descs));
     need = std::max(need, precond_ws(n, descs));
+    need = std::max(need, eigen_ws(n, descs));
+    need = std::max(need, precond_eigen_ws(n, descs));
     return need + 256;
 }
 
@@ -552,6 +591,112 @@ kfac_status kfac_precondition(const kfac_layer_desc *d, const float *d_A_inv, co
     return kfac_precondition_batched(1, d, &d_A_inv, &d_G_inv, &d_grad, &d_out, d_work, work_bytes, hip_stream);
 }
 
+kfac_status kfac_eigen_batched(int n, const kfac_layer_desc *descs, const float *const *d_A_run,
+                               const float *const *d_G_run, float *const *d_Q_A, float *const *d_v_A,
+                               float *const *d_Q_G, float *const *d_v_G, int *d_info, void *d_work,
+                               size_t work_bytes, void *hip_stream)
+{
+    if (n <= 0) return KFAC_ERR_SHAPE;
+    if (!descs || !d_A_run || !d_G_run || !d_Q_A || !d_v_A || !d_Q_G || !d_v_G || !d_info || !d_work)
+        return KFAC_ERR_NULL;
+    for (int i = 0; i < n; ++i) {
+        kfac_status st = desc_check(&descs[i]);
+        if (st != KFAC_OK) return st;
+        if (!d_A_run[i] || !d_G_run[i] || !d_Q_A[i] || !d_v_A[i] || !d_Q_G[i] || !d_v_G[i]) return KFAC_ERR_NULL;
+        if (!aligned(d_A_run[i], 4) || !aligned(d_G_run[i], 4) || !aligned(d_Q_A[i], 4) || !aligned(d_v_A[i], 4) ||
+            !aligned(d_Q_G[i], 4) || !aligned(d_v_G[i], 4))
+            return KFAC_ERR_ALIGN;
+        if (d_A_run[i] == d_Q_A[i] || d_G_run[i] == d_Q_G[i]) return KFAC_ERR_PARAM;
+    }
+    if (!aligned(d_work, 256)) return KFAC_ERR_ALIGN;
+    std::vector<EigenJob> jobs = eigen_jobs(n, descs, d_A_run, d_G_run, d_Q_A, d_v_A, d_Q_G, d_v_G, d_info);
+    if (eigen_workspace_bytes(jobs.data(), (int)jobs.size()) > work_bytes) return KFAC_ERR_WORKSPACE;
+    return eigen_launch(jobs.data(), (int)jobs.size(), d_work, work_bytes, (hipStream_t)hip_stream) == hipSuccess
+               ? KFAC_OK
+               : KFAC_ERR_HIP;
+}
+
+kfac_status kfac_eigen(const kfac_layer_desc *d, const float *d_A_run, const float *d_G_run, float *d_Q_A,
+                       float *d_v_A, float *d_Q_G, float *d_v_G, int *d_info, void *d_work, size_t work_bytes,
+                       void *hip_stream)
+{
+    if (!d) return KFAC_ERR_NULL;
+    return kfac_eigen_batched(1, d, &d_A_run, &d_G_run, &d_Q_A, &d_v_A, &d_Q_G, &d_v_G, d_info, d_work, work_bytes,
+                              hip_stream);
+}
+
+kfac_status kfac_precondition_eigen_batched(int n, const kfac_layer_desc *descs, const float *const *d_Q_A,
+                                            const float *const *d_v_A, const float *const *d_Q_G,
+                                            const float *const *d_v_G, float gamma, const float *const *d_grad,
+                                            float *const *d_out, void *d_work, size_t work_bytes,
+                                            void *hip_stream)
+{
+    if (n <= 0) return KFAC_ERR_SHAPE;
+    if (!descs || !d_Q_A || !d_v_A || !d_Q_G || !d_v_G || !d_grad || !d_out || !d_work) return KFAC_ERR_NULL;
+    if (!(gamma >= 0.f)) return KFAC_ERR_PARAM;
+    for (int i = 0; i < n; ++i) {
+        kfac_status st = desc_check(&descs[i]);
+        if (st != KFAC_OK) return st;
+        if (!d_Q_A[i] || !d_v_A[i] || !d_Q_G[i] || !d_v_G[i] || !d_grad[i] || !d_out[i]) return KFAC_ERR_NULL;
+        if (!aligned(d_Q_A[i], 4) || !aligned(d_v_A[i], 4) || !aligned(d_Q_G[i], 4) || !aligned(d_v_G[i], 4) ||
+            !aligned(d_grad[i], 4) || !aligned(d_out[i], 4))
+            return KFAC_ERR_ALIGN;
+    }
+    if (!aligned(d_work, 256)) return KFAC_ERR_ALIGN;
+    if (precond_eigen_ws(n, descs) > work_bytes) return KFAC_ERR_WORKSPACE;
+    // With Q = [eigenvectors in columns] and every product in the form C = X^T Y (both operands K-major):
+    //   U   [dA, dG] = grad^T Q_G                      (= (Q_G^T grad)^T)
+    //   T1  [dG, dA] = U^T Q_A  ./ (v_G v_A^T + gamma)   (division in the epilogue)
+    //   T2t [dA, dG] = T1^T Q_G^T                      (= (Q_G T1)^T)
+    //   P   [dG, dA] = T2t^T Q_A^T
+    std::vector<GemmJob> g1(n), g2(n), g3(n), g4(n);
+    std::vector<const float *> tsrc;
+    std::vector<float *> tdst;
+    std::vector<int> tn;
+    size_t off = 0;
+    auto take = [&](size_t floats) {
+        float *p = reinterpret_cast<float *>(static_cast<char *>(d_work) + off);
+        off += align_up(floats * sizeof(float), 256);
+        return p;
+    };
+    for (int i = 0; i < n; ++i) {
+        const int dA = core_dim(&descs[i]) + descs[i].has_bias, dG = descs[i].d_out;
+        float *U = take((size_t)dA * dG), *T1 = take((size_t)dA * dG);
+        float *QAt = take((size_t)dA * dA), *QGt = take((size_t)dG * dG);
+        tsrc.push_back(d_Q_A[i]); tdst.push_back(QAt); tn.push_back(dA);
+        tsrc.push_back(d_Q_G[i]); tdst.push_back(QGt); tn.push_back(dG);
+        GemmJob &a = g1[i];
+        a.A = d_grad[i]; a.B = d_Q_G[i]; a.C = U;
+        a.M = dA; a.N = dG; a.K = dG; a.lda = dA; a.ldb = dG; a.ldc = dG; a.mode = kStore; a.p0 = a.p1 = 0;
+        GemmJob &b = g2[i];
+        b.A = U; b.B = d_Q_A[i]; b.C = T1;
+        b.M = dG; b.N = dA; b.K = dA; b.lda = dG; b.ldb = dA; b.ldc = dA; b.mode = kStoreDiv; b.p0 = b.p1 = 0;
+        b.rv = d_v_G[i]; b.cv = d_v_A[i]; b.gamma = gamma;
+        GemmJob &c = g3[i];
+        c.A = T1; c.B = QGt; c.C = U;
+        c.M = dA; c.N = dG; c.K = dG; c.lda = dA; c.ldb = dG; c.ldc = dG; c.mode = kStore; c.p0 = c.p1 = 0;
+        GemmJob &e = g4[i];
+        e.A = U; e.B = QAt; e.C = d_out[i];
+        e.M = dG; e.N = dA; e.K = dA; e.lda = dG; e.ldb = dA; e.ldc = dA; e.mode = kStore; e.p0 = e.p1 = 0;
+    }
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (transpose_launch(tsrc.data(), tdst.data(), tn.data(), (int)tn.size(), s) != hipSuccess) return KFAC_ERR_HIP;
+    if (gemm_launch(g1.data(), n, s) != hipSuccess) return KFAC_ERR_HIP;
+    if (gemm_launch(g2.data(), n, s) != hipSuccess) return KFAC_ERR_HIP;
+    if (gemm_launch(g3.data(), n, s) != hipSuccess) return KFAC_ERR_HIP;
+    if (gemm_launch(g4.data(), n, s) != hipSuccess) return KFAC_ERR_HIP;
+    return KFAC_OK;
+}
+
+kfac_status kfac_precondition_eigen(const kfac_layer_desc *d, const float *d_Q_A, const float *d_v_A,
+                                    const float *d_Q_G, const float *d_v_G, float gamma, const float *d_grad,
+                                    float *d_out, void *d_work, size_t work_bytes, void *hip_stream)
+{
+    if (!d) return KFAC_ERR_NULL;
+    return kfac_precondition_eigen_batched(1, d, &d_Q_A, &d_v_A, &d_Q_G, &d_v_G, gamma, &d_grad, &d_out, d_work,
+                                           work_bytes, hip_stream);
+}
+
 const char *kfac_status_string(kfac_status s)
 {
     switch (s) {
@@ -597,7 +742,7 @@ const char *kfac_timing_class_name(int cls)
     static const char *names[KFAC_K_COUNT] = {"im2col", "syrk_partial", "syrk_reduce", "inv_init",
                                               "inv_pivot", "inv_panel", "inv_finish", "gemm_tn",
                                               "syrk_wave", "syrk_conv3", "syrk_small", "inv_step",
-                                              "syrk_bf16", "gemm_wave"};
+                                              "syrk_bf16", "gemm_wave", "eig_init", "eig_round", "eig_final"};
     return (cls >= 0 && cls < KFAC_K_COUNT) ? names[cls] : "?";
 }
 
@@ -635,6 +780,8 @@ int kfac_tune(const char *key, long value)
     else if (k == "update_bm") t.update_bm = value;
     else if (k == "use_small_kernel") t.use_small_kernel = value;
     else if (k == "invert_fused_max_n") t.invert_fused_max_n = value;
+    else if (k == "eigen_max_sweeps") t.eigen_max_sweeps = value;
+    else if (k == "eigen_inner_sweeps") t.eigen_inner_sweeps = value;
     else if (k == "im2col_piece_elems") t.im2col_piece_elems = value;
     else if (k == "im2col_block_bytes") t.im2col_block_bytes = value;
     else if (k == "im2col_lds_bytes") t.im2col_lds_bytes = value;

@@ -58,12 +58,24 @@ struct GemmJob {
     long lda, ldb, ldc;
     int mode;        // GemmMode
     int p0, p1;      // kSubLowerSkip: rows/cols in [p0, p1) are left untouched
+    const float *rv = nullptr, *cv = nullptr;   // kStoreDiv
+    float gamma = 0.f;
 };
 
 enum GemmMode : int {
     kStore = 0,          // C[m][n] = acc
     kStoreT = 1,         // C[n][m] = acc   (ldc is the pitch of the transposed matrix)
-    kSubLowerSkip = 2    // C[m][n] -= acc for n <= m, m and n outside [p0, p1)
+    kSubLowerSkip = 2,   // C[m][n] -= acc for n <= m, m and n outside [p0, p1)
+    kStoreDiv = 3        // C[m][n] = acc / (rv[m] * cv[n] + gamma)   (the division of Eq. 13)
+};
+
+// Symmetric eigen-decomposition M = Q diag(v) Q^T (eigenvectors in the columns of Q, order not sorted).
+struct EigenJob {
+    const float *M;  // [n, n], lower triangle read
+    float *Q;        // [n, n]
+    float *v;        // [n]
+    int *info;       // 0, or 1 when the sweep budget ran out
+    int n;
 };
 
 struct Im2colJob {
@@ -87,6 +99,9 @@ hipError_t pi_damping_launch(const float *const *A, const float *const *G, const
 hipError_t gemm_launch(const GemmJob *jobs, int n, hipStream_t s);
 
 hipError_t im2col_launch(const Im2colJob *jobs, int n, hipStream_t s);
+size_t eigen_workspace_bytes(const EigenJob *jobs, int n);
+hipError_t eigen_launch(const EigenJob *jobs, int n, void *work, size_t work_bytes, hipStream_t s);
+hipError_t transpose_launch(const float *const *src, float *const *dst, const int *n, int count, hipStream_t s);
 
 // output rows per stage of the fused 3x3 convolution factor kernel; 0 = image shape not supported
 int conv3_rows(int h, int w);
@@ -102,6 +117,8 @@ struct Tuning {
     long im2col_block_bytes = 80 * 1024;  // output bytes per workgroup aimed for
     long im2col_lds_bytes = 20 * 1024;    // slab budget of a workgroup
     long im2col_min_blocks = 1024;   // shorter strips until a layer has this many workgroups
+    long eigen_max_sweeps = 16;      // sweep budget of the block Jacobi eigen-decomposition
+    long eigen_inner_sweeps = 3;     // Jacobi sweeps over the 32 x 32 Gram matrix of a pair of blocks
     long invert_fused_max_n = 1280;  // orders up to this take the one-launch-per-step sweep
     long syrk_force_bm = 0;          // 0 = choose
     long use_wave_kernel = 1;        // wave-unit SYRK for aligned row-major fp32 operands

@@ -1,0 +1,476 @@
+// Batched symmetric eigen-decomposition of the Kronecker factors, M = Q diag(v) Q^T: the Q_A, v_A,
+// Q_G, v_G that the eigen-decomposition variant of the preconditioner uses (Eq. 13 of the DP-KFAC
+// paper, section 5.2).
+//
+// Method: one-sided block Jacobi on rows.  The working pair (W, V) starts as (M, I) and every step
+// applies the same orthogonal transform to both from the left, so W = V M holds throughout; when the
+// rows of W are mutually orthogonal, row i of V is an eigenvector and <v_i, w_i> its eigenvalue.
+// Rows are grouped into blocks of 16.  One round pairs all blocks off (round-robin tournament: every
+// two blocks meet once per sweep) and is ONE launch with one wavefront per pair of every matrix:
+//   1. the 32 x 32 Gram matrix S = X X^T of the pair's 32 rows of W on the MFMA units (K = n);
+//   2. S is diagonalised in LDS by two-sided cyclic Jacobi (16 disjoint rotations per inner round,
+//      31 inner rounds per inner sweep), which gives the 32 x 32 orthogonal R;
+//   3. the rows of W and of V are replaced by R^T X on the MFMA units.
+// A pair whose Gram matrix is already diagonal to rounding does nothing; a matrix none of whose
+// pairs did anything for a whole sweep has converged and its wavefronts return at once (the
+// per-matrix round stamp lives in device memory, so the host never synchronises).  The launch
+// sequence has a fixed length (a sweep budget); `info` reports a matrix that used it up.
+// Rows past n (padding of the last block, and the bye of an odd number of blocks) are zero rows:
+// their Gram entries vanish and no rotation touches them.
+#include "common.hpp"
+
+#include <algorithm>
+#include <cmath>
+#include <vector>
+
+namespace kfac {
+
+constexpr int EB = 16;              // rows per block
+constexpr int kMaxEigClasses = 16;  // distinct orders per launch sequence
+
+struct EigProb {                    // init / final kernels: one entry per matrix
+    const float *M;
+    float *Q;
+    float *v;
+    int *info;
+    float *Wt, *Vt;
+    float *scale;                   // [nb * 16] reciprocal row norms of V (final pass)
+    int *stamp;
+    int n, ld, nb;
+    int blk_start;
+    int rounds_total, m;
+};
+
+struct EigTable {
+    int count;
+    EigProb p[kMaxProblems];
+};
+
+struct EigClass {                   // round kernel: matrices of one order, stored back to back
+    float *Wt, *Vt;                 // first matrix; the next ones follow at `stride` floats
+    int *stamp;                     // per matrix: 1 + index of the last round in which a pair rotated
+    long stride;
+    int n, ld, nb, m;               // order, row pitch, blocks, blocks rounded up to even
+    int count;
+    int blk_start;
+    float tol;
+};
+
+struct EigSeq {
+    int nclass;
+    int t;                          // global round index
+    int inner_sweeps;
+    EigClass c[kMaxEigClasses];
+};
+
+__global__ __launch_bounds__(256) void eig_init_kernel(const EigTable tab)
+{
+    int pi = 0;
+    while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].blk_start) ++pi;
+    const EigProb &pr = tab.p[pi];
+    const long total = (long)pr.nb * EB * pr.ld;
+    const long e0 = ((long)(blockIdx.x - pr.blk_start) * 256 + threadIdx.x) * 4;
+    if (blockIdx.x == pr.blk_start && threadIdx.x == 0) {
+        *pr.stamp = 0;
+        *pr.info = 0;
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const long e = e0 + q;
+        if (e >= total) return;
+        const int i = (int)(e / pr.ld), j = (int)(e - (long)i * pr.ld);
+        float w = 0.f;
+        if (i < pr.n && j < pr.n) w = pr.M[(long)max(i, j) * pr.n + min(i, j)];   // lower triangle is authoritative
+        pr.Wt[e] = w;
+        pr.Vt[e] = (i == j && i < pr.n) ? 1.f : 0.f;
+    }
+}
+
+// Pair k of round r of a round-robin tournament over m (even) players.
+__device__ __forceinline__ void rr_pair(int m, int r, int k, int &a, int &b)
+{
+    if (k == 0) {
+        a = m - 1;
+        b = r;
+    } else {
+        a = (r + k) % (m - 1);
+        b = (r - k + (m - 1)) % (m - 1);
+    }
+}
+
+__global__ __launch_bounds__(64) void eig_round_kernel(const EigSeq q)
+{
+    __shared__ float S[32][33];
+    __shared__ float R[32][33];
+
+    int ci = 0;
+    while (ci + 1 < q.nclass && (int)blockIdx.x >= q.c[ci + 1].blk_start) ++ci;
+    const EigClass &c = q.c[ci];
+    const int local = blockIdx.x - c.blk_start;
+    const int half = c.m / 2;
+    const int mat = local / half, pk = local - mat * half;
+    if (mat >= c.count) return;
+    // converged: a whole sweep (m - 1 rounds) without a rotation
+    const int stamp = c.stamp[mat];
+    if (q.t - stamp >= c.m - 1) return;
+
+    int I, J;
+    rr_pair(c.m, q.t % (c.m - 1), pk, I, J);
+    if (I > J) { const int t = I; I = J; J = t; }
+    if (I >= c.nb) return;                      // cannot happen for m <= nb + 1; keeps the indexing safe
+    const bool hasJ = J < c.nb;                 // the bye block of an odd count is all zero rows
+    const int lane = threadIdx.x;
+    const int r = lane & 15, kk = lane >> 4;
+    const long ld = c.ld;
+    float *Wt = c.Wt + (long)mat * c.stride;
+    float *Vt = c.Vt + (long)mat * c.stride;
+    const float *wI = Wt + (long)(I * EB + r) * ld + 4 * kk;
+    const float *wJ = Wt + (long)(J * EB + r) * ld + 4 * kk;
+
+    // ---- 1. Gram matrix of the 32 rows ----
+    floatx4 s00 = {0.f, 0.f, 0.f, 0.f}, s10 = s00, s11 = s00;
+    for (int k0 = 0; k0 < c.ld; k0 += 16) {
+        const floatx4 x0 = *reinterpret_cast<const floatx4 *>(wI + k0);
+        floatx4 x1 = {0.f, 0.f, 0.f, 0.f};
+        if (hasJ) x1 = *reinterpret_cast<const floatx4 *>(wJ + k0);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            s00 = __builtin_amdgcn_mfma_f32_16x16x4f32(x0[e], x0[e], s00, 0, 0, 0);
+            s10 = __builtin_amdgcn_mfma_f32_16x16x4f32(x1[e], x0[e], s10, 0, 0, 0);
+            s11 = __builtin_amdgcn_mfma_f32_16x16x4f32(x1[e], x1[e], s11, 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        S[4 * kk + v][r] = s00[v];
+        S[16 + 4 * kk + v][r] = s10[v];
+        S[r][16 + 4 * kk + v] = s10[v];
+        S[16 + 4 * kk + v][16 + r] = s11[v];
+    }
+    for (int e = lane; e < 32 * 32; e += 64) R[e >> 5][e & 31] = ((e >> 5) == (e & 31)) ? 1.f : 0.f;
+    __syncthreads();
+
+    // ---- 2. two-sided cyclic Jacobi on S; lane (pair = lane & 15, part = lane >> 4) ----
+    const int pr_ = lane & 15, part = lane >> 4;
+    bool active = false;
+    for (int sw = 0; sw < q.inner_sweeps; ++sw) {
+        bool any = false;
+#pragma unroll 1
+        for (int rd = 0; rd < 31; ++rd) {
+            int p, qq;
+            rr_pair(32, rd, pr_, p, qq);
+            if (p > qq) { const int t = p; p = qq; qq = t; }
+            const float app = S[p][p], aqq = S[qq][qq], apq = S[p][qq];
+            float cs = 1.f, sn = 0.f;
+            const bool rot = fabsf(apq) > c.tol * sqrtf(fabsf(app * aqq)) && apq != 0.f;
+            if (rot) {
+                const float tau = (aqq - app) / (2.f * apq);
+                const float tt = (tau >= 0.f ? 1.f : -1.f) / (fabsf(tau) + sqrtf(1.f + tau * tau));
+                cs = 1.f / sqrtf(1.f + tt * tt);
+                sn = tt * cs;
+            }
+            any = any || rot;
+            __syncthreads();                    // every lane has read its pivots before anything moves
+            // columns p, q of S and of R:  S <- S J,  R <- R J
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int i = part * 8 + e;
+                const float sp = S[i][p], sq = S[i][qq];
+                S[i][p] = cs * sp - sn * sq;
+                S[i][qq] = sn * sp + cs * sq;
+                const float rp = R[i][p], rq = R[i][qq];
+                R[i][p] = cs * rp - sn * rq;
+                R[i][qq] = sn * rp + cs * rq;
+            }
+            __syncthreads();
+            // rows p, q of S:  S <- J^T S
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int j = part * 8 + e;
+                const float sp = S[p][j], sq = S[qq][j];
+                S[p][j] = cs * sp - sn * sq;
+                S[qq][j] = sn * sp + cs * sq;
+            }
+            __syncthreads();
+        }
+        const bool wave_any = __builtin_amdgcn_ballot_w64(any) != 0;
+        if (!wave_any) break;
+        active = true;
+    }
+    if (!active) return;                        // R is the identity: nothing to apply
+    if (lane == 0) atomicMax(c.stamp + mat, q.t + 1);
+
+    // ---- 3. rows <- R^T rows, for W and V ----
+    float a[2][8];
+#pragma unroll
+    for (int it = 0; it < 2; ++it)
+#pragma unroll
+        for (int s = 0; s < 8; ++s) a[it][s] = R[4 * s + kk][16 * it + r];
+#pragma unroll 1
+    for (int which = 0; which < 2; ++which) {
+        float *X = which == 0 ? Wt : Vt;
+        float *xI = X + (long)(I * EB) * ld;
+        float *xJ = X + (long)(J * EB) * ld;
+        for (int k0 = 0; k0 < c.ld; k0 += 16) {
+            float b[8];
+#pragma unroll
+            for (int s = 0; s < 4; ++s) b[s] = xI[(long)(4 * s + kk) * ld + k0 + r];
+#pragma unroll
+            for (int s = 4; s < 8; ++s) b[s] = hasJ ? xJ[(long)(4 * (s - 4) + kk) * ld + k0 + r] : 0.f;
+            floatx4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = d0;
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                d0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0][s], b[s], d0, 0, 0, 0);
+                d1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1][s], b[s], d1, 0, 0, 0);
+            }
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                xI[(long)(4 * kk + v) * ld + k0 + r] = d0[v];
+                if (hasJ) xJ[(long)(4 * kk + v) * ld + k0 + r] = d1[v];
+            }
+        }
+    }
+}
+
+// Row norms and eigenvalues.  A rotation whose tangent t is below sqrt(eps) has cosine 1 in fp32, so it
+// scales its two rows by sqrt(1 + t^2) instead of leaving their norms alone; over the thousands of small
+// rotations near convergence the rows of V (and of W, which sees the same transforms) grow by ~1e-4, all
+// by nearly the same factor, while staying orthogonal.  Hence v[i] = <V_i, W_i> / |V_i|^2 and the
+// eigenvector is V_i / |V_i|; scale[i] = 1 / |V_i|.  32 rows per workgroup, 8 lanes per row.
+// info = 1 if the sweep budget ran out before a quiet sweep.
+__global__ __launch_bounds__(256) void eig_values_kernel(const EigTable tab)
+{
+    int pi = 0;
+    while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].blk_start) ++pi;
+    const EigProb &pr = tab.p[pi];
+    const int local = blockIdx.x - pr.blk_start;
+    if (local == 0 && threadIdx.x == 0) *pr.info = (pr.rounds_total - *pr.stamp >= pr.m - 1) ? 0 : 1;
+    const int row = local * 32 + (threadIdx.x >> 3), l8 = threadIdx.x & 7;
+    float vw = 0.f, vv = 0.f;
+    if (row < pr.n) {
+        const float *vr = pr.Vt + (long)row * pr.ld, *wr = pr.Wt + (long)row * pr.ld;
+        for (int j = l8; j < pr.n; j += 8) {
+            vw += vr[j] * wr[j];
+            vv += vr[j] * vr[j];
+        }
+    }
+#pragma unroll
+    for (int h = 1; h < 8; h <<= 1) {
+        vw += __shfl_xor(vw, h);
+        vv += __shfl_xor(vv, h);
+    }
+    if (row < pr.n && l8 == 0) {
+        pr.v[row] = vw / vv;
+        pr.scale[row] = 1.f / sqrtf(vv);
+    }
+}
+
+// Q[j][i] = V[i][j] * scale[i] (eigenvectors in the columns of Q).  One workgroup per 32 x 32 tile of V.
+__global__ __launch_bounds__(256) void eig_final_kernel(const EigTable tab)
+{
+    __shared__ float t[32][33];
+    int pi = 0;
+    while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].blk_start) ++pi;
+    const EigProb &pr = tab.p[pi];
+    const int local = blockIdx.x - pr.blk_start;
+    const int nt = (pr.n + 31) / 32;
+    const int ti = local / nt, tj = local - ti * nt;       // tile (rows ti of V, columns tj)
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+        const int i = ti * 32 + ty + 8 * rr, j = tj * 32 + tx;
+        t[ty + 8 * rr][tx] = (i < pr.n && j < pr.n) ? pr.Vt[(long)i * pr.ld + j] * pr.scale[i] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+        const int j = tj * 32 + ty + 8 * rr, i = ti * 32 + tx;
+        if (i < pr.n && j < pr.n) pr.Q[(long)j * pr.n + i] = t[tx][ty + 8 * rr];
+    }
+}
+
+struct TrProb {
+    const float *src;
+    float *dst;
+    int n;
+    int blk_start;
+};
+
+struct TrTable {
+    int count;
+    TrProb p[kMaxProblems];
+};
+
+// dst = src^T for square matrices, 32 x 32 tiles through LDS.
+__global__ __launch_bounds__(256) void transpose_kernel(const TrTable tab)
+{
+    __shared__ float t[32][33];
+    int pi = 0;
+    while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].blk_start) ++pi;
+    const TrProb &pr = tab.p[pi];
+    const int local = blockIdx.x - pr.blk_start;
+    const int nt = (pr.n + 31) / 32;
+    const int ti = local / nt, tj = local - ti * nt;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+        const int i = ti * 32 + ty + 8 * rr, j = tj * 32 + tx;
+        t[ty + 8 * rr][tx] = (i < pr.n && j < pr.n) ? pr.src[(long)i * pr.n + j] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+        const int j = tj * 32 + ty + 8 * rr, i = ti * 32 + tx;
+        if (i < pr.n && j < pr.n) pr.dst[(long)j * pr.n + i] = t[tx][ty + 8 * rr];
+    }
+}
+
+hipError_t transpose_launch(const float *const *src, float *const *dst, const int *n, int count, hipStream_t s)
+{
+    for (int g0 = 0; g0 < count; g0 += kMaxProblems) {
+        TrTable tab;
+        tab.count = std::min(kMaxProblems, count - g0);
+        int blocks = 0;
+        for (int k = 0; k < tab.count; ++k) {
+            TrProb &p = tab.p[k];
+            p.src = src[g0 + k]; p.dst = dst[g0 + k]; p.n = n[g0 + k];
+            p.blk_start = blocks;
+            const int nt = (p.n + 31) / 32;
+            blocks += nt * nt;
+        }
+        KFAC_LAUNCH(KFAC_K_EIG_FINAL, s, transpose_kernel, dim3(blocks), dim3(256), 0, tab);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+namespace {
+
+struct EigLayout {
+    int ld, nb, m;
+    size_t floats;      // W or V of one matrix
+    size_t total;       // floats of one matrix in the workspace
+};
+
+EigLayout eig_layout(int n)
+{
+    EigLayout L;
+    L.ld = (n + 15) / 16 * 16;
+    L.nb = (n + EB - 1) / EB;
+    L.m = L.nb + (L.nb & 1);
+    if (L.m < 2) L.m = 2;
+    L.floats = (size_t)L.nb * EB * L.ld;
+    L.total = 2 * L.floats + (size_t)L.nb * EB;   // W, V, scale
+    return L;
+}
+
+}  // namespace
+
+size_t eigen_workspace_bytes(const EigenJob *jobs, int n)
+{
+    size_t total = 0;
+    for (int i = 0; i < n; ++i) total += align_up(eig_layout(jobs[i].n).total * sizeof(float), 256);
+    return total + align_up((size_t)n * sizeof(int), 256);
+}
+
+hipError_t eigen_launch(const EigenJob *jobs, int n, void *work, size_t work_bytes, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    if (eigen_workspace_bytes(jobs, n) > work_bytes) return hipErrorInvalidValue;
+    // matrices of one order back to back (largest first), W and V of a matrix adjacent
+    std::vector<int> order(n);
+    for (int i = 0; i < n; ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return jobs[a].n > jobs[b].n; });
+    int *stamps = reinterpret_cast<int *>(work);
+    char *base = static_cast<char *>(work) + align_up((size_t)n * sizeof(int), 256);
+    std::vector<EigProb> probs(n);
+    size_t off = 0;
+    const int sweeps = (int)std::max(1l, tuning().eigen_max_sweeps);
+    for (int k = 0; k < n; ++k) {
+        const EigenJob &j = jobs[order[k]];
+        const EigLayout L = eig_layout(j.n);
+        EigProb &p = probs[k];
+        p.M = j.M; p.Q = j.Q; p.v = j.v; p.info = j.info;
+        p.Wt = reinterpret_cast<float *>(base + off);
+        p.Vt = p.Wt + L.floats;
+        p.scale = p.Vt + L.floats;
+        off += align_up(L.total * sizeof(float), 256);
+        p.stamp = stamps + k;
+        p.n = j.n; p.ld = L.ld; p.nb = L.nb; p.m = L.m;
+        p.rounds_total = 0;
+    }
+    // launch sequences of at most kMaxEigClasses distinct orders
+    int k0 = 0;
+    while (k0 < n) {
+        EigSeq q;
+        q.nclass = 0;
+        q.inner_sweeps = (int)std::max(1l, tuning().eigen_inner_sweeps);
+        int blocks = 0, k1 = k0, mmax = 2;
+        while (k1 < n) {
+            const int nn = probs[k1].n;
+            int k2 = k1;
+            while (k2 < n && probs[k2].n == nn) ++k2;
+            if (q.nclass == kMaxEigClasses) break;
+            EigClass &c = q.c[q.nclass++];
+            const EigLayout L = eig_layout(nn);
+            c.Wt = probs[k1].Wt; c.Vt = probs[k1].Vt; c.stamp = probs[k1].stamp;
+            c.stride = (long)(align_up(L.total * sizeof(float), 256) / sizeof(float));
+            c.n = nn; c.ld = L.ld; c.nb = L.nb; c.m = L.m;
+            c.count = k2 - k1;
+            c.blk_start = blocks;
+            c.tol = std::max(5e-7f, 1.2e-7f * std::sqrt((float)nn));
+            blocks += c.count * (L.m / 2);
+            mmax = std::max(mmax, L.m);
+            k1 = k2;
+        }
+        const int rounds = sweeps * (mmax - 1);
+        for (int k = k0; k < k1; ++k) probs[k].rounds_total = rounds;
+        // init
+        for (int g0 = k0; g0 < k1; g0 += kMaxProblems) {
+            EigTable tab;
+            tab.count = std::min(kMaxProblems, k1 - g0);
+            int ib = 0;
+            for (int k = 0; k < tab.count; ++k) {
+                tab.p[k] = probs[g0 + k];
+                tab.p[k].blk_start = ib;
+                ib += (int)(((long)tab.p[k].nb * EB * tab.p[k].ld + 1023) / 1024);
+            }
+            KFAC_LAUNCH(KFAC_K_EIG_INIT, s, eig_init_kernel, dim3(ib), dim3(256), 0, tab);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+        for (int t = 0; t < rounds; ++t) {
+            q.t = t;
+            KFAC_LAUNCH(KFAC_K_EIG_ROUND, s, eig_round_kernel, dim3(blocks), dim3(64), 0, q);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+        for (int g0 = k0; g0 < k1; g0 += kMaxProblems) {
+            EigTable tab;
+            tab.count = std::min(kMaxProblems, k1 - g0);
+            int vb = 0;
+            for (int k = 0; k < tab.count; ++k) {
+                tab.p[k] = probs[g0 + k];
+                tab.p[k].blk_start = vb;
+                vb += (tab.p[k].n + 31) / 32;
+            }
+            KFAC_LAUNCH(KFAC_K_EIG_FINAL, s, eig_values_kernel, dim3(vb), dim3(256), 0, tab);
+            hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            int fb = 0;
+            for (int k = 0; k < tab.count; ++k) {
+                tab.p[k].blk_start = fb;
+                const int nt = (tab.p[k].n + 31) / 32;
+                fb += nt * nt;
+            }
+            KFAC_LAUNCH(KFAC_K_EIG_FINAL, s, eig_final_kernel, dim3(fb), dim3(256), 0, tab);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+        k0 = k1;
+    }
+    return hipSuccess;
+}
+
+}  // namespace kfac

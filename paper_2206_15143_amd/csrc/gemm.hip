@@ -23,6 +23,8 @@ struct GemmProb {
     int mode;
     int p0, p1;
     int vecA, vecB;
+    const float *rv, *cv;   // kStoreDiv
+    float gamma;
 };
 
 struct GemmTable {
@@ -101,6 +103,8 @@ __global__ __launch_bounds__(T::NT) void gemm_tn_kernel(const GemmTable tab)
                     pr.C[(long)m * pr.ldc + n] = val;
                 } else if (pr.mode == kStoreT) {
                     pr.C[(long)n * pr.ldc + m] = val;
+                } else if (pr.mode == kStoreDiv) {
+                    pr.C[(long)m * pr.ldc + n] = val / (pr.rv[m] * pr.cv[n] + pr.gamma);
                 } else {
                     const bool skip = (n > m) || (m >= pr.p0 && m < pr.p1) || (n >= pr.p0 && n < pr.p1);
                     if (!skip) pr.C[(long)m * pr.ldc + n] -= val;
@@ -146,7 +150,7 @@ namespace {
 // update qualifies only when its untouched band starts and ends on macro-tile boundaries.
 bool wave_gemm_eligible(const GemmJob &j)
 {
-    if (!tuning().use_wave_gemm || j.mode == kStoreT) return false;
+    if (!tuning().use_wave_gemm || j.mode == kStoreT || j.mode == kStoreDiv) return false;
     if (j.M < 100 || j.N < 100 || j.K < 16) return false;
     if ((long)j.K * j.lda * 4 > 0x7fffffffl || (long)j.K * j.ldb * 4 > 0x7fffffffl) return false;
     if (((uintptr_t)j.A) % 4 || ((uintptr_t)j.B) % 4) return false;
@@ -250,6 +254,7 @@ hipError_t gemm_launch(const GemmJob *jobs, int n, hipStream_t s)
             p.blk_start = blocks;
             p.mode = j.mode;
             p.p0 = j.p0; p.p1 = j.p1;
+            p.rv = j.rv; p.cv = j.cv; p.gamma = j.gamma;
             p.vecA = (((uintptr_t)j.A) % 16 == 0 && j.lda % 4 == 0) ? 1 : 0;
             p.vecB = (((uintptr_t)j.B) % 16 == 0 && j.ldb % 4 == 0) ? 1 : 0;
             blocks += (j.mode == kSubLowerSkip) ? p.tm * (p.tm + 1) / 2 : p.tm * p.tn;
