@@ -33,6 +33,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tune", action="append", default=[], help="development knob key=value")
     ap.add_argument("--seed", type=int, default=2000)
+    ap.add_argument("--variant", choices=["inverse", "eigen"], default="inverse",
+                    help="inverse: damped inverses + G_inv grad A_inv (the headline path); "
+                         "eigen: eigen-decompositions + the Eq. 13 preconditioner")
     ap.add_argument("--traffic", type=float, default=None,
                     help="HBM bytes per launch of the dominant kernel, from the rocprofv3 --pmc runs "
                          "(FETCH_SIZE + WRITE_SIZE, scaled by the calibration copy); default: the figure "
@@ -97,7 +100,7 @@ def im2col_leg(kf, torch, step_update, ws_bytes_fn, work, steps):
                      "goes through the extractor (grouped launches of up to 40 layers)")
 
 
-def cpu_baseline(config, layers, hp):
+def cpu_baseline(config, layers, hp, variant="inverse"):
     """The CPU oracle, as it stands, timed on one layer of each distinct shape;
     the whole-update figure is the sum over shapes of (time x number of layers of that shape)."""
     from collections import Counter
@@ -114,8 +117,11 @@ def cpu_baseline(config, layers, hp):
         sA, sG = shapes.layer_scales(l, hp["batch"])
         t0 = time.time()
         A, G = orc.update_factors_layer(l, act, gout, sA, sG, hp["decay"], np.eye(l.d_A), np.eye(l.d_G))
-        Ai, Gi = orc.invert_layer(A, G, hp["damping"], hp["damping"])
-        orc.precondition_layer(Ai, Gi, grad)
+        if variant == "eigen":
+            orc.precondition_eigen_layer(A, G, grad, hp["damping"])
+        else:
+            Ai, Gi = orc.invert_layer(A, G, hp["damping"], hp["damping"])
+            orc.precondition_layer(Ai, Gi, grad)
         dt = (time.time() - t0) * 1e3
         total_ms += dt * cnt
         sampled += cnt
@@ -167,10 +173,27 @@ def main():
     ws = torch.empty(kf.kfac_workspace_bytes_batched(descs, b, h, w), dtype=torch.uint8, device=dev)
     lam = hp["damping"]
 
+    eigen = args.variant == "eigen"
+    if eigen:   # A_inv / G_inv hold Q_A / Q_G
+        v_A = [torch.empty((l.d_A,), device=dev) for l in layers]
+        v_G = [torch.empty((l.d_G,), device=dev) for l in layers]
+
+    def second_stage():
+        if eigen:
+            kf.kfac_eigen_batched(descs, A_run, G_run, A_inv, v_A, G_inv, v_G, info, ws)
+        else:
+            kf.kfac_invert_batched(descs, A_run, G_run, lam, lam, A_inv, G_inv, info, ws)
+
+    def third_stage():
+        if eigen:
+            kf.kfac_precondition_eigen_batched(descs, A_inv, v_A, G_inv, v_G, lam, grads, outs, ws)
+        else:
+            kf.kfac_precondition_batched(descs, A_inv, G_inv, grads, outs, ws)
+
     def step():
         kf.kfac_update_factors_batched(descs, acts, gouts, b, h, w, sA, sG, hp["decay"], A_run, G_run, ws)
-        kf.kfac_invert_batched(descs, A_run, G_run, lam, lam, A_inv, G_inv, info, ws)
-        kf.kfac_precondition_batched(descs, A_inv, G_inv, grads, outs, ws)
+        second_stage()
+        third_stage()
 
     for _ in range(args.warmup):
         step()
@@ -180,7 +203,7 @@ def main():
         step()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-    assert int(info.abs().sum().item()) == 0, "a factor was flagged not positive definite"
+    assert int(info.abs().sum().item()) == 0, "a factor was flagged (not positive definite / eigen sweep budget)"
 
     # the three calls timed one by one, for the stale-factor schedule of the paper's last experiment
     # (factors refreshed every F_freq iterations, inverses every K_freq, preconditioning every iteration)
@@ -193,10 +216,11 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t) * 1e3 / args.steps
     t_upd = timed(lambda: kf.kfac_update_factors_batched(descs, acts, gouts, b, h, w, sA, sG, hp["decay"], A_run, G_run, ws))
-    t_inv = timed(lambda: kf.kfac_invert_batched(descs, A_run, G_run, lam, lam, A_inv, G_inv, info, ws))
-    t_pre = timed(lambda: kf.kfac_precondition_batched(descs, A_inv, G_inv, grads, outs, ws))
+    t_inv = timed(second_stage)
+    t_pre = timed(third_stage)
     F_FREQ, K_FREQ = 50, 500
-    schedule = dict(update_factors_ms=round(t_upd, 4), invert_ms=round(t_inv, 4), precondition_ms=round(t_pre, 4),
+    schedule = dict(update_factors_ms=round(t_upd, 4), **{"eigen_ms" if eigen else "invert_ms": round(t_inv, 4)},
+                    precondition_ms=round(t_pre, 4),
                     F_freq=F_FREQ, K_freq=K_FREQ,
                     amortised_ms_per_iteration=round(t_pre + t_upd / F_FREQ + t_inv / K_FREQ, 4))
 
@@ -261,7 +285,8 @@ def main():
     out = dict(metric=METRIC, value=round(ms_per_step, 4), unit="ms", n_gpus=1, steps=args.steps,
                warmup=args.warmup, ms_per_step=round(ms_per_step, 4), higher_is_better=False, scaling="weak",
                vs_baseline=None, dtype="f32" if not bf else "bf16 in, f32 accumulate", data="synthetic",
-               config=dict(workload=args.config, layers=len(layers), batch=batch, damping=lam, decay=hp["decay"],
+               config=dict(workload=args.config, variant=args.variant, layers=len(layers), batch=batch, damping=lam,
+                           decay=hp["decay"],
                            in_dtype=hp["dtype"]),
                kf_gemm_mfma_util_pct=round(100 * achieved / peak, 2),
                stage_ms=stages, launches_per_step=launches, roofline=roofline, **extra)
@@ -271,7 +296,7 @@ def main():
     kf.kfac_profile_copy(cdst, csrc, csrc.numel())
     torch.cuda.synchronize()
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(args.config, layers, hp)
+        out["cpu_baseline"] = cpu_baseline(args.config, layers, hp, args.variant)
     print(json.dumps(out))
 
 

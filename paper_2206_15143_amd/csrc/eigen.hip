@@ -6,13 +6,14 @@
 // applies the same orthogonal transform to both from the left, so W = V M holds throughout; when the
 // rows of W are mutually orthogonal, row i of V is an eigenvector and <v_i, w_i> its eigenvalue.
 // Rows are grouped into blocks of 16.  One round pairs all blocks off (round-robin tournament: every
-// two blocks meet once per sweep) and is ONE launch with one wavefront per pair of every matrix:
+// two blocks meet once per sweep) and is ONE launch with one workgroup per pair of every matrix:
 //   1. the 32 x 32 Gram matrix S = X X^T of the pair's 32 rows of W on the MFMA units (K = n);
-//   2. S is diagonalised in LDS by two-sided cyclic Jacobi (16 disjoint rotations per inner round,
-//      31 inner rounds per inner sweep), which gives the 32 x 32 orthogonal R;
+//   2. one sweep of two-sided cyclic Jacobi over S in LDS (16 disjoint rotations per inner round,
+//      31 inner rounds) gives the 32 x 32 orthogonal R (more inner sweeps per round did not save
+//      outer sweeps);
 //   3. the rows of W and of V are replaced by R^T X on the MFMA units.
 // A pair whose Gram matrix is already diagonal to rounding does nothing; a matrix none of whose
-// pairs did anything for a whole sweep has converged and its wavefronts return at once (the
+// pairs did anything for a whole sweep has converged and its workgroups return at once (the
 // per-matrix round stamp lives in device memory, so the host never synchronises).  The launch
 // sequence has a fixed length (a sweep budget); `info` reports a matrix that used it up.
 // Rows past n (padding of the last block, and the bye of an odd number of blocks) are zero rows:
@@ -98,10 +99,11 @@ __device__ __forceinline__ void rr_pair(int m, int r, int k, int &a, int &b)
     }
 }
 
-__global__ __launch_bounds__(64) void eig_round_kernel(const EigSeq q)
+__global__ __launch_bounds__(256) void eig_round_kernel(const EigSeq q)
 {
     __shared__ float S[32][33];
     __shared__ float R[32][33];
+    __shared__ float part_s[4][3][256];     // per-wavefront partial Gram tiles (summed in a fixed order)
 
     int ci = 0;
     while (ci + 1 < q.nclass && (int)blockIdx.x >= q.c[ci + 1].blk_start) ++ci;
@@ -119,7 +121,8 @@ __global__ __launch_bounds__(64) void eig_round_kernel(const EigSeq q)
     if (I > J) { const int t = I; I = J; J = t; }
     if (I >= c.nb) return;                      // cannot happen for m <= nb + 1; keeps the indexing safe
     const bool hasJ = J < c.nb;                 // the bye block of an odd count is all zero rows
-    const int lane = threadIdx.x;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, w = tid >> 6;
     const int r = lane & 15, kk = lane >> 4;
     const long ld = c.ld;
     float *Wt = c.Wt + (long)mat * c.stride;
@@ -127,31 +130,45 @@ __global__ __launch_bounds__(64) void eig_round_kernel(const EigSeq q)
     const float *wI = Wt + (long)(I * EB + r) * ld + 4 * kk;
     const float *wJ = Wt + (long)(J * EB + r) * ld + 4 * kk;
 
-    // ---- 1. Gram matrix of the 32 rows ----
-    floatx4 s00 = {0.f, 0.f, 0.f, 0.f}, s10 = s00, s11 = s00;
-    for (int k0 = 0; k0 < c.ld; k0 += 16) {
-        const floatx4 x0 = *reinterpret_cast<const floatx4 *>(wI + k0);
-        floatx4 x1 = {0.f, 0.f, 0.f, 0.f};
-        if (hasJ) x1 = *reinterpret_cast<const floatx4 *>(wJ + k0);
+    // ---- 1. Gram matrix of the 32 rows: wavefront w takes the 16-column chunks w, w + 4, ... ----
+    {
+        floatx4 s00 = {0.f, 0.f, 0.f, 0.f}, s10 = s00, s11 = s00;
+#pragma unroll 4
+        for (int k0 = 16 * w; k0 < c.ld; k0 += 64) {
+            const floatx4 x0 = *reinterpret_cast<const floatx4 *>(wI + k0);
+            floatx4 x1 = {0.f, 0.f, 0.f, 0.f};
+            if (hasJ) x1 = *reinterpret_cast<const floatx4 *>(wJ + k0);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            s00 = __builtin_amdgcn_mfma_f32_16x16x4f32(x0[e], x0[e], s00, 0, 0, 0);
-            s10 = __builtin_amdgcn_mfma_f32_16x16x4f32(x1[e], x0[e], s10, 0, 0, 0);
-            s11 = __builtin_amdgcn_mfma_f32_16x16x4f32(x1[e], x1[e], s11, 0, 0, 0);
+            for (int e = 0; e < 4; ++e) {
+                s00 = __builtin_amdgcn_mfma_f32_16x16x4f32(x0[e], x0[e], s00, 0, 0, 0);
+                s10 = __builtin_amdgcn_mfma_f32_16x16x4f32(x1[e], x0[e], s10, 0, 0, 0);
+                s11 = __builtin_amdgcn_mfma_f32_16x16x4f32(x1[e], x1[e], s11, 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {           // element (row 4 kk + v, column r) of each tile
+            part_s[w][0][(4 * kk + v) * 16 + r] = s00[v];
+            part_s[w][1][(4 * kk + v) * 16 + r] = s10[v];
+            part_s[w][2][(4 * kk + v) * 16 + r] = s11[v];
         }
     }
+    for (int e = tid; e < 32 * 32; e += 256) R[e >> 5][e & 31] = ((e >> 5) == (e & 31)) ? 1.f : 0.f;
+    __syncthreads();
+    {
+        const int row = tid >> 4, col = tid & 15;
+        float t3[3];
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-        S[4 * kk + v][r] = s00[v];
-        S[16 + 4 * kk + v][r] = s10[v];
-        S[r][16 + 4 * kk + v] = s10[v];
-        S[16 + 4 * kk + v][16 + r] = s11[v];
+        for (int k = 0; k < 3; ++k)
+            t3[k] = ((part_s[0][k][tid] + part_s[1][k][tid]) + part_s[2][k][tid]) + part_s[3][k][tid];
+        S[row][col] = t3[0];
+        S[16 + row][col] = t3[1];
+        S[col][16 + row] = t3[1];
+        S[16 + row][16 + col] = t3[2];
     }
-    for (int e = lane; e < 32 * 32; e += 64) R[e >> 5][e & 31] = ((e >> 5) == (e & 31)) ? 1.f : 0.f;
     __syncthreads();
 
-    // ---- 2. two-sided cyclic Jacobi on S; lane (pair = lane & 15, part = lane >> 4) ----
-    const int pr_ = lane & 15, part = lane >> 4;
+    // ---- 2. two-sided cyclic Jacobi on S; thread (pair = tid & 15, part = tid >> 4) moves 2 elements ----
+    const int pr_ = tid & 15, part = tid >> 4;
     bool active = false;
     for (int sw = 0; sw < q.inner_sweeps; ++sw) {
         bool any = false;
@@ -162,45 +179,62 @@ __global__ __launch_bounds__(64) void eig_round_kernel(const EigSeq q)
             if (p > qq) { const int t = p; p = qq; qq = t; }
             const float app = S[p][p], aqq = S[qq][qq], apq = S[p][qq];
             float cs = 1.f, sn = 0.f;
-            const bool rot = fabsf(apq) > c.tol * sqrtf(fabsf(app * aqq)) && apq != 0.f;
+            const bool rot = fabsf(apq) > c.tol * __builtin_amdgcn_sqrtf(fabsf(app * aqq)) && apq != 0.f;
             if (rot) {
-                const float tau = (aqq - app) / (2.f * apq);
-                const float tt = (tau >= 0.f ? 1.f : -1.f) / (fabsf(tau) + sqrtf(1.f + tau * tau));
-                cs = 1.f / sqrtf(1.f + tt * tt);
+                // tangent of the rotation that annihilates S[p][q]: the smaller root of t^2 + 2 tau t - 1 = 0.
+                // Hardware reciprocal / square root (1 ulp): the angle only has to be nearly right, and
+                // cs^2 + sn^2 = 1 holds to rounding whatever tt is.
+                const float tau = (aqq - app) * __builtin_amdgcn_rcpf(2.f * apq);
+                const float tt = (tau >= 0.f ? 1.f : -1.f) *
+                                 __builtin_amdgcn_rcpf(fabsf(tau) + __builtin_amdgcn_sqrtf(1.f + tau * tau));
+                cs = __builtin_amdgcn_rsqf(1.f + tt * tt);
                 sn = tt * cs;
             }
             any = any || rot;
-            __syncthreads();                    // every lane has read its pivots before anything moves
-            // columns p, q of S and of R:  S <- S J,  R <- R J
+            __syncthreads();                    // every thread has read its pivots before anything moves
+            // columns p, q of S and of R:  S <- S J,  R <- R J   (all loads first: they pipeline)
+            {
+                float sp[2], sq[2], rp[2], rq[2];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int i = part * 8 + e;
-                const float sp = S[i][p], sq = S[i][qq];
-                S[i][p] = cs * sp - sn * sq;
-                S[i][qq] = sn * sp + cs * sq;
-                const float rp = R[i][p], rq = R[i][qq];
-                R[i][p] = cs * rp - sn * rq;
-                R[i][qq] = sn * rp + cs * rq;
+                for (int e = 0; e < 2; ++e) {
+                    const int i = part * 2 + e;
+                    sp[e] = S[i][p]; sq[e] = S[i][qq];
+                    rp[e] = R[i][p]; rq[e] = R[i][qq];
+                }
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const int i = part * 2 + e;
+                    S[i][p] = cs * sp[e] - sn * sq[e];
+                    S[i][qq] = sn * sp[e] + cs * sq[e];
+                    R[i][p] = cs * rp[e] - sn * rq[e];
+                    R[i][qq] = sn * rp[e] + cs * rq[e];
+                }
             }
             __syncthreads();
             // rows p, q of S:  S <- J^T S
+            {
+                float sp[2], sq[2];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int j = part * 8 + e;
-                const float sp = S[p][j], sq = S[qq][j];
-                S[p][j] = cs * sp - sn * sq;
-                S[qq][j] = sn * sp + cs * sq;
+                for (int e = 0; e < 2; ++e) {
+                    const int j = part * 2 + e;
+                    sp[e] = S[p][j]; sq[e] = S[qq][j];
+                }
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const int j = part * 2 + e;
+                    S[p][j] = cs * sp[e] - sn * sq[e];
+                    S[qq][j] = sn * sp[e] + cs * sq[e];
+                }
             }
             __syncthreads();
         }
-        const bool wave_any = __builtin_amdgcn_ballot_w64(any) != 0;
-        if (!wave_any) break;
+        if (!__syncthreads_or(any ? 1 : 0)) break;
         active = true;
     }
     if (!active) return;                        // R is the identity: nothing to apply
-    if (lane == 0) atomicMax(c.stamp + mat, q.t + 1);
+    if (tid == 0) atomicMax(c.stamp + mat, q.t + 1);
 
-    // ---- 3. rows <- R^T rows, for W and V ----
+    // ---- 3. rows <- R^T rows, for W and V; wavefront w takes the 64-column groups w, w + 4, ... ----
     float a[2][8];
 #pragma unroll
     for (int it = 0; it < 2; ++it)
@@ -211,22 +245,38 @@ __global__ __launch_bounds__(64) void eig_round_kernel(const EigSeq q)
         float *X = which == 0 ? Wt : Vt;
         float *xI = X + (long)(I * EB) * ld;
         float *xJ = X + (long)(J * EB) * ld;
-        for (int k0 = 0; k0 < c.ld; k0 += 16) {
-            float b[8];
+        // four 16-column chunks at a time: 32 loads in flight, then the products, then the stores
+        for (int k0 = 64 * w; k0 < c.ld; k0 += 256) {
+            float b[4][8];
 #pragma unroll
-            for (int s = 0; s < 4; ++s) b[s] = xI[(long)(4 * s + kk) * ld + k0 + r];
+            for (int g = 0; g < 4; ++g) {
+                const int kc = k0 + 16 * g + r;
+                const bool in = k0 + 16 * g < c.ld;
 #pragma unroll
-            for (int s = 4; s < 8; ++s) b[s] = hasJ ? xJ[(long)(4 * (s - 4) + kk) * ld + k0 + r] : 0.f;
-            floatx4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = d0;
+                for (int s = 0; s < 4; ++s) b[g][s] = in ? xI[(long)(4 * s + kk) * ld + kc] : 0.f;
 #pragma unroll
-            for (int s = 0; s < 8; ++s) {
-                d0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0][s], b[s], d0, 0, 0, 0);
-                d1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1][s], b[s], d1, 0, 0, 0);
+                for (int s = 4; s < 8; ++s) b[g][s] = (in && hasJ) ? xJ[(long)(4 * (s - 4) + kk) * ld + kc] : 0.f;
+            }
+            floatx4 d0[4], d1[4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                d0[g] = floatx4{0.f, 0.f, 0.f, 0.f};
+                d1[g] = d0[g];
+#pragma unroll
+                for (int s = 0; s < 8; ++s) {
+                    d0[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0][s], b[g][s], d0[g], 0, 0, 0);
+                    d1[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1][s], b[g][s], d1[g], 0, 0, 0);
+                }
             }
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                xI[(long)(4 * kk + v) * ld + k0 + r] = d0[v];
-                if (hasJ) xJ[(long)(4 * kk + v) * ld + k0 + r] = d1[v];
+            for (int g = 0; g < 4; ++g) {
+                if (k0 + 16 * g >= c.ld) break;
+                const int kc = k0 + 16 * g + r;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    xI[(long)(4 * kk + v) * ld + kc] = d0[g][v];
+                    if (hasJ) xJ[(long)(4 * kk + v) * ld + kc] = d1[g][v];
+                }
             }
         }
     }
@@ -442,7 +492,7 @@ hipError_t eigen_launch(const EigenJob *jobs, int n, void *work, size_t work_byt
         }
         for (int t = 0; t < rounds; ++t) {
             q.t = t;
-            KFAC_LAUNCH(KFAC_K_EIG_ROUND, s, eig_round_kernel, dim3(blocks), dim3(64), 0, q);
+            KFAC_LAUNCH(KFAC_K_EIG_ROUND, s, eig_round_kernel, dim3(blocks), dim3(256), 0, q);
             hipError_t e = hipGetLastError();
             if (e != hipSuccess) return e;
         }

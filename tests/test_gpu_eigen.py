@@ -103,7 +103,7 @@ def test_eigen_sweep_budget_is_reported():
     try:
         QA, vA, QG, vG, info = _gpu_eigen(desc, A, G)
     finally:
-        kf.kfac_tune("eigen_max_sweeps", 16)
+        kf.kfac_tune("eigen_max_sweeps", 20)
     assert list(info) == [1, 0]
     Qd = QA.astype(np.float64)
     assert np.linalg.norm(Qd.T @ Qd - np.eye(100)) / 10 < 1e-3       # still an orthogonal iterate
