@@ -55,6 +55,9 @@ __host__ __device__ inline Conv3Geo conv3_geo(int H, int W, int R)
 __host__ __device__ inline long conv3_pack(int H, int W, int R) { return ((long)H << 40) | ((long)W << 20) | (long)R; }
 
 // Output rows per stage: the largest divisor of H whose ring of slabs fits LDS (0 = shape not supported).
+// A stage must hold at least 8 k-steps: with fewer (maps of 4 x 4 and below) the barrier and the slab loads of
+// every stage outweigh its products, and the explicit patch matrix is the faster route (measured on
+// 512-channel 4 x 4 layers).
 inline int conv3_choose_rows(int H, int W)
 {
     if (W % 4 != 0 || W < 4 || W > 252) return 0;
@@ -63,7 +66,7 @@ inline int conv3_choose_rows(int H, int W)
         if (H % R != 0 || (R * W) % 16 != 0) continue;
         const Conv3Geo g = conv3_geo(H, W, R);
         const long bytes = ((long)C3_NSTAGE * W_SLOTS * g.slab + C3_PRE + 256) * 4;
-        if (bytes > 150 * 1024 || (g.NI + 3) / 4 > 4) continue;
+        if (bytes > 150 * 1024 || (g.NI + 3) / 4 > 4 || g.nks < 8) continue;
         best = R;
     }
     return best;
