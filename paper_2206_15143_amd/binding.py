@@ -59,6 +59,11 @@ def load_library():
     if not os.path.exists(path):
         raise ImportError(f"{path} is missing: build it with `python -m paper_2206_15143_amd.build` "
                           "(there is no CPU or PyTorch fallback)")
+    # The caller's device memory and streams come from PyTorch, which ships its own HIP runtime.  Import it
+    # first so that this library binds to that same runtime: loaded the other way round the process holds
+    # two runtimes and a torch stream handle means nothing to the one the kernels are launched through
+    # (every launch then fails).
+    import torch  # noqa: F401
     lib = C.CDLL(path)
     vp, ip, fp, sz = C.c_void_p, C.POINTER(C.c_int), C.POINTER(C.c_float), C.c_size_t
     dp = C.POINTER(LayerDesc)
