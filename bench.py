@@ -22,6 +22,7 @@ sys.path.insert(0, ROOT)
 
 METRIC = "ms per full K-FAC update (factors+inverse+precondition); KF-GEMM MFMA util %"
 PEAK_FP32_MFMA_TFLOPS = 157.3
+PEAK_HBM_GBPS = 8000.0
 
 
 def parse():
@@ -293,6 +294,14 @@ def main():
     syrk_ms = sum(v["ms_per_step"] for v in per_kernel.values())
     achieved = syrk_flops / (syrk_ms * 1e-3) / 1e12
     extra = dict(kf_gemm_kernels=per_kernel, stale_schedule=schedule)
+    # running-average update = the epilogue of the split reduction: the library counts, per reduce launch, the
+    # split slices and the old factor read (one triangle) and the factor written (both triangles)
+    r_ms, r_n, r_bytes = cls["syrk_reduce"]
+    if r_n:
+        extra["running_average"] = dict(bound="hbm", kernel="syrk_reduce_kernel", achieved=round(r_bytes / (r_ms * 1e-3) / 1e9, 1),
+                                        peak=PEAK_HBM_GBPS, unit="GB/s", frac=round(r_bytes / (r_ms * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4),
+                                        ms_per_step=round(r_ms / args.steps, 4), launches_per_step=r_n // args.steps,
+                                        algorithmic_bytes_per_step=r_bytes / args.steps)
     im2 = im2col_leg(kf, torch,
                      lambda w_: kf.kfac_update_factors_batched(descs, acts, gouts, b, h, w, sA, sG, hp["decay"],
                                                                A_run, G_run, w_),

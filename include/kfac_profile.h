@@ -41,9 +41,11 @@ int kfac_timing_enable(int on);
 /* Waits for the recorded events, ADDS per-class elapsed milliseconds, launch
  * counts and algorithmic work into the host arrays of KFAC_K_COUNT entries (any
  * may be NULL) and forgets the recorded launches.  Work is counted for the
- * KF-GEMM classes only: sum over the launch's problems of rows * d * (d + 1)
- * flops (one triangle, d including the bias column).  Returns 0, or non-zero
- * on a HIP error. */
+ * KF-GEMM classes: sum over the launch's problems of rows * d * (d + 1) flops
+ * (one triangle, d including the bias column); and for KFAC_K_SYRK_REDUCE:
+ * bytes, 4 * ((splits + 1) * d (d + 1) / 2 + d * d) per problem (split slices
+ * and old factor read, factor written to both triangles).  Returns 0, or
+ * non-zero on a HIP error. */
 int kfac_timing_collect(double *ms_per_class, long *launches_per_class, double *work_per_class);
 const char *kfac_timing_class_name(int cls);
 

@@ -482,25 +482,27 @@ bool vec_ok(const FactorJob &j)
 }
 
 template <class T, int LAYOUT, int DT>
-hipError_t launch_cfg(const SyrkTable &tab, int blocks, int red_blocks, double flops, hipStream_t s)
+hipError_t launch_cfg(const SyrkTable &tab, int blocks, int red_blocks, double flops, double red_bytes, hipStream_t s)
 {
     KFAC_LAUNCH(KFAC_K_SYRK, s, (syrk_partial_kernel<T, LAYOUT, DT>), dim3(blocks), dim3(T::NT), 0, tab);
     timing_work(flops);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<T>), dim3(red_blocks), dim3(256), 0, tab);
+    timing_work(red_bytes);
     return hipGetLastError();
 }
 
 template <class T>
-hipError_t launch_ld(const SyrkTable &tab, int layout, int dt, int blocks, int red_blocks, double flops, hipStream_t s)
+hipError_t launch_ld(const SyrkTable &tab, int layout, int dt, int blocks, int red_blocks, double flops, double red_bytes,
+                     hipStream_t s)
 {
     if (layout == kRows) {
-        if (dt == 0) return launch_cfg<T, kRows, 0>(tab, blocks, red_blocks, flops, s);
-        return launch_cfg<T, kRows, 1>(tab, blocks, red_blocks, flops, s);
+        if (dt == 0) return launch_cfg<T, kRows, 0>(tab, blocks, red_blocks, flops, red_bytes, s);
+        return launch_cfg<T, kRows, 1>(tab, blocks, red_blocks, flops, red_bytes, s);
     }
-    if (dt == 0) return launch_cfg<T, kNCHW, 0>(tab, blocks, red_blocks, flops, s);
-    return launch_cfg<T, kNCHW, 1>(tab, blocks, red_blocks, flops, s);
+    if (dt == 0) return launch_cfg<T, kNCHW, 0>(tab, blocks, red_blocks, flops, red_bytes, s);
+    return launch_cfg<T, kNCHW, 1>(tab, blocks, red_blocks, flops, red_bytes, s);
 }
 
 }  // namespace
@@ -535,11 +537,15 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
         tab.count = (int)g.size();
         tab.debug = (int)tuning().wave_debug;
         int blocks = 0, red = 0;
-        double flops = 0.0;
+        double flops = 0.0, red_bytes = 0.0;
         for (int k = 0; k < tab.count; ++k) {
             const int j = g[k];
             const FactorJob &job = jobs[j];
             flops += (double)job.K * (job.d_core + job.has_bias) * (job.d_core + job.has_bias + 1);
+            {   // reduce + running average: the split slices and the old factor read (one triangle), the factor written (both)
+                const double dF = job.d_core + job.has_bias, tri = dF * (dF + 1) / 2;
+                red_bytes += 4.0 * ((pl[j].splits + 1) * tri + dF * dF);
+            }
             SyrkProb &p = tab.p[k];
             p.x = job.x;
             p.partial = reinterpret_cast<float *>(static_cast<char *>(work) + offs[j]);
@@ -589,6 +595,7 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
                 e = hipGetLastError();
                 if (e != hipSuccess) break;
                 KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<3, 3>, true>), dim3(red), dim3(256), 0, tab);
+                timing_work(red_bytes);
                 e = hipGetLastError();
                 break;
             }
@@ -607,6 +614,7 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
                     KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<1, 2>>), dim3(red), dim3(256), 0, tab);
                 else
                     KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<2, 2>>), dim3(red), dim3(256), 0, tab);
+                timing_work(red_bytes);
                 e = hipGetLastError();
                 break;
             }
@@ -619,6 +627,7 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
                 e = hipGetLastError();
                 if (e != hipSuccess) break;
                 KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<8, 2>>), dim3(red), dim3(256), 0, tab);
+                timing_work(red_bytes);
                 e = hipGetLastError();
                 break;
             }
@@ -628,6 +637,7 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
                 e = hipGetLastError();
                 if (e != hipSuccess) break;
                 KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<3, 3>, true>), dim3(red), dim3(256), 0, tab);
+                timing_work(red_bytes);
                 e = hipGetLastError();
                 break;
             }
@@ -637,13 +647,14 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
                 e = hipGetLastError();
                 if (e != hipSuccess) break;
                 KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<3, 3>, true>), dim3(red), dim3(256), 0, tab);
+                timing_work(red_bytes);
                 e = hipGetLastError();
                 break;
             }
-            case 0: e = launch_ld<Tile<4, 2>>(tab, layout, dt, blocks, red, flops, s); break;
-            case 1: e = launch_ld<Tile<3, 3>>(tab, layout, dt, blocks, red, flops, s); break;
-            case 2: e = launch_ld<Tile<2, 2>>(tab, layout, dt, blocks, red, flops, s); break;
-            default: e = launch_ld<Tile<1, 2>>(tab, layout, dt, blocks, red, flops, s); break;
+            case 0: e = launch_ld<Tile<4, 2>>(tab, layout, dt, blocks, red, flops, red_bytes, s); break;
+            case 1: e = launch_ld<Tile<3, 3>>(tab, layout, dt, blocks, red, flops, red_bytes, s); break;
+            case 2: e = launch_ld<Tile<2, 2>>(tab, layout, dt, blocks, red, flops, red_bytes, s); break;
+            default: e = launch_ld<Tile<1, 2>>(tab, layout, dt, blocks, red, flops, red_bytes, s); break;
         }
         if (e != hipSuccess) return e;
     }
