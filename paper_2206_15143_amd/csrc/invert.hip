@@ -233,11 +233,11 @@ hipError_t fused_launch(const InvertJob *jobs, const std::vector<int> &idx, cons
                         void *work, InvProbF *dtab, hipStream_t s)
 {
     const int total = (int)idx.size();
-    // descriptors -> device table, 64 per upload launch
-    for (int g0 = 0; g0 < total; g0 += 64) {
+    // descriptors -> device table
+    for (int g0 = 0; g0 < total; g0 += kInvUploadMax) {
         InvUpload u;
         u.dst = dtab + g0;
-        u.count = std::min(64, total - g0);
+        u.count = std::min(kInvUploadMax, total - g0);
         for (int k = 0; k < u.count; ++k) {
             const InvertJob &j = jobs[idx[g0 + k]];
             InvProbF &p = u.p[k];
@@ -250,7 +250,7 @@ hipError_t fused_launch(const InvertJob *jobs, const std::vector<int> &idx, cons
             p.P = ws;
             p.Vt = ws + 2 * FNB * FNB;
         }
-        KFAC_LAUNCH(KFAC_K_INV_INIT, s, inv_upload_kernel, dim3(1), dim3(64), 0, u);
+        KFAC_LAUNCH(KFAC_K_INV_INIT, s, inv_upload_kernel, dim3((u.count + 15) / 16), dim3(64), 0, u);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -47,10 +47,12 @@ struct InvProbF {
     const float *dptr; // device-side damping (overrides `damping` when not null)
 };
 
+constexpr int kInvUploadMax = 224;   // descriptors per upload launch (a 16 KB kernel argument)
+
 struct InvUpload {
     InvProbF *dst;
     int count;
-    InvProbF p[64];
+    InvProbF p[kInvUploadMax];
 };
 
 struct InvClass {
