@@ -780,6 +780,7 @@ int kfac_tune(const char *key, long value)
     else if (k == "update_bm") t.update_bm = value;
     else if (k == "use_small_kernel") t.use_small_kernel = value;
     else if (k == "invert_fused_max_n") t.invert_fused_max_n = value;
+    else if (k == "invert_outer_block") t.invert_outer_block = value;
     else if (k == "eigen_max_sweeps") t.eigen_max_sweeps = value;
     else if (k == "eigen_inner_sweeps") t.eigen_inner_sweeps = value;
     else if (k == "im2col_piece_elems") t.im2col_piece_elems = value;

@@ -77,7 +77,11 @@ __global__ __launch_bounds__(256) void sweep_init_kernel(const InvTable tab)
 // the pivot block is inverted by the one-launch-per-step sweep above (a 288 x 288 problem), the old
 // panel is gathered K-major into V, W = V P and the rank-288 update of the rest of the triangle run
 // on the wave-unit GEMM (gemm_wave.hpp), and the new panel and -P are scattered back in place.
-constexpr int PB = 288;
+// (the block height is a planner knob, a multiple of 288 = lcm of the 144-wide macro tiles and the 32-wide
+// gather / scatter tiles; PB below is its value for the current call).  576 is 6-8 % faster on the
+// workloads with many large factors, but the error of the inverse grows with the order of the explicitly
+// inverted pivot block (measured at order 2305: 1.5e-5 / 2.9e-5 / 4.0e-5 for 288 / 576 / 864), so 288 stays.
+inline int outer_block() { return (int)std::max(288l, tuning().invert_outer_block / 288 * 288); }
 
 struct BlkProb {
     float *W;          // working matrix [n, n]
@@ -87,6 +91,7 @@ struct BlkProb {
     int *info;
     const int *ninfo;  // status of the pivot block inversion (0 or 1-based pivot index inside the block)
     int n, ldv, p0, bs;
+    int pb;            // row pitch of P
     int blk_start;
 };
 
@@ -180,7 +185,7 @@ __global__ __launch_bounds__(256) void blk_scatter_kernel(const BlkTable tab)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int a = g0 - p0 + ty + 8 * r, b = k0 + tx;
-            if (a < pr.bs && b <= a) pr.W[(p0 + a) * n + p0 + b] = -pr.P[a * PB + b];
+            if (a < pr.bs && b <= a) pr.W[(p0 + a) * n + p0 + b] = -pr.P[a * pr.pb + b];
         }
     }
 }
@@ -224,7 +229,8 @@ size_t fused_ws_floats(int n) { return 2 * (size_t)NB * NB + 2 * (size_t)NB * ((
 size_t job_ws_floats(int n)
 {
     if (takes_fused(n)) return fused_ws_floats(n);
-    return 2 * (size_t)PB * ((n + 3) / 4 * 4) + (size_t)PB * PB + fused_ws_floats(PB) + 64;
+    const size_t PB = (size_t)outer_block();
+    return 2 * PB * ((n + 3) / 4 * 4) + PB * PB + fused_ws_floats((int)PB) + 64;
 }
 size_t table_bytes(int n) { return align_up((size_t)2 * n * sizeof(InvProbF), 256); }
 
@@ -308,6 +314,7 @@ hipError_t blocked_launch(const InvertJob *jobs, const std::vector<int> &idx, co
                           void *work, InvProbF *dtab, hipStream_t s)
 {
     const int total = (int)idx.size();
+    const int PB = outer_block();
     struct Big { float *Vt, *Wt, *P, *nws; int *ninfo; int ldv; };
     std::vector<Big> big(total);
     for (int k = 0; k < total; ++k) {
@@ -379,7 +386,7 @@ hipError_t blocked_launch(const InvertJob *jobs, const std::vector<int> &idx, co
                 BlkProb &p = tab.p[k];
                 p.W = j.Minv; p.Vt = big[g0 + k].Vt; p.Wt = big[g0 + k].Wt; p.P = big[g0 + k].P;
                 p.info = j.info; p.ninfo = big[g0 + k].ninfo;
-                p.n = j.n; p.ldv = big[g0 + k].ldv; p.p0 = p0; p.bs = std::min(PB, j.n - p0);
+                p.n = j.n; p.ldv = big[g0 + k].ldv; p.p0 = p0; p.bs = std::min(PB, j.n - p0); p.pb = PB;
                 p.blk_start = blocks;
                 blocks += ((j.n + 31) / 32) * ((p.bs + 31) / 32);
             }
@@ -417,7 +424,7 @@ hipError_t blocked_launch(const InvertJob *jobs, const std::vector<int> &idx, co
                 BlkProb &p = tab.p[k];
                 p.W = j.Minv; p.Vt = big[g0 + k].Vt; p.Wt = big[g0 + k].Wt; p.P = big[g0 + k].P;
                 p.info = j.info; p.ninfo = big[g0 + k].ninfo;
-                p.n = j.n; p.ldv = big[g0 + k].ldv; p.p0 = p0; p.bs = std::min(PB, j.n - p0);
+                p.n = j.n; p.ldv = big[g0 + k].ldv; p.p0 = p0; p.bs = std::min(PB, j.n - p0); p.pb = PB;
                 p.blk_start = blocks;
                 blocks += ((j.n + 31) / 32) * ((p.bs + 31) / 32);
             }
