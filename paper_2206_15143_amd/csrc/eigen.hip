@@ -26,7 +26,8 @@
 
 namespace kfac {
 
-constexpr int EB = 16;              // rows per block
+constexpr int EB = 16;              // rows per block (32 halves the rounds and the traffic, but the in-LDS sweep over
+                                    // the then 64 x 64 Gram matrix costs 8x more and the rounds become slower: measured)
 constexpr int kMaxEigClasses = 16;  // distinct orders per launch sequence
 
 struct EigProb {                    // init / final kernels: one entry per matrix
@@ -35,7 +36,7 @@ struct EigProb {                    // init / final kernels: one entry per matri
     float *v;
     int *info;
     float *Wt, *Vt;
-    float *scale;                   // [nb * 16] reciprocal row norms of V (final pass)
+    float *scale;                   // [nb * EB] reciprocal row norms of V (final pass)
     int *stamp;
     int n, ld, nb;
     int blk_start;
@@ -101,9 +102,10 @@ __device__ __forceinline__ void rr_pair(int m, int r, int k, int &a, int &b)
 
 __global__ __launch_bounds__(256) void eig_round_kernel(const EigSeq q)
 {
-    __shared__ float S[32][33];
-    __shared__ float R[32][33];
-    __shared__ float part_s[4][3][256];     // per-wavefront partial Gram tiles (summed in a fixed order)
+    constexpr int PR = 2 * EB;               // rows of a pair of blocks
+    constexpr int NG = PR / 16;              // 16-row groups of a pair
+    __shared__ float S[PR][PR + 1];
+    __shared__ float R[PR][PR + 1];
 
     int ci = 0;
     while (ci + 1 < q.nclass && (int)blockIdx.x >= q.c[ci + 1].blk_start) ++ci;
@@ -127,55 +129,73 @@ __global__ __launch_bounds__(256) void eig_round_kernel(const EigSeq q)
     const long ld = c.ld;
     float *Wt = c.Wt + (long)mat * c.stride;
     float *Vt = c.Vt + (long)mat * c.stride;
-    const float *wI = Wt + (long)(I * EB + r) * ld + 4 * kk;
-    const float *wJ = Wt + (long)(J * EB + r) * ld + 4 * kk;
+    // row of the pair -> row of the matrix: the first EB rows are block I, the rest block J
+    auto pair_row = [&](int pr) { return pr < EB ? I * EB + pr : J * EB + (pr - EB); };
 
-    // ---- 1. Gram matrix of the 32 rows: wavefront w takes the 16-column chunks w, w + 4, ... ----
+    // ---- 1. Gram matrix of the pair's rows: wavefront w takes the 16-column chunks w, w + 4, ...;
+    //         16 x 16 tiles of the lower triangle of the grid of row groups ----
     {
-        floatx4 s00 = {0.f, 0.f, 0.f, 0.f}, s10 = s00, s11 = s00;
-#pragma unroll 4
+        floatx4 acc[NG * (NG + 1) / 2];
+#pragma unroll
+        for (int t = 0; t < NG * (NG + 1) / 2; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+        const float *rowp[NG];
+#pragma unroll
+        for (int g = 0; g < NG; ++g) rowp[g] = Wt + (long)pair_row(16 * g + r) * ld + 4 * kk;
+#pragma unroll 2
         for (int k0 = 16 * w; k0 < c.ld; k0 += 64) {
-            const floatx4 x0 = *reinterpret_cast<const floatx4 *>(wI + k0);
-            floatx4 x1 = {0.f, 0.f, 0.f, 0.f};
-            if (hasJ) x1 = *reinterpret_cast<const floatx4 *>(wJ + k0);
+            floatx4 x[NG];
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                x[g] = floatx4{0.f, 0.f, 0.f, 0.f};
+                if (g < NG / 2 || hasJ) x[g] = *reinterpret_cast<const floatx4 *>(rowp[g] + k0);
+            }
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                s00 = __builtin_amdgcn_mfma_f32_16x16x4f32(x0[e], x0[e], s00, 0, 0, 0);
-                s10 = __builtin_amdgcn_mfma_f32_16x16x4f32(x1[e], x0[e], s10, 0, 0, 0);
-                s11 = __builtin_amdgcn_mfma_f32_16x16x4f32(x1[e], x1[e], s11, 0, 0, 0);
+                int t = 0;
+#pragma unroll
+                for (int gi = 0; gi < NG; ++gi)
+#pragma unroll
+                    for (int gj = 0; gj <= gi; ++gj, ++t)
+                        acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[gi][e], x[gj][e], acc[t], 0, 0, 0);
             }
         }
+        // the four wavefronts add their parts one after the other: a fixed order, no scratch tiles
+#pragma unroll 1
+        for (int ww = 0; ww < 4; ++ww) {
+            if (w == ww) {
+                int t = 0;
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {           // element (row 4 kk + v, column r) of each tile
-            part_s[w][0][(4 * kk + v) * 16 + r] = s00[v];
-            part_s[w][1][(4 * kk + v) * 16 + r] = s10[v];
-            part_s[w][2][(4 * kk + v) * 16 + r] = s11[v];
+                for (int gi = 0; gi < NG; ++gi)
+#pragma unroll
+                    for (int gj = 0; gj <= gi; ++gj, ++t)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const int row = 16 * gi + 4 * kk + v, col = 16 * gj + r;
+                            const float val = (ww == 0 ? 0.f : S[row][col]) + acc[t][v];
+                            S[row][col] = val;
+                        }
+            }
+            __syncthreads();
         }
     }
-    for (int e = tid; e < 32 * 32; e += 256) R[e >> 5][e & 31] = ((e >> 5) == (e & 31)) ? 1.f : 0.f;
-    __syncthreads();
-    {
-        const int row = tid >> 4, col = tid & 15;
-        float t3[3];
-#pragma unroll
-        for (int k = 0; k < 3; ++k)
-            t3[k] = ((part_s[0][k][tid] + part_s[1][k][tid]) + part_s[2][k][tid]) + part_s[3][k][tid];
-        S[row][col] = t3[0];
-        S[16 + row][col] = t3[1];
-        S[col][16 + row] = t3[1];
-        S[16 + row][16 + col] = t3[2];
+    // mirror the strictly lower tiles, R = I
+    for (int e = tid; e < PR * PR; e += 256) {
+        const int row = e / PR, col = e - row * PR;
+        if ((col >> 4) > (row >> 4)) S[row][col] = S[col][row];
+        R[row][col] = (row == col) ? 1.f : 0.f;
     }
     __syncthreads();
 
-    // ---- 2. two-sided cyclic Jacobi on S; thread (pair = tid & 15, part = tid >> 4) moves 2 elements ----
-    const int pr_ = tid & 15, part = tid >> 4;
+    // ---- 2. two-sided cyclic Jacobi on S; thread (pair = tid % EB, part = tid / EB) moves PE elements ----
+    const int pr_ = tid & (PR / 2 - 1), part = tid / (PR / 2);
+    constexpr int PE = PR / (256 / (PR / 2));   // elements per thread and phase
     bool active = false;
     for (int sw = 0; sw < q.inner_sweeps; ++sw) {
         bool any = false;
 #pragma unroll 1
-        for (int rd = 0; rd < 31; ++rd) {
+        for (int rd = 0; rd < PR - 1; ++rd) {
             int p, qq;
-            rr_pair(32, rd, pr_, p, qq);
+            rr_pair(PR, rd, pr_, p, qq);
             if (p > qq) { const int t = p; p = qq; qq = t; }
             const float app = S[p][p], aqq = S[qq][qq], apq = S[p][qq];
             float cs = 1.f, sn = 0.f;
@@ -194,16 +214,16 @@ __global__ __launch_bounds__(256) void eig_round_kernel(const EigSeq q)
             __syncthreads();                    // every thread has read its pivots before anything moves
             // columns p, q of S and of R:  S <- S J,  R <- R J   (all loads first: they pipeline)
             {
-                float sp[2], sq[2], rp[2], rq[2];
+                float sp[PE], sq[PE], rp[PE], rq[PE];
 #pragma unroll
-                for (int e = 0; e < 2; ++e) {
-                    const int i = part * 2 + e;
+                for (int e = 0; e < PE; ++e) {
+                    const int i = part * PE + e;
                     sp[e] = S[i][p]; sq[e] = S[i][qq];
                     rp[e] = R[i][p]; rq[e] = R[i][qq];
                 }
 #pragma unroll
-                for (int e = 0; e < 2; ++e) {
-                    const int i = part * 2 + e;
+                for (int e = 0; e < PE; ++e) {
+                    const int i = part * PE + e;
                     S[i][p] = cs * sp[e] - sn * sq[e];
                     S[i][qq] = sn * sp[e] + cs * sq[e];
                     R[i][p] = cs * rp[e] - sn * rq[e];
@@ -213,15 +233,15 @@ __global__ __launch_bounds__(256) void eig_round_kernel(const EigSeq q)
             __syncthreads();
             // rows p, q of S:  S <- J^T S
             {
-                float sp[2], sq[2];
+                float sp[PE], sq[PE];
 #pragma unroll
-                for (int e = 0; e < 2; ++e) {
-                    const int j = part * 2 + e;
+                for (int e = 0; e < PE; ++e) {
+                    const int j = part * PE + e;
                     sp[e] = S[p][j]; sq[e] = S[qq][j];
                 }
 #pragma unroll
-                for (int e = 0; e < 2; ++e) {
-                    const int j = part * 2 + e;
+                for (int e = 0; e < PE; ++e) {
+                    const int j = part * PE + e;
                     S[p][j] = cs * sp[e] - sn * sq[e];
                     S[qq][j] = sn * sp[e] + cs * sq[e];
                 }
@@ -234,49 +254,49 @@ __global__ __launch_bounds__(256) void eig_round_kernel(const EigSeq q)
     if (!active) return;                        // R is the identity: nothing to apply
     if (tid == 0) atomicMax(c.stamp + mat, q.t + 1);
 
-    // ---- 3. rows <- R^T rows, for W and V; wavefront w takes the 64-column groups w, w + 4, ... ----
-    float a[2][8];
+    // ---- 3. rows <- R^T rows, for W and V; wavefront w takes the 32-column groups w, w + 4, ... ----
+    float a[NG][PR / 4];
 #pragma unroll
-    for (int it = 0; it < 2; ++it)
+    for (int it = 0; it < NG; ++it)
 #pragma unroll
-        for (int s = 0; s < 8; ++s) a[it][s] = R[4 * s + kk][16 * it + r];
+        for (int s = 0; s < PR / 4; ++s) a[it][s] = R[4 * s + kk][16 * it + r];
 #pragma unroll 1
     for (int which = 0; which < 2; ++which) {
         float *X = which == 0 ? Wt : Vt;
-        float *xI = X + (long)(I * EB) * ld;
-        float *xJ = X + (long)(J * EB) * ld;
-        // four 16-column chunks at a time: 32 loads in flight, then the products, then the stores
-        for (int k0 = 64 * w; k0 < c.ld; k0 += 256) {
-            float b[4][8];
+        // two 16-column chunks at a time: 32 loads in flight, then the products, then the stores
+        for (int k0 = 32 * w; k0 < c.ld; k0 += 128) {
+            float b[2][PR / 4];
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
+            for (int g = 0; g < 2; ++g) {
                 const int kc = k0 + 16 * g + r;
                 const bool in = k0 + 16 * g < c.ld;
 #pragma unroll
-                for (int s = 0; s < 4; ++s) b[g][s] = in ? xI[(long)(4 * s + kk) * ld + kc] : 0.f;
-#pragma unroll
-                for (int s = 4; s < 8; ++s) b[g][s] = (in && hasJ) ? xJ[(long)(4 * (s - 4) + kk) * ld + kc] : 0.f;
-            }
-            floatx4 d0[4], d1[4];
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                d0[g] = floatx4{0.f, 0.f, 0.f, 0.f};
-                d1[g] = d0[g];
-#pragma unroll
-                for (int s = 0; s < 8; ++s) {
-                    d0[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0][s], b[g][s], d0[g], 0, 0, 0);
-                    d1[g] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1][s], b[g][s], d1[g], 0, 0, 0);
+                for (int s = 0; s < PR / 4; ++s) {
+                    const int pr = 4 * s + kk;
+                    b[g][s] = (in && (pr < EB || hasJ)) ? X[(long)pair_row(pr) * ld + kc] : 0.f;
                 }
             }
+            floatx4 d[2][NG];
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
+            for (int g = 0; g < 2; ++g)
+#pragma unroll
+                for (int it = 0; it < NG; ++it) {
+                    d[g][it] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int s = 0; s < PR / 4; ++s)
+                        d[g][it] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[it][s], b[g][s], d[g][it], 0, 0, 0);
+                }
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {
                 if (k0 + 16 * g >= c.ld) break;
                 const int kc = k0 + 16 * g + r;
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    xI[(long)(4 * kk + v) * ld + kc] = d0[g][v];
-                    if (hasJ) xJ[(long)(4 * kk + v) * ld + kc] = d1[g][v];
-                }
+                for (int it = 0; it < NG; ++it)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int pr = 16 * it + 4 * kk + v;
+                        if (pr < EB || hasJ) X[(long)pair_row(pr) * ld + kc] = d[g][it][v];
+                    }
             }
         }
     }
