@@ -259,7 +259,7 @@ def main():
     # the HIP-event time of its launches; the roofline object is the one with the largest share of time
     names = {"syrk_partial": "syrk_partial_kernel", "syrk_wave": "syrk_wave_kernel",
              "syrk_conv3": "syrk_conv3_kernel", "syrk_small": "syrk_small_nchw_kernel",
-             "syrk_bf16": "syrk_bf16_kernel"}
+             "syrk_bf16": "syrk_bf16_kernel", "syrk_corr3": "corr3_main_kernel"}
     per_kernel = {}
     for k, kname in names.items():
         ms, n, flops = cls[k]

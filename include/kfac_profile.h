@@ -31,7 +31,9 @@ enum {
     KFAC_K_EIG_INIT = 14,    /* eigen-decomposition: working copies W = M, V = I */
     KFAC_K_EIG_ROUND = 15,   /* eigen-decomposition: one round of the block Jacobi sweep */
     KFAC_K_EIG_FINAL = 16,   /* eigen-decomposition: eigenvalues and Q = V^T; transposes for Eq. 13 */
-    KFAC_K_COUNT = 17
+    KFAC_K_SYRK_CORR3 = 17,  /* KF-GEMM of 3x3 convolutions from input autocorrelations (lag matrices) */
+    KFAC_K_CORR3_ASM = 18,   /* border terms, sums and assembly (+ running average) of that path */
+    KFAC_K_COUNT = 19
 };
 
 /* When enabled, every kernel launch is bracketed by a pair of HIP events

@@ -169,7 +169,7 @@ def kfac_tune(key: str, value: int) -> None:
         raise KeyError(key)
 
 
-KFAC_K_COUNT = 17
+KFAC_K_COUNT = 19
 
 
 def kfac_profile_copy(dst, src, nbytes: int, stream=None) -> None:

@@ -742,7 +742,8 @@ const char *kfac_timing_class_name(int cls)
     static const char *names[KFAC_K_COUNT] = {"im2col", "syrk_partial", "syrk_reduce", "inv_init",
                                               "inv_pivot", "inv_panel", "inv_finish", "gemm_tn",
                                               "syrk_wave", "syrk_conv3", "syrk_small", "inv_step",
-                                              "syrk_bf16", "gemm_wave", "eig_init", "eig_round", "eig_final"};
+                                              "syrk_bf16", "gemm_wave", "eig_init", "eig_round", "eig_final",
+                                              "syrk_corr3", "corr3_assemble"};
     return (cls >= 0 && cls < KFAC_K_COUNT) ? names[cls] : "?";
 }
 
@@ -780,6 +781,7 @@ int kfac_tune(const char *key, long value)
     else if (k == "update_bm") t.update_bm = value;
     else if (k == "use_small_kernel") t.use_small_kernel = value;
     else if (k == "invert_fused_max_n") t.invert_fused_max_n = value;
+    else if (k == "use_corr3") t.use_corr3 = value;
     else if (k == "invert_outer_block") t.invert_outer_block = value;
     else if (k == "eigen_max_sweeps") t.eigen_max_sweeps = value;
     else if (k == "eigen_inner_sweeps") t.eigen_inner_sweeps = value;

@@ -27,6 +27,7 @@
 
 #include "syrk_wave.hpp"
 #include "syrk_conv3.hpp"
+#include "syrk_corr3.hpp"
 #include "syrk_small.hpp"
 #include "syrk_bf16.hpp"
 
@@ -294,8 +295,9 @@ namespace {
 struct Cfg { int wt, nw, bm; };
 // the last entry is the wave-unit kernel (syrk_wave.hpp): 144-wide macro tiles, same partial layout as Tile<3,3>
 const Cfg kCfgs[] = {{4, 2, 128}, {3, 3, 144}, {2, 2, 64}, {1, 2, 32}, {0, 0, 144}, {0, 0, 144}, {0, 0, 32}, {0, 0, 64},
-                     {0, 0, 256}, {0, 0, 144}};
+                     {0, 0, 256}, {0, 0, 144}, {0, 0, 16}, {0, 0, 16}, {0, 0, 16}};
 constexpr int kWaveCfg = 4;
+constexpr int kCorr3Cfg = 10;  // 3x3 convolution factors from autocorrelations (syrk_corr3.hpp): 10 / 11 / 12 = 16 / 32 / 64 channels
 constexpr int kConv3Cfg = 5;   // fused 3x3 convolution kernel (syrk_conv3.hpp), same partial layout
 constexpr int kSmall32Cfg = 6; // narrow NCHW operands (syrk_small.hpp), partial tile 32 x 32 (d <= 32)
 constexpr int kSmall64Cfg = 7; // same, 64 x 64 (d <= 64)
@@ -370,6 +372,36 @@ int choose_cfg(int d)
     return best;
 }
 
+// Strip height of the autocorrelation kernel: the largest divisor of H whose two slabs fit 72 KB of LDS and
+// whose slab is at most 12 float4 items per thread (0 = not eligible).  plane = floats per channel, padded
+// so that consecutive channels start 4 banks apart.
+int corr3_rows(int C, int H, int W, int *plane_out)
+{
+    int best = 0;
+    for (int SR = 1; SR <= H; ++SR) {
+        if (H % SR) continue;
+        int plane = (SR + 2) * (W + 4);
+        plane += (4 - plane % 32 + 32) % 32;
+        const long bytes = 2l * C * plane * 4;
+        const long items = (long)C * (SR + 2) * (W / 4);
+        if (bytes > 72 * 1024 || items > 12 * 256) continue;
+        best = SR;
+        if (plane_out) *plane_out = plane;
+    }
+    return best;
+}
+
+bool corr3_eligible(const FactorJob &j)
+{
+    if (!(tuning().use_corr3 && j.layout == kConv3 && j.dtype == 0)) return false;
+    if (!(j.ctot == 16 || j.ctot == 32 || j.ctot == 64)) return false;
+    if (j.w % 4 != 0 || j.w > 64 || j.h > 64 || j.h < 2) return false;
+    const long B = j.K / j.hw;
+    if (B < 1 || B > 4 * 64) return false;                     // corners: a chunk of images is one LDS line
+    if ((long)B * j.ctot * j.hw * 4 >= 0x7fffffffl) return false;
+    return corr3_rows(j.ctot, j.h, j.w, nullptr) > 0;
+}
+
 struct Planned {
     int cfg;
     int nb, nblk, splits, tps;
@@ -383,6 +415,26 @@ struct Planned {
 void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<Planned> &pl)
 {
     const Tuning &tu = tuning();
+    if (pl[idx[0]].cfg >= kCorr3Cfg) {
+        // autocorrelation kernel: (image, strip) units dealt evenly to about target_blocks workgroups
+        const long per = std::max<long>(1, tu.target_blocks / (long)idx.size());
+        for (int j : idx) {
+            Planned &p = pl[j];
+            const FactorJob &job = jobs[j];
+            const int C = job.ctot;
+            int plane = 0;
+            p.rows_per_stage = corr3_rows(C, job.h, job.w, &plane);
+            p.unit_rows = plane;                                   // carried to the launch
+            const long units = (job.K / job.hw) * (job.h / p.rows_per_stage);
+            p.tps = (int)std::max<long>(1, (units + per - 1) / per);       // units per block
+            p.splits = (int)((units + p.tps - 1) / p.tps);
+            p.nb = 1; p.nblk = 1; p.bps = 1;
+            const size_t parts = (size_t)p.splits * (C == 16 ? 4 : 1);
+            const size_t nF = (size_t)C3_LAGS * C * C, nB = (size_t)C3_BQ * C * C + (size_t)C3_BV * C;
+            p.partial_floats = parts * (nF + C) + (nF + C) + (size_t)C3_CHUNKS * nB + nB + 64;
+        }
+        return;
+    }
     double work = 0;
     for (int j : idx) {
         Planned &p = pl[j];
@@ -453,7 +505,8 @@ void plan_all(const FactorJob *jobs, int n, std::vector<Planned> &pl, std::vecto
     pl.assign(n, Planned());
     std::vector<int> keys(n);
     for (int i = 0; i < n; ++i) {
-        if (jobs[i].layout == kConv3) pl[i].cfg = kConv3Cfg;
+        if (corr3_eligible(jobs[i])) pl[i].cfg = kCorr3Cfg + (jobs[i].ctot == 16 ? 0 : (jobs[i].ctot == 32 ? 1 : 2));
+        else if (jobs[i].layout == kConv3) pl[i].cfg = kConv3Cfg;
         else if (small_eligible(jobs[i])) pl[i].cfg = jobs[i].d_core <= 32 ? kSmall32Cfg : kSmall64Cfg;
         else if (bf16_eligible(jobs[i])) pl[i].cfg = kBf16Cfg;
         else if (wave_nchw_eligible(jobs[i])) pl[i].cfg = kWaveNchwCfg;
@@ -461,7 +514,7 @@ void plan_all(const FactorJob *jobs, int n, std::vector<Planned> &pl, std::vecto
         keys[i] = group_key(jobs[i], pl[i].cfg);
     }
     groups.clear();
-    for (int key = 0; key < 40; ++key) {
+    for (int key = 0; key < 56; ++key) {
         std::vector<int> cur;
         for (int i = 0; i < n; ++i) {
             if (keys[i] != key) continue;
@@ -503,6 +556,100 @@ hipError_t launch_ld(const SyrkTable &tab, int layout, int dt, int blocks, int r
     }
     if (dt == 0) return launch_cfg<T, kNCHW, 0>(tab, blocks, red_blocks, flops, red_bytes, s);
     return launch_cfg<T, kNCHW, 1>(tab, blocks, red_blocks, flops, red_bytes, s);
+}
+
+}  // namespace
+
+namespace {
+
+template <int NT>
+hipError_t corr3_launch_nt(CorrTable &tab, const std::vector<size_t> &lds, double flops, hipStream_t s)
+{
+    // main kernel
+    int blocks = 0;
+    size_t lds_bytes = 0;
+    for (int k = 0; k < tab.count; ++k) {
+        tab.p[k].blk_start = blocks;
+        blocks += tab.p[k].splits;
+        lds_bytes = std::max(lds_bytes, lds[k]);
+    }
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&corr3_main_kernel<NT>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    KFAC_LAUNCH(KFAC_K_SYRK_CORR3, s, (corr3_main_kernel<NT>), dim3(blocks), dim3(256), lds_bytes, tab);
+    timing_work(flops);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    // border terms: 5 sides x image chunks per layer
+    blocks = 0;
+    for (int k = 0; k < tab.count; ++k) {
+        tab.p[k].blk_start = blocks;
+        blocks += 5 * C3_CHUNKS;
+    }
+    KFAC_LAUNCH(KFAC_K_CORR3_ASM, s, (corr3_border_kernel<NT>), dim3(blocks), dim3(256), 0, tab);
+    return hipGetLastError();
+}
+
+hipError_t corr3_launch(const FactorJob *jobs, const std::vector<int> &g, const std::vector<Planned> &pl,
+                        const std::vector<size_t> &offs, void *work, double flops, hipStream_t s)
+{
+    CorrTable tab;
+    tab.count = (int)g.size();
+    std::vector<size_t> lds(g.size());
+    for (int k = 0; k < tab.count; ++k) {
+        const int j = g[k];
+        const FactorJob &job = jobs[j];
+        const Planned &P = pl[j];
+        CorrProb &p = tab.p[k];
+        const int C = job.ctot;
+        const size_t nF = (size_t)C3_LAGS * C * C, nB = (size_t)C3_BQ * C * C + (size_t)C3_BV * C;
+        p.x = static_cast<const float *>(job.x);
+        p.C = C; p.H = job.h; p.W = job.w; p.B = (int)(job.K / job.hw);
+        p.SR = P.rows_per_stage; p.strips = job.h / P.rows_per_stage;
+        p.units = p.B * p.strips;
+        p.splits = P.splits; p.upb = P.tps;
+        p.parts = P.splits * (C == 16 ? 4 : 1);
+        p.plane = P.unit_rows;
+        p.has_bias = job.has_bias; p.scale = job.scale; p.decay = job.decay;
+        p.F = job.F;
+        float *base = reinterpret_cast<float *>(static_cast<char *>(work) + offs[j]);
+        p.Fp = base;
+        p.Fs = p.Fp + (size_t)p.parts * (nF + C);
+        p.Bp = p.Fs + (nF + C);
+        p.Bs = p.Bp + (size_t)C3_CHUNKS * nB;
+        p.blk_start = 0;
+        lds[k] = (size_t)2 * C * p.plane * sizeof(float);
+    }
+    const int cfg = pl[g[0]].cfg;
+    hipError_t e = cfg == kCorr3Cfg ? corr3_launch_nt<1>(tab, lds, flops, s)
+                 : cfg == kCorr3Cfg + 1 ? corr3_launch_nt<2>(tab, lds, flops, s)
+                                        : corr3_launch_nt<4>(tab, lds, flops, s);
+    if (e != hipSuccess) return e;
+    // sums over parts and chunks
+    int blocks = 0;
+    for (int k = 0; k < tab.count; ++k) {
+        const CorrProb &p = tab.p[k];
+        tab.p[k].blk_start = blocks;
+        const long total = (long)(C3_LAGS + C3_BQ) * p.C * p.C + (long)(1 + C3_BV) * p.C;
+        blocks += (int)((total + 255) / 256);
+    }
+    KFAC_LAUNCH(KFAC_K_CORR3_ASM, s, corr3_sum_kernel, dim3(blocks), dim3(256), 0, tab);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    // assembly, scale, running average
+    blocks = 0;
+    for (int k = 0; k < tab.count; ++k) {
+        const CorrProb &p = tab.p[k];
+        tab.p[k].blk_start = blocks;
+        const int nt = (9 * p.C + p.has_bias + 15) / 16;
+        blocks += nt * (nt + 1) / 2;
+    }
+    KFAC_LAUNCH(KFAC_K_CORR3_ASM, s, corr3_assemble_kernel, dim3(blocks), dim3(256), 0, tab);
+    return hipGetLastError();
 }
 
 }  // namespace
@@ -575,6 +722,11 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
         const int cfg = pl[g[0]].cfg;
         const int layout = jobs[g[0]].layout, dt = jobs[g[0]].dtype;
         hipError_t e = hipSuccess;
+        if (cfg >= kCorr3Cfg) {
+            e = corr3_launch(jobs, g, pl, offs, work, flops, s);
+            if (e != hipSuccess) return e;
+            continue;
+        }
         switch (cfg) {
             case kConv3Cfg: {
                 size_t lds_bytes = 0;

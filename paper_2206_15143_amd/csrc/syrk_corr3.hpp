@@ -1,0 +1,415 @@
+// A factor of a 3x3 / stride 1 / pad 1 convolution from spatial autocorrelations of its input.
+//
+// With zero padding, entry ((c,i,j), (c',i',j')) of  A = sum over patches of  a a^T  (Eq. 4 of the DP-KFAC
+// paper, the convolution seen as a linear map over patches) is
+//     sum_n sum_{a in Ra(i)} sum_{b in Rb(j)}  x[n,c,a,b] * x[n,c',a+di,b+dj],      (di, dj) = (i'-i, j'-j),
+// where x is 0 outside the image and Ra(0) = [0,H-2], Ra(1) = [0,H-1], Ra(2) = [1,H-1] (likewise Rb).  The sum
+// over ALL (a,b) depends on (di,dj) only: the autocorrelation F(di,dj)[c][c'] of the input at one of 25 lags,
+// of which 13 are independent (F(-d)[c][c'] = F(d)[c'][c]).  What the window removes is a single image row
+// (for i = 0 or 2) and/or a single column (j = 0 or 2), and such a term is non-zero only when the partner
+// lands in the same row (i' = i) resp. column (j' = j):
+//     A = F(d) - [i'=i in {0,2}] Row(a*, dj) - [j'=j in {0,2}] Col(b*, di) + [both] Corner(a*, b*),
+// with a* = H-1 for i = 0 and 0 for i = 2 (b* likewise), Row / Col the 1-D autocorrelations of that border
+// row / column and Corner the outer product of the corner pixel.  The bias border (column sums of the patch
+// matrix) follows the same inclusion-exclusion on plain sums.  The result is the same matrix as the direct
+// sum (up to rounding order) for 13 instead of 45 MFMA tiles per 16 x 16 channel pair and k-step.
+//
+// Three steps: corr3_main_kernel (the 13 lag matrices, split over images, on the MFMA units),
+// corr3_border_kernel (rows, columns, corners; MFMA as well, K = border pixels), corr3_sum_kernel +
+// corr3_assemble_kernel (sum of the splits, assembly of A with scale and running average, both triangles).
+#pragma once
+
+#include "common.hpp"
+#include "tn_engine.hpp"
+
+namespace kfac {
+
+constexpr int C3_LAGS = 13;
+constexpr int C3_BQ = 16;          // border matrices per layer: 6 row, 6 column, 4 corner
+constexpr int C3_BV = 8;           // border vectors per layer: 2 row sums, 2 column sums, 4 corner sums
+constexpr int C3_CHUNKS = 4;       // image chunks of the border kernel
+
+struct CorrProb {
+    const float *x;    // NCHW input [B, C, H, W]
+    float *Fp;         // [parts][13][C][C] lag matrices per part, then [parts][C] channel sums per part
+    float *Fs;         // [13][C][C] + [C]: summed over the parts
+    float *Bp;         // [chunks][16][C][C], then [chunks][8][C]
+    float *Bs;         // [16][C][C] + [8][C]: summed over the chunks
+    float *F;          // factor [dF, dF], dF = 9 C + has_bias
+    int C, H, W, B;
+    int SR, strips;    // rows per strip, strips per image
+    int units;         // B * strips
+    int splits, upb;   // blocks of the main kernel, units per block
+    int parts;         // splits * (wavefronts that split the k-steps)
+    int plane;         // floats per channel plane of a slab
+    int blk_start;     // first block of this problem in the kernel at hand
+    int has_bias;
+    float scale, decay;
+};
+
+struct CorrTable {
+    int count;
+    CorrProb p[kMaxProblems];
+};
+
+__device__ __forceinline__ int corr_locate(const CorrTable &tab, int blk)
+{
+    int pi = 0;
+    while (pi + 1 < tab.count && blk >= tab.p[pi + 1].blk_start) ++pi;
+    return pi;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Lag matrices.  A workgroup walks (image, strip) units: the strip of all C channels with two halo rows below
+// and two zero columns left and right is staged in LDS (double buffered, the next unit's global loads in
+// flight under the products); a k-step is four consecutive pixels of a row; the A operand is channel tile ct
+// at those pixels, the B operand channel tile ct' at the pixels shifted by the lag.
+//   NT = 1 (C = 16): one tile pair; the four wavefronts take every fourth k-step (four parts per block).
+//   NT = 2 (C = 32): four tile pairs, one per wavefront.     NT = 4 (C = 64): wavefront w = A tile w, all four B tiles.
+template <int NT>
+__global__ __launch_bounds__(256) void corr3_main_kernel(const CorrTable tab)
+{
+    extern __shared__ __align__(16) float corr_lds[];
+    constexpr int C = 16 * NT;
+    constexpr int KS = NT == 1 ? 4 : 1;
+    constexpr int PW = NT == 4 ? 4 : 1;
+    constexpr int MAXI = 12;                   // float4 items per thread and slab at most (checked by the planner)
+
+    const CorrProb &pr = tab.p[corr_locate(tab, blockIdx.x)];
+    const int blk = blockIdx.x - pr.blk_start;
+    const int u0 = blk * pr.upb, u1 = min(pr.units, u0 + pr.upb);
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int lr = lane & 15, kk = lane >> 4;
+    const int H = pr.H, W = pr.W, Wp = W + 4, SR = pr.SR, plane = pr.plane, w4 = W >> 2;
+    float *buf0 = corr_lds, *buf1 = corr_lds + C * plane;
+
+    for (int i = tid; i < 2 * C * plane; i += 256) corr_lds[i] = 0.f;   // the pad cells are never written again
+    __syncthreads();
+
+    int ct, ctp0;
+    if (NT == 1) { ct = 0; ctp0 = 0; }
+    else if (NT == 2) { ct = w >> 1; ctp0 = w & 1; }
+    else { ct = w; ctp0 = 0; }
+
+    floatx4 acc[PW][C3_LAGS];
+#pragma unroll
+    for (int p = 0; p < PW; ++p)
+#pragma unroll
+        for (int l = 0; l < C3_LAGS; ++l) acc[p][l] = floatx4{0.f, 0.f, 0.f, 0.f};
+    float tsum = 0.f;
+
+    int dl[C3_LAGS];                            // slab offset of each lag: (0,0..2), (1,-2..2), (2,-2..2)
+#pragma unroll
+    for (int l = 0; l < C3_LAGS; ++l) {
+        const int di = l < 3 ? 0 : (l < 8 ? 1 : 2);
+        const int dj = l < 3 ? l : (l < 8 ? l - 5 : l - 10);
+        dl[l] = di * Wp + dj;
+    }
+
+    const int rows = SR + 2;
+    const int items = C * rows * w4;
+    floatx4 regs[MAXI];
+    auto fetch = [&](int u) {
+        const int n = u / pr.strips, a0 = (u - n * pr.strips) * SR;
+        const float *img = pr.x + (long)n * C * H * W;
+#pragma unroll
+        for (int k = 0; k < MAXI; ++k) {
+            const int e = tid + 256 * k;
+            floatx4 v = {0.f, 0.f, 0.f, 0.f};
+            if (e < items) {
+                const int c = e / (rows * w4), rem = e - c * (rows * w4);
+                const int r = rem / w4, g = rem - r * w4;
+                const int a = a0 + r;
+                if (a < H) v = *reinterpret_cast<const floatx4 *>(img + ((long)c * H + a) * W + 4 * g);
+            }
+            regs[k] = v;
+        }
+    };
+    auto commit = [&](float *b) {
+#pragma unroll
+        for (int k = 0; k < MAXI; ++k) {
+            const int e = tid + 256 * k;
+            if (e < items) {
+                const int c = e / (rows * w4), rem = e - c * (rows * w4);
+                const int r = rem / w4, g = rem - r * w4;
+                float *d = b + c * plane + r * Wp + 2 + 4 * g;      // 8-byte aligned
+                *reinterpret_cast<float2 *>(d) = float2{regs[k].x, regs[k].y};
+                *reinterpret_cast<float2 *>(d + 2) = float2{regs[k].z, regs[k].w};
+            }
+        }
+    };
+
+    if (u0 < u1) fetch(u0);
+    for (int u = u0; u < u1; ++u) {
+        float *b = ((u - u0) & 1) ? buf1 : buf0;
+        commit(b);
+        __syncthreads();        // a wavefront gets here only after its products on the other buffer: one barrier per unit
+        if (u + 1 < u1) fetch(u + 1);
+        const float *pa = b + (16 * ct + lr) * plane + 2 + kk;
+        const float *pb[PW];
+#pragma unroll
+        for (int p = 0; p < PW; ++p) pb[p] = b + (16 * (ctp0 + p) + lr) * plane + 2 + kk;
+        int cnt = 0;
+        for (int r = 0; r < SR; ++r) {
+#pragma unroll 2
+            for (int g = 0; g < w4; ++g, ++cnt) {
+                if (KS == 4 && (cnt & 3) != w) continue;
+                const int off = r * Wp + 4 * g;
+                const float a = pa[off];
+                tsum += a;
+#pragma unroll
+                for (int p = 0; p < PW; ++p)
+#pragma unroll
+                    for (int l = 0; l < C3_LAGS; ++l)
+                        acc[p][l] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, pb[p][off + dl[l]], acc[p][l], 0, 0, 0);
+            }
+        }
+    }
+
+    // channel sums: the four k-lanes of a channel
+    tsum += __shfl_xor(tsum, 16);
+    tsum += __shfl_xor(tsum, 32);
+    const int part = blk * KS + (KS == 4 ? w : 0);
+    float *Fo = pr.Fp + (long)part * (C3_LAGS * C * C);
+#pragma unroll
+    for (int p = 0; p < PW; ++p)
+#pragma unroll
+        for (int l = 0; l < C3_LAGS; ++l)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                Fo[(l * C + 16 * ct + 4 * kk + v) * C + 16 * (ctp0 + p) + lr] = acc[p][l][v];
+    if ((NT != 2 || ctp0 == 0) && kk == 0)
+        pr.Fp[(long)pr.parts * (C3_LAGS * C * C) + (long)part * C + 16 * ct + lr] = tsum;
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Border terms.  One workgroup per (layer, side, image chunk); side 0 / 1 = image row 0 / H-1, 2 / 3 = column
+// 0 / W-1, 4 = the four corners.  For a row or column: per image the line [C][L] (+2 zero cells) is staged in
+// LDS, a k-step is four consecutive pixels of the line, lags 0, 1, 2.  Corners: the "line" of a corner is its
+// value in the images of the chunk (k runs over images), lag 0 only.
+// Wavefront w takes the channel-tile pairs w, w + 4, ...
+template <int NT>
+__global__ __launch_bounds__(256) void corr3_border_kernel(const CorrTable tab)
+{
+    constexpr int C = 16 * NT;
+    constexpr int NP = NT * NT;                       // tile pairs
+    constexpr int PPW = (NP + 3) / 4;                 // pairs per wavefront
+    constexpr int LMAX = 64 + 4;
+    __shared__ float line[C * LMAX];
+
+    const CorrProb &pr = tab.p[corr_locate(tab, blockIdx.x)];
+    const int local = blockIdx.x - pr.blk_start;
+    const int side = local / C3_CHUNKS, ch = local - side * C3_CHUNKS;
+    const int per = (pr.B + C3_CHUNKS - 1) / C3_CHUNKS;
+    const int n0 = ch * per, n1 = min(pr.B, n0 + per);
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int lr = lane & 15, kk = lane >> 4;
+    const int H = pr.H, W = pr.W;
+    float *Bm = pr.Bp + (long)ch * (C3_BQ * C * C);
+    float *Bv = pr.Bp + (long)C3_CHUNKS * (C3_BQ * C * C) + (long)ch * (C3_BV * C);
+
+    if (side < 4) {
+        const bool is_row = side < 2;
+        const int L = is_row ? W : H;                 // line length (a multiple of 4 for rows; any for columns)
+        const int Lp = L + 4;                         // k-steps may run up to 3 cells past the line, lags 2 more... zero
+        const int fixed = (side & 1) ? (is_row ? H - 1 : W - 1) : 0;
+        for (int i = tid; i < C * LMAX; i += 256) line[i] = 0.f;
+        floatx4 acc[PPW][3];
+#pragma unroll
+        for (int p = 0; p < PPW; ++p)
+#pragma unroll
+            for (int l = 0; l < 3; ++l) acc[p][l] = floatx4{0.f, 0.f, 0.f, 0.f};
+        float vs[PPW];
+#pragma unroll
+        for (int p = 0; p < PPW; ++p) vs[p] = 0.f;
+        const int nks = (L + 3) / 4;
+        for (int n = n0; n < n1; ++n) {
+            __syncthreads();
+            const float *img = pr.x + (long)n * C * H * W;
+            for (int i = tid; i < C * L; i += 256) {
+                const int c = i / L, p = i - c * L;
+                line[c * LMAX + p] = is_row ? img[((long)c * H + fixed) * W + p] : img[((long)c * H + p) * W + fixed];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int p = 0; p < PPW; ++p) {
+                const int pair = w + 4 * p;
+                if (pair >= NP) continue;
+                const int ct = pair / NT, ctp = pair - ct * NT;
+                const float *pa = line + (16 * ct + lr) * LMAX + kk;
+                const float *pb = line + (16 * ctp + lr) * LMAX + kk;
+                for (int ks = 0; ks < nks; ++ks) {
+                    const float a = pa[4 * ks];
+                    if (ctp == 0) vs[p] += a;
+#pragma unroll
+                    for (int l = 0; l < 3; ++l)
+                        acc[p][l] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, pb[4 * ks + l], acc[p][l], 0, 0, 0);
+                }
+            }
+        }
+        (void)Lp;
+#pragma unroll
+        for (int p = 0; p < PPW; ++p) {
+            const int pair = w + 4 * p;
+            if (pair >= NP) continue;
+            const int ct = pair / NT, ctp = pair - ct * NT;
+#pragma unroll
+            for (int l = 0; l < 3; ++l)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    Bm[((3 * side + l) * C + 16 * ct + 4 * kk + v) * C + 16 * ctp + lr] = acc[p][l][v];
+            float s = vs[p];
+            s += __shfl_xor(s, 16);
+            s += __shfl_xor(s, 32);
+            if (ctp == 0 && kk == 0) Bv[side * C + 16 * ct + lr] = s;
+        }
+    } else {
+        // corners: line[q][c][k] = value of corner q of channel c in image n0 + k
+        const int nimg = n1 - n0;                     // at most LMAX - 4 (checked by the planner)
+        floatx4 acc[PPW][4];
+#pragma unroll
+        for (int p = 0; p < PPW; ++p)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc[p][q] = floatx4{0.f, 0.f, 0.f, 0.f};
+        float vs[PPW][4];
+#pragma unroll
+        for (int p = 0; p < PPW; ++p)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) vs[p][q] = 0.f;
+        const int nks = (nimg + 3) / 4;
+        for (int q = 0; q < 4; ++q) {
+            const int a = (q & 2) ? H - 1 : 0, b = (q & 1) ? W - 1 : 0;
+            __syncthreads();
+            for (int i = tid; i < C * LMAX; i += 256) {
+                const int c = i / LMAX, k = i - c * LMAX;
+                line[i] = (k < nimg) ? pr.x[(((long)(n0 + k) * C + c) * H + a) * W + b] : 0.f;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int p = 0; p < PPW; ++p) {
+                const int pair = w + 4 * p;
+                if (pair >= NP) continue;
+                const int ct = pair / NT, ctp = pair - ct * NT;
+                const float *pa = line + (16 * ct + lr) * LMAX + kk;
+                const float *pb = line + (16 * ctp + lr) * LMAX + kk;
+                for (int ks = 0; ks < nks; ++ks) {
+                    const float av = pa[4 * ks];
+                    if (ctp == 0) vs[p][q] += av;
+                    acc[p][q] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, pb[4 * ks], acc[p][q], 0, 0, 0);
+                }
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < PPW; ++p) {
+            const int pair = w + 4 * p;
+            if (pair >= NP) continue;
+            const int ct = pair / NT, ctp = pair - ct * NT;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    Bm[((12 + q) * C + 16 * ct + 4 * kk + v) * C + 16 * ctp + lr] = acc[p][q][v];
+                float s = vs[p][q];
+                s += __shfl_xor(s, 16);
+                s += __shfl_xor(s, 32);
+                if (ctp == 0 && kk == 0) Bv[(4 + q) * C + 16 * ct + lr] = s;
+            }
+        }
+    }
+}
+
+// Sums over the parts (lag matrices, channel sums) and over the image chunks (border terms), fixed order.
+__global__ __launch_bounds__(256) void corr3_sum_kernel(const CorrTable tab)
+{
+    const CorrProb &pr = tab.p[corr_locate(tab, blockIdx.x)];
+    const int C = pr.C;
+    const long nF = (long)C3_LAGS * C * C, nB = (long)C3_BQ * C * C;
+    const long e = (long)(blockIdx.x - pr.blk_start) * 256 + threadIdx.x;
+    if (e < nF) {
+        float s = 0.f;
+        for (int p = 0; p < pr.parts; ++p) s += pr.Fp[(long)p * nF + e];
+        pr.Fs[e] = s;
+    } else if (e < nF + C) {
+        const long c = e - nF;
+        float s = 0.f;
+        for (int p = 0; p < pr.parts; ++p) s += pr.Fp[(long)pr.parts * nF + (long)p * C + c];
+        pr.Fs[e] = s;
+    } else if (e < nF + C + nB) {
+        const long i = e - nF - C;
+        float s = 0.f;
+        for (int k = 0; k < C3_CHUNKS; ++k) s += pr.Bp[(long)k * nB + i];
+        pr.Bs[i] = s;
+    } else if (e < nF + C + nB + C3_BV * C) {
+        const long i = e - nF - C - nB;
+        float s = 0.f;
+        for (int k = 0; k < C3_CHUNKS; ++k) s += pr.Bp[(long)C3_CHUNKS * nB + (long)k * (C3_BV * C) + i];
+        pr.Bs[nB + i] = s;
+    }
+}
+
+// A[u][v] for one 16 x 16 sub-tile of the lower triangle per workgroup: assembly from the lag matrices and
+// the border terms, scale, running average; the mirror image goes through LDS so that both stores run along rows.
+__global__ __launch_bounds__(256) void corr3_assemble_kernel(const CorrTable tab)
+{
+    __shared__ float mir[16][17];
+    const CorrProb &pr = tab.p[corr_locate(tab, blockIdx.x)];
+    const int C = pr.C, H = pr.H, W = pr.W;
+    const int d = 9 * C, dF = d + pr.has_bias;
+    int bi, bj;
+    tri_decode(blockIdx.x - pr.blk_start, bi, bj);
+    const int t = threadIdx.x;
+    const int u = 16 * bi + (t >> 4), v = 16 * bj + (t & 15);
+    const float *Fs = pr.Fs, *Ts = pr.Fs + (long)C3_LAGS * C * C;
+    const float *Bs = pr.Bs, *Bv = pr.Bs + (long)C3_BQ * C * C;
+    const float wnew = (1.0f - pr.decay) * pr.scale;
+    float out = 0.f;
+    if (u < dF && v <= u) {
+        float val;
+        if (u == d) {
+            if (v == d) {
+                val = (float)((long)pr.B * H * W);
+            } else {
+                // column sum of patch column (c, i, j): all pixels minus the removed row / column plus the corner
+                const int c = v / 9, ij = v - 9 * c, i = ij / 3, j = ij - 3 * i;
+                val = Ts[c];
+                if (i != 1) val -= Bv[(i == 0 ? 1 : 0) * C + c];
+                if (j != 1) val -= Bv[(j == 0 ? 3 : 2) * C + c];
+                if (i != 1 && j != 1) val += Bv[(4 + (i == 0 ? 2 : 0) + (j == 0 ? 1 : 0)) * C + c];
+            }
+        } else {
+            const int c = u / 9, ij = u - 9 * c, i = ij / 3, j = ij - 3 * i;
+            const int c2 = v / 9, ij2 = v - 9 * c2, i2 = ij2 / 3, j2 = ij2 - 3 * i2;
+            int di = i2 - i, dj = j2 - j;
+            int ca = c, cb = c2;
+            if (di < 0 || (di == 0 && dj < 0)) { di = -di; dj = -dj; ca = c2; cb = c; }   // F(-d)[c][c'] = F(d)[c'][c]
+            const int l = di == 0 ? dj : (di == 1 ? 5 + dj : 10 + dj);
+            val = Fs[((long)l * C + ca) * C + cb];
+            if (i2 == i && i != 1) {
+                // removed row a* = H-1 (i = 0) or 0 (i = 2); lag dj = j2 - j along the row
+                const int side = i == 0 ? 1 : 0;
+                const int lag = j2 - j;
+                val -= lag >= 0 ? Bs[((long)(3 * side + lag) * C + c) * C + c2]
+                                : Bs[((long)(3 * side - lag) * C + c2) * C + c];
+            }
+            if (j2 == j && j != 1) {
+                const int side = j == 0 ? 3 : 2;
+                const int lag = i2 - i;
+                val -= lag >= 0 ? Bs[((long)(3 * side + lag) * C + c) * C + c2]
+                                : Bs[((long)(3 * side - lag) * C + c2) * C + c];
+            }
+            if (i2 == i && i != 1 && j2 == j && j != 1)
+                val += Bs[((long)(12 + (i == 0 ? 2 : 0) + (j == 0 ? 1 : 0)) * C + c) * C + c2];
+        }
+        out = pr.decay * pr.F[(long)u * dF + v] + wnew * val;
+        pr.F[(long)u * dF + v] = out;
+    }
+    mir[t >> 4][t & 15] = out;
+    __syncthreads();
+    {
+        const int c2 = t >> 4, r2 = t & 15;
+        const int u2 = 16 * bi + r2, v2 = 16 * bj + c2;
+        if (u2 < dF && v2 < u2) pr.F[(long)v2 * dF + u2] = mir[r2][c2];
+    }
+}
+
+}  // namespace kfac
