@@ -78,7 +78,7 @@ __global__ __launch_bounds__(256) void corr3_main_kernel(const CorrTable tab)
     const CorrProb &pr = tab.p[corr_locate(tab, blockIdx.x)];
     const int blk = blockIdx.x - pr.blk_start;
     const int u0 = blk * pr.upb, u1 = min(pr.units, u0 + pr.upb);
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lr = lane & 15, kk = lane >> 4;
     const int H = pr.H, W = pr.W, Wp = W + 4, SR = pr.SR, plane = pr.plane, w4 = W >> 2;
     float *buf0 = corr_lds, *buf1 = corr_lds + C * plane;
@@ -149,19 +149,43 @@ __global__ __launch_bounds__(256) void corr3_main_kernel(const CorrTable tab)
         const float *pb[PW];
 #pragma unroll
         for (int p = 0; p < PW; ++p) pb[p] = b + (16 * (ctp0 + p) + lr) * plane + 2 + kk;
-        int cnt = 0;
-        for (int r = 0; r < SR; ++r) {
-#pragma unroll 2
-            for (int g = 0; g < w4; ++g, ++cnt) {
-                if (KS == 4 && (cnt & 3) != w) continue;
-                const int off = r * Wp + 4 * g;
-                const float a = pa[off];
+        // k-steps of this wavefront: every KS-th of the strip; two per trip when there is one tile pair, so
+        // that the operands of the second arrive under the products of the first
+        int r = 0, g = (KS == 4) ? w : 0;
+        while (g >= w4) { g -= w4; ++r; }
+        while (r < SR) {
+            const int off0 = r * Wp + 4 * g;
+            g += KS;
+            while (g >= w4) { g -= w4; ++r; }
+            if (PW == 1) {
+                const bool two = r < SR;
+                const int off1 = two ? r * Wp + 4 * g : off0;
+                const float a0 = pa[off0], a1 = pa[off1];
+                float b0[C3_LAGS], b1[C3_LAGS];
+#pragma unroll
+                for (int l = 0; l < C3_LAGS; ++l) b0[l] = pb[0][off0 + dl[l]];
+#pragma unroll
+                for (int l = 0; l < C3_LAGS; ++l) b1[l] = pb[0][off1 + dl[l]];
+                tsum += a0;
+#pragma unroll
+                for (int l = 0; l < C3_LAGS; ++l)
+                    acc[0][l] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b0[l], acc[0][l], 0, 0, 0);
+                if (two) {
+                    tsum += a1;
+#pragma unroll
+                    for (int l = 0; l < C3_LAGS; ++l)
+                        acc[0][l] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1[l], acc[0][l], 0, 0, 0);
+                    g += KS;
+                    while (g >= w4) { g -= w4; ++r; }
+                }
+            } else {
+                const float a = pa[off0];
                 tsum += a;
 #pragma unroll
                 for (int p = 0; p < PW; ++p)
 #pragma unroll
                     for (int l = 0; l < C3_LAGS; ++l)
-                        acc[p][l] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, pb[p][off + dl[l]], acc[p][l], 0, 0, 0);
+                        acc[p][l] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, pb[p][off0 + dl[l]], acc[p][l], 0, 0, 0);
             }
         }
     }
@@ -211,7 +235,6 @@ __global__ __launch_bounds__(256) void corr3_border_kernel(const CorrTable tab)
     if (side < 4) {
         const bool is_row = side < 2;
         const int L = is_row ? W : H;                 // line length (a multiple of 4 for rows; any for columns)
-        const int Lp = L + 4;                         // k-steps may run up to 3 cells past the line, lags 2 more... zero
         const int fixed = (side & 1) ? (is_row ? H - 1 : W - 1) : 0;
         for (int i = tid; i < C * LMAX; i += 256) line[i] = 0.f;
         floatx4 acc[PPW][3];
@@ -223,14 +246,34 @@ __global__ __launch_bounds__(256) void corr3_border_kernel(const CorrTable tab)
 #pragma unroll
         for (int p = 0; p < PPW; ++p) vs[p] = 0.f;
         const int nks = (L + 3) / 4;
-        for (int n = n0; n < n1; ++n) {
-            __syncthreads();
-            const float *img = pr.x + (long)n * C * H * W;
-            for (int i = tid; i < C * L; i += 256) {
+        // the elements of the line this thread moves (same for every image): global offset inside an image, LDS index
+        constexpr int EPT = (C * 64 + 255) / 256;
+        int goff[EPT], loff[EPT];
+        float nxt[EPT];
+#pragma unroll
+        for (int k = 0; k < EPT; ++k) {
+            const int i = tid + 256 * k;
+            goff[k] = -1;
+            loff[k] = 0;
+            if (i < C * L) {
                 const int c = i / L, p = i - c * L;
-                line[c * LMAX + p] = is_row ? img[((long)c * H + fixed) * W + p] : img[((long)c * H + p) * W + fixed];
+                goff[k] = is_row ? (c * H + fixed) * W + p : (c * H + p) * W + fixed;
+                loff[k] = c * LMAX + p;
             }
+        }
+        auto fetch_line = [&](int n) {
+            const float *img = pr.x + (long)n * C * H * W;
+#pragma unroll
+            for (int k = 0; k < EPT; ++k) nxt[k] = goff[k] >= 0 ? img[goff[k]] : 0.f;
+        };
+        if (n0 < n1) fetch_line(n0);
+        for (int n = n0; n < n1; ++n) {
+            __syncthreads();                                  // the products on the previous line are done
+#pragma unroll
+            for (int k = 0; k < EPT; ++k)
+                if (goff[k] >= 0) line[loff[k]] = nxt[k];
             __syncthreads();
+            if (n + 1 < n1) fetch_line(n + 1);                // in flight under the products
 #pragma unroll
             for (int p = 0; p < PPW; ++p) {
                 const int pair = w + 4 * p;
@@ -247,7 +290,6 @@ __global__ __launch_bounds__(256) void corr3_border_kernel(const CorrTable tab)
                 }
             }
         }
-        (void)Lp;
 #pragma unroll
         for (int p = 0; p < PPW; ++p) {
             const int pair = w + 4 * p;
@@ -326,9 +368,14 @@ __global__ __launch_bounds__(256) void corr3_sum_kernel(const CorrTable tab)
     const long nF = (long)C3_LAGS * C * C, nB = (long)C3_BQ * C * C;
     const long e = (long)(blockIdx.x - pr.blk_start) * 256 + threadIdx.x;
     if (e < nF) {
-        float s = 0.f;
-        for (int p = 0; p < pr.parts; ++p) s += pr.Fp[(long)p * nF + e];
-        pr.Fs[e] = s;
+        // eight interleaved running sums (fixed order) keep loads in flight
+        float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        int p = 0;
+        for (; p + 8 <= pr.parts; p += 8)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) a[j] += pr.Fp[(long)(p + j) * nF + e];
+        for (; p < pr.parts; ++p) a[0] += pr.Fp[(long)p * nF + e];
+        pr.Fs[e] = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
     } else if (e < nF + C) {
         const long c = e - nF;
         float s = 0.f;
