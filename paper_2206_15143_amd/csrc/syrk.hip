@@ -380,7 +380,8 @@ int corr3_rows(int C, int H, int W, int *plane_out)
     int best = 0;
     for (int SR = 1; SR <= H; ++SR) {
         if (H % SR) continue;
-        int plane = (SR + 2) * (W + 4);
+        if ((SR * W) % 16) continue;                           // whole groups of 16 pixels
+        int plane = (SR + 2) * (W + 8);
         plane += (4 - plane % 32 + 32) % 32;
         const long bytes = 2l * C * plane * 4;
         const long items = (long)C * (SR + 2) * (W / 4);
@@ -417,7 +418,8 @@ void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<
     const Tuning &tu = tuning();
     if (pl[idx[0]].cfg >= kCorr3Cfg) {
         // autocorrelation kernel: (image, strip) units dealt evenly to about target_blocks workgroups
-        const long per = std::max<long>(1, tu.target_blocks / (long)idx.size());
+        const long halves = pl[idx[0]].cfg == kCorr3Cfg + 2 ? 2 : 1;
+        const long per = std::max<long>(1, tu.target_blocks / ((long)idx.size() * halves));
         for (int j : idx) {
             Planned &p = pl[j];
             const FactorJob &job = jobs[j];
@@ -570,7 +572,7 @@ hipError_t corr3_launch_nt(CorrTable &tab, const std::vector<size_t> &lds, doubl
     size_t lds_bytes = 0;
     for (int k = 0; k < tab.count; ++k) {
         tab.p[k].blk_start = blocks;
-        blocks += tab.p[k].splits;
+        blocks += tab.p[k].splits * (NT == 4 ? 2 : 1);   // 64 channels: two workgroups per range of units
         lds_bytes = std::max(lds_bytes, lds[k]);
     }
     static bool attr_set = false;

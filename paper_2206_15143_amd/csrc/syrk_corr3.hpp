@@ -61,26 +61,30 @@ __device__ __forceinline__ int corr_locate(const CorrTable &tab, int blk)
 
 // ---------------------------------------------------------------------------------------------------------
 // Lag matrices.  A workgroup walks (image, strip) units: the strip of all C channels with two halo rows below
-// and two zero columns left and right is staged in LDS (double buffered, the next unit's global loads in
-// flight under the products); a k-step is four consecutive pixels of a row; the A operand is channel tile ct
-// at those pixels, the B operand channel tile ct' at the pixels shifted by the lag.
+// is staged in LDS (double buffered, the next unit's global loads in
+// flight under the products) with four zero columns left and right; the A operand of a k-step is channel tile
+// ct at four pixels, the B operand channel tile ct' at the pixels shifted by the lag.
 //   NT = 1 (C = 16): one tile pair; the four wavefronts take every fourth k-step (four parts per block).
-//   NT = 2 (C = 32): four tile pairs, one per wavefront.     NT = 4 (C = 64): wavefront w = A tile w, all four B tiles.
+//   NT = 2 (C = 32): four tile pairs, one per wavefront.
+//   NT = 4 (C = 64): wavefront w = A tile w and two of the four B tiles; two workgroups share a range of units
+//   (all 52 lag tiles per wavefront would leave one wavefront per SIMD).
 template <int NT>
 __global__ __launch_bounds__(256) void corr3_main_kernel(const CorrTable tab)
 {
     extern __shared__ __align__(16) float corr_lds[];
     constexpr int C = 16 * NT;
-    constexpr int KS = NT == 1 ? 4 : 1;
-    constexpr int PW = NT == 4 ? 4 : 1;
+    constexpr int KS = NT == 1 ? 4 : 1;        // wavefronts that split the pixel groups
+    constexpr int PW = NT == 4 ? 2 : 1;        // B tiles per wavefront
+    constexpr int HALVES = NT == 4 ? 2 : 1;    // workgroups that share a range of units (each takes half the B tiles)
     constexpr int MAXI = 12;                   // float4 items per thread and slab at most (checked by the planner)
 
     const CorrProb &pr = tab.p[corr_locate(tab, blockIdx.x)];
-    const int blk = blockIdx.x - pr.blk_start;
+    const int blk_raw = blockIdx.x - pr.blk_start;
+    const int blk = blk_raw / HALVES, half = blk_raw - blk * HALVES;
     const int u0 = blk * pr.upb, u1 = min(pr.units, u0 + pr.upb);
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lr = lane & 15, kk = lane >> 4;
-    const int H = pr.H, W = pr.W, Wp = W + 4, SR = pr.SR, plane = pr.plane, w4 = W >> 2;
+    const int H = pr.H, W = pr.W, Wp = W + 8, SR = pr.SR, plane = pr.plane, w4 = W >> 2;
     float *buf0 = corr_lds, *buf1 = corr_lds + C * plane;
 
     for (int i = tid; i < 2 * C * plane; i += 256) corr_lds[i] = 0.f;   // the pad cells are never written again
@@ -89,7 +93,7 @@ __global__ __launch_bounds__(256) void corr3_main_kernel(const CorrTable tab)
     int ct, ctp0;
     if (NT == 1) { ct = 0; ctp0 = 0; }
     else if (NT == 2) { ct = w >> 1; ctp0 = w & 1; }
-    else { ct = w; ctp0 = 0; }
+    else { ct = w; ctp0 = 2 * half; }
 
     floatx4 acc[PW][C3_LAGS];
 #pragma unroll
@@ -97,14 +101,6 @@ __global__ __launch_bounds__(256) void corr3_main_kernel(const CorrTable tab)
 #pragma unroll
         for (int l = 0; l < C3_LAGS; ++l) acc[p][l] = floatx4{0.f, 0.f, 0.f, 0.f};
     float tsum = 0.f;
-
-    int dl[C3_LAGS];                            // slab offset of each lag: (0,0..2), (1,-2..2), (2,-2..2)
-#pragma unroll
-    for (int l = 0; l < C3_LAGS; ++l) {
-        const int di = l < 3 ? 0 : (l < 8 ? 1 : 2);
-        const int dj = l < 3 ? l : (l < 8 ? l - 5 : l - 10);
-        dl[l] = di * Wp + dj;
-    }
 
     const int rows = SR + 2;
     const int items = C * rows * w4;
@@ -132,61 +128,54 @@ __global__ __launch_bounds__(256) void corr3_main_kernel(const CorrTable tab)
             if (e < items) {
                 const int c = e / (rows * w4), rem = e - c * (rows * w4);
                 const int r = rem / w4, g = rem - r * w4;
-                float *d = b + c * plane + r * Wp + 2 + 4 * g;      // 8-byte aligned
-                *reinterpret_cast<float2 *>(d) = float2{regs[k].x, regs[k].y};
-                *reinterpret_cast<float2 *>(d + 2) = float2{regs[k].z, regs[k].w};
+                *reinterpret_cast<floatx4 *>(b + c * plane + r * Wp + 4 + 4 * g) = regs[k];
             }
         }
     };
 
-    if (u0 < u1) fetch(u0);
-    for (int u = u0; u < u1; ++u) {
-        float *b = ((u - u0) & 1) ? buf1 : buf0;
+    // A group is 16 consecutive pixels of the strip (row-major); lane kk holds pixels 4 kk .. 4 kk + 3 of it and
+    // k-step e of the group takes pixel 4 kk + e from every lane.  For the shifted operand a lane reads, per
+    // row lag, the 12-pixel window around its four pixels (three 16-byte reads): every lag (di, dj) of k-step e
+    // is element e + dj of the window of row di, a register chosen at compile time.
+    const int ngroups = SR * W / 16;
+    for (int u = u0, it = 0; u < u1; ++u, ++it) {
+        float *b = (it & 1) ? buf1 : buf0;
+        if (it == 0) fetch(u0);
         commit(b);
         __syncthreads();        // a wavefront gets here only after its products on the other buffer: one barrier per unit
         if (u + 1 < u1) fetch(u + 1);
-        const float *pa = b + (16 * ct + lr) * plane + 2 + kk;
+        const float *pa = b + (16 * ct + lr) * plane + 4;
         const float *pb[PW];
 #pragma unroll
-        for (int p = 0; p < PW; ++p) pb[p] = b + (16 * (ctp0 + p) + lr) * plane + 2 + kk;
-        // k-steps of this wavefront: every KS-th of the strip; two per trip when there is one tile pair, so
-        // that the operands of the second arrive under the products of the first
-        int r = 0, g = (KS == 4) ? w : 0;
-        while (g >= w4) { g -= w4; ++r; }
-        while (r < SR) {
-            const int off0 = r * Wp + 4 * g;
-            g += KS;
-            while (g >= w4) { g -= w4; ++r; }
-            if (PW == 1) {
-                const bool two = r < SR;
-                const int off1 = two ? r * Wp + 4 * g : off0;
-                const float a0 = pa[off0], a1 = pa[off1];
-                float b0[C3_LAGS], b1[C3_LAGS];
+        for (int p = 0; p < PW; ++p) pb[p] = b + (16 * (ctp0 + p) + lr) * plane + 4;
+        int q0 = 16 * ((KS == 4) ? w : 0) + 4 * kk;            // first pixel of this lane in its first group
+        int row = q0 / W, col = q0 - row * W;
+        for (int G = (KS == 4) ? w : 0; G < ngroups; G += KS) {
+            const int base = row * Wp + col;
+            const floatx4 a4 = *reinterpret_cast<const floatx4 *>(pa + base);
+            floatx4 win[PW][3][3];
 #pragma unroll
-                for (int l = 0; l < C3_LAGS; ++l) b0[l] = pb[0][off0 + dl[l]];
+            for (int p = 0; p < PW; ++p)
 #pragma unroll
-                for (int l = 0; l < C3_LAGS; ++l) b1[l] = pb[0][off1 + dl[l]];
-                tsum += a0;
+                for (int di = 0; di < 3; ++di)
 #pragma unroll
-                for (int l = 0; l < C3_LAGS; ++l)
-                    acc[0][l] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b0[l], acc[0][l], 0, 0, 0);
-                if (two) {
-                    tsum += a1;
+                    for (int sgm = 0; sgm < 3; ++sgm)
+                        win[p][di][sgm] = *reinterpret_cast<const floatx4 *>(pb[p] + base + di * Wp + 4 * (sgm - 1));
+            tsum += (a4.x + a4.y) + (a4.z + a4.w);
 #pragma unroll
-                    for (int l = 0; l < C3_LAGS; ++l)
-                        acc[0][l] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1[l], acc[0][l], 0, 0, 0);
-                    g += KS;
-                    while (g >= w4) { g -= w4; ++r; }
-                }
-            } else {
-                const float a = pa[off0];
-                tsum += a;
+            for (int e = 0; e < 4; ++e) {
 #pragma unroll
                 for (int p = 0; p < PW; ++p)
 #pragma unroll
-                    for (int l = 0; l < C3_LAGS; ++l)
-                        acc[p][l] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, pb[p][off0 + dl[l]], acc[p][l], 0, 0, 0);
+                    for (int l = 0; l < C3_LAGS; ++l) {
+                        const int di = l < 3 ? 0 : (l < 8 ? 1 : 2);
+                        const int dj = l < 3 ? l : (l < 8 ? l - 5 : l - 10);
+                        const int idx = e + dj + 4;                       // 2 .. 9 inside the 12-pixel window
+                        acc[p][l] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[e], win[p][di][idx >> 2][idx & 3], acc[p][l], 0, 0, 0);
+                    }
             }
+            col += 16 * KS;
+            while (col >= W) { col -= W; ++row; }
         }
     }
 
@@ -202,7 +191,7 @@ __global__ __launch_bounds__(256) void corr3_main_kernel(const CorrTable tab)
 #pragma unroll
             for (int v = 0; v < 4; ++v)
                 Fo[(l * C + 16 * ct + 4 * kk + v) * C + 16 * (ctp0 + p) + lr] = acc[p][l][v];
-    if ((NT != 2 || ctp0 == 0) && kk == 0)
+    if (ctp0 == 0 && kk == 0)
         pr.Fp[(long)pr.parts * (C3_LAGS * C * C) + (long)part * C + 16 * ct + lr] = tsum;
 }
 
@@ -249,7 +238,8 @@ __global__ __launch_bounds__(256) void corr3_border_kernel(const CorrTable tab)
         // the elements of the line this thread moves (same for every image): global offset inside an image, LDS index
         constexpr int EPT = (C * 64 + 255) / 256;
         int goff[EPT], loff[EPT];
-        float nxt[EPT];
+        constexpr int DEPTH = 4;                              // images whose loads are in flight
+        float nxt[DEPTH][EPT];
 #pragma unroll
         for (int k = 0; k < EPT; ++k) {
             const int i = tid + 256 * k;
@@ -261,32 +251,43 @@ __global__ __launch_bounds__(256) void corr3_border_kernel(const CorrTable tab)
                 loff[k] = c * LMAX + p;
             }
         }
-        auto fetch_line = [&](int n) {
-            const float *img = pr.x + (long)n * C * H * W;
 #pragma unroll
-            for (int k = 0; k < EPT; ++k) nxt[k] = goff[k] >= 0 ? img[goff[k]] : 0.f;
-        };
-        if (n0 < n1) fetch_line(n0);
-        for (int n = n0; n < n1; ++n) {
-            __syncthreads();                                  // the products on the previous line are done
+        for (int j = 0; j < DEPTH; ++j) {
+            if (n0 + j < n1) {
+                const float *img = pr.x + (long)(n0 + j) * C * H * W;
 #pragma unroll
-            for (int k = 0; k < EPT; ++k)
-                if (goff[k] >= 0) line[loff[k]] = nxt[k];
-            __syncthreads();
-            if (n + 1 < n1) fetch_line(n + 1);                // in flight under the products
+                for (int k = 0; k < EPT; ++k) nxt[j][k] = goff[k] >= 0 ? img[goff[k]] : 0.f;
+            }
+        }
+        for (int nb = n0; nb < n1; nb += DEPTH) {
 #pragma unroll
-            for (int p = 0; p < PPW; ++p) {
-                const int pair = w + 4 * p;
-                if (pair >= NP) continue;
-                const int ct = pair / NT, ctp = pair - ct * NT;
-                const float *pa = line + (16 * ct + lr) * LMAX + kk;
-                const float *pb = line + (16 * ctp + lr) * LMAX + kk;
-                for (int ks = 0; ks < nks; ++ks) {
-                    const float a = pa[4 * ks];
-                    if (ctp == 0) vs[p] += a;
+            for (int j = 0; j < DEPTH; ++j) {
+                const int n = nb + j;
+                if (n >= n1) break;
+                __syncthreads();                              // the products on the previous line are done
 #pragma unroll
-                    for (int l = 0; l < 3; ++l)
-                        acc[p][l] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, pb[4 * ks + l], acc[p][l], 0, 0, 0);
+                for (int k = 0; k < EPT; ++k)
+                    if (goff[k] >= 0) line[loff[k]] = nxt[j][k];
+                __syncthreads();
+                if (n + DEPTH < n1) {                         // refill this register set: in flight for DEPTH lines
+                    const float *img = pr.x + (long)(n + DEPTH) * C * H * W;
+#pragma unroll
+                    for (int k = 0; k < EPT; ++k) nxt[j][k] = goff[k] >= 0 ? img[goff[k]] : 0.f;
+                }
+#pragma unroll
+                for (int p = 0; p < PPW; ++p) {
+                    const int pair = w + 4 * p;
+                    if (pair >= NP) continue;
+                    const int ct = pair / NT, ctp = pair - ct * NT;
+                    const float *pa = line + (16 * ct + lr) * LMAX + kk;
+                    const float *pb = line + (16 * ctp + lr) * LMAX + kk;
+                    for (int ks = 0; ks < nks; ++ks) {
+                        const float a = pa[4 * ks];
+                        if (ctp == 0) vs[p] += a;
+#pragma unroll
+                        for (int l = 0; l < 3; ++l)
+                            acc[p][l] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, pb[4 * ks + l], acc[p][l], 0, 0, 0);
+                    }
                 }
             }
         }
