@@ -385,7 +385,7 @@ int corr3_rows(int C, int H, int W, int *plane_out)
         plane += (4 - plane % 32 + 32) % 32;
         const long bytes = 2l * C * plane * 4;
         const long items = (long)C * (SR + 2) * (W / 4);
-        if (bytes > 72 * 1024 || items > 12 * 256) continue;
+        if (bytes > tuning().corr3_lds_kb * 1024 || items > 12 * 256) continue;
         best = SR;
         if (plane_out) *plane_out = plane;
     }
@@ -433,7 +433,8 @@ void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<
             p.nb = 1; p.nblk = 1; p.bps = 1;
             const size_t parts = (size_t)p.splits * (C == 16 ? 4 : 1);
             const size_t nF = (size_t)C3_LAGS * C * C, nB = (size_t)C3_BQ * C * C + (size_t)C3_BV * C;
-            p.partial_floats = parts * (nF + C) + (nF + C) + (size_t)C3_CHUNKS * nB + nB + 64;
+            p.partial_floats = parts * (nF + C) + (nF + C) + (size_t)C3_CHUNKS * nB + nB + 64 +
+                               (size_t)(job.K / job.hw) * 2 * C * job.h;          // + border columns
         }
         return;
     }
@@ -623,6 +624,7 @@ hipError_t corr3_launch(const FactorJob *jobs, const std::vector<int> &g, const 
         p.Fs = p.Fp + (size_t)p.parts * (nF + C);
         p.Bp = p.Fs + (nF + C);
         p.Bs = p.Bp + (size_t)C3_CHUNKS * nB;
+        p.cols = p.Bs + nB;
         p.blk_start = 0;
         lds[k] = (size_t)2 * C * p.plane * sizeof(float);
     }

@@ -35,6 +35,7 @@ struct CorrProb {
     float *Fs;         // [13][C][C] + [C]: summed over the parts
     float *Bp;         // [chunks][16][C][C], then [chunks][8][C]
     float *Bs;         // [16][C][C] + [8][C]: summed over the chunks
+    float *cols;       // [B][2][C][H]: first and last image column, written by the main kernel for the border kernel
     float *F;          // factor [dF, dF], dF = 9 C + has_bias
     int C, H, W, B;
     int SR, strips;    // rows per strip, strips per image
@@ -132,7 +133,19 @@ __global__ __launch_bounds__(256) void corr3_main_kernel(const CorrTable tab)
             }
         }
     };
-
+    // the first and the last pixel of every image row also go to a compact buffer (the border kernel would
+    // otherwise pull a whole cache line per pixel of those two columns): read back from the slab after the
+    // barrier, consecutive threads = consecutive rows of a channel
+    auto save_cols = [&](const float *b, int u) {
+        if (NT == 4) return;             // 64 channels: short columns, the border kernel reads them from the input
+        const int n = u / pr.strips, a0 = (u - n * pr.strips) * SR;
+        float *cbase = pr.cols + (long)n * 2 * C * H + a0;
+        for (int t = tid; t < 2 * C * SR; t += 256) {
+            const int side = t / (C * SR), rem = t - side * (C * SR);
+            const int c = rem / SR, r = rem - c * SR;
+            if (a0 + r < H) cbase[(side * C + c) * H + r] = b[c * plane + r * Wp + 4 + (side ? W - 1 : 0)];
+        }
+    };
     // A group is 16 consecutive pixels of the strip (row-major); lane kk holds pixels 4 kk .. 4 kk + 3 of it and
     // k-step e of the group takes pixel 4 kk + e from every lane.  For the shifted operand a lane reads, per
     // row lag, the 12-pixel window around its four pixels (three 16-byte reads): every lag (di, dj) of k-step e
@@ -143,6 +156,7 @@ __global__ __launch_bounds__(256) void corr3_main_kernel(const CorrTable tab)
         if (it == 0) fetch(u0);
         commit(b);
         __syncthreads();        // a wavefront gets here only after its products on the other buffer: one barrier per unit
+        save_cols(b, u);
         if (u + 1 < u1) fetch(u + 1);
         const float *pa = b + (16 * ct + lr) * plane + 4;
         const float *pb[PW];
@@ -247,14 +261,15 @@ __global__ __launch_bounds__(256) void corr3_border_kernel(const CorrTable tab)
             loff[k] = 0;
             if (i < C * L) {
                 const int c = i / L, p = i - c * L;
-                goff[k] = is_row ? (c * H + fixed) * W + p : (c * H + p) * W + fixed;
+                goff[k] = is_row ? (c * H + fixed) * W + p
+                                 : (NT == 4 ? (c * H + p) * W + fixed : ((side & 1) * C + c) * H + p);   // columns: compact buffer below 64 channels
                 loff[k] = c * LMAX + p;
             }
         }
 #pragma unroll
         for (int j = 0; j < DEPTH; ++j) {
             if (n0 + j < n1) {
-                const float *img = pr.x + (long)(n0 + j) * C * H * W;
+                const float *img = (is_row || NT == 4) ? pr.x + (long)(n0 + j) * C * H * W : pr.cols + (long)(n0 + j) * 2 * C * H;
 #pragma unroll
                 for (int k = 0; k < EPT; ++k) nxt[j][k] = goff[k] >= 0 ? img[goff[k]] : 0.f;
             }
@@ -270,7 +285,8 @@ __global__ __launch_bounds__(256) void corr3_border_kernel(const CorrTable tab)
                     if (goff[k] >= 0) line[loff[k]] = nxt[j][k];
                 __syncthreads();
                 if (n + DEPTH < n1) {                         // refill this register set: in flight for DEPTH lines
-                    const float *img = pr.x + (long)(n + DEPTH) * C * H * W;
+                    const float *img = (is_row || NT == 4) ? pr.x + (long)(n + DEPTH) * C * H * W
+                                                            : pr.cols + (long)(n + DEPTH) * 2 * C * H;
 #pragma unroll
                     for (int k = 0; k < EPT; ++k) nxt[j][k] = goff[k] >= 0 ? img[goff[k]] : 0.f;
                 }
