@@ -67,6 +67,8 @@ inline int conv3_choose_rows(int H, int W)
         const Conv3Geo g = conv3_geo(H, W, R);
         const long bytes = ((long)C3_NSTAGE * W_SLOTS * g.slab + C3_PRE + 256) * 4;
         if (bytes > 150 * 1024 || (g.NI + 3) / 4 > 4 || g.nks < 8) continue;
+        // the bias border is summed by one thread per slab row and at most four 16-byte pieces per thread
+        if (g.rows > 256 || g.rows * (W / 4) > 4 * 256) continue;
         best = R;
     }
     return best;

@@ -184,6 +184,44 @@ def test_nonsquare_layer_end_to_end(cin, kh, kw, h, w, pad, bias):
     _run_and_check([layer], 6, 9200 + 10 * kh + kw, batched=False)
 
 
+@pytest.mark.parametrize("cin,h,w,batch,bias", [
+    (16, 32, 32, 3, True),      # one strip pair per image, four wavefronts splitting the pixel groups
+    (16, 8, 8, 5, False),       # batch not a multiple of the four image chunks of the border kernel
+    (32, 16, 16, 2, True),
+    (32, 6, 8, 1, True),        # a single image; strips of 2 rows
+    (64, 8, 8, 7, True),        # two workgroups per range of units
+    (64, 4, 12, 3, False),
+    (16, 2, 16, 4, True),       # two rows: the first and the last image row are neighbours
+    (16, 12, 8, 9, True),
+    (32, 64, 4, 2, True),       # tall and narrow
+    (16, 3, 64, 2, True),       # odd height, widest map
+])
+def test_conv3_factor_from_autocorrelations(cin, h, w, batch, bias):
+    # 3x3 / stride 1 / pad 1 layers with 16, 32 or 64 input channels build A from 13 autocorrelation lag
+    # matrices plus border corrections: against the oracle, and against the direct kernel on the same inputs
+    layer = LayerSpec("conv", cin, 8, 3, 1, 1, h, has_bias=bias, w_in=w)
+    _run_and_check([layer], batch, 7300 + cin + h + w, batched=True)
+    inputs = gu.draw_inputs([layer], batch, 7400 + cin, "relu_normal", 0.05)
+    scales = gu.scales_for([layer], batch)
+    corr = gu.run_layers_gpu([layer], batch, inputs, scales, 0.95, 0.03)[0]
+    kf.kfac_tune("use_corr3", 0)
+    try:
+        direct = gu.run_layers_gpu([layer], batch, inputs, scales, 0.95, 0.03)[0]
+    finally:
+        kf.kfac_tune("use_corr3", 1)
+    assert gu.rel_fro(corr["A"], direct["A"]) < 1e-5
+    assert np.array_equal(corr["A"], corr["A"].T)
+
+
+@pytest.mark.parametrize("cin,h,w,batch", [(48, 64, 4, 2), (48, 32, 4, 3), (48, 64, 8, 2), (80, 16, 4, 2), (48, 8, 4, 2),
+                                            (48, 20, 12, 2)])
+def test_fused_conv3_kernel_on_tall_narrow_maps(cin, h, w, batch):
+    # the direct fused kernel (channel counts the autocorrelation path does not take) on maps much taller than
+    # wide: the strip height is bounded by what the bias-border summation of a workgroup covers (256 slab rows)
+    layer = LayerSpec("conv", cin, 8, 3, 1, 1, h, has_bias=True, w_in=w)
+    _run_and_check([layer], batch, 7500 + cin + h + w, batched=True)
+
+
 @pytest.mark.parametrize("n", [1, 5, 64, 65, 130, 257, 400])
 def test_inverse_sizes(n):
     gen = np.random.default_rng(n)
