@@ -283,7 +283,7 @@ hipError_t fused_launch(const InvertJob *jobs, const std::vector<int> &idx, cons
             for (int k = 0; k < nclass; ++k) {
                 t.c[k].per = per_fn(t.c[k]);
                 t.c[k].blk_start = (int)blocks;
-                blocks += (long)t.c[k].per * t.c[k].count;
+                blocks += (long)t.c[k].per * seq_slots(t.c[k].count);
             }
             return blocks;
         };

@@ -60,7 +60,7 @@ struct InvClass {
     int count;       // problems in the class
     int n, nblk;
     int per;         // blocks per problem in this launch
-    int blk_start;   // first block of the class in this launch
+    int blk_start;   // first block of the class in this launch (a multiple of 8)
 };
 
 struct InvSeq {
@@ -79,16 +79,24 @@ __global__ __launch_bounds__(64) void inv_upload_kernel(const InvUpload u)
     for (int e = threadIdx.x + blockIdx.x * 64; e < u.count * words; e += 64 * gridDim.x) dst[e] = src[e];
 }
 
+// Block -> (matrix, block of that matrix).  Inside a class the blocks are dealt block-major: block `local` of
+// every matrix before block `local + 1` of any, with the matrix count rounded up to a multiple of 8 (the slots
+// past the last matrix are empty).  Two things follow: workgroup i runs on XCD i mod 8, so every block of a
+// matrix runs on the same XCD and its panels and pivot inverse are fetched into one L2 instead of eight; and
+// block 0 of every matrix (the one that goes on to invert the next pivot block) is dispatched first.
+__host__ __device__ __forceinline__ int seq_slots(int count) { return (count + 7) & ~7; }
+
 __device__ __forceinline__ bool seq_locate(const InvSeq &q, int blk, int &prob, int &local, int &ci)
 {
     ci = 0;
     while (ci + 1 < q.nclass && blk >= q.c[ci + 1].blk_start) ++ci;
     const InvClass &c = q.c[ci];
     const int off = blk - c.blk_start;
-    const int pl = off / c.per;
-    if (pl >= c.count) return false;
+    const int slots = seq_slots(c.count);
+    local = off / slots;
+    const int pl = off - local * slots;
+    if (pl >= c.count || local >= c.per) return false;
     prob = c.first + pl;
-    local = off - pl * c.per;
     return true;
 }
 

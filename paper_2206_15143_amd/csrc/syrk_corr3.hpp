@@ -77,7 +77,8 @@ __global__ __launch_bounds__(256) void corr3_main_kernel(const CorrTable tab)
     constexpr int KS = NT == 1 ? 4 : 1;        // wavefronts that split the pixel groups
     constexpr int PW = NT == 4 ? 2 : 1;        // B tiles per wavefront
     constexpr int HALVES = NT == 4 ? 2 : 1;    // workgroups that share a range of units (each takes half the B tiles)
-    constexpr int MAXI = 12;                   // float4 items per thread and slab at most (checked by the planner)
+    constexpr int MAXI = 6;                    // float4 items per thread and slab at most (checked by the planner)
+    constexpr int SCI = 2;                     // border-column cells per thread with a precomputed address
 
     const CorrProb &pr = tab.p[corr_locate(tab, blockIdx.x)];
     const int blk_raw = blockIdx.x - pr.blk_start;
@@ -103,58 +104,89 @@ __global__ __launch_bounds__(256) void corr3_main_kernel(const CorrTable tab)
         for (int l = 0; l < C3_LAGS; ++l) acc[p][l] = floatx4{0.f, 0.f, 0.f, 0.f};
     float tsum = 0.f;
 
+    // what this thread moves per slab is the same for every unit: offset inside the (image, strip) window of
+    // the input (-1: nothing), and the LDS offset with the slab row above bit 20
     const int rows = SR + 2;
     const int items = C * rows * w4;
+    int gofs[MAXI], lofs[MAXI];
+#pragma unroll
+    for (int k = 0; k < MAXI; ++k) {
+        const int e = tid + 256 * k;
+        gofs[k] = -1;
+        lofs[k] = 0;
+        if (e < items) {
+            const int c = e / (rows * w4), rem = e - c * (rows * w4);
+            const int r = rem / w4, g = rem - r * w4;
+            gofs[k] = (c * H + r) * W + 4 * g;
+            lofs[k] = (c * plane + r * Wp + 4 + 4 * g) | (r << 20);
+        }
+    }
     floatx4 regs[MAXI];
-    auto fetch = [&](int u) {
+    auto fetch = [&](int u) {                  // loads only: nothing here may wait for them
         const int n = u / pr.strips, a0 = (u - n * pr.strips) * SR;
-        const float *img = pr.x + (long)n * C * H * W;
+        const float *win0 = pr.x + (long)n * C * H * W + (long)a0 * W;
 #pragma unroll
         for (int k = 0; k < MAXI; ++k) {
-            const int e = tid + 256 * k;
-            floatx4 v = {0.f, 0.f, 0.f, 0.f};
-            if (e < items) {
-                const int c = e / (rows * w4), rem = e - c * (rows * w4);
-                const int r = rem / w4, g = rem - r * w4;
-                const int a = a0 + r;
-                if (a < H) v = *reinterpret_cast<const floatx4 *>(img + ((long)c * H + a) * W + 4 * g);
-            }
-            regs[k] = v;
+            const bool ok = gofs[k] >= 0 && a0 + (lofs[k] >> 20) < H;
+            regs[k] = *reinterpret_cast<const floatx4 *>(win0 + (ok ? gofs[k] : 0));
         }
     };
-    auto commit = [&](float *b) {
+    auto commit = [&](float *b, int u) {
+        // unconditional stores (a store skipped by a branch would leave its load unwaited for, and the next
+        // fetch would then have to wait instead): rows below the image are stored as zeros, and an item that
+        // does not exist stores zeros to the first pad cell of the slab, which holds zeros anyway
+        const int a0 = (u % pr.strips) * SR;
 #pragma unroll
         for (int k = 0; k < MAXI; ++k) {
-            const int e = tid + 256 * k;
-            if (e < items) {
-                const int c = e / (rows * w4), rem = e - c * (rows * w4);
-                const int r = rem / w4, g = rem - r * w4;
-                *reinterpret_cast<floatx4 *>(b + c * plane + r * Wp + 4 + 4 * g) = regs[k];
-            }
+            const bool ok = gofs[k] >= 0 && a0 + (lofs[k] >> 20) < H;
+            *reinterpret_cast<floatx4 *>(b + (lofs[k] & 0xfffff)) = ok ? regs[k] : floatx4{0.f, 0.f, 0.f, 0.f};
         }
     };
     // the first and the last pixel of every image row also go to a compact buffer (the border kernel would
     // otherwise pull a whole cache line per pixel of those two columns): read back from the slab after the
     // barrier, consecutive threads = consecutive rows of a channel
+    int sc_l[SCI], sc_g[SCI];
+#pragma unroll
+    for (int j = 0; j < SCI; ++j) {
+        const int t = tid + 256 * j;
+        sc_l[j] = -1;
+        sc_g[j] = 0;
+        if (NT != 4 && t < 2 * C * SR) {
+            const int side = t / (C * SR), rem = t - side * (C * SR);
+            const int c = rem / SR, r = rem - c * SR;
+            sc_l[j] = c * plane + r * Wp + 4 + (side ? W - 1 : 0);
+            sc_g[j] = (side * C + c) * H + r;
+        }
+    }
     auto save_cols = [&](const float *b, int u) {
         if (NT == 4) return;             // 64 channels: short columns, the border kernel reads them from the input
         const int n = u / pr.strips, a0 = (u - n * pr.strips) * SR;
         float *cbase = pr.cols + (long)n * 2 * C * H + a0;
-        for (int t = tid; t < 2 * C * SR; t += 256) {
+#pragma unroll
+        for (int j = 0; j < SCI; ++j)
+            if (sc_l[j] >= 0) cbase[sc_g[j]] = b[sc_l[j]];
+        for (int t = tid + 256 * SCI; t < 2 * C * SR; t += 256) {
             const int side = t / (C * SR), rem = t - side * (C * SR);
             const int c = rem / SR, r = rem - c * SR;
-            if (a0 + r < H) cbase[(side * C + c) * H + r] = b[c * plane + r * Wp + 4 + (side ? W - 1 : 0)];
+            cbase[(side * C + c) * H + r] = b[c * plane + r * Wp + 4 + (side ? W - 1 : 0)];
         }
     };
     // A group is 16 consecutive pixels of the strip (row-major); lane kk holds pixels 4 kk .. 4 kk + 3 of it and
     // k-step e of the group takes pixel 4 kk + e from every lane.  For the shifted operand a lane reads, per
     // row lag, the 12-pixel window around its four pixels (three 16-byte reads): every lag (di, dj) of k-step e
     // is element e + dj of the window of row di, a register chosen at compile time.
+    // A stage is one group and one B tile: 52 products on 10 operand reads.  Two register sets alternate, the
+    // reads of the next stage are issued before the products of the current one (all wavefronts of a SIMD
+    // advance at the same pace, so none of them would cover the read latency of another).
     const int ngroups = SR * W / 16;
+    const int gfirst = (KS == 4) ? w : 0;
+    const int nstages = ((ngroups - gfirst + KS - 1) / KS) * PW;
+    const int q0 = 16 * gfirst + 4 * kk;                       // first pixel of this lane in its first group
+    const int row0 = q0 / W, col0 = q0 - row0 * W;
     for (int u = u0, it = 0; u < u1; ++u, ++it) {
         float *b = (it & 1) ? buf1 : buf0;
         if (it == 0) fetch(u0);
-        commit(b);
+        commit(b, u);
         __syncthreads();        // a wavefront gets here only after its products on the other buffer: one barrier per unit
         save_cols(b, u);
         if (u + 1 < u1) fetch(u + 1);
@@ -162,34 +194,59 @@ __global__ __launch_bounds__(256) void corr3_main_kernel(const CorrTable tab)
         const float *pb[PW];
 #pragma unroll
         for (int p = 0; p < PW; ++p) pb[p] = b + (16 * (ctp0 + p) + lr) * plane + 4;
-        int q0 = 16 * ((KS == 4) ? w : 0) + 4 * kk;            // first pixel of this lane in its first group
-        int row = q0 / W, col = q0 - row * W;
-        for (int G = (KS == 4) ? w : 0; G < ngroups; G += KS) {
-            const int base = row * Wp + col;
-            const floatx4 a4 = *reinterpret_cast<const floatx4 *>(pa + base);
-            floatx4 win[PW][3][3];
+        // operand registers of a set: the four pixels of the A tile, and per row lag the window elements that
+        // some lag uses (pixels -2 .. 5 around the lane's first pixel; 0 .. 5 for row lag 0), read as 8 + 16 + 8 bytes
+        typedef float floatx2 __attribute__((ext_vector_type(2)));
+        floatx4 a4[2], wmid[2][3];
+        floatx2 wlo[2][3], whi[2][3];
+        auto load = [&](int set, int base, int p) {
+            a4[set] = *reinterpret_cast<const floatx4 *>(pa + base);
 #pragma unroll
-            for (int p = 0; p < PW; ++p)
-#pragma unroll
-                for (int di = 0; di < 3; ++di)
-#pragma unroll
-                    for (int sgm = 0; sgm < 3; ++sgm)
-                        win[p][di][sgm] = *reinterpret_cast<const floatx4 *>(pb[p] + base + di * Wp + 4 * (sgm - 1));
-            tsum += (a4.x + a4.y) + (a4.z + a4.w);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-#pragma unroll
-                for (int p = 0; p < PW; ++p)
-#pragma unroll
-                    for (int l = 0; l < C3_LAGS; ++l) {
-                        const int di = l < 3 ? 0 : (l < 8 ? 1 : 2);
-                        const int dj = l < 3 ? l : (l < 8 ? l - 5 : l - 10);
-                        const int idx = e + dj + 4;                       // 2 .. 9 inside the 12-pixel window
-                        acc[p][l] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[e], win[p][di][idx >> 2][idx & 3], acc[p][l], 0, 0, 0);
-                    }
+            for (int di = 0; di < 3; ++di) {
+                const float *q = pb[p] + base + di * Wp;
+                if (di > 0) wlo[set][di] = *reinterpret_cast<const floatx2 *>(q - 2);
+                wmid[set][di] = *reinterpret_cast<const floatx4 *>(q);
+                whi[set][di] = *reinterpret_cast<const floatx2 *>(q + 4);
             }
+        };
+        auto products = [&](int set, int p) {
+            if (p == 0) tsum += (a4[set].x + a4[set].y) + (a4[set].z + a4[set].w);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int l = 0; l < C3_LAGS; ++l) {
+                    const int di = l < 3 ? 0 : (l < 8 ? 1 : 2);
+                    const int dj = l < 3 ? l : (l < 8 ? l - 5 : l - 10);
+                    const int idx = e + dj;                           // -2 .. 5 relative to the lane's first pixel
+                    const float bv = idx < 0 ? wlo[set][di][idx + 2] : (idx < 4 ? wmid[set][di][idx] : whi[set][di][idx - 4]);
+                    acc[p][l] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[set][e], bv, acc[p][l], 0, 0, 0);
+                }
+        };
+        int row = row0, col = col0;
+        auto advance = [&]() {                                  // next group of this wavefront
             col += 16 * KS;
             while (col >= W) { col -= W; ++row; }
+            return row * Wp + col;
+        };
+        int base = row * Wp + col;
+        if (nstages > 0) load(0, base, 0);      // a wavefront without a group has no valid address to read
+        for (int s = 0; s < nstages; s += 2) {
+            // stage s sits in set 0; with two B tiles per wavefront stage s + 1 is the same group, second tile.
+            // The reads are unconditional (past the last stage they repeat a valid address and are dropped):
+            // reads under a branch of their own would be moved down to the products that use them.
+            const bool more1 = s + 1 < nstages, more2 = s + 2 < nstages;
+            if (PW == 1 && more1) base = advance();
+            load(1, base, PW - 1);
+            products(0, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 9, 0);      // the nine reads first,
+            __builtin_amdgcn_sched_group_barrier(0x008, 52, 0);     // then the products of the other set
+            if (more1) {
+                if (more2) base = advance();
+                load(0, base, 0);
+                products(1, PW - 1);
+                __builtin_amdgcn_sched_group_barrier(0x100, 9, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 52, 0);
+            }
         }
     }
 
