@@ -27,9 +27,15 @@ struct GemmProb {
     float gamma;
 };
 
+// A launch covers up to kMaxGemmProblems products (a 14 KB kernel argument): the preconditioning of a whole
+// network is then two launches, and the k-loop latency of a small product is paid once, not once per group of
+// layers.  The first block of every product sits in a compact array of its own, searched by bisection.
+constexpr int kMaxGemmProblems = 128;
+
 struct GemmTable {
     int count;
-    GemmProb p[kMaxProblems];
+    int starts[kMaxGemmProblems];
+    GemmProb p[kMaxGemmProblems];
 };
 
 template <class T>
@@ -42,8 +48,12 @@ __global__ __launch_bounds__(T::NT) void gemm_tn_kernel(const GemmTable tab)
     const int wave = tid >> 6;
     const int wm = wave / T::NW, wn = wave % T::NW;
 
-    int pi = 0;
-    while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].blk_start) ++pi;
+    int pi = 0, hi = tab.count - 1;
+    while (pi < hi) {
+        const int mid = (pi + hi + 1) >> 1;
+        if ((int)blockIdx.x >= tab.starts[mid]) pi = mid;
+        else hi = mid - 1;
+    }
     const GemmProb &pr = tab.p[pi];
     const int local = blockIdx.x - pr.blk_start;
     int bi, bj;
@@ -217,6 +227,29 @@ hipError_t gemm_launch(const GemmJob *jobs, int n, hipStream_t s)
             cfg[i] = choose_bm(jobs[i].M, jobs[i].N, jobs[i].mode == kSubLowerSkip);
         }
     }
+    {   // a small call is bound by its launches, not by its flops: one tile shape for all its products then
+        double flops = 0.0, cost[4] = {0.0, 0.0, 0.0, 0.0};
+        int used = 0;
+        for (int i = 0; i < n; ++i) {
+            const GemmJob &j = jobs[i];
+            if (cfg[i] < 0 || j.mode == kSubLowerSkip) continue;      // the update products keep their own tile
+            if (j.M <= 0 || j.N <= 0 || j.K <= 0) continue;
+            used |= 1 << cfg[i];
+            flops += 2.0 * j.M * j.N * j.K;
+            for (int c = 0; c < 4; ++c) {
+                const long bm = kBms[c];
+                const long tm = (j.M + bm - 1) / bm, tn = (j.N + bm - 1) / bm;
+                cost[c] += (double)tm * tn * bm * bm * (bm >= 128 ? 1.0 : (bm >= 64 ? 1.15 : 1.4)) * j.K;
+            }
+        }
+        if (!tuning().gemm_bm && (used & (used - 1)) != 0 && flops < 8e9) {
+            int best = 0;
+            for (int c = 1; c < 4; ++c)
+                if (cost[c] < cost[best]) best = c;
+            for (int i = 0; i < n; ++i)
+                if (cfg[i] >= 0 && jobs[i].mode != kSubLowerSkip) cfg[i] = best;
+        }
+    }
     if (!wave.empty()) {
         // deepest products first: launches of similar depth, and the long workgroups start early
         std::stable_sort(wave.begin(), wave.end(), [&](int a, int b) { return jobs[a].K > jobs[b].K; });
@@ -252,13 +285,14 @@ hipError_t gemm_launch(const GemmJob *jobs, int n, hipStream_t s)
             p.tm = (j.M + bm - 1) / bm;
             p.tn = (j.N + bm - 1) / bm;
             p.blk_start = blocks;
+            tab.starts[tab.count - 1] = blocks;
             p.mode = j.mode;
             p.p0 = j.p0; p.p1 = j.p1;
             p.rv = j.rv; p.cv = j.cv; p.gamma = j.gamma;
             p.vecA = (((uintptr_t)j.A) % 16 == 0 && j.lda % 4 == 0) ? 1 : 0;
             p.vecB = (((uintptr_t)j.B) % 16 == 0 && j.ldb % 4 == 0) ? 1 : 0;
             blocks += (j.mode == kSubLowerSkip) ? p.tm * (p.tm + 1) / 2 : p.tm * p.tn;
-            if (tab.count == kMaxProblems) {
+            if (tab.count == kMaxGemmProblems) {
                 hipError_t e = flush();
                 if (e != hipSuccess) return e;
             }

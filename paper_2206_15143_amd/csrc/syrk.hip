@@ -434,6 +434,7 @@ void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<
             const size_t parts = (size_t)p.splits * (C == 16 ? 4 : 1);
             const size_t nF = (size_t)C3_LAGS * C * C, nB = (size_t)C3_BQ * C * C + (size_t)C3_BV * C;
             p.partial_floats = parts * (nF + C) + (nF + C) + (size_t)C3_CHUNKS * nB + nB + 64 +
+                               nF + (size_t)C3_BQ * C * C +                        // transposed copies
                                (size_t)(job.K / job.hw) * 2 * C * job.h;          // + border columns
         }
         return;
@@ -573,6 +574,7 @@ hipError_t corr3_launch_nt(CorrTable &tab, const std::vector<size_t> &lds, doubl
     size_t lds_bytes = 0;
     for (int k = 0; k < tab.count; ++k) {
         tab.p[k].blk_start = blocks;
+        tab.starts[k] = blocks;
         blocks += tab.p[k].splits * (NT == 4 ? 2 : 1);   // 64 channels: two workgroups per range of units
         lds_bytes = std::max(lds_bytes, lds[k]);
     }
@@ -591,6 +593,7 @@ hipError_t corr3_launch_nt(CorrTable &tab, const std::vector<size_t> &lds, doubl
     blocks = 0;
     for (int k = 0; k < tab.count; ++k) {
         tab.p[k].blk_start = blocks;
+        tab.starts[k] = blocks;
         blocks += 5 * C3_CHUNKS;
     }
     KFAC_LAUNCH(KFAC_K_CORR3_ASM, s, (corr3_border_kernel<NT>), dim3(blocks), dim3(256), 0, tab);
@@ -624,7 +627,9 @@ hipError_t corr3_launch(const FactorJob *jobs, const std::vector<int> &g, const 
         p.Fs = p.Fp + (size_t)p.parts * (nF + C);
         p.Bp = p.Fs + (nF + C);
         p.Bs = p.Bp + (size_t)C3_CHUNKS * nB;
-        p.cols = p.Bs + nB;
+        p.FsT = p.Bs + nB;
+        p.BsT = p.FsT + nF;
+        p.cols = p.BsT + (size_t)C3_BQ * C * C;
         p.blk_start = 0;
         lds[k] = (size_t)2 * C * p.plane * sizeof(float);
     }
@@ -638,6 +643,7 @@ hipError_t corr3_launch(const FactorJob *jobs, const std::vector<int> &g, const 
     for (int k = 0; k < tab.count; ++k) {
         const CorrProb &p = tab.p[k];
         tab.p[k].blk_start = blocks;
+        tab.starts[k] = blocks;
         const long total = (long)(C3_LAGS + C3_BQ) * p.C * p.C + (long)(1 + C3_BV) * p.C;
         blocks += (int)((total + 255) / 256);
     }
@@ -649,8 +655,8 @@ hipError_t corr3_launch(const FactorJob *jobs, const std::vector<int> &g, const 
     for (int k = 0; k < tab.count; ++k) {
         const CorrProb &p = tab.p[k];
         tab.p[k].blk_start = blocks;
-        const int nt = (9 * p.C + p.has_bias + 15) / 16;
-        blocks += nt * (nt + 1) / 2;
+        tab.starts[k] = blocks;
+        blocks += (3 * p.C + p.has_bias + C3_ARW - 1) / C3_ARW;       // one wavefront per channel and kernel row (+ the bias row)
     }
     KFAC_LAUNCH(KFAC_K_CORR3_ASM, s, corr3_assemble_kernel, dim3(blocks), dim3(256), 0, tab);
     return hipGetLastError();

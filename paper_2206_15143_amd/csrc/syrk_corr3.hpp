@@ -35,6 +35,7 @@ struct CorrProb {
     float *Fs;         // [13][C][C] + [C]: summed over the parts
     float *Bp;         // [chunks][16][C][C], then [chunks][8][C]
     float *Bs;         // [16][C][C] + [8][C]: summed over the chunks
+    float *FsT, *BsT;  // the matrices of Fs and Bs transposed ([l][c'][c]): the assembly reads both orders along rows
     float *cols;       // [B][2][C][H]: first and last image column, written by the main kernel for the border kernel
     float *F;          // factor [dF, dF], dF = 9 C + has_bias
     int C, H, W, B;
@@ -50,14 +51,19 @@ struct CorrProb {
 
 struct CorrTable {
     int count;
+    int starts[kMaxProblems];     // blk_start of every problem, compact: searched by bisection
     CorrProb p[kMaxProblems];
 };
 
 __device__ __forceinline__ int corr_locate(const CorrTable &tab, int blk)
 {
-    int pi = 0;
-    while (pi + 1 < tab.count && blk >= tab.p[pi + 1].blk_start) ++pi;
-    return pi;
+    int lo = 0, hi = tab.count - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (blk >= tab.starts[mid]) lo = mid;
+        else hi = mid - 1;
+    }
+    return lo;
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -449,7 +455,10 @@ __global__ __launch_bounds__(256) void corr3_sum_kernel(const CorrTable tab)
 #pragma unroll
             for (int j = 0; j < 8; ++j) a[j] += pr.Fp[(long)(p + j) * nF + e];
         for (; p < pr.parts; ++p) a[0] += pr.Fp[(long)p * nF + e];
-        pr.Fs[e] = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
+        const float sum = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
+        pr.Fs[e] = sum;
+        const int cc = C * C, l = (int)(e / cc), rem = (int)(e - (long)l * cc), c = rem / C, c2 = rem - c * C;
+        pr.FsT[(long)l * cc + c2 * C + c] = sum;
     } else if (e < nF + C) {
         const long c = e - nF;
         float s = 0.f;
@@ -460,6 +469,8 @@ __global__ __launch_bounds__(256) void corr3_sum_kernel(const CorrTable tab)
         float s = 0.f;
         for (int k = 0; k < C3_CHUNKS; ++k) s += pr.Bp[(long)k * nB + i];
         pr.Bs[i] = s;
+        const int cc = C * C, l = (int)(i / cc), rem = (int)(i - (long)l * cc), c = rem / C, c2 = rem - c * C;
+        pr.BsT[(long)l * cc + c2 * C + c] = s;
     } else if (e < nF + C + nB + C3_BV * C) {
         const long i = e - nF - C - nB;
         float s = 0.f;
@@ -468,69 +479,115 @@ __global__ __launch_bounds__(256) void corr3_sum_kernel(const CorrTable tab)
     }
 }
 
-// A[u][v] for one 16 x 16 sub-tile of the lower triangle per workgroup: assembly from the lag matrices and
-// the border terms, scale, running average; the mirror image goes through LDS so that both stores run along rows.
-__global__ __launch_bounds__(256) void corr3_assemble_kernel(const CorrTable tab)
+// Assembly of A from the lag matrices and the border terms, with scale and running average.  A wavefront
+// takes three rows of A (input channel c, kernel row i), lane c2 their entries for the channel pair (c, c2):
+// every lag matrix and border matrix is read once at [c][c2] and once at [c2][c] (F(-d)[c][c'] = F(d)[c'][c]; the
+// summation kernel leaves a transposed copy, so both reads run along rows),
+// and which of them enters element ((i,j), (i',j')) is known at compile time.  The nine values of a lane per
+// row go to an LDS strip and are read back along the row of A, so the old factor is read and the new one
+// stored in whole rows; both triangles are computed, nothing is stored transposed.  The wavefront after the
+// last channel writes the bias row.
+constexpr int C3_ARW = 4;          // row triples (wavefronts) per workgroup
+
+template <int I>
+__device__ __forceinline__ void corr3_assemble_rows(const CorrProb &pr, int c, int lane, float *st)
 {
-    __shared__ float mir[16][17];
-    const CorrProb &pr = tab.p[corr_locate(tab, blockIdx.x)];
-    const int C = pr.C, H = pr.H, W = pr.W;
-    const int d = 9 * C, dF = d + pr.has_bias;
-    int bi, bj;
-    tri_decode(blockIdx.x - pr.blk_start, bi, bj);
-    const int t = threadIdx.x;
-    const int u = 16 * bi + (t >> 4), v = 16 * bj + (t & 15);
+    const int C = pr.C, d = 9 * C, dF = d + pr.has_bias;
     const float *Fs = pr.Fs, *Ts = pr.Fs + (long)C3_LAGS * C * C;
     const float *Bs = pr.Bs, *Bv = pr.Bs + (long)C3_BQ * C * C;
-    const float wnew = (1.0f - pr.decay) * pr.scale;
-    float out = 0.f;
-    if (u < dF && v <= u) {
-        float val;
-        if (u == d) {
-            if (v == d) {
-                val = (float)((long)pr.B * H * W);
-            } else {
-                // column sum of patch column (c, i, j): all pixels minus the removed row / column plus the corner
-                const int c = v / 9, ij = v - 9 * c, i = ij / 3, j = ij - 3 * i;
-                val = Ts[c];
-                if (i != 1) val -= Bv[(i == 0 ? 1 : 0) * C + c];
-                if (j != 1) val -= Bv[(j == 0 ? 3 : 2) * C + c];
-                if (i != 1 && j != 1) val += Bv[(4 + (i == 0 ? 2 : 0) + (j == 0 ? 1 : 0)) * C + c];
-            }
-        } else {
-            const int c = u / 9, ij = u - 9 * c, i = ij / 3, j = ij - 3 * i;
-            const int c2 = v / 9, ij2 = v - 9 * c2, i2 = ij2 / 3, j2 = ij2 - 3 * i2;
-            int di = i2 - i, dj = j2 - j;
-            int ca = c, cb = c2;
-            if (di < 0 || (di == 0 && dj < 0)) { di = -di; dj = -dj; ca = c2; cb = c; }   // F(-d)[c][c'] = F(d)[c'][c]
-            const int l = di == 0 ? dj : (di == 1 ? 5 + dj : 10 + dj);
-            val = Fs[((long)l * C + ca) * C + cb];
-            if (i2 == i && i != 1) {
-                // removed row a* = H-1 (i = 0) or 0 (i = 2); lag dj = j2 - j along the row
-                const int side = i == 0 ? 1 : 0;
-                const int lag = j2 - j;
-                val -= lag >= 0 ? Bs[((long)(3 * side + lag) * C + c) * C + c2]
-                                : Bs[((long)(3 * side - lag) * C + c2) * C + c];
+    const float wnew = (1.0f - pr.decay) * pr.scale, decay = pr.decay;
+    const int c2 = lane < C ? lane : 0;                              // idle lanes repeat a valid address
+    // the old rows (clamped addresses: no branch, all loads in flight at once) and the bias column entries:
+    // column sum of patch column (c, I, j) = all pixels minus the removed row / column plus the corner
+    float old[3][9], oldb[3];
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+        const float *row = pr.F + (long)(9 * c + 3 * I + j) * dF;
+#pragma unroll
+        for (int k = 0; k < 9; ++k) old[j][k] = row[min(lane + 64 * k, dF - 1)];
+        float t = Ts[c];
+        if (I != 1) t -= Bv[(I == 0 ? 1 : 0) * C + c];
+        if (j != 1) t -= Bv[(j == 0 ? 3 : 2) * C + c];
+        if (I != 1 && j != 1) t += Bv[(4 + (I == 0 ? 2 : 0) + (j == 0 ? 1 : 0)) * C + c];
+        oldb[j] = decay * row[dF - 1] + wnew * t;
+    }
+    float Fp[C3_LAGS], Fn[C3_LAGS], Rp[4][3], Rn[4][3], Cq[4];
+#pragma unroll
+    for (int l = 0; l < C3_LAGS; ++l) {
+        Fp[l] = Fs[((long)l * C + c) * C + c2];
+        Fn[l] = pr.FsT[((long)l * C + c) * C + c2];
+    }
+#pragma unroll
+    for (int sd = 0; sd < 4; ++sd)
+#pragma unroll
+        for (int lag = 0; lag < 3; ++lag) {
+            Rp[sd][lag] = Bs[((long)(3 * sd + lag) * C + c) * C + c2];
+            Rn[sd][lag] = pr.BsT[((long)(3 * sd + lag) * C + c) * C + c2];
+        }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) Cq[q] = Bs[((long)(12 + q) * C + c) * C + c2];
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+#pragma unroll
+        for (int ij2 = 0; ij2 < 9; ++ij2) {
+            const int i2 = ij2 / 3, j2 = ij2 - 3 * i2;
+            const int di = i2 - I, dj = j2 - j;
+            const bool pos = di > 0 || (di == 0 && dj >= 0);
+            const int adi = pos ? di : -di, adj = pos ? dj : -dj;
+            const int l = adi == 0 ? adj : (adi == 1 ? 5 + adj : 10 + adj);
+            float val = pos ? Fp[l] : Fn[l];
+            if (i2 == I && I != 1) {          // removed row a* = H-1 (i = 0) or 0 (i = 2); lag j2 - j along the row
+                const int sd = I == 0 ? 1 : 0;
+                val -= dj >= 0 ? Rp[sd][dj >= 0 ? dj : 0] : Rn[sd][dj < 0 ? -dj : 0];
             }
             if (j2 == j && j != 1) {
-                const int side = j == 0 ? 3 : 2;
-                const int lag = i2 - i;
-                val -= lag >= 0 ? Bs[((long)(3 * side + lag) * C + c) * C + c2]
-                                : Bs[((long)(3 * side - lag) * C + c2) * C + c];
+                const int sd = j == 0 ? 3 : 2;
+                val -= di >= 0 ? Rp[sd][di >= 0 ? di : 0] : Rn[sd][di < 0 ? -di : 0];
             }
-            if (i2 == i && i != 1 && j2 == j && j != 1)
-                val += Bs[((long)(12 + (i == 0 ? 2 : 0) + (j == 0 ? 1 : 0)) * C + c) * C + c2];
+            if (i2 == I && I != 1 && j2 == j && j != 1) val += Cq[(I == 0 ? 2 : 0) + (j == 0 ? 1 : 0)];
+            if (lane < C) st[9 * lane + ij2] = val;
         }
-        out = pr.decay * pr.F[(long)u * dF + v] + wnew * val;
-        pr.F[(long)u * dF + v] = out;
+        __builtin_amdgcn_wave_barrier();       // LDS serves a wavefront's accesses in order: the reads below see the row
+        float *row = pr.F + (long)(9 * c + 3 * I + j) * dF;
+#pragma unroll
+        for (int k = 0; k < 9; ++k)
+            if (lane + 64 * k < d) row[lane + 64 * k] = decay * old[j][k] + wnew * st[lane + 64 * k];
+        if (pr.has_bias && lane == 0) row[d] = oldb[j];
+        __builtin_amdgcn_wave_barrier();
     }
-    mir[t >> 4][t & 15] = out;
-    __syncthreads();
-    {
-        const int c2 = t >> 4, r2 = t & 15;
-        const int u2 = 16 * bi + r2, v2 = 16 * bj + c2;
-        if (u2 < dF && v2 < u2) pr.F[(long)v2 * dF + u2] = mir[r2][c2];
+}
+
+__global__ __launch_bounds__(256) void corr3_assemble_kernel(const CorrTable tab)
+{
+    __shared__ float strip[C3_ARW][9 * 64 + 4];
+    const CorrProb &pr = tab.p[corr_locate(tab, blockIdx.x)];
+    const int C = pr.C, d = 9 * C, dF = d + pr.has_bias;
+    const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int rt = C3_ARW * (blockIdx.x - pr.blk_start) + w;         // row triple: the same for the whole wavefront
+    const int c = rt / 3, i = rt - 3 * c;
+    if (c > C || (c == C && (i > 0 || !pr.has_bias))) return;
+    if (c == C) {
+        const float *Ts = pr.Fs + (long)C3_LAGS * C * C, *Bv = pr.Bs + (long)C3_BQ * C * C;
+        const float wnew = (1.0f - pr.decay) * pr.scale;
+        float *row = pr.F + (long)d * dF;
+        for (int x = lane; x < dF; x += 64) {
+            float val;
+            if (x == d) {
+                val = (float)((long)pr.B * pr.H * pr.W);
+            } else {
+                const int cc = x / 9, ij = x - 9 * cc, ii = ij / 3, jj = ij - 3 * ii;
+                val = Ts[cc];
+                if (ii != 1) val -= Bv[(ii == 0 ? 1 : 0) * C + cc];
+                if (jj != 1) val -= Bv[(jj == 0 ? 3 : 2) * C + cc];
+                if (ii != 1 && jj != 1) val += Bv[(4 + (ii == 0 ? 2 : 0) + (jj == 0 ? 1 : 0)) * C + cc];
+            }
+            row[x] = pr.decay * row[x] + wnew * val;
+        }
+        return;
     }
+    if (i == 0) corr3_assemble_rows<0>(pr, c, lane, strip[w]);
+    else if (i == 1) corr3_assemble_rows<1>(pr, c, lane, strip[w]);
+    else corr3_assemble_rows<2>(pr, c, lane, strip[w]);
 }
 
 }  // namespace kfac
