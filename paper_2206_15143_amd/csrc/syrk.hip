@@ -589,15 +589,32 @@ hipError_t corr3_launch_nt(CorrTable &tab, const std::vector<size_t> &lds, doubl
     timing_work(flops);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    // border terms: 5 sides x image chunks per layer
-    blocks = 0;
+    // border terms: small maps of at least 32 channels from whole images (the problems of a launch share a
+    // shape class, not a shape: both kernels may run, each on its own table)
+    CorrTable line_tab, plane_tab;
+    line_tab.count = plane_tab.count = 0;
+    int line_blocks = 0, plane_blocks = 0;
     for (int k = 0; k < tab.count; ++k) {
-        tab.p[k].blk_start = blocks;
-        tab.starts[k] = blocks;
-        blocks += 5 * C3_CHUNKS;
+        const bool plane = NT >= 2 && tab.p[k].H * tab.p[k].W <= 64;
+        CorrTable &t = plane ? plane_tab : line_tab;
+        int &nb = plane ? plane_blocks : line_blocks;
+        t.p[t.count] = tab.p[k];
+        t.p[t.count].blk_start = nb;
+        t.starts[t.count] = nb;
+        ++t.count;
+        nb += plane ? C3_CHUNKS * (NT * NT / 4) : 5 * C3_CHUNKS;      // line kernel: 5 sides x image chunks
     }
-    KFAC_LAUNCH(KFAC_K_CORR3_ASM, s, (corr3_border_kernel<NT>), dim3(blocks), dim3(256), 0, tab);
-    return hipGetLastError();
+    if (line_tab.count > 0) {
+        KFAC_LAUNCH(KFAC_K_CORR3_ASM, s, (corr3_border_kernel<NT>), dim3(line_blocks), dim3(256), 0, line_tab);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (NT >= 2 && plane_tab.count > 0) {
+        KFAC_LAUNCH(KFAC_K_CORR3_ASM, s, (corr3_border_plane_kernel<(NT >= 2 ? NT : 2)>), dim3(plane_blocks), dim3(256), 0,
+                    plane_tab);
+        e = hipGetLastError();
+    }
+    return e;
 }
 
 hipError_t corr3_launch(const FactorJob *jobs, const std::vector<int> &g, const std::vector<Planned> &pl,

@@ -440,6 +440,132 @@ __global__ __launch_bounds__(256) void corr3_border_kernel(const CorrTable tab)
     }
 }
 
+// Border terms of small maps (H * W <= 64, 32 or 64 channels), where rows, columns and corners together are a
+// large part of every plane and gathering them side by side pulls the input several times over: a workgroup
+// stages whole images (contiguous, read once per group of channel-tile pairs) and takes all sixteen border
+// matrices from LDS.  One workgroup per (layer, image chunk, group of four tile pairs), one pair per wavefront;
+// the loads of two images are in flight.
+// Cells past the end of a line are masked in the operand, not padded.
+template <int NT>
+__global__ __launch_bounds__(256) void corr3_border_plane_kernel(const CorrTable tab)
+{
+    constexpr int C = 16 * NT;
+    constexpr int NG = NT * NT / 4;                   // groups of four tile pairs
+    constexpr int PL = 64 + 4;                        // cells per channel plane in LDS
+    constexpr int DEPTH = 2;                          // images whose loads are in flight (more would cost a wavefront per SIMD)
+    __shared__ __align__(16) float img[C * PL];
+
+    const CorrProb &pr = tab.p[corr_locate(tab, blockIdx.x)];
+    const int local = blockIdx.x - pr.blk_start;
+    const int ch = local / NG, pg = local - ch * NG;
+    const int per = (pr.B + C3_CHUNKS - 1) / C3_CHUNKS;
+    const int n0 = ch * per, n1 = min(pr.B, n0 + per);
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lr = lane & 15, kk = lane >> 4;
+    const int H = pr.H, W = pr.W, HW = H * W;
+    const int pair = 4 * pg + w, ct = pair / NT, ctp = pair - ct * NT;
+    float *Bm = pr.Bp + (long)ch * (C3_BQ * C * C);
+    float *Bv = pr.Bp + (long)C3_CHUNKS * (C3_BQ * C * C) + (long)ch * (C3_BV * C);
+
+    // what this thread moves per image: float4 f of the image -> plane c, cell p
+    int gofs[NT], lofs[NT];
+#pragma unroll
+    for (int k = 0; k < NT; ++k) {
+        const int e = 4 * (tid + 256 * k);
+        gofs[k] = -1;
+        lofs[k] = 0;
+        if (e < C * HW) {
+            const int c = e / HW;
+            gofs[k] = e;
+            lofs[k] = c * PL + (e - c * HW);
+        }
+    }
+    floatx4 regs[DEPTH][NT];
+    auto fetch = [&](int j, int n) {
+        const float *src = pr.x + (long)n * C * HW;
+#pragma unroll
+        for (int k = 0; k < NT; ++k) regs[j][k] = *reinterpret_cast<const floatx4 *>(src + (gofs[k] >= 0 ? gofs[k] : 0));
+    };
+    // matrices: 3 * side + lag for the sides row 0, row H-1, column 0, column W-1, then the four corners;
+    // vectors: the four sides, then the four corners
+    floatx4 acc[C3_BQ];
+    float vs[C3_BV];
+#pragma unroll
+    for (int m = 0; m < C3_BQ; ++m) acc[m] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int m = 0; m < C3_BV; ++m) vs[m] = 0.f;
+    const float *pa = img + (16 * ct + lr) * PL;
+    const float *pb = img + (16 * ctp + lr) * PL;
+
+    // one k-step of the two sides of a direction: position p = 4 ks + kk of the line, cells org + p * step
+    auto lines = [&](int L, int step, int org1, int m0, int v0) {
+        const int nks = (L + 3) / 4;
+#pragma unroll 2
+        for (int ks = 0; ks < nks; ++ks) {
+            const int p = 4 * ks + kk;
+            const int c0 = min(p, L - 1) * step, c1 = min(p + 1, L - 1) * step, c2 = min(p + 2, L - 1) * step;
+            // all eight operand cells first, then the six products; cells past the end of the line are masked
+            const float a0 = pa[c0], b00 = pb[c0], b01 = pb[c1], b02 = pb[c2];
+            const float a1 = pa[org1 + c0], b10 = pb[org1 + c0], b11 = pb[org1 + c1], b12 = pb[org1 + c2];
+            const bool in0 = p < L, in1 = p + 1 < L, in2 = p + 2 < L;
+            const float a0m = in0 ? a0 : 0.f, a1m = in0 ? a1 : 0.f;
+            vs[v0] += a0m;
+            vs[v0 + 1] += a1m;
+            acc[m0 + 0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0m, in0 ? b00 : 0.f, acc[m0 + 0], 0, 0, 0);
+            acc[m0 + 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0m, in1 ? b01 : 0.f, acc[m0 + 1], 0, 0, 0);
+            acc[m0 + 2] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0m, in2 ? b02 : 0.f, acc[m0 + 2], 0, 0, 0);
+            acc[m0 + 3] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1m, in0 ? b10 : 0.f, acc[m0 + 3], 0, 0, 0);
+            acc[m0 + 4] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1m, in1 ? b11 : 0.f, acc[m0 + 4], 0, 0, 0);
+            acc[m0 + 5] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1m, in2 ? b12 : 0.f, acc[m0 + 5], 0, 0, 0);
+        }
+    };
+
+#pragma unroll
+    for (int j = 0; j < DEPTH; ++j)
+        if (n0 + j < n1) fetch(j, n0 + j);
+    for (int nb = n0; nb < n1; nb += DEPTH) {
+#pragma unroll
+        for (int j = 0; j < DEPTH; ++j) {
+            const int n = nb + j;
+            if (n >= n1) break;
+            __syncthreads();                          // the products on the previous image are done
+#pragma unroll
+            for (int k = 0; k < NT; ++k)
+                if (gofs[k] >= 0) *reinterpret_cast<floatx4 *>(img + lofs[k]) = regs[j][k];
+            __syncthreads();
+            if (n + DEPTH < n1) fetch(j, n + DEPTH);  // refill this register set: in flight for DEPTH images
+            float av[4], bv[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int cell = ((q & 2) ? (H - 1) * W : 0) + ((q & 1) ? W - 1 : 0);
+                av[q] = pa[cell];
+                bv[q] = pb[cell];
+            }
+            lines(W, 1, (H - 1) * W, 0, 0);           // rows 0 and H-1: k runs along the row
+            lines(H, W, W - 1, 6, 2);                 // columns 0 and W-1: k runs down the column
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                // a corner is a single cell: only k = 0 of the step carries it
+                const float a = kk == 0 ? av[q] : 0.f;
+                vs[4 + q] += a;
+                acc[12 + q] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, bv[q], acc[12 + q], 0, 0, 0);
+            }
+        }
+    }
+
+#pragma unroll
+    for (int m = 0; m < C3_BQ; ++m)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) Bm[((long)m * C + 16 * ct + 4 * kk + v) * C + 16 * ctp + lr] = acc[m][v];
+#pragma unroll
+    for (int m = 0; m < C3_BV; ++m) {
+        float sm = vs[m];
+        sm += __shfl_xor(sm, 16);
+        sm += __shfl_xor(sm, 32);
+        if (ctp == 0 && kk == 0) Bv[m * C + 16 * ct + lr] = sm;
+    }
+}
+
 // Sums over the parts (lag matrices, channel sums) and over the image chunks (border terms), fixed order.
 __global__ __launch_bounds__(256) void corr3_sum_kernel(const CorrTable tab)
 {

@@ -195,6 +195,8 @@ def test_nonsquare_layer_end_to_end(cin, kh, kw, h, w, pad, bias):
     (16, 12, 8, 9, True),
     (32, 64, 4, 2, True),       # tall and narrow
     (16, 3, 64, 2, True),       # odd height, widest map
+    (32, 2, 8, 3, True),        # small map, two rows: border terms from whole images
+    (64, 3, 16, 6, True),       # small map, odd height
 ])
 def test_conv3_factor_from_autocorrelations(cin, h, w, batch, bias):
     # 3x3 / stride 1 / pad 1 layers with 16, 32 or 64 input channels build A from 13 autocorrelation lag
