@@ -585,7 +585,7 @@ hipError_t corr3_launch_nt(CorrTable &tab, const std::vector<size_t> &lds, doubl
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    KFAC_LAUNCH(KFAC_K_SYRK_CORR3, s, (corr3_main_kernel<NT>), dim3(blocks), dim3(256), lds_bytes, tab);
+    KFAC_LAUNCH(KFAC_K_SYRK_CORR3, s, (corr3_main_kernel<NT>), dim3(blocks), dim3(512), lds_bytes, tab);
     timing_work(flops);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

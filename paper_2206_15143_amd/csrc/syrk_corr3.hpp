@@ -67,37 +67,123 @@ __device__ __forceinline__ int corr_locate(const CorrTable &tab, int blk)
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// Lag matrices.  A workgroup walks (image, strip) units: the strip of all C channels with two halo rows below
-// is staged in LDS (double buffered, the next unit's global loads in
+// Lag matrices.  A workgroup (four product and four staging wavefronts) walks (image, strip) units: the strip of
+// all C channels with two halo rows below is staged in LDS (double buffered, the next unit's global loads in
 // flight under the products) with four zero columns left and right; the A operand of a k-step is channel tile
 // ct at four pixels, the B operand channel tile ct' at the pixels shifted by the lag.
-//   NT = 1 (C = 16): one tile pair; the four wavefronts take every fourth k-step (four parts per block).
-//   NT = 2 (C = 32): four tile pairs, one per wavefront.
-//   NT = 4 (C = 64): wavefront w = A tile w and two of the four B tiles; two workgroups share a range of units
-//   (all 52 lag tiles per wavefront would leave one wavefront per SIMD).
+//   NT = 1 (C = 16): one tile pair; the four product wavefronts take every fourth group (four parts per block).
+//   NT = 2 (C = 32): four tile pairs, one per product wavefront.
+//   NT = 4 (C = 64): product wavefront w = A tile w and two of the four B tiles; two workgroups share a range of
+//   units (all 52 lag tiles per wavefront would leave one wavefront per SIMD).
 template <int NT>
-__global__ __launch_bounds__(256) void corr3_main_kernel(const CorrTable tab)
+__global__ __launch_bounds__(512) void corr3_main_kernel(const CorrTable tab)
 {
     extern __shared__ __align__(16) float corr_lds[];
     constexpr int C = 16 * NT;
     constexpr int KS = NT == 1 ? 4 : 1;        // wavefronts that split the pixel groups
     constexpr int PW = NT == 4 ? 2 : 1;        // B tiles per wavefront
     constexpr int HALVES = NT == 4 ? 2 : 1;    // workgroups that share a range of units (each takes half the B tiles)
-    constexpr int MAXI = 6;                    // float4 items per thread and slab at most (checked by the planner)
-    constexpr int SCI = 2;                     // border-column cells per thread with a precomputed address
+    constexpr int MAXI = 6;                    // float4 items per staging thread and slab at most (checked by the planner)
+    constexpr int SCI = 2;                     // border-column cells per staging thread with a precomputed address
 
     const CorrProb &pr = tab.p[corr_locate(tab, blockIdx.x)];
     const int blk_raw = blockIdx.x - pr.blk_start;
     const int blk = blk_raw / HALVES, half = blk_raw - blk * HALVES;
     const int u0 = blk * pr.upb, u1 = min(pr.units, u0 + pr.upb);
-    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int lr = lane & 15, kk = lane >> 4;
+    const int lane = threadIdx.x & 63, w8 = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int H = pr.H, W = pr.W, Wp = W + 8, SR = pr.SR, plane = pr.plane, w4 = W >> 2;
     float *buf0 = corr_lds, *buf1 = corr_lds + C * plane;
 
-    for (int i = tid; i < 2 * C * plane; i += 256) corr_lds[i] = 0.f;   // the pad cells are never written again
+    for (int i = threadIdx.x; i < 2 * C * plane; i += 512) corr_lds[i] = 0.f;   // the pad cells are never written again
     __syncthreads();
 
+    // Wavefronts 4 .. 7 stage the slabs, wavefronts 0 .. 3 only read operands and issue products.  Workgroups
+    // that share a CU advance at the same pace (the MFMA unit alternates between their wavefronts), so staging
+    // done by the product wavefronts themselves would fall into the same moments in all of them and leave the
+    // MFMA unit idle; as wavefronts of their own the loads, LDS stores and address arithmetic run beside it.
+    // One barrier per unit: past barrier `it` the slab of unit `it` is complete and every product wavefront is
+    // done with unit it - 1, whose buffer the staging wavefronts then fill with unit it + 1.
+    if (w8 >= 4) {
+        const int tid = threadIdx.x - 256;
+        // what this thread moves per slab is the same for every unit: offset inside the (image, strip) window
+        // of the input (-1: nothing), and the LDS offset with the slab row above bit 20
+        const int rows = SR + 2;
+        const int items = C * rows * w4;
+        int gofs[MAXI], lofs[MAXI];
+#pragma unroll
+        for (int k = 0; k < MAXI; ++k) {
+            const int e = tid + 256 * k;
+            gofs[k] = -1;
+            lofs[k] = 0;
+            if (e < items) {
+                const int c = e / (rows * w4), rem = e - c * (rows * w4);
+                const int r = rem / w4, g = rem - r * w4;
+                gofs[k] = (c * H + r) * W + 4 * g;
+                lofs[k] = (c * plane + r * Wp + 4 + 4 * g) | (r << 20);
+            }
+        }
+        floatx4 regs[MAXI];
+        auto fetch = [&](int u) {                  // loads only: nothing here may wait for them
+            const int n = u / pr.strips, a0 = (u - n * pr.strips) * SR;
+            const float *win0 = pr.x + (long)n * C * H * W + (long)a0 * W;
+#pragma unroll
+            for (int k = 0; k < MAXI; ++k) {
+                const bool ok = gofs[k] >= 0 && a0 + (lofs[k] >> 20) < H;
+                regs[k] = *reinterpret_cast<const floatx4 *>(win0 + (ok ? gofs[k] : 0));
+            }
+        };
+        auto commit = [&](float *b, int u) {
+            // unconditional stores: rows below the image are stored as zeros, and an item that does not exist
+            // stores zeros to the first pad cell of the slab, which holds zeros anyway
+            const int a0 = (u % pr.strips) * SR;
+#pragma unroll
+            for (int k = 0; k < MAXI; ++k) {
+                const bool ok = gofs[k] >= 0 && a0 + (lofs[k] >> 20) < H;
+                *reinterpret_cast<floatx4 *>(b + (lofs[k] & 0xfffff)) = ok ? regs[k] : floatx4{0.f, 0.f, 0.f, 0.f};
+            }
+        };
+        // the first and the last pixel of every image row also go to a compact buffer (the border kernel would
+        // otherwise pull a whole cache line per pixel of those two columns): read back from the slab,
+        // consecutive threads = consecutive rows of a channel
+        int sc_l[SCI], sc_g[SCI];
+#pragma unroll
+        for (int j = 0; j < SCI; ++j) {
+            const int t = tid + 256 * j;
+            sc_l[j] = -1;
+            sc_g[j] = 0;
+            if (NT != 4 && t < 2 * C * SR) {
+                const int side = t / (C * SR), rem = t - side * (C * SR);
+                const int c = rem / SR, r = rem - c * SR;
+                sc_l[j] = c * plane + r * Wp + 4 + (side ? W - 1 : 0);
+                sc_g[j] = (side * C + c) * H + r;
+            }
+        }
+        auto save_cols = [&](const float *b, int u) {
+            if (NT == 4) return;             // 64 channels: short columns, the border kernel reads them from the input
+            const int n = u / pr.strips, a0 = (u - n * pr.strips) * SR;
+            float *cbase = pr.cols + (long)n * 2 * C * H + a0;
+#pragma unroll
+            for (int j = 0; j < SCI; ++j)
+                if (sc_l[j] >= 0) cbase[sc_g[j]] = b[sc_l[j]];
+            for (int t = tid + 256 * SCI; t < 2 * C * SR; t += 256) {
+                const int side = t / (C * SR), rem = t - side * (C * SR);
+                const int c = rem / SR, r = rem - c * SR;
+                cbase[(side * C + c) * H + r] = b[c * plane + r * Wp + 4 + (side ? W - 1 : 0)];
+            }
+        };
+        if (u0 < u1) fetch(u0);
+        for (int u = u0, it = 0; u < u1; ++u, ++it) {
+            float *b = (it & 1) ? buf1 : buf0;
+            commit(b, u);                       // the loads were issued a unit ago
+            if (u + 1 < u1) fetch(u + 1);
+            __syncthreads();
+            save_cols(b, u);                    // the slab stays as it is until the barrier after next
+        }
+        return;
+    }
+
+    const int w = w8;
+    const int lr = lane & 15, kk = lane >> 4;
     int ct, ctp0;
     if (NT == 1) { ct = 0; ctp0 = 0; }
     else if (NT == 2) { ct = w >> 1; ctp0 = w & 1; }
@@ -110,78 +196,11 @@ __global__ __launch_bounds__(256) void corr3_main_kernel(const CorrTable tab)
         for (int l = 0; l < C3_LAGS; ++l) acc[p][l] = floatx4{0.f, 0.f, 0.f, 0.f};
     float tsum = 0.f;
 
-    // what this thread moves per slab is the same for every unit: offset inside the (image, strip) window of
-    // the input (-1: nothing), and the LDS offset with the slab row above bit 20
-    const int rows = SR + 2;
-    const int items = C * rows * w4;
-    int gofs[MAXI], lofs[MAXI];
-#pragma unroll
-    for (int k = 0; k < MAXI; ++k) {
-        const int e = tid + 256 * k;
-        gofs[k] = -1;
-        lofs[k] = 0;
-        if (e < items) {
-            const int c = e / (rows * w4), rem = e - c * (rows * w4);
-            const int r = rem / w4, g = rem - r * w4;
-            gofs[k] = (c * H + r) * W + 4 * g;
-            lofs[k] = (c * plane + r * Wp + 4 + 4 * g) | (r << 20);
-        }
-    }
-    floatx4 regs[MAXI];
-    auto fetch = [&](int u) {                  // loads only: nothing here may wait for them
-        const int n = u / pr.strips, a0 = (u - n * pr.strips) * SR;
-        const float *win0 = pr.x + (long)n * C * H * W + (long)a0 * W;
-#pragma unroll
-        for (int k = 0; k < MAXI; ++k) {
-            const bool ok = gofs[k] >= 0 && a0 + (lofs[k] >> 20) < H;
-            regs[k] = *reinterpret_cast<const floatx4 *>(win0 + (ok ? gofs[k] : 0));
-        }
-    };
-    auto commit = [&](float *b, int u) {
-        // unconditional stores (a store skipped by a branch would leave its load unwaited for, and the next
-        // fetch would then have to wait instead): rows below the image are stored as zeros, and an item that
-        // does not exist stores zeros to the first pad cell of the slab, which holds zeros anyway
-        const int a0 = (u % pr.strips) * SR;
-#pragma unroll
-        for (int k = 0; k < MAXI; ++k) {
-            const bool ok = gofs[k] >= 0 && a0 + (lofs[k] >> 20) < H;
-            *reinterpret_cast<floatx4 *>(b + (lofs[k] & 0xfffff)) = ok ? regs[k] : floatx4{0.f, 0.f, 0.f, 0.f};
-        }
-    };
-    // the first and the last pixel of every image row also go to a compact buffer (the border kernel would
-    // otherwise pull a whole cache line per pixel of those two columns): read back from the slab after the
-    // barrier, consecutive threads = consecutive rows of a channel
-    int sc_l[SCI], sc_g[SCI];
-#pragma unroll
-    for (int j = 0; j < SCI; ++j) {
-        const int t = tid + 256 * j;
-        sc_l[j] = -1;
-        sc_g[j] = 0;
-        if (NT != 4 && t < 2 * C * SR) {
-            const int side = t / (C * SR), rem = t - side * (C * SR);
-            const int c = rem / SR, r = rem - c * SR;
-            sc_l[j] = c * plane + r * Wp + 4 + (side ? W - 1 : 0);
-            sc_g[j] = (side * C + c) * H + r;
-        }
-    }
-    auto save_cols = [&](const float *b, int u) {
-        if (NT == 4) return;             // 64 channels: short columns, the border kernel reads them from the input
-        const int n = u / pr.strips, a0 = (u - n * pr.strips) * SR;
-        float *cbase = pr.cols + (long)n * 2 * C * H + a0;
-#pragma unroll
-        for (int j = 0; j < SCI; ++j)
-            if (sc_l[j] >= 0) cbase[sc_g[j]] = b[sc_l[j]];
-        for (int t = tid + 256 * SCI; t < 2 * C * SR; t += 256) {
-            const int side = t / (C * SR), rem = t - side * (C * SR);
-            const int c = rem / SR, r = rem - c * SR;
-            cbase[(side * C + c) * H + r] = b[c * plane + r * Wp + 4 + (side ? W - 1 : 0)];
-        }
-    };
     // A group is 16 consecutive pixels of the strip (row-major); lane kk holds pixels 4 kk .. 4 kk + 3 of it and
     // k-step e of the group takes pixel 4 kk + e from every lane.  For the shifted operand a lane reads, per
-    // row lag, the 12-pixel window around its four pixels (three 16-byte reads): every lag (di, dj) of k-step e
-    // is element e + dj of the window of row di, a register chosen at compile time.
-    // A stage is one group and one B tile: 52 products on 10 operand reads.  Two register sets alternate, the
+    // row lag, the window around its four pixels: every lag (di, dj) of k-step e is element e + dj of the window
+    // of row di, a register chosen at compile time.
+    // A stage is one group and one B tile: 52 products on 9 operand reads.  Two register sets alternate, the
     // reads of the next stage are issued before the products of the current one (all wavefronts of a SIMD
     // advance at the same pace, so none of them would cover the read latency of another).
     const int ngroups = SR * W / 16;
@@ -189,13 +208,10 @@ __global__ __launch_bounds__(256) void corr3_main_kernel(const CorrTable tab)
     const int nstages = ((ngroups - gfirst + KS - 1) / KS) * PW;
     const int q0 = 16 * gfirst + 4 * kk;                       // first pixel of this lane in its first group
     const int row0 = q0 / W, col0 = q0 - row0 * W;
+    const int drow = (16 * KS) / W, dcol = 16 * KS - drow * W;  // from a group to the next of this wavefront
     for (int u = u0, it = 0; u < u1; ++u, ++it) {
         float *b = (it & 1) ? buf1 : buf0;
-        if (it == 0) fetch(u0);
-        commit(b, u);
-        __syncthreads();        // a wavefront gets here only after its products on the other buffer: one barrier per unit
-        save_cols(b, u);
-        if (u + 1 < u1) fetch(u + 1);
+        __syncthreads();
         const float *pa = b + (16 * ct + lr) * plane + 4;
         const float *pb[PW];
 #pragma unroll
@@ -228,30 +244,41 @@ __global__ __launch_bounds__(256) void corr3_main_kernel(const CorrTable tab)
                     acc[p][l] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[set][e], bv, acc[p][l], 0, 0, 0);
                 }
         };
+        // Positions run one stage ahead of the reads, which run one stage ahead of the products: no address
+        // arithmetic and no branch between the reads of a stage and the products before them.
         int row = row0, col = col0;
-        auto advance = [&]() {                                  // next group of this wavefront
-            col += 16 * KS;
-            while (col >= W) { col -= W; ++row; }
-            return row * Wp + col;
+        auto advance = [&](bool take, int base) {               // next group of this wavefront, if there is one
+            int c = col + dcol, r = row + drow;
+            const bool wrap = c >= W;
+            c -= wrap ? W : 0;
+            r += wrap ? 1 : 0;
+            col = take ? c : col;
+            row = take ? r : row;
+            return take ? r * Wp + c : base;
         };
-        int base = row * Wp + col;
-        if (nstages > 0) load(0, base, 0);      // a wavefront without a group has no valid address to read
+        const int b0 = row0 * Wp + col0;
+        if (nstages > 0) load(0, b0, 0);        // a wavefront without a group has no valid address to read
+        int b1 = PW == 1 ? advance(1 < nstages, b0) : b0;
         for (int s = 0; s < nstages; s += 2) {
             // stage s sits in set 0; with two B tiles per wavefront stage s + 1 is the same group, second tile.
             // The reads are unconditional (past the last stage they repeat a valid address and are dropped):
             // reads under a branch of their own would be moved down to the products that use them.
-            const bool more1 = s + 1 < nstages, more2 = s + 2 < nstages;
-            if (PW == 1 && more1) base = advance();
-            load(1, base, PW - 1);
+            const bool more1 = s + 1 < nstages;
+            load(1, b1, PW - 1);
+            const int b2 = advance(s + 2 < nstages, b1);
             products(0, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 9, 0);      // the nine reads first,
-            __builtin_amdgcn_sched_group_barrier(0x008, 52, 0);     // then the products of the other set
+            __builtin_amdgcn_sched_group_barrier(0x100, 9, 0);      // the reads first,
+            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);      // the address arithmetic under the products
+            __builtin_amdgcn_sched_group_barrier(0x002, 16, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 48, 0);
             if (more1) {
-                if (more2) base = advance();
-                load(0, base, 0);
+                load(0, b2, 0);
+                b1 = PW == 1 ? advance(s + 3 < nstages, b2) : b2;
                 products(1, PW - 1);
                 __builtin_amdgcn_sched_group_barrier(0x100, 9, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 52, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 16, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 48, 0);
             }
         }
     }
