@@ -174,13 +174,9 @@ constexpr int kRedGroup = 4;   // sub-tiles per block
 // NATIVE: the partial tiles are stored as the MFMA accumulators lie in registers (per 16x16 tile
 // [lane][4], tiles row-major inside the 144-wide macro tile), which lets the wave kernels store
 // 16 bytes per lane; element e of a macro tile then maps to row / column as decoded below.
-template <class T, bool NATIVE = false>
-__global__ __launch_bounds__(256) void syrk_reduce_kernel(const SyrkTable tab)
+template <class T, bool NATIVE>
+__device__ __forceinline__ void syrk_reduce_body(const SyrkProb &pr, int local, float (*mir)[16][17])
 {
-    int pi = 0;
-    while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].red_start) ++pi;
-    const SyrkProb &pr = tab.p[pi];
-    const int local = blockIdx.x - pr.red_start;
     const int nblk = pr.nb * (pr.nb + 1) / 2;
     const int dF = pr.d + pr.has_bias;
     const float wnew = (1.0f - pr.decay) * pr.scale;
@@ -191,7 +187,6 @@ __global__ __launch_bounds__(256) void syrk_reduce_kernel(const SyrkTable tab)
     if (local < nblk * GPT) {
         // kRedGroup 16 x 16 sub-tiles per block: thread t holds one element of each; all loads are issued
         // before the first store.  The mirror image goes through LDS so that both stores run along rows of F.
-        __shared__ float mir[kRedGroup][16][17];
         const int tile = local / GPT;
         const int grp = local - tile * GPT;
         int bi, bj;
@@ -284,6 +279,38 @@ __global__ __launch_bounds__(256) void syrk_reduce_kernel(const SyrkTable tab)
             const long dd = (long)pr.d * dF + pr.d;
             pr.F[dd] = pr.decay * pr.F[dd] + wnew * (float)pr.K;
         }
+    }
+}
+
+// One reduce launch for the factors of a whole call, whatever kernel produced their partial tiles: the reduce
+// of a group of layers is a few small workgroups, a launch of its own per group costs more than it runs.
+constexpr int kMaxRedProblems = 128;   // a 14 KB kernel argument
+
+struct RedTable {
+    int count;
+    int starts[kMaxRedProblems];       // first block of every problem, searched by bisection
+    int kind[kMaxRedProblems];         // partial tile layout, see the switch below
+    SyrkProb p[kMaxRedProblems];
+};
+
+__global__ __launch_bounds__(256) void syrk_reduce_kernel(const RedTable tab)
+{
+    __shared__ float mir[kRedGroup][16][17];
+    int pi = 0, hi = tab.count - 1;
+    while (pi < hi) {
+        const int mid = (pi + hi + 1) >> 1;
+        if ((int)blockIdx.x >= tab.starts[mid]) pi = mid;
+        else hi = mid - 1;
+    }
+    const SyrkProb &pr = tab.p[pi];
+    const int local = blockIdx.x - tab.starts[pi];
+    switch (tab.kind[pi]) {
+        case 0: syrk_reduce_body<Tile<4, 2>, false>(pr, local, mir); break;
+        case 1: syrk_reduce_body<Tile<3, 3>, false>(pr, local, mir); break;
+        case 2: syrk_reduce_body<Tile<2, 2>, false>(pr, local, mir); break;
+        case 3: syrk_reduce_body<Tile<1, 2>, false>(pr, local, mir); break;
+        case 4: syrk_reduce_body<Tile<3, 3>, true>(pr, local, mir); break;    // 144-wide tiles in accumulator order
+        default: syrk_reduce_body<Tile<8, 2>, false>(pr, local, mir); break;
     }
 }
 
@@ -539,27 +566,54 @@ bool vec_ok(const FactorJob &j)
 }
 
 template <class T, int LAYOUT, int DT>
-hipError_t launch_cfg(const SyrkTable &tab, int blocks, int red_blocks, double flops, double red_bytes, hipStream_t s)
+hipError_t launch_cfg(const SyrkTable &tab, int blocks, double flops, hipStream_t s)
 {
     KFAC_LAUNCH(KFAC_K_SYRK, s, (syrk_partial_kernel<T, LAYOUT, DT>), dim3(blocks), dim3(T::NT), 0, tab);
     timing_work(flops);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<T>), dim3(red_blocks), dim3(256), 0, tab);
-    timing_work(red_bytes);
     return hipGetLastError();
 }
 
 template <class T>
-hipError_t launch_ld(const SyrkTable &tab, int layout, int dt, int blocks, int red_blocks, double flops, double red_bytes,
-                     hipStream_t s)
+hipError_t launch_ld(const SyrkTable &tab, int layout, int dt, int blocks, double flops, hipStream_t s)
 {
     if (layout == kRows) {
-        if (dt == 0) return launch_cfg<T, kRows, 0>(tab, blocks, red_blocks, flops, red_bytes, s);
-        return launch_cfg<T, kRows, 1>(tab, blocks, red_blocks, flops, red_bytes, s);
+        if (dt == 0) return launch_cfg<T, kRows, 0>(tab, blocks, flops, s);
+        return launch_cfg<T, kRows, 1>(tab, blocks, flops, s);
     }
-    if (dt == 0) return launch_cfg<T, kNCHW, 0>(tab, blocks, red_blocks, flops, red_bytes, s);
-    return launch_cfg<T, kNCHW, 1>(tab, blocks, red_blocks, flops, red_bytes, s);
+    if (dt == 0) return launch_cfg<T, kNCHW, 0>(tab, blocks, flops, s);
+    return launch_cfg<T, kNCHW, 1>(tab, blocks, flops, s);
+}
+
+// reduce work of the groups launched so far, flushed as one launch
+struct PendingReduce {
+    RedTable tab;
+    int blocks = 0;
+    double bytes = 0.0;
+};
+
+hipError_t red_flush(PendingReduce &pend, hipStream_t s)
+{
+    if (pend.tab.count == 0) return hipSuccess;
+    KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, syrk_reduce_kernel, dim3(pend.blocks), dim3(256), 0, pend.tab);
+    timing_work(pend.bytes);
+    pend.tab.count = 0;
+    pend.blocks = 0;
+    pend.bytes = 0.0;
+    return hipGetLastError();
+}
+
+int red_kind(int cfg)
+{
+    switch (cfg) {
+        case 0: return 0;
+        case 1: return 1;
+        case 2: return 2;
+        case 3: return 3;
+        case kSmall32Cfg: return 3;
+        case kSmall64Cfg: return 2;
+        case kBf16Cfg: return 5;
+        default: return 4;             // wave-unit and fused convolution kernels
+    }
 }
 
 }  // namespace
@@ -706,19 +760,23 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
     }
     if (off > work_bytes) return hipErrorInvalidValue;
 
+    PendingReduce pend;
+    pend.tab.count = 0;
     for (auto &g : groups) {
         SyrkTable tab;
         tab.count = (int)g.size();
         tab.debug = (int)tuning().wave_debug;
-        int blocks = 0, red = 0;
-        double flops = 0.0, red_bytes = 0.0;
+        int blocks = 0;
+        double flops = 0.0;
+        std::vector<int> red_n(g.size());
+        std::vector<double> red_b(g.size());
         for (int k = 0; k < tab.count; ++k) {
             const int j = g[k];
             const FactorJob &job = jobs[j];
             flops += (double)job.K * (job.d_core + job.has_bias) * (job.d_core + job.has_bias + 1);
             {   // reduce + running average: the split slices and the old factor read (one triangle), the factor written (both)
                 const double dF = job.d_core + job.has_bias, tri = dF * (dF + 1) / 2;
-                red_bytes += 4.0 * ((pl[j].splits + 1) * tri + dF * dF);
+                red_b[k] = 4.0 * ((pl[j].splits + 1) * tri + dF * dF);
             }
             SyrkProb &p = tab.p[k];
             p.x = job.x;
@@ -733,7 +791,7 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
             p.splits = pl[j].splits;
             p.tiles_per_split = pl[j].tps;
             p.blk_start = blocks;
-            p.red_start = red;
+            p.red_start = 0;
             p.vec = vec_ok(job) ? 1 : 0;
             p.has_bias = job.has_bias;
             p.scale = job.scale;
@@ -743,7 +801,7 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
                 const int bm = kCfgs[pl[j].cfg].bm;
                 const int cpt = (bm * bm + kRedChunk - 1) / kRedChunk;
                 const int gpt = (cpt + kRedGroup - 1) / kRedGroup;
-                red += pl[j].nblk * gpt + (job.has_bias ? pl[j].nb : 0);
+                red_n[k] = pl[j].nblk * gpt + (job.has_bias ? pl[j].nb : 0);
             }
         }
         const int cfg = pl[g[0]].cfg;
@@ -772,10 +830,6 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
                 KFAC_LAUNCH(KFAC_K_SYRK_CONV3, s, (syrk_conv3_kernel<4>), dim3(blocks), dim3(256), lds_bytes, tab);
                 timing_work(flops);
                 e = hipGetLastError();
-                if (e != hipSuccess) break;
-                KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<3, 3>, true>), dim3(red), dim3(256), 0, tab);
-                timing_work(red_bytes);
-                e = hipGetLastError();
                 break;
             }
             case kSmall32Cfg:
@@ -788,13 +842,6 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
                 else KFAC_LAUNCH(KFAC_K_SYRK_SMALL, s, (syrk_small_nchw_kernel<4>), dim3(blocks), dim3(256), 0, tab);
                 timing_work(flops);
                 e = hipGetLastError();
-                if (e != hipSuccess) break;
-                if (cfg == kSmall32Cfg)
-                    KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<1, 2>>), dim3(red), dim3(256), 0, tab);
-                else
-                    KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<2, 2>>), dim3(red), dim3(256), 0, tab);
-                timing_work(red_bytes);
-                e = hipGetLastError();
                 break;
             }
             case kBf16Cfg: {
@@ -804,19 +851,11 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
                     KFAC_LAUNCH(KFAC_K_SYRK_BF16, s, syrk_bf16_kernel<kNCHW>, dim3(blocks), dim3(512), 0, tab);
                 timing_work(flops);
                 e = hipGetLastError();
-                if (e != hipSuccess) break;
-                KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<8, 2>>), dim3(red), dim3(256), 0, tab);
-                timing_work(red_bytes);
-                e = hipGetLastError();
                 break;
             }
             case kWaveNchwCfg: {
                 KFAC_LAUNCH(KFAC_K_SYRK_WAVE, s, syrk_wave_nchw_kernel, dim3(blocks), dim3(256), 0, tab);
                 timing_work(flops);
-                e = hipGetLastError();
-                if (e != hipSuccess) break;
-                KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<3, 3>, true>), dim3(red), dim3(256), 0, tab);
-                timing_work(red_bytes);
                 e = hipGetLastError();
                 break;
             }
@@ -824,20 +863,30 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
                 KFAC_LAUNCH(KFAC_K_SYRK_WAVE, s, syrk_wave_kernel, dim3(blocks), dim3(256), 0, tab);
                 timing_work(flops);
                 e = hipGetLastError();
-                if (e != hipSuccess) break;
-                KFAC_LAUNCH(KFAC_K_SYRK_REDUCE, s, (syrk_reduce_kernel<Tile<3, 3>, true>), dim3(red), dim3(256), 0, tab);
-                timing_work(red_bytes);
-                e = hipGetLastError();
                 break;
             }
-            case 0: e = launch_ld<Tile<4, 2>>(tab, layout, dt, blocks, red, flops, red_bytes, s); break;
-            case 1: e = launch_ld<Tile<3, 3>>(tab, layout, dt, blocks, red, flops, red_bytes, s); break;
-            case 2: e = launch_ld<Tile<2, 2>>(tab, layout, dt, blocks, red, flops, red_bytes, s); break;
-            default: e = launch_ld<Tile<1, 2>>(tab, layout, dt, blocks, red, flops, red_bytes, s); break;
+            case 0: e = launch_ld<Tile<4, 2>>(tab, layout, dt, blocks, flops, s); break;
+            case 1: e = launch_ld<Tile<3, 3>>(tab, layout, dt, blocks, flops, s); break;
+            case 2: e = launch_ld<Tile<2, 2>>(tab, layout, dt, blocks, flops, s); break;
+            default: e = launch_ld<Tile<1, 2>>(tab, layout, dt, blocks, flops, s); break;
         }
         if (e != hipSuccess) return e;
+        // the reduce of this group joins the launch at the end of the call
+        const int kind = red_kind(cfg);
+        for (int k = 0; k < tab.count; ++k) {
+            if (pend.tab.count == kMaxRedProblems) {
+                e = red_flush(pend, s);
+                if (e != hipSuccess) return e;
+            }
+            const int i = pend.tab.count++;
+            pend.tab.p[i] = tab.p[k];
+            pend.tab.starts[i] = pend.blocks;
+            pend.tab.kind[i] = kind;
+            pend.blocks += red_n[k];
+            pend.bytes += red_b[k];
+        }
     }
-    return hipSuccess;
+    return red_flush(pend, s);
 }
 
 }  // namespace kfac
