@@ -454,24 +454,212 @@ hipError_t blocked_launch(const InvertJob *jobs, const std::vector<int> &idx, co
     }
     return hipSuccess;
 }
+
+// ---- orders 64 k + 1: the last row and column by bordering ---------------------------------
+// A factor with a bias column has order 9 C + 1 or d + 1: with C or d a multiple of 64 the last pivot block of
+// the sweep would be a single row, a whole step (and a block row of tiles in every other step) for a rank-1
+// update.  Instead the sweep inverts the leading block, X = (M_11 + damping I)^-1, and with b the last row of M
+// and c its corner,  y = X b,  s = c + damping - b^T y,
+//     M^-1 = [ X + y y^T / s   -y / s ]
+//            [   -y^T / s       1 / s ],
+// which is the last pivot step of the same sweep (s is its pivot: not positive -> flagged as pivot n).
+struct BorderProb {
+    const float *M;
+    float *W;
+    float *y;          // workspace, n - 1 floats
+    int *info;
+    const float *dptr;
+    float damping;
+    int n, ldm, ldw;
+    int blk_start;
+};
+
+struct BorderTable {
+    int count;
+    BorderProb p[kMaxProblems];
+};
+
+constexpr int kBorderRows = 16;   // rows per workgroup: four per wavefront, their loads in flight together
+
+__device__ __forceinline__ const BorderProb &border_locate(const BorderTable &tab, int &chunk)
+{
+    int pi = 0;
+    while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].blk_start) ++pi;
+    chunk = blockIdx.x - tab.p[pi].blk_start;
+    return tab.p[pi];
+}
+
+// y = X b: a wavefront per row, lanes along the row
+__global__ __launch_bounds__(256) void border_matvec_kernel(const BorderTable tab)
+{
+    __shared__ float bs[1280 + 64];
+    int chunk;
+    const BorderProb &pr = border_locate(tab, chunk);
+    const int m = pr.n - 1, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    for (int j = threadIdx.x; j < m; j += 256) bs[j] = pr.M[(long)m * pr.ldm + j];
+    __syncthreads();
+    // rows 4 w .. 4 w + 3 of the chunk: rows past the end repeat the last one and are not stored
+    const int i0 = chunk * kBorderRows + 4 * w;
+    const float *row[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) row[q] = pr.W + (long)min(i0 + q, m - 1) * pr.ldw;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    int j = lane;
+    for (; j + 64 < m; j += 128) {              // two columns per lane and trip: eight loads in flight
+        float v0[4], v1[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { v0[q] = row[q][j]; v1[q] = row[q][j + 64]; }
+        const float b0 = bs[j], b1 = bs[j + 64];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[q] = __builtin_fmaf(v1[q], b1, __builtin_fmaf(v0[q], b0, acc[q]));
+    }
+    for (; j < m; j += 64) {
+        const float b0 = bs[j];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[q] = __builtin_fmaf(row[q][j], b0, acc[q]);
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        float a = acc[q];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) a += __shfl_xor(a, o);
+        if (lane == 0 && i0 + q < m) pr.y[i0 + q] = a;
+    }
+}
+
+// the rank-1 update of X and the last row and column
+__global__ __launch_bounds__(256) void border_update_kernel(const BorderTable tab)
+{
+    __shared__ float ys[1280 + 64];
+    __shared__ float red[256];
+    int chunk;
+    const BorderProb &pr = border_locate(tab, chunk);
+    const int m = pr.n - 1, t = threadIdx.x, lane = t & 63, w = t >> 6;
+    float part = 0.f;
+    for (int j = t; j < m; j += 256) {
+        const float yj = pr.y[j];
+        ys[j] = yj;
+        part += pr.M[(long)m * pr.ldm + j] * yj;
+    }
+    red[t] = part;
+    __syncthreads();
+    for (int h = 128; h > 0; h >>= 1) {
+        if (t < h) red[t] += red[t + h];
+        __syncthreads();
+    }
+    const float damping = pr.dptr ? *pr.dptr : pr.damping;
+    const float sp = pr.M[(long)m * pr.ldm + m] + damping - red[0];      // the same in every workgroup
+    const float is = 1.0f / sp;
+    if (chunk == 0) {
+        if (t == 0) {
+            if (!(sp > 0.f) && *pr.info == 0) *pr.info = pr.n;
+            pr.W[(long)m * pr.ldw + m] = is;
+        }
+        for (int j = t; j < m; j += 256) pr.W[(long)m * pr.ldw + j] = -ys[j] * is;
+    }
+    // rows 4 w .. 4 w + 3 of the chunk (rows past the end repeat the last one and are not stored), three
+    // column pieces per trip: twelve loads in flight before the first store
+    const int i0 = chunk * kBorderRows + 4 * w;
+    float *row[4];
+    float yi[4];
+    bool live[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        live[q] = i0 + q < m;
+        const int i = min(i0 + q, m - 1);
+        row[q] = pr.W + (long)i * pr.ldw;
+        yi[q] = ys[i];
+    }
+    for (int j0 = lane; j0 < m; j0 += 192) {
+        float v[3][4];
+#pragma unroll
+        for (int c = 0; c < 3; ++c)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[c][q] = row[q][min(j0 + 64 * c, m - 1)];
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            const int j = j0 + 64 * c;
+            if (j < m) {
+                const float yj = ys[j];
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (live[q]) row[q][j] = v[c][q] + (yi[q] * yj) * is;   // y_i y_j first: the same value at (i, j) and (j, i)
+            }
+        }
+    }
+    if (lane == 0) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (live[q]) row[q][m] = -yi[q] * is;
+    }
+}
+
+hipError_t border_launch(const InvertJob *jobs, const std::vector<int> &idx, const std::vector<float *> &ybuf,
+                         hipStream_t s)
+{
+    for (size_t g0 = 0; g0 < idx.size(); g0 += kMaxProblems) {
+        BorderTable tab;
+        tab.count = (int)std::min<size_t>(kMaxProblems, idx.size() - g0);
+        int blocks = 0;
+        for (int k = 0; k < tab.count; ++k) {
+            const InvertJob &j = jobs[idx[g0 + k]];
+            BorderProb &p = tab.p[k];
+            p.M = j.M; p.W = j.Minv; p.y = ybuf[g0 + k]; p.info = j.info; p.dptr = j.damping_dev; p.damping = j.damping;
+            p.n = j.n;
+            p.ldm = j.ldm > 0 ? j.ldm : j.n;
+            p.ldw = j.ldo > 0 ? j.ldo : j.n;
+            p.blk_start = blocks;
+            blocks += (j.n - 1 + kBorderRows - 1) / kBorderRows;
+        }
+        KFAC_LAUNCH(KFAC_K_INV_FINISH, s, border_matvec_kernel, dim3(blocks), dim3(256), 0, tab);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        KFAC_LAUNCH(KFAC_K_INV_FINISH, s, border_update_kernel, dim3(blocks), dim3(256), 0, tab);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+// orders the sweep hands to the bordering: 64 k + 1 inside the range of the one-launch-per-step path
+bool takes_border(int n)
+{
+    return tuning().invert_border && n > 64 && n % 64 == 1 && takes_fused(n - 1) && n - 1 <= 1280;   // 1280: the LDS vectors of the two kernels
+}
+size_t border_ws_floats(int n) { return takes_border(n) ? (size_t)(n + 63) / 64 * 64 : 0; }
 }  // namespace
 
 size_t invert_workspace_bytes(const InvertJob *jobs, int n)
 {
     size_t total = table_bytes(n);
-    for (int i = 0; i < n; ++i) total += align_up(job_ws_floats(jobs[i].n) * sizeof(float), 256);
+    for (int i = 0; i < n; ++i)
+        total += align_up((job_ws_floats(jobs[i].n) + border_ws_floats(jobs[i].n)) * sizeof(float), 256);
     return total;
 }
 
-hipError_t invert_launch(const InvertJob *jobs, int n_all, void *work, size_t work_bytes, hipStream_t s)
+hipError_t invert_launch(const InvertJob *jobs_in, int n_all, void *work, size_t work_bytes, hipStream_t s)
 {
-    if (invert_workspace_bytes(jobs, n_all) > work_bytes) return hipErrorInvalidValue;
+    if (invert_workspace_bytes(jobs_in, n_all) > work_bytes) return hipErrorInvalidValue;
     std::vector<size_t> offs(n_all);
     size_t off = table_bytes(n_all);
+    // bordered orders: the sweep sees the leading block (same storage, same pitches), the last row and column
+    // follow at the end
+    std::vector<InvertJob> inner(jobs_in, jobs_in + n_all);
+    std::vector<int> bordered;
+    std::vector<float *> ybuf;
     for (int i = 0; i < n_all; ++i) {
         offs[i] = off;
-        off += align_up(job_ws_floats(jobs[i].n) * sizeof(float), 256);
+        const int n = jobs_in[i].n;
+        if (takes_border(n)) {
+            inner[i].n = n - 1;
+            inner[i].ldm = jobs_in[i].ldm > 0 ? jobs_in[i].ldm : n;
+            inner[i].ldo = jobs_in[i].ldo > 0 ? jobs_in[i].ldo : n;
+            bordered.push_back(i);
+            ybuf.push_back(reinterpret_cast<float *>(static_cast<char *>(work) + off) + job_ws_floats(n));
+        }
+        off += align_up((job_ws_floats(n) + border_ws_floats(n)) * sizeof(float), 256);
     }
+    const InvertJob *jobs = inner.data();
     // largest matrices first so that the matrices still active at a step form a prefix
     std::vector<int> large, fused;
     for (int i = 0; i < n_all; ++i) (takes_fused(jobs[i].n) ? fused : large).push_back(i);
@@ -488,6 +676,7 @@ hipError_t invert_launch(const InvertJob *jobs, int n_all, void *work, size_t wo
         hipError_t e = blocked_launch(jobs, large, offs, work, dtab + n_all, s);
         if (e != hipSuccess) return e;
     }
+    if (!bordered.empty()) return border_launch(jobs_in, bordered, ybuf, s);
     return hipSuccess;
 }
 

@@ -297,6 +297,55 @@ def test_not_positive_definite_in_a_late_block_is_flagged_by_the_blocked_path():
     assert flags[0] == orc.inverse_info(M.astype(np.float64), 0.01)
 
 
+@pytest.mark.parametrize("n", [65, 129, 577, 1153])
+def test_inverse_of_order_64k_plus_1_by_bordering(n):
+    # orders 64 k + 1 (a bias column after a multiple of 64 columns): the sweep inverts the leading block, the
+    # last row and column follow by bordering; same result as the plain sweep (knob off) and as the oracle
+    gen = np.random.default_rng(300 + n)
+    X = gen.standard_normal((n + 11, n))
+    M = (X.T @ X / (n + 11)).astype(np.float32)
+    lam = 0.04
+    desc = kf.LayerDesc.linear(n - 1, 3, has_bias=True)
+    G = np.eye(3, dtype=np.float32)
+    ws = gu.workspace(kf.kfac_workspace_bytes(desc, 8))
+    got = {}
+    for border in (1, 0):
+        A_inv = torch.full((n, n), float("nan"), device=gu.DEV)
+        G_inv = torch.full((3, 3), float("nan"), device=gu.DEV)
+        info = torch.full((2,), -1, dtype=torch.int32, device=gu.DEV)
+        kf.kfac_tune("invert_border", border)
+        try:
+            kf.kfac_invert(desc, gu.to_dev(M), gu.to_dev(G), lam, lam, A_inv, G_inv, info, ws)
+            torch.cuda.synchronize()
+        finally:
+            kf.kfac_tune("invert_border", 1)
+        assert list(info.cpu().numpy()) == [0, 0]
+        got[border] = A_inv.cpu().numpy()
+    ref = orc.inverse(M.astype(np.float64), lam)
+    assert gu.rel_fro(got[1], ref) < 1e-4
+    assert gu.rel_fro(got[0], ref) < 1e-4
+    assert gu.rel_fro(got[1], got[0]) < 2e-5
+    assert np.array_equal(got[1], got[1].T)
+
+
+def test_bordered_pivot_not_positive_is_flagged():
+    # leading block positive definite, the Schur complement of the last row is not: pivot n
+    n = 129
+    M = np.eye(n, dtype=np.float32)
+    M[n - 1, :n - 1] = 0.2
+    M[:n - 1, n - 1] = 0.2
+    M[n - 1, n - 1] = 1.0          # 1 + 0.5 - 128 * 0.04 / 1.5 < 0
+    desc = kf.LayerDesc.linear(n - 1, 2, has_bias=True)
+    A_inv = torch.zeros((n, n), device=gu.DEV)
+    G_inv = torch.zeros((2, 2), device=gu.DEV)
+    info = torch.full((2,), -1, dtype=torch.int32, device=gu.DEV)
+    ws = gu.workspace(kf.kfac_workspace_bytes(desc, 8))
+    kf.kfac_invert(desc, gu.to_dev(M), gu.to_dev(np.eye(2, dtype=np.float32)), 0.5, 0.5, A_inv, G_inv, info, ws)
+    torch.cuda.synchronize()
+    assert list(info.cpu().numpy()) == [n, 0]
+    assert orc.inverse_info(M.astype(np.float64), 0.5) == n
+
+
 def test_not_positive_definite_is_flagged():
     n = 70
     M = np.eye(n, dtype=np.float32)
