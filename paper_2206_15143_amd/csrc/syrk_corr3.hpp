@@ -122,24 +122,41 @@ __global__ __launch_bounds__(512) void corr3_main_kernel(const CorrTable tab)
                 lofs[k] = (c * plane + r * Wp + 4 + 4 * g) | (r << 20);
             }
         }
+        // Every instruction of these wavefronts takes an issue slot from the product wavefronts of its SIMD, so
+        // the per-unit work is kept to the loads and stores themselves: byte offsets precomputed (uniform base +
+        // 32-bit lane offset), and the test for rows below the image only in units that have such rows.
+        unsigned gbyte[MAXI];
+#pragma unroll
+        for (int k = 0; k < MAXI; ++k) gbyte[k] = gofs[k] >= 0 ? 4u * (unsigned)gofs[k] : 0u;
         floatx4 regs[MAXI];
         auto fetch = [&](int u) {                  // loads only: nothing here may wait for them
             const int n = u / pr.strips, a0 = (u - n * pr.strips) * SR;
-            const float *win0 = pr.x + (long)n * C * H * W + (long)a0 * W;
+            const char *win0 = reinterpret_cast<const char *>(pr.x + (long)n * C * H * W + (long)a0 * W);
+            if (a0 + rows <= H) {                  // uniform: the whole slab lies inside the image
 #pragma unroll
-            for (int k = 0; k < MAXI; ++k) {
-                const bool ok = gofs[k] >= 0 && a0 + (lofs[k] >> 20) < H;
-                regs[k] = *reinterpret_cast<const floatx4 *>(win0 + (ok ? gofs[k] : 0));
+                for (int k = 0; k < MAXI; ++k) regs[k] = *reinterpret_cast<const floatx4 *>(win0 + gbyte[k]);
+            } else {
+#pragma unroll
+                for (int k = 0; k < MAXI; ++k) {
+                    const bool ok = a0 + (lofs[k] >> 20) < H;
+                    regs[k] = *reinterpret_cast<const floatx4 *>(win0 + (ok ? gbyte[k] : 0u));
+                }
             }
         };
         auto commit = [&](float *b, int u) {
             // unconditional stores: rows below the image are stored as zeros, and an item that does not exist
             // stores zeros to the first pad cell of the slab, which holds zeros anyway
             const int a0 = (u % pr.strips) * SR;
+            if (a0 + rows <= H) {
 #pragma unroll
-            for (int k = 0; k < MAXI; ++k) {
-                const bool ok = gofs[k] >= 0 && a0 + (lofs[k] >> 20) < H;
-                *reinterpret_cast<floatx4 *>(b + (lofs[k] & 0xfffff)) = ok ? regs[k] : floatx4{0.f, 0.f, 0.f, 0.f};
+                for (int k = 0; k < MAXI; ++k)
+                    *reinterpret_cast<floatx4 *>(b + (lofs[k] & 0xfffff)) = gofs[k] >= 0 ? regs[k] : floatx4{0.f, 0.f, 0.f, 0.f};
+            } else {
+#pragma unroll
+                for (int k = 0; k < MAXI; ++k) {
+                    const bool ok = gofs[k] >= 0 && a0 + (lofs[k] >> 20) < H;
+                    *reinterpret_cast<floatx4 *>(b + (lofs[k] & 0xfffff)) = ok ? regs[k] : floatx4{0.f, 0.f, 0.f, 0.f};
+                }
             }
         };
         // the first and the last pixel of every image row also go to a compact buffer (the border kernel would
