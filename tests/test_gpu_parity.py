@@ -346,6 +346,26 @@ def test_bordered_pivot_not_positive_is_flagged():
     assert orc.inverse_info(M.astype(np.float64), 0.5) == n
 
 
+@pytest.mark.parametrize("dA,dG", [(1, 1), (7, 3), (65, 10), (145, 16), (130, 17), (289, 32), (300, 33), (577, 64),
+                                   (64, 64), (1153, 48)])
+def test_two_sided_product_shapes(dA, dG):
+    # P = G_inv grad A_inv called directly on given (symmetric positive definite) inverses, against fp64:
+    # orders around the tile sizes of the small-product GEMM and the widths of config 2
+    gen = np.random.default_rng(17 * dA + dG)
+    def spd(n):
+        X = gen.standard_normal((n + 5, n))
+        return (X.T @ X / (n + 5) + 0.1 * np.eye(n)).astype(np.float32)
+    A_inv, G_inv = spd(dA), spd(dG)
+    grad = gen.standard_normal((dG, dA)).astype(np.float32)
+    desc = kf.LayerDesc.linear(dA, dG, has_bias=False)
+    ws = gu.workspace(kf.kfac_workspace_bytes(desc, 8))
+    out = torch.full((dG, dA), float("nan"), device=gu.DEV)
+    kf.kfac_precondition(desc, gu.to_dev(A_inv), gu.to_dev(G_inv), gu.to_dev(grad), out, ws)
+    torch.cuda.synchronize()
+    ref = G_inv.astype(np.float64) @ grad.astype(np.float64) @ A_inv.astype(np.float64)
+    assert gu.rel_fro(out.cpu().numpy(), ref) < 1e-5
+
+
 def test_not_positive_definite_is_flagged():
     n = 70
     M = np.eye(n, dtype=np.float32)
