@@ -27,7 +27,7 @@ namespace kfac {
 constexpr int C3_LAGS = 13;
 constexpr int C3_BQ = 16;          // border matrices per layer: 6 row, 6 column, 4 corner
 constexpr int C3_BV = 8;           // border vectors per layer: 2 row sums, 2 column sums, 4 corner sums
-constexpr int C3_CHUNKS = 4;       // image chunks of the border kernel
+constexpr int C3_CHUNKS = 5;       // image chunks of the border kernels (5 x 4 pair groups x 36 layers = 720 workgroups at 64 channels: under 3 per CU)
 
 struct CorrProb {
     const float *x;    // NCHW input [B, C, H, W]
@@ -445,10 +445,22 @@ __global__ __launch_bounds__(256) void corr3_border_kernel(const CorrTable tab)
         const int nks = (nimg + 3) / 4;
         for (int q = 0; q < 4; ++q) {
             const int a = (q & 2) ? H - 1 : 0, b = (q & 1) ? W - 1 : 0;
-            __syncthreads();
-            for (int i = tid; i < C * LMAX; i += 256) {
+            // one cache line per value: all loads of a thread in flight before the first is stored
+            constexpr int EPC = (C * LMAX + 255) / 256;
+            float val[EPC];
+#pragma unroll
+            for (int e = 0; e < EPC; ++e) {
+                const int i = tid + 256 * e;
                 const int c = i / LMAX, k = i - c * LMAX;
-                line[i] = (k < nimg) ? pr.x[(((long)(n0 + k) * C + c) * H + a) * W + b] : 0.f;
+                const bool ok = i < C * LMAX && k < nimg;
+                const float v = pr.x[ok ? (((long)(n0 + k) * C + c) * H + a) * W + b : 0];
+                val[e] = ok ? v : 0.f;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int e = 0; e < EPC; ++e) {
+                const int i = tid + 256 * e;
+                if (i < C * LMAX) line[i] = val[e];
             }
             __syncthreads();
 #pragma unroll
