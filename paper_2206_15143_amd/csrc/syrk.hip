@@ -715,7 +715,7 @@ hipError_t corr3_launch(const FactorJob *jobs, const std::vector<int> &g, const 
         const CorrProb &p = tab.p[k];
         tab.p[k].blk_start = blocks;
         tab.starts[k] = blocks;
-        const long total = (long)(C3_LAGS + C3_BQ) * p.C * p.C + (long)(1 + C3_BV) * p.C;
+        const long total = (long)(C3_LAGS + C3_BQ) * p.C * p.C / 4 + (long)(1 + C3_BV) * p.C;   // four matrix elements per thread
         blocks += (int)((total + 255) / 256);
     }
     KFAC_LAUNCH(KFAC_K_CORR3_ASM, s, corr3_sum_kernel, dim3(blocks), dim3(256), 0, tab);

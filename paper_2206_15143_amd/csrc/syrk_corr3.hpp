@@ -626,38 +626,44 @@ __global__ __launch_bounds__(256) void corr3_border_plane_kernel(const CorrTable
 __global__ __launch_bounds__(256) void corr3_sum_kernel(const CorrTable tab)
 {
     const CorrProb &pr = tab.p[corr_locate(tab, blockIdx.x)];
-    const int C = pr.C;
-    const long nF = (long)C3_LAGS * C * C, nB = (long)C3_BQ * C * C;
-    const long e = (long)(blockIdx.x - pr.blk_start) * 256 + threadIdx.x;
-    if (e < nF) {
-        // eight interleaved running sums (fixed order) keep loads in flight
-        float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        int p = 0;
-        for (; p + 8 <= pr.parts; p += 8)
+    const int C = pr.C, cc = C * C;
+    const long nF = (long)C3_LAGS * cc, nB = (long)C3_BQ * cc;
+    const long qF = nF / 4, qB = nB / 4;            // matrices: four consecutive elements (one row) per thread
+    const long q = (long)(blockIdx.x - pr.blk_start) * 256 + threadIdx.x;
+    auto store_both = [&](float *dst, float *dstT, long e, const floatx4 &v) {
+        *reinterpret_cast<floatx4 *>(dst + e) = v;
+        const int l = (int)(e / cc), rem = (int)(e - (long)l * cc), c = rem / C, c2 = rem - c * C;
+        float *t = dstT + (long)l * cc + (long)c2 * C + c;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) a[j] += pr.Fp[(long)(p + j) * nF + e];
-        for (; p < pr.parts; ++p) a[0] += pr.Fp[(long)p * nF + e];
-        const float sum = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
-        pr.Fs[e] = sum;
-        const int cc = C * C, l = (int)(e / cc), rem = (int)(e - (long)l * cc), c = rem / C, c2 = rem - c * C;
-        pr.FsT[(long)l * cc + c2 * C + c] = sum;
-    } else if (e < nF + C) {
-        const long c = e - nF;
-        float s = 0.f;
-        for (int p = 0; p < pr.parts; ++p) s += pr.Fp[(long)pr.parts * nF + (long)p * C + c];
-        pr.Fs[e] = s;
-    } else if (e < nF + C + nB) {
-        const long i = e - nF - C;
-        float s = 0.f;
-        for (int k = 0; k < C3_CHUNKS; ++k) s += pr.Bp[(long)k * nB + i];
-        pr.Bs[i] = s;
-        const int cc = C * C, l = (int)(i / cc), rem = (int)(i - (long)l * cc), c = rem / C, c2 = rem - c * C;
-        pr.BsT[(long)l * cc + c2 * C + c] = s;
-    } else if (e < nF + C + nB + C3_BV * C) {
-        const long i = e - nF - C - nB;
-        float s = 0.f;
-        for (int k = 0; k < C3_CHUNKS; ++k) s += pr.Bp[(long)C3_CHUNKS * nB + (long)k * (C3_BV * C) + i];
-        pr.Bs[nB + i] = s;
+        for (int i = 0; i < 4; ++i) t[(long)i * C] = v[i];
+    };
+    if (q < qF) {
+        // four interleaved running sums (fixed order) keep loads in flight
+        const long e = 4 * q;
+        floatx4 a[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a[j] = floatx4{0.f, 0.f, 0.f, 0.f};
+        int p = 0;
+        for (; p + 4 <= pr.parts; p += 4)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) a[j] += *reinterpret_cast<const floatx4 *>(pr.Fp + (long)(p + j) * nF + e);
+        for (; p < pr.parts; ++p) a[0] += *reinterpret_cast<const floatx4 *>(pr.Fp + (long)p * nF + e);
+        store_both(pr.Fs, pr.FsT, e, (a[0] + a[1]) + (a[2] + a[3]));
+    } else if (q < qF + qB) {
+        const long i = 4 * (q - qF);
+        floatx4 sum = {0.f, 0.f, 0.f, 0.f};
+        for (int k = 0; k < C3_CHUNKS; ++k) sum += *reinterpret_cast<const floatx4 *>(pr.Bp + (long)k * nB + i);
+        store_both(pr.Bs, pr.BsT, i, sum);
+    } else if (q < qF + qB + C) {
+        const long c = q - qF - qB;
+        float sum = 0.f;
+        for (int p = 0; p < pr.parts; ++p) sum += pr.Fp[(long)pr.parts * nF + (long)p * C + c];
+        pr.Fs[nF + c] = sum;
+    } else if (q < qF + qB + C + C3_BV * C) {
+        const long i = q - qF - qB - C;
+        float sum = 0.f;
+        for (int k = 0; k < C3_CHUNKS; ++k) sum += pr.Bp[(long)C3_CHUNKS * nB + (long)k * (C3_BV * C) + i];
+        pr.Bs[nB + i] = sum;
     }
 }
 

@@ -186,7 +186,7 @@ def test_nonsquare_layer_end_to_end(cin, kh, kw, h, w, pad, bias):
 
 @pytest.mark.parametrize("cin,h,w,batch,bias", [
     (16, 32, 32, 3, True),      # one strip pair per image, four wavefronts splitting the pixel groups
-    (16, 8, 8, 5, False),       # batch not a multiple of the four image chunks of the border kernel
+    (16, 8, 8, 7, False),       # batch not a multiple of the image chunks of the border kernel
     (32, 16, 16, 2, True),
     (32, 6, 8, 1, True),        # a single image; strips of 2 rows
     (64, 8, 8, 7, True),        # two workgroups per range of units
