@@ -309,17 +309,35 @@ hipError_t fused_launch(const InvertJob *jobs, const std::vector<int> &idx, cons
     }
     return hipSuccess;
 }
-// Two-level blocked sweep of the matrices listed in `idx` (sorted by order, largest first).
-hipError_t blocked_launch(const InvertJob *jobs, const std::vector<int> &idx, const std::vector<size_t> &offs,
-                          void *work, InvProbF *dtab, hipStream_t s)
-{
-    const int total = (int)idx.size();
-    const int PB = outer_block();
+// Two-level blocked sweep of the matrices listed in `idx` (sorted by order, largest first), as three calls
+// (start, one outer step, finish) so that two groups of matrices can advance side by side on two streams.
+struct BlockedRun {
     struct Big { float *Vt, *Wt, *P, *nws; int *ninfo; int ldv; };
-    std::vector<Big> big(total);
+    const InvertJob *jobs = nullptr;
+    std::vector<int> idx;
+    const std::vector<size_t> *offs = nullptr;
+    void *work = nullptr;
+    InvProbF *dtab = nullptr;
+    std::vector<Big> big;
+    int total = 0, PB = 0, steps = 0;
+    std::vector<InvertJob> nested;
+    std::vector<int> nidx;
+    std::vector<size_t> noffs;
+    std::vector<GemmJob> gp, gu;
+
+    hipError_t start(hipStream_t s);
+    hipError_t step(int st, hipStream_t s);
+    hipError_t finish(hipStream_t s);
+};
+
+hipError_t BlockedRun::start(hipStream_t s)
+{
+    total = (int)idx.size();
+    PB = outer_block();
+    big.assign(total, Big());
     for (int k = 0; k < total; ++k) {
         const InvertJob &j = jobs[idx[k]];
-        float *ws = reinterpret_cast<float *>(static_cast<char *>(work) + offs[idx[k]]);
+        float *ws = reinterpret_cast<float *>(static_cast<char *>(work) + (*offs)[idx[k]]);
         Big &b = big[k];
         b.ldv = (j.n + 3) / 4 * 4;
         b.Vt = ws;
@@ -346,12 +364,13 @@ hipError_t blocked_launch(const InvertJob *jobs, const std::vector<int> &idx, co
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    const int steps = (jobs[idx[0]].n + PB - 1) / PB;
-    std::vector<InvertJob> nested;
-    std::vector<int> nidx;
-    std::vector<size_t> noffs;
-    std::vector<GemmJob> gp, gu;
-    for (int st = 0; st < steps; ++st) {
+    steps = total > 0 ? (jobs[idx[0]].n + PB - 1) / PB : 0;
+    return hipSuccess;
+}
+
+hipError_t BlockedRun::step(int st, hipStream_t s)
+{
+    {
         const int p0 = st * PB;
         int active = 0;
         while (active < total && jobs[idx[active]].n > p0) ++active;
@@ -433,6 +452,11 @@ hipError_t blocked_launch(const InvertJob *jobs, const std::vector<int> &idx, co
             if (e != hipSuccess) return e;
         }
     }
+    return hipSuccess;
+}
+
+hipError_t BlockedRun::finish(hipStream_t s)
+{
     // negate and mirror
     for (int g0 = 0; g0 < total; g0 += kMaxProblems) {
         InvTable tab;
@@ -453,6 +477,74 @@ hipError_t blocked_launch(const InvertJob *jobs, const std::vector<int> &idx, co
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
+}
+
+
+hipError_t blocked_launch(const InvertJob *jobs, const std::vector<int> &idx, const std::vector<size_t> &offs,
+                          void *work, InvProbF *dtab, hipStream_t s)
+{
+    BlockedRun run;
+    run.jobs = jobs; run.idx = idx; run.offs = &offs; run.work = work; run.dtab = dtab;
+    hipError_t e = run.start(s);
+    if (e != hipSuccess) return e;
+    for (int st = 0; st < run.steps; ++st) {
+        e = run.step(st, s);
+        if (e != hipSuccess) return e;
+    }
+    return run.finish(s);
+}
+
+// Two groups of matrices on two streams: the pivot-block inversions, panel products and copies of a group are
+// short dependent launches that leave most of the chip idle, its rank-k updates fill it; dealt alternately to
+// the groups and enqueued step by step, the small launches of one group run beside the updates of the other.
+struct AuxStream {
+    hipStream_t s = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+};
+
+AuxStream *aux_stream()
+{
+    static AuxStream per_dev[16];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return nullptr;
+    AuxStream &a = per_dev[dev];
+    if (!a.s) {
+        if (hipStreamCreateWithFlags(&a.s, hipStreamNonBlocking) != hipSuccess) { a.s = nullptr; return nullptr; }
+        if (hipEventCreateWithFlags(&a.fork, hipEventDisableTiming) != hipSuccess ||
+            hipEventCreateWithFlags(&a.join, hipEventDisableTiming) != hipSuccess) {
+            (void)hipStreamDestroy(a.s);
+            a.s = nullptr;
+            return nullptr;
+        }
+    }
+    return &a;
+}
+
+hipError_t blocked_launch_pair(const InvertJob *jobs, const std::vector<int> &idx, const std::vector<size_t> &offs,
+                               void *work, InvProbF *dtab, hipStream_t s)
+{
+    AuxStream *aux = (tuning().invert_two_streams && idx.size() >= 2) ? aux_stream() : nullptr;
+    if (!aux) return blocked_launch(jobs, idx, offs, work, dtab, s);
+    BlockedRun run[2];
+    for (size_t k = 0; k < idx.size(); ++k) run[k & 1].idx.push_back(idx[k]);   // sorted by order: dealt alternately
+    for (int g = 0; g < 2; ++g) {
+        run[g].jobs = jobs; run[g].offs = &offs; run[g].work = work;
+        run[g].dtab = dtab + (g == 0 ? 0 : run[0].idx.size());    // descriptors of the nested inversions: a range each
+    }
+    if (hipEventRecord(aux->fork, s) != hipSuccess || hipStreamWaitEvent(aux->s, aux->fork, 0) != hipSuccess)
+        return hipErrorUnknown;
+    hipStream_t st2[2] = {s, aux->s};
+    hipError_t e = hipSuccess;
+    for (int g = 0; g < 2 && e == hipSuccess; ++g) e = run[g].start(st2[g]);
+    const int steps = std::max(run[0].steps, run[1].steps);
+    for (int st = 0; st < steps && e == hipSuccess; ++st)
+        for (int g = 0; g < 2 && e == hipSuccess; ++g)
+            if (st < run[g].steps) e = run[g].step(st, st2[g]);
+    for (int g = 0; g < 2 && e == hipSuccess; ++g) e = run[g].finish(st2[g]);
+    // always join, also after an error: the caller's stream must not run ahead of what the other one still holds
+    if (hipEventRecord(aux->join, aux->s) != hipSuccess || hipStreamWaitEvent(s, aux->join, 0) != hipSuccess)
+        return hipErrorUnknown;
+    return e;
 }
 
 // ---- orders 64 k + 1: the last row and column by bordering ---------------------------------
@@ -673,7 +765,7 @@ hipError_t invert_launch(const InvertJob *jobs_in, int n_all, void *work, size_t
     }
     if (!large.empty()) {
         // the nested pivot-block inversions use the second half of the descriptor table
-        hipError_t e = blocked_launch(jobs, large, offs, work, dtab + n_all, s);
+        hipError_t e = blocked_launch_pair(jobs, large, offs, work, dtab + n_all, s);
         if (e != hipSuccess) return e;
     }
     if (!bordered.empty()) return border_launch(jobs_in, bordered, ybuf, s);
