@@ -411,8 +411,8 @@ int corr3_rows(int C, int H, int W, int *plane_out)
         int plane = (SR + 2) * (W + 8);
         plane += (4 - plane % 32 + 32) % 32;
         const long bytes = 2l * C * plane * 4;
-        const long items = (long)C * (SR + 2) * (W / 4);
-        if (bytes > std::min<long>(tuning().corr3_lds_kb, 80) * 1024 || items > 6 * 256) continue;   // 80 KB: what the launch asks the runtime for
+        const long copies = ((long)C * plane / 4 + 63) / 64;       // 1 KB global -> LDS copies per slab, nine per staging wavefront at most
+        if (bytes > std::min<long>(tuning().corr3_lds_kb, 80) * 1024 || copies > 36) continue;   // 80 KB: what the launch asks the runtime for
         best = SR;
         if (plane_out) *plane_out = plane;
     }

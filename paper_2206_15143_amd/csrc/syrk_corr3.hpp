@@ -21,6 +21,7 @@
 
 #include "common.hpp"
 #include "tn_engine.hpp"
+#include "wave_common.hpp"
 
 namespace kfac {
 
@@ -83,7 +84,6 @@ __global__ __launch_bounds__(512) void corr3_main_kernel(const CorrTable tab)
     constexpr int KS = NT == 1 ? 4 : 1;        // wavefronts that split the pixel groups
     constexpr int PW = NT == 4 ? 2 : 1;        // B tiles per wavefront
     constexpr int HALVES = NT == 4 ? 2 : 1;    // workgroups that share a range of units (each takes half the B tiles)
-    constexpr int MAXI = 6;                    // float4 items per staging thread and slab at most (checked by the planner)
     constexpr int SCI = 2;                     // border-column cells per staging thread with a precomputed address
 
     const CorrProb &pr = tab.p[corr_locate(tab, blockIdx.x)];
@@ -94,9 +94,6 @@ __global__ __launch_bounds__(512) void corr3_main_kernel(const CorrTable tab)
     const int H = pr.H, W = pr.W, Wp = W + 8, SR = pr.SR, plane = pr.plane, w4 = W >> 2;
     float *buf0 = corr_lds, *buf1 = corr_lds + C * plane;
 
-    for (int i = threadIdx.x; i < 2 * C * plane; i += 512) corr_lds[i] = 0.f;   // the pad cells are never written again
-    __syncthreads();
-
     // Wavefronts 4 .. 7 stage the slabs, wavefronts 0 .. 3 only read operands and issue products.  Workgroups
     // that share a CU advance at the same pace (the MFMA unit alternates between their wavefronts), so staging
     // done by the product wavefronts themselves would fall into the same moments in all of them and leave the
@@ -105,57 +102,52 @@ __global__ __launch_bounds__(512) void corr3_main_kernel(const CorrTable tab)
     // done with unit it - 1, whose buffer the staging wavefronts then fill with unit it + 1.
     if (w8 >= 4) {
         const int tid = threadIdx.x - 256;
-        // what this thread moves per slab is the same for every unit: offset inside the (image, strip) window
-        // of the input (-1: nothing), and the LDS offset with the slab row above bit 20
+        // The slab is filled by global -> LDS copies of 1 KB (64 lanes x 16 bytes, consecutive in LDS): instruction
+        // i of a slab covers its 16-byte cells 64 i .. 64 i + 63; a lane whose cell is a pixel piece reads it from
+        // the input, a lane whose cell is padding (the four columns either side of a row, the tail of a plane)
+        // reads out of range, which stores zeros, and so does a halo row below the image.  Per unit that is at
+        // most MAXD copies per wavefront with precomputed lane offsets and one scalar base: every instruction of
+        // these wavefronts takes an issue slot from the product wavefronts of its SIMD.
+        constexpr int MAXD = 9;                    // copies per wavefront and slab at most (checked by the planner)
         const int rows = SR + 2;
-        const int items = C * rows * w4;
-        int gofs[MAXI], lofs[MAXI];
+        const int cells = C * plane / 4, ninstr = (cells + 63) / 64;
+        const int lw = w8 - 4;
+        unsigned vo[MAXD];
+        int vr[MAXD];                              // slab row of the cell (rows below the image are masked per unit)
+        bool vlive[MAXD];
 #pragma unroll
-        for (int k = 0; k < MAXI; ++k) {
-            const int e = tid + 256 * k;
-            gofs[k] = -1;
-            lofs[k] = 0;
-            if (e < items) {
-                const int c = e / (rows * w4), rem = e - c * (rows * w4);
-                const int r = rem / w4, g = rem - r * w4;
-                gofs[k] = (c * H + r) * W + 4 * g;
-                lofs[k] = (c * plane + r * Wp + 4 + 4 * g) | (r << 20);
+        for (int j = 0; j < MAXD; ++j) {
+            const int q = (lw + 4 * j) * 64 + lane;
+            vo[j] = W_OOB;
+            vr[j] = 0;
+            vlive[j] = lw + 4 * j < ninstr && q < cells;
+            if (vlive[j]) {
+                const int f = 4 * q, c = f / plane, rem = f - c * plane;
+                const int r = rem / Wp, x = rem - r * Wp;
+                vr[j] = r;
+                if (r < rows && x >= 4 && x < 4 + W) vo[j] = (unsigned)(((c * H + r) * W + x - 4) * 4);
             }
         }
-        // Every instruction of these wavefronts takes an issue slot from the product wavefronts of its SIMD, so
-        // the per-unit work is kept to the loads and stores themselves: byte offsets precomputed (uniform base +
-        // 32-bit lane offset), and the test for rows below the image only in units that have such rows.
-        unsigned gbyte[MAXI];
-#pragma unroll
-        for (int k = 0; k < MAXI; ++k) gbyte[k] = gofs[k] >= 0 ? 4u * (unsigned)gofs[k] : 0u;
-        floatx4 regs[MAXI];
-        auto fetch = [&](int u) {                  // loads only: nothing here may wait for them
+        int4v rsrc;
+        {
+            const unsigned long ba = (unsigned long)pr.x;
+            rsrc.x = (int)(unsigned)ba;
+            rsrc.y = (int)(unsigned)(ba >> 32);
+            rsrc.z = (int)((long)pr.B * C * H * W * 4);          // below 2^31 (checked by the planner)
+            rsrc.w = 0x00020000;
+        }
+        const unsigned lds0 = (unsigned)(unsigned long)(__attribute__((address_space(3))) float *)corr_lds;
+        const unsigned slab_bytes = (unsigned)(C * plane * 4);
+        auto issue = [&](unsigned dst, int u) {
             const int n = u / pr.strips, a0 = (u - n * pr.strips) * SR;
-            const char *win0 = reinterpret_cast<const char *>(pr.x + (long)n * C * H * W + (long)a0 * W);
-            if (a0 + rows <= H) {                  // uniform: the whole slab lies inside the image
+            const unsigned so = (unsigned)((n * C * H + a0) * W) * 4u;
+            const bool tail = a0 + rows > H;       // uniform: this slab reaches below the image
 #pragma unroll
-                for (int k = 0; k < MAXI; ++k) regs[k] = *reinterpret_cast<const floatx4 *>(win0 + gbyte[k]);
-            } else {
-#pragma unroll
-                for (int k = 0; k < MAXI; ++k) {
-                    const bool ok = a0 + (lofs[k] >> 20) < H;
-                    regs[k] = *reinterpret_cast<const floatx4 *>(win0 + (ok ? gbyte[k] : 0u));
-                }
-            }
-        };
-        auto commit = [&](float *b, int u) {
-            // unconditional stores: rows below the image are stored as zeros, and an item that does not exist
-            // stores zeros to the first pad cell of the slab, which holds zeros anyway
-            const int a0 = (u % pr.strips) * SR;
-            if (a0 + rows <= H) {
-#pragma unroll
-                for (int k = 0; k < MAXI; ++k)
-                    *reinterpret_cast<floatx4 *>(b + (lofs[k] & 0xfffff)) = gofs[k] >= 0 ? regs[k] : floatx4{0.f, 0.f, 0.f, 0.f};
-            } else {
-#pragma unroll
-                for (int k = 0; k < MAXI; ++k) {
-                    const bool ok = gofs[k] >= 0 && a0 + (lofs[k] >> 20) < H;
-                    *reinterpret_cast<floatx4 *>(b + (lofs[k] & 0xfffff)) = ok ? regs[k] : floatx4{0.f, 0.f, 0.f, 0.f};
+            for (int j = 0; j < MAXD; ++j) {
+                if (lw + 4 * j < ninstr) {         // uniform
+                    const unsigned v = (tail && a0 + vr[j] >= H) ? W_OOB : vo[j];
+                    const unsigned to = (unsigned)__builtin_amdgcn_readfirstlane((int)(dst + (unsigned)(lw + 4 * j) * 1024u));
+                    if (vlive[j]) dma16(to, v, rsrc, (unsigned)__builtin_amdgcn_readfirstlane((int)so));
                 }
             }
         };
@@ -188,12 +180,13 @@ __global__ __launch_bounds__(512) void corr3_main_kernel(const CorrTable tab)
                 cbase[(side * C + c) * H + r] = b[c * plane + r * Wp + 4 + (side ? W - 1 : 0)];
             }
         };
-        if (u0 < u1) fetch(u0);
+        if (u0 < u1) issue(lds0, u0);
         for (int u = u0, it = 0; u < u1; ++u, ++it) {
             float *b = (it & 1) ? buf1 : buf0;
-            commit(b, u);                       // the loads were issued a unit ago
-            if (u + 1 < u1) fetch(u + 1);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // the copies of this unit have landed
             __syncthreads();
+            // the other buffer is free now: every product wavefront is past unit it - 1
+            if (u + 1 < u1) issue(lds0 + ((it & 1) ? 0u : slab_bytes), u + 1);
             save_cols(b, u);                    // the slab stays as it is until the barrier after next
         }
         return;
