@@ -4,7 +4,7 @@ Every arithmetic step runs in the HIP kernels of libkfac_hip.so; this package
 only marshals arguments.  PyTorch is used for device memory and streams.
 """
 from .binding import (  # noqa: F401
-    LayerDesc, KfacError, lib_path, load_library,
+    LayerDesc, KfacError, lib_path, load_library, marshal_descs, marshal_ptrs, marshal_ints, marshal_floats,
     kfac_dim_A, kfac_dim_G, kfac_patch_ld, kfac_workspace_bytes, kfac_workspace_bytes_batched,
     kfac_im2col, kfac_update_factors, kfac_invert, kfac_precondition,
     kfac_update_factors_batched, kfac_invert_batched, kfac_invert_pi, kfac_invert_pi_batched, kfac_precondition_batched,

@@ -8,6 +8,7 @@ from __future__ import annotations
 
 import ctypes as C
 import os
+from array import array
 from typing import Optional, Sequence
 
 KFAC_F32, KFAC_BF16 = 0, 1
@@ -140,20 +141,55 @@ def _check(st: int, where: str):
         raise KfacError(st, where)
 
 
-def _descs(descs: Sequence[LayerDesc]):
+def _descs(descs):
+    if isinstance(descs, C.Array):
+        return descs
     return (LayerDesc * len(descs))(*descs)
 
 
-def _ints(v: Sequence[int]):
-    return (C.c_int * len(v))(*[int(x) for x in v])
+def _ints(v):
+    if isinstance(v, C.Array):
+        return v
+    return (C.c_int * len(v)).from_buffer(array("i", [int(x) for x in v]))
 
 
-def _floats(v: Sequence[float]):
-    return (C.c_float * len(v))(*[float(x) for x in v])
+def _floats(v):
+    if isinstance(v, C.Array):
+        return v
+    return (C.c_float * len(v)).from_buffer(array("f", [float(x) for x in v]))
 
 
 def _ptrs(ts):
-    return (C.c_void_p * len(ts))(*[_ptr(t) for t in ts])
+    if isinstance(ts, C.Array):
+        return ts
+    return (C.c_void_p * len(ts)).from_buffer(array("Q", [0 if t is None else t if isinstance(t, int)
+                                                          else t.data_ptr() for t in ts]))
+
+
+def marshal_descs(descs: Sequence[LayerDesc]):
+    """The C array of layer descriptors a batched call takes, built once.
+
+    Every batched call accepts the result of a ``marshal_*`` function in place of the Python list it was
+    made from, and then skips the conversion: a training loop whose layers and buffers are fixed converts
+    them once instead of on every call (for a hundred layers the conversion costs as much host time as the
+    preconditioning kernels take on the GPU)."""
+    return _descs(list(descs))
+
+
+def marshal_ptrs(tensors):
+    """The C array of device addresses of ``tensors`` (see marshal_descs).  The array holds addresses, not
+    references: the caller keeps the tensors alive and at the same addresses for as long as it is used."""
+    return _ptrs(list(tensors))
+
+
+def marshal_ints(values: Sequence[int]):
+    """The C int array of ``values`` (see marshal_descs)."""
+    return _ints(list(values))
+
+
+def marshal_floats(values: Sequence[float]):
+    """The C float array of ``values`` (see marshal_descs)."""
+    return _floats(list(values))
 
 
 def kfac_status_string(status: int) -> str:

@@ -40,8 +40,10 @@ class GpuLayerResult:
     pass
 
 
-def run_layers_gpu(layers, batch, inputs, scales, decay, damping, dtype="f32", batched=True, A0=None, G0=None):
-    """inputs: list of (act, gout, grad) numpy arrays.  Returns per-layer dict of numpy results."""
+def run_layers_gpu(layers, batch, inputs, scales, decay, damping, dtype="f32", batched=True, A0=None, G0=None,
+                   marshalled=False):
+    """inputs: list of (act, gout, grad) numpy arrays.  Returns per-layer dict of numpy results.
+    marshalled: the batched calls get C arrays built beforehand instead of Python lists."""
     n = len(layers)
     bf = dtype == "bf16"
     descs = [kf.LayerDesc.from_spec(l, kf.KFAC_BF16 if bf else kf.KFAC_F32) for l in layers]
@@ -61,9 +63,18 @@ def run_layers_gpu(layers, batch, inputs, scales, decay, damping, dtype="f32", b
     sG = [s[1] for s in scales]
     if batched:
         ws = workspace(kf.kfac_workspace_bytes_batched(descs, b, h, w))
-        kf.kfac_update_factors_batched(descs, acts, gouts, b, h, w, sA, sG, decay, A_run, G_run, ws)
-        kf.kfac_invert_batched(descs, A_run, G_run, damping, damping, A_inv, G_inv, info, ws)
-        kf.kfac_precondition_batched(descs, A_inv, G_inv, grads, outs, ws)
+        if marshalled:
+            P = kf.marshal_ptrs
+            md, mb, mh, mw = kf.marshal_descs(descs), kf.marshal_ints(b), kf.marshal_ints(h), kf.marshal_ints(w)
+            mAr, mGr, mAi, mGi = P(A_run), P(G_run), P(A_inv), P(G_inv)
+            kf.kfac_update_factors_batched(md, P(acts), P(gouts), mb, mh, mw, kf.marshal_floats(sA),
+                                           kf.marshal_floats(sG), decay, mAr, mGr, ws)
+            kf.kfac_invert_batched(md, mAr, mGr, damping, damping, mAi, mGi, info, ws)
+            kf.kfac_precondition_batched(md, mAi, mGi, P(grads), P(outs), ws)
+        else:
+            kf.kfac_update_factors_batched(descs, acts, gouts, b, h, w, sA, sG, decay, A_run, G_run, ws)
+            kf.kfac_invert_batched(descs, A_run, G_run, damping, damping, A_inv, G_inv, info, ws)
+            kf.kfac_precondition_batched(descs, A_inv, G_inv, grads, outs, ws)
     else:
         for i in range(n):
             ws = workspace(kf.kfac_workspace_bytes(descs[i], b[i], h[i], w[i]))

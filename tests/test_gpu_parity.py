@@ -394,6 +394,11 @@ def test_batched_mixed_layers_match_oracle_and_single_calls():
         ref = gu.run_layer_oracle(l, inputs[i], scales[i], 0.9, 0.01)
         gu.check_layer(g1[i], ref, tag=f"batched {i}")
         gu.check_layer(g2[i], ref, tag=f"single {i}")
+    # the same batched calls on C arrays built beforehand: the same launches, the same bits
+    g3 = gu.run_layers_gpu(layers, batch, inputs, scales, 0.9, 0.01, batched=True, marshalled=True)
+    for i in range(len(layers)):
+        for k in ("A", "G", "A_inv", "G_inv", "P"):
+            assert np.array_equal(g1[i][k], g3[i][k]), (i, k)
 
 
 def test_running_average_ends_and_repeat_is_bitwise_reproducible():

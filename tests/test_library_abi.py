@@ -86,3 +86,21 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert lib.kfac_precondition(ctypes.byref(d), fake, fake, fake, fake, fake, 16, None) == 4
     with pytest.raises(kf.KfacError):
         kf.kfac_precondition(d, fake, fake, fake, fake, None, stream=0)
+
+
+def test_marshalled_arrays_hold_the_values_and_pass_through():
+    descs = [kf.LayerDesc.linear(8, 4), kf.LayerDesc.conv2d(3, 16, 3, 1, 1, has_bias=False)]
+    md = kf.marshal_descs(descs)
+    assert len(md) == 2 and md[1].d_out == 16 and md[1].has_bias == 0 and md[0].d_in == 8
+    mp = kf.marshal_ptrs([0x1000, None, 0x7f0000001000])
+    assert [mp[i] for i in range(3)] == [0x1000, None, 0x7f0000001000]
+    mi, mf = kf.marshal_ints([3, 0, -1]), kf.marshal_floats([0.5, 2.0])
+    assert list(mi) == [3, 0, -1] and list(mf) == [0.5, 2.0]
+    # a batched call takes the arrays in place of the lists: same answer, no conversion
+    b = kf.marshal_ints([4, 2])
+    one = kf.marshal_ints([1, 1])
+    hw = kf.marshal_ints([1, 8])
+    assert kf.kfac_workspace_bytes_batched(md, b, one, hw) == kf.kfac_workspace_bytes_batched(descs, [4, 2], [1, 1],
+                                                                                              [1, 8])
+    from paper_2206_15143_amd import binding
+    assert binding._descs(md) is md and binding._ptrs(mp) is mp and binding._ints(mi) is mi
