@@ -334,7 +334,7 @@ constexpr int kBf16Cfg = 8;    // row-major bf16 operands on the bf16 MFMA units
 bool small_eligible(const FactorJob &j)
 {
     return tuning().use_small_kernel && j.dtype == 0 && j.layout == kNCHW && j.d_core <= 64 && !j.has_bias &&
-           j.hw % 4 == 0;
+           j.hw % 4 == 0 && j.hw < (1l << 22);      // 32-bit element offsets inside an image
 }
 
 bool bf16_eligible(const FactorJob &j)
@@ -479,7 +479,7 @@ void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<
             p.rows_per_stage = conv3_choose_rows(jobs[j].h, jobs[j].w);
             p.unit_rows = p.rows_per_stage * jobs[j].w;
         } else {
-            p.unit_rows = (p.cfg == kBf16Cfg) ? H_KT : 16;
+            p.unit_rows = (p.cfg == kBf16Cfg) ? H_KT : (p.cfg == kSmall32Cfg || p.cfg == kSmall64Cfg) ? S_GROUP : 16;
         }
         // A block that holds a single unit (one macro tile in all) spreads it over its four waves and
         // needs a quarter of the time per K row: give it four times the rows.
@@ -490,7 +490,7 @@ void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<
     // The narrow-NCHW kernel is bound by loads in flight, not by MFMAs: several of its light workgroups
     // share a CU, so it gets four times the blocks.
     const int cfg0 = pl[idx[0]].cfg;
-    const long target = (cfg0 == kSmall32Cfg || cfg0 == kSmall64Cfg) ? 4 * tu.target_blocks : tu.target_blocks;
+    const long target = (cfg0 == kSmall32Cfg || cfg0 == kSmall64Cfg) ? tu.small_blocks_x * tu.target_blocks : tu.target_blocks;
     long tpb = (long)std::ceil(work / (double)target);
     tpb = std::max<long>(tpb, tu.min_tiles_per_split);
     // Blocks of a launch carry equal work and run about one per CU, so a launch a few blocks over the
@@ -501,8 +501,8 @@ void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<
             Planned &p = pl[j];
             const Cfg &c = kCfgs[p.cfg];
             long ktiles = std::max<long>(1, (jobs[j].K + p.unit_rows - 1) / p.unit_rows);
-            if (p.cfg == kSmall32Cfg || p.cfg == kSmall64Cfg)   // walked in 16-position groups per image
-                ktiles = (jobs[j].K / jobs[j].hw) * ((jobs[j].hw + 15) / 16);
+            if (p.cfg == kSmall32Cfg || p.cfg == kSmall64Cfg)   // walked in groups of positions that never cross an image
+                ktiles = (jobs[j].K / jobs[j].hw) * ((jobs[j].hw + S_GROUP - 1) / S_GROUP);
             if (p.cfg == kWaveNchwCfg)   // 16-position stages that never cross an image
                 ktiles = (jobs[j].K / jobs[j].hw) * ((jobs[j].hw + W_KT - 1) / W_KT);
             if (p.cfg == kBf16Cfg && jobs[j].layout == kNCHW)   // 32-position stages that never cross an image
@@ -791,6 +791,7 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
             p.splits = pl[j].splits;
             p.tiles_per_split = pl[j].tps;
             p.blk_start = blocks;
+            tab.starts[k] = blocks;
             p.red_start = 0;
             p.vec = vec_ok(job) ? 1 : 0;
             p.has_bias = job.has_bias;

@@ -26,6 +26,7 @@ struct SyrkProb {
 struct SyrkTable {
     int count;
     int debug;   // measurement switches of the wave kernel (0 in normal use): 1 = no MFMAs, 2 = no data loads
+    int starts[kMaxProblems];   // blk_start of every problem, compact: searched by bisection
     SyrkProb p[kMaxProblems];
 };
 

@@ -96,6 +96,8 @@ def test_fused_3x3_conv_factor(cin, h, batch, bias):
     (64, 8, 9),      # four tiles
     (40, 4, 6),      # d not a multiple of 16, HW = 16
     (24, 7, 4),      # HW = 49 is not a multiple of 4: the block-tile kernel takes it
+    (8, 12, 5),      # d = 8: the second load of the tile (channels 8..15) reads nothing; HW = 144 = 4.5 groups
+    (16, 32, 3),     # HW = 1024, the map of config 2's first stage: 32 groups per image
 ])
 def test_narrow_nchw_output_gradient_factor(cout, h, batch):
     # G of a conv layer with few output channels: read from NCHW by the direct (no-LDS) kernel
