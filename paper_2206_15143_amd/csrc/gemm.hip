@@ -5,6 +5,7 @@
 // panel products and rank-k updates of the blocked inversion.  Wide products
 // go to the wave-unit kernel (gemm_wave.hpp), the rest to the block-tile kernel
 // below.
+#include <type_traits>
 #include "gemm_wave.hpp"
 
 #include <algorithm>
@@ -75,38 +76,48 @@ __global__ __launch_bounds__(T::NT) void gemm_tn_kernel(const GemmTable tab)
 #pragma unroll
         for (int j = 0; j < T::WT; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    // The small tiles serve the short, latency-bound products (a few workgroups per matrix, each walking
-    // the whole depth): there the panels are fetched D stages ahead into a ring of register sets, so that a
-    // stage waits for a load issued D stages earlier.  Set r holds stage t with t mod D = r; it is free
-    // again once that stage has been written to LDS.  The large tiles keep one set (registers).
+    // The panels are fetched D stages ahead into a ring of register sets, so that a stage waits for loads
+    // issued D stages earlier: the short, latency-bound products (a few workgroups per matrix, each walking
+    // the whole depth) live on that.  Set r holds stage t with t mod D = r; it is free again once that stage
+    // has been written to LDS.  The large tiles keep one set (registers).
     constexpr int D = T::BM <= 64 ? 3 : 1;
     const long ktiles = (pr.K + T::KT - 1) / T::KT;
-    floatx4 sa[D][T::PASSES], sb[D][T::PASSES];
+    auto k_loop = [&](auto vec_a, auto vec_b) {
+        constexpr bool VA = decltype(vec_a)::value, VB = decltype(vec_b)::value;
+        floatx4 sa[D][T::PASSES], sb[D][T::PASSES];
 #pragma unroll
-    for (int r = 0; r < D; ++r) {       // stages past the depth fetch nothing and hold zeros
-        fetch_panel<T, kRows, 0>(sa[r], opA, (long)r * T::KT, m0, tid);
-        fetch_panel<T, kRows, 0>(sb[r], opB, (long)r * T::KT, n0, tid);
-    }
-    commit_panel<T, kRows>(sa[0], lds[0][0], tid);
-    commit_panel<T, kRows>(sb[0], lds[0][1], tid);
-    __syncthreads();
-    for (long t0 = 0; t0 < ktiles; t0 += D) {
-#pragma unroll
-        for (int r = 0; r < D; ++r) {
-            const long t = t0 + r;
-            if (t >= ktiles) break;
-            const int cur = (int)(t & 1);
-            if (t + D < ktiles) {
-                fetch_panel<T, kRows, 0>(sa[r], opA, (t + D) * T::KT, m0, tid);
-                fetch_panel<T, kRows, 0>(sb[r], opB, (t + D) * T::KT, n0, tid);
-            }
-            mma_stage<T, kRows, kRows, false>(lds[cur][0], lds[cur][1], wm, wn, lane, acc);
-            if (t + 1 < ktiles) {
-                commit_panel<T, kRows>(sa[(r + 1) % D], lds[cur ^ 1][0], tid);
-                commit_panel<T, kRows>(sb[(r + 1) % D], lds[cur ^ 1][1], tid);
-            }
-            __syncthreads();
+        for (int r = 0; r < D; ++r) {       // stages past the depth re-read the last rows and are never written to LDS
+            fetch_rows_clamped<T, 0, VA>(sa[r], opA, (long)r * T::KT, m0, tid);
+            fetch_rows_clamped<T, 0, VB>(sb[r], opB, (long)r * T::KT, n0, tid);
+            __builtin_amdgcn_sched_barrier(0);      // issued in the order the loop consumes them
         }
+        commit_rows_masked<T>(sa[0], opA, 0, m0, lds[0][0], tid);
+        commit_rows_masked<T>(sb[0], opB, 0, n0, lds[0][1], tid);
+        __syncthreads();
+        for (long t0 = 0; t0 < ktiles; t0 += D) {
+#pragma unroll
+            for (int r = 0; r < D; ++r) {
+                const long t = t0 + r;
+                if (t >= ktiles) break;
+                const int cur = (int)(t & 1);
+                fetch_rows_clamped<T, 0, VA>(sa[r], opA, (t + D) * T::KT, m0, tid);
+                fetch_rows_clamped<T, 0, VB>(sb[r], opB, (t + D) * T::KT, n0, tid);
+                mma_stage<T, kRows, kRows, false>(lds[cur][0], lds[cur][1], wm, wn, lane, acc);
+                if (t + 1 < ktiles) {
+                    commit_rows_masked<T>(sa[(r + 1) % D], opA, (t + 1) * T::KT, m0, lds[cur ^ 1][0], tid);
+                    commit_rows_masked<T>(sb[(r + 1) % D], opB, (t + 1) * T::KT, n0, lds[cur ^ 1][1], tid);
+                }
+                __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    };
+    if (opA.vec) {
+        if (opB.vec) k_loop(std::true_type{}, std::true_type{});
+        else k_loop(std::true_type{}, std::false_type{});
+    } else {
+        if (opB.vec) k_loop(std::false_type{}, std::true_type{});
+        else k_loop(std::false_type{}, std::false_type{});
     }
 
     const int lr = lane & 15, lk = lane >> 4;

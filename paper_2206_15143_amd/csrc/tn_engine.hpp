@@ -115,6 +115,63 @@ __device__ __forceinline__ void fetch_panel(floatx4 (&st)[T::PASSES], const Oper
     }
 }
 
+// Row-major panels for a prefetch ring: every load is issued unconditionally, from an address clamped into
+// the operand, and what lies outside is zeroed when the panel is written to LDS (commit_rows_masked).  A
+// load under a condition cannot be counted as in flight by the compiler, which then waits for every
+// outstanding load wherever it needs one of them, and a ring of register sets is left without effect.
+// VEC (aligned 4-element loads) is a template argument for the same reason: both shapes of load in one
+// loop, chosen at run time, would again leave the count open.
+template <class T, int DT, bool VEC>
+__device__ __forceinline__ void fetch_rows_clamped(floatx4 (&st)[T::PASSES], const Operand &op, long k0, int col0,
+                                                   int tid)
+{
+#pragma unroll
+    for (int p = 0; p < T::PASSES; ++p) {
+        int idx = tid + p * T::NT;
+        if (T::V4 % T::NT != 0 && idx >= T::V4) idx = T::V4 - 1;      // threads without a slot in the last pass
+        const int r = idx / (T::BM / 4);
+        const int c = (idx % (T::BM / 4)) * 4;
+        long k = k0 + r;
+        if (k >= op.K) k = op.K - 1;
+        const int col = col0 + c;
+        if (VEC) {
+            // col0 is a tile origin inside the operand and a multiple of 4; the row pitch is a multiple of 4
+            // and at least d, so the four elements from any aligned column below d lie inside the row
+            st[p] = load4<DT>(op.x, k * op.ld + (col < op.d ? col : col0));
+        } else {
+            const int last = op.d - 1;
+            floatx4 v;
+            v.x = load1<DT>(op.x, k * op.ld + (col < last ? col : last));
+            v.y = load1<DT>(op.x, k * op.ld + (col + 1 < last ? col + 1 : last));
+            v.z = load1<DT>(op.x, k * op.ld + (col + 2 < last ? col + 2 : last));
+            v.w = load1<DT>(op.x, k * op.ld + (col + 3 < last ? col + 3 : last));
+            st[p] = v;
+        }
+    }
+}
+
+template <class T>
+__device__ __forceinline__ void commit_rows_masked(const floatx4 (&st)[T::PASSES], const Operand &op, long k0,
+                                                   int col0, float *lds, int tid)
+{
+#pragma unroll
+    for (int p = 0; p < T::PASSES; ++p) {
+        const int idx = tid + p * T::NT;
+        if (idx < T::V4) {
+            const int r = idx / (T::BM / 4);
+            const int c = (idx % (T::BM / 4)) * 4;
+            const bool row = k0 + r < op.K;
+            const int col = col0 + c;
+            floatx4 v;
+            v.x = (row && col < op.d) ? st[p].x : 0.f;
+            v.y = (row && col + 1 < op.d) ? st[p].y : 0.f;
+            v.z = (row && col + 2 < op.d) ? st[p].z : 0.f;
+            v.w = (row && col + 3 < op.d) ? st[p].w : 0.f;
+            *reinterpret_cast<floatx4 *>(lds + r * T::PITCH + c) = v;
+        }
+    }
+}
+
 // ---- registers -> LDS --------------------------------------------------------
 template <class T, int LAYOUT>
 __device__ __forceinline__ void commit_panel(const floatx4 (&st)[T::PASSES], float *lds, int tid)
