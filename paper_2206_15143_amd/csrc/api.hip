@@ -772,6 +772,7 @@ int kfac_tune(const char *key, long value)
     Tuning &t = tuning();
     const std::string k(key ? key : "");
     if (k == "target_blocks") t.target_blocks = value;
+    else if (k == "tile_max_splits") t.tile_max_splits = value < 1 ? 1 : value;
     else if (k == "small_blocks_x") t.small_blocks_x = value < 1 ? 1 : value;
     else if (k == "min_tiles_per_split") t.min_tiles_per_split = value;
     else if (k == "patch_chunk_bytes") t.patch_chunk_bytes = value;

@@ -111,6 +111,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 // development knobs (set through kfac_tune)
 struct Tuning {
     long target_blocks = 512;        // blocks a grouped SYRK launch aims for
+    long tile_max_splits = 256;      // cap on the K splits of a block-tile SYRK problem (serial chain of its reduction)
     long small_blocks_x = 1;         // multiple of target_blocks for the narrow-NCHW kernel (loads in flight, light blocks)
     long min_tiles_per_split = 16;   // K tiles (of 16 rows) per split at least
     long patch_chunk_bytes = 160l << 20;   // patch bytes materialised per chunk in the batched path

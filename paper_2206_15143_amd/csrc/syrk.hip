@@ -264,13 +264,32 @@ __device__ __forceinline__ void syrk_reduce_body(const SyrkProb &pr, int local, 
             if (chunk < CPT && u2 < pr.d && v2 < u2) pr.F[(long)v2 * dF + u2] = mir[q][r2][c2];
         }
     } else {
+        // bias row: LP adjacent lanes share an element and take every LP-th split, four loads in flight each;
+        // their sums meet by shuffles (fixed order: deterministic).  A single serial chain over a hundred
+        // splits cost more than the tiles of the factor.
         const int bi = local - nblk * GPT;
         const float *csum = pr.partial + (long)pr.splits * nblk * TILE;
-        for (int r = threadIdx.x; r < T::BM; r += 256) {
-            const int u = bi * T::BM + r;
-            if (u >= pr.d) continue;
-            float s = 0.f;
-            for (int k = 0; k < pr.splits; ++k) s += csum[((long)k * pr.nb + bi) * T::BM + r];
+        constexpr int LP = T::BM <= 32 ? 8 : T::BM <= 64 ? 4 : T::BM <= 128 ? 2 : 1;
+        const int r = threadIdx.x / LP, j = threadIdx.x % LP;
+        const int u = bi * T::BM + r;
+        const bool live = r < T::BM && u < pr.d;
+        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+        if (live) {
+            const long step = (long)pr.nb * T::BM;
+            const float *col = csum + (long)bi * T::BM + r;
+            int k = j;
+            for (; k + 3 * LP < pr.splits; k += 4 * LP) {
+                a0 += col[k * step];
+                a1 += col[(k + LP) * step];
+                a2 += col[(k + 2 * LP) * step];
+                a3 += col[(k + 3 * LP) * step];
+            }
+            for (; k < pr.splits; k += LP) a0 += col[k * step];
+        }
+        float s = (a0 + a1) + (a2 + a3);
+#pragma unroll
+        for (int h = 1; h < LP; h <<= 1) s += __shfl_xor(s, h);
+        if (live && j == 0) {
             const float out = pr.decay * pr.F[(long)pr.d * dF + u] + wnew * s;
             pr.F[(long)pr.d * dF + u] = out;
             pr.F[(long)u * dF + pr.d] = out;
@@ -515,7 +534,7 @@ void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<
             p.splits = (int)((ktiles + tpb_j - 1) / tpb_j);
             // every element of the block-tile kernels' partials is summed serially over the splits by one
             // thread of the reduction: keep that chain short
-            if (p.cfg < kWaveCfg) p.splits = std::min(p.splits, 128);
+            if (p.cfg < kWaveCfg) p.splits = std::min<int>(p.splits, (int)tu.tile_max_splits);
             p.tps = (int)((ktiles + p.splits - 1) / p.splits);
             p.splits = (int)((ktiles + p.tps - 1) / p.tps);
             p.partial_floats = (size_t)p.splits * ((size_t)p.nblk * c.bm * c.bm + (size_t)p.nb * c.bm);
