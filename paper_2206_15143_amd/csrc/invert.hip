@@ -523,7 +523,10 @@ AuxStream *aux_stream()
 hipError_t blocked_launch_pair(const InvertJob *jobs, const std::vector<int> &idx, const std::vector<size_t> &offs,
                                void *work, InvProbF *dtab, hipStream_t s)
 {
-    AuxStream *aux = (tuning().invert_two_streams && idx.size() >= 2) ? aux_stream() : nullptr;
+    // With a handful of matrices every launch of a run is a few workgroups, and two runs double the number of
+    // launches that sit in a row: measured slower with 4 matrices of order 1345..1569 (2.33 -> 2.64 ms), faster
+    // from 12 matrices on (threshold: invert_two_streams_min).
+    AuxStream *aux = (tuning().invert_two_streams && (long)idx.size() >= tuning().invert_two_streams_min) ? aux_stream() : nullptr;
     if (!aux) return blocked_launch(jobs, idx, offs, work, dtab, s);
     BlockedRun run[2];
     for (size_t k = 0; k < idx.size(); ++k) run[k & 1].idx.push_back(idx[k]);   // sorted by order: dealt alternately

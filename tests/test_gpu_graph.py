@@ -15,7 +15,16 @@ from workloads.shapes import LayerSpec
 import gpu_util as gu
 
 
-def test_three_calls_captured_in_a_graph_replay_like_eager():
+@pytest.fixture
+def two_streams_from_two_matrices():
+    # the library forks to its second stream from 8 large matrices on: lower the threshold so that the two
+    # order-1301 factors of this test take that path
+    kf.kfac_tune("invert_two_streams_min", 2)
+    yield
+    kf.kfac_tune("invert_two_streams_min", 8)
+
+
+def test_three_calls_captured_in_a_graph_replay_like_eager(two_streams_from_two_matrices):
     layers = [LayerSpec("conv", 16, 16, 3, 1, 1, 8),            # A factor from autocorrelations
               LayerSpec("conv", 3, 8, 3, 1, 1, 8),              # patch extraction + block-tile kernel
               LayerSpec("conv", 8, 8, 1, 1, 0, 4),
