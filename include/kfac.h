@@ -104,7 +104,7 @@ kfac_status kfac_update_factors(const kfac_layer_desc *desc, const void *d_act, 
 
 /* Damped inverses (section 5.2, matrix-inversion variant with the damping of
  * each factor given explicitly).  d_info: 2 ints (A, G).
- * Streams: with two or more factors of order above 1280 in one call, part of
+ * Streams: with eight or more factors of order above 1280 in one call, part of
  * the work runs on a second stream that the library creates once per device
  * (default priority), forked from and joined back to hip_stream by events inside
  * the call: ordering on hip_stream is as if everything ran there. */
