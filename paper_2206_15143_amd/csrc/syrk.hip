@@ -20,6 +20,7 @@
 //                            the running average, writes both triangles.
 // The planner below picks the kernel and the split of K per factor and groups
 // equal choices into launches of up to 40 factors.
+#include <type_traits>
 #include "tn_engine.hpp"
 
 #include <algorithm>
@@ -76,43 +77,108 @@ __global__ __launch_bounds__(T::NT) void syrk_partial_kernel(const SyrkTable tab
     const bool active = !diag || wn <= wm;
     const bool tri = diag && wn == wm;
 
-    floatx4 su[T::PASSES], sv[T::PASSES];
-    if (t0 < t1) {
-        fetch_panel<T, LAYOUT, DT>(su, op, t0 * T::KT, u0, tid);
-        if (!diag) fetch_panel<T, LAYOUT, DT>(sv, op, t0 * T::KT, v0, tid);
-        if (do_colsum) {
+    if constexpr (LAYOUT == kRows && T::BM <= 64) {
+        // Small tiles, row-major operand: a few workgroups walk a long K with little work per stage, so the loop
+        // is bound by the latency of its loads.  The panels are fetched D stages ahead into a ring of register
+        // sets; every load is unconditional (clamped address, zeroed before use) and the shape of the loop
+        // (vector or scalar loads, one panel or two) is fixed at compile time, so that the compiler can count
+        // the loads in flight and wait for the oldest set only.
+        constexpr int D = 3;
+        auto k_loop = [&](auto vec_c, auto diag_c) {
+            constexpr bool VEC = decltype(vec_c)::value, DG = decltype(diag_c)::value;
+            floatx4 su[D][T::PASSES], sv[D][T::PASSES];
 #pragma unroll
-            for (int p = 0; p < T::PASSES; ++p) cs[p] += su[p];
+            for (int r = 0; r < D; ++r) {
+                fetch_rows_clamped<T, DT, VEC>(su[r], op, (t0 + r) * T::KT, u0, tid);
+                if (!DG) fetch_rows_clamped<T, DT, VEC>(sv[r], op, (t0 + r) * T::KT, v0, tid);
+                __builtin_amdgcn_sched_barrier(0);      // issued in the order the loop consumes them
+            }
+            auto stage_in = [&](floatx4 (&pu)[T::PASSES], floatx4 (&pv)[T::PASSES], long t, int buf) {
+                mask_rows<T>(pu, op, t * T::KT, u0, tid);
+                if (do_colsum) {
+#pragma unroll
+                    for (int p = 0; p < T::PASSES; ++p) cs[p] += pu[p];
+                }
+                commit_panel<T, kRows>(pu, lds[buf][0], tid);
+                if (!DG) {
+                    mask_rows<T>(pv, op, t * T::KT, v0, tid);
+                    commit_panel<T, kRows>(pv, lds[buf][1], tid);
+                }
+            };
+            stage_in(su[0], sv[0], t0, 0);
+            __syncthreads();
+            for (long tb = t0; tb < t1; tb += D) {
+#pragma unroll
+                for (int r = 0; r < D; ++r) {
+                    const long t = tb + r;
+                    if (t >= t1) break;
+                    const int cur = (int)((t - t0) & 1);
+                    // stages past the split (or past K) are read from clamped rows and never used
+                    fetch_rows_clamped<T, DT, VEC>(su[r], op, (t + D) * T::KT, u0, tid);
+                    if (!DG) fetch_rows_clamped<T, DT, VEC>(sv[r], op, (t + D) * T::KT, v0, tid);
+                    if (active) {
+                        const float *Us = lds[cur][0];
+                        const float *Vs = DG ? lds[cur][0] : lds[cur][1];
+                        if (tri)
+                            mma_stage<T, LAYOUT, LAYOUT, true>(Us, Vs, wm, wn, lane, acc);
+                        else
+                            mma_stage<T, LAYOUT, LAYOUT, false>(Us, Vs, wm, wn, lane, acc);
+                    }
+                    if (t + 1 < t1) stage_in(su[(r + 1) % D], sv[(r + 1) % D], t + 1, cur ^ 1);
+                    __syncthreads();
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        };
+        if (t0 < t1) {
+            if (op.vec) {
+                if (diag) k_loop(std::true_type{}, std::true_type{});
+                else k_loop(std::true_type{}, std::false_type{});
+            } else {
+                if (diag) k_loop(std::false_type{}, std::true_type{});
+                else k_loop(std::false_type{}, std::false_type{});
+            }
         }
-        commit_panel<T, LAYOUT>(su, lds[0][0], tid);
-        if (!diag) commit_panel<T, LAYOUT>(sv, lds[0][1], tid);
-    }
-    __syncthreads();
-
-    for (long t = t0; t < t1; ++t) {
-        const int cur = (int)((t - t0) & 1);
-        const bool more = (t + 1 < t1);
-        if (more) {
-            fetch_panel<T, LAYOUT, DT>(su, op, (t + 1) * T::KT, u0, tid);
-            if (!diag) fetch_panel<T, LAYOUT, DT>(sv, op, (t + 1) * T::KT, v0, tid);
-        }
-        if (active) {
-            const float *Us = lds[cur][0];
-            const float *Vs = diag ? lds[cur][0] : lds[cur][1];
-            if (tri)
-                mma_stage<T, LAYOUT, LAYOUT, true>(Us, Vs, wm, wn, lane, acc);
-            else
-                mma_stage<T, LAYOUT, LAYOUT, false>(Us, Vs, wm, wn, lane, acc);
-        }
-        if (more) {
+    } else {
+        floatx4 su[T::PASSES], sv[T::PASSES];
+        if (t0 < t1) {
+            fetch_panel<T, LAYOUT, DT>(su, op, t0 * T::KT, u0, tid);
+            if (!diag) fetch_panel<T, LAYOUT, DT>(sv, op, t0 * T::KT, v0, tid);
             if (do_colsum) {
-#pragma unroll
+    #pragma unroll
                 for (int p = 0; p < T::PASSES; ++p) cs[p] += su[p];
             }
-            commit_panel<T, LAYOUT>(su, lds[cur ^ 1][0], tid);
-            if (!diag) commit_panel<T, LAYOUT>(sv, lds[cur ^ 1][1], tid);
+            commit_panel<T, LAYOUT>(su, lds[0][0], tid);
+            if (!diag) commit_panel<T, LAYOUT>(sv, lds[0][1], tid);
         }
         __syncthreads();
+
+        for (long t = t0; t < t1; ++t) {
+            const int cur = (int)((t - t0) & 1);
+            const bool more = (t + 1 < t1);
+            if (more) {
+                fetch_panel<T, LAYOUT, DT>(su, op, (t + 1) * T::KT, u0, tid);
+                if (!diag) fetch_panel<T, LAYOUT, DT>(sv, op, (t + 1) * T::KT, v0, tid);
+            }
+            if (active) {
+                const float *Us = lds[cur][0];
+                const float *Vs = diag ? lds[cur][0] : lds[cur][1];
+                if (tri)
+                    mma_stage<T, LAYOUT, LAYOUT, true>(Us, Vs, wm, wn, lane, acc);
+                else
+                    mma_stage<T, LAYOUT, LAYOUT, false>(Us, Vs, wm, wn, lane, acc);
+            }
+            if (more) {
+                if (do_colsum) {
+    #pragma unroll
+                    for (int p = 0; p < T::PASSES; ++p) cs[p] += su[p];
+                }
+                commit_panel<T, LAYOUT>(su, lds[cur ^ 1][0], tid);
+                if (!diag) commit_panel<T, LAYOUT>(sv, lds[cur ^ 1][1], tid);
+            }
+            __syncthreads();
+        }
+
     }
 
     // ---- partial tile out ----

@@ -150,6 +150,24 @@ __device__ __forceinline__ void fetch_rows_clamped(floatx4 (&st)[T::PASSES], con
     }
 }
 
+// Zero what a clamped fetch read from outside the operand (in registers, before the panel is used).
+template <class T>
+__device__ __forceinline__ void mask_rows(floatx4 (&st)[T::PASSES], const Operand &op, long k0, int col0, int tid)
+{
+#pragma unroll
+    for (int p = 0; p < T::PASSES; ++p) {
+        const int idx = tid + p * T::NT;
+        const int r = idx / (T::BM / 4);
+        const int c = (idx % (T::BM / 4)) * 4;
+        const bool row = idx < T::V4 && k0 + r < op.K;
+        const int col = col0 + c;
+        st[p].x = (row && col < op.d) ? st[p].x : 0.f;
+        st[p].y = (row && col + 1 < op.d) ? st[p].y : 0.f;
+        st[p].z = (row && col + 2 < op.d) ? st[p].z : 0.f;
+        st[p].w = (row && col + 3 < op.d) ? st[p].w : 0.f;
+    }
+}
+
 template <class T>
 __device__ __forceinline__ void commit_rows_masked(const floatx4 (&st)[T::PASSES], const Operand &op, long k0,
                                                    int col0, float *lds, int tid)
