@@ -45,6 +45,10 @@ def test_config1_fc_tiny_end_to_end():
     (144, 16, 300, True),     # the 144 tile config
     (150, 40, 257, False),    # just over 144, no bias, rows not a multiple of 16
     (300, 130, 100, True),    # several tiles per side, R < d (rank deficient before the average)
+    (100, 40, 3000, True),    # two 64-tiles per side (diagonal and off-diagonal blocks), many K stages and splits: the
+                              # prefetch ring of the small row-major tiles, aligned loads (ld = 100), long bias sums
+    (45, 33, 777, False),     # odd row pitch (scalar loads), K = 48 stages + 9 rows, no bias
+    (27, 16, 8200, True),     # the stem's shape class: 28-column factor, one 32-tile, hundreds of splits
 ])
 def test_linear_layers(d_in, d_out, rows, bias):
     layer = LayerSpec("linear", d_in, d_out, rows=rows, has_bias=bias)
