@@ -58,7 +58,8 @@ typedef enum {
     KFAC_ERR_WORKSPACE = 4,  /* workspace smaller than kfac_workspace_bytes says */
     KFAC_ERR_PARAM = 5,      /* decay outside [0,1], negative damping, scale <= 0 */
     KFAC_ERR_HIP = 6,        /* a HIP launch failed */
-    KFAC_ERR_ALIGN = 7       /* a device pointer is not aligned as required */
+    KFAC_ERR_ALIGN = 7,      /* a device pointer is not aligned as required */
+    KFAC_ERR_TOO_LARGE = 8   /* kfac_precondition_static: d_A * d_G * 4 exceeds KFAC_STATIC_SCRATCH_BYTES */
 } kfac_status;
 
 typedef enum { KFAC_F32 = 0, KFAC_BF16 = 1 } kfac_dtype;
@@ -125,6 +126,18 @@ kfac_status kfac_invert_pi(const kfac_layer_desc *desc, const float *d_A_run, co
 kfac_status kfac_precondition(const kfac_layer_desc *desc, const float *d_A_inv, const float *d_G_inv,
                               const float *d_grad, float *d_out, void *d_work, size_t work_bytes,
                               void *hip_stream);
+
+/* kfac_precondition for callers that cannot allocate device memory or pass a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same two products, by the same kernels,
+ * with the d_A x d_G intermediate in a buffer of KFAC_STATIC_SCRATCH_BYTES that is part of the library image
+ * (one copy per GPU, held until the process ends).  Allocates nothing.  A layer with
+ * d_A * d_G * 4 > KFAC_STATIC_SCRATCH_BYTES is rejected with KFAC_ERR_TOO_LARGE before any launch.  Every
+ * call on a GPU shares that GPU's buffer: calls that may overlap on one GPU (different streams, different
+ * host threads) race and must be ordered by the caller.  Nothing in the buffer needs clearing between calls
+ * (the first product overwrites all of what the second reads).  Arguments as kfac_precondition. */
+#define KFAC_STATIC_SCRATCH_BYTES (32u << 20)
+kfac_status kfac_precondition_static(const kfac_layer_desc *desc, const float *d_A_inv, const float *d_G_inv,
+                                     const float *d_grad, float *d_out, void *hip_stream);
 
 /* Eigen-decomposition variant of the preconditioner (section 5.2, Eq. 13).
  *

@@ -86,6 +86,7 @@ def load_library():
     lib.kfac_invert_pi_batched.argtypes = [C.c_int, dp, vpp, vpp, C.c_float, vpp, vpp, vp, vp, vp, sz, vp]
     lib.kfac_invert_pi_batched.restype = C.c_int
     lib.kfac_precondition.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]; lib.kfac_precondition.restype = C.c_int
+    lib.kfac_precondition_static.argtypes = [dp, vp, vp, vp, vp, vp]; lib.kfac_precondition_static.restype = C.c_int
     lib.kfac_update_factors_batched.argtypes = [C.c_int, dp, vpp, vpp, ip, ip, ip, fp, fp, C.c_float, vpp, vpp,
                                                 vp, sz, vp]
     lib.kfac_update_factors_batched.restype = C.c_int
@@ -278,6 +279,14 @@ def kfac_invert_pi(desc, A_run, G_run, gamma, A_inv, G_inv, info, damping, work,
 def kfac_precondition(desc, A_inv, G_inv, grad, out, work, stream=None) -> None:
     _check(load_library().kfac_precondition(C.byref(desc), _ptr(A_inv), _ptr(G_inv), _ptr(grad), _ptr(out),
                                             _ptr(work), _nbytes(work), _stream(stream)), "kfac_precondition")
+
+
+KFAC_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def kfac_precondition_static(desc, A_inv, G_inv, grad, out, stream=None) -> None:
+    _check(load_library().kfac_precondition_static(C.byref(desc), _ptr(A_inv), _ptr(G_inv), _ptr(grad), _ptr(out),
+                                                   _stream(stream)), "kfac_precondition_static")
 
 
 def kfac_update_factors_batched(descs, acts, gouts, batch, h, w, scale_A, scale_G, decay, A_runs, G_runs, work,

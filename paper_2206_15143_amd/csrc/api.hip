@@ -5,9 +5,14 @@
 #include "common.hpp"
 
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <tuple>
 #include <vector>
+
+// Intermediate product of kfac_precondition_static: device memory that belongs to the library image, one copy
+// per GPU, held until the process ends.  In host code this name is only a handle for hipGetSymbolAddress.
+static __device__ __align__(256) unsigned char scratch[KFAC_STATIC_SCRATCH_BYTES];
 
 namespace kfac {
 
@@ -697,6 +702,39 @@ kfac_status kfac_precondition_eigen(const kfac_layer_desc *d, const float *d_Q_A
                                            work_bytes, hip_stream);
 }
 
+// Device address of `scratch` on the current device, looked up once per device.
+static kfac_status static_scratch_ptr(void **out)
+{
+    static std::mutex mu;
+    static void *per_dev[64] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return KFAC_ERR_HIP;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!per_dev[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return KFAC_ERR_HIP;
+        per_dev[dev] = p;
+    }
+    *out = per_dev[dev];
+    return KFAC_OK;
+}
+
+kfac_status kfac_precondition_static(const kfac_layer_desc *d, const float *d_A_inv, const float *d_G_inv,
+                                     const float *d_grad, float *d_out, void *hip_stream)
+{
+    kfac_status st = desc_check(d);
+    if (st != KFAC_OK) return st;
+    const size_t dA = (size_t)core_dim(d) + d->has_bias, dG = (size_t)d->d_out;
+    if (dA * dG * sizeof(float) > (size_t)KFAC_STATIC_SCRATCH_BYTES) return KFAC_ERR_TOO_LARGE;
+    void *ptr = nullptr;
+    st = static_scratch_ptr(&ptr);
+    if (st != KFAC_OK) return st;
+    // the intermediate U^T [d_A, d_G] is written in full by the first product before the second reads it:
+    // nothing in the buffer has to start at zero
+    return kfac_precondition_batched(1, d, &d_A_inv, &d_G_inv, &d_grad, &d_out, ptr, KFAC_STATIC_SCRATCH_BYTES,
+                                     hip_stream);
+}
+
 const char *kfac_status_string(kfac_status s)
 {
     switch (s) {
@@ -708,6 +746,7 @@ const char *kfac_status_string(kfac_status s)
         case KFAC_ERR_PARAM: return "bad parameter";
         case KFAC_ERR_HIP: return "HIP launch failed";
         case KFAC_ERR_ALIGN: return "misaligned pointer";
+        case KFAC_ERR_TOO_LARGE: return "problem exceeds the library's static scratch buffer";
     }
     return "unknown status";
 }
