@@ -33,7 +33,8 @@ enum {
     KFAC_K_EIG_FINAL = 16,   /* eigen-decomposition: eigenvalues and Q = V^T; transposes for Eq. 13 */
     KFAC_K_SYRK_CORR3 = 17,  /* KF-GEMM of 3x3 convolutions from input autocorrelations (lag matrices) */
     KFAC_K_CORR3_ASM = 18,   /* border terms, sums and assembly (+ running average) of that path */
-    KFAC_K_COUNT = 19
+    KFAC_K_GEMM_SPLIT = 19,  /* A^T B of fp32 operands as six bf16 MFMA products of their bf16 pieces */
+    KFAC_K_COUNT = 20
 };
 
 /* When enabled, every kernel launch is bracketed by a pair of HIP events
@@ -49,6 +50,12 @@ int kfac_timing_enable(int on);
  * and old factor read, factor written to both triangles).  Returns 0, or
  * non-zero on a HIP error. */
 int kfac_timing_collect(double *ms_per_class, long *launches_per_class, double *work_per_class);
+/* The same with a fourth array: the flops each class's kernels execute on the MFMA units by their own method
+ * (equal to the work of the definition except where the method differs: fewer for the factors built from
+ * autocorrelations, six bf16 products per fp32 product for the split-bf16 GEMM).  Set for the KF-GEMM and
+ * GEMM classes, 0 elsewhere. */
+int kfac_timing_collect_ex(double *ms_per_class, long *launches_per_class, double *work_per_class,
+                           double *executed_per_class);
 const char *kfac_timing_class_name(int cls);
 
 /* Plain device-to-device copy kernel (calib_copy_kernel) of `bytes` bytes (a

@@ -107,6 +107,9 @@ def load_library():
     lib.kfac_timing_enable.argtypes = [C.c_int]; lib.kfac_timing_enable.restype = C.c_int
     lib.kfac_timing_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_long), C.POINTER(C.c_double)]
     lib.kfac_timing_collect.restype = C.c_int
+    lib.kfac_timing_collect_ex.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_long), C.POINTER(C.c_double),
+                                           C.POINTER(C.c_double)]
+    lib.kfac_timing_collect_ex.restype = C.c_int
     lib.kfac_profile_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.kfac_profile_copy.restype = C.c_int
     lib.kfac_timing_class_name.argtypes = [C.c_int]; lib.kfac_timing_class_name.restype = C.c_char_p
@@ -206,7 +209,7 @@ def kfac_tune(key: str, value: int) -> None:
         raise KeyError(key)
 
 
-KFAC_K_COUNT = 19
+KFAC_K_COUNT = 20
 
 
 def kfac_profile_copy(dst, src, nbytes: int, stream=None) -> None:
@@ -228,6 +231,20 @@ def kfac_timing_collect() -> dict:
     if lib.kfac_timing_collect(ms, cnt, work) != 0:
         raise RuntimeError("kfac_timing_collect: HIP event error")
     return {lib.kfac_timing_class_name(i).decode(): (float(ms[i]), int(cnt[i]), float(work[i]))
+            for i in range(KFAC_K_COUNT)}
+
+
+def kfac_timing_collect_ex() -> dict:
+    """{class name: (milliseconds, launches, work, executed)}: as kfac_timing_collect plus the flops the class's
+    kernels execute on the MFMA units by their own method."""
+    lib = load_library()
+    ms = (C.c_double * KFAC_K_COUNT)()
+    cnt = (C.c_long * KFAC_K_COUNT)()
+    work = (C.c_double * KFAC_K_COUNT)()
+    ex = (C.c_double * KFAC_K_COUNT)()
+    if lib.kfac_timing_collect_ex(ms, cnt, work, ex) != 0:
+        raise RuntimeError("kfac_timing_collect_ex: HIP event error")
+    return {lib.kfac_timing_class_name(i).decode(): (float(ms[i]), int(cnt[i]), float(work[i]), float(ex[i]))
             for i in range(KFAC_K_COUNT)}
 
 

@@ -25,7 +25,7 @@ Tuning &tuning()
 namespace {
 struct TimingState {
     bool on = false;
-    struct Rec { int cls; hipEvent_t a, b; double work; };
+    struct Rec { int cls; hipEvent_t a, b; double work, executed; };
     std::vector<Rec> recs;
     std::vector<hipEvent_t> pool;
     hipEvent_t get()
@@ -47,7 +47,7 @@ void timing_begin(int cls, hipStream_t s)
 {
     TimingState &t = timing();
     if (!t.on) return;
-    TimingState::Rec r{cls, t.get(), t.get(), 0.0};
+    TimingState::Rec r{cls, t.get(), t.get(), 0.0, 0.0};
     (void)hipEventRecord(r.a, s);
     t.recs.push_back(r);
 }
@@ -59,11 +59,12 @@ void timing_end(hipStream_t s)
     (void)hipEventRecord(t.recs.back().b, s);
 }
 
-void timing_work(double work)
+void timing_work(double work, double executed)
 {
     TimingState &t = timing();
     if (!t.on || t.recs.empty()) return;
     t.recs.back().work = work;
+    t.recs.back().executed = executed < 0.0 ? work : executed;
 }
 
 namespace {
@@ -759,7 +760,7 @@ int kfac_timing_enable(int on)
     return 0;
 }
 
-int kfac_timing_collect(double *ms, long *launches, double *work)
+int kfac_timing_collect_ex(double *ms, long *launches, double *work, double *executed)
 {
     auto &t = timing();
     int rc = 0;
@@ -769,11 +770,17 @@ int kfac_timing_collect(double *ms, long *launches, double *work)
         if (ms) ms[r.cls] += e;
         if (launches) launches[r.cls] += 1;
         if (work) work[r.cls] += r.work;
+        if (executed) executed[r.cls] += r.executed;
         t.pool.push_back(r.a);
         t.pool.push_back(r.b);
     }
     t.recs.clear();
     return rc;
+}
+
+int kfac_timing_collect(double *ms, long *launches, double *work)
+{
+    return kfac_timing_collect_ex(ms, launches, work, nullptr);
 }
 
 const char *kfac_timing_class_name(int cls)
@@ -782,7 +789,7 @@ const char *kfac_timing_class_name(int cls)
                                               "inv_pivot", "inv_panel", "inv_finish", "gemm_tn",
                                               "syrk_wave", "syrk_conv3", "syrk_small", "inv_step",
                                               "syrk_bf16", "gemm_wave", "eig_init", "eig_round", "eig_final",
-                                              "syrk_corr3", "corr3_assemble"};
+                                              "syrk_corr3", "corr3_assemble", "gemm_split"};
     return (cls >= 0 && cls < KFAC_K_COUNT) ? names[cls] : "?";
 }
 
@@ -836,6 +843,8 @@ int kfac_tune(const char *key, long value)
     else if (k == "im2col_min_blocks") t.im2col_min_blocks = value;
     else if (k == "use_bf16_mfma") t.use_bf16_mfma = value;
     else if (k == "use_wave_gemm") t.use_wave_gemm = value;
+    else if (k == "use_split_gemm") t.use_split_gemm = value;
+    else if (k == "split_gemm_min_m") t.split_gemm_min_m = value;
     else if (k == "gemm_xcd_remap_min") t.gemm_xcd_remap_min = value;
     else if (k == "gemm_bm") t.gemm_bm = value;
     else return 1;

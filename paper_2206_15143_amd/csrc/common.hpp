@@ -57,7 +57,8 @@ struct GemmJob {
     int M, N, K;
     long lda, ldb, ldc;
     int mode;        // GemmMode
-    int p0, p1;      // kSubLowerSkip: rows/cols in [p0, p1) are left untouched
+    int p0, p1;      // kSubLowerSkip: rows/cols in [p0, p1) are left untouched; kSubRect: columns in [p0, p1)
+    long doff = 0;   // kSubRect: only entries with n <= m + doff are touched
     const float *rv = nullptr, *cv = nullptr;   // kStoreDiv
     float gamma = 0.f;
 };
@@ -66,7 +67,8 @@ enum GemmMode : int {
     kStore = 0,          // C[m][n] = acc
     kStoreT = 1,         // C[n][m] = acc   (ldc is the pitch of the transposed matrix)
     kSubLowerSkip = 2,   // C[m][n] -= acc for n <= m, m and n outside [p0, p1)
-    kStoreDiv = 3        // C[m][n] = acc / (rv[m] * cv[n] + gamma)   (the division of Eq. 13)
+    kStoreDiv = 3,       // C[m][n] = acc / (rv[m] * cv[n] + gamma)   (the division of Eq. 13)
+    kSubRect = 4         // C[m][n] -= acc for n <= m + doff, n outside [p0, p1)   (a rectangle of a lower triangle)
 };
 
 // Symmetric eigen-decomposition M = Q diag(v) Q^T (eigenvectors in the columns of Q, order not sorted).
@@ -121,7 +123,7 @@ struct Tuning {
     long im2col_min_blocks = 1024;   // shorter strips until a layer has this many workgroups
     long eigen_max_sweeps = 20;      // sweep budget of the block Jacobi eigen-decomposition (12-13 used at order 577)
     long eigen_inner_sweeps = 1;     // Jacobi sweeps over the 32 x 32 Gram matrix of a pair of blocks per round
-    long invert_outer_block = 288;   // outer pivot block of the two-level inversion (multiple of 288)
+    long invert_outer_block = 256;   // outer pivot block of the two-level inversion (multiple of 32)
     long invert_border = 1;          // orders 64 k + 1: last row and column by bordering instead of a one-row pivot block
     long invert_two_streams = 1;     // large matrices in two groups on two streams (small launches of one beside the updates of the other)
     long invert_two_streams_min = 8; // ... from this many large matrices on
@@ -133,6 +135,8 @@ struct Tuning {
     long use_bf16_mfma = 1;          // row-major bf16 operands: bf16 MFMA kernel instead of widening to fp32
     long gemm_xcd_remap_min = 8;     // wave GEMM launches with at least this many problems renumber their tiles per XCD
     long use_wave_gemm = 1;          // wide A^T B products on the wave-unit GEMM
+    long use_split_gemm = 1;         // large A^T B products as six bf16 MFMA products of the operands' bf16 pieces
+    long split_gemm_min_m = 192;     // ... from this many output rows on
     long use_small_kernel = 1;       // direct MFMA kernel for narrow NCHW operands (d <= 64)
     long fuse_conv3 = 1;             // 3x3/s1/p1 fp32 convs: build A straight from the NCHW input
     long update_bm = 64;             // block tile of the inverse's rank-64 update GEMM (0 = choose; 64 measured best)
@@ -144,7 +148,10 @@ Tuning &tuning();
 // Optional per-launch HIP-event timing (see include/kfac_profile.h).
 void timing_begin(int cls, hipStream_t s);
 void timing_end(hipStream_t s);
-void timing_work(double work);   // algorithmic work of the launch recorded last
+// work of the launch recorded last: `work` in units of the definition (flops of the factor, inverse or product
+// being computed, or bytes), `executed` the flops the kernel's own method spends on the MFMA units (negative:
+// the same as `work`)
+void timing_work(double work, double executed = -1.0);
 
 // Launch wrapper: records the event pair when timing is enabled.
 #define KFAC_LAUNCH(cls, stream, kernel, grid, block, smem, ...)               \

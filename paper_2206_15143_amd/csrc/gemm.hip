@@ -7,6 +7,7 @@
 // below.
 #include <type_traits>
 #include "gemm_wave.hpp"
+#include "gemm_split.hpp"
 
 #include <algorithm>
 #include <vector>
@@ -23,6 +24,7 @@ struct GemmProb {
     int blk_start;
     int mode;
     int p0, p1;
+    long doff;
     int vecA, vecB;
     const float *rv, *cv;   // kStoreDiv
     float gamma;
@@ -138,6 +140,9 @@ __global__ __launch_bounds__(T::NT) void gemm_tn_kernel(const GemmTable tab)
                     pr.C[(long)n * pr.ldc + m] = val;
                 } else if (pr.mode == kStoreDiv) {
                     pr.C[(long)m * pr.ldc + n] = val / (pr.rv[m] * pr.cv[n] + pr.gamma);
+                } else if (pr.mode == kSubRect) {
+                    const bool skip = ((long)n > (long)m + pr.doff) || (n >= pr.p0 && n < pr.p1);
+                    if (!skip) pr.C[(long)m * pr.ldc + n] -= val;
                 } else {
                     const bool skip = (n > m) || (m >= pr.p0 && m < pr.p1) || (n >= pr.p0 && n < pr.p1);
                     if (!skip) pr.C[(long)m * pr.ldc + n] -= val;
@@ -173,17 +178,46 @@ template <class T>
 hipError_t launch_one(const GemmTable &tab, int blocks, hipStream_t s)
 {
     KFAC_LAUNCH(KFAC_K_GEMM, s, (gemm_tn_kernel<T>), dim3(blocks), dim3(T::NT), 0, tab);
+    double flops = 0.0;
+    for (int k = 0; k < tab.count; ++k) {
+        const GemmProb &p = tab.p[k];
+        if (p.mode != kSubLowerSkip) { flops += 2.0 * p.M * p.N * p.K; continue; }
+        const double live = (double)p.M - (double)(std::min(p.p1, p.M) - p.p0);
+        flops += live * (live + 1.0) * p.K;
+    }
+    timing_work(flops, flops);
     return hipGetLastError();
 }
 
 }  // namespace
 
 namespace {
+// flops of the definition of a product (the lower-triangle update counts the entries it touches)
+double gemm_job_flops(const GemmJob &j)
+{
+    if (j.mode == kSubRect) {
+        // rows m = 0..M-1 touch the columns n <= min(N - 1, m + doff) outside [p0, p1)
+        double cnt = 0.0;
+        for (int m = 0; m < j.M; ++m) {
+            const long hi = std::min<long>(j.N - 1, m + j.doff);
+            if (hi < 0) continue;
+            long c = hi + 1;
+            const long a = std::max<long>(0, j.p0), b = std::min<long>(hi + 1, j.p1);
+            if (b > a) c -= b - a;
+            cnt += (double)c;
+        }
+        return 2.0 * cnt * j.K;
+    }
+    if (j.mode != kSubLowerSkip) return 2.0 * j.M * j.N * j.K;
+    const double live = (double)j.M - (double)(std::min(j.p1, j.M) - j.p0);
+    return live * (live + 1.0) * j.K;
+}
+
 // Products wide enough to fill 144-wide macro tiles go to the wave-unit kernel.  A lower-triangular
 // update qualifies only when its untouched band starts and ends on macro-tile boundaries.
 bool wave_gemm_eligible(const GemmJob &j)
 {
-    if (!tuning().use_wave_gemm || j.mode == kStoreT || j.mode == kStoreDiv) return false;
+    if (!tuning().use_wave_gemm || j.mode == kStoreT || j.mode == kStoreDiv || j.mode == kSubRect) return false;
     if (j.M < 100 || j.N < 100 || j.K < 16) return false;
     if ((long)j.K * j.lda * 4 > 0x7fffffffl || (long)j.K * j.ldb * 4 > 0x7fffffffl) return false;
     if (((uintptr_t)j.A) % 4 || ((uintptr_t)j.B) % 4) return false;
@@ -197,6 +231,7 @@ hipError_t wave_gemm_launch(const GemmJob *jobs, const std::vector<int> &idx, hi
     GemmWTable tab;
     tab.count = 0;
     long blocks = 0;
+    double wflops = 0.0;
     auto flush = [&]() -> hipError_t {
         if (tab.count == 0) return hipSuccess;
         // Contiguous tile ranges per XCD pay when a launch spans many problems of similar depth (each XCD
@@ -209,6 +244,8 @@ hipError_t wave_gemm_launch(const GemmJob *jobs, const std::vector<int> &idx, hi
         }
         tab.xcd_remap = (tab.count >= tuning().gemm_xcd_remap_min && 2 * kmax <= 3 * kmin) ? 1 : 0;
         KFAC_LAUNCH(KFAC_K_GEMM_WAVE, s, gemm_wave_kernel, dim3((unsigned)blocks), dim3(256), 0, tab);
+        timing_work(wflops, wflops);
+        wflops = 0.0;
         tab.count = 0;
         blocks = 0;
         return hipGetLastError();
@@ -224,6 +261,7 @@ hipError_t wave_gemm_launch(const GemmJob *jobs, const std::vector<int> &idx, hi
         p.nJ2 = (nJ + 1) / 2;
         p.mode = j.mode; p.p0 = j.p0; p.p1 = j.p1;
         p.blk_start = (int)blocks;
+        wflops += gemm_job_flops(j);
         if (j.mode == kSubLowerSkip) {
             for (int I = 0; I < p.mI; ++I) blocks += I / 2 + 1;
         } else {
@@ -238,12 +276,66 @@ hipError_t wave_gemm_launch(const GemmJob *jobs, const std::vector<int> &idx, hi
 }
 }  // namespace
 
+namespace {
+// Products that fill 256 x 128 tiles reasonably go to the split-bf16 kernel (gemm_split.hpp).
+bool split_gemm_eligible(const GemmJob &j)
+{
+    if (!tuning().use_split_gemm || (j.mode != kStore && j.mode != kSubLowerSkip && j.mode != kSubRect)) return false;
+    if (j.M < tuning().split_gemm_min_m || j.N < 64 || j.K < 16) return false;
+    if ((long)j.K * j.lda * 4 > 0x7fffffffl || (long)j.K * j.ldb * 4 > 0x7fffffffl) return false;
+    if ((long)j.M * j.ldc * 4 > 0x7fffffffl) return false;
+    if (((uintptr_t)j.A) % 4 || ((uintptr_t)j.B) % 4) return false;
+    if (j.mode == kSubLowerSkip) return j.M == j.N;
+    return true;
+}
+
+hipError_t split_gemm_launch(const GemmJob *jobs, const std::vector<int> &idx, hipStream_t s)
+{
+    GemmSTable tab;
+    tab.count = 0;
+    long blocks = 0;
+    double flops = 0.0;
+    auto flush = [&]() -> hipError_t {
+        if (tab.count == 0) return hipSuccess;
+        KFAC_LAUNCH(KFAC_K_GEMM_SPLIT, s, gemm_split_kernel, dim3((unsigned)blocks), dim3(256), 0, tab);
+        timing_work(flops, 6.0 * flops);
+        tab.count = 0;
+        blocks = 0;
+        flops = 0.0;
+        return hipGetLastError();
+    };
+    for (int i : idx) {
+        const GemmJob &j = jobs[i];
+        GemmSProb &p = tab.p[tab.count++];
+        p.A = j.A; p.B = j.B; p.C = j.C;
+        p.lda = (int)j.lda; p.ldb = (int)j.ldb; p.ldc = (int)j.ldc;
+        p.M = j.M; p.N = j.N; p.K = j.K;
+        p.tI = (j.M + S_BM - 1) / S_BM;
+        p.tJ = (j.N + S_BN - 1) / S_BN;
+        p.mode = j.mode; p.p0 = j.p0; p.p1 = j.p1;
+        p.doff = (int)std::min<long>(j.doff, 1l << 30);
+        if (j.mode == kSubLowerSkip) p.doff = 0;
+        p.blk_start = (int)blocks;
+        for (int I = 0; I < p.tI; ++I) blocks += split_row_len(p.mode, p.tJ, p.doff, I);
+        flops += gemm_job_flops(j);
+        if (tab.count == kMaxProblems) {
+            hipError_t e = flush();
+            if (e != hipSuccess) return e;
+        }
+    }
+    return flush();
+}
+}  // namespace
+
 hipError_t gemm_launch(const GemmJob *jobs, int n, hipStream_t s)
 {
     std::vector<int> cfg(n);
-    std::vector<int> wave;
+    std::vector<int> wave, split;
     for (int i = 0; i < n; ++i) {
-        if (jobs[i].M > 0 && jobs[i].N > 0 && jobs[i].K > 0 && wave_gemm_eligible(jobs[i])) {
+        if (jobs[i].M > 0 && jobs[i].N > 0 && jobs[i].K > 0 && split_gemm_eligible(jobs[i])) {
+            cfg[i] = -1;
+            split.push_back(i);
+        } else if (jobs[i].M > 0 && jobs[i].N > 0 && jobs[i].K > 0 && wave_gemm_eligible(jobs[i])) {
             cfg[i] = -1;
             wave.push_back(i);
         } else {
@@ -272,6 +364,11 @@ hipError_t gemm_launch(const GemmJob *jobs, int n, hipStream_t s)
             for (int i = 0; i < n; ++i)
                 if (cfg[i] >= 0 && jobs[i].mode != kSubLowerSkip) cfg[i] = best;
         }
+    }
+    if (!split.empty()) {
+        std::stable_sort(split.begin(), split.end(), [&](int a, int b) { return jobs[a].K > jobs[b].K; });
+        hipError_t e = split_gemm_launch(jobs, split, s);
+        if (e != hipSuccess) return e;
     }
     if (!wave.empty()) {
         // deepest products first: launches of similar depth, and the long workgroups start early
@@ -310,7 +407,7 @@ hipError_t gemm_launch(const GemmJob *jobs, int n, hipStream_t s)
             p.blk_start = blocks;
             tab.starts[tab.count - 1] = blocks;
             p.mode = j.mode;
-            p.p0 = j.p0; p.p1 = j.p1;
+            p.p0 = j.p0; p.p1 = j.p1; p.doff = j.doff;
             p.rv = j.rv; p.cv = j.cv; p.gamma = j.gamma;
             p.vecA = (((uintptr_t)j.A) % 16 == 0 && j.lda % 4 == 0) ? 1 : 0;
             p.vecB = (((uintptr_t)j.B) % 16 == 0 && j.ldb % 4 == 0) ? 1 : 0;

@@ -1,0 +1,303 @@
+// C = A^T B for fp32 operands (both K-major) on the bf16 MFMA units, at fp32 accuracy.
+//
+// MI355X multiplies bf16 matrices sixteen times faster than fp32 ones (2.5 PFLOP/s against 157 TFLOP/s),
+// so an fp32 product is cheaper as several bf16 products.  Every fp32 operand element is cut into three bf16
+// pieces, x = x1 + x2 + x3 (x1 = bf16(x), x2 = bf16(x - x1), x3 = bf16(x - x1 - x2): 3 x 8 significant bits,
+// the sum is exact), and the product keeps the six piece products down to 2^-16 of the leading one,
+//     a b  ~  a1 b1 + a1 b2 + a2 b1 + a1 b3 + a3 b1 + a2 b2,
+// each exact in the fp32 accumulator of v_mfma_f32_32x32x16_bf16.  The terms left out (a2 b3, a3 b2, a3 b3)
+// are below 2^-24 |a b|, the size of the rounding of an fp32 product: the result is as accurate as an fp32
+// MFMA product, for 6/16 of its MFMA time.
+//
+// Used for the preconditioning products (Eq. 5 of the DP-KFAC paper) and for the rank-k updates and panel
+// products of the blocked inversion (section 5.2).
+//
+// A workgroup of four wavefronts owns a 256 x 128 tile of C (256 columns of A, 128 of B); wave (wm, wn) owns
+// 128 x 64 of it: 4 x 2 MFMA tiles, 128 accumulator registers.  K is walked in stages of 16 rows = one MFMA
+// step.  The fp32 panels [16 k][256 | 128 columns] are copied from global memory straight into LDS by
+// buffer_load_dwordx4 ... lds (no staging registers) in a ring of three stage buffers, two stages in flight:
+// a stage waits for loads issued two stages earlier, which is what hides the latency of the loads behind the
+// 48 MFMAs of a stage (with the panels fetched through registers one stage ahead, the kernel spent three
+// quarters of its time waiting for them).  A lane reads the eight k of its row of an operand tile from the
+// panel (lanes along the columns: conflict-free), cuts them into the three pieces in registers and feeds the
+// MFMAs; the conversions (5.5 VALU operations per element) are issued in the shadow of the MFMAs.  Three stage
+// buffers take 72 KB: two workgroups share a CU, so the epilogue of one runs beside the MFMAs of the other.
+//
+// Rows past K lie outside the buffer range and arrive as zeros.  Columns past M (or N) may hold neighbouring
+// data (a 16-byte piece is not split); they only feed outputs that are never stored.
+#pragma once
+
+#include "wave_common.hpp"
+
+namespace kfac {
+
+constexpr int S_BM = 256;                     // rows of C per workgroup (columns of A)
+constexpr int S_BN = 128;                     // columns of C per workgroup (columns of B)
+constexpr int S_KT = 16;                      // rows of the operands per stage
+constexpr int S_PANEL_A = S_KT * S_BM;        // floats
+constexpr int S_PANEL_B = S_KT * S_BN;
+constexpr int S_STAGE = S_PANEL_A + S_PANEL_B;   // 6144 floats = 24 KB
+constexpr int S_NSTAGE = 3;
+constexpr int S_LDS_FLOATS = S_NSTAGE * S_STAGE; // 72 KB
+
+struct GemmSProb {
+    const float *A;
+    const float *B;
+    float *C;
+    int lda, ldb, ldc;
+    int M, N, K;
+    int tI, tJ;      // tiles over M (256 rows) and N (128 columns)
+    int blk_start;
+    int mode;        // kStore, kSubLowerSkip or kSubRect
+    int p0, p1;
+    int doff;        // the subtracting modes touch n <= m + doff (0 for kSubLowerSkip)
+};
+
+struct GemmSTable {
+    int count;
+    GemmSProb p[kMaxProblems];
+};
+
+// column tiles of tile row i: all of them, or those that reach the line n = m + doff
+__host__ __device__ inline int split_row_len(int mode, int tJ, int doff, int i)
+{
+    if (mode == kStore) return tJ;
+    const long last = ((long)i * S_BM + S_BM - 1 + doff) / S_BN + 1;
+    return (int)(last < tJ ? last : tJ);
+}
+
+typedef __bf16 sbf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 sbf16x2 __attribute__((ext_vector_type(2)));
+typedef float sfloat2 __attribute__((ext_vector_type(2)));
+typedef unsigned suint4 __attribute__((ext_vector_type(4)));
+
+// Eight fp32 values -> three packed bf16 pieces (round to nearest even at every level; the residuals are exact).
+__device__ __forceinline__ void split_pieces(const float (&x)[8], suint4 &p1, suint4 &p2, suint4 &p3)
+{
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const float a = x[2 * q], b = x[2 * q + 1];
+        const unsigned u1 = __builtin_bit_cast(unsigned, __builtin_convertvector(sfloat2{a, b}, sbf16x2));
+        const float ra = a - __builtin_bit_cast(float, u1 << 16);
+        const float rb = b - __builtin_bit_cast(float, u1 & 0xffff0000u);
+        const unsigned u2 = __builtin_bit_cast(unsigned, __builtin_convertvector(sfloat2{ra, rb}, sbf16x2));
+        const float sa = ra - __builtin_bit_cast(float, u2 << 16);
+        const float sb = rb - __builtin_bit_cast(float, u2 & 0xffff0000u);
+        const unsigned u3 = __builtin_bit_cast(unsigned, __builtin_convertvector(sfloat2{sa, sb}, sbf16x2));
+        p1[q] = u1;
+        p2[q] = u2;
+        p3[q] = u3;
+    }
+}
+
+__global__ __launch_bounds__(256, 2) void gemm_split_kernel(const GemmSTable tab)
+{
+    __shared__ __attribute__((aligned(16))) float lds[S_LDS_FLOATS];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = w >> 1, wn = w & 1;
+
+    // Every XCD takes a contiguous range of tile numbers (its L2 then sees few operand panels), and the tiles of
+    // a product are numbered in groups of four tile rows, column by column inside a group: the tiles that run
+    // at the same time share their A panels (four per group) and their B panels (one per four tiles).
+    const int bid = xcd_block_id();
+    int pi = 0;
+    while (pi + 1 < tab.count && bid >= tab.p[pi + 1].blk_start) ++pi;
+    const GemmSProb &pr = tab.p[pi];
+    int local = bid - pr.blk_start;
+    int I, J;
+    const bool lower = pr.mode != kStore;         // read-modify-write below the line n = m + doff
+    const bool rows_skip = pr.mode == kSubLowerSkip;
+    {
+        auto row_len = [&](int i) { return i >= pr.tI ? 0 : split_row_len(pr.mode, pr.tJ, pr.doff, i); };
+        int g = 0;
+        for (;;) {
+            const int c = row_len(4 * g) + row_len(4 * g + 1) + row_len(4 * g + 2) + row_len(4 * g + 3);
+            if (local < c) break;
+            local -= c;
+            ++g;
+        }
+        // inside the group: column J holds the rows whose length exceeds J (row lengths grow with i)
+        const int l0 = row_len(4 * g), l1 = row_len(4 * g + 1), l2 = row_len(4 * g + 2), l3 = row_len(4 * g + 3);
+        J = 0;
+        for (;;) {
+            const int c = (J < l0) + (J < l1) + (J < l2) + (J < l3);
+            if (local < c) break;
+            local -= c;
+            ++J;
+        }
+        // the local-th row (in increasing order) among those with length > J
+        int i = 0;
+        for (int seen = 0;; ++i) {
+            const int len = i == 0 ? l0 : (i == 1 ? l1 : (i == 2 ? l2 : l3));
+            if (J < len) {
+                if (seen == local) break;
+                ++seen;
+            }
+        }
+        I = 4 * g + i;
+    }
+    const int m0 = I * S_BM, n0 = J * S_BN;
+    if (lower) {
+        // tiles wholly inside the pivot rows or columns are left untouched
+        const int m1 = min(m0 + S_BM, pr.M), n1 = min(n0 + S_BN, pr.N);
+        if ((rows_skip && m0 >= pr.p0 && m1 <= pr.p1) || (n0 >= pr.p0 && n1 <= pr.p1)) return;
+    }
+
+    const int lda = pr.lda, ldb = pr.ldb;
+    const int nstages = (pr.K + S_KT - 1) / S_KT;
+    int4v rsrcA, rsrcB;
+    {
+        const unsigned long ba = (unsigned long)pr.A, bb = (unsigned long)pr.B;
+        const long na = (long)pr.K * lda * 4, nb = (long)pr.K * ldb * 4;
+        rsrcA.x = (int)(unsigned)ba; rsrcA.y = (int)(unsigned)(ba >> 32);
+        rsrcA.z = na > 0x7fffffffl ? 0x7fffffff : (int)na; rsrcA.w = 0x00020000;
+        rsrcB.x = (int)(unsigned)bb; rsrcB.y = (int)(unsigned)(bb >> 32);
+        rsrcB.z = nb > 0x7fffffffl ? 0x7fffffff : (int)nb; rsrcB.w = 0x00020000;
+    }
+    // this wave's copies of a stage: rows 4 w .. 4 w + 3 of the A panel (one instruction per row: 64 lanes x
+    // 4 columns) and of the B panel (one instruction per two rows: 32 lanes x 4 columns each)
+    const unsigned lds_base = (unsigned)(unsigned long)(__attribute__((address_space(3))) float *)lds;
+    const int ca = m0 + 4 * lane, cb = n0 + 4 * (lane & 31);
+    const unsigned voa = ca < pr.M ? (unsigned)(ca * 4) : W_OOB;
+    const unsigned vob = cb < pr.N ? (unsigned)(((lane >> 5) * ldb + cb) * 4) : W_OOB;
+    const unsigned rowa = (unsigned)lda * 4u, rowb = (unsigned)ldb * 4u;
+    auto issue = [&](int g) {
+        const bool live_stage = g < nstages;
+        const unsigned buf = lds_base + (unsigned)((g % S_NSTAGE) * S_STAGE * 4);
+        const unsigned k0 = (unsigned)(g * S_KT + 4 * w);
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            dma16(buf + (unsigned)((4 * w + r) * S_BM * 4), live_stage ? voa : W_OOB, rsrcA,
+                  live_stage ? (k0 + r) * rowa : 0u);
+#pragma unroll
+        for (int r = 0; r < 2; ++r)
+            dma16(buf + (unsigned)((S_PANEL_A + (4 * w + 2 * r) * S_BN) * 4), live_stage ? vob : W_OOB, rsrcB,
+                  live_stage ? (k0 + 2 * r) * rowb : 0u);
+    };
+
+    floatx16 acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+
+    const int lr = lane & 31, lg = lane >> 5;
+    // a wave whose 128 x 64 part lies wholly above the line n = m + doff has nothing to compute
+    const bool idle = lower && (n0 + wn * 64 > m0 + wm * 128 + 127 + pr.doff);
+    const int fa = 8 * lg * S_BM + wm * 128 + lr;                    // + e * S_BM (k) + t * 32 (tile)
+    const int fb = S_PANEL_A + 8 * lg * S_BN + wn * 64 + lr;
+
+    issue(0);
+    issue(1);
+    asm volatile("s_waitcnt vmcnt(6)\n\ts_barrier" ::: "memory");
+    for (int g = 0; g < nstages; ++g) {
+        issue(g + 2);        // into the buffer every wave left at the last barrier (stages past the end: zeros)
+        if (!idle) {
+            const float *buf = lds + (g % S_NSTAGE) * S_STAGE;
+            suint4 b1[2], b2[2], b3[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                float x[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) x[e] = buf[fb + e * S_BN + t * 32];
+                split_pieces(x, b1[t], b2[t], b3[t]);
+            }
+            // the panel reads of tile ti + 1 go out before the conversions and products of tile ti
+            float xn[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) xn[e] = buf[fa + e * S_BM];
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int ti = 0; ti < 4; ++ti) {
+                float x[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) x[e] = xn[e];
+                if (ti + 1 < 4) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) xn[e] = buf[fa + e * S_BM + (ti + 1) * 32];
+                }
+                suint4 a1, a2, a3;
+                split_pieces(x, a1, a2, a3);
+                const sbf16x8 A1 = __builtin_bit_cast(sbf16x8, a1), A2 = __builtin_bit_cast(sbf16x8, a2),
+                              A3 = __builtin_bit_cast(sbf16x8, a3);
+#pragma unroll
+                for (int tj = 0; tj < 2; ++tj) {
+                    const sbf16x8 B1 = __builtin_bit_cast(sbf16x8, b1[tj]), B2 = __builtin_bit_cast(sbf16x8, b2[tj]),
+                                  B3 = __builtin_bit_cast(sbf16x8, b3[tj]);
+                    floatx16 c = acc[ti * 2 + tj];
+                    // smallest terms first
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A2, B2, c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A3, B1, c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A1, B3, c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A2, B1, c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A1, B2, c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A1, B1, c, 0, 0, 0);
+                    acc[ti * 2 + tj] = c;
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        // at most the copies of the stage issued last are still on their way, then meet the other waves
+        asm volatile("s_waitcnt vmcnt(6)\n\ts_barrier" ::: "memory");
+    }
+    // the zero-filling copies of the stages past the end may still be landing
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    if (idle) return;
+
+    // ---- epilogue: acc[ti*2 + tj][v] = C[m0 + wm*128 + ti*32 + 8*(v>>2) + 4*lg + (v&3)][n0 + wn*64 + tj*32 + lr]
+    // An address is a wave-uniform row pointer (scalar registers) plus one per-lane offset that is the same for
+    // every tile and row: the 16 accesses of a tile need no address registers of their own.
+    const int mw = m0 + wm * 128, nw = n0 + wn * 64;
+    const long ldc = pr.ldc;
+    const unsigned lane_off = (unsigned)(4 * lg) * (unsigned)pr.ldc + (unsigned)lr;
+    auto row_ptr = [&](int t, int r) { return pr.C + ((long)(mw + (t >> 1) * 32 + r) * ldc + nw + (t & 1) * 32); };
+    if (!lower) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const int n = nw + (t & 1) * 32 + lr;
+            if (n >= pr.N) continue;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int r = 8 * (v >> 2) + (v & 3);
+                if (mw + (t >> 1) * 32 + r + 4 * lg < pr.M) row_ptr(t, r)[lane_off] = acc[t][v];
+            }
+        }
+        return;
+    }
+    // read-modify-write below the line n = m + doff, outside the pivot rows and columns: the 16 loads of a tile
+    // are issued together, and the loads of the next tile go out before the stores of the current one
+    const int p0 = pr.p0, p1 = pr.p1, doff = pr.doff;
+    auto live = [&](int m, int n) {
+        return m < pr.M && n < pr.N && n <= m + doff && !(rows_skip && m >= p0 && m < p1) && !(n >= p0 && n < p1);
+    };
+    auto load_tile = [&](int t, float (&old)[16]) {
+        const int n = nw + (t & 1) * 32 + lr;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = 8 * (v >> 2) + (v & 3);
+            old[v] = live(mw + (t >> 1) * 32 + r + 4 * lg, n) ? row_ptr(t, r)[lane_off] : 0.f;
+        }
+    };
+    auto store_tile = [&](int t, const float (&old)[16]) {
+        const int n = nw + (t & 1) * 32 + lr;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int r = 8 * (v >> 2) + (v & 3);
+            if (live(mw + (t >> 1) * 32 + r + 4 * lg, n)) row_ptr(t, r)[lane_off] = old[v] - acc[t][v];
+        }
+    };
+    float oa[16], ob[16];
+    load_tile(0, oa);
+#pragma unroll
+    for (int t = 0; t < 8; t += 2) {
+        load_tile(t + 1, ob);
+        store_tile(t, oa);
+        if (t + 2 < 8) load_tile(t + 2, oa);
+        store_tile(t + 1, ob);
+    }
+}
+
+}  // namespace kfac

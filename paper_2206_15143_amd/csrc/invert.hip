@@ -28,6 +28,7 @@
 #include "invert_fused.hpp"
 
 #include <algorithm>
+#include <mutex>
 #include <vector>
 
 namespace kfac {
@@ -81,7 +82,7 @@ __global__ __launch_bounds__(256) void sweep_init_kernel(const InvTable tab)
 // gather / scatter tiles; PB below is its value for the current call).  576 is 6-8 % faster on the
 // workloads with many large factors, but the error of the inverse grows with the order of the explicitly
 // inverted pivot block (measured at order 2305: 1.5e-5 / 2.9e-5 / 4.0e-5 for 288 / 576 / 864), so 288 stays.
-inline int outer_block() { return (int)std::max(288l, tuning().invert_outer_block / 288 * 288); }
+inline int outer_block() { return (int)std::max(64l, tuning().invert_outer_block / 32 * 32); }
 
 struct BlkProb {
     float *W;          // working matrix [n, n]
@@ -225,12 +226,12 @@ __global__ __launch_bounds__(256) void sweep_finish_kernel(const InvTable tab)
 namespace {
 bool takes_fused(int n) { return n <= tuning().invert_fused_max_n; }
 size_t fused_ws_floats(int n) { return 2 * (size_t)NB * NB + 2 * (size_t)NB * ((n + 3) / 4 * 4); }
-// large matrices: V, W panels, P, the workspace of the nested pivot-block inversion, its status word
+// large matrices: two sets of V, W panels, P, the workspace of the nested pivot-block inversion, its status word
 size_t job_ws_floats(int n)
 {
     if (takes_fused(n)) return fused_ws_floats(n);
     const size_t PB = (size_t)outer_block();
-    return 2 * PB * ((n + 3) / 4 * 4) + PB * PB + fused_ws_floats((int)PB) + 64;
+    return 4 * PB * ((n + 3) / 4 * 4) + PB * PB + fused_ws_floats((int)PB) + 64;
 }
 size_t table_bytes(int n) { return align_up((size_t)2 * n * sizeof(InvProbF), 256); }
 
@@ -309,10 +310,15 @@ hipError_t fused_launch(const InvertJob *jobs, const std::vector<int> &idx, cons
     }
     return hipSuccess;
 }
-// Two-level blocked sweep of the matrices listed in `idx` (sorted by order, largest first), as three calls
-// (start, one outer step, finish) so that two groups of matrices can advance side by side on two streams.
+// Two-level blocked sweep of the matrices listed in `idx` (sorted by order, largest first).  An outer step K is
+// cut into a *chain* (inverse of pivot block K, gather of the old panel, panel product, scatter: short dependent
+// launches) and a *bulk* rank-PB update of everything outside the pivot rows and columns.  With look-ahead the
+// chain of step K+1 runs on a second stream beside the bulk update of step K: the bulk update then leaves out
+// the rows and columns of pivot block K+1 as well, and the chain of step K+1 first applies update K to just
+// that band (two rectangular products), so that its pivot block and panel are ready without waiting for the
+// bulk.  Panels are double buffered (the bulk of step K reads panels K while the chain writes panels K+1).
 struct BlockedRun {
-    struct Big { float *Vt, *Wt, *P, *nws; int *ninfo; int ldv; };
+    struct Big { float *Vt[2], *Wt[2], *P, *nws; int *ninfo; int ldv; };
     const InvertJob *jobs = nullptr;
     std::vector<int> idx;
     const std::vector<size_t> *offs = nullptr;
@@ -323,11 +329,20 @@ struct BlockedRun {
     std::vector<InvertJob> nested;
     std::vector<int> nidx;
     std::vector<size_t> noffs;
-    std::vector<GemmJob> gp, gu;
+    std::vector<GemmJob> gj;
 
+    int active(int st) const
+    {
+        int a = 0;
+        while (a < total && jobs[idx[a]].n > st * PB) ++a;
+        return a;
+    }
     hipError_t start(hipStream_t s);
-    hipError_t step(int st, hipStream_t s);
+    hipError_t look(int st, hipStream_t s);     // update st applied to the band of pivot block st + 1
+    hipError_t chain(int st, hipStream_t s);
+    hipError_t bulk(int st, bool skip_next, hipStream_t s);
     hipError_t finish(hipStream_t s);
+    hipError_t copy_kernel(bool scatter, int st, int act, hipStream_t s);
 };
 
 hipError_t BlockedRun::start(hipStream_t s)
@@ -340,9 +355,12 @@ hipError_t BlockedRun::start(hipStream_t s)
         float *ws = reinterpret_cast<float *>(static_cast<char *>(work) + (*offs)[idx[k]]);
         Big &b = big[k];
         b.ldv = (j.n + 3) / 4 * 4;
-        b.Vt = ws;
-        b.Wt = b.Vt + (size_t)PB * b.ldv;
-        b.P = b.Wt + (size_t)PB * b.ldv;
+        const size_t panel = (size_t)PB * b.ldv;
+        b.Vt[0] = ws;
+        b.Wt[0] = ws + panel;
+        b.Vt[1] = ws + 2 * panel;
+        b.Wt[1] = ws + 3 * panel;
+        b.P = ws + 4 * panel;
         b.nws = b.P + (size_t)PB * PB;
         b.ninfo = reinterpret_cast<int *>(b.nws + fused_ws_floats(PB));
     }
@@ -368,91 +386,117 @@ hipError_t BlockedRun::start(hipStream_t s)
     return hipSuccess;
 }
 
-hipError_t BlockedRun::step(int st, hipStream_t s)
+hipError_t BlockedRun::copy_kernel(bool scatter, int st, int act, hipStream_t s)
 {
-    {
-        const int p0 = st * PB;
-        int active = 0;
-        while (active < total && jobs[idx[active]].n > p0) ++active;
-        // 1. inverse of the pivot blocks (in their current, updated state) -> P
-        nested.assign(active, InvertJob());
-        nidx.resize(active);
-        noffs.resize(active);
-        for (int k = 0; k < active; ++k) {
-            const InvertJob &j = jobs[idx[k]];
-            InvertJob &q = nested[k];
-            q.M = j.Minv + (size_t)p0 * j.n + p0;
-            q.Minv = big[k].P;
-            q.n = std::min(PB, j.n - p0);
-            q.damping = 0.f;
-            q.info = big[k].ninfo;
-            q.ldm = j.n;
-            q.ldo = PB;
-            nidx[k] = k;
-            noffs[k] = (size_t)(reinterpret_cast<char *>(big[k].nws) - static_cast<char *>(work));
+    const int p0 = st * PB;
+    for (int g0 = 0; g0 < act; g0 += 32) {
+        BlkTable tab;
+        tab.count = std::min(32, act - g0);
+        int blocks = 0;
+        for (int k = 0; k < tab.count; ++k) {
+            const InvertJob &j = jobs[idx[g0 + k]];
+            BlkProb &p = tab.p[k];
+            p.W = j.Minv; p.Vt = big[g0 + k].Vt[st & 1]; p.Wt = big[g0 + k].Wt[st & 1]; p.P = big[g0 + k].P;
+            p.info = j.info; p.ninfo = big[g0 + k].ninfo;
+            p.n = j.n; p.ldv = big[g0 + k].ldv; p.p0 = p0; p.bs = std::min(PB, j.n - p0); p.pb = PB;
+            p.blk_start = blocks;
+            blocks += ((j.n + 31) / 32) * ((p.bs + 31) / 32);
         }
-        // nested problems are grouped by order (all PB except possibly the last block of a matrix)
-        std::stable_sort(nidx.begin(), nidx.end(), [&](int a, int b) { return nested[a].n > nested[b].n; });
-        hipError_t e = fused_launch(nested.data(), nidx, noffs, work, dtab, s);
+        if (scatter) KFAC_LAUNCH(KFAC_K_INV_PANEL, s, blk_scatter_kernel, dim3(blocks), dim3(256), 0, tab);
+        else KFAC_LAUNCH(KFAC_K_INV_PANEL, s, blk_gather_kernel, dim3(blocks), dim3(256), 0, tab);
+        hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        // 2. gather V, 3. W^T = P V^T, 4. update, 5. scatter
-        for (int g0 = 0; g0 < active; g0 += 32) {
-            BlkTable tab;
-            tab.count = std::min(32, active - g0);
-            int blocks = 0;
-            for (int k = 0; k < tab.count; ++k) {
-                const InvertJob &j = jobs[idx[g0 + k]];
-                BlkProb &p = tab.p[k];
-                p.W = j.Minv; p.Vt = big[g0 + k].Vt; p.Wt = big[g0 + k].Wt; p.P = big[g0 + k].P;
-                p.info = j.info; p.ninfo = big[g0 + k].ninfo;
-                p.n = j.n; p.ldv = big[g0 + k].ldv; p.p0 = p0; p.bs = std::min(PB, j.n - p0); p.pb = PB;
-                p.blk_start = blocks;
-                blocks += ((j.n + 31) / 32) * ((p.bs + 31) / 32);
-            }
-            KFAC_LAUNCH(KFAC_K_INV_PANEL, s, blk_gather_kernel, dim3(blocks), dim3(256), 0, tab);
-            e = hipGetLastError();
-            if (e != hipSuccess) return e;
-        }
-        gp.assign(active, GemmJob());
-        gu.assign(active, GemmJob());
-        int nupd = 0;
-        for (int k = 0; k < active; ++k) {
-            const InvertJob &j = jobs[idx[k]];
-            const int bs = std::min(PB, j.n - p0);
-            GemmJob &a = gp[k];
-            a.A = big[k].P; a.B = big[k].Vt; a.C = big[k].Wt;
-            a.M = bs; a.N = j.n; a.K = bs; a.lda = PB; a.ldb = big[k].ldv; a.ldc = big[k].ldv;
-            a.mode = kStore; a.p0 = a.p1 = 0;
-            if (j.n > PB) {
-                GemmJob &u = gu[nupd++];
-                u.A = big[k].Wt; u.B = big[k].Vt; u.C = j.Minv;
-                u.M = j.n; u.N = j.n; u.K = bs; u.lda = big[k].ldv; u.ldb = big[k].ldv; u.ldc = j.n;
-                u.mode = kSubLowerSkip; u.p0 = p0; u.p1 = p0 + bs;
-            }
-        }
-        e = gemm_launch(gp.data(), active, s);
-        if (e != hipSuccess) return e;
-        e = gemm_launch(gu.data(), nupd, s);
-        if (e != hipSuccess) return e;
-        for (int g0 = 0; g0 < active; g0 += 32) {
-            BlkTable tab;
-            tab.count = std::min(32, active - g0);
-            int blocks = 0;
-            for (int k = 0; k < tab.count; ++k) {
-                const InvertJob &j = jobs[idx[g0 + k]];
-                BlkProb &p = tab.p[k];
-                p.W = j.Minv; p.Vt = big[g0 + k].Vt; p.Wt = big[g0 + k].Wt; p.P = big[g0 + k].P;
-                p.info = j.info; p.ninfo = big[g0 + k].ninfo;
-                p.n = j.n; p.ldv = big[g0 + k].ldv; p.p0 = p0; p.bs = std::min(PB, j.n - p0); p.pb = PB;
-                p.blk_start = blocks;
-                blocks += ((j.n + 31) / 32) * ((p.bs + 31) / 32);
-            }
-            KFAC_LAUNCH(KFAC_K_INV_PANEL, s, blk_scatter_kernel, dim3(blocks), dim3(256), 0, tab);
-            e = hipGetLastError();
-            if (e != hipSuccess) return e;
-        }
     }
     return hipSuccess;
+}
+
+// Update st restricted to the band of pivot block st + 1 (rows q0..q1 left of and on the diagonal block, and
+// the columns q0..q1 below it), leaving out the columns of pivot block st, which the scatter of step st owns.
+hipError_t BlockedRun::look(int st, hipStream_t s)
+{
+    const int p0 = st * PB, q0 = p0 + PB;
+    const int act = active(st + 1);
+    gj.clear();
+    for (int k = 0; k < act; ++k) {
+        const InvertJob &j = jobs[idx[k]];
+        const int q1 = std::min(q0 + PB, j.n);
+        const Big &b = big[k];
+        const float *Wt = b.Wt[st & 1], *Vt = b.Vt[st & 1];
+        GemmJob r{};       // rows q0..q1, columns 0..q1 up to the diagonal
+        r.A = Wt + q0; r.B = Vt; r.C = j.Minv + (size_t)q0 * j.n;
+        r.M = q1 - q0; r.N = q1; r.K = PB; r.lda = b.ldv; r.ldb = b.ldv; r.ldc = j.n;
+        r.mode = kSubRect; r.p0 = p0; r.p1 = q0; r.doff = q0;
+        gj.push_back(r);
+        if (j.n > q1) {
+            GemmJob c{};   // rows below q1, columns q0..q1
+            c.A = Wt + q1; c.B = Vt + q0; c.C = j.Minv + (size_t)q1 * j.n + q0;
+            c.M = j.n - q1; c.N = q1 - q0; c.K = PB; c.lda = b.ldv; c.ldb = b.ldv; c.ldc = j.n;
+            c.mode = kSubRect; c.p0 = c.p1 = 0; c.doff = 1l << 30;
+            gj.push_back(c);
+        }
+    }
+    return gemm_launch(gj.data(), (int)gj.size(), s);
+}
+
+hipError_t BlockedRun::chain(int st, hipStream_t s)
+{
+    const int p0 = st * PB;
+    const int act = active(st);
+    // 1. inverse of the pivot blocks (in their current, updated state) -> P
+    nested.assign(act, InvertJob());
+    nidx.resize(act);
+    noffs.resize(act);
+    for (int k = 0; k < act; ++k) {
+        const InvertJob &j = jobs[idx[k]];
+        InvertJob &q = nested[k];
+        q.M = j.Minv + (size_t)p0 * j.n + p0;
+        q.Minv = big[k].P;
+        q.n = std::min(PB, j.n - p0);
+        q.damping = 0.f;
+        q.info = big[k].ninfo;
+        q.ldm = j.n;
+        q.ldo = PB;
+        nidx[k] = k;
+        noffs[k] = (size_t)(reinterpret_cast<char *>(big[k].nws) - static_cast<char *>(work));
+    }
+    // nested problems are grouped by order (all PB except possibly the last block of a matrix)
+    std::stable_sort(nidx.begin(), nidx.end(), [&](int a, int b) { return nested[a].n > nested[b].n; });
+    hipError_t e = fused_launch(nested.data(), nidx, noffs, work, dtab, s);
+    if (e != hipSuccess) return e;
+    // 2. gather V, 3. W^T = P V^T, 4. scatter
+    e = copy_kernel(false, st, act, s);
+    if (e != hipSuccess) return e;
+    gj.assign(act, GemmJob());
+    for (int k = 0; k < act; ++k) {
+        const InvertJob &j = jobs[idx[k]];
+        const int bs = std::min(PB, j.n - p0);
+        GemmJob &a = gj[k];
+        a.A = big[k].P; a.B = big[k].Vt[st & 1]; a.C = big[k].Wt[st & 1];
+        a.M = bs; a.N = j.n; a.K = bs; a.lda = PB; a.ldb = big[k].ldv; a.ldc = big[k].ldv;
+        a.mode = kStore; a.p0 = a.p1 = 0;
+    }
+    e = gemm_launch(gj.data(), act, s);
+    if (e != hipSuccess) return e;
+    return copy_kernel(true, st, act, s);
+}
+
+hipError_t BlockedRun::bulk(int st, bool skip_next, hipStream_t s)
+{
+    const int p0 = st * PB;
+    const int act = active(st);
+    gj.clear();
+    for (int k = 0; k < act; ++k) {
+        const InvertJob &j = jobs[idx[k]];
+        const int bs = std::min(PB, j.n - p0);
+        const int p1 = std::min(j.n, p0 + bs + (skip_next ? PB : 0));
+        if (p1 - p0 >= j.n) continue;      // nothing outside the bands
+        GemmJob u{};
+        u.A = big[k].Wt[st & 1]; u.B = big[k].Vt[st & 1]; u.C = j.Minv;
+        u.M = j.n; u.N = j.n; u.K = bs; u.lda = big[k].ldv; u.ldb = big[k].ldv; u.ldc = j.n;
+        u.mode = kSubLowerSkip; u.p0 = p0; u.p1 = p1;
+        gj.push_back(u);
+    }
+    return gemm_launch(gj.data(), (int)gj.size(), s);
 }
 
 hipError_t BlockedRun::finish(hipStream_t s)
@@ -479,75 +523,94 @@ hipError_t BlockedRun::finish(hipStream_t s)
     return hipSuccess;
 }
 
-
-hipError_t blocked_launch(const InvertJob *jobs, const std::vector<int> &idx, const std::vector<size_t> &offs,
-                          void *work, InvProbF *dtab, hipStream_t s)
-{
-    BlockedRun run;
-    run.jobs = jobs; run.idx = idx; run.offs = &offs; run.work = work; run.dtab = dtab;
-    hipError_t e = run.start(s);
-    if (e != hipSuccess) return e;
-    for (int st = 0; st < run.steps; ++st) {
-        e = run.step(st, s);
-        if (e != hipSuccess) return e;
-    }
-    return run.finish(s);
-}
-
-// Two groups of matrices on two streams: the pivot-block inversions, panel products and copies of a group are
-// short dependent launches that leave most of the chip idle, its rank-k updates fill it; dealt alternately to
-// the groups and enqueued step by step, the small launches of one group run beside the updates of the other.
-struct AuxStream {
-    hipStream_t s = nullptr;
-    hipEvent_t fork = nullptr, join = nullptr;
+// Streams and events of the library, per device, created at the first call that needs them (default priority).
+struct AuxStreams {
+    static constexpr int kEvents = 64;
+    hipStream_t chain = nullptr, side = nullptr;
+    hipEvent_t fork = nullptr, side_done = nullptr;
+    hipEvent_t ev_chain[kEvents] = {}, ev_bulk[kEvents] = {};
+    bool ok = false;
 };
 
-AuxStream *aux_stream()
+std::mutex &aux_mutex()
 {
-    static AuxStream per_dev[16];
+    static std::mutex m;
+    return m;
+}
+
+// call with aux_mutex() held
+AuxStreams *aux_streams()
+{
+    static AuxStreams per_dev[16];
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return nullptr;
-    AuxStream &a = per_dev[dev];
-    if (!a.s) {
-        if (hipStreamCreateWithFlags(&a.s, hipStreamNonBlocking) != hipSuccess) { a.s = nullptr; return nullptr; }
-        if (hipEventCreateWithFlags(&a.fork, hipEventDisableTiming) != hipSuccess ||
-            hipEventCreateWithFlags(&a.join, hipEventDisableTiming) != hipSuccess) {
-            (void)hipStreamDestroy(a.s);
-            a.s = nullptr;
-            return nullptr;
-        }
+    AuxStreams &a = per_dev[dev];
+    if (a.ok) return &a;
+    if (a.chain) return nullptr;     // an earlier attempt failed half way: stay on one stream
+    bool good = hipStreamCreateWithFlags(&a.chain, hipStreamNonBlocking) == hipSuccess &&
+                hipStreamCreateWithFlags(&a.side, hipStreamNonBlocking) == hipSuccess &&
+                hipEventCreateWithFlags(&a.fork, hipEventDisableTiming) == hipSuccess &&
+                hipEventCreateWithFlags(&a.side_done, hipEventDisableTiming) == hipSuccess;
+    for (int i = 0; good && i < AuxStreams::kEvents; ++i)
+        good = hipEventCreateWithFlags(&a.ev_chain[i], hipEventDisableTiming) == hipSuccess &&
+               hipEventCreateWithFlags(&a.ev_bulk[i], hipEventDisableTiming) == hipSuccess;
+    if (!good) {
+        if (!a.chain) a.chain = reinterpret_cast<hipStream_t>(1);   // marks the failed attempt
+        return nullptr;
     }
+    a.ok = true;
     return &a;
 }
 
-hipError_t blocked_launch_pair(const InvertJob *jobs, const std::vector<int> &idx, const std::vector<size_t> &offs,
-                               void *work, InvProbF *dtab, hipStream_t s)
+// One stream: chain and bulk of every step in a row.
+hipError_t blocked_serial(BlockedRun &run, hipStream_t s)
 {
-    // With a handful of matrices every launch of a run is a few workgroups, and two runs double the number of
-    // launches that sit in a row: measured slower with 4 matrices of order 1345..1569 (2.33 -> 2.64 ms), faster
-    // from 12 matrices on (threshold: invert_two_streams_min).
-    AuxStream *aux = (tuning().invert_two_streams && (long)idx.size() >= tuning().invert_two_streams_min) ? aux_stream() : nullptr;
-    if (!aux) return blocked_launch(jobs, idx, offs, work, dtab, s);
-    BlockedRun run[2];
-    for (size_t k = 0; k < idx.size(); ++k) run[k & 1].idx.push_back(idx[k]);   // sorted by order: dealt alternately
-    for (int g = 0; g < 2; ++g) {
-        run[g].jobs = jobs; run[g].offs = &offs; run[g].work = work;
-        run[g].dtab = dtab + (g == 0 ? 0 : run[0].idx.size());    // descriptors of the nested inversions: a range each
+    hipError_t e = run.start(s);
+    for (int st = 0; st < run.steps && e == hipSuccess; ++st) {
+        e = run.chain(st, s);
+        if (e == hipSuccess) e = run.bulk(st, false, s);
     }
-    if (hipEventRecord(aux->fork, s) != hipSuccess || hipStreamWaitEvent(aux->s, aux->fork, 0) != hipSuccess)
+    return e == hipSuccess ? run.finish(s) : e;
+}
+
+// Look-ahead on two streams: bulk updates on the caller's stream `s`, chains on `aux->chain`.
+//   chain stream: chain(0) | look(0) chain(1) | wait bulk(0); look(1) chain(2) | ... wait bulk(st-2); look(st-1) chain(st)
+//   bulk stream:  wait chain(st); bulk(st) leaving out the band of block st + 1
+// The band of block st + 1 has received every update up to st - 1 from the bulk stream when look(st) starts, and
+// panels st (buffer st mod 2) are not overwritten before bulk(st) is done: chain(st + 2) waits for it.
+hipError_t blocked_lookahead(BlockedRun &run, AuxStreams *aux, hipStream_t s)
+{
+    hipError_t e = run.start(s);
+    if (e != hipSuccess) return e;
+    hipStream_t c = aux->chain;
+    if (hipEventRecord(aux->fork, s) != hipSuccess || hipStreamWaitEvent(c, aux->fork, 0) != hipSuccess)
         return hipErrorUnknown;
-    hipStream_t st2[2] = {s, aux->s};
-    hipError_t e = hipSuccess;
-    for (int g = 0; g < 2 && e == hipSuccess; ++g) e = run[g].start(st2[g]);
-    const int steps = std::max(run[0].steps, run[1].steps);
-    for (int st = 0; st < steps && e == hipSuccess; ++st)
-        for (int g = 0; g < 2 && e == hipSuccess; ++g)
-            if (st < run[g].steps) e = run[g].step(st, st2[g]);
-    for (int g = 0; g < 2 && e == hipSuccess; ++g) e = run[g].finish(st2[g]);
-    // always join, also after an error: the caller's stream must not run ahead of what the other one still holds
-    if (hipEventRecord(aux->join, aux->s) != hipSuccess || hipStreamWaitEvent(s, aux->join, 0) != hipSuccess)
-        return hipErrorUnknown;
-    return e;
+    bool forked = true;
+    for (int st = 0; st < run.steps && e == hipSuccess; ++st) {
+        if (st >= 2 && hipStreamWaitEvent(c, aux->ev_bulk[st - 2], 0) != hipSuccess) e = hipErrorUnknown;
+        if (e == hipSuccess && st >= 1) e = run.look(st - 1, c);
+        if (e == hipSuccess) e = run.chain(st, c);
+        if (e == hipSuccess && hipEventRecord(aux->ev_chain[st], c) != hipSuccess) e = hipErrorUnknown;
+        if (e == hipSuccess && hipStreamWaitEvent(s, aux->ev_chain[st], 0) != hipSuccess) e = hipErrorUnknown;
+        if (e == hipSuccess) forked = false;      // everything on the chain stream so far is joined
+        if (e == hipSuccess) e = run.bulk(st, st + 1 < run.steps, s);
+        if (e == hipSuccess && hipEventRecord(aux->ev_bulk[st], s) != hipSuccess) e = hipErrorUnknown;
+        if (e != hipSuccess) forked = true;
+    }
+    if (forked) {
+        // after an error the caller's stream must still not run ahead of what the chain stream holds
+        if (hipEventRecord(aux->ev_chain[0], c) == hipSuccess) (void)hipStreamWaitEvent(s, aux->ev_chain[0], 0);
+    }
+    return e == hipSuccess ? run.finish(s) : e;
+}
+
+hipError_t blocked_launch(const InvertJob *jobs, const std::vector<int> &idx, const std::vector<size_t> &offs,
+                          void *work, InvProbF *dtab, AuxStreams *aux, hipStream_t s)
+{
+    BlockedRun run;
+    run.jobs = jobs; run.idx = idx; run.offs = &offs; run.work = work; run.dtab = dtab;
+    if (!aux) return blocked_serial(run, s);
+    return blocked_lookahead(run, aux, s);
 }
 
 // ---- orders 64 k + 1: the last row and column by bordering ---------------------------------
@@ -762,17 +825,35 @@ hipError_t invert_launch(const InvertJob *jobs_in, int n_all, void *work, size_t
     std::stable_sort(large.begin(), large.end(), by_size);
     std::stable_sort(fused.begin(), fused.end(), by_size);
     InvProbF *dtab = static_cast<InvProbF *>(work);
-    if (!fused.empty()) {
-        hipError_t e = fused_launch(jobs, fused, offs, work, dtab, s);
-        if (e != hipSuccess) return e;
+    // The library's own streams: the chains of the blocked sweep on one, and, when there are large matrices too,
+    // the one-launch-per-step class on the other (independent matrices: the two classes run side by side).
+    std::unique_lock<std::mutex> lock(aux_mutex(), std::defer_lock);
+    AuxStreams *aux = nullptr;
+    if (!large.empty() && tuning().invert_two_streams) {
+        lock.lock();       // the events are shared by all calls on a device: one call enqueues at a time
+        aux = aux_streams();
+        if (!aux) lock.unlock();
     }
-    if (!large.empty()) {
+    hipStream_t fs = s;
+    if (aux && !fused.empty()) {
+        fs = aux->side;
+        if (hipEventRecord(aux->fork, s) != hipSuccess || hipStreamWaitEvent(fs, aux->fork, 0) != hipSuccess)
+            return hipErrorUnknown;
+    }
+    hipError_t e = hipSuccess;
+    if (!fused.empty()) e = fused_launch(jobs, fused, offs, work, dtab, fs);
+    // bordered orders of the fused class finish on the same stream
+    if (e == hipSuccess && !bordered.empty()) e = border_launch(jobs_in, bordered, ybuf, fs);
+    bool side_open = fs != s;
+    if (side_open && hipEventRecord(aux->side_done, fs) != hipSuccess) return hipErrorUnknown;
+    if (e == hipSuccess && !large.empty()) {
         // the nested pivot-block inversions use the second half of the descriptor table
-        hipError_t e = blocked_launch_pair(jobs, large, offs, work, dtab + n_all, s);
-        if (e != hipSuccess) return e;
+        const int steps = (jobs[large[0]].n + outer_block() - 1) / outer_block();
+        e = blocked_launch(jobs, large, offs, work, dtab + n_all, steps <= AuxStreams::kEvents ? aux : nullptr, s);
     }
-    if (!bordered.empty()) return border_launch(jobs_in, bordered, ybuf, s);
-    return hipSuccess;
+    // always join the side stream, also after an error
+    if (side_open && hipStreamWaitEvent(s, aux->side_done, 0) != hipSuccess) return hipErrorUnknown;
+    return e;
 }
 
 // ---- factored Tikhonov damping (Eq. 12) ----------------------------------------------------

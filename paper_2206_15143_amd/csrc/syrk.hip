@@ -706,7 +706,7 @@ int red_kind(int cfg)
 namespace {
 
 template <int NT>
-hipError_t corr3_launch_nt(CorrTable &tab, const std::vector<size_t> &lds, double flops, hipStream_t s)
+hipError_t corr3_launch_nt(CorrTable &tab, const std::vector<size_t> &lds, double flops, double exflops, hipStream_t s)
 {
     // main kernel
     int blocks = 0;
@@ -725,7 +725,7 @@ hipError_t corr3_launch_nt(CorrTable &tab, const std::vector<size_t> &lds, doubl
         attr_set = true;
     }
     KFAC_LAUNCH(KFAC_K_SYRK_CORR3, s, (corr3_main_kernel<NT>), dim3(blocks), dim3(512), lds_bytes, tab);
-    timing_work(flops);
+    timing_work(flops, exflops);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     // border terms: small maps of at least 32 channels from whole images (the problems of a launch share a
@@ -757,7 +757,7 @@ hipError_t corr3_launch_nt(CorrTable &tab, const std::vector<size_t> &lds, doubl
 }
 
 hipError_t corr3_launch(const FactorJob *jobs, const std::vector<int> &g, const std::vector<Planned> &pl,
-                        const std::vector<size_t> &offs, void *work, double flops, hipStream_t s)
+                        const std::vector<size_t> &offs, void *work, double flops, double exflops, hipStream_t s)
 {
     CorrTable tab;
     tab.count = (int)g.size();
@@ -790,9 +790,9 @@ hipError_t corr3_launch(const FactorJob *jobs, const std::vector<int> &g, const 
         lds[k] = (size_t)2 * C * p.plane * sizeof(float);
     }
     const int cfg = pl[g[0]].cfg;
-    hipError_t e = cfg == kCorr3Cfg ? corr3_launch_nt<1>(tab, lds, flops, s)
-                 : cfg == kCorr3Cfg + 1 ? corr3_launch_nt<2>(tab, lds, flops, s)
-                                        : corr3_launch_nt<4>(tab, lds, flops, s);
+    hipError_t e = cfg == kCorr3Cfg ? corr3_launch_nt<1>(tab, lds, flops, exflops, s)
+                 : cfg == kCorr3Cfg + 1 ? corr3_launch_nt<2>(tab, lds, flops, exflops, s)
+                                        : corr3_launch_nt<4>(tab, lds, flops, exflops, s);
     if (e != hipSuccess) return e;
     // sums over parts and chunks
     int blocks = 0;
@@ -852,13 +852,14 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
         tab.count = (int)g.size();
         tab.debug = (int)tuning().wave_debug;
         int blocks = 0;
-        double flops = 0.0;
+        double flops = 0.0, corr_flops = 0.0;   // corr_flops: 13 lag tiles per channel-tile pair and pixel, 26 C^2 per pixel
         std::vector<int> red_n(g.size());
         std::vector<double> red_b(g.size());
         for (int k = 0; k < tab.count; ++k) {
             const int j = g[k];
             const FactorJob &job = jobs[j];
             flops += (double)job.K * (job.d_core + job.has_bias) * (job.d_core + job.has_bias + 1);
+            corr_flops += 26.0 * job.ctot * job.ctot * (double)job.K;
             {   // reduce + running average: the split slices and the old factor read (one triangle), the factor written (both)
                 const double dF = job.d_core + job.has_bias, tri = dF * (dF + 1) / 2;
                 red_b[k] = 4.0 * ((pl[j].splits + 1) * tri + dF * dF);
@@ -894,7 +895,7 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
         const int layout = jobs[g[0]].layout, dt = jobs[g[0]].dtype;
         hipError_t e = hipSuccess;
         if (cfg >= kCorr3Cfg) {
-            e = corr3_launch(jobs, g, pl, offs, work, flops, s);
+            e = corr3_launch(jobs, g, pl, offs, work, flops, corr_flops, s);
             if (e != hipSuccess) return e;
             continue;
         }
