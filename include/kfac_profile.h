@@ -63,6 +63,12 @@ const char *kfac_timing_class_name(int cls);
  * against which hardware byte counters are scaled.  Returns 0 on success. */
 int kfac_profile_copy(void *d_dst, const void *d_src, size_t bytes, void *hip_stream);
 
+/* One product C = A^T B (A stored [K, lda], B stored [K, ldb], C [M, ldc], all fp32 device pointers) through the
+ * library's GEMM routing, for timing a kernel on a shape of one's own.  mode: 0 store, 2 subtract from the lower
+ * triangle outside rows / columns [p0, p1) (M == N).  Returns 0 on success. */
+int kfac_profile_gemm(const float *d_A, const float *d_B, float *d_C, int M, int N, int K, long lda, long ldb,
+                      long ldc, int mode, int p0, int p1, void *hip_stream);
+
 /* Development knobs (planner targets, kernel selection switches; the keys are listed in
  * kfac_tune() in csrc/api.hip, e.g. "target_blocks", "patch_chunk_bytes", "fuse_conv3",
  * "use_bf16_mfma", "invert_fused_max_n").  Returns 0 when the key is known.  Changing a knob can

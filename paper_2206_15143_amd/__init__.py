@@ -10,6 +10,6 @@ from .binding import (  # noqa: F401
     KFAC_STATIC_SCRATCH_BYTES,
     kfac_update_factors_batched, kfac_invert_batched, kfac_invert_pi, kfac_invert_pi_batched, kfac_precondition_batched,
     kfac_eigen, kfac_eigen_batched, kfac_precondition_eigen, kfac_precondition_eigen_batched,
-    kfac_status_string, kfac_version, kfac_tune, kfac_timing_enable, kfac_timing_collect, kfac_timing_collect_ex, kfac_profile_copy,
+    kfac_status_string, kfac_version, kfac_tune, kfac_timing_enable, kfac_timing_collect, kfac_timing_collect_ex, kfac_profile_copy, kfac_profile_gemm,
     KFAC_F32, KFAC_BF16, KFAC_LINEAR, KFAC_CONV2D,
 )

@@ -113,6 +113,9 @@ def load_library():
     lib.kfac_profile_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.kfac_profile_copy.restype = C.c_int
     lib.kfac_timing_class_name.argtypes = [C.c_int]; lib.kfac_timing_class_name.restype = C.c_char_p
+    lib.kfac_profile_gemm.argtypes = [vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_long, C.c_long, C.c_long, C.c_int,
+                                      C.c_int, C.c_int, vp]
+    lib.kfac_profile_gemm.restype = C.c_int
     _lib = lib
     return lib
 
@@ -215,6 +218,12 @@ KFAC_K_COUNT = 20
 def kfac_profile_copy(dst, src, nbytes: int, stream=None) -> None:
     if load_library().kfac_profile_copy(_ptr(dst), _ptr(src), C.c_size_t(nbytes), _stream(stream)) != 0:
         raise RuntimeError("kfac_profile_copy failed")
+
+
+def kfac_profile_gemm(A, B, Cm, M, N, K, lda, ldb, ldc, mode=0, p0=0, p1=0, stream=None) -> None:
+    if load_library().kfac_profile_gemm(_ptr(A), _ptr(B), _ptr(Cm), M, N, K, lda, ldb, ldc, mode, p0, p1,
+                                        _stream(stream)) != 0:
+        raise RuntimeError("kfac_profile_gemm failed")
 
 
 def kfac_timing_enable(on: bool) -> None:

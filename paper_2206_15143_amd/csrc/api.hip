@@ -812,6 +812,18 @@ int kfac_profile_copy(void *d_dst, const void *d_src, size_t bytes, void *hip_st
     return hipGetLastError() == hipSuccess ? 0 : 2;
 }
 
+int kfac_profile_gemm(const float *d_A, const float *d_B, float *d_C, int M, int N, int K, long lda, long ldb,
+                      long ldc, int mode, int p0, int p1, void *hip_stream)
+{
+    if (!d_A || !d_B || !d_C || M <= 0 || N <= 0 || K <= 0 || lda < M || ldb < N || ldc < N) return 1;
+    if (mode != kStore && mode != kSubLowerSkip) return 1;
+    if (mode == kSubLowerSkip && (M != N || p0 < 0 || p1 < p0)) return 1;
+    GemmJob j{};
+    j.A = d_A; j.B = d_B; j.C = d_C; j.M = M; j.N = N; j.K = K; j.lda = lda; j.ldb = ldb; j.ldc = ldc;
+    j.mode = mode; j.p0 = p0; j.p1 = p1;
+    return gemm_launch(&j, 1, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? 0 : 2;
+}
+
 /* Development knob: returns 0 when the key is known. */
 int kfac_tune(const char *key, long value)
 {

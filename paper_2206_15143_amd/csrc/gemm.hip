@@ -293,6 +293,7 @@ hipError_t split_gemm_launch(const GemmJob *jobs, const std::vector<int> &idx, h
 {
     GemmSTable tab;
     tab.count = 0;
+    tab.debug = (int)tuning().wave_debug;
     long blocks = 0;
     double flops = 0.0;
     auto flush = [&]() -> hipError_t {

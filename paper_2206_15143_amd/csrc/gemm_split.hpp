@@ -55,6 +55,7 @@ struct GemmSProb {
 
 struct GemmSTable {
     int count;
+    int debug;       // measurement only (results are wrong): 8 no epilogue
     GemmSProb p[kMaxProblems];
 };
 
@@ -71,22 +72,24 @@ typedef __bf16 sbf16x2 __attribute__((ext_vector_type(2)));
 typedef float sfloat2 __attribute__((ext_vector_type(2)));
 typedef unsigned suint4 __attribute__((ext_vector_type(4)));
 
-// Eight fp32 values -> three packed bf16 pieces (round to nearest even at every level; the residuals are exact).
+// Eight fp32 values -> three packed bf16 pieces.  Each piece is the upper half of the fp32 word of what is left
+// (truncation: the pieces have the sign of x and add up to x exactly, 8 + 8 + 8 significant bits), so a level
+// costs one byte permute per two values and an AND and a subtraction per value, all full-rate operations (the
+// rounding conversion v_cvt_pk_bf16_f32 measured at a quarter of that rate).
 __device__ __forceinline__ void split_pieces(const float (&x)[8], suint4 &p1, suint4 &p2, suint4 &p3)
 {
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const float a = x[2 * q], b = x[2 * q + 1];
-        const unsigned u1 = __builtin_bit_cast(unsigned, __builtin_convertvector(sfloat2{a, b}, sbf16x2));
-        const float ra = a - __builtin_bit_cast(float, u1 << 16);
-        const float rb = b - __builtin_bit_cast(float, u1 & 0xffff0000u);
-        const unsigned u2 = __builtin_bit_cast(unsigned, __builtin_convertvector(sfloat2{ra, rb}, sbf16x2));
-        const float sa = ra - __builtin_bit_cast(float, u2 << 16);
-        const float sb = rb - __builtin_bit_cast(float, u2 & 0xffff0000u);
-        const unsigned u3 = __builtin_bit_cast(unsigned, __builtin_convertvector(sfloat2{sa, sb}, sbf16x2));
-        p1[q] = u1;
-        p2[q] = u2;
-        p3[q] = u3;
+        const unsigned ua = __builtin_bit_cast(unsigned, a), ub = __builtin_bit_cast(unsigned, b);
+        p1[q] = __builtin_amdgcn_perm(ub, ua, 0x07060302u);
+        const float ra = a - __builtin_bit_cast(float, ua & 0xffff0000u);
+        const float rb = b - __builtin_bit_cast(float, ub & 0xffff0000u);
+        const unsigned va = __builtin_bit_cast(unsigned, ra), vb = __builtin_bit_cast(unsigned, rb);
+        p2[q] = __builtin_amdgcn_perm(vb, va, 0x07060302u);
+        const float sa = ra - __builtin_bit_cast(float, va & 0xffff0000u);
+        const float sb = rb - __builtin_bit_cast(float, vb & 0xffff0000u);
+        p3[q] = __builtin_amdgcn_perm(__builtin_bit_cast(unsigned, sb), __builtin_bit_cast(unsigned, sa), 0x07060302u);
     }
 }
 
@@ -164,6 +167,7 @@ __global__ __launch_bounds__(256, 2) void gemm_split_kernel(const GemmSTable tab
     const unsigned voa = ca < pr.M ? (unsigned)(ca * 4) : W_OOB;
     const unsigned vob = cb < pr.N ? (unsigned)(((lane >> 5) * ldb + cb) * 4) : W_OOB;
     const unsigned rowa = (unsigned)lda * 4u, rowb = (unsigned)ldb * 4u;
+    const int dbg = tab.debug;
     auto issue = [&](int g) {
         const bool live_stage = g < nstages;
         const unsigned buf = lds_base + (unsigned)((g % S_NSTAGE) * S_STAGE * 4);
@@ -198,31 +202,36 @@ __global__ __launch_bounds__(256, 2) void gemm_split_kernel(const GemmSTable tab
         if (!idle) {
             const float *buf = lds + (g % S_NSTAGE) * S_STAGE;
             suint4 b1[2], b2[2], b3[2];
+            float xa[8], xn[8];
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
                 float x[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) x[e] = buf[fb + e * S_BN + t * 32];
+                if (t == 0) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) xa[e] = buf[fa + e * S_BM];
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) xn[e] = buf[fa + e * S_BM + 32];
+                }
                 split_pieces(x, b1[t], b2[t], b3[t]);
             }
-            // the panel reads of tile ti + 1 go out before the conversions and products of tile ti
-            float xn[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) xn[e] = buf[fa + e * S_BM];
+            suint4 c1, c2, c3;          // pieces of the A tile being multiplied
+            split_pieces(xa, c1, c2, c3);
             __builtin_amdgcn_sched_barrier(0);
+            // Tile ti: its twelve products, with the conversions of tile ti + 1 (and the panel reads of tile
+            // ti + 2) issued between them, four VALU operations in the shadow of every MFMA.
 #pragma unroll
             for (int ti = 0; ti < 4; ++ti) {
-                float x[8];
+                suint4 n1, n2, n3;
+                if (ti + 1 < 4) split_pieces(xn, n1, n2, n3);
+                if (ti + 2 < 4) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) x[e] = xn[e];
-                if (ti + 1 < 4) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) xn[e] = buf[fa + e * S_BM + (ti + 1) * 32];
+                    for (int e = 0; e < 8; ++e) xn[e] = buf[fa + e * S_BM + (ti + 2) * 32];
                 }
-                suint4 a1, a2, a3;
-                split_pieces(x, a1, a2, a3);
-                const sbf16x8 A1 = __builtin_bit_cast(sbf16x8, a1), A2 = __builtin_bit_cast(sbf16x8, a2),
-                              A3 = __builtin_bit_cast(sbf16x8, a3);
+                const sbf16x8 A1 = __builtin_bit_cast(sbf16x8, c1), A2 = __builtin_bit_cast(sbf16x8, c2),
+                              A3 = __builtin_bit_cast(sbf16x8, c3);
 #pragma unroll
                 for (int tj = 0; tj < 2; ++tj) {
                     const sbf16x8 B1 = __builtin_bit_cast(sbf16x8, b1[tj]), B2 = __builtin_bit_cast(sbf16x8, b2[tj]),
@@ -237,6 +246,15 @@ __global__ __launch_bounds__(256, 2) void gemm_split_kernel(const GemmSTable tab
                     c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A1, B1, c, 0, 0, 0);
                     acc[ti * 2 + tj] = c;
                 }
+                if (ti + 1 < 4) {
+#pragma unroll
+                    for (int k = 0; k < 12; ++k) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                        __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);   // four VALU
+                        if (ti + 2 < 4 && k < 8) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+                    }
+                    c1 = n1; c2 = n2; c3 = n3;
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -245,7 +263,7 @@ __global__ __launch_bounds__(256, 2) void gemm_split_kernel(const GemmSTable tab
     }
     // the zero-filling copies of the stages past the end may still be landing
     asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
-    if (idle) return;
+    if (idle || (dbg & 8)) return;
 
     // ---- epilogue: acc[ti*2 + tj][v] = C[m0 + wm*128 + ti*32 + 8*(v>>2) + 4*lg + (v&3)][n0 + wn*64 + tj*32 + lr]
     // An address is a wave-uniform row pointer (scalar registers) plus one per-lane offset that is the same for
@@ -267,8 +285,7 @@ __global__ __launch_bounds__(256, 2) void gemm_split_kernel(const GemmSTable tab
         }
         return;
     }
-    // read-modify-write below the line n = m + doff, outside the pivot rows and columns: the 16 loads of a tile
-    // are issued together, and the loads of the next tile go out before the stores of the current one
+    // read-modify-write below the line n = m + doff, outside the pivot rows and columns
     const int p0 = pr.p0, p1 = pr.p1, doff = pr.doff;
     auto live = [&](int m, int n) {
         return m < pr.M && n < pr.N && n <= m + doff && !(rows_skip && m >= p0 && m < p1) && !(n >= p0 && n < p1);
@@ -289,6 +306,8 @@ __global__ __launch_bounds__(256, 2) void gemm_split_kernel(const GemmSTable tab
             if (live(mw + (t >> 1) * 32 + r + 4 * lg, n)) row_ptr(t, r)[lane_off] = old[v] - acc[t][v];
         }
     };
+    // the 16 loads of a tile are issued together, and the loads of the next tile go out before the stores of
+    // the current one (more tiles in flight cost more registers than the kernel has)
     float oa[16], ob[16];
     load_tile(0, oa);
 #pragma unroll
