@@ -304,6 +304,11 @@ hipError_t fused_launch(const InvertJob *jobs, const std::vector<int> &idx, cons
             blocks = lay_out(q, active, [](const InvClass &k) { return k.nblk * (k.nblk + 1) / 2; });
             if (blocks > 0x7fffffffL) return hipErrorInvalidValue;
             KFAC_LAUNCH(KFAC_K_INV_STEP, s, fsweep_step_kernel, dim3((unsigned)blocks), dim3(256), 0, q);
+            {   // a rank-64 update of the triangle, n^2 * 64 flops per matrix; every tile also forms its own W = V P
+                double fl = 0.0;
+                for (int k = 0; k < active; ++k) fl += (double)q.c[k].count * q.c[k].n * q.c[k].n * FNB;
+                timing_work(fl, 2.0 * fl);
+            }
             e = hipGetLastError();
             if (e != hipSuccess) return e;
         }
