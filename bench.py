@@ -37,6 +37,7 @@ CLASSES = {
     "syrk_small": ("syrk_small_nchw_kernel", "hbm", "f32", True),
     "syrk_bf16": ("syrk_bf16_kernel", "mfma", "bf16", True),
     "syrk_corr3": ("corr3_main_kernel", "mfma", "f32", True),
+    "syrk_split": ("syrk_split_kernel", "mfma", "bf16", True),
     "gemm_tn": ("gemm_tn_kernel", "mfma", "f32", False),
     "gemm_wave": ("gemm_wave_kernel", "mfma", "f32", False),
     "gemm_split": ("gemm_split_kernel", "mfma", "bf16", False),

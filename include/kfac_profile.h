@@ -34,7 +34,8 @@ enum {
     KFAC_K_SYRK_CORR3 = 17,  /* KF-GEMM of 3x3 convolutions from input autocorrelations (lag matrices) */
     KFAC_K_CORR3_ASM = 18,   /* border terms, sums and assembly (+ running average) of that path */
     KFAC_K_GEMM_SPLIT = 19,  /* A^T B of fp32 operands as six bf16 MFMA products of their bf16 pieces */
-    KFAC_K_COUNT = 20
+    KFAC_K_SYRK_SPLIT = 20,  /* KF-GEMM of wide fp32 inputs as six bf16 MFMA products of their bf16 pieces */
+    KFAC_K_COUNT = 21
 };
 
 /* When enabled, every kernel launch is bracketed by a pair of HIP events

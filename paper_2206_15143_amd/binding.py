@@ -212,7 +212,7 @@ def kfac_tune(key: str, value: int) -> None:
         raise KeyError(key)
 
 
-KFAC_K_COUNT = 20
+KFAC_K_COUNT = 21
 
 
 def kfac_profile_copy(dst, src, nbytes: int, stream=None) -> None:

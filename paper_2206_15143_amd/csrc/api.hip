@@ -125,7 +125,7 @@ kfac_status geometry(const kfac_layer_desc *d, int batch, int h, int w, Geo &g)
         g.R = (long)batch * g.Ho * g.Wo;
         g.patches = !(d->kh == 1 && d->kw == 1 && d->stride == 1 && d->pad == 0);
         g.fused3 = tuning().fuse_conv3 && d->in_dtype == KFAC_F32 && d->kh == 3 && d->kw == 3 && d->stride == 1 &&
-                   d->pad == 1 && d->d_in % 16 == 0 && conv3_rows(h, w) > 0 &&
+                   d->pad == 1 && d->d_in % 16 == 0 && d->d_in <= tuning().fuse_conv3_max_c && conv3_rows(h, w) > 0 &&
                    (long)batch * d->d_in * h * w * 4 < 0x7fff0000l;
         if (g.fused3) g.patches = false;
     } else {
@@ -789,7 +789,7 @@ const char *kfac_timing_class_name(int cls)
                                               "inv_pivot", "inv_panel", "inv_finish", "gemm_tn",
                                               "syrk_wave", "syrk_conv3", "syrk_small", "inv_step",
                                               "syrk_bf16", "gemm_wave", "eig_init", "eig_round", "eig_final",
-                                              "syrk_corr3", "corr3_assemble", "gemm_split"};
+                                              "syrk_corr3", "corr3_assemble", "gemm_split", "syrk_split"};
     return (cls >= 0 && cls < KFAC_K_COUNT) ? names[cls] : "?";
 }
 
@@ -838,6 +838,8 @@ int kfac_tune(const char *key, long value)
     else if (k == "use_wave_kernel") t.use_wave_kernel = value;
     else if (k == "wave_debug") t.wave_debug = value;
     else if (k == "fuse_conv3") t.fuse_conv3 = value;
+    else if (k == "fuse_conv3_max_c") t.fuse_conv3_max_c = value;
+    else if (k == "split_gemm_min_k") t.split_gemm_min_k = value;
     else if (k == "update_bm") t.update_bm = value;
     else if (k == "use_small_kernel") t.use_small_kernel = value;
     else if (k == "invert_fused_max_n") t.invert_fused_max_n = value;
@@ -856,7 +858,11 @@ int kfac_tune(const char *key, long value)
     else if (k == "use_bf16_mfma") t.use_bf16_mfma = value;
     else if (k == "use_wave_gemm") t.use_wave_gemm = value;
     else if (k == "use_split_gemm") t.use_split_gemm = value;
+    else if (k == "use_split_syrk") t.use_split_syrk = value;
+    else if (k == "split_syrk_fill_rows") t.split_syrk_fill_rows = value;
+    else if (k == "split_syrk_fill_nchw") t.split_syrk_fill_nchw = value;
     else if (k == "split_gemm_min_m") t.split_gemm_min_m = value;
+    else if (k == "split_gemm_min_fill") t.split_gemm_min_fill = value;
     else if (k == "gemm_xcd_remap_min") t.gemm_xcd_remap_min = value;
     else if (k == "gemm_bm") t.gemm_bm = value;
     else return 1;

@@ -135,10 +135,16 @@ struct Tuning {
     long use_bf16_mfma = 1;          // row-major bf16 operands: bf16 MFMA kernel instead of widening to fp32
     long gemm_xcd_remap_min = 8;     // wave GEMM launches with at least this many problems renumber their tiles per XCD
     long use_wave_gemm = 1;          // wide A^T B products on the wave-unit GEMM
+    long use_split_syrk = 1;         // wide fp32 factors as six bf16 MFMA products of the inputs' bf16 pieces
+    long split_syrk_fill_rows = 60;  // ... row-major inputs: when the factor fills this percentage of its 256 x 128 tiles
+    long split_syrk_fill_nchw = 40;  // ... NCHW inputs (tile fill x share of real positions in the K stages)
     long use_split_gemm = 1;         // large A^T B products as six bf16 MFMA products of the operands' bf16 pieces
     long split_gemm_min_m = 192;     // ... from this many output rows on
+    long split_gemm_min_k = 1024;     // ... and this depth (stores only)
+    long split_gemm_min_fill = 70;   // ... when the product fills at least this percentage of its 256 x 128 tiles
     long use_small_kernel = 1;       // direct MFMA kernel for narrow NCHW operands (d <= 64)
     long fuse_conv3 = 1;             // 3x3/s1/p1 fp32 convs: build A straight from the NCHW input
+    long fuse_conv3_max_c = 64;      // ... up to this many input channels (wider ones: patch matrix + split-bf16 kernel)
     long update_bm = 64;             // block tile of the inverse's rank-64 update GEMM (0 = choose; 64 measured best)
     long gemm_bm = 0;                // block tile of the preconditioning GEMMs (0 = choose)
     long wave_debug = 0;             // measurement only: 1 = skip MFMAs, 2 = skip data loads (results are wrong)

@@ -282,6 +282,13 @@ bool split_gemm_eligible(const GemmJob &j)
 {
     if (!tuning().use_split_gemm || (j.mode != kStore && j.mode != kSubLowerSkip && j.mode != kSubRect)) return false;
     if (j.M < tuning().split_gemm_min_m || j.N < 64 || j.K < 16) return false;
+    if (j.mode == kStore) {
+        if (j.K < tuning().split_gemm_min_k) return false;
+        // 256 x 128 tiles: products that fill them badly (a 257-row or 65-column operand) stay with the 144-wide
+        // tiles of the fp32 kernel
+        const double tiles = (double)((j.M + S_BM - 1) / S_BM) * ((j.N + S_BN - 1) / S_BN);
+        if ((double)j.M * j.N < 0.01 * tuning().split_gemm_min_fill * tiles * S_BM * S_BN) return false;
+    }
     if ((long)j.K * j.lda * 4 > 0x7fffffffl || (long)j.K * j.ldb * 4 > 0x7fffffffl) return false;
     if ((long)j.M * j.ldc * 4 > 0x7fffffffl) return false;
     if (((uintptr_t)j.A) % 4 || ((uintptr_t)j.B) % 4) return false;

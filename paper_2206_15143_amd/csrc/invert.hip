@@ -578,11 +578,12 @@ hipError_t blocked_serial(BlockedRun &run, hipStream_t s)
     return e == hipSuccess ? run.finish(s) : e;
 }
 
-// Look-ahead on two streams: bulk updates on the caller's stream `s`, chains on `aux->chain`.
-//   chain stream: chain(0) | look(0) chain(1) | wait bulk(0); look(1) chain(2) | ... wait bulk(st-2); look(st-1) chain(st)
-//   bulk stream:  wait chain(st); bulk(st) leaving out the band of block st + 1
-// The band of block st + 1 has received every update up to st - 1 from the bulk stream when look(st) starts, and
-// panels st (buffer st mod 2) are not overwritten before bulk(st) is done: chain(st + 2) waits for it.
+// Look-ahead on two streams: updates on the caller's stream `s`, chains on `aux->chain`.
+//   update stream: wait chain(st); look(st) [update st on the band of block st + 1]; record; bulk(st) without that band
+//   chain stream:  wait look(st - 1); chain(st) [pivot inverse, gather, panel product, scatter]; record
+// look(st) is a small product: at the head of the update stream it has the whole chip and is done in a few tens
+// of microseconds, after which chain(st + 1) runs beside bulk(st).  Panels st (buffer st mod 2) are not
+// overwritten before bulk(st) is done: chain(st + 2) waits for look(st + 1), which follows bulk(st) on its stream.
 hipError_t blocked_lookahead(BlockedRun &run, AuxStreams *aux, hipStream_t s)
 {
     hipError_t e = run.start(s);
@@ -590,19 +591,23 @@ hipError_t blocked_lookahead(BlockedRun &run, AuxStreams *aux, hipStream_t s)
     hipStream_t c = aux->chain;
     if (hipEventRecord(aux->fork, s) != hipSuccess || hipStreamWaitEvent(c, aux->fork, 0) != hipSuccess)
         return hipErrorUnknown;
-    bool forked = true;
+    bool joined = false;
     for (int st = 0; st < run.steps && e == hipSuccess; ++st) {
-        if (st >= 2 && hipStreamWaitEvent(c, aux->ev_bulk[st - 2], 0) != hipSuccess) e = hipErrorUnknown;
-        if (e == hipSuccess && st >= 1) e = run.look(st - 1, c);
-        if (e == hipSuccess) e = run.chain(st, c);
+        joined = false;
+        e = run.chain(st, c);
         if (e == hipSuccess && hipEventRecord(aux->ev_chain[st], c) != hipSuccess) e = hipErrorUnknown;
         if (e == hipSuccess && hipStreamWaitEvent(s, aux->ev_chain[st], 0) != hipSuccess) e = hipErrorUnknown;
-        if (e == hipSuccess) forked = false;      // everything on the chain stream so far is joined
-        if (e == hipSuccess) e = run.bulk(st, st + 1 < run.steps, s);
-        if (e == hipSuccess && hipEventRecord(aux->ev_bulk[st], s) != hipSuccess) e = hipErrorUnknown;
-        if (e != hipSuccess) forked = true;
+        if (e != hipSuccess) break;
+        joined = true;            // everything the chain stream holds so far is ordered before what follows on `s`
+        const bool more = st + 1 < run.steps;
+        if (more) {
+            e = run.look(st, s);
+            if (e == hipSuccess && hipEventRecord(aux->ev_bulk[st], s) != hipSuccess) e = hipErrorUnknown;
+            if (e == hipSuccess && hipStreamWaitEvent(c, aux->ev_bulk[st], 0) != hipSuccess) e = hipErrorUnknown;
+        }
+        if (e == hipSuccess) e = run.bulk(st, more, s);
     }
-    if (forked) {
+    if (!joined) {
         // after an error the caller's stream must still not run ahead of what the chain stream holds
         if (hipEventRecord(aux->ev_chain[0], c) == hipSuccess) (void)hipStreamWaitEvent(s, aux->ev_chain[0], 0);
     }

@@ -16,6 +16,7 @@
 //   syrk_conv3_kernel      : 3x3 convolution inputs, patch matrix never built (syrk_conv3.hpp)
 //   syrk_small_nchw_kernel : narrow NCHW fp32, no LDS staging (syrk_small.hpp)
 //   syrk_bf16_kernel       : bf16 inputs on the bf16 MFMA units (syrk_bf16.hpp)
+//   syrk_split_kernel      : wide fp32 inputs as three bf16 pieces on the bf16 MFMA units (syrk_split.hpp)
 //   syrk_reduce_kernel     : sums the slices in a fixed order (deterministic), applies scale and
 //                            the running average, writes both triangles.
 // The planner below picks the kernel and the split of K per factor and groups
@@ -31,6 +32,7 @@
 #include "syrk_corr3.hpp"
 #include "syrk_small.hpp"
 #include "syrk_bf16.hpp"
+#include "syrk_split.hpp"
 
 namespace kfac {
 
@@ -407,7 +409,7 @@ namespace {
 struct Cfg { int wt, nw, bm; };
 // the last entry is the wave-unit kernel (syrk_wave.hpp): 144-wide macro tiles, same partial layout as Tile<3,3>
 const Cfg kCfgs[] = {{4, 2, 128}, {3, 3, 144}, {2, 2, 64}, {1, 2, 32}, {0, 0, 144}, {0, 0, 144}, {0, 0, 32}, {0, 0, 64},
-                     {0, 0, 256}, {0, 0, 144}, {0, 0, 16}, {0, 0, 16}, {0, 0, 16}};
+                     {0, 0, 256}, {0, 0, 144}, {0, 0, 16}, {0, 0, 16}, {0, 0, 16}, {0, 0, 256}};
 constexpr int kWaveCfg = 4;
 constexpr int kCorr3Cfg = 10;  // 3x3 convolution factors from autocorrelations (syrk_corr3.hpp): 10 / 11 / 12 = 16 / 32 / 64 channels
 constexpr int kConv3Cfg = 5;   // fused 3x3 convolution kernel (syrk_conv3.hpp), same partial layout
@@ -415,6 +417,8 @@ constexpr int kSmall32Cfg = 6; // narrow NCHW operands (syrk_small.hpp), partial
 constexpr int kSmall64Cfg = 7; // same, 64 x 64 (d <= 64)
 constexpr int kWaveNchwCfg = 9; // wave-unit kernel for NCHW fp32 operands (same partial layout as kWaveCfg)
 constexpr int kBf16Cfg = 8;    // row-major bf16 operands on the bf16 MFMA units (syrk_bf16.hpp), 256 x 256 tiles
+inline bool is_corr3_cfg(int cfg) { return cfg >= kCorr3Cfg && cfg < kCorr3Cfg + 3; }
+constexpr int kSplitCfg = 13;  // wide fp32 operands on the bf16 MFMA units (syrk_split.hpp), same partial layout as kBf16Cfg
 
 bool small_eligible(const FactorJob &j)
 {
@@ -431,6 +435,24 @@ bool bf16_eligible(const FactorJob &j)
         return j.ld % 8 == 0 && (j.d_core + 7) / 8 * 8 <= j.ld && j.ld < (1l << 22);
     // NCHW: channel rows must start on 4-byte boundaries and the tensor must fit 32-bit buffer offsets
     return j.layout == kNCHW && j.hw % 2 == 0 && (j.K / j.hw) * (long)j.ctot * j.hw * 2 < 0x7fffffffl;
+}
+
+// Wide fp32 factors on the bf16 MFMA units.  The 256 x 128 tiles of that kernel cover the lower triangle of a
+// narrow factor badly (d = 576: 46 %), and the kernel runs about twice as fast per tile as the fp32 kernels it
+// competes with: the wave-unit kernel for row-major operands, the slower block-tile kernel for NCHW ones.
+bool split_syrk_eligible(const FactorJob &j)
+{
+    if (!(tuning().use_split_syrk && j.dtype == 0 && j.d_core >= 192)) return false;
+    const double fill = 0.5 * j.d_core * (double)j.d_core / ((double)syrk_split_tiles(j.d_core) * S_BM * S_BN);
+    if (j.layout == kRows) {
+        if (!(j.ld % 4 == 0 && j.ld < (1l << 22))) return false;
+        return fill * 100 >= tuning().split_syrk_fill_rows;
+    }
+    if (j.layout != kNCHW || j.hw <= 0) return false;
+    if ((j.K / j.hw) * (long)j.ctot * j.hw * 4 >= 0x7fffffffl) return false;
+    // K stages of 16 positions that never cross an image: small odd maps pad K (7 x 7: by 30 %)
+    const long slots = (j.hw + S_KT - 1) / S_KT * S_KT;
+    return fill * (double)j.hw / (double)slots * 100 >= tuning().split_syrk_fill_nchw;
 }
 
 bool wave_waste_ok(int d)
@@ -528,7 +550,7 @@ struct Planned {
 void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<Planned> &pl)
 {
     const Tuning &tu = tuning();
-    if (pl[idx[0]].cfg >= kCorr3Cfg) {
+    if (is_corr3_cfg(pl[idx[0]].cfg)) {
         // autocorrelation kernel: (image, strip) units dealt evenly to about target_blocks workgroups
         const long halves = pl[idx[0]].cfg == kCorr3Cfg + 2 ? 2 : 1;
         const long per = std::max<long>(1, tu.target_blocks / ((long)idx.size() * halves));
@@ -558,7 +580,7 @@ void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<
         p.nb = (jobs[j].d_core + c.bm - 1) / c.bm;
         p.nblk = p.nb * (p.nb + 1) / 2;
         p.bps = (p.cfg == kWaveCfg || p.cfg == kConv3Cfg || p.cfg == kWaveNchwCfg) ? wave_blocks_per_split(p.nb)
-                                                                                    : p.nblk;
+                : p.cfg == kSplitCfg ? syrk_split_tiles(jobs[j].d_core) : p.nblk;
         if (p.cfg == kConv3Cfg) {
             // K is walked in conv stages of R output rows; count them in units of 16 patch rows
             p.rows_per_stage = conv3_choose_rows(jobs[j].h, jobs[j].w);
@@ -588,12 +610,12 @@ void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<
             long ktiles = std::max<long>(1, (jobs[j].K + p.unit_rows - 1) / p.unit_rows);
             if (p.cfg == kSmall32Cfg || p.cfg == kSmall64Cfg)   // walked in groups of positions that never cross an image
                 ktiles = (jobs[j].K / jobs[j].hw) * ((jobs[j].hw + S_GROUP - 1) / S_GROUP);
-            if (p.cfg == kWaveNchwCfg)   // 16-position stages that never cross an image
+            if ((p.cfg == kWaveNchwCfg || p.cfg == kSplitCfg) && jobs[j].layout == kNCHW)   // 16-position stages that never cross an image
                 ktiles = (jobs[j].K / jobs[j].hw) * ((jobs[j].hw + W_KT - 1) / W_KT);
             if (p.cfg == kBf16Cfg && jobs[j].layout == kNCHW)   // 32-position stages that never cross an image
                 ktiles = (jobs[j].K / jobs[j].hw) * ((jobs[j].hw + H_KT - 1) / H_KT);
             long tpb_j = std::max<long>(1, tpb * p.stretch * 16 / p.unit_rows);
-            if (p.cfg == kWaveCfg)   // a split's byte range must stay below 2^31 (32-bit buffer offsets)
+            if (p.cfg == kWaveCfg || (p.cfg == kSplitCfg && jobs[j].layout == kRows))   // a split's byte range must stay below 2^31 (32-bit buffer offsets)
                 tpb_j = std::max<long>(1, std::min<long>(tpb_j, 0x7fffffffl / (64 * jobs[j].ld) - 1));
             if (p.cfg == kBf16Cfg && jobs[j].layout == kRows)
                 tpb_j = std::max<long>(1, std::min<long>(tpb_j, 0x7fffffffl / (2 * H_KT * jobs[j].ld) - 1));
@@ -614,7 +636,7 @@ void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<
     }
 }
 
-int group_key(const FactorJob &j, int cfg) { return cfg * 4 + j.layout * 2 + j.dtype; }
+int group_key(const FactorJob &j, int cfg) { return cfg * 8 + j.layout * 2 + j.dtype; }   // layout 0..2, dtype 0..1
 
 void plan_all(const FactorJob *jobs, int n, std::vector<Planned> &pl, std::vector<std::vector<int>> &groups)
 {
@@ -625,12 +647,13 @@ void plan_all(const FactorJob *jobs, int n, std::vector<Planned> &pl, std::vecto
         else if (jobs[i].layout == kConv3) pl[i].cfg = kConv3Cfg;
         else if (small_eligible(jobs[i])) pl[i].cfg = jobs[i].d_core <= 32 ? kSmall32Cfg : kSmall64Cfg;
         else if (bf16_eligible(jobs[i])) pl[i].cfg = kBf16Cfg;
+        else if (split_syrk_eligible(jobs[i])) pl[i].cfg = kSplitCfg;
         else if (wave_nchw_eligible(jobs[i])) pl[i].cfg = kWaveNchwCfg;
         else pl[i].cfg = wave_eligible(jobs[i]) ? kWaveCfg : choose_cfg(jobs[i].d_core);
         keys[i] = group_key(jobs[i], pl[i].cfg);
     }
     groups.clear();
-    for (int key = 0; key < 56; ++key) {
+    for (int key = 0; key < 8 * (kSplitCfg + 1); ++key) {
         std::vector<int> cur;
         for (int i = 0; i < n; ++i) {
             if (keys[i] != key) continue;
@@ -697,6 +720,7 @@ int red_kind(int cfg)
         case kSmall32Cfg: return 3;
         case kSmall64Cfg: return 2;
         case kBf16Cfg: return 5;
+        case kSplitCfg: return 5;
         default: return 4;             // wave-unit and fused convolution kernels
     }
 }
@@ -894,7 +918,7 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
         const int cfg = pl[g[0]].cfg;
         const int layout = jobs[g[0]].layout, dt = jobs[g[0]].dtype;
         hipError_t e = hipSuccess;
-        if (cfg >= kCorr3Cfg) {
+        if (is_corr3_cfg(cfg)) {
             e = corr3_launch(jobs, g, pl, offs, work, flops, corr_flops, s);
             if (e != hipSuccess) return e;
             continue;
@@ -937,6 +961,15 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
                 else
                     KFAC_LAUNCH(KFAC_K_SYRK_BF16, s, syrk_bf16_kernel<kNCHW>, dim3(blocks), dim3(512), 0, tab);
                 timing_work(flops);
+                e = hipGetLastError();
+                break;
+            }
+            case kSplitCfg: {
+                if (layout == kRows)
+                    KFAC_LAUNCH(KFAC_K_SYRK_SPLIT, s, syrk_split_kernel<kRows>, dim3(blocks), dim3(256), 0, tab);
+                else
+                    KFAC_LAUNCH(KFAC_K_SYRK_SPLIT, s, syrk_split_kernel<kNCHW>, dim3(blocks), dim3(256), 0, tab);
+                timing_work(flops, 6.0 * flops);
                 e = hipGetLastError();
                 break;
             }
