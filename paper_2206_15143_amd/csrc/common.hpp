@@ -138,6 +138,7 @@ struct Tuning {
     long use_split_syrk = 1;         // wide fp32 factors as six bf16 MFMA products of the inputs' bf16 pieces
     long split_syrk_fill_rows = 60;  // ... row-major inputs: when the factor fills this percentage of its 256 x 128 tiles
     long split_syrk_fill_nchw = 40;  // ... NCHW inputs (tile fill x share of real positions in the K stages)
+    long split_syrk_max_stages = 32; // ... K stages (of 16 rows) per slice at most: bounds the accumulation chain
     long use_split_gemm = 1;         // large A^T B products as six bf16 MFMA products of the operands' bf16 pieces
     long split_gemm_min_m = 192;     // ... from this many output rows on
     long split_gemm_min_k = 1024;     // ... and this depth (stores only)

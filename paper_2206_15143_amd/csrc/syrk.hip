@@ -619,6 +619,12 @@ void plan_group(const FactorJob *jobs, const std::vector<int> &idx, std::vector<
                 tpb_j = std::max<long>(1, std::min<long>(tpb_j, 0x7fffffffl / (64 * jobs[j].ld) - 1));
             if (p.cfg == kBf16Cfg && jobs[j].layout == kRows)
                 tpb_j = std::max<long>(1, std::min<long>(tpb_j, 0x7fffffffl / (2 * H_KT * jobs[j].ld) - 1));
+            // The bf16 MFMA adds its sixteen products to the accumulator with the low bits of the aligned addends cut
+            // off: on non-negative inputs (post-ReLU activations) every stage biases the sum down by about a
+            // quarter of an ulp, measured -1.6e-8 per stage relative to the result (-3e-6 over 200 stages, where
+            // the fp32 MFMA kernels stay at 2.5e-7).  Slices are therefore kept short; the reduction adds them in
+            // fp32 with round-to-nearest.
+            if (p.cfg == kSplitCfg) tpb_j = std::max<long>(1, std::min<long>(tpb_j, tu.split_syrk_max_stages));
             p.splits = (int)((ktiles + tpb_j - 1) / tpb_j);
             // every element of the block-tile kernels' partials is summed serially over the splits by one
             // thread of the reduction: keep that chain short

@@ -43,12 +43,15 @@ def test_resnet110_config_batched_full_size():
     scales = gu.scales_for(layers, batch)
     print("gpu run", flush=True)
     gpu = gu.run_layers_gpu(layers, batch, inputs, scales, hp["decay"], hp["damping"], batched=True)
-    sampled = [0, 1, 36, 37, 72, 73, 108, 109]
-    for i in sampled:
-        print("oracle layer", i, layers[i].d_A, flush=True)
+    worst = {}
+    for i in range(len(layers)):      # every layer against the oracle's whole chain
         ref = gu.run_layer_oracle(layers[i], inputs[i], scales[i], hp["decay"], hp["damping"])
         errs = gu.check_layer(gpu[i], ref, tag=f"{name} layer {i}")
-        print(i, {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+        for k, v in errs.items():
+            worst[k] = max(worst.get(k, 0.0), v)
+        if i % 10 == 9:
+            print(f"{i + 1} layers compared with the oracle", flush=True)
+    print("worst relative Frobenius errors over the 110 layers:", {k: f"{v:.2e}" for k, v in worst.items()}, flush=True)
     lam = hp["damping"]
     for i, l in enumerate(layers):
         g = gpu[i]
@@ -112,6 +115,13 @@ def test_distinct_shapes_full_size(name, i):
         got = F[us, vs].astype(np.float64)
         assert np.linalg.norm(got - ref) / np.linalg.norm(ref) < 1e-4
         assert np.array_equal(F, F.T)
+    # Freivalds check of both factors: F z against decay z + (1 - decay) s X^T (X z) for random +-1 vectors, from
+    # the oracle's rows in fp64: a wrong tile anywhere in the factor shows, which sampled entries would miss
+    for F, X, s, d in ((g["A"], abar, sc[0], l.d_A), (g["G"], grow, sc[1], l.d_G)):
+        z = gen.integers(0, 2, size=(d, 4)).astype(np.float64) * 2.0 - 1.0
+        want = hp["decay"] * z + (1.0 - hp["decay"]) * s * (X.T @ (X @ z))
+        got = (torch.from_numpy(F).to(gu.DEV, torch.float64) @ torch.from_numpy(z).to(gu.DEV)).cpu().numpy()
+        assert np.linalg.norm(got - want) / np.linalg.norm(want) < 1e-4
     # trace of the new A factor = scale * ||abar||_F^2 (cheap at any size)
     tr_new = (np.trace(g["A"].astype(np.float64)) - hp["decay"] * l.d_A) / (1 - hp["decay"])
     assert abs(tr_new - sc[0] * (abar ** 2).sum()) <= 1e-4 * tr_new

@@ -1,7 +1,8 @@
 """The three batched calls recorded into a HIP graph and replayed: every replay must give the bits of the eager run.
 
 The library allocates nothing and takes every table as a kernel argument, so a captured sequence holds all it
-needs; the inverse of two large factors forks to the library's second stream and joins back inside the capture.
+needs; the inverse of the two large factors forks to the library's own streams (look-ahead of the blocked sweep,
+the small factors beside the large ones) and joins back inside the capture.
 """
 import numpy as np
 import pytest
@@ -15,22 +16,13 @@ from workloads.shapes import LayerSpec
 import gpu_util as gu
 
 
-@pytest.fixture
-def two_streams_from_two_matrices():
-    # the library forks to its second stream from 8 large matrices on: lower the threshold so that the two
-    # order-1301 factors of this test take that path
-    kf.kfac_tune("invert_two_streams_min", 2)
-    yield
-    kf.kfac_tune("invert_two_streams_min", 8)
-
-
-def test_three_calls_captured_in_a_graph_replay_like_eager(two_streams_from_two_matrices):
+def test_three_calls_captured_in_a_graph_replay_like_eager():
     layers = [LayerSpec("conv", 16, 16, 3, 1, 1, 8),            # A factor from autocorrelations
               LayerSpec("conv", 3, 8, 3, 1, 1, 8),              # patch extraction + block-tile kernel
               LayerSpec("conv", 8, 8, 1, 1, 0, 4),
               LayerSpec("linear", 70, 20, rows=40),
-              LayerSpec("linear", 1300, 12, rows=24),           # two factors of order 1301: the two-level inverse,
-              LayerSpec("linear", 1300, 12, rows=24)]           # two groups on two streams
+              LayerSpec("linear", 1300, 12, rows=24),           # two factors of order 1301: the two-level inverse with
+              LayerSpec("linear", 1300, 12, rows=24)]           # its look-ahead on the library's second stream
     batch = 4
     inputs = gu.draw_inputs(layers, batch, 8800, "relu_normal", 0.05)
     scales = gu.scales_for(layers, batch)
@@ -73,6 +65,12 @@ def test_three_calls_captured_in_a_graph_replay_like_eager(two_streams_from_two_
     step()
     ref = snapshot()
     assert int(ref[-1].abs().sum().item()) == 0
+    # the eager run itself against the CPU oracle (the replays are then compared with it bit for bit)
+    for i, l in enumerate(layers):
+        want = gu.run_layer_oracle(l, inputs[i], scales[i], 0.9, 0.02)
+        got = dict(A=ref[i].cpu().numpy(), G=ref[n + i].cpu().numpy(), A_inv=ref[2 * n + i].cpu().numpy(),
+                   G_inv=ref[3 * n + i].cpu().numpy(), P=ref[4 * n + i].cpu().numpy(), info=np.zeros(2, dtype=np.int32))
+        gu.check_layer(got, want, tag=f"eager layer {i}")
 
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())

@@ -1,0 +1,160 @@
+"""Whole configurations through ONE batched call per stage, exactly as bench.py issues them (marshalled
+arrays, all layers of the workload, mixed shapes in shared launches, the inversion's look-ahead on the library's
+own streams), checked against the CPU oracle.
+
+Per layer of the configuration:
+  * `d_info == 0` and bitwise symmetry of both factors and both inverses;
+  * a Freivalds check of both factors against the oracle's rows: for four random +-1 vectors z,
+    `F z` must equal `decay z + (1 - decay) s X^T (X z)` (fp64, X from the oracle's patch / row extraction).  A wrong
+    tile anywhere in F changes `F z`, so this sees every entry of every factor;
+  * the residual of both inverses, which bounds their error rigorously: `X - M^-1 = M^-1 (M X - I)` and a running
+    average started at the identity has `M >= (decay + lambda) I` (where that bound is not below the tolerance,
+    which happens for ill-conditioned factors of moderate order, the inverse is compared with the oracle's);
+  * the preconditioned gradient against `G_inv grad A_inv` applied to random vectors (fp64).
+On one layer of every distinct shape the oracle can afford, the whole chain (factors, inverses, preconditioned
+gradient) is compared element by element with the oracle run from the same inputs.
+"""
+from collections import OrderedDict
+
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import paper_2206_15143_amd as kf
+from oracle import kfac_oracle as orc
+from workloads import rng, shapes
+
+import gpu_util as gu
+
+NZ = 4
+
+
+def _pm1(gen, d):
+    return gen.integers(0, 2, size=(d, NZ)).astype(np.float64) * 2.0 - 1.0
+
+
+def _dev64(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).to(gu.DEV, torch.float64)
+
+
+def _run_whole_config(name, chain_cost_cap, full_residual_cap):
+    hp = shapes.config_hparams(name)
+    layers = shapes.config_layers(name)
+    batch, lam, decay, dtype = hp["batch"], hp["damping"], hp["decay"], hp["dtype"]
+    bf = dtype == "bf16"
+    std = hp["gout_var"] ** 0.5
+    n = len(layers)
+    gen = np.random.default_rng(77 + hp["index"])
+    scales = gu.scales_for(layers, batch)
+
+    acts, gouts, grads = [], [], []
+    zA, zG, refA, refG = [], [], [], []
+    chain = OrderedDict()          # layer index -> oracle result of the whole chain, one per affordable distinct shape
+    seen = set()
+    for i, l in enumerate(layers):
+        act, gout, grad = rng.layer_inputs(l, batch, 1000 * hp["index"] + i, hp["act"], std, dtype)
+        abar, grow = orc.layer_rows(l, act, gout)
+        za, zg = _pm1(gen, l.d_A), _pm1(gen, l.d_G)
+        zA.append(za)
+        zG.append(zg)
+        refA.append(decay * za + (1.0 - decay) * scales[i][0] * (abar.T @ (abar @ za)))
+        refG.append(decay * zg + (1.0 - decay) * scales[i][1] * (grow.T @ (grow @ zg)))
+        cost = l.n_rows(batch) * (l.d_A ** 2 + l.d_G ** 2) + l.d_A ** 3 + l.d_G ** 3
+        if l not in seen and cost <= chain_cost_cap:
+            A = orc.running_average(np.eye(l.d_A), orc.factor(abar, scales[i][0]), decay)
+            G = orc.running_average(np.eye(l.d_G), orc.factor(grow, scales[i][1]), decay)
+            Ai, Gi = orc.invert_layer(A, G, lam, lam)
+            chain[i] = dict(A=A, G=G, A_inv=Ai, G_inv=Gi, P=orc.precondition_layer(Ai, Gi, grad))
+        seen.add(l)
+        del abar, grow
+        acts.append(gu.to_dev(act, bf))
+        gouts.append(gu.to_dev(gout, bf))
+        grads.append(gu.to_dev(grad))
+        if i % 16 == 15:
+            print(f"{name}: {i + 1}/{n} layers drawn", flush=True)
+
+    descs = [kf.LayerDesc.from_spec(l, kf.KFAC_BF16 if bf else kf.KFAC_F32) for l in layers]
+    b, h, w = gu.batch_args(layers, batch)
+    A_run = [torch.eye(l.d_A, device=gu.DEV) for l in layers]
+    G_run = [torch.eye(l.d_G, device=gu.DEV) for l in layers]
+    A_inv = [torch.full((l.d_A, l.d_A), float("nan"), device=gu.DEV) for l in layers]
+    G_inv = [torch.full((l.d_G, l.d_G), float("nan"), device=gu.DEV) for l in layers]
+    outs = [torch.full((l.d_G, l.d_A), float("nan"), device=gu.DEV) for l in layers]
+    info = torch.full((2 * n,), -1, dtype=torch.int32, device=gu.DEV)
+    ws = gu.workspace(kf.kfac_workspace_bytes_batched(descs, b, h, w))
+    P_ = kf.marshal_ptrs
+    md, mb, mh, mw = kf.marshal_descs(descs), kf.marshal_ints(b), kf.marshal_ints(h), kf.marshal_ints(w)
+    mAr, mGr, mAi, mGi = P_(A_run), P_(G_run), P_(A_inv), P_(G_inv)
+    print(f"{name}: one batched call per stage over {n} layers", flush=True)
+    kf.kfac_update_factors_batched(md, P_(acts), P_(gouts), mb, mh, mw, kf.marshal_floats([s[0] for s in scales]),
+                                   kf.marshal_floats([s[1] for s in scales]), decay, mAr, mGr, ws)
+    kf.kfac_invert_batched(md, mAr, mGr, lam, lam, mAi, mGi, info, ws)
+    kf.kfac_precondition_batched(md, mAi, mGi, P_(grads), P_(outs), ws)
+    torch.cuda.synchronize()
+    del acts, gouts
+
+    inf = info.cpu().numpy()
+    assert not inf.any(), f"{name}: d_info flags {np.nonzero(inf)[0]}"
+    tol_f = 1e-4                       # factors
+    tol_i = 1e-4                       # inverses
+    tol_p = 1e-3 if not bf else 2e-2   # preconditioned gradient
+    worst = dict(factor=0.0, inverse=0.0, precond=0.0)
+    zgen = torch.Generator(device=gu.DEV)
+    zgen.manual_seed(5)
+    for i, l in enumerate(layers):
+        for F, X, z, ref, tag in ((A_run[i], A_inv[i], zA[i], refA[i], "A"), (G_run[i], G_inv[i], zG[i], refG[i], "G")):
+            assert torch.equal(F, F.T), f"{name} layer {i}: {tag} not bitwise symmetric"
+            assert torch.equal(X, X.T), f"{name} layer {i}: {tag}_inv not bitwise symmetric"
+            Fd = F.double()
+            got = (Fd @ _dev64(z)).cpu().numpy()
+            e = np.linalg.norm(got - ref) / np.linalg.norm(ref)
+            worst["factor"] = max(worst["factor"], e)
+            assert e < tol_f, f"{name} layer {i}: Freivalds check of {tag} {e:.2e}"
+            d = F.shape[0]
+            Md = Fd + lam * torch.eye(d, device=gu.DEV, dtype=torch.float64)
+            Xd = X.double()
+            if d <= full_residual_cap:
+                res = float(torch.linalg.norm(Md @ Xd - torch.eye(d, device=gu.DEV, dtype=torch.float64)))
+            else:
+                # ||R||_F from 32 random +-1 vectors: E ||R z||^2 = ||R||_F^2 (relative spread 1/4; a factor 2 is kept)
+                Z = torch.randint(0, 2, (d, 32), generator=zgen, device=gu.DEV).double() * 2.0 - 1.0
+                Rz = Md @ (Xd @ Z) - Z
+                res = 2.0 * float(torch.sqrt((Rz * Rz).sum() / 32.0))
+            bound = res / (decay + lam) / float(torch.linalg.norm(Xd))
+            if bound >= tol_i and d <= 1600:
+                # the bound is loose for an ill-conditioned factor (it grows with the condition number, the
+                # error does not have to): such a matrix is compared with the oracle's inverse itself
+                bound = gu.rel_fro(X.cpu().numpy(), orc.inverse(F.cpu().numpy().astype(np.float64), lam))
+            worst["inverse"] = max(worst["inverse"], bound)
+            assert bound < tol_i, f"{name} layer {i}: error (bound) of {tag}_inv {bound:.2e}"
+        # P = G_inv grad A_inv on random vectors
+        Z = torch.randint(0, 2, (l.d_A, NZ), generator=zgen, device=gu.DEV).double() * 2.0 - 1.0
+        want = G_inv[i].double() @ (grads[i].double() @ (A_inv[i].double() @ Z))
+        got = outs[i].double() @ Z
+        e = float(torch.linalg.norm(got - want) / torch.linalg.norm(want))
+        worst["precond"] = max(worst["precond"], e)
+        assert e < tol_p, f"{name} layer {i}: preconditioned gradient on random vectors {e:.2e}"
+    print(f"{name}: worst Freivalds {worst['factor']:.2e}, inverse bound {worst['inverse']:.2e}, "
+          f"precondition {worst['precond']:.2e}", flush=True)
+    # the whole chain against the oracle on one layer of every affordable distinct shape
+    assert chain, "no layer of this configuration is within the oracle's budget"
+    for i, ref in chain.items():
+        g = dict(A=A_run[i].cpu().numpy(), G=G_run[i].cpu().numpy(), A_inv=A_inv[i].cpu().numpy(),
+                 G_inv=G_inv[i].cpu().numpy(), P=outs[i].cpu().numpy(), info=inf[2 * i:2 * i + 2])
+        errs = gu.check_layer(g, ref, tol_p=1e-3, tag=f"{name} layer {i} (whole chain)")
+        print(f"{name} layer {i} {layers[i].d_A}x{layers[i].d_G} vs oracle:",
+              {k: f"{v:.1e}" for k, v in errs.items()}, flush=True)
+
+
+def test_resnet50_fp32_whole_config_one_batched_call():
+    _run_whole_config("resnet50_imagenet", chain_cost_cap=2.5e10, full_residual_cap=5000)
+
+
+def test_resnet50_bf16_whole_config_one_batched_call():
+    _run_whole_config("resnet50_imagenet_bf16", chain_cost_cap=1.5e10, full_residual_cap=2400)
+
+
+def test_transformer_whole_config_one_batched_call():
+    _run_whole_config("transformer_encoder_bf16", chain_cost_cap=5e10, full_residual_cap=1100)
