@@ -211,3 +211,38 @@ def test_eigen_variant_resnet110_shapes_full_size():
         e_p = gu.rel_fro(g["P"], ref)
         print(f"layer {i}: preconditioned gradient {e_p:.2e}", flush=True)
         assert e_p < 1e-3, i
+
+
+def test_eigen_variant_order_1153_full_size():
+    """A ResNet-50-shaped 3x3 layer at full size (d_A = 1153, d_G = 128, 25 088 patch rows).  The oracle's cyclic
+    Jacobi iteration would take minutes at this order, so the decomposition is checked through what defines it --
+    Q orthogonal and M Q = Q diag(v), which together bound every eigenvalue's error by the residual -- and the
+    preconditioned gradient through the equation Eq. 13 solves exactly, (A (x) G + gamma I) vec(P) = vec(grad),
+    i.e. G P A + gamma P = grad, with the oracle's own factors A and G (fp64, from the same inputs)."""
+    hp = shapes.config_hparams("resnet50_imagenet")
+    l = LayerSpec("conv", 128, 128, 3, 1, 1, 28)
+    batch, decay, gamma = hp["batch"], hp["decay"], 0.01
+    inputs = gu.draw_inputs([l], batch, 8950, hp["act"], hp["gout_var"] ** 0.5)
+    scales = gu.scales_for([l], batch)
+    res, info = _eigen_path_gpu([l], batch, inputs, scales, decay, gamma, True)
+    assert not info.any()
+    g = res[0]
+    A, G = orc.update_factors_layer(l, inputs[0][0], inputs[0][1], scales[0][0], scales[0][1], decay,
+                                    np.eye(l.d_A), np.eye(l.d_G))
+    assert gu.rel_fro(g["A"], A) < 1e-4 and gu.rel_fro(g["G"], G) < 1e-4
+    for M, Q, v, tag in ((g["A"], g["QA"], g["vA"], "A"), (g["G"], g["QG"], g["vG"], "G")):
+        n = M.shape[0]
+        Md, Qd, vd = M.astype(np.float64), Q.astype(np.float64), v.astype(np.float64)
+        e_orth = np.linalg.norm(Qd.T @ Qd - np.eye(n)) / np.sqrt(n)
+        e_res = np.linalg.norm(Md @ Qd - Qd * vd) / np.linalg.norm(Md)
+        e_tr = abs(vd.sum() - np.trace(Md)) / np.trace(Md)
+        print(f"{tag} n={n}: orthogonality {e_orth:.2e} residual {e_res:.2e} trace {e_tr:.2e}", flush=True)
+        assert e_orth < 1e-4 and e_res < 2e-5 and e_tr < 1e-5, tag
+        assert vd.min() > 0.9 * decay           # a running average started at the identity: M >= decay I
+    P = g["P"].astype(np.float64)
+    grad = inputs[0][2].astype(np.float64)
+    resid = G @ P @ A + gamma * P - grad
+    # ||P - P*||_F <= ||resid||_F / (lambda_min(A) lambda_min(G) + gamma), lambda_min >= decay
+    bound = np.linalg.norm(resid) / (decay * decay + gamma) / np.linalg.norm(P)
+    print(f"preconditioned gradient: residual bound {bound:.2e}", flush=True)
+    assert bound < 1e-3
