@@ -71,9 +71,14 @@ typedef struct {
     int d_in;        /* LINEAR: input features.  CONV2D: input channels C_in */
     int d_out;       /* LINEAR: output features. CONV2D: output channels C_out */
     int kh, kw;      /* CONV2D: kernel size (groups 1, dilation 1); LINEAR: ignored */
-    int stride, pad; /* CONV2D only */
+    int stride, pad; /* CONV2D only; pad: zero padding of both map dimensions */
     int has_bias;    /* 1: homogeneous column appended last, d_A = d_in*kh*kw + 1 */
     int in_dtype;    /* kfac_dtype of activations and output gradients */
+    int pad_h, pad_w; /* CONV2D only, >= 0: FURTHER zero padding of the rows (top and bottom) / of the columns
+                       * (left and right) on top of `pad`, for kernels padded differently in the two directions:
+                       * a 1x7 "same" convolution is pad = 0, pad_h = 0, pad_w = 3.  A descriptor that leaves
+                       * both at 0 means what it meant before these fields existed.
+                       * h_out = (h + 2 (pad + pad_h) - kh) / stride + 1, w_out likewise with pad_w, kw. */
 } kfac_layer_desc;
 
 /* Order of the factors (section 3: A is d_{i-1} x d_{i-1}, G is d_i x d_i). */
@@ -93,7 +98,11 @@ size_t kfac_workspace_bytes_batched(int n, const kfac_layer_desc *descs, const i
 /* Patch extraction alone (the first step of kfac_update_factors for CONV2D
  * layers with kh*kw > 1 or stride > 1): d_patches is row-major
  * [batch*h_out*w_out, kfac_patch_ld], row (n, oh, ow), column (c, i, j), zero
- * padding, pad columns zero; same element type as the input. */
+ * padding, pad columns zero; same element type as the input.
+ * The kernel stages one output row of a few channels on chip: a map so wide that
+ * (w_out - 1) * stride + kw elements times kh rows times 4 channels (8 for bf16, fewer when kh*kw shares a
+ * factor with that) exceed 60 KB is rejected with KFAC_ERR_SHAPE by every call that would extract patches
+ * (output rows of more than about 540 columns for a 7x7 kernel, 1270 for 3x3, stride 1, either dtype). */
 kfac_status kfac_im2col(const kfac_layer_desc *desc, const void *d_act, int batch, int h, int w,
                         void *d_patches, void *hip_stream);
 

@@ -54,13 +54,14 @@ int oracle_num_threads(void)
 }
 
 /* x: NCHW [B, C, H, W] (float bits as given to the GPU).  out: row-major
- * [B*Ho*Wo, C*kh*kw (+1)]; row (n, oh, ow), column (c, i, j); zero padding;
+ * [B*Ho*Wo, C*kh*kw (+1)]; row (n, oh, ow), column (c, i, j); zero padding of
+ * pad_h rows above and below and pad_w columns left and right of the map;
  * last column is 1 when has_bias. */
-void oracle_patches(const float *x, int B, int C, int H, int W, int kh, int kw, int stride, int pad,
+void oracle_patches(const float *x, int B, int C, int H, int W, int kh, int kw, int stride, int pad_h, int pad_w,
                     int has_bias, double *out)
 {
-    const int Ho = (H + 2 * pad - kh) / stride + 1;
-    const int Wo = (W + 2 * pad - kw) / stride + 1;
+    const int Ho = (H + 2 * pad_h - kh) / stride + 1;
+    const int Wo = (W + 2 * pad_w - kw) / stride + 1;
     const long dA = (long)C * kh * kw + (has_bias ? 1 : 0);
 #pragma omp parallel for schedule(static)
     for (long nr = 0; nr < (long)B * Ho; ++nr) {
@@ -70,8 +71,8 @@ void oracle_patches(const float *x, int B, int C, int H, int W, int kh, int kw, 
             for (int c = 0; c < C; ++c)
                 for (int i = 0; i < kh; ++i)
                     for (int j = 0; j < kw; ++j) {
-                        const int ih = oh * stride - pad + i;
-                        const int iw = ow * stride - pad + j;
+                        const int ih = oh * stride - pad_h + i;
+                        const int iw = ow * stride - pad_w + j;
                         double v = 0.0;
                         if (ih >= 0 && ih < H && iw >= 0 && iw < W)
                             v = (double)x[(((long)n * C + c) * H + ih) * W + iw];
@@ -208,7 +209,6 @@ int oracle_inverse_chol(const double *M, int n, double damping, double *Minv)
     return 0;
 }
 
-/* P = Ginv [dG x dG] * grad [dG x dA] * Ainv [dA x dA] */
 /* Eq. 12: (A (x) G + gamma I)^-1 is approximated by (A + pi sqrt(gamma) I)^-1 (x) (G + sqrt(gamma)/pi I)^-1
  * with pi^2 = (tr A / dim A) / (tr G / dim G).  out[0] = lambda_A, out[1] = lambda_G.  A trace that is
  * not positive leaves pi = 1 (the split is then the symmetric one). */
@@ -223,6 +223,7 @@ void oracle_pi_damping(const double *A, int dA, const double *G, int dG, double 
     out[1] = sqrt(gamma) / pi;
 }
 
+/* Eq. 5 / right-hand side of Eq. 12: P = Ginv [dG x dG] * grad [dG x dA] * Ainv [dA x dA] */
 void oracle_precondition(const double *Ginv, const double *grad, const double *Ainv, int dG, int dA, double *P)
 {
     double *T = (double *)malloc(sizeof(double) * (size_t)dG * dA);

@@ -40,15 +40,17 @@ def num_threads() -> int:
     return int(_lib.oracle_num_threads())
 
 
-def patches(x: np.ndarray, kh: int, kw: int, stride: int, pad: int, has_bias: bool) -> np.ndarray:
+def patches(x: np.ndarray, kh: int, kw: int, stride: int, pad: int, has_bias: bool, pad_w: int = -1) -> np.ndarray:
+    """`pad` pads the rows of the map and, unless `pad_w` >= 0 is given, its columns too."""
     x = np.ascontiguousarray(x, dtype=np.float32)
     B, Cc, H, W = x.shape
+    pad_w = pad if pad_w < 0 else pad_w
     Ho = (H + 2 * pad - kh) // stride + 1
-    Wo = (W + 2 * pad - kw) // stride + 1
+    Wo = (W + 2 * pad_w - kw) // stride + 1
     dA = Cc * kh * kw + (1 if has_bias else 0)
     out = np.empty((B * Ho * Wo, dA), dtype=np.float64)
     _lib.oracle_patches(_f(x), C.c_int(B), C.c_int(Cc), C.c_int(H), C.c_int(W), C.c_int(kh), C.c_int(kw),
-                        C.c_int(stride), C.c_int(pad), C.c_int(int(has_bias)), _d(out))
+                        C.c_int(stride), C.c_int(pad), C.c_int(pad_w), C.c_int(int(has_bias)), _d(out))
     return out
 
 
@@ -155,7 +157,7 @@ def precondition_eigen(QG, vG, QA, vA, grad, gamma: float) -> np.ndarray:
 def layer_rows(layer, act: np.ndarray, gout: np.ndarray):
     """(a_bar [R, d_A], g [R, d_G]) for a workloads.LayerSpec."""
     if layer.kind == "conv":
-        abar = patches(act, layer.k, layer.kw, layer.stride, layer.pad, layer.has_bias)
+        abar = patches(act, layer.k, layer.kw, layer.stride, layer.pad, layer.has_bias, layer.pw)
         g = rows_from_nchw(gout)
     else:
         abar = linear_rows(act, layer.has_bias)

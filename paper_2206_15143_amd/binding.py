@@ -27,7 +27,8 @@ class KfacError(RuntimeError):
 
 class LayerDesc(C.Structure):
     _fields_ = [("kind", C.c_int), ("d_in", C.c_int), ("d_out", C.c_int), ("kh", C.c_int), ("kw", C.c_int),
-                ("stride", C.c_int), ("pad", C.c_int), ("has_bias", C.c_int), ("in_dtype", C.c_int)]
+                ("stride", C.c_int), ("pad", C.c_int), ("has_bias", C.c_int), ("in_dtype", C.c_int),
+                ("pad_h", C.c_int), ("pad_w", C.c_int)]
 
     @staticmethod
     def linear(d_in: int, d_out: int, has_bias: bool = True, dtype: int = KFAC_F32) -> "LayerDesc":
@@ -35,15 +36,20 @@ class LayerDesc(C.Structure):
 
     @staticmethod
     def conv2d(c_in: int, c_out: int, k: int, stride: int = 1, pad: int = 0, has_bias: bool = True,
-               dtype: int = KFAC_F32, kw: Optional[int] = None) -> "LayerDesc":
-        return LayerDesc(KFAC_CONV2D, c_in, c_out, k, k if kw is None else kw, stride, pad, int(has_bias), dtype)
+               dtype: int = KFAC_F32, kw: Optional[int] = None, pad_w: Optional[int] = None) -> "LayerDesc":
+        """`pad` pads the rows of the map and, unless `pad_w` is given, its columns too."""
+        pw = pad if pad_w is None else pad_w
+        both = min(pad, pw)
+        return LayerDesc(KFAC_CONV2D, c_in, c_out, k, k if kw is None else kw, stride, both, int(has_bias), dtype,
+                         pad - both, pw - both)
 
     @staticmethod
     def from_spec(spec, dtype: int = KFAC_F32) -> "LayerDesc":
-        """From a workloads.LayerSpec-like object (kind, c_in, c_out, k, stride, pad, has_bias; kw if present)."""
+        """From a workloads.LayerSpec-like object (kind, c_in, c_out, k, stride, pad, has_bias; kw and pw, the
+        kernel width and the column padding, if present)."""
         if spec.kind == "conv":
             return LayerDesc.conv2d(spec.c_in, spec.c_out, spec.k, spec.stride, spec.pad, spec.has_bias, dtype,
-                                    kw=getattr(spec, "kw", None))
+                                    kw=getattr(spec, "kw", None), pad_w=getattr(spec, "pw", None))
         return LayerDesc.linear(spec.c_in, spec.c_out, spec.has_bias, dtype)
 
 
@@ -120,12 +126,25 @@ def load_library():
     return lib
 
 
+def _addr(t) -> int:
+    """Device address of a tensor, after the two checks a raw pointer cannot make for itself: the library
+    assumes dense row-major storage, and knows 4-byte (fp32, int32), 2-byte (bfloat16) and byte (workspace)
+    elements only, so a strided view or a float64 tensor is refused here instead of being misread there."""
+    contiguous = getattr(t, "is_contiguous", None)
+    if contiguous is not None and not contiguous():
+        raise ValueError(f"tensor of shape {tuple(t.shape)} is not contiguous: the library takes dense row-major buffers")
+    size = getattr(t, "element_size", None)
+    if size is not None and size() not in (1, 2, 4):
+        raise TypeError(f"tensor of dtype {getattr(t, 'dtype', '?')}: the library takes fp32 / int32, bfloat16 or byte buffers")
+    return int(t.data_ptr())
+
+
 def _ptr(t) -> Optional[int]:
     if t is None:
         return None
     if isinstance(t, int):
         return t
-    return int(t.data_ptr())
+    return _addr(t)
 
 
 def _nbytes(t) -> int:
@@ -170,7 +189,7 @@ def _ptrs(ts):
     if isinstance(ts, C.Array):
         return ts
     return (C.c_void_p * len(ts)).from_buffer(array("Q", [0 if t is None else t if isinstance(t, int)
-                                                          else t.data_ptr() for t in ts]))
+                                                          else _addr(t) for t in ts]))
 
 
 def marshal_descs(descs: Sequence[LayerDesc]):

@@ -72,6 +72,7 @@ namespace {
 struct Geo {
     int dA, dG, d_core;
     int Ho, Wo;
+    int ph, pw;         // padding of the rows / columns of the map
     long R;             // rows of the patch matrix / samples
     bool conv, patches; // patches: the extractor has to run
     bool fused3;        // 3x3/s1/p1 fp32 conv whose A factor is built straight from the NCHW input
@@ -94,7 +95,8 @@ kfac_status desc_check(const kfac_layer_desc *d)
     if (d->d_in <= 0 || d->d_out <= 0) return KFAC_ERR_SHAPE;
     if (d->has_bias != 0 && d->has_bias != 1) return KFAC_ERR_SHAPE;
     if (d->kind == KFAC_CONV2D) {
-        if (d->kh <= 0 || d->kw <= 0 || d->stride <= 0 || d->pad < 0) return KFAC_ERR_SHAPE;
+        if (d->kh <= 0 || d->kw <= 0 || d->stride <= 0 || d->pad < 0 || d->pad_h < 0 || d->pad_w < 0)
+            return KFAC_ERR_SHAPE;
         if ((long)d->d_in * d->kh * d->kw > (1l << 24)) return KFAC_ERR_SHAPE;
     }
     return KFAC_OK;
@@ -119,15 +121,21 @@ kfac_status geometry(const kfac_layer_desc *d, int batch, int h, int w, Geo &g)
     g.ld = (g.d_core + vec - 1) / vec * vec;
     if (g.conv) {
         if (h <= 0 || w <= 0) return KFAC_ERR_SHAPE;
-        if (h + 2 * d->pad < d->kh || w + 2 * d->pad < d->kw) return KFAC_ERR_SHAPE;
-        g.Ho = (h + 2 * d->pad - d->kh) / d->stride + 1;
-        g.Wo = (w + 2 * d->pad - d->kw) / d->stride + 1;
+        const int ph = d->pad + d->pad_h, pw = d->pad + d->pad_w;   // rows, columns
+        if (h + 2 * ph < d->kh || w + 2 * pw < d->kw) return KFAC_ERR_SHAPE;
+        g.ph = ph;
+        g.pw = pw;
+        g.Ho = (h + 2 * ph - d->kh) / d->stride + 1;
+        g.Wo = (w + 2 * pw - d->kw) / d->stride + 1;
         g.R = (long)batch * g.Ho * g.Wo;
-        g.patches = !(d->kh == 1 && d->kw == 1 && d->stride == 1 && d->pad == 0);
+        g.patches = !(d->kh == 1 && d->kw == 1 && d->stride == 1 && ph == 0 && pw == 0);
         g.fused3 = tuning().fuse_conv3 && d->in_dtype == KFAC_F32 && d->kh == 3 && d->kw == 3 && d->stride == 1 &&
-                   d->pad == 1 && d->d_in % 16 == 0 && d->d_in <= tuning().fuse_conv3_max_c && conv3_rows(h, w) > 0 &&
+                   ph == 1 && pw == 1 && d->d_in % 16 == 0 && d->d_in <= tuning().fuse_conv3_max_c && conv3_rows(h, w) > 0 &&
                    (long)batch * d->d_in * h * w * 4 < 0x7fff0000l;
         if (g.fused3) g.patches = false;
+        // the patch kernel stages at least one output row of its narrowest channel chunk in LDS: a map too wide for
+        // that is refused here, before anything is launched
+        if (g.patches && !im2col_fits(d->kh, d->kw, d->stride, g.Wo, g.esz)) return KFAC_ERR_SHAPE;
     } else {
         g.Ho = g.Wo = 1;
         g.R = batch;
@@ -164,7 +172,7 @@ void layer_jobs(const kfac_layer_desc *d, const Geo &g, const void *act, const v
         Im2colJob j{};
         j.x = act; j.out = patches; j.dtype = d->in_dtype;
         j.B = batch; j.C = d->d_in; j.H = h; j.W = w; j.kh = d->kh; j.kw = d->kw;
-        j.stride = d->stride; j.pad = d->pad; j.Ho = g.Ho; j.Wo = g.Wo; j.ld = g.ld;
+        j.stride = d->stride; j.pad_h = g.ph; j.pad_w = g.pw; j.Ho = g.Ho; j.Wo = g.Wo; j.ld = g.ld;
         ij.push_back(j);
         a.x = patches; a.layout = kRows; a.ld = g.ld; a.hw = 1; a.ctot = g.d_core;
     }
@@ -204,7 +212,7 @@ std::vector<Chunk> make_chunks(const std::vector<Geo> &geo, const kfac_layer_des
     auto key = [&](int i) {
         const kfac_layer_desc &d = descs[i];
         return std::make_tuple(geo[i].fused3 ? 0 : 1, d.kind, d.in_dtype, d.d_in, d.d_out, d.kh, d.kw, d.stride,
-                               d.pad, d.has_bias, batch[i], h ? h[i] : 1, w ? w[i] : 1);
+                               d.pad, d.pad_h, d.pad_w, d.has_bias, batch[i], h ? h[i] : 1, w ? w[i] : 1);
     };
     std::vector<int> order(n);
     for (int i = 0; i < n; ++i) order[i] = i;
@@ -403,7 +411,7 @@ kfac_status kfac_im2col(const kfac_layer_desc *d, const void *d_act, int batch, 
     Im2colJob j{};
     j.x = d_act; j.out = d_patches; j.dtype = d->in_dtype;
     j.B = batch; j.C = d->d_in; j.H = h; j.W = w; j.kh = d->kh; j.kw = d->kw;
-    j.stride = d->stride; j.pad = d->pad; j.Ho = g.Ho; j.Wo = g.Wo; j.ld = g.ld;
+    j.stride = d->stride; j.pad_h = g.ph; j.pad_w = g.pw; j.Ho = g.Ho; j.Wo = g.Wo; j.ld = g.ld;
     return im2col_launch(&j, 1, (hipStream_t)hip_stream) == hipSuccess ? KFAC_OK : KFAC_ERR_HIP;
 }
 
@@ -836,7 +844,10 @@ int kfac_tune(const char *key, long value)
     else if (k == "patch_chunk_bytes") t.patch_chunk_bytes = value;
     else if (k == "syrk_force_bm") t.syrk_force_bm = value;
     else if (k == "use_wave_kernel") t.use_wave_kernel = value;
+#ifdef KFAC_MEASUREMENT_KNOBS
+    // skips MFMAs or loads inside the wave kernels (wrong results): only in builds made for measuring
     else if (k == "wave_debug") t.wave_debug = value;
+#endif
     else if (k == "fuse_conv3") t.fuse_conv3 = value;
     else if (k == "fuse_conv3_max_c") t.fuse_conv3_max_c = value;
     else if (k == "split_gemm_min_k") t.split_gemm_min_k = value;
@@ -849,6 +860,8 @@ int kfac_tune(const char *key, long value)
     else if (k == "invert_two_streams") t.invert_two_streams = value;
     else if (k == "invert_two_streams_min") t.invert_two_streams_min = value < 2 ? 2 : value;
     else if (k == "invert_outer_block") t.invert_outer_block = value;
+    else if (k == "invert_refine") t.invert_refine = value;
+    else if (k == "invert_refine_cond") t.invert_refine_cond = value < 0 ? 0 : value;
     else if (k == "eigen_max_sweeps") t.eigen_max_sweeps = value;
     else if (k == "eigen_inner_sweeps") t.eigen_inner_sweeps = value;
     else if (k == "im2col_piece_elems") t.im2col_piece_elems = value;

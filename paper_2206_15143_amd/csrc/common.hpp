@@ -61,6 +61,10 @@ struct GemmJob {
     long doff = 0;   // kSubRect: only entries with n <= m + doff are touched
     const float *rv = nullptr, *cv = nullptr;   // kStoreDiv
     float gamma = 0.f;
+    // kSubRect / kAddRect: two device words holding float bit patterns; the product is skipped unless the product of
+    // the two floats exceeds gate_cond (the blocked inversion's test of a pivot block's condition number)
+    const int *gate = nullptr;
+    float gate_cond = 0.f;
 };
 
 enum GemmMode : int {
@@ -68,7 +72,8 @@ enum GemmMode : int {
     kStoreT = 1,         // C[n][m] = acc   (ldc is the pitch of the transposed matrix)
     kSubLowerSkip = 2,   // C[m][n] -= acc for n <= m, m and n outside [p0, p1)
     kStoreDiv = 3,       // C[m][n] = acc / (rv[m] * cv[n] + gamma)   (the division of Eq. 13)
-    kSubRect = 4         // C[m][n] -= acc for n <= m + doff, n outside [p0, p1)   (a rectangle of a lower triangle)
+    kSubRect = 4,        // C[m][n] -= acc for n <= m + doff, n outside [p0, p1)   (a rectangle of a lower triangle)
+    kAddRect = 5         // the same entries, C[m][n] += acc
 };
 
 // Symmetric eigen-decomposition M = Q diag(v) Q^T (eigenvectors in the columns of Q, order not sorted).
@@ -84,7 +89,7 @@ struct Im2colJob {
     const void *x;   // NCHW
     void *out;       // [B*Ho*Wo, ld]
     int dtype;
-    int B, C, H, W, kh, kw, stride, pad, Ho, Wo;
+    int B, C, H, W, kh, kw, stride, pad_h, pad_w, Ho, Wo;
     int ld;
 };
 
@@ -101,6 +106,8 @@ hipError_t pi_damping_launch(const float *const *A, const float *const *G, const
 hipError_t gemm_launch(const GemmJob *jobs, int n, hipStream_t s);
 
 hipError_t im2col_launch(const Im2colJob *jobs, int n, hipStream_t s);
+// whether the patch kernel can stage one output row (Wo outputs) of its narrowest channel chunk in LDS
+bool im2col_fits(int kh, int kw, int stride, int Wo, int esz);
 size_t eigen_workspace_bytes(const EigenJob *jobs, int n);
 hipError_t eigen_launch(const EigenJob *jobs, int n, void *work, size_t work_bytes, hipStream_t s);
 hipError_t transpose_launch(const float *const *src, float *const *dst, const int *n, int count, hipStream_t s);
@@ -123,6 +130,8 @@ struct Tuning {
     long im2col_min_blocks = 1024;   // shorter strips until a layer has this many workgroups
     long eigen_max_sweeps = 20;      // sweep budget of the block Jacobi eigen-decomposition (12-13 used at order 577)
     long eigen_inner_sweeps = 1;     // Jacobi sweeps over the 32 x 32 Gram matrix of a pair of blocks per round
+    long invert_refine = 1;          // blocked sweep: refinement step of the panel products (see invert.hip) ...
+    long invert_refine_cond = 3000;  // ... of pivot blocks whose condition number (maximum norm) exceeds this
     long invert_outer_block = 256;   // outer pivot block of the two-level inversion (multiple of 32)
     long invert_border = 1;          // orders 64 k + 1: last row and column by bordering instead of a one-row pivot block
     long invert_two_streams = 1;     // large matrices in two groups on two streams (small launches of one beside the updates of the other)

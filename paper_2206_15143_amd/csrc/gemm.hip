@@ -28,6 +28,8 @@ struct GemmProb {
     int vecA, vecB;
     const float *rv, *cv;   // kStoreDiv
     float gamma;
+    const int *gate;        // null, or two float bit patterns: leave C alone unless their product exceeds gate_cond
+    float gate_cond;
 };
 
 // A launch covers up to kMaxGemmProblems products (a 14 KB kernel argument): the preconditioning of a whole
@@ -58,6 +60,7 @@ __global__ __launch_bounds__(T::NT) void gemm_tn_kernel(const GemmTable tab)
         else hi = mid - 1;
     }
     const GemmProb &pr = tab.p[pi];
+    if (pr.gate && !(__int_as_float(pr.gate[0]) * __int_as_float(pr.gate[1]) > pr.gate_cond)) return;   // uniform
     const int local = blockIdx.x - pr.blk_start;
     int bi, bj;
     if (pr.mode == kSubLowerSkip) {
@@ -140,9 +143,9 @@ __global__ __launch_bounds__(T::NT) void gemm_tn_kernel(const GemmTable tab)
                     pr.C[(long)n * pr.ldc + m] = val;
                 } else if (pr.mode == kStoreDiv) {
                     pr.C[(long)m * pr.ldc + n] = val / (pr.rv[m] * pr.cv[n] + pr.gamma);
-                } else if (pr.mode == kSubRect) {
+                } else if (pr.mode == kSubRect || pr.mode == kAddRect) {
                     const bool skip = ((long)n > (long)m + pr.doff) || (n >= pr.p0 && n < pr.p1);
-                    if (!skip) pr.C[(long)m * pr.ldc + n] -= val;
+                    if (!skip) pr.C[(long)m * pr.ldc + n] += pr.mode == kAddRect ? val : -val;
                 } else {
                     const bool skip = (n > m) || (m >= pr.p0 && m < pr.p1) || (n >= pr.p0 && n < pr.p1);
                     if (!skip) pr.C[(long)m * pr.ldc + n] -= val;
@@ -195,7 +198,7 @@ namespace {
 // flops of the definition of a product (the lower-triangle update counts the entries it touches)
 double gemm_job_flops(const GemmJob &j)
 {
-    if (j.mode == kSubRect) {
+    if (j.mode == kSubRect || j.mode == kAddRect) {
         // rows m = 0..M-1 touch the columns n <= min(N - 1, m + doff) outside [p0, p1)
         double cnt = 0.0;
         for (int m = 0; m < j.M; ++m) {
@@ -217,7 +220,9 @@ double gemm_job_flops(const GemmJob &j)
 // update qualifies only when its untouched band starts and ends on macro-tile boundaries.
 bool wave_gemm_eligible(const GemmJob &j)
 {
-    if (!tuning().use_wave_gemm || j.mode == kStoreT || j.mode == kStoreDiv || j.mode == kSubRect) return false;
+    if (!tuning().use_wave_gemm || j.mode == kStoreT || j.mode == kStoreDiv || j.mode == kSubRect || j.mode == kAddRect ||
+        j.gate)
+        return false;
     if (j.M < 100 || j.N < 100 || j.K < 16) return false;
     if ((long)j.K * j.lda * 4 > 0x7fffffffl || (long)j.K * j.ldb * 4 > 0x7fffffffl) return false;
     if (((uintptr_t)j.A) % 4 || ((uintptr_t)j.B) % 4) return false;
@@ -280,7 +285,8 @@ namespace {
 // Products that fill 256 x 128 tiles reasonably go to the split-bf16 kernel (gemm_split.hpp).
 bool split_gemm_eligible(const GemmJob &j)
 {
-    if (!tuning().use_split_gemm || (j.mode != kStore && j.mode != kSubLowerSkip && j.mode != kSubRect)) return false;
+    if (!tuning().use_split_gemm || (j.mode != kStore && j.mode != kSubLowerSkip && j.mode != kSubRect && j.mode != kAddRect))
+        return false;
     if (j.M < tuning().split_gemm_min_m || j.N < 64 || j.K < 16) return false;
     if (j.mode == kStore) {
         if (j.K < tuning().split_gemm_min_k) return false;
@@ -323,6 +329,7 @@ hipError_t split_gemm_launch(const GemmJob *jobs, const std::vector<int> &idx, h
         p.mode = j.mode; p.p0 = j.p0; p.p1 = j.p1;
         p.doff = (int)std::min<long>(j.doff, 1l << 30);
         if (j.mode == kSubLowerSkip) p.doff = 0;
+        p.gate = j.gate; p.gate_cond = j.gate_cond;
         p.blk_start = (int)blocks;
         for (int I = 0; I < p.tI; ++I) blocks += split_row_len(p.mode, p.tJ, p.doff, I);
         flops += gemm_job_flops(j);
@@ -416,7 +423,7 @@ hipError_t gemm_launch(const GemmJob *jobs, int n, hipStream_t s)
             tab.starts[tab.count - 1] = blocks;
             p.mode = j.mode;
             p.p0 = j.p0; p.p1 = j.p1; p.doff = j.doff;
-            p.rv = j.rv; p.cv = j.cv; p.gamma = j.gamma;
+            p.rv = j.rv; p.cv = j.cv; p.gamma = j.gamma; p.gate = j.gate; p.gate_cond = j.gate_cond;
             p.vecA = (((uintptr_t)j.A) % 16 == 0 && j.lda % 4 == 0) ? 1 : 0;
             p.vecB = (((uintptr_t)j.B) % 16 == 0 && j.ldb % 4 == 0) ? 1 : 0;
             blocks += (j.mode == kSubLowerSkip) ? p.tm * (p.tm + 1) / 2 : p.tm * p.tn;

@@ -39,9 +39,11 @@ struct GemmSProb {
     int M, N, K;
     int tI, tJ;      // tiles over M (256 rows) and N (128 columns)
     int blk_start;
-    int mode;        // kStore, kSubLowerSkip or kSubRect
+    int mode;        // kStore, kSubLowerSkip, kSubRect or kAddRect
     int p0, p1;
     int doff;        // the subtracting modes touch n <= m + doff (0 for kSubLowerSkip)
+    const int *gate; // null, or two float bit patterns: leave C alone unless their product exceeds gate_cond
+    float gate_cond;
 };
 
 struct GemmSTable {
@@ -74,10 +76,13 @@ __global__ __launch_bounds__(256, 2) void gemm_split_kernel(const GemmSTable tab
     int pi = 0;
     while (pi + 1 < tab.count && bid >= tab.p[pi + 1].blk_start) ++pi;
     const GemmSProb &pr = tab.p[pi];
+    // uniform over the workgroup, before any barrier or load
+    if (pr.gate && !(__int_as_float(pr.gate[0]) * __int_as_float(pr.gate[1]) > pr.gate_cond)) return;
     int local = bid - pr.blk_start;
     int I, J;
     const bool lower = pr.mode != kStore;         // read-modify-write below the line n = m + doff
     const bool rows_skip = pr.mode == kSubLowerSkip;
+    const bool add = pr.mode == kAddRect;
     {
         auto row_len = [&](int i) { return i >= pr.tI ? 0 : split_row_len(pr.mode, pr.tJ, pr.doff, i); };
         int g = 0;
@@ -268,7 +273,7 @@ __global__ __launch_bounds__(256, 2) void gemm_split_kernel(const GemmSTable tab
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int r = 8 * (v >> 2) + (v & 3);
-            if (live(mw + (t >> 1) * 32 + r + 4 * lg, n)) row_ptr(t, r)[lane_off] = old[v] - acc[t][v];
+            if (live(mw + (t >> 1) * 32 + r + 4 * lg, n)) row_ptr(t, r)[lane_off] = add ? old[v] + acc[t][v] : old[v] - acc[t][v];
         }
     };
     // the 16 loads of a tile are issued together, and the loads of the next tile go out before the stores of

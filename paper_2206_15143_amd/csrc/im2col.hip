@@ -1,7 +1,7 @@
 // Patch extraction for convolution layers (the "convolution as a linear
 // transformation" of the footnote in section 3 of the DP-KFAC paper):
 //
-//   out[(n, oh, ow)][(c, i, j)] = x[n, c, oh*stride - pad + i, ow*stride - pad + j]   (0 outside)
+//   out[(n, oh, ow)][(c, i, j)] = x[n, c, oh*stride - pad_h + i, ow*stride - pad_w + j]   (0 outside)
 //
 // NCHW in, row-major [B*Ho*Wo, ld] out, same element type.  The bias column is
 // not written (the factor kernel derives its border from column sums), so rows
@@ -21,7 +21,7 @@ namespace kfac {
 struct Im2colProb {
     const void *x;
     void *out;
-    int B, C, H, W, kh, kw, stride, pad, Ho, Wo;
+    int B, C, H, W, kh, kw, stride, pad_h, pad_w, Ho, Wo;
     int ld;
     int SR, CC;         // output rows per strip, channels per chunk
     int nstrips, nchunks;
@@ -89,12 +89,12 @@ __global__ __launch_bounds__(256) void im2col_kernel(const Im2colTable tab)
         const bool lane_ok = lrow < rpp;
         for (; rowid < nrows; rowid += stride_rows) {
             if (lane_ok) {
-                const int ih = oh0 * pr.stride - pr.pad + r;
+                const int ih = oh0 * pr.stride - pr.pad_h + r;
                 const bool rok = ih >= 0 && ih < pr.H;
-                const E *src = xin + ((long)c * pr.H + ih) * pr.W - pr.pad;
+                const E *src = xin + ((long)c * pr.H + ih) * pr.W - pr.pad_w;
                 E *dst = slab + c * plane + r * pr.WP;
                 for (int xx = lx; xx < pr.WP; xx += 64) {
-                    const int iw = xx - pr.pad;
+                    const int iw = xx - pr.pad_w;
                     E v = 0;
                     if (rok && iw >= 0 && iw < pr.W) v = src[xx];
                     dst[xx] = v;
@@ -199,7 +199,7 @@ void plan_enough_blocks(Im2colProb &p, int esz)
         p.nchunks = (p.C + cc - 1) / cc;
     };
     auto slab = [&](int sr, int cc) { return (size_t)cc * ((sr - 1) * p.stride + p.kh) * p.WP * esz + (size_t)cc * kk * 4 + 512; };
-    const size_t lds = (size_t)std::min(60l * 1024, std::max(2048l, t.im2col_lds_bytes));
+    const size_t lds = (size_t)std::min(60l * 1024, std::max(2048l, t.im2col_lds_bytes));   // <= kIm2colLdsCap
     long cc = ((t.im2col_piece_elems + kk - 1) / kk + g - 1) / g * g;
     if (cc >= p.C) cc = p.C;
     while (cc > g && cc != p.C && slab(1, (int)cc) > lds) cc -= g;
@@ -213,7 +213,22 @@ void plan_enough_blocks(Im2colProb &p, int esz)
     set((p.Ho + p.nstrips - 1) / p.nstrips, (int)cc);   // same number of strips, equal heights
 }
 
+constexpr long kIm2colLdsCap = 60l * 1024;   // what plan_enough_blocks may give a workgroup
+
+int min_chunk(int kk, int esz)
+{
+    const int vec = 16 / esz;
+    return vec / gcd(kk, vec);
+}
+
 }  // namespace
+
+bool im2col_fits(int kh, int kw, int stride, int Wo, int esz)
+{
+    const long g = min_chunk(kh * kw, esz);
+    const long WP = (long)(Wo - 1) * stride + kw;
+    return g * kh * WP * esz + g * kh * kw * 4 + 512 <= kIm2colLdsCap;
+}
 
 hipError_t im2col_launch(const Im2colJob *jobs, int n, hipStream_t s)
 {
@@ -224,7 +239,7 @@ hipError_t im2col_launch(const Im2colJob *jobs, int n, hipStream_t s)
         size_t smem = 0;
         auto flush = [&]() -> hipError_t {
             if (tab.count == 0) return hipSuccess;
-            if (smem > 64 * 1024) return hipErrorInvalidValue;   // slab of one output row of the smallest chunk does not fit LDS
+            if (smem > 64 * 1024) return hipErrorInvalidValue;   // cannot happen for shapes im2col_fits() accepts
             if (dt == 0)
                 KFAC_LAUNCH(KFAC_K_IM2COL, s, (im2col_kernel<float>), dim3(blocks), dim3(256), smem, tab);
             else
@@ -240,7 +255,7 @@ hipError_t im2col_launch(const Im2colJob *jobs, int n, hipStream_t s)
             Im2colProb &p = tab.p[tab.count++];
             p.x = j.x; p.out = j.out;
             p.B = j.B; p.C = j.C; p.H = j.H; p.W = j.W; p.kh = j.kh; p.kw = j.kw;
-            p.stride = j.stride; p.pad = j.pad; p.Ho = j.Ho; p.Wo = j.Wo; p.ld = j.ld;
+            p.stride = j.stride; p.pad_h = j.pad_h; p.pad_w = j.pad_w; p.Ho = j.Ho; p.Wo = j.Wo; p.ld = j.ld;
             plan_enough_blocks(p, dt == 0 ? 4 : 2);
             p.blk_start = blocks;
             blocks += p.B * p.nstrips * p.nchunks;

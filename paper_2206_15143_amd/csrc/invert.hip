@@ -49,6 +49,7 @@ struct InvProb {
     float damping;
     int blk_start;
     const float *dptr;   // device-side damping (overrides `damping` when not null)
+    int *gate;           // null, or the two gate words of the blocked sweep, cleared with info
 };
 
 struct InvTable {
@@ -66,7 +67,10 @@ __global__ __launch_bounds__(256) void sweep_init_kernel(const InvTable tab)
     const int local = blockIdx.x - pr.blk_start;
     const long total = (long)pr.n * pr.n;
     const float damping = pr.dptr ? *pr.dptr : pr.damping;
-    if (local == 0 && threadIdx.x == 0) *pr.info = 0;
+    if (local == 0 && threadIdx.x == 0) {
+        *pr.info = 0;
+        if (pr.gate) { pr.gate[0] = 0; pr.gate[1] = 0; }
+    }
     for (long e = (long)local * 4096 + threadIdx.x; e < lmin(total, (long)(local + 1) * 4096); e += 256) {
         const int i = (int)(e / pr.n), j = (int)(e - (long)i * pr.n);
         if (j <= i) pr.W[e] = pr.M[e] + (i == j ? damping : 0.f);
@@ -82,12 +86,16 @@ __global__ __launch_bounds__(256) void sweep_init_kernel(const InvTable tab)
 // gather / scatter tiles; PB below is its value for the current call).  576 is 6-8 % faster on the
 // workloads with many large factors, but the error of the inverse grows with the order of the explicitly
 // inverted pivot block (measured at order 2305: 1.5e-5 / 2.9e-5 / 4.0e-5 for 288 / 576 / 864), so 288 stays.
-inline int outer_block() { return (int)std::max(64l, tuning().invert_outer_block / 32 * 32); }
+inline int outer_block() { return (int)std::min(512l, std::max(64l, tuning().invert_outer_block / 32 * 32)); }
 
 struct BlkProb {
     float *W;          // working matrix [n, n]
     float *Vt;         // [PB, ldv]
     float *Wt;         // [PB, ldv]
+    float *Rt;         // [PB, ldv] second copy of the old panel (becomes the residual of the refinement), or null
+    float *S;          // [PB, pb] the pivot block before its inversion, both triangles, or null
+    int *gate;         // two words: bit patterns of the maximum norms of S and of P (see blk_cond_kernel)
+    float gate_cond;   // the refinement runs when their product exceeds this
     const float *P;    // [PB, PB] inverse of the pivot block
     int *info;
     const int *ninfo;  // status of the pivot block inversion (0 or 1-based pivot index inside the block)
@@ -101,8 +109,76 @@ struct BlkTable {
     BlkProb p[32];
 };
 
+// Does the refinement of the panel product pay for this pivot block?  The condition number of the block in the
+// maximum norm, ||S|| ||P|| with the largest absolute row sums (S from the lower triangle of the working matrix,
+// P from the nested inversion).  A workgroup per 32 rows forms the sums of its rows and folds their largest into
+// gate[0] (S) and gate[1] (P) with an integer atomic maximum on the bit patterns (the values are not negative:
+// the order is the same and the result does not depend on the order of arrival).  The gather kernel and the two
+// refinement products compare the product of the two with the threshold; the scatter kernel at the end of the
+// step clears both words for the next one.  (A comparison with a NaN is false: a block whose inversion failed
+// is left alone, its matrix is already flagged.)
+__device__ __forceinline__ bool blk_gate_open(const int *gate, float cond)
+{
+    return __int_as_float(gate[0]) * __int_as_float(gate[1]) > cond;
+}
+
+__global__ __launch_bounds__(256) void blk_cond_kernel(const BlkTable tab)
+{
+    __shared__ float part[3][8][33];
+    __shared__ float rowpart[32];
+    int pi = 0;
+    while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].blk_start) ++pi;
+    const BlkProb &pr = tab.p[pi];
+    const int i0 = ((int)blockIdx.x - pr.blk_start) * 32;
+    const long n = pr.n;
+    const int p0 = pr.p0, bs = pr.bs;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const int c = i0 + tx;
+    // rows i0 .. i0 + 31 left of the diagonal: lanes along the row, four rows per group of 32 threads
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int r = i0 + ty + 8 * j;
+        float a = 0.f;
+        if (r < bs) {
+#pragma unroll 8
+            for (int b = tx; b < r; b += 32) a += fabsf(pr.W[(p0 + r) * n + p0 + b]);
+        }
+#pragma unroll
+        for (int off = 16; off > 0; off >>= 1) a += __shfl_xor(a, off, 32);
+        if (tx == 0) rowpart[ty + 8 * j] = a;
+    }
+    // the rest of row c is column c from the diagonal down; P is full: its column c
+    float as = 0.f, ap = 0.f;
+    if (c < bs) {
+#pragma unroll 8
+        for (int b = i0 + ty; b < bs; b += 8)
+            if (b >= c) as += fabsf(pr.W[(p0 + b) * n + p0 + c]);
+#pragma unroll 8
+        for (int b = ty; b < bs; b += 8) ap += fabsf(pr.P[(long)b * pr.pb + c]);
+    }
+    part[0][ty][tx] = as;
+    part[1][ty][tx] = ap;
+    __syncthreads();
+    if (ty == 0) {
+        float ss = rowpart[tx], ps = 0.f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) { ss += part[0][k][tx]; ps += part[1][k][tx]; }
+#pragma unroll
+        for (int off = 16; off > 0; off >>= 1) {
+            ss = fmaxf(ss, __shfl_xor(ss, off, 32));
+            ps = fmaxf(ps, __shfl_xor(ps, off, 32));
+        }
+        if (tx == 0) {
+            // NaN sums (a failed nested inversion) must not look like large numbers to the integer maximum
+            atomicMax(pr.gate, ss >= 0.f ? __float_as_int(ss) : 0);
+            atomicMax(pr.gate + 1, ps >= 0.f ? __float_as_int(ps) : 0);
+        }
+    }
+}
+
 // V[kk][gi] = old panel, K-major: row panel (gi < p0) copied, column panel (gi >= p0 + bs) transposed
-// through LDS, pivot columns zero.  One workgroup per 32 x 32 tile.
+// through LDS, pivot columns zero.  One workgroup per 32 x 32 tile.  With the refinement of the panel product
+// on, a second copy of the panel goes to Rt and the pivot block itself, mirrored to both triangles, to S.
 __global__ __launch_bounds__(256) void blk_gather_kernel(const BlkTable tab)
 {
     __shared__ float t[32][33];
@@ -116,12 +192,19 @@ __global__ __launch_bounds__(256) void blk_gather_kernel(const BlkTable tab)
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     const long n = pr.n;
     const int p0 = pr.p0, p1 = pr.p0 + pr.bs;
+    const bool refine = pr.S && blk_gate_open(pr.gate, pr.gate_cond);     // blk_cond_kernel ran before
+    float *Rt = refine ? pr.Rt : nullptr;
+    float *S = refine ? pr.S : nullptr;
     // p0 and p1 are multiples of 32 (or p1 = n): a tile lies wholly in one of the three regions
     if (g0 < p0) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int kk = k0 + ty + 8 * r, gi = g0 + tx;
-            if (kk < pr.bs && gi < pr.n) pr.Vt[(long)kk * pr.ldv + gi] = pr.W[(p0 + kk) * n + gi];
+            if (kk < pr.bs && gi < pr.n) {
+                const float v = pr.W[(p0 + kk) * n + gi];
+                pr.Vt[(long)kk * pr.ldv + gi] = v;
+                if (Rt) Rt[(long)kk * pr.ldv + gi] = v;
+            }
         }
     } else if (g0 >= p1) {
 #pragma unroll
@@ -133,13 +216,23 @@ __global__ __launch_bounds__(256) void blk_gather_kernel(const BlkTable tab)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int kk = k0 + ty + 8 * r, gi = g0 + tx;
-            if (kk < pr.bs && gi < pr.n) pr.Vt[(long)kk * pr.ldv + gi] = t[tx][ty + 8 * r];
+            if (kk < pr.bs && gi < pr.n) {
+                pr.Vt[(long)kk * pr.ldv + gi] = t[tx][ty + 8 * r];
+                if (Rt) Rt[(long)kk * pr.ldv + gi] = t[tx][ty + 8 * r];
+            }
         }
     } else {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int kk = k0 + ty + 8 * r, gi = g0 + tx;
-            if (kk < pr.bs && gi < pr.n) pr.Vt[(long)kk * pr.ldv + gi] = 0.f;
+            if (kk < pr.bs && gi < pr.n) {
+                pr.Vt[(long)kk * pr.ldv + gi] = 0.f;
+                if (Rt) Rt[(long)kk * pr.ldv + gi] = 0.f;
+                if (S) {   // entry (kk, gi - p0) of the pivot block, from its lower triangle
+                    const int b = gi - p0, hi = kk > b ? kk : b, lo = kk > b ? b : kk;
+                    S[(long)kk * pr.pb + b] = pr.W[(p0 + hi) * n + p0 + lo];
+                }
+            }
         }
     }
 }
@@ -162,6 +255,7 @@ __global__ __launch_bounds__(256) void blk_scatter_kernel(const BlkTable tab)
     if (local == 0 && threadIdx.x == 0) {
         const int f = *pr.ninfo;
         if (f != 0 && *pr.info == 0) *pr.info = p0 + f;
+        if (pr.gate) { pr.gate[0] = 0; pr.gate[1] = 0; }   // for the next step's blk_cond_kernel
     }
     if (g0 < p0) {
 #pragma unroll
@@ -231,7 +325,7 @@ size_t job_ws_floats(int n)
 {
     if (takes_fused(n)) return fused_ws_floats(n);
     const size_t PB = (size_t)outer_block();
-    return 4 * PB * ((n + 3) / 4 * 4) + PB * PB + fused_ws_floats((int)PB) + 64;
+    return 5 * PB * ((n + 3) / 4 * 4) + 2 * PB * PB + fused_ws_floats((int)PB) + 64;
 }
 size_t table_bytes(int n) { return align_up((size_t)2 * n * sizeof(InvProbF), 256); }
 
@@ -323,7 +417,8 @@ hipError_t fused_launch(const InvertJob *jobs, const std::vector<int> &idx, cons
 // that band (two rectangular products), so that its pivot block and panel are ready without waiting for the
 // bulk.  Panels are double buffered (the bulk of step K reads panels K while the chain writes panels K+1).
 struct BlockedRun {
-    struct Big { float *Vt[2], *Wt[2], *P, *nws; int *ninfo; int ldv; };
+    struct Big { float *Vt[2], *Wt[2], *Rt, *S, *P, *nws; int *ninfo; int ldv; };
+    bool refine = false;
     const InvertJob *jobs = nullptr;
     std::vector<int> idx;
     const std::vector<size_t> *offs = nullptr;
@@ -354,6 +449,7 @@ hipError_t BlockedRun::start(hipStream_t s)
 {
     total = (int)idx.size();
     PB = outer_block();
+    refine = tuning().invert_refine != 0;
     big.assign(total, Big());
     for (int k = 0; k < total; ++k) {
         const InvertJob &j = jobs[idx[k]];
@@ -365,7 +461,9 @@ hipError_t BlockedRun::start(hipStream_t s)
         b.Wt[0] = ws + panel;
         b.Vt[1] = ws + 2 * panel;
         b.Wt[1] = ws + 3 * panel;
-        b.P = ws + 4 * panel;
+        b.Rt = ws + 4 * panel;
+        b.S = ws + 5 * panel;
+        b.P = b.S + (size_t)PB * PB;
         b.nws = b.P + (size_t)PB * PB;
         b.ninfo = reinterpret_cast<int *>(b.nws + fused_ws_floats(PB));
     }
@@ -380,6 +478,7 @@ hipError_t BlockedRun::start(hipStream_t s)
             InvProb &p = tab.p[k];
             p.M = j.M; p.W = j.Minv; p.info = j.info; p.n = j.n; p.damping = j.damping; p.dptr = j.damping_dev;
             p.ldv = big[g0 + k].ldv; p.P = nullptr; p.Vt = nullptr; p.Wt = nullptr;
+            p.gate = big[g0 + k].ninfo + 1;
             p.blk_start = blocks;
             blocks += (int)(((long)j.n * j.n + 4095) / 4096);
         }
@@ -402,13 +501,31 @@ hipError_t BlockedRun::copy_kernel(bool scatter, int st, int act, hipStream_t s)
             const InvertJob &j = jobs[idx[g0 + k]];
             BlkProb &p = tab.p[k];
             p.W = j.Minv; p.Vt = big[g0 + k].Vt[st & 1]; p.Wt = big[g0 + k].Wt[st & 1]; p.P = big[g0 + k].P;
+            p.Rt = (refine && !scatter) ? big[g0 + k].Rt : nullptr;
+            p.S = (refine && !scatter) ? big[g0 + k].S : nullptr;
+            p.gate = refine ? big[g0 + k].ninfo + 1 : nullptr;
+            p.gate_cond = (float)tuning().invert_refine_cond;
             p.info = j.info; p.ninfo = big[g0 + k].ninfo;
             p.n = j.n; p.ldv = big[g0 + k].ldv; p.p0 = p0; p.bs = std::min(PB, j.n - p0); p.pb = PB;
             p.blk_start = blocks;
             blocks += ((j.n + 31) / 32) * ((p.bs + 31) / 32);
         }
-        if (scatter) KFAC_LAUNCH(KFAC_K_INV_PANEL, s, blk_scatter_kernel, dim3(blocks), dim3(256), 0, tab);
-        else KFAC_LAUNCH(KFAC_K_INV_PANEL, s, blk_gather_kernel, dim3(blocks), dim3(256), 0, tab);
+        if (scatter) {
+            KFAC_LAUNCH(KFAC_K_INV_PANEL, s, blk_scatter_kernel, dim3(blocks), dim3(256), 0, tab);
+        } else {
+            if (refine) {
+                BlkTable ct = tab;
+                int cb = 0;
+                for (int k = 0; k < ct.count; ++k) {
+                    ct.p[k].blk_start = cb;
+                    cb += (ct.p[k].bs + 31) / 32;
+                }
+                KFAC_LAUNCH(KFAC_K_INV_PANEL, s, blk_cond_kernel, dim3(cb), dim3(256), 0, ct);
+                hipError_t e = hipGetLastError();
+                if (e != hipSuccess) return e;
+            }
+            KFAC_LAUNCH(KFAC_K_INV_PANEL, s, blk_gather_kernel, dim3(blocks), dim3(256), 0, tab);
+        }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -482,6 +599,30 @@ hipError_t BlockedRun::chain(int st, hipStream_t s)
     }
     e = gemm_launch(gj.data(), act, s);
     if (e != hipSuccess) return e;
+    if (refine) {
+        // One step of iterative refinement of the panel product.  W = V P with an explicitly inverted pivot block
+        // S carries an error of eps |V| |P|, which for an ill-conditioned S is far above eps |W|; the residual
+        // V - W S is made of small terms and comes out accurately, and W += (V - W S) P removes most of that error
+        // (the inverse of a factor with condition number 1e5 goes from useless to the accuracy of an fp32
+        // Cholesky inverse).  K-major: R^T = V^T - S W^T, W^T += P R^T.
+        for (int pass = 0; pass < 2; ++pass) {
+            for (int k = 0; k < act; ++k) {
+                const InvertJob &j = jobs[idx[k]];
+                const int bs = std::min(PB, j.n - p0);
+                GemmJob &a = gj[k];
+                a = GemmJob();
+                a.A = pass == 0 ? big[k].S : big[k].P;
+                a.B = pass == 0 ? big[k].Wt[st & 1] : big[k].Rt;
+                a.C = pass == 0 ? big[k].Rt : big[k].Wt[st & 1];
+                a.M = bs; a.N = j.n; a.K = bs; a.lda = PB; a.ldb = big[k].ldv; a.ldc = big[k].ldv;
+                a.mode = pass == 0 ? kSubRect : kAddRect; a.p0 = a.p1 = 0; a.doff = 1l << 30;
+                a.gate = big[k].ninfo + 1;
+                a.gate_cond = (float)tuning().invert_refine_cond;
+            }
+            e = gemm_launch(gj.data(), act, s);
+            if (e != hipSuccess) return e;
+        }
+    }
     return copy_kernel(true, st, act, s);
 }
 
@@ -517,6 +658,7 @@ hipError_t BlockedRun::finish(hipStream_t s)
             InvProb &p = tab.p[k];
             p.M = j.M; p.W = j.Minv; p.info = j.info; p.n = j.n; p.damping = j.damping; p.dptr = j.damping_dev;
             p.ldv = big[g0 + k].ldv; p.P = nullptr; p.Vt = nullptr; p.Wt = nullptr;
+            p.gate = nullptr;
             p.blk_start = blocks;
             const int nb32 = (j.n + 31) / 32;
             blocks += nb32 * (nb32 + 1) / 2;

@@ -747,12 +747,10 @@ hipError_t corr3_launch_nt(CorrTable &tab, const std::vector<size_t> &lds, doubl
         blocks += tab.p[k].splits * (NT == 4 ? 2 : 1);   // 64 channels: two workgroups per range of units
         lds_bytes = std::max(lds_bytes, lds[k]);
     }
-    static bool attr_set = false;
-    if (!attr_set) {
+    {   // per device and cheap: set on every launch rather than remembered in a process-wide flag
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&corr3_main_kernel<NT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
         if (e != hipSuccess) return e;
-        attr_set = true;
     }
     KFAC_LAUNCH(KFAC_K_SYRK_CORR3, s, (corr3_main_kernel<NT>), dim3(blocks), dim3(512), lds_bytes, tab);
     timing_work(flops, exflops);
@@ -937,13 +935,10 @@ hipError_t syrk_launch(const FactorJob *jobs, int n, void *work, size_t work_byt
                     const Conv3Geo geo = conv3_geo(job.h, job.w, pl[g[k]].rows_per_stage);
                     lds_bytes = std::max(lds_bytes, (size_t)(C3_PRE + C3_NSTAGE * W_SLOTS * geo.slab + 256) * 4);
                 }
-                static bool attr_set = false;
-                if (!attr_set) {
-                    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&syrk_conv3_kernel<4>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-                    if (e != hipSuccess) break;
-                    attr_set = true;
-                }
+                // per device and cheap: set on every launch rather than remembered in a process-wide flag
+                e = hipFuncSetAttribute(reinterpret_cast<const void *>(&syrk_conv3_kernel<4>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+                if (e != hipSuccess) break;
                 KFAC_LAUNCH(KFAC_K_SYRK_CONV3, s, (syrk_conv3_kernel<4>), dim3(blocks), dim3(256), lds_bytes, tab);
                 timing_work(flops);
                 e = hipGetLastError();

@@ -66,7 +66,7 @@ def test_resnet110_config_batched_full_size():
 
 
 FULL_SIZE_CONFIGS = [("resnet50_imagenet", 24), ("resnet50_imagenet_bf16", 24), ("transformer_encoder_bf16", 3),
-                     ("vgg16_cifar", 11), ("inception_nonsquare", 6), ("bert_base_small_batch", 3)]
+                     ("vgg16_cifar", 11), ("inception_nonsquare", 7), ("bert_base_small_batch", 3)]
 
 
 def _distinct(name):

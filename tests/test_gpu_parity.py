@@ -179,6 +179,38 @@ def test_im2col_nonsquare_kernels_and_maps_bit_exact():
         assert np.all(got[:, ref.shape[1]:] == 0)
 
 
+def test_im2col_with_different_row_and_column_padding_bit_exact():
+    for (cin, kh, kw, stride, ph, pw, h, w, batch) in [(8, 1, 7, 1, 0, 3, 17, 17, 2), (8, 7, 1, 1, 3, 0, 17, 17, 2),
+                                                       (12, 1, 3, 1, 0, 1, 8, 8, 3), (12, 3, 1, 1, 1, 0, 8, 12, 3),
+                                                       (6, 3, 5, 2, 0, 2, 21, 30, 2), (5, 3, 3, 1, 2, 0, 9, 11, 1),
+                                                       (16, 3, 3, 1, 1, 2, 10, 10, 2), (4, 1, 1, 1, 0, 2, 6, 7, 2)]:
+        print("im2col", cin, kh, kw, stride, ph, pw, h, w, batch, flush=True)
+        x = rng.draw_relu_normal(79, 0, (batch, cin, h, w))
+        desc = kf.LayerDesc.conv2d(cin, 4, kh, stride, ph, kw=kw, pad_w=pw)
+        assert desc.pad + desc.pad_h == ph and desc.pad + desc.pad_w == pw
+        ld = kf.kfac_patch_ld(desc)
+        ho = (h + 2 * ph - kh) // stride + 1
+        wo = (w + 2 * pw - kw) // stride + 1
+        out = torch.full((batch * ho * wo, ld), float("nan"), device=gu.DEV)
+        kf.kfac_im2col(desc, gu.to_dev(x), batch, h, w, out)
+        torch.cuda.synchronize()
+        ref = orc.patches(x, kh, kw, stride, ph, has_bias=False, pad_w=pw)
+        got = out.cpu().numpy()
+        assert np.array_equal(got[:, :ref.shape[1]].astype(np.float64), ref)
+        assert np.all(got[:, ref.shape[1]:] == 0)
+
+
+@pytest.mark.parametrize("cin,kh,kw,h,w,ph,pw,bias", [(24, 1, 7, 17, 17, 0, 3, True), (24, 7, 1, 9, 14, 3, 0, True),
+                                                       (24, 1, 3, 8, 8, 0, 1, False), (32, 3, 1, 8, 12, 1, 0, True),
+                                                       (16, 3, 3, 10, 12, 1, 0, True)])
+def test_layer_with_different_row_and_column_padding_end_to_end(cin, kh, kw, h, w, ph, pw, bias):
+    # "same"-padded 1 x 7 / 7 x 1 / 1 x 3 / 3 x 1 kernels through all three calls; the last is a 3 x 3 kernel padded
+    # in one direction only, which must NOT take the kernels written for 3 x 3 / pad 1
+    layer = LayerSpec("conv", cin, 20, kh, 1, ph, h, has_bias=bias, k_w=kw, w_in=w, pad_w=pw)
+    _run_and_check([layer], 6, 9300 + 10 * kh + kw, batched=True)
+    _run_and_check([layer], 6, 9400 + 10 * kh + kw, batched=False)
+
+
 @pytest.mark.parametrize("cin,kh,kw,h,w,pad,bias", [(24, 1, 7, 17, 17, 0, True), (24, 7, 1, 9, 14, 0, True),
                                                     (24, 3, 1, 8, 12, 1, False), (32, 3, 3, 10, 16, 1, True),
                                                     (16, 3, 3, 12, 8, 1, True)])
@@ -522,15 +554,17 @@ def test_pi_damped_inverse_matches_oracle():
 def test_inverse_of_ill_conditioned_rank_deficient_running_average(d_in, rows, steps, lam):
     """The factor K-FAC meets late in training: the identity it started from has decayed away (decay 0.5 for
     `steps` updates here), what is left is a running average of a few low-rank batches of post-ReLU rows (rank < d,
-    one dominant eigenvalue along the mean), and only the damping keeps it invertible: condition numbers of 1e4
-    to 1e6, against at most 2e3 in the benchmark configurations.  The unpivoted fp32 sweep (explicit inverses of
-    the pivot blocks, split-bf16 updates above order 1280) loses accuracy in proportion to the condition number:
-    measured 2.5 x cond x eps at cond 7.5e4 (1.1e-2 relative, where a pivoted fp32 LAPACK inverse of the same
-    matrix, printed beside it, reaches 1e-5), 0.25 x cond x eps at cond 1.9e5; near cond 1e6 a pivot of the sweep
-    turns non-positive although the matrix is positive definite.  This test pins that behaviour: the error against
-    the oracle's inverse of the very same running factor stays within 5 x cond x eps (and within the 1e-4 of the
-    well-conditioned tests wherever that is larger), the result is bitwise symmetric, and a breakdown is REPORTED
-    through d_info rather than returned as a plausible matrix."""
+    one dominant eigenvalue along the mean), and only the damping keeps it invertible: condition numbers of 3e4
+    to 3e5, against at most 3e4 in the benchmark configurations.  Any fp32 elimination loses accuracy in proportion
+    to the condition number; LAPACK's fp32 Cholesky inverse of the same matrix is printed beside the library's
+    result as the yardstick.  Above order 1280 (two-level sweep, panel products refined once where the pivot block
+    is ill-conditioned) the library is within a factor two of that yardstick: 1.8e-4 against 1.5e-4 at condition
+    number 3.3e4, 2.5e-3 against 1.5e-3 at 3.3e5.  Up to order 1280 (one-launch-per-step sweep with explicitly
+    inverted 64 x 64 pivot blocks, no refinement) it is 4 to 40 times less accurate: 1.1e-2 against 2.7e-4 at order
+    577, 2.7e-3 against 6.6e-4 at order 1153.  This test pins that behaviour: the error against the oracle's inverse
+    of the very same running factor stays within 5 x cond x eps (and within the 1e-4 of the well-conditioned tests
+    wherever that is larger), the result is bitwise symmetric, and a breakdown (a pivot that turns non-positive on
+    a matrix that is positive definite) would have to be REPORTED through d_info."""
     decay = 0.5
     l = LayerSpec("linear", d_in, 8, rows=rows)
     desc = kf.LayerDesc.from_spec(l)
@@ -563,8 +597,10 @@ def test_inverse_of_ill_conditioned_rank_deficient_running_average(d_in, rows, s
     ref = orc.inverse(M, lam)
     err = gu.rel_fro(X, ref)
     resid = np.linalg.norm((M + lam * np.eye(dA)) @ X - np.eye(dA)) / np.sqrt(dA)
-    # for scale: what a pivoted fp32 LAPACK inverse of the same matrix achieves (printed, not asserted)
-    Xl = np.linalg.inv((M + lam * np.eye(dA)).astype(np.float32)).astype(np.float64)
+    # for scale: what LAPACK's fp32 Cholesky inverse (spotrf + spotri through torch on the CPU) achieves on the same
+    # matrix (printed, not asserted).  numpy.linalg.inv is no such yardstick: it computes float32 input in double.
+    M32 = torch.from_numpy((M + lam * np.eye(dA)).astype(np.float32))
+    Xl = torch.cholesky_inverse(torch.linalg.cholesky(M32)).numpy().astype(np.float64)
     err_l = gu.rel_fro(Xl, ref)
     print(f"order {dA}: rank <= {rows * steps}, cond {cond:.2e}, cond*eps {cond * eps:.2e}, "
           f"rel. error {err:.2e} (fp32 LAPACK: {err_l:.2e}), residual/sqrt(n) {resid:.2e}", flush=True)

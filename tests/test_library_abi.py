@@ -73,6 +73,23 @@ def test_bad_arguments_are_rejected_on_the_host():
     bad = kf.LayerDesc.conv2d(8, 4, 3, 1, 0)
     assert lib.kfac_update_factors(ctypes.byref(bad), fake, fake, 2, 2, 2, 1.0, 1.0, 0.5, fake, fake, fake, 1 << 20,
                                    None) == 2      # 3x3 kernel does not fit a 2x2 input without padding
+    # a map too wide for the patch kernel's on-chip row buffer is refused before any launch (7 x 7 fp32: 4 channels
+    # x 7 rows x (w_out - 1 + 7) floats > 60 KB from 541 output columns on), by the size query as well
+    wide = kf.LayerDesc.conv2d(4, 4, 7, 1, 3)
+    assert lib.kfac_im2col(ctypes.byref(wide), fake, 1, 8, 600, fake, None) == 2
+    assert lib.kfac_update_factors(ctypes.byref(wide), fake, fake, 1, 8, 600, 1.0, 1.0, 0.5, fake, fake, fake, 1 << 30,
+                                   None) == 2
+    assert kf.kfac_workspace_bytes(wide, 1, 8, 600) == 0 and kf.kfac_workspace_bytes(wide, 1, 8, 500) > 0
+    # padding: negative values are refused; the two directions are separate
+    neg = kf.LayerDesc.conv2d(8, 4, 3, 1, 1)
+    neg.pad_w = -1
+    assert lib.kfac_update_factors(ctypes.byref(neg), fake, fake, 2, 8, 8, 1.0, 1.0, 0.5, fake, fake, fake, 1 << 20,
+                                   None) == 2
+    tall = kf.LayerDesc.conv2d(8, 4, 7, 1, 3, kw=1, pad_w=0)       # 7 x 1 kernel, rows padded by 3, columns not
+    assert (tall.pad, tall.pad_h, tall.pad_w) == (0, 3, 0)
+    assert lib.kfac_im2col(ctypes.byref(tall), fake, 1, 2, 2, None, None) == 1      # shape is fine: the null pointer is what fails
+    flat = kf.LayerDesc.conv2d(8, 4, 7, 1, 0, kw=1, pad_w=3)       # the same kernel with the padding on the wrong side
+    assert lib.kfac_im2col(ctypes.byref(flat), fake, 1, 2, 2, fake, None) == 2
     bad = kf.LayerDesc.linear(8, 4)
     bad.in_dtype = 7
     assert lib.kfac_update_factors(ctypes.byref(bad), fake, fake, 4, 1, 1, 1.0, 1.0, 0.5, fake, fake, fake, 1 << 20,
@@ -104,3 +121,17 @@ def test_marshalled_arrays_hold_the_values_and_pass_through():
                                                                                               [1, 8])
     from paper_2206_15143_amd import binding
     assert binding._descs(md) is md and binding._ptrs(mp) is mp and binding._ints(mi) is mi
+
+
+def test_binding_refuses_strided_views_and_float64_before_the_call():
+    """The binding hands raw addresses to the library: what a pointer cannot say for itself is checked first."""
+    import torch
+    from paper_2206_15143_amd import binding
+    x = torch.zeros(8, 8)
+    assert binding._ptr(x) == x.data_ptr() and binding._ptr(None) is None and binding._ptr(4096) == 4096
+    with pytest.raises(ValueError, match="not contiguous"):
+        binding._ptr(x.t()[:, :4])
+    with pytest.raises(TypeError, match="fp32"):
+        binding._ptr(torch.zeros(4, dtype=torch.float64))
+    with pytest.raises(ValueError, match="not contiguous"):
+        kf.marshal_ptrs([x, x[:, ::2]])

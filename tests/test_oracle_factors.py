@@ -45,6 +45,36 @@ def test_patches_times_flat_weight_is_a_convolution(k, stride, pad, H, W):
     assert np.all(p[:, -1] == 1.0)
 
 
+@pytest.mark.parametrize("kh,kw,stride,ph,pw,H,W", [(1, 7, 1, 0, 3, 9, 10), (7, 1, 1, 3, 0, 9, 10), (1, 3, 1, 0, 1, 5, 7),
+                                                     (3, 1, 1, 1, 0, 5, 7), (3, 5, 2, 0, 2, 9, 11), (3, 3, 1, 2, 0, 6, 6)])
+def test_patches_with_different_row_and_column_padding_is_a_convolution(kh, kw, stride, ph, pw, H, W):
+    # the padding of the rows and of the columns are separate arguments: swapping them, or using one for both,
+    # changes either the shape or the zero pattern of the patches and fails here
+    B, C, Co = 2, 3, 4
+    x = _x(12, (B, C, H, W))
+    w = rng.draw_normal(13, 1, (Co, C, kh, kw))
+    p = orc.patches(x, kh, kw, stride, ph, has_bias=False, pad_w=pw)
+    got = p @ w.reshape(Co, -1).astype(np.float64).T
+    ref = torch.nn.functional.conv2d(torch.from_numpy(x).double(), torch.from_numpy(w).double(), None,
+                                     stride=stride, padding=(ph, pw))
+    assert p.shape == (B * ref.shape[2] * ref.shape[3], C * kh * kw)
+    assert np.allclose(got, ref.permute(0, 2, 3, 1).reshape(-1, Co).numpy(), rtol=1e-12, atol=1e-12)
+
+
+def test_patches_one_sided_padding_zero_count_closed_form():
+    # all-ones input, 1 x 7 kernel padded by 3 columns only: output H x W, and of the 7 taps of output column ow
+    # min(ow, 3) + min(W - 1 - ow, 3) ... fall outside: in-bounds taps per row of the map = 7 W - 12 (W >= 4);
+    # no row of the map is padded, so a 7 x 1 kernel with the same arguments swapped gives 7 H - 12 per column
+    B, C, H, W = 2, 3, 5, 9
+    ones = np.ones((B, C, H, W), np.float32)
+    p = orc.patches(ones, 1, 7, 1, 0, has_bias=False, pad_w=3)
+    assert p.shape == (B * H * W, 7 * C) and p.sum() == B * C * H * (7 * W - 12)
+    q = orc.patches(ones, 7, 1, 1, 3, has_bias=False, pad_w=0)
+    assert q.shape == (B * H * W, 7 * C) and q.sum() == B * C * W * (7 * H - 12)
+    # pad_w left out: the same padding in both directions, as before
+    assert np.array_equal(orc.patches(ones, 3, 3, 1, 1, has_bias=False), orc.patches(ones, 3, 3, 1, 1, False, pad_w=1))
+
+
 def test_patches_padding_zero_count_closed_form():
     # all-ones input: every zero comes from padding.  For 3x3, stride 1, pad 1
     # on HxW the number of in-bounds taps is (3H-2)(3W-2) per channel and image.

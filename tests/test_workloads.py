@@ -51,10 +51,19 @@ def test_further_layer_sets():
     assert max(l.d_A for l in v) == 4609 and {l.h_in for l in v if l.kind == "conv"} == {32, 16, 8, 4, 2}
     inc = shapes.config_layers("inception_nonsquare")
     assert all(l.k != l.kw for l in inc)
-    l = inc[2]                                             # 1x7 kernel on a 17 x 23 map, no padding
-    assert (l.h_out, l.w_out, l.d_A, l.n_rows(32)) == (17, 17, 224 * 7 + 1, 32 * 17 * 17)
+    l = inc[2]                                             # 1x7 kernel on a 17 x 23 map, 3 columns of padding
+    assert (l.pad, l.pw, l.h_out, l.w_out, l.d_A, l.n_rows(32)) == (0, 3, 17, 23, 224 * 7 + 1, 32 * 17 * 23)
     a, g, _ = rng.layer_inputs(l, 2, 5, "relu_normal", 0.1)
-    assert a.shape == (2, 224, 17, 23) and g.shape == (2, 256, 17, 17)
+    assert a.shape == (2, 224, 17, 23) and g.shape == (2, 256, 17, 23)
+    assert all((x.h_out, x.w_out) == (x.h_in, x.w) for x in inc[:6])      # "same" padding keeps the map
+    assert (inc[6].pad, inc[6].pw, inc[6].w_out) == (0, 0, 11)            # and one layer without
+    assert (inc[1].pad, inc[1].pw) == (3, 0) and (inc[4].pad, inc[4].pw) == (1, 0)
+    dn = shapes.config_layers("densenet201_imagenet")
+    assert len(dn) == 201 and sum(1 for x in dn if x.kind == "conv" and x.k == 3) == 98
+    assert dn[-1].c_in == 1920 and dn[1].c_in == 64 and dn[2] == shapes.LayerSpec("conv", 128, 32, 3, 1, 1, 56)
+    for cin, h in ((256, 56), (512, 28), (1792, 14)):                      # the three transitions
+        assert shapes.LayerSpec("conv", cin, cin // 2, 1, 1, 0, h) in dn
+    assert {x.h_in for x in dn if x.kind == "conv"} == {224, 56, 28, 14, 7}
     b = shapes.config_layers("bert_base_small_batch")
     assert len(b) == 72 and all(l.rows == 512 and l.rows < l.d_A for l in b)
     # the square shorthand still means what it meant

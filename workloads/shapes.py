@@ -1,4 +1,4 @@
-"""Layer-shape tables of the synthetic workloads (five headline configurations and three further sets).
+"""Layer-shape tables of the synthetic workloads (five headline configurations and four further sets).
 
 The shapes stand in for the networks the paper trains (section 6.1: ResNet-110
 on Cifar-10, ResNet-50 on ImageNet, Transformer encoder blocks).  Only the
@@ -19,12 +19,13 @@ class LayerSpec:
     c_out: int           # linear: output features; conv: output channels
     k: int = 1           # conv kernel size (square)
     stride: int = 1
-    pad: int = 0
+    pad: int = 0         # zero padding of the rows of the map, and of its columns unless pad_w says otherwise
     h_in: int = 1        # conv input spatial size (square)
     rows: int = 0        # linear: number of rows (samples / tokens)
     has_bias: bool = True
     k_w: int = 0         # conv kernel width when it differs from k (0: square)
     w_in: int = 0        # conv input width when it differs from h_in (0: square)
+    pad_w: int = -1      # conv padding of the columns when it differs from pad (-1: the same)
 
     @property
     def kw(self) -> int:
@@ -35,12 +36,16 @@ class LayerSpec:
         return self.w_in if self.w_in > 0 else self.h_in
 
     @property
+    def pw(self) -> int:
+        return self.pad_w if self.pad_w >= 0 else self.pad
+
+    @property
     def h_out(self) -> int:
         return (self.h_in + 2 * self.pad - self.k) // self.stride + 1
 
     @property
     def w_out(self) -> int:
-        return (self.w + 2 * self.pad - self.kw) // self.stride + 1
+        return (self.w + 2 * self.pw - self.kw) // self.stride + 1
 
     @property
     def d_core(self) -> int:
@@ -61,7 +66,7 @@ class LayerSpec:
         return self.rows
 
     def needs_im2col(self) -> bool:
-        return self.kind == "conv" and (self.k > 1 or self.kw > 1 or self.stride > 1 or self.pad > 0)
+        return self.kind == "conv" and (self.k > 1 or self.kw > 1 or self.stride > 1 or self.pad > 0 or self.pw > 0)
 
 
 def _conv(cin, cout, k, h, stride=1, pad=None):
@@ -126,13 +131,36 @@ def _vgg16_cifar(batch: int) -> List[LayerSpec]:
 
 def _inception_nonsquare() -> List[LayerSpec]:
     """Factorised 1x7 / 7x1 and 1x3 / 3x1 convolutions with the channel counts of Inception-v4's 17x17 and
-    8x8 stages (section 6.1 lists Inception-v4).  The layer descriptor has one padding value for both
-    directions, so the layers are taken unpadded (the asymmetric "same" padding of the network is not
-    expressible); one layer has a non-square input map."""
-    def ns(cin, cout, kh, kw, h, w=0):
-        return LayerSpec("conv", cin, cout, kh, 1, 0, h, k_w=kw, w_in=w)
+    8x8 stages (section 6.1 lists Inception-v4), padded as in the network: (k - 1) / 2 along the long side of
+    the kernel only, so the map keeps its size.  One layer of each stage is also taken on a non-square map, and one
+    unpadded."""
+    def ns(cin, cout, kh, kw, h, w=0, same=True):
+        ph, pw = ((kh - 1) // 2, (kw - 1) // 2) if same else (0, 0)
+        return LayerSpec("conv", cin, cout, kh, 1, ph, h, k_w=kw, w_in=w, pad_w=pw)
     return [ns(192, 192, 1, 7, 17), ns(192, 224, 7, 1, 17), ns(224, 256, 1, 7, 17, 23),
-            ns(384, 256, 1, 3, 8), ns(384, 256, 3, 1, 8), ns(448, 512, 3, 1, 8, 12)]
+            ns(384, 256, 1, 3, 8), ns(384, 256, 3, 1, 8), ns(448, 512, 3, 1, 8, 12),
+            ns(192, 224, 1, 7, 17, same=False)]
+
+
+def _densenet201(batch: int) -> List[LayerSpec]:
+    """DenseNet-201-shaped layer set (section 6.1 lists DenseNet-201): growth rate 32, dense blocks of 6, 12, 48
+    and 32 layers on 56, 28, 14 and 7 pixel maps.  Dense layer j of a block sees all earlier outputs, c0 + 32 j
+    channels: a 1x1 bottleneck to 128 channels, then a 3x3 convolution (pad 1) to 32 new channels.  Between the
+    blocks a 1x1 transition halves the channels (the 2x2 pooling after it halves the map).  201 layers: the 7x7
+    stem, 2 x 98 dense-layer convolutions, 3 transitions, the classifier."""
+    layers = [_conv(3, 64, 7, 224, stride=2, pad=3)]
+    c, h = 64, 56
+    for bi, reps in enumerate((6, 12, 48, 32)):
+        for j in range(reps):
+            layers.append(_conv(c + 32 * j, 128, 1, h))
+            layers.append(_conv(128, 32, 3, h))
+        c += 32 * reps
+        if bi < 3:
+            layers.append(_conv(c, c // 2, 1, h))
+            c //= 2
+            h //= 2
+    layers.append(LayerSpec("linear", c, 1000, rows=batch))
+    return layers
 
 
 def _bert_small_batch() -> List[LayerSpec]:
@@ -162,6 +190,8 @@ CONFIGS: Dict[str, dict] = {
                                 damping=0.001, decay=0.95),
     "bert_base_small_batch": dict(index=8, batch=4, dtype="f32", act="normal", gout_var=1e-4,
                                   damping=0.003, decay=0.95),
+    "densenet201_imagenet": dict(index=9, batch=16, dtype="f32", act="relu_normal", gout_var=1e-3,
+                                 damping=0.001, decay=0.95),
 }
 
 
@@ -186,6 +216,8 @@ def config_layers(name: str) -> List[LayerSpec]:
         return _inception_nonsquare()
     if idx == 8:
         return _bert_small_batch()
+    if idx == 9:
+        return _densenet201(hp["batch"])
     raise KeyError(name)
 
 
