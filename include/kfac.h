@@ -14,9 +14,23 @@
  *
  * Conventions
  *   - Every pointer whose name starts with d_ is a DEVICE pointer owned by the
- *     caller.  The library allocates no device memory and keeps no state.
- *     Arrays of descriptors / pointers / scalars passed to the *_batched calls
- *     are HOST arrays of length n.
+ *     caller.  The library allocates no device memory: every intermediate lives in
+ *     the caller's workspace (kfac_precondition_static: in a buffer that is part of
+ *     the library image).  Arrays of descriptors / pointers / scalars passed to the
+ *     *_batched calls are HOST arrays of length n, read before the call returns.
+ *   - State the library keeps, all of it per process:
+ *       * per device, created at the first inversion call that has a factor of order
+ *         above 1280 and kept until the process ends: two HIP streams (non-blocking,
+ *         default priority) and 130 events (timing disabled).  See kfac_invert.
+ *       * a mutex that serialises the part of an inversion call that enqueues work on
+ *         those streams: inversion calls from several host threads are safe, and
+ *         their enqueueing is serialised for that part.
+ *       * the address of the static scratch buffer of kfac_precondition_static, per device.
+ *       * the planner knobs set through kfac_tune and the timing hooks of
+ *         kfac_profile.h (development and measurement interfaces: process-wide, not
+ *         synchronised; change them only while no other thread is inside the library,
+ *         and not between a workspace query and the call it sizes).
+ *     Nothing else persists from call to call: no cached plans, no device buffers.
  *   - All matrices are row-major.  Factors and inverses are d x d fp32 with
  *     leading dimension d.  Running factors: the LOWER triangle is read; both
  *     triangles are written (mirrored) on exit.  Inverses are written as full,
@@ -114,10 +128,16 @@ kfac_status kfac_update_factors(const kfac_layer_desc *desc, const void *d_act, 
 
 /* Damped inverses (section 5.2, matrix-inversion variant with the damping of
  * each factor given explicitly).  d_info: 2 ints (A, G).
- * Streams: with eight or more factors of order above 1280 in one call, part of
- * the work runs on a second stream that the library creates once per device
- * (default priority), forked from and joined back to hip_stream by events inside
- * the call: ordering on hip_stream is as if everything ran there. */
+ * The inversion works in place in the output buffer: d_A_inv / d_G_inv must not alias the running factors, and
+ * the inverse of a factor that is reported as not positive definite holds whatever the elimination had reached
+ * (see Conventions); the running factor itself is never modified.
+ * Accuracy: fp32 elimination, relative error of the order of a few hundredths of cond(M) * 2^-24.  Above order
+ * 1280 the panel products of ill-conditioned pivot blocks are refined once, which keeps the result within a
+ * factor two of an fp32 LAPACK Cholesky inverse up to condition numbers of a few 1e5.
+ * Streams: when a call has a factor of order above 1280, part of the work (the short dependent kernels of every
+ * elimination step, and the factors of order up to 1280) runs on the two library streams named under
+ * Conventions, forked from and joined back to hip_stream by events inside the call: ordering on hip_stream is
+ * as if everything ran there, and the call may be captured into a HIP graph like any other. */
 kfac_status kfac_invert(const kfac_layer_desc *desc, const float *d_A_run, const float *d_G_run,
                         float damping_A, float damping_G, float *d_A_inv, float *d_G_inv, int *d_info,
                         void *d_work, size_t work_bytes, void *hip_stream);

@@ -40,7 +40,12 @@ enum {
 
 /* When enabled, every kernel launch is bracketed by a pair of HIP events
  * recorded on the launch stream (this allocates events; leave it off in
- * production).  Host arrays; returns 0. */
+ * production), and the inversion calls keep all their kernels on the caller's
+ * stream instead of spreading them over the library's streams: an event pair
+ * around a kernel that has to wait for another stream's kernel to leave the
+ * chip would time the wait as well.  The per-class times are therefore those
+ * of each kernel running alone; their sum exceeds the wall time of a call that
+ * overlaps them.  Host arrays; returns 0. */
 int kfac_timing_enable(int on);
 /* Waits for the recorded events, ADDS per-class elapsed milliseconds, launch
  * counts and algorithmic work into the host arrays of KFAC_K_COUNT entries (any

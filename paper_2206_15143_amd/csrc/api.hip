@@ -43,6 +43,8 @@ TimingState &timing()
 }
 }  // namespace
 
+bool timing_active() { return timing().on; }
+
 void timing_begin(int cls, hipStream_t s)
 {
     TimingState &t = timing();

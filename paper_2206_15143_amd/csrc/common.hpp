@@ -162,6 +162,7 @@ struct Tuning {
 Tuning &tuning();
 
 // Optional per-launch HIP-event timing (see include/kfac_profile.h).
+bool timing_active();
 void timing_begin(int cls, hipStream_t s);
 void timing_end(hipStream_t s);
 // work of the launch recorded last: `work` in units of the definition (flops of the factor, inverse or product

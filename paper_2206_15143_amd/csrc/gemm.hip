@@ -184,6 +184,7 @@ hipError_t launch_one(const GemmTable &tab, int blocks, hipStream_t s)
     double flops = 0.0;
     for (int k = 0; k < tab.count; ++k) {
         const GemmProb &p = tab.p[k];
+        if (p.gate) continue;       // may be skipped on the device: not counted
         if (p.mode != kSubLowerSkip) { flops += 2.0 * p.M * p.N * p.K; continue; }
         const double live = (double)p.M - (double)(std::min(p.p1, p.M) - p.p0);
         flops += live * (live + 1.0) * p.K;
@@ -332,7 +333,7 @@ hipError_t split_gemm_launch(const GemmJob *jobs, const std::vector<int> &idx, h
         p.gate = j.gate; p.gate_cond = j.gate_cond;
         p.blk_start = (int)blocks;
         for (int I = 0; I < p.tI; ++I) blocks += split_row_len(p.mode, p.tJ, p.doff, I);
-        flops += gemm_job_flops(j);
+        if (!j.gate) flops += gemm_job_flops(j);       // a gated product may be skipped on the device: not counted
         if (tab.count == kMaxProblems) {
             hipError_t e = flush();
             if (e != hipSuccess) return e;

@@ -236,56 +236,79 @@ __global__ __launch_bounds__(256, 2) void gemm_split_kernel(const GemmSTable tab
     if (idle || (dbg & 8)) return;
 
     // ---- epilogue: acc[ti*2 + tj][v] = C[m0 + wm*128 + ti*32 + 8*(v>>2) + 4*lg + (v&3)][n0 + wn*64 + tj*32 + lr]
-    // An address is a wave-uniform row pointer (scalar registers) plus one per-lane offset that is the same for
-    // every tile and row: the 16 accesses of a tile need no address registers of their own.
+    // A lane of the MFMA result holds single elements of many rows: written or updated from there, every memory
+    // instruction moves 4 bytes per lane.  Instead each wavefront passes its part through LDS (the ring is free
+    // now: 18 KB per wavefront), 32 rows x 64 columns at a time, and reads it back with 16 lanes along a row, four
+    // columns each: the accesses to C are 16 bytes per lane and 256 contiguous bytes per row.  (C need not be
+    // 16-byte aligned: the vector type below asks for 4.)  A chunk that the bounds of the product, the line
+    // n = m + doff or the pivot rows and columns cut through takes the element-wise path further down.
     const int mw = m0 + wm * 128, nw = n0 + wn * 64;
     const long ldc = pr.ldc;
+    const int p0 = pr.p0, p1 = pr.p1, doff = pr.doff;
+    typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
+    constexpr int EP = 68;                                   // LDS row pitch of a chunk (floats)
+    float *wl = lds + w * (S_LDS_FLOATS / 4);
+    const int rr = lane >> 4, c4 = (lane & 15) * 4;
     const unsigned lane_off = (unsigned)(4 * lg) * (unsigned)pr.ldc + (unsigned)lr;
     auto row_ptr = [&](int t, int r) { return pr.C + ((long)(mw + (t >> 1) * 32 + r) * ldc + nw + (t & 1) * 32); };
-    if (!lower) {
+    auto live = [&](int m, int n) {
+        if (!lower) return m < pr.M && n < pr.N;
+        return m < pr.M && n < pr.N && n <= m + doff && !(rows_skip && m >= p0 && m < p1) && !(n >= p0 && n < p1);
+    };
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const int n = nw + (t & 1) * 32 + lr;
-            if (n >= pr.N) continue;
+    for (int ti = 0; ti < 4; ++ti) {
+        const int mr0 = mw + ti * 32;
+        bool whole = mr0 + 32 <= pr.M && nw + 64 <= pr.N;                    // uniform over the wavefront
+        if (lower)
+            whole = whole && nw + 63 <= mr0 + doff && !(rows_skip && mr0 < p1 && mr0 + 32 > p0) &&
+                    !(nw < p1 && nw + 64 > p0);
+        if (whole) {
+#pragma unroll
+            for (int tj = 0; tj < 2; ++tj)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    wl[(8 * (v >> 2) + 4 * lg + (v & 3)) * EP + tj * 32 + lr] = acc[ti * 2 + tj][v];
+            // (LDS operations of one wavefront complete in order: no barrier between these writes and the reads)
+            float *crow = pr.C + ((long)(mr0 + rr) * ldc + nw + c4);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                f4u val[4], old[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int row = 4 * (4 * h + q);      // + rr, in crow and below
+                    val[q] = *reinterpret_cast<const f4u *>(wl + (row + rr) * EP + c4);
+                    if (lower) old[q] = *reinterpret_cast<const f4u *>(crow + (long)row * ldc);
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int row = 4 * (4 * h + q);
+                    f4u out = val[q];
+                    if (lower) out = add ? old[q] + val[q] : old[q] - val[q];
+                    *reinterpret_cast<f4u *>(crow + (long)row * ldc) = out;
+                }
+            }
+            continue;
+        }
+        // element-wise: the 16 loads of a tile are issued together
+#pragma unroll
+        for (int tj = 0; tj < 2; ++tj) {
+            const int t = ti * 2 + tj;
+            const int n = nw + tj * 32 + lr;
+            float old[16];
+            if (lower) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int r = 8 * (v >> 2) + (v & 3);
+                    old[v] = live(mr0 + r + 4 * lg, n) ? row_ptr(t, r)[lane_off] : 0.f;
+                }
+            }
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int r = 8 * (v >> 2) + (v & 3);
-                if (mw + (t >> 1) * 32 + r + 4 * lg < pr.M) row_ptr(t, r)[lane_off] = acc[t][v];
+                if (!live(mr0 + r + 4 * lg, n)) continue;
+                row_ptr(t, r)[lane_off] = !lower ? acc[t][v] : (add ? old[v] + acc[t][v] : old[v] - acc[t][v]);
             }
         }
-        return;
-    }
-    // read-modify-write below the line n = m + doff, outside the pivot rows and columns
-    const int p0 = pr.p0, p1 = pr.p1, doff = pr.doff;
-    auto live = [&](int m, int n) {
-        return m < pr.M && n < pr.N && n <= m + doff && !(rows_skip && m >= p0 && m < p1) && !(n >= p0 && n < p1);
-    };
-    auto load_tile = [&](int t, float (&old)[16]) {
-        const int n = nw + (t & 1) * 32 + lr;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int r = 8 * (v >> 2) + (v & 3);
-            old[v] = live(mw + (t >> 1) * 32 + r + 4 * lg, n) ? row_ptr(t, r)[lane_off] : 0.f;
-        }
-    };
-    auto store_tile = [&](int t, const float (&old)[16]) {
-        const int n = nw + (t & 1) * 32 + lr;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int r = 8 * (v >> 2) + (v & 3);
-            if (live(mw + (t >> 1) * 32 + r + 4 * lg, n)) row_ptr(t, r)[lane_off] = add ? old[v] + acc[t][v] : old[v] - acc[t][v];
-        }
-    };
-    // the 16 loads of a tile are issued together, and the loads of the next tile go out before the stores of
-    // the current one (more tiles in flight cost more registers than the kernel has)
-    float oa[16], ob[16];
-    load_tile(0, oa);
-#pragma unroll
-    for (int t = 0; t < 8; t += 2) {
-        load_tile(t + 1, ob);
-        store_tile(t, oa);
-        if (t + 2 < 8) load_tile(t + 2, oa);
-        store_tile(t + 1, ob);
     }
 }
 

@@ -981,7 +981,9 @@ hipError_t invert_launch(const InvertJob *jobs_in, int n_all, void *work, size_t
     // the one-launch-per-step class on the other (independent matrices: the two classes run side by side).
     std::unique_lock<std::mutex> lock(aux_mutex(), std::defer_lock);
     AuxStreams *aux = nullptr;
-    if (!large.empty() && tuning().invert_two_streams) {
+    // (with the per-launch event timing on, everything stays on the caller's stream: an event pair around a kernel
+    // that waits for another stream's kernel to leave the chip would time the wait as well)
+    if (!large.empty() && tuning().invert_two_streams && !timing_active()) {
         lock.lock();       // the events are shared by all calls on a device: one call enqueues at a time
         aux = aux_streams();
         if (!aux) lock.unlock();

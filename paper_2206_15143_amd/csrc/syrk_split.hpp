@@ -279,14 +279,27 @@ __global__ __launch_bounds__(256, 2) void syrk_split_kernel(const SyrkTable tab)
     }
     if (idle) return;
     const int blk = I * (I + 1) / 2 + (J >> 1);
-    float *dst = pr.partial + ((long)split * nblk + blk) * (S_BM * S_BM) + (J & 1) * S_BN + wn * 64 + lr;
+    // Each wavefront passes its 128 x 64 part through LDS (the ring is free now), 32 rows at a time, and reads it
+    // back with 16 lanes along a row: the stores are 16 bytes per lane and 256 contiguous bytes per row instead of
+    // 4 bytes per lane.  (LDS operations of one wavefront complete in order: no barrier between writes and reads.)
+    float *dst = pr.partial + ((long)split * nblk + blk) * (S_BM * S_BM) + (J & 1) * S_BN + wn * 64;
+    constexpr int EP = 68;                                   // LDS row pitch of a chunk (floats)
+    float *wl = lds + w * (S_LDS_FLOATS / 4);
+    const int rr = lane >> 4, c4 = (lane & 15) * 4;
 #pragma unroll
-    for (int t = 0; t < 8; ++t)
+    for (int ti = 0; ti < 4; ++ti) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = wm * 128 + (t >> 1) * 32 + 8 * (v >> 2) + 4 * lg + (v & 3);
-            dst[row * S_BM + (t & 1) * 32] = acc[t][v];
+        for (int tj = 0; tj < 2; ++tj)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                wl[(8 * (v >> 2) + 4 * lg + (v & 3)) * EP + tj * 32 + lr] = acc[ti * 2 + tj][v];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int row = 4 * q + rr;
+            const floatx4 val = *reinterpret_cast<const floatx4 *>(wl + row * EP + c4);
+            *reinterpret_cast<floatx4 *>(dst + (long)(wm * 128 + ti * 32 + row) * S_BM + c4) = val;
         }
+    }
 }
 
 }  // namespace kfac
