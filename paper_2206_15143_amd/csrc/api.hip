@@ -863,6 +863,7 @@ int kfac_tune(const char *key, long value)
     else if (k == "invert_two_streams_min") t.invert_two_streams_min = value < 2 ? 2 : value;
     else if (k == "invert_outer_block") t.invert_outer_block = value;
     else if (k == "invert_refine") t.invert_refine = value;
+    else if (k == "invert_panel_split") t.invert_panel_split = value;
     else if (k == "invert_refine_cond") t.invert_refine_cond = value < 0 ? 0 : value;
     else if (k == "eigen_max_sweeps") t.eigen_max_sweeps = value;
     else if (k == "eigen_inner_sweeps") t.eigen_inner_sweeps = value;

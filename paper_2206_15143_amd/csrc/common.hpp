@@ -65,6 +65,7 @@ struct GemmJob {
     // the two floats exceeds gate_cond (the blocked inversion's test of a pivot block's condition number)
     const int *gate = nullptr;
     float gate_cond = 0.f;
+    bool wide_tiles = false;     // kStore: take the split-bf16 kernel whatever the depth and tile fill
 };
 
 enum GemmMode : int {
@@ -130,6 +131,7 @@ struct Tuning {
     long im2col_min_blocks = 1024;   // shorter strips until a layer has this many workgroups
     long eigen_max_sweeps = 20;      // sweep budget of the block Jacobi eigen-decomposition (12-13 used at order 577)
     long eigen_inner_sweeps = 1;     // Jacobi sweeps over the 32 x 32 Gram matrix of a pair of blocks per round
+    long invert_panel_split = 1;     // blocked sweep: panel products on the split-bf16 kernel
     long invert_refine = 1;          // blocked sweep: refinement step of the panel products (see invert.hip) ...
     long invert_refine_cond = 3000;  // ... of pivot blocks whose condition number (maximum norm) exceeds this
     long invert_outer_block = 256;   // outer pivot block of the two-level inversion (multiple of 32)

@@ -289,7 +289,7 @@ bool split_gemm_eligible(const GemmJob &j)
     if (!tuning().use_split_gemm || (j.mode != kStore && j.mode != kSubLowerSkip && j.mode != kSubRect && j.mode != kAddRect))
         return false;
     if (j.M < tuning().split_gemm_min_m || j.N < 64 || j.K < 16) return false;
-    if (j.mode == kStore) {
+    if (j.mode == kStore && !j.wide_tiles) {
         if (j.K < tuning().split_gemm_min_k) return false;
         // 256 x 128 tiles: products that fill them badly (a 257-row or 65-column operand) stay with the 144-wide
         // tiles of the fp32 kernel

@@ -596,6 +596,7 @@ hipError_t BlockedRun::chain(int st, hipStream_t s)
         a.A = big[k].P; a.B = big[k].Vt[st & 1]; a.C = big[k].Wt[st & 1];
         a.M = bs; a.N = j.n; a.K = bs; a.lda = PB; a.ldb = big[k].ldv; a.ldc = big[k].ldv;
         a.mode = kStore; a.p0 = a.p1 = 0;
+        a.wide_tiles = tuning().invert_panel_split != 0;
     }
     e = gemm_launch(gj.data(), act, s);
     if (e != hipSuccess) return e;
@@ -988,23 +989,29 @@ hipError_t invert_launch(const InvertJob *jobs_in, int n_all, void *work, size_t
         aux = aux_streams();
         if (!aux) lock.unlock();
     }
+    // With the library's streams the large matrices are enqueued first: their lock-step sequence of launches is the
+    // critical path of the call, and the hundred-odd launches of the other class take the host half a millisecond
+    // to enqueue, which would otherwise pass before the first kernel of the long sequence starts.
     hipStream_t fs = s;
     if (aux && !fused.empty()) {
         fs = aux->side;
         if (hipEventRecord(aux->fork, s) != hipSuccess || hipStreamWaitEvent(fs, aux->fork, 0) != hipSuccess)
             return hipErrorUnknown;
     }
+    const bool side_open = fs != s;
     hipError_t e = hipSuccess;
-    if (!fused.empty()) e = fused_launch(jobs, fused, offs, work, dtab, fs);
-    // bordered orders of the fused class finish on the same stream
-    if (e == hipSuccess && !bordered.empty()) e = border_launch(jobs_in, bordered, ybuf, fs);
-    bool side_open = fs != s;
-    if (side_open && hipEventRecord(aux->side_done, fs) != hipSuccess) return hipErrorUnknown;
-    if (e == hipSuccess && !large.empty()) {
+    auto run_large = [&]() -> hipError_t {
+        if (large.empty()) return hipSuccess;
         // the nested pivot-block inversions use the second half of the descriptor table
         const int steps = (jobs[large[0]].n + outer_block() - 1) / outer_block();
-        e = blocked_launch(jobs, large, offs, work, dtab + n_all, steps <= AuxStreams::kEvents ? aux : nullptr, s);
-    }
+        return blocked_launch(jobs, large, offs, work, dtab + n_all, steps <= AuxStreams::kEvents ? aux : nullptr, s);
+    };
+    if (side_open) e = run_large();
+    if (e == hipSuccess && !fused.empty()) e = fused_launch(jobs, fused, offs, work, dtab, fs);
+    // bordered orders of the fused class finish on the same stream
+    if (e == hipSuccess && !bordered.empty()) e = border_launch(jobs_in, bordered, ybuf, fs);
+    if (side_open && hipEventRecord(aux->side_done, fs) != hipSuccess) return hipErrorUnknown;
+    if (!side_open && e == hipSuccess) e = run_large();
     // always join the side stream, also after an error
     if (side_open && hipStreamWaitEvent(s, aux->side_done, 0) != hipSuccess) return hipErrorUnknown;
     return e;
