@@ -18,11 +18,12 @@
 //   - up to invert_fused_max_n (1280): 64-row blocks, ONE launch per step for all
 //     matrices (invert_fused.hpp): panel product, update and the inversion of
 //     the next pivot block fused;
-//   - above: two-level blocking with 288-row outer blocks (blocked_launch
-//     below): the pivot block is inverted by the first form, the panel product
-//     W = P V and the rank-288 update run on the wave-unit GEMM (gemm.hip, mode
-//     kSubLowerSkip), small kernels gather the old panel K-major and scatter
-//     the new one.
+//   - above: two-level blocking with 256-row outer blocks (BlockedRun below): the
+//     pivot block is inverted by the first form, the panel product W = P V, its
+//     gated refinement and the rank-256 update run on the split-bf16 GEMM
+//     (gemm_split.hpp), small kernels gather the old panel K-major and scatter
+//     the new one; with the library's streams the short dependent launches of
+//     step K+1 run beside the update of step K (look-ahead).
 // kfac_invert_pi computes the two damping terms of Eq. 12 on the device first
 // (pi_damping_kernel) and the kernels above read them through a device pointer.
 #include "invert_fused.hpp"
@@ -78,14 +79,13 @@ __global__ __launch_bounds__(256) void sweep_init_kernel(const InvTable tab)
 }
 
 // ---- two-level blocked sweep for the large factors -------------------------------------------
-// Outer pivot blocks of PB = 288 rows (two 144-wide macro tiles of the wave GEMM).  Per outer step:
-// the pivot block is inverted by the one-launch-per-step sweep above (a 288 x 288 problem), the old
-// panel is gathered K-major into V, W = V P and the rank-288 update of the rest of the triangle run
-// on the wave-unit GEMM (gemm_wave.hpp), and the new panel and -P are scattered back in place.
-// (the block height is a planner knob, a multiple of 288 = lcm of the 144-wide macro tiles and the 32-wide
-// gather / scatter tiles; PB below is its value for the current call).  576 is 6-8 % faster on the
-// workloads with many large factors, but the error of the inverse grows with the order of the explicitly
-// inverted pivot block (measured at order 2305: 1.5e-5 / 2.9e-5 / 4.0e-5 for 288 / 576 / 864), so 288 stays.
+// Outer pivot blocks of PB rows (invert_outer_block, 256; a multiple of the 32-wide gather / scatter tiles, at
+// most 512).  Per outer step: the pivot block is inverted by the one-launch-per-step sweep above (a PB x PB
+// problem), the old panel is gathered K-major into V, W = V P (refined once where the pivot block is
+// ill-conditioned) and the rank-PB update of the rest of the triangle run on the split-bf16 GEMM, and the new panel
+// and -P are scattered back in place.  512 is 12 % faster on the workloads with many large factors, but the error
+// of the inverse grows with the order of the explicitly inverted pivot block (measured at order 2305:
+// 2.8e-5 / 6.2e-5 for 256 / 512), so 256 stays.
 inline int outer_block() { return (int)std::min(512l, std::max(64l, tuning().invert_outer_block / 32 * 32)); }
 
 struct BlkProb {
