@@ -80,6 +80,8 @@ struct Geo {
     bool fused3;        // 3x3/s1/p1 fp32 conv whose A factor is built straight from the NCHW input
     int ld;             // patch leading dimension (elements)
     int esz;
+    bool g_rows;        // bf16 output gradients on a map with an odd number of positions: through a row-major copy
+    int ldg;            // its leading dimension (elements)
 };
 
 bool desc_ok(const kfac_layer_desc *d)
@@ -135,6 +137,14 @@ kfac_status geometry(const kfac_layer_desc *d, int batch, int h, int w, Geo &g)
                    ph == 1 && pw == 1 && d->d_in % 16 == 0 && d->d_in <= tuning().fuse_conv3_max_c && conv3_rows(h, w) > 0 &&
                    (long)batch * d->d_in * h * w * 4 < 0x7fff0000l;
         if (g.fused3) g.patches = false;
+        // The bf16 MFMA kernel reads NCHW operands in 4-byte pieces along a channel row, which an odd number of
+        // positions per channel (7 x 7 maps) misaligns; the fp32-widening kernel that would take such operands
+        // runs at a tenth of its rate.  They are first copied into row-major form instead, [positions, channels],
+        // by the patch kernel (a 1 x 1 "extraction" is that transposition): a few MB per layer.
+        const bool bf = d->in_dtype == KFAC_BF16;
+        if (bf && !g.patches && tuning().bf16_rows_copy && ((long)h * w) % 2 == 1 && d->d_in >= 96) g.patches = true;
+        g.g_rows = bf && tuning().bf16_rows_copy && ((long)g.Ho * g.Wo) % 2 == 1 && d->d_out >= 96;
+        g.ldg = (d->d_out + 7) / 8 * 8;
         // the patch kernel stages at least one output row of its narrowest channel chunk in LDS: a map too wide for
         // that is refused here, before anything is launched
         if (g.patches && !im2col_fits(d->kh, d->kw, d->stride, g.Wo, g.esz)) return KFAC_ERR_SHAPE;
@@ -143,11 +153,17 @@ kfac_status geometry(const kfac_layer_desc *d, int batch, int h, int w, Geo &g)
         g.R = batch;
         g.patches = false;
         g.fused3 = false;
+        g.g_rows = false;
+        g.ldg = 0;
     }
     return KFAC_OK;
 }
 
-size_t patch_bytes(const Geo &g) { return g.patches ? align_up((size_t)g.R * g.ld * g.esz, 256) : 0; }
+size_t a_patch_bytes(const Geo &g) { return g.patches ? align_up((size_t)g.R * g.ld * g.esz, 256) : 0; }
+size_t patch_bytes(const Geo &g)
+{
+    return a_patch_bytes(g) + (g.g_rows ? align_up((size_t)g.R * g.ldg * g.esz, 256) : 0);
+}
 
 bool aligned(const void *p, size_t a) { return ((uintptr_t)p) % a == 0; }
 
@@ -191,6 +207,13 @@ void layer_jobs(const kfac_layer_desc *d, const Geo &g, const void *act, const v
     q.x = gout;
     if (!g.conv) {
         q.layout = kRows; q.ld = d->d_out; q.hw = 1; q.ctot = d->d_out;
+    } else if (g.g_rows) {
+        Im2colJob j{};
+        j.x = gout; j.out = patches ? static_cast<char *>(patches) + a_patch_bytes(g) : nullptr; j.dtype = d->in_dtype;
+        j.B = batch; j.C = d->d_out; j.H = g.Ho; j.W = g.Wo; j.kh = 1; j.kw = 1;
+        j.stride = 1; j.pad_h = 0; j.pad_w = 0; j.Ho = g.Ho; j.Wo = g.Wo; j.ld = g.ldg;
+        ij.push_back(j);
+        q.x = j.out; q.layout = kRows; q.ld = g.ldg; q.hw = 1; q.ctot = d->d_out;
     } else {
         q.layout = kNCHW; q.ld = 0; q.hw = g.Ho * g.Wo; q.ctot = d->d_out;
     }
@@ -863,6 +886,7 @@ int kfac_tune(const char *key, long value)
     else if (k == "invert_two_streams_min") t.invert_two_streams_min = value < 2 ? 2 : value;
     else if (k == "invert_outer_block") t.invert_outer_block = value;
     else if (k == "invert_refine") t.invert_refine = value;
+    else if (k == "bf16_rows_copy") t.bf16_rows_copy = value;
     else if (k == "invert_panel_split") t.invert_panel_split = value;
     else if (k == "invert_refine_cond") t.invert_refine_cond = value < 0 ? 0 : value;
     else if (k == "eigen_max_sweeps") t.eigen_max_sweeps = value;

@@ -131,6 +131,7 @@ struct Tuning {
     long im2col_min_blocks = 1024;   // shorter strips until a layer has this many workgroups
     long eigen_max_sweeps = 20;      // sweep budget of the block Jacobi eigen-decomposition (12-13 used at order 577)
     long eigen_inner_sweeps = 1;     // Jacobi sweeps over the 32 x 32 Gram matrix of a pair of blocks per round
+    long bf16_rows_copy = 1;         // bf16 NCHW operands with an odd number of positions: row-major copy first
     long invert_panel_split = 1;     // blocked sweep: panel products on the split-bf16 kernel
     long invert_refine = 1;          // blocked sweep: refinement step of the panel products (see invert.hip) ...
     long invert_refine_cond = 3000;  // ... of pivot blocks whose condition number (maximum norm) exceeds this

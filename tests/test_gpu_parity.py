@@ -486,7 +486,10 @@ def test_bf16_inputs_match_oracle_on_the_same_bits():
     (LayerSpec("conv", 128, 96, 1, 1, 0, 6), 3),                   # 1x1: A and G read from NCHW, HW = 36 (4-position tail)
     (LayerSpec("conv", 264, 100, 1, 1, 0, 8), 5),                  # two block columns, HW = 64 (no tail), d_G not a multiple of 8
     (LayerSpec("conv", 8, 300, 3, 1, 1, 14), 2),                   # G of a 3x3 conv, HW = 196, two block rows
-    (LayerSpec("conv", 96, 96, 1, 1, 0, 5), 4),                    # HW = 25 is odd: the widening kernel takes it
+    (LayerSpec("conv", 96, 96, 1, 1, 0, 5), 4),                    # HW = 25 is odd: both operands through a row-major copy
+    (LayerSpec("conv", 200, 136, 1, 1, 0, 7), 6),                  # 7 x 7 maps, widths that are no multiple of 8 or 16
+    (LayerSpec("conv", 16, 128, 3, 1, 1, 7), 5),                   # 3 x 3 on 7 x 7: only G takes the copy (A has its patch matrix)
+    (LayerSpec("conv", 128, 40, 1, 1, 0, 3, w_in=5), 4),           # 3 x 5 map; G (40 wide) stays on the widening kernel
 ])
 def test_bf16_mfma_factor_kernel(layer, batch):
     # row-major bf16 operands take the bf16 MFMA kernel; same bits into the oracle
@@ -503,6 +506,16 @@ def test_bf16_mfma_factor_kernel(layer, batch):
         kf.kfac_tune("use_bf16_mfma", 1)
     assert gu.rel_fro(fast["A"], wide["A"]) < 1e-5
     assert gu.rel_fro(fast["G"], wide["G"]) < 1e-5
+    if layer.kind == "conv" and (layer.h_out * layer.w_out) % 2 == 1:
+        # maps with an odd number of positions: with the row-major copy off, the NCHW operands go to the widening
+        # kernel directly; same factors either way
+        kf.kfac_tune("bf16_rows_copy", 0)
+        try:
+            direct = gu.run_layers_gpu([layer], batch, inputs, scales, 0.95, 0.03, dtype="bf16")[0]
+        finally:
+            kf.kfac_tune("bf16_rows_copy", 1)
+        assert gu.rel_fro(fast["A"], direct["A"]) < 1e-5
+        assert gu.rel_fro(fast["G"], direct["G"]) < 1e-5
 
 
 def test_pi_damped_inverse_matches_oracle():
