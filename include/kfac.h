@@ -21,7 +21,7 @@
  *   - State the library keeps, all of it per process:
  *       * per device, created at the first inversion call that has a factor of order
  *         above 1280 and kept until the process ends: two HIP streams (non-blocking,
- *         default priority) and 130 events (timing disabled).  See kfac_invert.
+ *         default priority) and 194 events (timing disabled).  See kfac_invert.
  *       * a mutex that serialises the part of an inversion call that enqueues work on
  *         those streams: inversion calls from several host threads are safe, and
  *         their enqueueing is serialised for that part.

@@ -900,6 +900,7 @@ int kfac_tune(const char *key, long value)
     else if (k == "use_split_gemm") t.use_split_gemm = value;
     else if (k == "use_split_syrk") t.use_split_syrk = value;
     else if (k == "split_syrk_fill_rows") t.split_syrk_fill_rows = value;
+    else if (k == "split_syrk_min_d") t.split_syrk_min_d = value < 64 ? 64 : value;
     else if (k == "split_syrk_max_stages") t.split_syrk_max_stages = value < 1 ? 1 : value;
     else if (k == "split_syrk_fill_nchw") t.split_syrk_fill_nchw = value;
     else if (k == "split_gemm_min_m") t.split_gemm_min_m = value;

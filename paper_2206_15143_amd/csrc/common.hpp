@@ -65,6 +65,8 @@ struct GemmJob {
     // the two floats exceeds gate_cond (the blocked inversion's test of a pivot block's condition number)
     const int *gate = nullptr;
     float gate_cond = 0.f;
+    const float *D = nullptr;    // kSubFrom
+    long ldd = 0;
     bool wide_tiles = false;     // kStore: take the split-bf16 kernel whatever the depth and tile fill
 };
 
@@ -74,7 +76,8 @@ enum GemmMode : int {
     kSubLowerSkip = 2,   // C[m][n] -= acc for n <= m, m and n outside [p0, p1)
     kStoreDiv = 3,       // C[m][n] = acc / (rv[m] * cv[n] + gamma)   (the division of Eq. 13)
     kSubRect = 4,        // C[m][n] -= acc for n <= m + doff, n outside [p0, p1)   (a rectangle of a lower triangle)
-    kAddRect = 5         // the same entries, C[m][n] += acc
+    kAddRect = 5,        // the same entries, C[m][n] += acc
+    kSubFrom = 6         // C[m][n] = D[m][n] - acc   (D a second matrix, row pitch ldd; block-tile kernel only)
 };
 
 // Symmetric eigen-decomposition M = Q diag(v) Q^T (eigenvectors in the columns of Q, order not sorted).
@@ -148,6 +151,7 @@ struct Tuning {
     long gemm_xcd_remap_min = 8;     // wave GEMM launches with at least this many problems renumber their tiles per XCD
     long use_wave_gemm = 1;          // wide A^T B products on the wave-unit GEMM
     long use_split_syrk = 1;         // wide fp32 factors as six bf16 MFMA products of the inputs' bf16 pieces
+    long split_syrk_min_d = 192;     // narrowest factor the split-bf16 KF-GEMM takes
     long split_syrk_fill_rows = 60;  // ... row-major inputs: when the factor fills this percentage of its 256 x 128 tiles
     long split_syrk_fill_nchw = 40;  // ... NCHW inputs (tile fill x share of real positions in the K stages)
     long split_syrk_max_stages = 32; // ... K stages (of 16 rows) per slice at most: bounds the accumulation chain

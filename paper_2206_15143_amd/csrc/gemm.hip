@@ -30,6 +30,8 @@ struct GemmProb {
     float gamma;
     const int *gate;        // null, or two float bit patterns: leave C alone unless their product exceeds gate_cond
     float gate_cond;
+    const float *D;         // kSubFrom
+    long ldd;
 };
 
 // A launch covers up to kMaxGemmProblems products (a 14 KB kernel argument): the preconditioning of a whole
@@ -143,6 +145,8 @@ __global__ __launch_bounds__(T::NT) void gemm_tn_kernel(const GemmTable tab)
                     pr.C[(long)n * pr.ldc + m] = val;
                 } else if (pr.mode == kStoreDiv) {
                     pr.C[(long)m * pr.ldc + n] = val / (pr.rv[m] * pr.cv[n] + pr.gamma);
+                } else if (pr.mode == kSubFrom) {
+                    pr.C[(long)m * pr.ldc + n] = pr.D[(long)m * pr.ldd + n] - val;
                 } else if (pr.mode == kSubRect || pr.mode == kAddRect) {
                     const bool skip = ((long)n > (long)m + pr.doff) || (n >= pr.p0 && n < pr.p1);
                     if (!skip) pr.C[(long)m * pr.ldc + n] += pr.mode == kAddRect ? val : -val;
@@ -222,7 +226,7 @@ double gemm_job_flops(const GemmJob &j)
 bool wave_gemm_eligible(const GemmJob &j)
 {
     if (!tuning().use_wave_gemm || j.mode == kStoreT || j.mode == kStoreDiv || j.mode == kSubRect || j.mode == kAddRect ||
-        j.gate)
+        j.mode == kSubFrom || j.gate)
         return false;
     if (j.M < 100 || j.N < 100 || j.K < 16) return false;
     if ((long)j.K * j.lda * 4 > 0x7fffffffl || (long)j.K * j.ldb * 4 > 0x7fffffffl) return false;
@@ -289,6 +293,9 @@ bool split_gemm_eligible(const GemmJob &j)
     if (!tuning().use_split_gemm || (j.mode != kStore && j.mode != kSubLowerSkip && j.mode != kSubRect && j.mode != kAddRect))
         return false;
     if (j.M < tuning().split_gemm_min_m || j.N < 64 || j.K < 16) return false;
+    // a product of a tile or two is bound by the latency of one tile's K loop and read-modify-write (55 us at
+    // K = 256): the 64-wide tiles of the block-tile kernel spread it over many CUs and finish in 10-15 us
+    if ((long)j.M * j.N < 4l * S_BM * S_BN) return false;
     if (j.mode == kStore && !j.wide_tiles) {
         if (j.K < tuning().split_gemm_min_k) return false;
         // 256 x 128 tiles: products that fill them badly (a 257-row or 65-column operand) stay with the 144-wide
@@ -381,6 +388,20 @@ hipError_t gemm_launch(const GemmJob *jobs, int n, hipStream_t s)
                 if (cfg[i] >= 0 && jobs[i].mode != kSubLowerSkip) cfg[i] = best;
         }
     }
+    if (!tuning().gemm_bm) {
+        // a call whose block-tile products would not even give every CU a workgroup is bound by the K loop of one
+        // tile: the 64-wide tiles spread it over four times as many CUs
+        long wgs = 0;
+        for (int i = 0; i < n; ++i) {
+            const GemmJob &j = jobs[i];
+            if (cfg[i] < 0 || j.mode == kSubLowerSkip || j.M <= 0 || j.N <= 0 || j.K <= 0) continue;
+            const long bm = kBms[cfg[i]];
+            wgs += ((j.M + bm - 1) / bm) * ((j.N + bm - 1) / bm);
+        }
+        if (wgs > 0 && wgs < 200)
+            for (int i = 0; i < n; ++i)
+                if (cfg[i] >= 0 && jobs[i].mode != kSubLowerSkip && kBms[cfg[i]] > 64) cfg[i] = 2;
+    }
     if (!split.empty()) {
         std::stable_sort(split.begin(), split.end(), [&](int a, int b) { return jobs[a].K > jobs[b].K; });
         hipError_t e = split_gemm_launch(jobs, split, s);
@@ -425,6 +446,7 @@ hipError_t gemm_launch(const GemmJob *jobs, int n, hipStream_t s)
             p.mode = j.mode;
             p.p0 = j.p0; p.p1 = j.p1; p.doff = j.doff;
             p.rv = j.rv; p.cv = j.cv; p.gamma = j.gamma; p.gate = j.gate; p.gate_cond = j.gate_cond;
+            p.D = j.D; p.ldd = j.ldd;
             p.vecA = (((uintptr_t)j.A) % 16 == 0 && j.lda % 4 == 0) ? 1 : 0;
             p.vecB = (((uintptr_t)j.B) % 16 == 0 && j.ldb % 4 == 0) ? 1 : 0;
             blocks += (j.mode == kSubLowerSkip) ? p.tm * (p.tm + 1) / 2 : p.tm * p.tn;

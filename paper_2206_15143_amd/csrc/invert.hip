@@ -92,7 +92,6 @@ struct BlkProb {
     float *W;          // working matrix [n, n]
     float *Vt;         // [PB, ldv]
     float *Wt;         // [PB, ldv]
-    float *Rt;         // [PB, ldv] second copy of the old panel (becomes the residual of the refinement), or null
     float *S;          // [PB, pb] the pivot block before its inversion, both triangles, or null
     int *gate;         // two words: bit patterns of the maximum norms of S and of P (see blk_cond_kernel)
     float gate_cond;   // the refinement runs when their product exceeds this
@@ -178,7 +177,8 @@ __global__ __launch_bounds__(256) void blk_cond_kernel(const BlkTable tab)
 
 // V[kk][gi] = old panel, K-major: row panel (gi < p0) copied, column panel (gi >= p0 + bs) transposed
 // through LDS, pivot columns zero.  One workgroup per 32 x 32 tile.  With the refinement of the panel product
-// on, a second copy of the panel goes to Rt and the pivot block itself, mirrored to both triangles, to S.
+// on, the pivot block itself, mirrored to both triangles, goes to S (whether or not the gate will open: the test of
+// the pivot block runs beside this kernel on another stream).
 __global__ __launch_bounds__(256) void blk_gather_kernel(const BlkTable tab)
 {
     __shared__ float t[32][33];
@@ -192,9 +192,7 @@ __global__ __launch_bounds__(256) void blk_gather_kernel(const BlkTable tab)
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     const long n = pr.n;
     const int p0 = pr.p0, p1 = pr.p0 + pr.bs;
-    const bool refine = pr.S && blk_gate_open(pr.gate, pr.gate_cond);     // blk_cond_kernel ran before
-    float *Rt = refine ? pr.Rt : nullptr;
-    float *S = refine ? pr.S : nullptr;
+    float *S = pr.S;      // null unless the refinement is on
     // p0 and p1 are multiples of 32 (or p1 = n): a tile lies wholly in one of the three regions
     if (g0 < p0) {
 #pragma unroll
@@ -203,7 +201,6 @@ __global__ __launch_bounds__(256) void blk_gather_kernel(const BlkTable tab)
             if (kk < pr.bs && gi < pr.n) {
                 const float v = pr.W[(p0 + kk) * n + gi];
                 pr.Vt[(long)kk * pr.ldv + gi] = v;
-                if (Rt) Rt[(long)kk * pr.ldv + gi] = v;
             }
         }
     } else if (g0 >= p1) {
@@ -218,7 +215,6 @@ __global__ __launch_bounds__(256) void blk_gather_kernel(const BlkTable tab)
             const int kk = k0 + ty + 8 * r, gi = g0 + tx;
             if (kk < pr.bs && gi < pr.n) {
                 pr.Vt[(long)kk * pr.ldv + gi] = t[tx][ty + 8 * r];
-                if (Rt) Rt[(long)kk * pr.ldv + gi] = t[tx][ty + 8 * r];
             }
         }
     } else {
@@ -227,7 +223,6 @@ __global__ __launch_bounds__(256) void blk_gather_kernel(const BlkTable tab)
             const int kk = k0 + ty + 8 * r, gi = g0 + tx;
             if (kk < pr.bs && gi < pr.n) {
                 pr.Vt[(long)kk * pr.ldv + gi] = 0.f;
-                if (Rt) Rt[(long)kk * pr.ldv + gi] = 0.f;
                 if (S) {   // entry (kk, gi - p0) of the pivot block, from its lower triangle
                     const int b = gi - p0, hi = kk > b ? kk : b, lo = kk > b ? b : kk;
                     S[(long)kk * pr.pb + b] = pr.W[(p0 + hi) * n + p0 + lo];
@@ -438,11 +433,12 @@ struct BlockedRun {
         return a;
     }
     hipError_t start(hipStream_t s);
-    hipError_t look(int st, hipStream_t s);     // update st applied to the band of pivot block st + 1
-    hipError_t chain(int st, hipStream_t s);
+    hipError_t look(int st, int part, hipStream_t s);   // update st applied to the band of pivot block st + 1
+    hipError_t chain(int st, hipStream_t sn, hipStream_t sc, hipEvent_t before_gather, hipEvent_t ev_nest,
+                     hipEvent_t ev_cond);
     hipError_t bulk(int st, bool skip_next, hipStream_t s);
     hipError_t finish(hipStream_t s);
-    hipError_t copy_kernel(bool scatter, int st, int act, hipStream_t s);
+    hipError_t copy_kernel(int what, int st, int act, hipStream_t s);    // 0 gather, 1 scatter, 2 condition test
 };
 
 hipError_t BlockedRun::start(hipStream_t s)
@@ -490,8 +486,9 @@ hipError_t BlockedRun::start(hipStream_t s)
     return hipSuccess;
 }
 
-hipError_t BlockedRun::copy_kernel(bool scatter, int st, int act, hipStream_t s)
+hipError_t BlockedRun::copy_kernel(int what, int st, int act, hipStream_t s)
 {
+    const bool scatter = what == 1;
     const int p0 = st * PB;
     for (int g0 = 0; g0 < act; g0 += 32) {
         BlkTable tab;
@@ -501,8 +498,7 @@ hipError_t BlockedRun::copy_kernel(bool scatter, int st, int act, hipStream_t s)
             const InvertJob &j = jobs[idx[g0 + k]];
             BlkProb &p = tab.p[k];
             p.W = j.Minv; p.Vt = big[g0 + k].Vt[st & 1]; p.Wt = big[g0 + k].Wt[st & 1]; p.P = big[g0 + k].P;
-            p.Rt = (refine && !scatter) ? big[g0 + k].Rt : nullptr;
-            p.S = (refine && !scatter) ? big[g0 + k].S : nullptr;
+            p.S = (refine && !scatter) ? big[g0 + k].S : nullptr;   // the condition test reads the matrix itself
             p.gate = refine ? big[g0 + k].ninfo + 1 : nullptr;
             p.gate_cond = (float)tuning().invert_refine_cond;
             p.info = j.info; p.ninfo = big[g0 + k].ninfo;
@@ -510,20 +506,16 @@ hipError_t BlockedRun::copy_kernel(bool scatter, int st, int act, hipStream_t s)
             p.blk_start = blocks;
             blocks += ((j.n + 31) / 32) * ((p.bs + 31) / 32);
         }
-        if (scatter) {
+        if (what == 1) {
             KFAC_LAUNCH(KFAC_K_INV_PANEL, s, blk_scatter_kernel, dim3(blocks), dim3(256), 0, tab);
-        } else {
-            if (refine) {
-                BlkTable ct = tab;
-                int cb = 0;
-                for (int k = 0; k < ct.count; ++k) {
-                    ct.p[k].blk_start = cb;
-                    cb += (ct.p[k].bs + 31) / 32;
-                }
-                KFAC_LAUNCH(KFAC_K_INV_PANEL, s, blk_cond_kernel, dim3(cb), dim3(256), 0, ct);
-                hipError_t e = hipGetLastError();
-                if (e != hipSuccess) return e;
+        } else if (what == 2) {
+            int cb = 0;
+            for (int k = 0; k < tab.count; ++k) {
+                tab.p[k].blk_start = cb;
+                cb += (tab.p[k].bs + 31) / 32;
             }
+            KFAC_LAUNCH(KFAC_K_INV_PANEL, s, blk_cond_kernel, dim3(cb), dim3(256), 0, tab);
+        } else {
             KFAC_LAUNCH(KFAC_K_INV_PANEL, s, blk_gather_kernel, dim3(blocks), dim3(256), 0, tab);
         }
         hipError_t e = hipGetLastError();
@@ -532,9 +524,11 @@ hipError_t BlockedRun::copy_kernel(bool scatter, int st, int act, hipStream_t s)
     return hipSuccess;
 }
 
-// Update st restricted to the band of pivot block st + 1 (rows q0..q1 left of and on the diagonal block, and
-// the columns q0..q1 below it), leaving out the columns of pivot block st, which the scatter of step st owns.
-hipError_t BlockedRun::look(int st, hipStream_t s)
+// Update st restricted to the band of pivot block st + 1, leaving out the columns of pivot block st, which the
+// scatter of step st owns.  part 0: the diagonal block of the band alone (all the nested inversion of step st + 1
+// needs); part 1: the rest, i.e. the rows q0..q1 left of pivot block st and the columns q0..q1 below the diagonal
+// block (what the gather of step st + 1 needs as well).
+hipError_t BlockedRun::look(int st, int part, hipStream_t s)
 {
     const int p0 = st * PB, q0 = p0 + PB;
     const int act = active(st + 1);
@@ -544,11 +538,21 @@ hipError_t BlockedRun::look(int st, hipStream_t s)
         const int q1 = std::min(q0 + PB, j.n);
         const Big &b = big[k];
         const float *Wt = b.Wt[st & 1], *Vt = b.Vt[st & 1];
-        GemmJob r{};       // rows q0..q1, columns 0..q1 up to the diagonal
-        r.A = Wt + q0; r.B = Vt; r.C = j.Minv + (size_t)q0 * j.n;
-        r.M = q1 - q0; r.N = q1; r.K = PB; r.lda = b.ldv; r.ldb = b.ldv; r.ldc = j.n;
-        r.mode = kSubRect; r.p0 = p0; r.p1 = q0; r.doff = q0;
-        gj.push_back(r);
+        if (part == 0) {
+            GemmJob d{};   // rows and columns q0..q1, on and below the diagonal
+            d.A = Wt + q0; d.B = Vt + q0; d.C = j.Minv + (size_t)q0 * j.n + q0;
+            d.M = q1 - q0; d.N = q1 - q0; d.K = PB; d.lda = b.ldv; d.ldb = b.ldv; d.ldc = j.n;
+            d.mode = kSubRect; d.p0 = d.p1 = 0; d.doff = 0;
+            gj.push_back(d);
+            continue;
+        }
+        if (p0 > 0) {
+            GemmJob r{};   // rows q0..q1, columns left of pivot block st
+            r.A = Wt + q0; r.B = Vt; r.C = j.Minv + (size_t)q0 * j.n;
+            r.M = q1 - q0; r.N = p0; r.K = PB; r.lda = b.ldv; r.ldb = b.ldv; r.ldc = j.n;
+            r.mode = kSubRect; r.p0 = r.p1 = 0; r.doff = 1l << 30;
+            gj.push_back(r);
+        }
         if (j.n > q1) {
             GemmJob c{};   // rows below q1, columns q0..q1
             c.A = Wt + q1; c.B = Vt + q0; c.C = j.Minv + (size_t)q1 * j.n + q0;
@@ -557,11 +561,18 @@ hipError_t BlockedRun::look(int st, hipStream_t s)
             gj.push_back(c);
         }
     }
-    return gemm_launch(gj.data(), (int)gj.size(), s);
+    return gj.empty() ? hipSuccess : gemm_launch(gj.data(), (int)gj.size(), s);
 }
 
-hipError_t BlockedRun::chain(int st, hipStream_t s)
+// The chain of step st.  The nested inversion of the pivot block and the test of its condition number go to
+// stream sn, the gather, the panel product, its refinement and the scatter to stream sc: the gather needs the band
+// of the pivot block (before_gather: null, or the event after which it is up to date) but not the inverse, so
+// with two streams it runs beside the nested inversion, the longest link of the chain; ev_nest and ev_cond (used
+// when the streams differ) order the panel product after the inversion and the refinement after the test.
+hipError_t BlockedRun::chain(int st, hipStream_t sn, hipStream_t sc, hipEvent_t before_gather, hipEvent_t ev_nest,
+                             hipEvent_t ev_cond)
 {
+    const bool two = sn != sc;
     const int p0 = st * PB;
     const int act = active(st);
     // 1. inverse of the pivot blocks (in their current, updated state) -> P
@@ -583,11 +594,20 @@ hipError_t BlockedRun::chain(int st, hipStream_t s)
     }
     // nested problems are grouped by order (all PB except possibly the last block of a matrix)
     std::stable_sort(nidx.begin(), nidx.end(), [&](int a, int b) { return nested[a].n > nested[b].n; });
-    hipError_t e = fused_launch(nested.data(), nidx, noffs, work, dtab, s);
+    hipError_t e = fused_launch(nested.data(), nidx, noffs, work, dtab, sn);
     if (e != hipSuccess) return e;
+    if (two && hipEventRecord(ev_nest, sn) != hipSuccess) return hipErrorUnknown;
+    if (refine) {
+        e = copy_kernel(2, st, act, sn);
+        if (e != hipSuccess) return e;
+        if (two && hipEventRecord(ev_cond, sn) != hipSuccess) return hipErrorUnknown;
+    }
+    hipStream_t s = sc;
+    if (before_gather && hipStreamWaitEvent(s, before_gather, 0) != hipSuccess) return hipErrorUnknown;
     // 2. gather V, 3. W^T = P V^T, 4. scatter
-    e = copy_kernel(false, st, act, s);
+    e = copy_kernel(0, st, act, s);
     if (e != hipSuccess) return e;
+    if (two && hipStreamWaitEvent(s, ev_nest, 0) != hipSuccess) return hipErrorUnknown;
     gj.assign(act, GemmJob());
     for (int k = 0; k < act; ++k) {
         const InvertJob &j = jobs[idx[k]];
@@ -606,6 +626,7 @@ hipError_t BlockedRun::chain(int st, hipStream_t s)
         // V - W S is made of small terms and comes out accurately, and W += (V - W S) P removes most of that error
         // (the inverse of a factor with condition number 1e5 goes from useless to the accuracy of an fp32
         // Cholesky inverse).  K-major: R^T = V^T - S W^T, W^T += P R^T.
+        if (two && hipStreamWaitEvent(s, ev_cond, 0) != hipSuccess) return hipErrorUnknown;
         for (int pass = 0; pass < 2; ++pass) {
             for (int k = 0; k < act; ++k) {
                 const InvertJob &j = jobs[idx[k]];
@@ -616,7 +637,8 @@ hipError_t BlockedRun::chain(int st, hipStream_t s)
                 a.B = pass == 0 ? big[k].Wt[st & 1] : big[k].Rt;
                 a.C = pass == 0 ? big[k].Rt : big[k].Wt[st & 1];
                 a.M = bs; a.N = j.n; a.K = bs; a.lda = PB; a.ldb = big[k].ldv; a.ldc = big[k].ldv;
-                a.mode = pass == 0 ? kSubRect : kAddRect; a.p0 = a.p1 = 0; a.doff = 1l << 30;
+                a.mode = pass == 0 ? kSubFrom : kAddRect; a.p0 = a.p1 = 0; a.doff = 1l << 30;
+                if (pass == 0) { a.D = big[k].Vt[st & 1]; a.ldd = big[k].ldv; }
                 a.gate = big[k].ninfo + 1;
                 a.gate_cond = (float)tuning().invert_refine_cond;
             }
@@ -624,7 +646,7 @@ hipError_t BlockedRun::chain(int st, hipStream_t s)
             if (e != hipSuccess) return e;
         }
     }
-    return copy_kernel(true, st, act, s);
+    return copy_kernel(1, st, act, s);
 }
 
 hipError_t BlockedRun::bulk(int st, bool skip_next, hipStream_t s)
@@ -674,9 +696,10 @@ hipError_t BlockedRun::finish(hipStream_t s)
 // Streams and events of the library, per device, created at the first call that needs them (default priority).
 struct AuxStreams {
     static constexpr int kEvents = 64;
-    hipStream_t chain = nullptr, side = nullptr;
+    hipStream_t chain = nullptr, nest = nullptr, side = nullptr;
     hipEvent_t fork = nullptr, side_done = nullptr;
-    hipEvent_t ev_chain[kEvents] = {}, ev_bulk[kEvents] = {};
+    hipEvent_t ev_chain[kEvents] = {}, ev_bulk[kEvents] = {}, ev_look[kEvents] = {}, ev_nest[kEvents] = {},
+               ev_cond[kEvents] = {};
     bool ok = false;
 };
 
@@ -696,12 +719,16 @@ AuxStreams *aux_streams()
     if (a.ok) return &a;
     if (a.chain) return nullptr;     // an earlier attempt failed half way: stay on one stream
     bool good = hipStreamCreateWithFlags(&a.chain, hipStreamNonBlocking) == hipSuccess &&
+                hipStreamCreateWithFlags(&a.nest, hipStreamNonBlocking) == hipSuccess &&
                 hipStreamCreateWithFlags(&a.side, hipStreamNonBlocking) == hipSuccess &&
                 hipEventCreateWithFlags(&a.fork, hipEventDisableTiming) == hipSuccess &&
                 hipEventCreateWithFlags(&a.side_done, hipEventDisableTiming) == hipSuccess;
     for (int i = 0; good && i < AuxStreams::kEvents; ++i)
         good = hipEventCreateWithFlags(&a.ev_chain[i], hipEventDisableTiming) == hipSuccess &&
-               hipEventCreateWithFlags(&a.ev_bulk[i], hipEventDisableTiming) == hipSuccess;
+               hipEventCreateWithFlags(&a.ev_bulk[i], hipEventDisableTiming) == hipSuccess &&
+               hipEventCreateWithFlags(&a.ev_look[i], hipEventDisableTiming) == hipSuccess &&
+               hipEventCreateWithFlags(&a.ev_nest[i], hipEventDisableTiming) == hipSuccess &&
+               hipEventCreateWithFlags(&a.ev_cond[i], hipEventDisableTiming) == hipSuccess;
     if (!good) {
         if (!a.chain) a.chain = reinterpret_cast<hipStream_t>(1);   // marks the failed attempt
         return nullptr;
@@ -715,44 +742,53 @@ hipError_t blocked_serial(BlockedRun &run, hipStream_t s)
 {
     hipError_t e = run.start(s);
     for (int st = 0; st < run.steps && e == hipSuccess; ++st) {
-        e = run.chain(st, s);
+        e = run.chain(st, s, s, nullptr, nullptr, nullptr);
         if (e == hipSuccess) e = run.bulk(st, false, s);
     }
     return e == hipSuccess ? run.finish(s) : e;
 }
 
-// Look-ahead on two streams: updates on the caller's stream `s`, chains on `aux->chain`.
-//   update stream: wait chain(st); look(st) [update st on the band of block st + 1]; record; bulk(st) without that band
-//   chain stream:  wait look(st - 1); chain(st) [pivot inverse, gather, panel product, scatter]; record
-// look(st) is a small product: at the head of the update stream it has the whole chip and is done in a few tens
-// of microseconds, after which chain(st + 1) runs beside bulk(st).  Panels st (buffer st mod 2) are not
-// overwritten before bulk(st) is done: chain(st + 2) waits for look(st + 1), which follows bulk(st) on its stream.
+// Look-ahead on three streams: updates on the caller's stream `s`, nested inversions on `aux->nest`, the rest of
+// the chains on `aux->chain`.
+//   update stream: wait chain(st); look(st, 0) [update st on the diagonal block of band st + 1]; record A;
+//                  look(st, 1) [the rest of the band]; record B; bulk(st) without that band
+//   nest stream:   wait A(st - 1); nested inversion of pivot block st; record N; condition test; record C
+//   chain stream:  wait B(st - 1); gather; wait N; panel product; wait C; refinement; scatter; record
+// The nested inversion, the longest link of the chain, only needs the diagonal block, a product of two tiles per
+// matrix; it runs beside the rest of the band product, the gather and the bulk update.  Panels st (buffer st mod 2)
+// are not overwritten before bulk(st) is done: the gather of step st + 2 waits for B(st + 1), which follows
+// bulk(st) on its stream.  The inverse of pivot block st - 1 is not overwritten before scatter(st - 1) is done:
+// A(st - 1) follows chain(st - 1).
 hipError_t blocked_lookahead(BlockedRun &run, AuxStreams *aux, hipStream_t s)
 {
     hipError_t e = run.start(s);
     if (e != hipSuccess) return e;
-    hipStream_t c = aux->chain;
-    if (hipEventRecord(aux->fork, s) != hipSuccess || hipStreamWaitEvent(c, aux->fork, 0) != hipSuccess)
+    hipStream_t c = aux->chain, nn = aux->nest;
+    if (hipEventRecord(aux->fork, s) != hipSuccess || hipStreamWaitEvent(c, aux->fork, 0) != hipSuccess ||
+        hipStreamWaitEvent(nn, aux->fork, 0) != hipSuccess)
         return hipErrorUnknown;
     bool joined = false;
     for (int st = 0; st < run.steps && e == hipSuccess; ++st) {
         joined = false;
-        e = run.chain(st, c);
+        e = run.chain(st, nn, c, st > 0 ? aux->ev_bulk[st - 1] : nullptr, aux->ev_nest[st], aux->ev_cond[st]);
         if (e == hipSuccess && hipEventRecord(aux->ev_chain[st], c) != hipSuccess) e = hipErrorUnknown;
         if (e == hipSuccess && hipStreamWaitEvent(s, aux->ev_chain[st], 0) != hipSuccess) e = hipErrorUnknown;
         if (e != hipSuccess) break;
-        joined = true;            // everything the chain stream holds so far is ordered before what follows on `s`
+        joined = true;            // everything the other two streams hold so far is ordered before what follows on `s`
         const bool more = st + 1 < run.steps;
         if (more) {
-            e = run.look(st, s);
+            e = run.look(st, 0, s);
+            if (e == hipSuccess && hipEventRecord(aux->ev_look[st], s) != hipSuccess) e = hipErrorUnknown;
+            if (e == hipSuccess && hipStreamWaitEvent(nn, aux->ev_look[st], 0) != hipSuccess) e = hipErrorUnknown;
+            if (e == hipSuccess) e = run.look(st, 1, s);
             if (e == hipSuccess && hipEventRecord(aux->ev_bulk[st], s) != hipSuccess) e = hipErrorUnknown;
-            if (e == hipSuccess && hipStreamWaitEvent(c, aux->ev_bulk[st], 0) != hipSuccess) e = hipErrorUnknown;
         }
         if (e == hipSuccess) e = run.bulk(st, more, s);
     }
     if (!joined) {
-        // after an error the caller's stream must still not run ahead of what the chain stream holds
+        // after an error the caller's stream must still not run ahead of what the other two streams hold
         if (hipEventRecord(aux->ev_chain[0], c) == hipSuccess) (void)hipStreamWaitEvent(s, aux->ev_chain[0], 0);
+        if (hipEventRecord(aux->ev_nest[0], nn) == hipSuccess) (void)hipStreamWaitEvent(s, aux->ev_nest[0], 0);
     }
     return e == hipSuccess ? run.finish(s) : e;
 }

@@ -442,7 +442,7 @@ bool bf16_eligible(const FactorJob &j)
 // competes with: the wave-unit kernel for row-major operands, the slower block-tile kernel for NCHW ones.
 bool split_syrk_eligible(const FactorJob &j)
 {
-    if (!(tuning().use_split_syrk && j.dtype == 0 && j.d_core >= 192)) return false;
+    if (!(tuning().use_split_syrk && j.dtype == 0 && j.d_core >= tuning().split_syrk_min_d)) return false;
     const double fill = 0.5 * j.d_core * (double)j.d_core / ((double)syrk_split_tiles(j.d_core) * S_BM * S_BN);
     if (j.layout == kRows) {
         if (!(j.ld % 4 == 0 && j.ld < (1l << 22))) return false;
