@@ -889,6 +889,7 @@ int kfac_tune(const char *key, long value)
     else if (k == "bf16_rows_copy") t.bf16_rows_copy = value;
     else if (k == "invert_panel_split") t.invert_panel_split = value;
     else if (k == "invert_refine_cond") t.invert_refine_cond = value < 0 ? 0 : value;
+    else if (k == "invert_fused_refine_cond") t.invert_fused_refine_cond = value < 0 ? 0 : value;
     else if (k == "eigen_max_sweeps") t.eigen_max_sweeps = value;
     else if (k == "eigen_inner_sweeps") t.eigen_inner_sweeps = value;
     else if (k == "im2col_piece_elems") t.im2col_piece_elems = value;

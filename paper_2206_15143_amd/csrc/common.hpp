@@ -137,6 +137,7 @@ struct Tuning {
     long bf16_rows_copy = 1;         // bf16 NCHW operands with an odd number of positions: row-major copy first
     long invert_panel_split = 1;     // blocked sweep: panel products on the split-bf16 kernel
     long invert_refine = 1;          // blocked sweep: refinement step of the panel products (see invert.hip) ...
+    long invert_fused_refine_cond = 300;  // the same test for the 64 x 64 pivot blocks of the one-launch-per-step path
     long invert_refine_cond = 3000;  // ... of pivot blocks whose condition number (maximum norm) exceeds this
     long invert_outer_block = 256;   // outer pivot block of the two-level inversion (multiple of 32)
     long invert_border = 1;          // orders 64 k + 1: last row and column by bordering instead of a one-row pivot block

@@ -314,13 +314,18 @@ __global__ __launch_bounds__(256) void sweep_finish_kernel(const InvTable tab)
 
 namespace {
 bool takes_fused(int n) { return n <= tuning().invert_fused_max_n; }
-size_t fused_ws_floats(int n) { return 2 * (size_t)NB * NB + 2 * (size_t)NB * ((n + 3) / 4 * 4); }
+size_t fused_ws_floats(int n) { return 4 * (size_t)NB * NB + 2 * (size_t)NB * ((n + 3) / 4 * 4) + 16; }
 // large matrices: two sets of V, W panels, P, the workspace of the nested pivot-block inversion, its status word
 size_t job_ws_floats(int n)
 {
     if (takes_fused(n)) return fused_ws_floats(n);
     const size_t PB = (size_t)outer_block();
     return 5 * PB * ((n + 3) / 4 * 4) + 2 * PB * PB + fused_ws_floats((int)PB) + 64;
+}
+// the three flags at the end of a matrix's one-launch-per-step workspace: gate of either step parity, sticky flag
+int *fused_gate_ptr(float *ws, int n)
+{
+    return reinterpret_cast<int *>(ws + 4 * (size_t)NB * NB + 2 * (size_t)NB * ((n + 3) / 4 * 4));
 }
 size_t table_bytes(int n) { return align_up((size_t)2 * n * sizeof(InvProbF), 256); }
 
@@ -345,6 +350,8 @@ hipError_t fused_launch(const InvertJob *jobs, const std::vector<int> &idx, cons
             p.ldw = j.ldo > 0 ? j.ldo : j.n;
             p.P = ws;
             p.Vt = ws + 2 * FNB * FNB;
+            p.S = p.Vt + 2 * (size_t)FNB * p.ldv;
+            p.gate = fused_gate_ptr(ws, j.n);
         }
         KFAC_LAUNCH(KFAC_K_INV_INIT, s, inv_upload_kernel, dim3((u.count + 15) / 16), dim3(64), 0, u);
         hipError_t e = hipGetLastError();
@@ -357,6 +364,7 @@ hipError_t fused_launch(const InvertJob *jobs, const std::vector<int> &idx, cons
         q.tab = dtab;
         q.nclass = 0;
         q.step = 0;
+        q.refine_cond = tuning().invert_refine ? (float)tuning().invert_fused_refine_cond : -1.f;
         int c = c0;
         while (c < total && q.nclass < kMaxInvClasses) {
             int e = c;
@@ -810,15 +818,24 @@ hipError_t blocked_launch(const InvertJob *jobs, const std::vector<int> &idx, co
 //     M^-1 = [ X + y y^T / s   -y / s ]
 //            [   -y^T / s       1 / s ],
 // which is the last pivot step of the same sweep (s is its pivot: not positive -> flagged as pivot n).
+// On an ill-conditioned factor b^T y cancels c almost entirely and the error of the computed X makes s useless (a
+// relative error of 0.2 to 1.5 in s at condition numbers of 1e5, emulated and measured).  Where the sweep found an
+// ill-conditioned pivot block (the sticky flag of its gate), the residual r = b - (M_11 + damping I) y is formed and
+//     s = c + damping - b^T y - y^T r        (b^T M_11^-1 b to second order in the error of y)
+//     y <- y + X r
+// which brings the bordered inverse back to the accuracy of X itself.  Elsewhere the two extra kernels return at
+// once and the result is bit for bit what it was without them.
 struct BorderProb {
     const float *M;
     float *W;
-    float *y;          // workspace, n - 1 floats
+    float *y;          // workspace: y, then r, then X r, each n - 1 floats rounded up to 64
+    const int *sticky; // the sweep's flag: some pivot block of this matrix was ill-conditioned
     int *info;
     const float *dptr;
     float damping;
     int n, ldm, ldw;
     int blk_start;
+    int rblk_start;    // first block of the residual kernel (one per 64 rows)
 };
 
 struct BorderTable {
@@ -836,14 +853,21 @@ __device__ __forceinline__ const BorderProb &border_locate(const BorderTable &ta
     return tab.p[pi];
 }
 
-// y = X b: a wavefront per row, lanes along the row
+__device__ __forceinline__ int border_vec_len(int n) { return (n - 1 + 63) / 64 * 64; }
+
+// y = X b (second = 0) or z = X r for the refinement (second = 1: only where the sticky flag is set): a wavefront
+// per row, lanes along the row
+template <int second>
 __global__ __launch_bounds__(256) void border_matvec_kernel(const BorderTable tab)
 {
     __shared__ float bs[1280 + 64];
     int chunk;
     const BorderProb &pr = border_locate(tab, chunk);
+    if (second && *pr.sticky == 0) return;
     const int m = pr.n - 1, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    for (int j = threadIdx.x; j < m; j += 256) bs[j] = pr.M[(long)m * pr.ldm + j];
+    const float *vin = second ? pr.y + border_vec_len(pr.n) : pr.M + (long)m * pr.ldm;
+    float *vout = second ? pr.y + 2 * border_vec_len(pr.n) : pr.y;
+    for (int j = threadIdx.x; j < m; j += 256) bs[j] = vin[j];
     __syncthreads();
     // rows 4 w .. 4 w + 3 of the chunk: rows past the end repeat the last one and are not stored
     const int i0 = chunk * kBorderRows + 4 * w;
@@ -870,7 +894,50 @@ __global__ __launch_bounds__(256) void border_matvec_kernel(const BorderTable ta
         float a = acc[q];
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) a += __shfl_xor(a, o);
-        if (lane == 0 && i0 + q < m) pr.y[i0 + q] = a;
+        if (lane == 0 && i0 + q < m) vout[i0 + q] = a;
+    }
+}
+
+// r = b - (M_11 + damping I) y from the lower triangle of M (the part the inversion may read), where the sticky flag
+// is set.  One workgroup per 64 rows (the order of M_11 is a multiple of 64); the 64 x 64 tiles left of the diagonal
+// are read as they are, those right of it from their mirror images, transposed through LDS.
+__global__ __launch_bounds__(256) void border_resid_kernel(const BorderTable tab)
+{
+    __shared__ float L[64][65];
+    __shared__ float ysh[1280 + 64];
+    __shared__ float part[4][64];
+    int pi = 0;
+    while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].rblk_start) ++pi;
+    const BorderProb &pr = tab.p[pi];
+    if (*pr.sticky == 0) return;
+    const int i0 = ((int)blockIdx.x - pr.rblk_start) * 64;
+    const int m = pr.n - 1, t = threadIdx.x;
+    for (int j = t; j < m; j += 256) ysh[j] = pr.y[j];
+    const int r = t & 63, q = t >> 6;
+    float acc = 0.f;
+    for (int j0 = 0; j0 < m; j0 += 64) {
+        const int R0 = j0 > i0 ? j0 : i0, C0 = j0 > i0 ? i0 : j0;
+        __syncthreads();                       // the last tile has been consumed (and, first trip, ysh is complete)
+        for (int e = t; e < 64 * 64; e += 256) {
+            const int a = e >> 6, b = e & 63;
+            L[a][b] = pr.M[(long)(R0 + a) * pr.ldm + C0 + b];
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int c = 16 * q; c < 16 * q + 16; ++c) {
+            float v;
+            if (j0 < i0) v = L[r][c];
+            else if (j0 > i0) v = L[c][r];
+            else v = c <= r ? L[r][c] : L[c][r];
+            acc = __builtin_fmaf(v, ysh[j0 + c], acc);
+        }
+    }
+    part[q][r] = acc;
+    __syncthreads();
+    if (t < 64) {
+        const float damping = pr.dptr ? *pr.dptr : pr.damping;
+        const float My = part[0][t] + part[1][t] + part[2][t] + part[3][t] + damping * ysh[i0 + t];
+        pr.y[border_vec_len(pr.n) + i0 + t] = pr.M[(long)m * pr.ldm + i0 + t] - My;
     }
 }
 
@@ -882,11 +949,15 @@ __global__ __launch_bounds__(256) void border_update_kernel(const BorderTable ta
     int chunk;
     const BorderProb &pr = border_locate(tab, chunk);
     const int m = pr.n - 1, t = threadIdx.x, lane = t & 63, w = t >> 6;
+    const bool fix = *pr.sticky != 0;          // uniform over the workgroup
+    const float *rv = pr.y + border_vec_len(pr.n), *zv = rv + border_vec_len(pr.n);
     float part = 0.f;
     for (int j = t; j < m; j += 256) {
         const float yj = pr.y[j];
-        ys[j] = yj;
-        part += pr.M[(long)m * pr.ldm + j] * yj;
+        float term = pr.M[(long)m * pr.ldm + j];
+        if (fix) term += rv[j];                 // b^T y + y^T r
+        ys[j] = fix ? yj + zv[j] : yj;
+        part += term * yj;
     }
     red[t] = part;
     __syncthreads();
@@ -942,25 +1013,36 @@ __global__ __launch_bounds__(256) void border_update_kernel(const BorderTable ta
 }
 
 hipError_t border_launch(const InvertJob *jobs, const std::vector<int> &idx, const std::vector<float *> &ybuf,
-                         hipStream_t s)
+                         const std::vector<const int *> &sticky, hipStream_t s)
 {
     for (size_t g0 = 0; g0 < idx.size(); g0 += kMaxProblems) {
         BorderTable tab;
         tab.count = (int)std::min<size_t>(kMaxProblems, idx.size() - g0);
-        int blocks = 0;
+        int blocks = 0, rblocks = 0;
         for (int k = 0; k < tab.count; ++k) {
             const InvertJob &j = jobs[idx[g0 + k]];
             BorderProb &p = tab.p[k];
             p.M = j.M; p.W = j.Minv; p.y = ybuf[g0 + k]; p.info = j.info; p.dptr = j.damping_dev; p.damping = j.damping;
+            p.sticky = sticky[g0 + k];
             p.n = j.n;
             p.ldm = j.ldm > 0 ? j.ldm : j.n;
             p.ldw = j.ldo > 0 ? j.ldo : j.n;
             p.blk_start = blocks;
             blocks += (j.n - 1 + kBorderRows - 1) / kBorderRows;
+            p.rblk_start = rblocks;
+            rblocks += (j.n - 1) / 64;
         }
-        KFAC_LAUNCH(KFAC_K_INV_FINISH, s, border_matvec_kernel, dim3(blocks), dim3(256), 0, tab);
+        KFAC_LAUNCH(KFAC_K_INV_FINISH, s, border_matvec_kernel<0>, dim3(blocks), dim3(256), 0, tab);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
+        if (tuning().invert_refine) {
+            KFAC_LAUNCH(KFAC_K_INV_FINISH, s, border_resid_kernel, dim3(rblocks), dim3(256), 0, tab);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            KFAC_LAUNCH(KFAC_K_INV_FINISH, s, border_matvec_kernel<1>, dim3(blocks), dim3(256), 0, tab);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
         KFAC_LAUNCH(KFAC_K_INV_FINISH, s, border_update_kernel, dim3(blocks), dim3(256), 0, tab);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -973,7 +1055,7 @@ bool takes_border(int n)
 {
     return tuning().invert_border && n > 64 && n % 64 == 1 && takes_fused(n - 1) && n - 1 <= 1280;   // 1280: the LDS vectors of the two kernels
 }
-size_t border_ws_floats(int n) { return takes_border(n) ? (size_t)(n + 63) / 64 * 64 : 0; }
+size_t border_ws_floats(int n) { return takes_border(n) ? 3 * (size_t)((n - 1 + 63) / 64 * 64) : 0; }
 }  // namespace
 
 size_t invert_workspace_bytes(const InvertJob *jobs, int n)
@@ -994,6 +1076,7 @@ hipError_t invert_launch(const InvertJob *jobs_in, int n_all, void *work, size_t
     std::vector<InvertJob> inner(jobs_in, jobs_in + n_all);
     std::vector<int> bordered;
     std::vector<float *> ybuf;
+    std::vector<const int *> sticky;
     for (int i = 0; i < n_all; ++i) {
         offs[i] = off;
         const int n = jobs_in[i].n;
@@ -1003,6 +1086,7 @@ hipError_t invert_launch(const InvertJob *jobs_in, int n_all, void *work, size_t
             inner[i].ldo = jobs_in[i].ldo > 0 ? jobs_in[i].ldo : n;
             bordered.push_back(i);
             ybuf.push_back(reinterpret_cast<float *>(static_cast<char *>(work) + off) + job_ws_floats(n));
+            sticky.push_back(fused_gate_ptr(reinterpret_cast<float *>(static_cast<char *>(work) + off), n - 1) + 2);
         }
         off += align_up((job_ws_floats(n) + border_ws_floats(n)) * sizeof(float), 256);
     }
@@ -1045,7 +1129,7 @@ hipError_t invert_launch(const InvertJob *jobs_in, int n_all, void *work, size_t
     if (side_open) e = run_large();
     if (e == hipSuccess && !fused.empty()) e = fused_launch(jobs, fused, offs, work, dtab, fs);
     // bordered orders of the fused class finish on the same stream
-    if (e == hipSuccess && !bordered.empty()) e = border_launch(jobs_in, bordered, ybuf, fs);
+    if (e == hipSuccess && !bordered.empty()) e = border_launch(jobs_in, bordered, ybuf, sticky, fs);
     if (side_open && hipEventRecord(aux->side_done, fs) != hipSuccess) return hipErrorUnknown;
     if (!side_open && e == hipSuccess) e = run_large();
     // always join the side stream, also after an error

@@ -38,6 +38,9 @@ struct InvProbF {
     float *W;         // working matrix = output [n, n]
     float *P;         // 2 x [64, 64] pivot-block inverses (step parity)
     float *Vt;        // 2 x [64, ldv] K-major panels (step parity)
+    float *S;         // 2 x [64, 64] pivot blocks before their inversion, both triangles (step parity)
+    int *gate;        // 2 flags (step parity): the pivot block is ill-conditioned, refine the panel product;
+                      // a third that stays set once either was (read by the bordering of orders 64 k + 1)
     int *info;
     int n;
     int ldv;          // n rounded up to 4
@@ -67,6 +70,7 @@ struct InvSeq {
     const InvProbF *tab;
     int nclass;
     int step;
+    float refine_cond;   // panel products of pivot blocks whose condition number exceeds this are refined (< 0: never)
     InvClass c[kMaxInvClasses];
 };
 
@@ -220,6 +224,23 @@ __device__ __forceinline__ int sweep64_blocked(float *S, float *Pb, float *Wb, i
     return fail;
 }
 
+// Largest absolute row sum of the leading bs x bs part of a 64 x 64 block in LDS (row pitch `pitch`), the same
+// value in every thread.  scratch: 64 floats of LDS.  Barriers inside: call from all 256 threads.
+__device__ __forceinline__ float block_norm_inf(const float *B, int pitch, int bs, float *scratch, int tid)
+{
+    if (tid < 64) {
+        float a = 0.f;
+        if (tid < bs)
+            for (int j = 0; j < bs; ++j) a += fabsf(B[tid * pitch + j]);
+        scratch[tid] = a;
+    }
+    __syncthreads();
+    float m = 0.f;
+    for (int i = 0; i < 64; ++i) m = fmaxf(m, scratch[i]);
+    __syncthreads();
+    return m;
+}
+
 // Workgroup 0 of a matrix inverts the first pivot block; workgroup r >= 1 copies block r of the first
 // column panel K-major into V[0] (transposed through LDS), so that step 0 stages its panels like any
 // other step.
@@ -256,9 +277,18 @@ __global__ __launch_bounds__(256) void fsweep_pivot0_kernel(const InvSeq q)
             v = pr.M[a * ldm + b] + (a == b ? damping : 0.f);
         }
         sbuf[i * SW_PITCH + j] = v;
+        pr.S[i * FNB + j] = (i < bs && j < bs) ? v : 0.f;
     }
     __syncthreads();
+    const float s_norm = block_norm_inf(sbuf, SW_PITCH, bs, pw, tid);
     const int fail = sweep64_blocked(sbuf, pw, pw + 16 * 17, tid);   // valid in wavefront 0
+    __syncthreads();
+    const float p_norm = block_norm_inf(sbuf, SW_PITCH, bs, pw, tid);
+    if (tid == 0) {
+        const int open = (q.refine_cond >= 0.f && s_norm * p_norm > q.refine_cond) ? 1 : 0;
+        pr.gate[0] = open;
+        pr.gate[2] = open;
+    }
     const bool whole = pr.nblk == 1;   // the block is the matrix: store the result itself, both triangles
     for (int e = tid; e < FNB * FNB; e += 256) {
         const int i = e >> 6, j = e & 63;
@@ -324,6 +354,9 @@ __global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
     const float *Pk = pr.P + (K & 1) * FNB * FNB;
     const float *Vk = pr.Vt + (long)(K & 1) * FNB * ldv;
     float *Pn = pr.P + (K1 & 1) * FNB * FNB;
+    float *Sn = pr.S + (K1 & 1) * FNB * FNB;
+    const float *Sk = pr.S + (K & 1) * FNB * FNB;
+    const bool refine = q.refine_cond >= 0.f && pr.gate[K & 1] != 0;      // uniform over the workgroup
     float *Vn = pr.Vt + (long)(K1 & 1) * FNB * ldv;
     const bool panel = (bi == K) != (bj == K);
     const int ra = panel ? (bi == K ? bj : bi) : bi;   // block whose V goes to Va
@@ -403,6 +436,72 @@ __global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
 #pragma unroll
             for (int tj = 0; tj < T::WT; ++tj)
                 acc[ti][tj] = __builtin_amdgcn_mfma_f32_16x16x4f32(pa[s4][ti], b[tj], acc[ti][tj], 0, 0, 0);
+    }
+
+    if (refine) {
+        // One step of iterative refinement of W = V P for an ill-conditioned pivot block S (see the blocked sweep in
+        // invert.hip for the reason): R^T = V^T - S W^T, W^T += P R^T, two more 64 x 64 x 64 products.  W^T and R^T
+        // pass through the LDS buffer this kind of tile does not need at this point.
+        float sa[FNB / 4][T::WT];
+#pragma unroll
+        for (int s4 = 0; s4 < FNB / 4; ++s4)
+#pragma unroll
+            for (int t2 = 0; t2 < T::WT; ++t2) sa[s4][t2] = Sk[(4 * s4 + lk) * FNB + (wm * T::WT + t2) * 16 + lr];
+        float vt[T::WT][T::WT][4];      // V^T in the layout of the accumulators
+#pragma unroll
+        for (int ti = 0; ti < T::WT; ++ti)
+#pragma unroll
+            for (int tj = 0; tj < T::WT; ++tj)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    vt[ti][tj][v] = Va[((wm * T::WT + ti) * 16 + 4 * lk + v) * PITCH + (wn * T::WT + tj) * 16 + lr];
+        float *X = (panel || diag) ? Vb : Va;
+        __syncthreads();   // every wave is done reading V_a
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+            for (int ti = 0; ti < T::WT; ++ti)
+#pragma unroll
+                for (int tj = 0; tj < T::WT; ++tj)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        X[((wm * T::WT + ti) * 16 + 4 * lk + v) * PITCH + (wn * T::WT + tj) * 16 + lr] =
+                            pass == 0 ? acc[ti][tj][v] : vt[ti][tj][v];
+            __syncthreads();
+            floatx4 r2[T::WT][T::WT];
+#pragma unroll
+            for (int a = 0; a < T::WT; ++a)
+#pragma unroll
+                for (int b = 0; b < T::WT; ++b) r2[a][b] = pass == 0 ? floatx4{0.f, 0.f, 0.f, 0.f} : acc[a][b];
+#pragma unroll
+            for (int s4 = 0; s4 < FNB / 4; ++s4) {
+                float b[T::WT];
+#pragma unroll
+                for (int t2 = 0; t2 < T::WT; ++t2) b[t2] = X[(4 * s4 + lk) * PITCH + (wn * T::WT + t2) * 16 + lr];
+#pragma unroll
+                for (int ti = 0; ti < T::WT; ++ti)
+#pragma unroll
+                    for (int tj = 0; tj < T::WT; ++tj)
+                        r2[ti][tj] = __builtin_amdgcn_mfma_f32_16x16x4f32(pass == 0 ? sa[s4][ti] : pa[s4][ti], b[tj],
+                                                                          r2[ti][tj], 0, 0, 0);
+            }
+            __syncthreads();   // every wave is done reading X
+            if (pass == 0) {
+                // R^T = V^T - S W^T takes the place of V^T
+#pragma unroll
+                for (int ti = 0; ti < T::WT; ++ti)
+#pragma unroll
+                    for (int tj = 0; tj < T::WT; ++tj)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) vt[ti][tj][v] -= r2[ti][tj][v];
+            } else {
+#pragma unroll
+                for (int a = 0; a < T::WT; ++a)
+#pragma unroll
+                    for (int b = 0; b < T::WT; ++b) acc[a][b] = r2[a][b];
+            }
+        }
+        // off-diagonal tiles: V_a now holds R^T, which nothing reads again (W^T goes there next)
     }
 
     if (panel) {
@@ -502,9 +601,18 @@ __global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
             float v = (i == j) ? 1.f : 0.f;
             if (i < bs1 && j < bs1) v = (j <= i) ? Va[i * PITCH + j] : Va[j * PITCH + i];
             Vb[i * SW_PITCH + j] = v;
+            Sn[i * FNB + j] = (i < bs1 && j < bs1) ? v : 0.f;
         }
         __syncthreads();
+        const float s_norm = block_norm_inf(Vb, SW_PITCH, bs1, Va, tid);
         const int fail = sweep64_blocked(Vb, Va, Va + 16 * 17, tid);
+        __syncthreads();
+        const float p_norm = block_norm_inf(Vb, SW_PITCH, bs1, Va, tid);
+        if (tid == 0) {
+            const int open = (q.refine_cond >= 0.f && s_norm * p_norm > q.refine_cond) ? 1 : 0;
+            pr.gate[K1 & 1] = open;
+            if (open) pr.gate[2] = 1;
+        }
         for (int e = tid; e < FNB * FNB; e += 256) {
             const int i = e >> 6, j = e & 63;
             const bool in = (i < bs1 && j < bs1);
