@@ -20,8 +20,8 @@
  *     *_batched calls are HOST arrays of length n, read before the call returns.
  *   - State the library keeps, all of it per process:
  *       * per device, created at the first inversion call that has a factor of order
- *         above 1280 and kept until the process ends: two HIP streams (non-blocking,
- *         default priority) and 194 events (timing disabled).  See kfac_invert.
+ *         above 1280 and kept until the process ends: three HIP streams (non-blocking,
+ *         default priority) and 322 events (timing disabled).  See kfac_invert.
  *       * a mutex that serialises the part of an inversion call that enqueues work on
  *         those streams: inversion calls from several host threads are safe, and
  *         their enqueueing is serialised for that part.
@@ -131,11 +131,12 @@ kfac_status kfac_update_factors(const kfac_layer_desc *desc, const void *d_act, 
  * The inversion works in place in the output buffer: d_A_inv / d_G_inv must not alias the running factors, and
  * the inverse of a factor that is reported as not positive definite holds whatever the elimination had reached
  * (see Conventions); the running factor itself is never modified.
- * Accuracy: fp32 elimination, relative error of the order of a few hundredths of cond(M) * 2^-24.  Above order
- * 1280 the panel products of ill-conditioned pivot blocks are refined once, which keeps the result within a
- * factor two of an fp32 LAPACK Cholesky inverse up to condition numbers of a few 1e5.
+ * Accuracy: fp32 elimination, relative error of the order of a few hundredths of cond(M) * 2^-24.  The panel
+ * products of ill-conditioned pivot blocks are refined once and the bordering step of orders 64 k + 1 corrected
+ * to second order (both decided on the device from the condition number of the pivot block), which keeps the
+ * result within a factor two of an fp32 LAPACK Cholesky inverse up to condition numbers of a few 1e5.
  * Streams: when a call has a factor of order above 1280, part of the work (the short dependent kernels of every
- * elimination step, and the factors of order up to 1280) runs on the two library streams named under
+ * elimination step, and the factors of order up to 1280) runs on the three library streams named under
  * Conventions, forked from and joined back to hip_stream by events inside the call: ordering on hip_stream is
  * as if everything ran there, and the call may be captured into a HIP graph like any other. */
 kfac_status kfac_invert(const kfac_layer_desc *desc, const float *d_A_run, const float *d_G_run,

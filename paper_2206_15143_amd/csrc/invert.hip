@@ -829,7 +829,7 @@ struct BorderProb {
     const float *M;
     float *W;
     float *y;          // workspace: y, then r, then X r, each n - 1 floats rounded up to 64
-    const int *sticky; // the sweep's flag: some pivot block of this matrix was ill-conditioned
+    const int *sticky; // the sweep's flag: some pivot block of this matrix was ill-conditioned (null: refinement off)
     int *info;
     const float *dptr;
     float damping;
@@ -863,7 +863,7 @@ __global__ __launch_bounds__(256) void border_matvec_kernel(const BorderTable ta
     __shared__ float bs[1280 + 64];
     int chunk;
     const BorderProb &pr = border_locate(tab, chunk);
-    if (second && *pr.sticky == 0) return;
+    if (second && (!pr.sticky || *pr.sticky == 0)) return;
     const int m = pr.n - 1, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const float *vin = second ? pr.y + border_vec_len(pr.n) : pr.M + (long)m * pr.ldm;
     float *vout = second ? pr.y + 2 * border_vec_len(pr.n) : pr.y;
@@ -909,7 +909,7 @@ __global__ __launch_bounds__(256) void border_resid_kernel(const BorderTable tab
     int pi = 0;
     while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].rblk_start) ++pi;
     const BorderProb &pr = tab.p[pi];
-    if (*pr.sticky == 0) return;
+    if (!pr.sticky || *pr.sticky == 0) return;
     const int i0 = ((int)blockIdx.x - pr.rblk_start) * 64;
     const int m = pr.n - 1, t = threadIdx.x;
     for (int j = t; j < m; j += 256) ysh[j] = pr.y[j];
@@ -949,7 +949,7 @@ __global__ __launch_bounds__(256) void border_update_kernel(const BorderTable ta
     int chunk;
     const BorderProb &pr = border_locate(tab, chunk);
     const int m = pr.n - 1, t = threadIdx.x, lane = t & 63, w = t >> 6;
-    const bool fix = *pr.sticky != 0;          // uniform over the workgroup
+    const bool fix = pr.sticky && *pr.sticky != 0;          // uniform over the workgroup
     const float *rv = pr.y + border_vec_len(pr.n), *zv = rv + border_vec_len(pr.n);
     float part = 0.f;
     for (int j = t; j < m; j += 256) {
@@ -1023,7 +1023,7 @@ hipError_t border_launch(const InvertJob *jobs, const std::vector<int> &idx, con
             const InvertJob &j = jobs[idx[g0 + k]];
             BorderProb &p = tab.p[k];
             p.M = j.M; p.W = j.Minv; p.y = ybuf[g0 + k]; p.info = j.info; p.dptr = j.damping_dev; p.damping = j.damping;
-            p.sticky = sticky[g0 + k];
+            p.sticky = tuning().invert_refine ? sticky[g0 + k] : nullptr;    // not maintained with the refinement off
             p.n = j.n;
             p.ldm = j.ldm > 0 ? j.ldm : j.n;
             p.ldw = j.ldo > 0 ? j.ldo : j.n;

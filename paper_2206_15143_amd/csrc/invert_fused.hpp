@@ -224,21 +224,17 @@ __device__ __forceinline__ int sweep64_blocked(float *S, float *Pb, float *Wb, i
     return fail;
 }
 
-// Largest absolute row sum of the leading bs x bs part of a 64 x 64 block in LDS (row pitch `pitch`), the same
-// value in every thread.  scratch: 64 floats of LDS.  Barriers inside: call from all 256 threads.
-__device__ __forceinline__ float block_norm_inf(const float *B, int pitch, int bs, float *scratch, int tid)
+// The condition test of a pivot block (largest absolute row sums of the block and of its inverse) rides on the loops
+// that load the block and store its inverse: in those loops thread t visits column t mod 64 in the rows t / 64 + 4 k,
+// so it sums the absolute values it sees (both matrices are symmetric: column sums are row sums), leaves its part
+// in nrm[(t / 64) * 64 + column], and after the next barrier one wavefront folds the four parts of every column and
+// takes the largest.  nrm: 4 * 64 + 2 floats of LDS; the result goes to nrm[256 + slot], read after a later barrier.
+__device__ __forceinline__ void norm_fold(float *nrm, int slot, int lane)
 {
-    if (tid < 64) {
-        float a = 0.f;
-        if (tid < bs)
-            for (int j = 0; j < bs; ++j) a += fabsf(B[tid * pitch + j]);
-        scratch[tid] = a;
-    }
-    __syncthreads();
-    float m = 0.f;
-    for (int i = 0; i < 64; ++i) m = fmaxf(m, scratch[i]);
-    __syncthreads();
-    return m;
+    float a = nrm[lane] + nrm[64 + lane] + nrm[128 + lane] + nrm[192 + lane];
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) a = fmaxf(a, __shfl_xor(a, off));
+    if (lane == 0) nrm[256 + slot] = a;
 }
 
 // Workgroup 0 of a matrix inverts the first pivot block; workgroup r >= 1 copies block r of the first
@@ -248,6 +244,7 @@ __global__ __launch_bounds__(256) void fsweep_pivot0_kernel(const InvSeq q)
 {
     __shared__ __attribute__((aligned(16))) float sbuf[64 * SW_PITCH];
     __shared__ __attribute__((aligned(16))) float pw[16 * 17 + 64 * 17];
+    __shared__ float nrm[4 * 64 + 2];
     float (*tile)[65] = reinterpret_cast<float (*)[65]>(sbuf);
     int prob, local, ci;
     if (!seq_locate(q, blockIdx.x, prob, local, ci)) return;
@@ -269,31 +266,31 @@ __global__ __launch_bounds__(256) void fsweep_pivot0_kernel(const InvSeq q)
     const int bs = min(FNB, pr.n);
     const long ldm = pr.ldm, ldw = pr.ldw;
     const float damping = pr.dptr ? *pr.dptr : pr.damping;
+    const bool test = q.refine_cond >= 0.f;
+    float colsum = 0.f;
     for (int e = tid; e < FNB * FNB; e += 256) {
         const int i = e >> 6, j = e & 63;
         float v = (i == j) ? 1.f : 0.f;
-        if (i < bs && j < bs) {
+        const bool in = i < bs && j < bs;
+        if (in) {
             const int a = max(i, j), b = min(i, j);
             v = pr.M[a * ldm + b] + (a == b ? damping : 0.f);
+            colsum += fabsf(v);
         }
         sbuf[i * SW_PITCH + j] = v;
-        pr.S[i * FNB + j] = (i < bs && j < bs) ? v : 0.f;
+        if (test) pr.S[i * FNB + j] = in ? v : 0.f;
     }
+    nrm[tid] = colsum;
     __syncthreads();
-    const float s_norm = block_norm_inf(sbuf, SW_PITCH, bs, pw, tid);
+    if (test && (tid >> 6) == 1) norm_fold(nrm, 0, tid & 63);       // beside the first in-register sweep of wavefront 0
     const int fail = sweep64_blocked(sbuf, pw, pw + 16 * 17, tid);   // valid in wavefront 0
-    __syncthreads();
-    const float p_norm = block_norm_inf(sbuf, SW_PITCH, bs, pw, tid);
-    if (tid == 0) {
-        const int open = (q.refine_cond >= 0.f && s_norm * p_norm > q.refine_cond) ? 1 : 0;
-        pr.gate[0] = open;
-        pr.gate[2] = open;
-    }
     const bool whole = pr.nblk == 1;   // the block is the matrix: store the result itself, both triangles
+    colsum = 0.f;
     for (int e = tid; e < FNB * FNB; e += 256) {
         const int i = e >> 6, j = e & 63;
         const bool in = (i < bs && j < bs);
         const float v = sbuf[i * SW_PITCH + j];
+        if (in) colsum += fabsf(v);
         pr.P[i * FNB + j] = in ? -v : 0.f;
         if (in && j <= i) {
             pr.W[i * ldw + j] = whole ? -v : v;
@@ -301,6 +298,18 @@ __global__ __launch_bounds__(256) void fsweep_pivot0_kernel(const InvSeq q)
         }
     }
     if (tid == 0) *pr.info = (fail <= bs) ? fail : 0;
+    if (!test) return;
+    nrm[tid] = colsum;
+    __syncthreads();
+    if ((tid >> 6) == 0) {
+        norm_fold(nrm, 1, tid);
+        if (tid == 0) {
+            // (a failed inversion leaves a NaN here: the comparison is false and the block is left alone)
+            const int open = nrm[256] * nrm[257] > q.refine_cond ? 1 : 0;
+            pr.gate[0] = open;
+            pr.gate[2] = open;
+        }
+    }
 }
 
 // One step of the sweep for every tile of every active matrix (see the header of this file).
@@ -312,6 +321,7 @@ __global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
     // not staged: every lane keeps its 32 operand values of P in registers.
     __shared__ __attribute__((aligned(16))) float Va[FNB * PITCH];   // V of the tile's row block (or the panel block)
     __shared__ __attribute__((aligned(16))) float Vb[FNB * PITCH];   // V of the tile's column block, or W^T
+    __shared__ float nrm[4 * 64 + 2];                                // the condition test of the next pivot block
 
     int prob, t, ci;
     if (!seq_locate(q, blockIdx.x, prob, t, ci)) return;
@@ -596,32 +606,45 @@ __global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
     // ---- this workgroup holds the next pivot block: invert it now ----
     __syncthreads();
     {
+        const bool test = q.refine_cond >= 0.f;
+        float colsum = 0.f;
         for (int e = tid; e < FNB * FNB; e += 256) {
             const int i = e >> 6, j = e & 63;
             float v = (i == j) ? 1.f : 0.f;
-            if (i < bs1 && j < bs1) v = (j <= i) ? Va[i * PITCH + j] : Va[j * PITCH + i];
+            const bool in = i < bs1 && j < bs1;
+            if (in) {
+                v = (j <= i) ? Va[i * PITCH + j] : Va[j * PITCH + i];
+                colsum += fabsf(v);
+            }
             Vb[i * SW_PITCH + j] = v;
-            Sn[i * FNB + j] = (i < bs1 && j < bs1) ? v : 0.f;
+            if (test) Sn[i * FNB + j] = in ? v : 0.f;
         }
+        nrm[tid] = colsum;
         __syncthreads();
-        const float s_norm = block_norm_inf(Vb, SW_PITCH, bs1, Va, tid);
+        if (test && (tid >> 6) == 1) norm_fold(nrm, 0, tid & 63);   // beside the first in-register sweep of wavefront 0
         const int fail = sweep64_blocked(Vb, Va, Va + 16 * 17, tid);
-        __syncthreads();
-        const float p_norm = block_norm_inf(Vb, SW_PITCH, bs1, Va, tid);
-        if (tid == 0) {
-            const int open = (q.refine_cond >= 0.f && s_norm * p_norm > q.refine_cond) ? 1 : 0;
-            pr.gate[K1 & 1] = open;
-            if (open) pr.gate[2] = 1;
-        }
+        colsum = 0.f;
         for (int e = tid; e < FNB * FNB; e += 256) {
             const int i = e >> 6, j = e & 63;
             const bool in = (i < bs1 && j < bs1);
             const float v = Vb[i * SW_PITCH + j];
+            if (in) colsum += fabsf(v);
             Pn[i * FNB + j] = in ? -v : 0.f;
             if (in && j <= i) pr.W[(long)(p1 + i) * ldw + p1 + j] = v;
         }
         // launches of one sequence are ordered, so the first failing pivot wins
         if (fail != 0 && fail <= bs1 && tid == 0 && *pr.info == 0) *pr.info = p1 + fail;
+        if (!test) return;
+        nrm[tid] = colsum;
+        __syncthreads();
+        if ((tid >> 6) == 0) {
+            norm_fold(nrm, 1, tid);
+            if (tid == 0) {
+                const int open = nrm[256] * nrm[257] > q.refine_cond ? 1 : 0;
+                pr.gate[K1 & 1] = open;
+                if (open) pr.gate[2] = 1;
+            }
+        }
     }
 }
 
