@@ -312,6 +312,57 @@ def test_inverse_two_level_blocked_path(n):
     assert gu.rel_fro(G_inv.cpu().numpy(), orc.inverse(G.astype(np.float64), lam)) < 1e-4
 
 
+def test_inverse_on_the_library_streams_is_reproducible_and_agrees_with_the_one_stream_run():
+    """The blocked sweep spreads a call over the caller's stream and three of its own (nested inversions, the rest of
+    each step's chain, the smaller factors), ordered by events.  A missing dependency between the streams would
+    make the result depend on timing: the call is repeated and must return the same bits every time.  The one-stream
+    schedule applies the same updates through differently shaped products (no separate band products), so it
+    agrees to rounding, not to the bit.  Mixed batch: orders on both paths, a last block of one row, a bordered
+    order, an ill-conditioned factor whose refinement gates open."""
+    gen = np.random.default_rng(11)
+    orders = [1301, 2049, 1536, 700, 577, 1793, 64, 2304]
+    mats = []
+    for k, n in enumerate(orders):
+        X = np.maximum(gen.standard_normal((n // 2 + 9, n)), 0.0) if k % 2 == 0 else gen.standard_normal((n + 9, n))
+        M = (X.T @ X / X.shape[0]).astype(np.float32)
+        if k == 1:
+            M *= np.float32(40.0)           # condition number of a few 1e4 with the damping below
+        mats.append(gu.to_dev(M))
+    descs = [kf.LayerDesc.linear(n, 8, has_bias=False) for n in orders]
+    G = [torch.eye(8, device=gu.DEV) for _ in orders]
+    ws = gu.workspace(kf.kfac_workspace_bytes_batched(descs, [8] * len(orders), [1] * len(orders), [1] * len(orders)))
+
+    def run():
+        A_inv = [torch.full((n, n), float("nan"), device=gu.DEV) for n in orders]
+        G_inv = [torch.empty((8, 8), device=gu.DEV) for _ in orders]
+        info = torch.full((2 * len(orders),), -1, dtype=torch.int32, device=gu.DEV)
+        kf.kfac_invert_batched(descs, mats, G, 0.02, 0.02, A_inv, G_inv, info, ws)
+        torch.cuda.synchronize()
+        flags = info.cpu().numpy()
+        assert not flags.any(), f"flagged: {flags.reshape(-1, 2)[:, 0].tolist()} for orders {orders}"
+        return A_inv
+
+    kf.kfac_tune("invert_two_streams", 0)
+    try:
+        serial = run()
+    finally:
+        kf.kfac_tune("invert_two_streams", 1)
+    first = run()
+    for rep in range(6):
+        again = run()
+        for n, a, b in zip(orders, first, again):
+            assert torch.equal(a, b), f"order {n}, repetition {rep}: the result depends on the run"
+    for n, a, b in zip(orders, serial, first):
+        diff = float(torch.linalg.norm(a.double() - b.double()) / torch.linalg.norm(a.double()))
+        # (each is within rounding x condition number of the exact inverse: 3.6e-5 apart on the ill-conditioned one)
+        assert diff < 1e-4, f"order {n}: pipelined and one-stream runs differ by {diff:.2e}"
+    # and the one-stream result is right
+    for n, M, X in zip(orders[:3], mats[:3], serial[:3]):
+        Md = M.double() + 0.02 * torch.eye(n, device=gu.DEV, dtype=torch.float64)
+        res = float(torch.linalg.norm(Md @ X.double() - torch.eye(n, device=gu.DEV, dtype=torch.float64))) / n ** 0.5
+        assert res < 1e-3, (n, res)
+
+
 def test_not_positive_definite_in_a_late_block_is_flagged_by_the_blocked_path():
     n = 700
     gen = np.random.default_rng(5)
