@@ -452,11 +452,6 @@ __global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
         // One step of iterative refinement of W = V P for an ill-conditioned pivot block S (see the blocked sweep in
         // invert.hip for the reason): R^T = V^T - S W^T, W^T += P R^T, two more 64 x 64 x 64 products.  W^T and R^T
         // pass through the LDS buffer this kind of tile does not need at this point.
-        float sa[FNB / 4][T::WT];
-#pragma unroll
-        for (int s4 = 0; s4 < FNB / 4; ++s4)
-#pragma unroll
-            for (int t2 = 0; t2 < T::WT; ++t2) sa[s4][t2] = Sk[(4 * s4 + lk) * FNB + (wm * T::WT + t2) * 16 + lr];
         float vt[T::WT][T::WT][4];      // V^T in the layout of the accumulators
 #pragma unroll
         for (int ti = 0; ti < T::WT; ++ti)
@@ -485,14 +480,17 @@ __global__ __launch_bounds__(256) void fsweep_step_kernel(const InvSeq q)
                 for (int b = 0; b < T::WT; ++b) r2[a][b] = pass == 0 ? floatx4{0.f, 0.f, 0.f, 0.f} : acc[a][b];
 #pragma unroll
             for (int s4 = 0; s4 < FNB / 4; ++s4) {
-                float b[T::WT];
+                float b[T::WT], sop[T::WT];     // the operand values of S are read as they are used: this path is rare
 #pragma unroll
-                for (int t2 = 0; t2 < T::WT; ++t2) b[t2] = X[(4 * s4 + lk) * PITCH + (wn * T::WT + t2) * 16 + lr];
+                for (int t2 = 0; t2 < T::WT; ++t2) {
+                    b[t2] = X[(4 * s4 + lk) * PITCH + (wn * T::WT + t2) * 16 + lr];
+                    sop[t2] = pass == 0 ? Sk[(4 * s4 + lk) * FNB + (wm * T::WT + t2) * 16 + lr] : 0.f;
+                }
 #pragma unroll
                 for (int ti = 0; ti < T::WT; ++ti)
 #pragma unroll
                     for (int tj = 0; tj < T::WT; ++tj)
-                        r2[ti][tj] = __builtin_amdgcn_mfma_f32_16x16x4f32(pass == 0 ? sa[s4][ti] : pa[s4][ti], b[tj],
+                        r2[ti][tj] = __builtin_amdgcn_mfma_f32_16x16x4f32(pass == 0 ? sop[ti] : pa[s4][ti], b[tj],
                                                                           r2[ti][tj], 0, 0, 0);
             }
             __syncthreads();   // every wave is done reading X
