@@ -883,7 +883,6 @@ int kfac_tune(const char *key, long value)
     else if (k == "corr3_lds_kb") t.corr3_lds_kb = value;
     else if (k == "invert_border") t.invert_border = value;
     else if (k == "invert_two_streams") t.invert_two_streams = value;
-    else if (k == "invert_two_streams_min") t.invert_two_streams_min = value < 2 ? 2 : value;
     else if (k == "invert_outer_block") t.invert_outer_block = value;
     else if (k == "invert_refine") t.invert_refine = value;
     else if (k == "bf16_rows_copy") t.bf16_rows_copy = value;

@@ -141,8 +141,7 @@ struct Tuning {
     long invert_refine_cond = 3000;  // ... of pivot blocks whose condition number (maximum norm) exceeds this
     long invert_outer_block = 256;   // outer pivot block of the two-level inversion (multiple of 32)
     long invert_border = 1;          // orders 64 k + 1: last row and column by bordering instead of a one-row pivot block
-    long invert_two_streams = 1;     // large matrices in two groups on two streams (small launches of one beside the updates of the other)
-    long invert_two_streams_min = 8; // ... from this many large matrices on
+    long invert_two_streams = 1;     // blocked sweep and smaller factors on the library's streams (look-ahead); 0: everything on the caller's stream
     long corr3_lds_kb = 72;          // LDS budget (both slabs) of the autocorrelation kernel
     long use_corr3 = 1;              // 3x3 convolution factors of 16 / 32 / 64 channels from input autocorrelations
     long invert_fused_max_n = 1280;  // orders up to this take the one-launch-per-step sweep

@@ -286,8 +286,8 @@ def test_inverse_sizes(n):
 
 @pytest.mark.parametrize("n", [130, 288, 289, 400, 577, 700, 1000])
 def test_inverse_two_level_blocked_path(n):
-    # orders above the knob take the two-level blocked sweep (288-row outer blocks, wave-unit GEMM
-    # updates); lowering the knob exercises it at sizes the oracle inverts in a moment
+    # orders above the knob take the two-level blocked sweep (256-row outer blocks, nested pivot inversions, panel
+    # products, rank-256 updates); lowering the knob exercises it at sizes the oracle inverts in a moment
     gen = np.random.default_rng(100 + n)
     X = gen.standard_normal((n + 7, n))
     M = (X.T @ X / (n + 7)).astype(np.float32)
