@@ -239,19 +239,29 @@ __global__ __launch_bounds__(256, 2) void syrk_split_kernel(const SyrkTable tab)
                 if (ti + 2 < 4) read8(buf, S_BM, ca0 + (ti + 2) * 32, xn);
                 const sbf16x8 A1 = __builtin_bit_cast(sbf16x8, c1), A2 = __builtin_bit_cast(sbf16x8, c2),
                               A3 = __builtin_bit_cast(sbf16x8, c3);
-#pragma unroll
-                for (int tj = 0; tj < 2; ++tj) {
-                    const sbf16x8 B1 = __builtin_bit_cast(sbf16x8, b1[tj]), B2 = __builtin_bit_cast(sbf16x8, b2[tj]),
-                                  B3 = __builtin_bit_cast(sbf16x8, b3[tj]);
-                    floatx16 c = acc[ti * 2 + tj];
-                    // smallest terms first
-                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A2, B2, c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A3, B1, c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A1, B3, c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A2, B1, c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A1, B2, c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A1, B1, c, 0, 0, 0);
-                    acc[ti * 2 + tj] = c;
+                {
+                    // Smallest terms first.  The two column tiles alternate: an MFMA that accumulates into the result of the one
+                    // just before it waits for that result (a single chain reaches 67 % of the rate of two, measured), and the
+                    // order of the six terms of each accumulator is what fixes the bits, not the interleaving.
+                    const sbf16x8 P1 = __builtin_bit_cast(sbf16x8, b1[0]), P2 = __builtin_bit_cast(sbf16x8, b2[0]),
+                                  P3 = __builtin_bit_cast(sbf16x8, b3[0]);
+                    const sbf16x8 Q1 = __builtin_bit_cast(sbf16x8, b1[1]), Q2 = __builtin_bit_cast(sbf16x8, b2[1]),
+                                  Q3 = __builtin_bit_cast(sbf16x8, b3[1]);
+                    floatx16 c = acc[ti * 2], d = acc[ti * 2 + 1];
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A2, P2, c, 0, 0, 0);
+                    d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A2, Q2, d, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A3, P1, c, 0, 0, 0);
+                    d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A3, Q1, d, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A1, P3, c, 0, 0, 0);
+                    d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A1, Q3, d, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A2, P1, c, 0, 0, 0);
+                    d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A2, Q1, d, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A1, P2, c, 0, 0, 0);
+                    d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A1, Q2, d, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A1, P1, c, 0, 0, 0);
+                    d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A1, Q1, d, 0, 0, 0);
+                    acc[ti * 2] = c;
+                    acc[ti * 2 + 1] = d;
                 }
                 if (ti + 1 < 4) {
 #pragma unroll
