@@ -50,7 +50,7 @@ struct InvProbF {
     const float *dptr; // device-side damping (overrides `damping` when not null)
 };
 
-constexpr int kInvUploadMax = 224;   // descriptors per upload launch (a 16 KB kernel argument)
+constexpr int kInvUploadMax = 224;   // descriptors per upload launch (a 20 KB kernel argument)
 
 struct InvUpload {
     InvProbF *dst;
