@@ -152,7 +152,11 @@ kfac_status kfac_invert_pi(const kfac_layer_desc *desc, const float *d_A_run, co
                            float *d_A_inv, float *d_G_inv, int *d_info, float *d_damping, void *d_work,
                            size_t work_bytes, void *hip_stream);
 
-/* P = G_inv * grad * A_inv (Eq. 5 / right-hand side of Eq. 12).  d_out may alias d_grad. */
+/* P = G_inv * grad * A_inv (Eq. 5 / right-hand side of Eq. 12).  d_out may alias d_grad.  The workspace holds
+ * the d_A x d_G intermediate of every layer; with the size kfac_workspace_bytes reports there is also room for
+ * partial products, and a call of few, deep products (orders above about 1800) then computes each in K slices
+ * that are summed in a fixed order (same result on every call; it differs in the last bits from the result of
+ * a call whose workspace has room for the intermediates only, which computes every product in one piece). */
 kfac_status kfac_precondition(const kfac_layer_desc *desc, const float *d_A_inv, const float *d_G_inv,
                               const float *d_grad, float *d_out, void *d_work, size_t work_bytes,
                               void *hip_stream);
@@ -164,7 +168,9 @@ kfac_status kfac_precondition(const kfac_layer_desc *desc, const float *d_A_inv,
  * d_A * d_G * 4 > KFAC_STATIC_SCRATCH_BYTES is rejected with KFAC_ERR_TOO_LARGE before any launch.  Every
  * call on a GPU shares that GPU's buffer: calls that may overlap on one GPU (different streams, different
  * host threads) race and must be ordered by the caller.  Nothing in the buffer needs clearing between calls
- * (the first product overwrites all of what the second reads).  Arguments as kfac_precondition. */
+ * (the first product overwrites all of what the second reads).  Every product is computed in one piece (no K
+ * slices): the result equals kfac_precondition's bit for bit for a layer that call does not slice, and to
+ * rounding otherwise.  Arguments as kfac_precondition. */
 #define KFAC_STATIC_SCRATCH_BYTES (32u << 20)
 kfac_status kfac_precondition_static(const kfac_layer_desc *desc, const float *d_A_inv, const float *d_G_inv,
                                      const float *d_grad, float *d_out, void *hip_stream);

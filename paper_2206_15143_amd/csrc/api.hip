@@ -332,7 +332,8 @@ size_t invert_ws_total(int n, const kfac_layer_desc *descs)
     return align_up(invert_ws(n, descs), 256) + align_up((size_t)2 * n * sizeof(float), 256);
 }
 
-size_t precond_ws(int n, const kfac_layer_desc *descs)
+// the intermediates U^T [d_A, d_G] of kfac_precondition_batched, one per layer
+size_t precond_ws_min(int n, const kfac_layer_desc *descs)
 {
     size_t total = 0;
     for (int i = 0; i < n; ++i) {
@@ -340,6 +341,30 @@ size_t precond_ws(int n, const kfac_layer_desc *descs)
         total += align_up(dA * dG * sizeof(float), 256);
     }
     return total;
+}
+
+// the two products of layer i: U^T = grad^T G_inv, P = (U^T)^T A_inv (pointers may be null: shapes only)
+void precond_jobs(const kfac_layer_desc &d, const float *A_inv, const float *G_inv, const float *grad, float *out,
+                  float *Ut, GemmJob &a, GemmJob &b)
+{
+    const int dA = core_dim(&d) + d.has_bias, dG = d.d_out;
+    // U^T[dA, dG] = grad^T G_inv  (G_inv symmetric): A = grad, B = G_inv, both K-major over d_G
+    a = GemmJob{};
+    a.A = grad; a.B = G_inv; a.C = Ut;
+    a.M = dA; a.N = dG; a.K = dG; a.lda = dA; a.ldb = dG; a.ldc = dG; a.mode = kStore; a.p0 = a.p1 = 0;
+    // P[dG, dA] = (U^T)^T A_inv
+    b = GemmJob{};
+    b.A = Ut; b.B = A_inv; b.C = out;
+    b.M = dG; b.N = dA; b.K = dA; b.lda = dG; b.ldb = dA; b.ldc = dA; b.mode = kStore; b.p0 = b.p1 = 0;
+}
+
+// ... plus room for the K-slice partials of the deeper of the two groups of products
+size_t precond_ws(int n, const kfac_layer_desc *descs)
+{
+    std::vector<GemmJob> g1(n), g2(n);
+    for (int i = 0; i < n; ++i) precond_jobs(descs[i], nullptr, nullptr, nullptr, nullptr, nullptr, g1[i], g2[i]);
+    return precond_ws_min(n, descs) + align_up(std::max(gemm_workspace_bytes(g1.data(), n),
+                                                        gemm_workspace_bytes(g2.data(), n)), 256);
 }
 
 std::vector<EigenJob> eigen_jobs(int n, const kfac_layer_desc *descs, const float *const *A, const float *const *G,
@@ -600,25 +625,21 @@ kfac_status kfac_precondition_batched(int n, const kfac_layer_desc *descs, const
             return KFAC_ERR_ALIGN;
     }
     if (!aligned(d_work, 256)) return KFAC_ERR_ALIGN;
-    if (precond_ws(n, descs) > work_bytes) return KFAC_ERR_WORKSPACE;
+    // the intermediates are required; the K-slice partials behind them are used when there is room for them
+    if (precond_ws_min(n, descs) > work_bytes) return KFAC_ERR_WORKSPACE;
     std::vector<GemmJob> g1(n), g2(n);
     size_t off = 0;
     for (int i = 0; i < n; ++i) {
-        const int dA = core_dim(&descs[i]) + descs[i].has_bias, dG = descs[i].d_out;
+        const size_t dA = (size_t)core_dim(&descs[i]) + descs[i].has_bias, dG = descs[i].d_out;
         float *Ut = reinterpret_cast<float *>(static_cast<char *>(d_work) + off);
-        off += align_up((size_t)dA * dG * sizeof(float), 256);
-        // U^T[dA, dG] = grad^T G_inv  (G_inv symmetric): A = grad, B = G_inv, both K-major over d_G
-        GemmJob &a = g1[i];
-        a.A = d_grad[i]; a.B = d_G_inv[i]; a.C = Ut;
-        a.M = dA; a.N = dG; a.K = dG; a.lda = dA; a.ldb = dG; a.ldc = dG; a.mode = kStore; a.p0 = a.p1 = 0;
-        // P[dG, dA] = (U^T)^T A_inv
-        GemmJob &b = g2[i];
-        b.A = Ut; b.B = d_A_inv[i]; b.C = d_out[i];
-        b.M = dG; b.N = dA; b.K = dA; b.lda = dG; b.ldb = dA; b.ldc = dA; b.mode = kStore; b.p0 = b.p1 = 0;
+        off += align_up(dA * dG * sizeof(float), 256);
+        precond_jobs(descs[i], d_A_inv[i], d_G_inv[i], d_grad[i], d_out[i], Ut, g1[i], g2[i]);
     }
+    void *slices = static_cast<char *>(d_work) + off;
+    const size_t slice_bytes = work_bytes - off;
     hipStream_t s = (hipStream_t)hip_stream;
-    if (gemm_launch(g1.data(), n, s) != hipSuccess) return KFAC_ERR_HIP;
-    if (gemm_launch(g2.data(), n, s) != hipSuccess) return KFAC_ERR_HIP;
+    if (gemm_launch(g1.data(), n, s, slices, slice_bytes) != hipSuccess) return KFAC_ERR_HIP;
+    if (gemm_launch(g2.data(), n, s, slices, slice_bytes) != hipSuccess) return KFAC_ERR_HIP;
     return KFAC_OK;
 }
 
@@ -765,8 +786,9 @@ kfac_status kfac_precondition_static(const kfac_layer_desc *d, const float *d_A_
     if (st != KFAC_OK) return st;
     // the intermediate U^T [d_A, d_G] is written in full by the first product before the second reads it:
     // nothing in the buffer has to start at zero
-    return kfac_precondition_batched(1, d, &d_A_inv, &d_G_inv, &d_grad, &d_out, ptr, KFAC_STATIC_SCRATCH_BYTES,
-                                     hip_stream);
+    // (the size passed is that of the intermediate alone: no K-slice partials, every product in one piece)
+    return kfac_precondition_batched(1, d, &d_A_inv, &d_G_inv, &d_grad, &d_out, ptr,
+                                     align_up(dA * dG * sizeof(float), 256), hip_stream);
 }
 
 const char *kfac_status_string(kfac_status s)
@@ -876,6 +898,7 @@ int kfac_tune(const char *key, long value)
     else if (k == "fuse_conv3") t.fuse_conv3 = value;
     else if (k == "fuse_conv3_max_c") t.fuse_conv3_max_c = value;
     else if (k == "split_gemm_min_k") t.split_gemm_min_k = value;
+    else if (k == "gemm_kslice_stages") t.gemm_kslice_stages = value;
     else if (k == "update_bm") t.update_bm = value;
     else if (k == "use_small_kernel") t.use_small_kernel = value;
     else if (k == "invert_fused_max_n") t.invert_fused_max_n = value;

@@ -107,7 +107,10 @@ hipError_t invert_launch(const InvertJob *jobs, int n, void *work, size_t work_b
 hipError_t pi_damping_launch(const float *const *A, const float *const *G, const int *dA, const int *dG, int n,
                              float gamma, float *lam, hipStream_t s);
 
-hipError_t gemm_launch(const GemmJob *jobs, int n, hipStream_t s);
+// `work` (optional): room for the K-slice partials of deep products, gemm_workspace_bytes(jobs, n) bytes; without
+// it (or with less) every product is computed in one piece
+hipError_t gemm_launch(const GemmJob *jobs, int n, hipStream_t s, void *work = nullptr, size_t work_bytes = 0);
+size_t gemm_workspace_bytes(const GemmJob *jobs, int n);
 
 hipError_t im2col_launch(const Im2colJob *jobs, int n, hipStream_t s);
 // whether the patch kernel can stage one output row (Wo outputs) of its narrowest channel chunk in LDS
@@ -158,7 +161,8 @@ struct Tuning {
     long use_split_gemm = 1;         // large A^T B products as six bf16 MFMA products of the operands' bf16 pieces
     long split_gemm_min_m = 192;     // ... from this many output rows on
     long split_gemm_min_k = 1024;     // ... and this depth (stores only)
-    long split_gemm_min_fill = 70;   // ... when the product fills at least this percentage of its 256 x 128 tiles
+    long split_gemm_min_fill = 60;   // ... when the product fills at least this percentage of its 256 x 128 tiles
+    long gemm_kslice_stages = 75;    // ... deep stores of a call with few tiles: K slices of about this many stages (0 = never)
     long use_small_kernel = 1;       // direct MFMA kernel for narrow NCHW operands (d <= 64)
     long fuse_conv3 = 1;             // 3x3/s1/p1 fp32 convs: build A straight from the NCHW input
     long fuse_conv3_max_c = 64;      // ... up to this many input channels (wider ones: patch matrix + split-bf16 kernel)

@@ -350,7 +350,140 @@ hipError_t split_gemm_launch(const GemmJob *jobs, const std::vector<int> &idx, h
 }
 }  // namespace
 
-hipError_t gemm_launch(const GemmJob *jobs, int n, hipStream_t s)
+namespace {
+// K slices of deep products.  A call with few 256 x 128 tiles, some of them hundreds of K stages deep, leaves most
+// compute units with one long workgroup and nothing to pack beside it (three 512 x 4609 x 4609 products: 222 tiles
+// of 289 stages on 256 units).  Such a product is cut into K slices: slice 0 stores into C, the others into
+// partial matrices in the workspace, and a reduction adds them to C in slice order (a fixed order: the result
+// does not depend on the schedule).  The partials are M x N, small beside the K x N operand that is read.
+constexpr int kMaxKSlices = 8;
+
+int kslice_count(const GemmJob &j, long split_tiles)
+{
+    const long cap = tuning().gemm_kslice_stages;
+    if (cap <= 0 || split_tiles >= 1024) return 1;     // enough tiles to keep every unit busy as it is
+    if (j.mode != kStore || j.gate || j.wide_tiles) return 1;
+    const long stages = (j.K + S_KT - 1) / S_KT;
+    if (2 * stages <= 3 * cap) return 1;
+    return (int)std::min<long>(kMaxKSlices, (stages + cap - 1) / cap);
+}
+
+// slices per job (1 = as it is); returns the floats of partial matrices needed
+size_t plan_kslices(const GemmJob *jobs, int n, std::vector<int> &ks)
+{
+    ks.assign(n, 1);
+    long tiles = 0;
+    for (int i = 0; i < n; ++i)
+        if (jobs[i].M > 0 && jobs[i].N > 0 && jobs[i].K > 0 && split_gemm_eligible(jobs[i]))
+            tiles += (long)((jobs[i].M + S_BM - 1) / S_BM) * ((jobs[i].N + S_BN - 1) / S_BN);
+    size_t floats = 0;
+    for (int i = 0; i < n; ++i) {
+        if (!(jobs[i].M > 0 && jobs[i].N > 0 && jobs[i].K > 0) || !split_gemm_eligible(jobs[i])) continue;
+        ks[i] = kslice_count(jobs[i], tiles);
+        floats += (size_t)(ks[i] - 1) * align_up((size_t)jobs[i].M * jobs[i].N, 64);
+    }
+    return floats;
+}
+
+struct KRedProb {
+    float *C;
+    const float *P;      // first partial; the next ones follow at `stride` floats
+    long ldc, stride;
+    int M, N, parts;
+    int blk_start;
+};
+
+struct KRedTable {
+    int count;
+    KRedProb p[kMaxProblems];
+};
+
+// C += P_1 + P_2 + ... (in this order); one thread per four consecutive entries of a row
+__global__ __launch_bounds__(256) void gemm_kreduce_kernel(const KRedTable tab)
+{
+    int pi = 0;
+    while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].blk_start) ++pi;
+    const KRedProb &pr = tab.p[pi];
+    const int n4 = (pr.N + 3) / 4;
+    const long item = (long)(blockIdx.x - pr.blk_start) * 256 + threadIdx.x;
+    if (item >= (long)pr.M * n4) return;
+    const int m = (int)(item / n4), c0 = (int)(item - (long)m * n4) * 4;
+    float *c = pr.C + (long)m * pr.ldc + c0;
+    const float *q = pr.P + (long)m * pr.N + c0;
+    const int cnt = min(4, pr.N - c0);
+    float acc[4];
+    for (int e = 0; e < cnt; ++e) acc[e] = c[e];
+    for (int t = 0; t < pr.parts; ++t, q += pr.stride)
+        for (int e = 0; e < cnt; ++e) acc[e] += q[e];
+    for (int e = 0; e < cnt; ++e) c[e] = acc[e];
+}
+
+hipError_t gemm_launch_plain(const GemmJob *jobs, int n, hipStream_t s);
+}  // namespace
+
+size_t gemm_workspace_bytes(const GemmJob *jobs, int n)
+{
+    std::vector<int> ks;
+    return plan_kslices(jobs, n, ks) * sizeof(float);
+}
+
+hipError_t gemm_launch(const GemmJob *jobs, int n, hipStream_t s, void *work, size_t work_bytes)
+{
+    std::vector<int> ks;
+    const size_t need = (work != nullptr) ? plan_kslices(jobs, n, ks) * sizeof(float) : 0;
+    if (need == 0 || need > work_bytes) return gemm_launch_plain(jobs, n, s);
+    std::vector<GemmJob> v;
+    std::vector<KRedProb> red;
+    float *part = static_cast<float *>(work);
+    for (int i = 0; i < n; ++i) {
+        const GemmJob &j = jobs[i];
+        if (ks[i] <= 1) {
+            v.push_back(j);
+            continue;
+        }
+        const long stages = (j.K + S_KT - 1) / S_KT;
+        const long per = (stages + ks[i] - 1) / ks[i] * S_KT;      // rows of K per slice
+        const size_t stride = align_up((size_t)j.M * j.N, 64);
+        int made = 0;
+        for (long k0 = 0; k0 < j.K; k0 += per, ++made) {
+            GemmJob t = j;
+            t.A = j.A + k0 * j.lda;
+            t.B = j.B + k0 * j.ldb;
+            t.K = (int)std::min<long>(per, j.K - k0);
+            t.wide_tiles = true;            // a slice stays on the split-bf16 kernel whatever its depth
+            if (made > 0) {
+                t.C = part + (size_t)(made - 1) * stride;
+                t.ldc = j.N;
+            }
+            v.push_back(t);
+        }
+        KRedProb r;
+        r.C = j.C; r.P = part; r.ldc = j.ldc; r.stride = (long)stride; r.M = j.M; r.N = j.N; r.parts = made - 1;
+        r.blk_start = 0;
+        if (r.parts > 0) red.push_back(r);
+        part += (size_t)(ks[i] - 1) * stride;
+    }
+    hipError_t e = gemm_launch_plain(v.data(), (int)v.size(), s);
+    if (e != hipSuccess) return e;
+    for (size_t g0 = 0; g0 < red.size(); g0 += kMaxProblems) {
+        KRedTable tab;
+        tab.count = (int)std::min<size_t>(kMaxProblems, red.size() - g0);
+        long blocks = 0;
+        for (int k = 0; k < tab.count; ++k) {
+            tab.p[k] = red[g0 + k];
+            tab.p[k].blk_start = (int)blocks;
+            blocks += ((long)tab.p[k].M * ((tab.p[k].N + 3) / 4) + 255) / 256;
+        }
+        KFAC_LAUNCH(KFAC_K_GEMM, s, gemm_kreduce_kernel, dim3((unsigned)blocks), dim3(256), 0, tab);
+        timing_work(0.0, 0.0);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+namespace {
+hipError_t gemm_launch_plain(const GemmJob *jobs, int n, hipStream_t s)
 {
     std::vector<int> cfg(n);
     std::vector<int> wave, split;
@@ -460,5 +593,7 @@ hipError_t gemm_launch(const GemmJob *jobs, int n, hipStream_t s)
     }
     return hipSuccess;
 }
+
+}  // namespace
 
 }  // namespace kfac

@@ -455,6 +455,43 @@ def test_two_sided_product_shapes(dA, dG):
     assert gu.rel_fro(out.cpu().numpy(), ref) < 1e-5
 
 
+@pytest.mark.parametrize("dA,dG", [(2401, 256), (3000, 2100)])
+def test_two_sided_product_with_k_slices(dA, dG):
+    # a call of few tiles with deep products: they are cut into K slices (partials in the workspace, summed in
+    # slice order), ragged last slice included; with room for the intermediate only, or with the slices
+    # switched off, every product is computed in one piece -- the same result to rounding
+    gen = np.random.default_rng(31 * dA + dG)
+    A_inv = gen.standard_normal((dA, dA)).astype(np.float32)
+    A_inv = ((A_inv + A_inv.T) / 2).astype(np.float32)
+    G_inv = gen.standard_normal((dG, dG)).astype(np.float32)
+    G_inv = ((G_inv + G_inv.T) / 2).astype(np.float32)
+    grad = gen.standard_normal((dG, dA)).astype(np.float32)
+    desc = kf.LayerDesc.linear(dA, dG, has_bias=False)
+    full = kf.kfac_workspace_bytes(desc, 8)
+    least = (dA * dG * 4 + 255) // 256 * 256
+    assert full >= least + dA * dG * 4, "no room for K-slice partials was planned"
+    dev = [gu.to_dev(x) for x in (A_inv, G_inv, grad)]
+    ref = G_inv.astype(np.float64) @ grad.astype(np.float64) @ A_inv.astype(np.float64)
+
+    def run(nbytes):
+        out = torch.full((dG, dA), float("nan"), device=gu.DEV)
+        kf.kfac_precondition(desc, dev[0], dev[1], dev[2], out, gu.workspace(nbytes))
+        torch.cuda.synchronize()
+        return out.cpu().numpy()
+    sliced, again, one_piece = run(full), run(full), run(least)
+    kf.kfac_tune("gemm_kslice_stages", 0)
+    try:
+        off = run(full)
+    finally:
+        kf.kfac_tune("gemm_kslice_stages", 75)
+    assert gu.rel_fro(sliced, ref) < 1e-5
+    assert gu.rel_fro(one_piece, ref) < 1e-5
+    assert np.array_equal(sliced, again), "the sliced product is not reproducible"
+    assert np.array_equal(one_piece, off)
+    assert not np.array_equal(sliced, one_piece), "the slices were not used"
+    assert gu.rel_fro(sliced, one_piece.astype(np.float64)) < 2e-6
+
+
 def test_not_positive_definite_is_flagged():
     n = 70
     M = np.eye(n, dtype=np.float32)
