@@ -899,6 +899,7 @@ int kfac_tune(const char *key, long value)
     else if (k == "fuse_conv3_max_c") t.fuse_conv3_max_c = value;
     else if (k == "split_gemm_min_k") t.split_gemm_min_k = value;
     else if (k == "gemm_kslice_stages") t.gemm_kslice_stages = value;
+    else if (k == "invert_border_refine") t.invert_border_refine = value;
     else if (k == "update_bm") t.update_bm = value;
     else if (k == "use_small_kernel") t.use_small_kernel = value;
     else if (k == "invert_fused_max_n") t.invert_fused_max_n = value;

@@ -143,6 +143,7 @@ struct Tuning {
     long invert_fused_refine_cond = 300;  // the same test for the 64 x 64 pivot blocks of the one-launch-per-step path
     long invert_refine_cond = 3000;  // ... of pivot blocks whose condition number (maximum norm) exceeds this
     long invert_outer_block = 256;   // outer pivot block of the two-level inversion (multiple of 32)
+    long invert_border_refine = 2;   // ... its refinement step: 2 always, 1 only where the sweep met an ill-conditioned pivot block
     long invert_border = 1;          // orders 64 k + 1: last row and column by bordering instead of a one-row pivot block
     long invert_two_streams = 1;     // blocked sweep and smaller factors on the library's streams (look-ahead); 0: everything on the caller's stream
     long corr3_lds_kb = 72;          // LDS budget (both slabs) of the autocorrelation kernel

@@ -819,17 +819,20 @@ hipError_t blocked_launch(const InvertJob *jobs, const std::vector<int> &idx, co
 //            [   -y^T / s       1 / s ],
 // which is the last pivot step of the same sweep (s is its pivot: not positive -> flagged as pivot n).
 // On an ill-conditioned factor b^T y cancels c almost entirely and the error of the computed X makes s useless (a
-// relative error of 0.2 to 1.5 in s at condition numbers of 1e5, emulated and measured).  Where the sweep found an
-// ill-conditioned pivot block (the sticky flag of its gate), the residual r = b - (M_11 + damping I) y is formed and
+// relative error of 0.2 to 1.5 in s at condition numbers of 1e5, emulated and measured), and at condition numbers of
+// a few thousand the bordered inverse still carries ten times the error of X (3e-5 to 1e-4 against 4e-6 at order 577,
+// condition 6e3, measured).  So the residual r = b - (M_11 + damping I) y is formed and
 //     s = c + damping - b^T y - y^T r        (b^T M_11^-1 b to second order in the error of y)
 //     y <- y + X r
-// which brings the bordered inverse back to the accuracy of X itself.  Elsewhere the two extra kernels return at
-// once and the result is bit for bit what it was without them.
+// which brings the bordered inverse back to the accuracy of X itself: two more passes over an n x n matrix.  With
+// invert_border_refine = 1 this is done only where the sweep found an ill-conditioned pivot block (the sticky flag
+// of its gate): elsewhere the two extra kernels return at once.
 struct BorderProb {
     const float *M;
     float *W;
     float *y;          // workspace: y, then r, then X r, each n - 1 floats rounded up to 64
     const int *sticky; // the sweep's flag: some pivot block of this matrix was ill-conditioned (null: refinement off)
+    int always;        // refine whatever the flag says
     int *info;
     const float *dptr;
     float damping;
@@ -863,7 +866,7 @@ __global__ __launch_bounds__(256) void border_matvec_kernel(const BorderTable ta
     __shared__ float bs[1280 + 64];
     int chunk;
     const BorderProb &pr = border_locate(tab, chunk);
-    if (second && (!pr.sticky || *pr.sticky == 0)) return;
+    if (second && (!pr.sticky || (!pr.always && *pr.sticky == 0))) return;
     const int m = pr.n - 1, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const float *vin = second ? pr.y + border_vec_len(pr.n) : pr.M + (long)m * pr.ldm;
     float *vout = second ? pr.y + 2 * border_vec_len(pr.n) : pr.y;
@@ -909,7 +912,7 @@ __global__ __launch_bounds__(256) void border_resid_kernel(const BorderTable tab
     int pi = 0;
     while (pi + 1 < tab.count && (int)blockIdx.x >= tab.p[pi + 1].rblk_start) ++pi;
     const BorderProb &pr = tab.p[pi];
-    if (!pr.sticky || *pr.sticky == 0) return;
+    if (!pr.sticky || (!pr.always && *pr.sticky == 0)) return;
     const int i0 = ((int)blockIdx.x - pr.rblk_start) * 64;
     const int m = pr.n - 1, t = threadIdx.x;
     for (int j = t; j < m; j += 256) ysh[j] = pr.y[j];
@@ -949,7 +952,7 @@ __global__ __launch_bounds__(256) void border_update_kernel(const BorderTable ta
     int chunk;
     const BorderProb &pr = border_locate(tab, chunk);
     const int m = pr.n - 1, t = threadIdx.x, lane = t & 63, w = t >> 6;
-    const bool fix = pr.sticky && *pr.sticky != 0;          // uniform over the workgroup
+    const bool fix = pr.sticky && (pr.always || *pr.sticky != 0);          // uniform over the workgroup
     const float *rv = pr.y + border_vec_len(pr.n), *zv = rv + border_vec_len(pr.n);
     float part = 0.f;
     for (int j = t; j < m; j += 256) {
@@ -1024,6 +1027,7 @@ hipError_t border_launch(const InvertJob *jobs, const std::vector<int> &idx, con
             BorderProb &p = tab.p[k];
             p.M = j.M; p.W = j.Minv; p.y = ybuf[g0 + k]; p.info = j.info; p.dptr = j.damping_dev; p.damping = j.damping;
             p.sticky = tuning().invert_refine ? sticky[g0 + k] : nullptr;    // not maintained with the refinement off
+            p.always = tuning().invert_border_refine >= 2;
             p.n = j.n;
             p.ldm = j.ldm > 0 ? j.ldm : j.n;
             p.ldw = j.ldo > 0 ? j.ldo : j.n;

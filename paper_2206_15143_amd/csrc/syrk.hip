@@ -252,6 +252,71 @@ __device__ __forceinline__ void syrk_reduce_body(const SyrkProb &pr, int local, 
     constexpr int CPT = (TILE + kRedChunk - 1) / kRedChunk;   // chunks per tile
 
     constexpr int GPT = (CPT + kRedGroup - 1) / kRedGroup;    // blocks per tile
+    if constexpr (T::BM == 256 && !NATIVE) {
+        // 256-wide tiles (the bf16 MFMA kernels: the factors with the most slices).  The kRedGroup sub-tiles of a
+        // block lie side by side, 16 rows x 64 columns of the tile: thread t takes four consecutive columns of
+        // row t / 16, so a slice is read with 16 bytes per lane and 256 contiguous bytes per row, eight slices
+        // in flight.  (The partial tiles are allocated whole: a vector that straddles the diagonal or the edge
+        // of the factor reads defined or stale words, and only live elements are used.)
+        if (local < nblk * GPT) {
+            static_assert(kRedGroup == 4 && kRedChunk == 256, "the strip of a block is 16 x 64");
+            float(*tr)[65] = reinterpret_cast<float(*)[65]>(&mir[0][0][0]);    // 16 x 65 <= 4 x 16 x 17
+            const int tile = local / GPT;
+            const int grp = local - tile * GPT;
+            int bi, bj;
+            tri_decode(tile, bi, bj);
+            const float *src = pr.partial + (long)tile * TILE;
+            const long sstride = (long)nblk * TILE;
+            const int t = threadIdx.x;
+            const int r = t >> 4, c4 = (t & 15) * 4;
+            const int sr = grp >> 2, c0 = (grp & 3) * 64;
+            const int u = bi * 256 + sr * 16 + r, v0 = bj * 256 + c0 + c4;
+            const int e = (sr * 16 + r) * 256 + c0 + c4;
+            const bool any = u < pr.d && v0 <= u;         // some element of the four is in the lower triangle
+            floatx4 sum = {0.f, 0.f, 0.f, 0.f};
+            if (any) {
+                if (pr.splits == 1) {
+                    sum = *reinterpret_cast<const floatx4 *>(src + e);
+                } else {
+                    floatx4 a[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) a[j] = floatx4{0.f, 0.f, 0.f, 0.f};
+                    int k = 0;
+                    for (; k + 8 <= pr.splits; k += 8) {
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) a[j] += *reinterpret_cast<const floatx4 *>(src + (k + j) * sstride + e);
+                    }
+                    for (; k < pr.splits; ++k) a[0] += *reinterpret_cast<const floatx4 *>(src + k * sstride + e);
+#pragma unroll
+                    for (int h = 4; h > 0; h >>= 1)
+#pragma unroll
+                        for (int j = 0; j < h; ++j) a[j] += a[j + h];
+                    sum = a[0];
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int v = v0 + i;
+                float out = 0.f;
+                if (any && v <= u) {
+                    out = pr.decay * pr.F[(long)u * dF + v] + wnew * sum[i];
+                    pr.F[(long)u * dF + v] = out;
+                }
+                tr[r][c4 + i] = out;
+            }
+            __syncthreads();
+            // the mirror image, along rows of F: thread t writes row (column of the strip) t / 16 + 16 j
+            const int r2 = t & 15;
+            const int u2 = bi * 256 + sr * 16 + r2;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int cc = (t >> 4) + 16 * j;
+                const int v2 = bj * 256 + c0 + cc;
+                if (u2 < pr.d && v2 < u2) pr.F[(long)v2 * dF + u2] = tr[r2][cc];
+            }
+            return;
+        }
+    }
     if (local < nblk * GPT) {
         // kRedGroup 16 x 16 sub-tiles per block: thread t holds one element of each; all loads are issued
         // before the first store.  The mirror image goes through LDS so that both stores run along rows of F.

@@ -123,15 +123,24 @@ def _run_whole_config(name, chain_cost_cap, full_residual_cap, chain_every=1, to
                 Rz = Md @ (Xd @ Z) - Z
                 res = 2.0 * float(torch.sqrt((Rz * Rz).sum() / 32.0))
             bound = res / (decay + lam) / float(torch.linalg.norm(Xd))
+            tol_here = tol_i
             if bound >= tol_i and d <= 1600:
                 # the bound is loose for an ill-conditioned factor (it grows with the condition number, the
-                # error does not have to): such a matrix is compared with the oracle's inverse itself
-                bound = gu.rel_fro(X.cpu().numpy(), orc.inverse(F.cpu().numpy().astype(np.float64), lam))
+                # error does not have to): such a matrix is compared with the oracle's inverse itself, and held
+                # to what an fp32 inverse can give, 0.5 x cond x eps (the yardstick of the ill-conditioned test in
+                # test_gpu_parity.py; the inverse of section 5.2 is computed in fp32), where that exceeds tol_i
+                Fh = F.cpu().numpy().astype(np.float64)
+                bound = gu.rel_fro(X.cpu().numpy(), orc.inverse(Fh, lam))
+                ev = np.linalg.eigvalsh(Fh + lam * np.eye(d))
+                cond = ev[-1] / ev[0]
+                tol_here = max(tol_i, 0.5 * cond * 2.0 ** -24)
+                print(f"{name} layer {i} {tag} (order {d}): inverse against the oracle {bound:.2e}, cond {cond:.2e}, "
+                      f"tolerance {tol_here:.2e}", flush=True)
             if bound > worst["inverse"]:
                 worst["inverse"], worst["inverse_at"] = bound, f"layer {i} {tag} (order {d})"
             if d > 1600:
                 worst["inverse_big"] = max(worst["inverse_big"], bound)
-            assert bound < tol_i, f"{name} layer {i}: error (bound) of {tag}_inv {bound:.2e}"
+            assert bound < tol_here, f"{name} layer {i}: error (bound) of {tag}_inv {bound:.2e}"
         # P = G_inv grad A_inv on random vectors
         Z = torch.randint(0, 2, (l.d_A, NZ), generator=zgen, device=gu.DEV).double() * 2.0 - 1.0
         want = G_inv[i].double() @ (grads[i].double() @ (A_inv[i].double() @ Z))
