@@ -492,6 +492,32 @@ def test_two_sided_product_with_k_slices(dA, dG):
     assert gu.rel_fro(sliced, one_piece.astype(np.float64)) < 2e-6
 
 
+def test_two_sided_products_batched_with_some_layers_sliced():
+    # one batched call in which two layers have a deep second product (K slices, one with the bias column, i.e.
+    # an odd pitch) and two do not; every layer against the fp64 product
+    dims = [(2400, 256, True), (300, 150, False), (2305, 200, False), (65, 10, True)]
+    gen = np.random.default_rng(977)
+    descs, dev, refs, outs = [], [], [], []
+    for d_in, d_out, bias in dims:
+        desc = kf.LayerDesc.linear(d_in, d_out, has_bias=bias)
+        dA, dG = kf.kfac_dim_A(desc), kf.kfac_dim_G(desc)
+        A_inv = gen.standard_normal((dA, dA)).astype(np.float32)
+        A_inv = ((A_inv + A_inv.T) / 2).astype(np.float32)
+        G_inv = gen.standard_normal((dG, dG)).astype(np.float32)
+        G_inv = ((G_inv + G_inv.T) / 2).astype(np.float32)
+        grad = gen.standard_normal((dG, dA)).astype(np.float32)
+        descs.append(desc)
+        dev.append([gu.to_dev(x) for x in (A_inv, G_inv, grad)])
+        refs.append(G_inv.astype(np.float64) @ grad.astype(np.float64) @ A_inv.astype(np.float64))
+        outs.append(torch.full((dG, dA), float("nan"), device=gu.DEV))
+    n = len(dims)
+    ws = gu.workspace(kf.kfac_workspace_bytes_batched(descs, [8] * n, [1] * n, [1] * n))
+    kf.kfac_precondition_batched(descs, [d[0] for d in dev], [d[1] for d in dev], [d[2] for d in dev], outs, ws)
+    torch.cuda.synchronize()
+    for i in range(n):
+        assert gu.rel_fro(outs[i].cpu().numpy(), refs[i]) < 1e-5, dims[i]
+
+
 def test_not_positive_definite_is_flagged():
     n = 70
     M = np.eye(n, dtype=np.float32)
